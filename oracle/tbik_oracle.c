@@ -1,0 +1,439 @@
+/*
+ * CPU oracle for the Tree-Based Invariant Kernels (TBIK).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * HIP kernels are checked against.  It shares no code with the HIP path and is
+ * used only by the tests, the smoke check and the CPU-baseline leg of the
+ * benchmark.  Nothing in the product path calls it.
+ *
+ * Everything floating point here is IEEE-754 binary32 with round-to-nearest-even,
+ * because the method is *about* the order of fp32 roundings (Sec. 2.1: fp32
+ * accumulators; App. C: the operator "(+)" is the rounded addition).  Build with
+ * `gcc -O2 -ffp-contract=off` and never with -ffast-math.
+ *
+ * What is defined here, and from where:
+ *   tbik_oracle_T            App. C "Operator definition": T(k_1..k_{2^t}), recursive.
+ *   tbik_oracle_T_counter    App. D.1 / Alg. 1: the same value, evaluated by the
+ *                            streaming counter/stash ("carry-over") loop.
+ *   tbik_oracle_allreduce    App. D.2 / Alg. 2: tree all-reduce over W=2^q ranks,
+ *                            simulated rank by rank (reduce phase + broadcast phase).
+ *   tbik_oracle_gemm*        Sec. 3.3 (Y = XW, row-parallel K shards), Sec. 4.2
+ *                            (K cut into tiles = leaves, fixed binary tree over
+ *                            them), App. D.1 (K_first leaves chained before the
+ *                            first tree level), Theorem 1 (sharded == whole).
+ *   tbik_oracle_treesum,
+ *   tbik_oracle_rmsnorm,
+ *   tbik_oracle_row_*        App. B (one row = one fixed reduction order,
+ *                            independent of the batch) with the tree order of
+ *                            App. C applied along the row.
+ *
+ * Pins (tests marked "not gpu"): hand-derived tree values, Theorem 1 across
+ * P and M, exact-integer inputs against int64 arithmetic, fp64 brute force
+ * within the summation-tree error bound, one-superleaf == sequential sum,
+ * leaf 1 == level-by-level pairwise sum, closed forms for RMSNorm and
+ * log-softmax.  No function here is "parity unpinned".
+ */
+#include <float.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#if defined(FLT_EVAL_METHOD) && FLT_EVAL_METHOD != 0
+#error "float expressions must be evaluated in binary32 (FLT_EVAL_METHOD == 0)"
+#endif
+
+/* ------------------------------------------------------------------ bf16 */
+
+static float bf16_to_f32(uint16_t h) {
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+/* fp32 -> bf16, round to nearest, ties to even (the single final rounding of an output). */
+static uint16_t f32_to_bf16(float f) {
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u); /* NaN stays NaN */
+    uint32_t lsb = (u >> 16) & 1u;
+    u += 0x7fffu + lsb;
+    return (uint16_t)(u >> 16);
+}
+
+uint16_t tbik_oracle_f32_to_bf16(float f) { return f32_to_bf16(f); }
+float tbik_oracle_bf16_to_f32(uint16_t h) { return bf16_to_f32(h); }
+
+static int is_pow2(long n) { return n >= 1 && (n & (n - 1)) == 0; }
+
+/* ------------------------------------------------------------------ the tree */
+
+/* App. C, operator definition.  n must be a power of two. */
+float tbik_oracle_T(const float *k, long n) {
+    if (n == 1) return k[0];
+    if (n == 2) return k[0] + k[1];
+    float left = tbik_oracle_T(k, n / 2);
+    float right = tbik_oracle_T(k + n / 2, n / 2);
+    return left + right;
+}
+
+/*
+ * App. D.1 / Alg. 1, restricted to the tree part: the n values arrive one at a
+ * time; a stash S[level] holds a finished subtree of 2^level values waiting for
+ * its right sibling, Count[level] says whether it is occupied.  A new value
+ * climbs while the stash at its level is occupied ("carry-over": the two
+ * partial sums of a level are added and move one level up).  After the last
+ * value every level has been emptied and the running value is T(k_1..k_n).
+ * (As printed, the listing never clears the running accumulator after it is
+ * stashed; the prose of App. D.1 fixes the intent, which is what is coded.)
+ */
+float tbik_oracle_T_counter(const float *k, long n) {
+    float S[64];
+    int Count[64];
+    for (int l = 0; l < 64; ++l) { S[l] = 0.0f; Count[l] = 0; }
+    float acc = 0.0f;
+    for (long t = 0; t < n; ++t) {
+        acc = k[t];
+        int level = 0;
+        while (Count[level] == 1) {
+            acc = S[level] + acc;        /* left sibling (earlier) + right sibling (later) */
+            S[level] = 0.0f;
+            Count[level] = 0;
+            ++level;
+        }
+        if (t + 1 < n) {
+            S[level] = acc;
+            Count[level] = 1;
+        }
+    }
+    return acc;
+}
+
+/*
+ * App. D.2 / Alg. 2, simulated for all W ranks at once, element by element.
+ * bufs is [W][n]: on entry rank r's local tensor, on exit every rank holds the
+ * all-reduced tensor.  Each simulated rank follows its own copy of the listing;
+ * a Send/Recv pair is a copy between the two ranks' buffers in the round in
+ * which both sides reach it.
+ */
+int tbik_oracle_allreduce(float *bufs, int W, long n) {
+    if (!is_pow2(W)) return -1;
+    int q = 0;
+    while ((1 << q) < W) ++q;
+    char *done = (char *)calloc((size_t)W, 1);   /* rank has executed its "break" */
+    if (!done) return -2;
+    /* reduce phase */
+    for (int l = 0; l < q; ++l) {
+        int s = 1 << l;
+        for (int r = 0; r < W; ++r) {
+            if (done[r]) continue;
+            if (r % (2 * s) == 0) {
+                const float *recv = bufs + (size_t)(r + s) * n;   /* Recv(r+s): what rank r+s sends this round */
+                float *buf = bufs + (size_t)r * n;
+                for (long i = 0; i < n; ++i) buf[i] = buf[i] + recv[i];
+            }
+        }
+        for (int r = 0; r < W; ++r)
+            if (!done[r] && r % (2 * s) == s) done[r] = 1;        /* Send(buf, r-s); break */
+    }
+    /* broadcast phase */
+    for (int l = q - 1; l >= 0; --l) {
+        int s = 1 << l;
+        for (int r = 0; r < W; ++r) {
+            if (r % (2 * s) == 0)
+                memcpy(bufs + (size_t)(r + s) * n, bufs + (size_t)r * n, (size_t)n * sizeof(float));
+        }
+    }
+    free(done);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ GEMM */
+
+enum { EVAL_RECURSIVE = 0, EVAL_COUNTER = 1, EVAL_SHARDED = 2 };
+
+/* Checks the tree parameters: K = n_s * leaf * k_first with n_s a power of two, P | n_s. */
+static long superleaf_count(int K, int leaf, int k_first, int P) {
+    if (K <= 0 || leaf <= 0 || k_first <= 0) return -1;
+    long sl = (long)leaf * k_first;
+    if (K % sl) return -1;
+    long ns = K / sl;
+    if (!is_pow2(ns)) return -1;
+    if (P < 1 || !is_pow2(P) || P > ns || P > 64) return -1;
+    return ns;
+}
+
+/* y = tree over the n_s superleaf sums s[0..n_s), by the chosen evaluator.
+ * For EVAL_SHARDED also writes the P per-shard subtree sums to part[0..P) (if not NULL). */
+static float combine_superleaves(const float *s, long ns, int evaluator, int P, float *part) {
+    if (evaluator == EVAL_RECURSIVE) return tbik_oracle_T(s, ns);
+    if (evaluator == EVAL_COUNTER) return tbik_oracle_T_counter(s, ns);
+    /* Theorem 1 route: rank p reduces its contiguous block of n_s/P superleaves with
+     * the in-kernel tree (Alg. 1), then the ranks run Alg. 2 on their partial sums. */
+    float bufs[64];
+    long per = ns / P;
+    for (int p = 0; p < P; ++p) {
+        bufs[p] = tbik_oracle_T_counter(s + p * per, per);
+        if (part) part[p] = bufs[p];
+    }
+    tbik_oracle_allreduce(bufs, P, 1);
+    return bufs[0];
+}
+
+/*
+ * One output element, written as plainly as possible (Sec. 3.3 for the sum
+ * over k; Sec. 4.2 / App. D.1 for leaves and K_first):
+ *   p_k  = x[m,k] * w[k,n]                 (exact in fp32 for bf16 operands)
+ *   s_j  = ((+0 + p_a) + p_{a+1}) + ...    over superleaf j = leaf*k_first consecutive k
+ *   y    = T(s_0 .. s_{n_s-1})
+ */
+float tbik_oracle_gemm_element(const uint16_t *X, long ldx, const uint16_t *W, long ldw,
+                               long m, long n, int K, int leaf, int k_first, int evaluator, int P) {
+    long ns = superleaf_count(K, leaf, k_first, P);
+    if (ns < 0) return NAN;
+    long sl = (long)leaf * k_first;
+    float *s = (float *)malloc((size_t)ns * sizeof(float));
+    for (long j = 0; j < ns; ++j) {
+        float acc = 0.0f;
+        for (long k = j * sl; k < (j + 1) * sl; ++k) {
+            float p = bf16_to_f32(X[m * ldx + k]) * bf16_to_f32(W[k * ldw + n]);
+            acc = acc + p;
+        }
+        s[j] = acc;
+    }
+    float y = combine_superleaves(s, ns, evaluator, P, NULL);
+    free(s);
+    return y;
+}
+
+/*
+ * The same element by App. D.1 / Alg. 1 taken as a whole: one loop over the
+ * T = K/leaf tiles of the K dimension; the running accumulator takes K_first
+ * tiles in a row before the first carry-over, higher levels carry at two.
+ * Level 0 of the listing is the running accumulator itself; S[l], Count[l]
+ * (l >= 1) hold a finished subtree of 2^(l-1) superleaves.
+ */
+float tbik_oracle_gemm_element_alg1(const uint16_t *X, long ldx, const uint16_t *W, long ldw,
+                                    long m, long n, int K, int leaf, int k_first) {
+    long ns = superleaf_count(K, leaf, k_first, 1);
+    if (ns < 0) return NAN;
+    const long T = K / leaf;
+    float S[64];
+    int Count[64];
+    for (int l = 0; l < 64; ++l) { S[l] = 0.0f; Count[l] = 0; }
+    float acc = 0.0f;
+    int tiles_in_acc = 0;
+    for (long t = 0; t < T; ++t) {
+        for (long k = t * leaf; k < (t + 1) * leaf; ++k) {        /* acc <- acc + A_t B_t */
+            float p = bf16_to_f32(X[m * ldx + k]) * bf16_to_f32(W[k * ldw + n]);
+            acc = acc + p;
+        }
+        if (++tiles_in_acc < k_first) continue;                   /* level 0 not full yet */
+        tiles_in_acc = 0;
+        int level = 1;
+        while (Count[level] == 1) {                               /* carry-over */
+            acc = S[level] + acc;
+            S[level] = 0.0f;
+            Count[level] = 0;
+            ++level;
+        }
+        if (t + 1 < T) {
+            S[level] = acc;
+            Count[level] = 1;
+            acc = 0.0f;
+        }
+    }
+    return acc;
+}
+
+/* A list of elements (spot checks at big shapes). */
+int tbik_oracle_gemm_elements(const uint16_t *X, long ldx, const uint16_t *W, long ldw,
+                              const int64_t *rows, const int64_t *cols, long count,
+                              int K, int leaf, int k_first, int evaluator, int P, float *out) {
+    if (superleaf_count(K, leaf, k_first, P) < 0) return -1;
+#pragma omp parallel for schedule(dynamic, 16)
+    for (long i = 0; i < count; ++i)
+        out[i] = tbik_oracle_gemm_element(X, ldx, W, ldw, rows[i], cols[i], K, leaf, k_first, evaluator, P);
+    return 0;
+}
+
+/*
+ * Whole matrix.  Same arithmetic per element as tbik_oracle_gemm_element; the
+ * only difference is that the chains of a block of neighbouring columns of one
+ * row advance together (k outer, n inner), which leaves each element's own
+ * sequence of additions untouched and lets the compiler use SIMD across
+ * independent elements.  Parallel over (row, column block) only.
+ *   Y32  [M,ldy] fp32 result (may be NULL)
+ *   Ybf  [M,ldy] bf16 = single RNE rounding of the fp32 result (may be NULL)
+ *   partials [P,M,N] fp32 per-shard subtree sums, only for EVAL_SHARDED (may be NULL)
+ */
+int tbik_oracle_gemm(const uint16_t *X, long ldx, const uint16_t *W, long ldw,
+                     float *Y32, uint16_t *Ybf, long ldy, int M, int N, int K,
+                     int leaf, int k_first, int evaluator, int P, float *partials) {
+    long ns = superleaf_count(K, leaf, k_first, P);
+    if (ns < 0) return -1;
+    if (M <= 0 || N <= 0) return 0;
+    const long sl = (long)leaf * k_first;
+    const int NB = 256;
+    const long nblk = (N + NB - 1) / NB;
+#pragma omp parallel
+    {
+        float *S = (float *)malloc((size_t)ns * NB * sizeof(float));  /* S[j][c]: superleaf sums of a column block */
+        float *col = (float *)malloc((size_t)ns * sizeof(float));
+        float part[64];
+#pragma omp for schedule(dynamic, 1) collapse(2)
+        for (long m = 0; m < M; ++m) {
+            for (long b = 0; b < nblk; ++b) {
+                const long n0 = b * NB;
+                const int nb = (int)((N - n0) < NB ? (N - n0) : NB);
+                for (long j = 0; j < ns; ++j) {
+                    float *acc = S + j * NB;
+                    for (int c = 0; c < nb; ++c) acc[c] = 0.0f;
+                    for (long k = j * sl; k < (j + 1) * sl; ++k) {
+                        const float xv = bf16_to_f32(X[m * ldx + k]);
+                        const uint16_t *wrow = W + k * ldw + n0;
+                        for (int c = 0; c < nb; ++c) {
+                            float p = xv * bf16_to_f32(wrow[c]);
+                            acc[c] = acc[c] + p;
+                        }
+                    }
+                }
+                for (int c = 0; c < nb; ++c) {
+                    for (long j = 0; j < ns; ++j) col[j] = S[j * NB + c];
+                    float y = combine_superleaves(col, ns, evaluator, P, part);
+                    if (Y32) Y32[m * ldy + n0 + c] = y;
+                    if (Ybf) Ybf[m * ldy + n0 + c] = f32_to_bf16(y);
+                    if (partials && evaluator == EVAL_SHARDED)
+                        for (int p = 0; p < P; ++p)
+                            partials[((size_t)p * M + m) * N + n0 + c] = part[p];
+                }
+            }
+        }
+        free(S);
+        free(col);
+    }
+    return 0;
+}
+
+/*
+ * Top-of-tree combine on its own (Alg. 2's reduce phase applied to P partial
+ * tensors [P][count], followed by the one rounding to the output type).
+ */
+int tbik_oracle_tree_combine(const float *partials, int P, long count, float *Y32, uint16_t *Ybf) {
+    if (!is_pow2(P) || P > 64) return -1;
+    float bufs[64];
+    for (long i = 0; i < count; ++i) {
+        for (int p = 0; p < P; ++p) bufs[p] = partials[(size_t)p * count + i];
+        tbik_oracle_allreduce(bufs, P, 1);
+        if (Y32) Y32[i] = bufs[0];
+        if (Ybf) Ybf[i] = f32_to_bf16(bufs[0]);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ row reductions */
+
+/*
+ * Tree-ordered sum of a row: leaves are left-to-right sums (from +0) of `leaf`
+ * consecutive elements, the last leaf possibly short; the leaf count is padded
+ * with +0 leaves to a power of two, then T (App. C) is applied.
+ */
+float tbik_oracle_treesum(const float *v, long n, int leaf) {
+    long nl = (n + leaf - 1) / leaf;
+    long n2 = 1;
+    while (n2 < nl) n2 *= 2;
+    float *L = (float *)malloc((size_t)n2 * sizeof(float));
+    for (long i = 0; i < n2; ++i) {
+        float acc = 0.0f;
+        for (long e = i * leaf; e < (i + 1) * leaf && e < n; ++e) acc = acc + v[e];
+        L[i] = acc;
+    }
+    float r = tbik_oracle_T(L, n2);
+    free(L);
+    return r;
+}
+
+/*
+ * RMSNorm of bf16 rows (App. B: each row reduced on its own in a fixed order):
+ *   ss = TreeSum_i( x_i * x_i )        squares of bf16 values are exact in fp32
+ *   r  = 1 / sqrt( ss / H + eps )      correctly rounded fp32 divide and sqrt
+ *   y_i = bf16( (x_i * r) * w_i )      one rounding to bf16, at the end
+ */
+int tbik_oracle_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int M, int H, float eps, int leaf) {
+    if (H <= 0 || leaf <= 0) return -1;
+#pragma omp parallel
+    {
+        float *sq = (float *)malloc((size_t)H * sizeof(float));
+#pragma omp for schedule(static)
+        for (long m = 0; m < M; ++m) {
+            const uint16_t *row = x + m * (long)H;
+            for (int i = 0; i < H; ++i) {
+                float xv = bf16_to_f32(row[i]);
+                sq[i] = xv * xv;
+            }
+            float ss = tbik_oracle_treesum(sq, H, leaf);
+            float ms = ss / (float)H;
+            float r = 1.0f / sqrtf(ms + eps);
+            for (int i = 0; i < H; ++i) {
+                float t = bf16_to_f32(row[i]) * r;
+                y[m * (long)H + i] = f32_to_bf16(t * bf16_to_f32(w[i]));
+            }
+        }
+        free(sq);
+    }
+    return 0;
+}
+
+/* The sum of squares alone (to pin the reduction separately from the epilogue). */
+float tbik_oracle_sumsq_bf16(const uint16_t *row, int H, int leaf) {
+    float *sq = (float *)malloc((size_t)H * sizeof(float));
+    for (int i = 0; i < H; ++i) {
+        float xv = bf16_to_f32(row[i]);
+        sq[i] = xv * xv;
+    }
+    float ss = tbik_oracle_treesum(sq, H, leaf);
+    free(sq);
+    return ss;
+}
+
+/* out[m] = TreeSum(x[m, :]) */
+int tbik_oracle_row_sum(const float *x, float *out, int M, long V, int leaf) {
+#pragma omp parallel for schedule(static)
+    for (long m = 0; m < M; ++m) out[m] = tbik_oracle_treesum(x + m * V, V, leaf);
+    return 0;
+}
+
+/* out[m] = max_i x[m, i]   (exact, order-free) */
+int tbik_oracle_row_max(const float *x, float *out, int M, long V) {
+#pragma omp parallel for schedule(static)
+    for (long m = 0; m < M; ++m) {
+        float mx = -INFINITY;
+        for (long i = 0; i < V; ++i) mx = x[m * V + i] > mx ? x[m * V + i] : mx;
+        out[m] = mx;
+    }
+    return 0;
+}
+
+/*
+ * Row log-softmax in fp32 (Sec. 2.1: softmax runs in fp32):
+ *   m = max_i x_i;  e_i = exp(x_i - m);  S = TreeSum(e);  o_i = (x_i - m) - log(S)
+ */
+int tbik_oracle_row_logsoftmax(const float *x, float *out, int M, long V, int leaf) {
+#pragma omp parallel
+    {
+        float *e = (float *)malloc((size_t)V * sizeof(float));
+#pragma omp for schedule(static)
+        for (long m = 0; m < M; ++m) {
+            const float *row = x + m * V;
+            float mx = -INFINITY;
+            for (long i = 0; i < V; ++i) mx = row[i] > mx ? row[i] : mx;
+            for (long i = 0; i < V; ++i) e[i] = expf(row[i] - mx);
+            float S = tbik_oracle_treesum(e, V, leaf);
+            float lg = logf(S);
+            for (long i = 0; i < V; ++i) out[m * V + i] = (row[i] - mx) - lg;
+        }
+        free(e);
+    }
+    return 0;
+}

@@ -1,0 +1,256 @@
+"""Python face of the CPU oracle (TEST INFRASTRUCTURE ONLY).
+
+Loads ``oracle/libtbik_oracle.so`` (plain C, ``oracle/tbik_oracle.c``; compiled
+on demand with gcc) and exposes its functions on numpy arrays.  bf16 tensors are
+``uint16`` bit patterns.  Nothing here touches a GPU or the HIP library, and the
+HIP path never imports this module: only tests, the smoke check and the
+benchmark's CPU-baseline leg do.
+
+A second, pure-Python evaluator of the tree operator (``T_python``) is kept for
+tiny inputs, so that the C code is cross-checked by an independent transcription
+of App. C's definition.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "tbik_oracle.c")
+_LIB = os.path.join(_HERE, "libtbik_oracle.so")
+
+EVAL_RECURSIVE, EVAL_COUNTER, EVAL_SHARDED = 0, 1, 2
+
+# Leaf sizes of the row reductions: one 16-byte chunk of the row per leaf.
+LEAF_BF16 = 8
+LEAF_F32 = 4
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle (gcc, strict fp32: no contraction, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-shared", "-fPIC",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(build())
+        f32p, u16p, i64p = C.POINTER(C.c_float), C.POINTER(C.c_uint16), C.POINTER(C.c_int64)
+        L.tbik_oracle_T.restype = C.c_float
+        L.tbik_oracle_T.argtypes = [f32p, C.c_long]
+        L.tbik_oracle_T_counter.restype = C.c_float
+        L.tbik_oracle_T_counter.argtypes = [f32p, C.c_long]
+        L.tbik_oracle_allreduce.restype = C.c_int
+        L.tbik_oracle_allreduce.argtypes = [f32p, C.c_int, C.c_long]
+        L.tbik_oracle_gemm_element.restype = C.c_float
+        L.tbik_oracle_gemm_element.argtypes = [u16p, C.c_long, u16p, C.c_long, C.c_long, C.c_long,
+                                               C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]
+        L.tbik_oracle_gemm_element_alg1.restype = C.c_float
+        L.tbik_oracle_gemm_element_alg1.argtypes = [u16p, C.c_long, u16p, C.c_long, C.c_long, C.c_long,
+                                                    C.c_int, C.c_int, C.c_int]
+        L.tbik_oracle_gemm_elements.restype = C.c_int
+        L.tbik_oracle_gemm_elements.argtypes = [u16p, C.c_long, u16p, C.c_long, i64p, i64p, C.c_long,
+                                                C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f32p]
+        L.tbik_oracle_gemm.restype = C.c_int
+        L.tbik_oracle_gemm.argtypes = [u16p, C.c_long, u16p, C.c_long, f32p, u16p, C.c_long,
+                                       C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f32p]
+        L.tbik_oracle_tree_combine.restype = C.c_int
+        L.tbik_oracle_tree_combine.argtypes = [f32p, C.c_int, C.c_long, f32p, u16p]
+        L.tbik_oracle_treesum.restype = C.c_float
+        L.tbik_oracle_treesum.argtypes = [f32p, C.c_long, C.c_int]
+        L.tbik_oracle_rmsnorm.restype = C.c_int
+        L.tbik_oracle_rmsnorm.argtypes = [u16p, u16p, u16p, C.c_int, C.c_int, C.c_float, C.c_int]
+        L.tbik_oracle_sumsq_bf16.restype = C.c_float
+        L.tbik_oracle_sumsq_bf16.argtypes = [u16p, C.c_int, C.c_int]
+        L.tbik_oracle_row_sum.restype = C.c_int
+        L.tbik_oracle_row_sum.argtypes = [f32p, f32p, C.c_int, C.c_long, C.c_int]
+        L.tbik_oracle_row_max.restype = C.c_int
+        L.tbik_oracle_row_max.argtypes = [f32p, f32p, C.c_int, C.c_long]
+        L.tbik_oracle_row_logsoftmax.restype = C.c_int
+        L.tbik_oracle_row_logsoftmax.argtypes = [f32p, f32p, C.c_int, C.c_long, C.c_int]
+        L.tbik_oracle_f32_to_bf16.restype = C.c_uint16
+        L.tbik_oracle_f32_to_bf16.argtypes = [C.c_float]
+        _lib = L
+    return _lib
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a, a.ctypes.data_as(C.POINTER(C.c_float))
+
+
+def _u16(a):
+    a = np.ascontiguousarray(a, dtype=np.uint16)
+    return a, a.ctypes.data_as(C.POINTER(C.c_uint16))
+
+
+def _i64(a):
+    a = np.ascontiguousarray(a, dtype=np.int64)
+    return a, a.ctypes.data_as(C.POINTER(C.c_int64))
+
+
+# ------------------------------------------------------------------ tree operator
+
+def T(values) -> np.float32:
+    """App. C operator T on a power-of-two sequence (recursive definition, C)."""
+    a, p = _f32(values)
+    assert a.size >= 1 and a.size & (a.size - 1) == 0
+    return np.float32(lib().tbik_oracle_T(p, a.size))
+
+
+def T_counter(values) -> np.float32:
+    """The same value through Alg. 1's counter / stash loop (C)."""
+    a, p = _f32(values)
+    assert a.size >= 1 and a.size & (a.size - 1) == 0
+    return np.float32(lib().tbik_oracle_T_counter(p, a.size))
+
+
+def T_python(values) -> np.float32:
+    """App. C's definition transcribed in Python with numpy.float32 scalars (tiny inputs only)."""
+    v = [np.float32(x) for x in values]
+    n = len(v)
+    assert n >= 1 and n & (n - 1) == 0
+    if n == 1:
+        return v[0]
+    if n == 2:
+        return np.float32(v[0] + v[1])
+    return np.float32(T_python(v[: n // 2]) + T_python(v[n // 2:]))
+
+
+def allreduce(bufs: np.ndarray) -> np.ndarray:
+    """Alg. 2 on W rank buffers [W, n]; returns the [W, n] buffers after the call."""
+    a = np.array(bufs, dtype=np.float32, copy=True, order="C")
+    assert a.ndim == 2
+    rc = lib().tbik_oracle_allreduce(a.ctypes.data_as(C.POINTER(C.c_float)), a.shape[0], a.shape[1])
+    assert rc == 0, rc
+    return a
+
+
+# ------------------------------------------------------------------ GEMM
+
+def gemm(X, W, leaf: int, k_first: int = 1, evaluator: int = EVAL_RECURSIVE, P: int = 1,
+         want_partials: bool = False):
+    """Y = X W in the tree order.  Returns (Y fp32 [M,N], Y bf16 bits [M,N][, partials [P,M,N])."""
+    X, xp = _u16(X)
+    W, wp = _u16(W)
+    M, K = X.shape
+    K2, N = W.shape
+    assert K == K2
+    Y32 = np.empty((M, N), dtype=np.float32)
+    Ybf = np.empty((M, N), dtype=np.uint16)
+    parts = np.zeros((P, M, N), dtype=np.float32) if want_partials else None
+    rc = lib().tbik_oracle_gemm(xp, K, wp, N, Y32.ctypes.data_as(C.POINTER(C.c_float)),
+                                Ybf.ctypes.data_as(C.POINTER(C.c_uint16)), N, M, N, K, leaf, k_first,
+                                evaluator, P,
+                                parts.ctypes.data_as(C.POINTER(C.c_float)) if want_partials else None)
+    if rc != 0:
+        raise ValueError("oracle gemm: illegal tree parameters (K, leaf, k_first, P)")
+    return (Y32, Ybf, parts) if want_partials else (Y32, Ybf)
+
+
+def gemm_element(X, W, m: int, n: int, leaf: int, k_first: int = 1, evaluator: int = EVAL_RECURSIVE,
+                 P: int = 1) -> np.float32:
+    X, xp = _u16(X)
+    W, wp = _u16(W)
+    return np.float32(lib().tbik_oracle_gemm_element(xp, X.shape[1], wp, W.shape[1], m, n, X.shape[1],
+                                                     leaf, k_first, evaluator, P))
+
+
+def gemm_element_alg1(X, W, m: int, n: int, leaf: int, k_first: int = 1) -> np.float32:
+    X, xp = _u16(X)
+    W, wp = _u16(W)
+    return np.float32(lib().tbik_oracle_gemm_element_alg1(xp, X.shape[1], wp, W.shape[1], m, n,
+                                                          X.shape[1], leaf, k_first))
+
+
+def gemm_elements(X, W, rows, cols, leaf: int, k_first: int = 1, evaluator: int = EVAL_RECURSIVE,
+                  P: int = 1) -> np.ndarray:
+    """fp32 results at the listed (row, col) positions."""
+    X, xp = _u16(X)
+    W, wp = _u16(W)
+    rows, rp = _i64(rows)
+    cols, cp = _i64(cols)
+    out = np.empty(rows.size, dtype=np.float32)
+    rc = lib().tbik_oracle_gemm_elements(xp, X.shape[1], wp, W.shape[1], rp, cp, rows.size, X.shape[1],
+                                         leaf, k_first, evaluator, P,
+                                         out.ctypes.data_as(C.POINTER(C.c_float)))
+    if rc != 0:
+        raise ValueError("oracle gemm: illegal tree parameters (K, leaf, k_first, P)")
+    return out
+
+
+def tree_combine(partials: np.ndarray):
+    """Top-of-tree combine of [P, ...] fp32 partials: (Y fp32, Y bf16 bits), shaped like partials[0]."""
+    a, p = _f32(partials)
+    P = a.shape[0]
+    count = int(np.prod(a.shape[1:]))
+    Y32 = np.empty(a.shape[1:], dtype=np.float32)
+    Ybf = np.empty(a.shape[1:], dtype=np.uint16)
+    rc = lib().tbik_oracle_tree_combine(p, P, count, Y32.ctypes.data_as(C.POINTER(C.c_float)),
+                                        Ybf.ctypes.data_as(C.POINTER(C.c_uint16)))
+    if rc != 0:
+        raise ValueError("oracle tree_combine: P must be a power of two <= 64")
+    return Y32, Ybf
+
+
+def f32_to_bf16_bits(a) -> np.ndarray:
+    """The oracle's own output rounding (RNE), elementwise through the C routine."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    f = lib().tbik_oracle_f32_to_bf16
+    return np.array([f(float(v)) for v in a.ravel()], dtype=np.uint16).reshape(a.shape)
+
+
+# ------------------------------------------------------------------ row reductions
+
+def treesum(v, leaf: int) -> np.float32:
+    a, p = _f32(v)
+    return np.float32(lib().tbik_oracle_treesum(p, a.size, leaf))
+
+
+def rmsnorm(x, w, eps: float = 1e-6, leaf: int = LEAF_BF16) -> np.ndarray:
+    x, xp = _u16(x)
+    w, wp = _u16(w)
+    M, H = x.shape
+    y = np.empty((M, H), dtype=np.uint16)
+    rc = lib().tbik_oracle_rmsnorm(xp, wp, y.ctypes.data_as(C.POINTER(C.c_uint16)), M, H, eps, leaf)
+    assert rc == 0
+    return y
+
+
+def sumsq_bf16(row, leaf: int = LEAF_BF16) -> np.float32:
+    row, rp = _u16(row)
+    return np.float32(lib().tbik_oracle_sumsq_bf16(rp, row.size, leaf))
+
+
+def row_sum(x, leaf: int = LEAF_F32) -> np.ndarray:
+    x, xp = _f32(x)
+    M, V = x.shape
+    out = np.empty(M, dtype=np.float32)
+    lib().tbik_oracle_row_sum(xp, out.ctypes.data_as(C.POINTER(C.c_float)), M, V, leaf)
+    return out
+
+
+def row_max(x) -> np.ndarray:
+    x, xp = _f32(x)
+    M, V = x.shape
+    out = np.empty(M, dtype=np.float32)
+    lib().tbik_oracle_row_max(xp, out.ctypes.data_as(C.POINTER(C.c_float)), M, V)
+    return out
+
+
+def row_logsoftmax(x, leaf: int = LEAF_F32) -> np.ndarray:
+    x, xp = _f32(x)
+    M, V = x.shape
+    out = np.empty((M, V), dtype=np.float32)
+    lib().tbik_oracle_row_logsoftmax(xp, out.ctypes.data_as(C.POINTER(C.c_float)), M, V, leaf)
+    return out

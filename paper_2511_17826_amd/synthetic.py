@@ -1,0 +1,164 @@
+"""Seeded synthetic inputs for the TBIK kernels and for the CPU oracle that checks them.
+
+This module only *makes data*: random draws, casts to bf16 storage and the
+elementwise recipe of a workload's inputs.  It holds none of the method's
+arithmetic (no tree, no reduction, no GEMM) and is the one module that the
+HIP path's tests/bench and the CPU oracle's tests both use.
+
+bf16 tensors travel as ``numpy.uint16`` arrays holding the raw bit patterns,
+so that the CPU oracle and the GPU see exactly the same bits.
+
+Workloads follow the row-parallel layers of the paper's models (Sec. 3.3:
+``o_proj`` and ``down_proj`` split K across GPUs) at 8B-class and 32B-class
+shapes; the tensors are random stand-ins for the activations and weights of
+those layers, not items of any dataset.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """Round fp32 values to bf16 storage (round-to-nearest-even), as uint16 bit patterns.
+
+    Only used to put generated inputs into their storage format.
+    NaN is not expected in generated data and is not special-cased.
+    """
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    bias = ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
+    return ((u + bias) >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Widen bf16 bit patterns (uint16) to the fp32 values they denote (exact)."""
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def _rng(seed: int) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+def normal_bf16(rng: np.random.Generator, shape, std: float, mean: float = 0.0) -> np.ndarray:
+    """N(mean, std) drawn in fp32, stored as bf16 bits."""
+    v = rng.standard_normal(size=shape, dtype=np.float32) * np.float32(std) + np.float32(mean)
+    return f32_to_bf16_bits(v)
+
+
+# ----------------------------------------------------------------------------
+# GEMM workloads: X [M,K] bf16, W [K,N] bf16 (row-major), plus the tree
+# parameters (leaf = K-elements per leaf, k_first = leaves chained before the
+# first tree level, App. D.1).
+# ----------------------------------------------------------------------------
+
+def gemm_tiny(seed: int = 0):
+    """Tiny case: X [4,512] ~ N(0,1), W [512,256] ~ N(0,0.02); leaf 64, 8 leaves."""
+    rng = _rng(seed)
+    X = normal_bf16(rng, (4, 512), 1.0)
+    W = normal_bf16(rng, (512, 256), 0.02)
+    return dict(X=X, W=W, M=4, K=512, N=256, leaf=64, k_first=1)
+
+
+def gemm_oproj(M: int = 4096, seed: int = 1, K: int = 4096, N: int = 4096, leaf: int = 256, k_first: int = 1):
+    """8B-class attention output projection: X [M,4096] ~ N(0,1), W [4096,4096] ~ N(0,0.02).
+
+    The tensor is always drawn at M_max=4096 rows and the first M rows are
+    returned, so row r holds the same bits for every M.
+    """
+    rng = _rng(seed)
+    X = normal_bf16(rng, (4096, K), 1.0)[:M]
+    W = normal_bf16(rng, (K, N), 0.02)
+    return dict(X=np.ascontiguousarray(X), W=W, M=M, K=K, N=N, leaf=leaf, k_first=k_first)
+
+
+def silu_gated_bf16(rng: np.random.Generator, shape) -> np.ndarray:
+    """bf16(silu(a) * b), a, b ~ N(0,1): the input distribution of an MLP down projection."""
+    a = rng.standard_normal(size=shape, dtype=np.float32)
+    b = rng.standard_normal(size=shape, dtype=np.float32)
+    return f32_to_bf16_bits((a / (np.float32(1.0) + np.exp(-a))) * b)
+
+
+def gemm_downproj(M: int = 4096, seed: int = 2, K: int = 12288, N: int = 4096, leaf: int = 256, k_first: int = 3):
+    """8B-class MLP down projection: X = bf16(silu(a)*b) [M,12288], W [12288,4096] ~ N(0,0.02).
+
+    48 leaves of 256 = 3 * 16, hence k_first = 3 and 16 superleaves of 768.
+    """
+    rng = _rng(seed)
+    X = silu_gated_bf16(rng, (4096, K))[:M]
+    W = normal_bf16(rng, (K, N), 0.02)
+    return dict(X=np.ascontiguousarray(X), W=W, M=M, K=K, N=N, leaf=leaf, k_first=k_first)
+
+
+def gemm_random(seed: int, M: int, K: int, N: int, x_std: float = 1.0, w_std: float = 0.02):
+    """Generic random GEMM operands of the same distributions, any shape."""
+    rng = _rng(seed)
+    return normal_bf16(rng, (M, K), x_std), normal_bf16(rng, (K, N), w_std)
+
+
+def gemm_small_integers(seed: int, M: int, K: int, N: int, mag: int = 8):
+    """Integer-valued operands with |x|,|w| <= mag.
+
+    Every partial sum stays far below 2**24, so any summation order gives the
+    exact integer: such inputs test indexing and layout, not rounding.
+    """
+    rng = _rng(seed)
+    X = rng.integers(-mag, mag + 1, size=(M, K)).astype(np.float32)
+    W = rng.integers(-mag, mag + 1, size=(K, N)).astype(np.float32)
+    return f32_to_bf16_bits(X), f32_to_bf16_bits(W)
+
+
+def gemm_leaf_sparse(seed: int, M: int, K: int, N: int, superleaf: int, exp_spread: int = 12):
+    """Operands with exactly one non-zero product per (row, column, superleaf).
+
+    In every superleaf (``superleaf`` consecutive k) X has one non-zero column
+    position per row -- the same position is used for W's only non-zero row in
+    that superleaf -- so each superleaf sum is a single exact product whatever
+    the order inside the leaf, and only the tree between superleaves rounds.
+    Magnitudes are random bf16 values scaled by 2**e, e uniform in
+    [-exp_spread, exp_spread], which makes the tree's roundings visible.
+    """
+    assert K % superleaf == 0
+    rng = _rng(seed)
+    ns = K // superleaf
+    X = np.zeros((M, K), dtype=np.float32)
+    W = np.zeros((K, N), dtype=np.float32)
+    pos = rng.integers(0, superleaf, size=ns)
+    for j in range(ns):
+        k = j * superleaf + int(pos[j])
+        X[:, k] = rng.standard_normal(M).astype(np.float32) * np.exp2(
+            rng.integers(-exp_spread, exp_spread + 1, size=M)).astype(np.float32)
+        W[k, :] = rng.standard_normal(N).astype(np.float32) * np.exp2(
+            rng.integers(-exp_spread, exp_spread + 1, size=N)).astype(np.float32)
+    return f32_to_bf16_bits(X), f32_to_bf16_bits(W)
+
+
+# ----------------------------------------------------------------------------
+# Reduction workloads
+# ----------------------------------------------------------------------------
+
+def rmsnorm_inputs(M: int, H: int, seed: int = 3):
+    """x [M,H] ~ N(0,1) bf16, weight [H] ~ N(1,0.1) bf16; drawn at 8192 rows, first M returned."""
+    rng = _rng(seed + 1000 * H)
+    w = normal_bf16(rng, (H,), 0.1, mean=1.0)
+    x = normal_bf16(rng, (8192, H), 1.0)[:M]
+    return np.ascontiguousarray(x), w
+
+
+def logits_f32(M: int, V: int = 151936, seed: int = 3, std: float = 3.0) -> np.ndarray:
+    """fp32 logits [M,V] ~ N(0,3); row r is the same for every M (rows drawn one stream each)."""
+    out = np.empty((M, V), dtype=np.float32)
+    for r in range(M):
+        out[r] = _rng(seed * 1_000_003 + r).standard_normal(size=V, dtype=np.float32) * np.float32(std)
+    return out
+
+
+def sample_elements(seed: int, M: int, N: int, n_rows: int = 64, n_cols: int = 256):
+    """A seeded grid of (row, col) output positions for spot checks at large shapes.
+
+    Always includes the first and last row and column, so the ragged edges of
+    a tiling are covered.
+    """
+    rng = _rng(seed)
+    rows = np.unique(np.concatenate([[0, M - 1], rng.integers(0, M, size=max(0, min(n_rows, M) - 2))]))
+    cols = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, size=max(0, min(n_cols, N) - 2))]))
+    rr, cc = np.meshgrid(rows, cols, indexing="ij")
+    return rr.ravel().astype(np.int64), cc.ravel().astype(np.int64)
