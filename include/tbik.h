@@ -1,0 +1,162 @@
+/*
+ * tbik.h -- C ABI of the Tree-Based Invariant Kernels (TBIK) for AMD MI355X (gfx950).
+ *
+ * The library computes matrix products and row reductions whose floating-point
+ * summation order is one fixed binary tree, so that the output bits do not depend
+ * on the batch size M, on the position of a row in the batch, or on the number P
+ * of tensor-parallel shards the reduction dimension K is split into.
+ *
+ * Vocabulary (Sec. 4.2, App. D.1):
+ *   leaf        number of consecutive K-elements in one tile of the K dimension (Block_K)
+ *   k_first     number of leaves accumulated in one chain before the first tree level (K_first)
+ *   superleaf   leaf * k_first consecutive k; its products are accumulated in ascending k from +0
+ *   n_s         K / (leaf * k_first), the number of superleaves; must be a power of two
+ *   P           number of K-shards (the tensor-parallel size C); a power of two, P <= n_s
+ *   T(...)      the full-binary-tree reduction of App. C over the n_s superleaf sums
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library never
+ *     allocates, frees or keeps device memory; scratch space is passed in as `workspace`.
+ *   - Matrices are row-major; leading dimensions (ld*) are in ELEMENTS.
+ *   - bf16 is the 16-bit brain-float storage format (upper half of an IEEE binary32).
+ *   - `hip_stream` is a hipStream_t cast to void* (NULL = the default stream).  All work is
+ *     enqueued on it; no call synchronises.  Outputs are valid once the stream reaches that point.
+ *   - Every call returns a tbik_status.  Arguments are validated before the first launch,
+ *     so a failing call has launched nothing.  M == 0 or N == 0 (V == 0 rows excepted, see
+ *     tbik_row_reduce) is TBIK_OK and does nothing.
+ *   - Determinism contract: for fixed (leaf, k_first) the bits of row m of an output depend only
+ *     on row m of the input and on the weights -- not on M, the row's position, P, the stream,
+ *     the internal kernel variant or the number of repetitions; and
+ *     tbik_gemm(...) == tbik_tree_combine(tbik_gemm_shard_partials(..., P)) bit for bit for
+ *     every legal P (Theorem 1, App. C).
+ */
+#ifndef TBIK_H
+#define TBIK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TBIK_OK = 0,
+    TBIK_ERR_NULL = 1,        /* a required pointer is NULL                                             */
+    TBIK_ERR_SHAPE = 2,       /* negative size; K % (leaf*k_first) != 0; n_s not a power of two;
+                                 leaf*k_first not a multiple of 16; a leading dimension too small      */
+    TBIK_ERR_SHARDS = 3,      /* P < 1, P not a power of two, P > n_s, or P > TBIK_MAX_SHARDS           */
+    TBIK_ERR_DTYPE = 4,       /* unknown tbik_dtype / tbik_rowop, or a combination that is not offered */
+    TBIK_ERR_ALIGN = 5,       /* a pointer or leading dimension violates the stated alignment          */
+    TBIK_ERR_WORKSPACE = 6,   /* workspace missing or smaller than the matching *_workspace_bytes()    */
+    TBIK_ERR_UNSUPPORTED = 7, /* legal request that this build does not implement                      */
+    TBIK_ERR_HIP = 8          /* a HIP runtime call failed; see tbik_last_hip_error()                  */
+} tbik_status;
+
+typedef enum { TBIK_F32 = 0, TBIK_BF16 = 1 } tbik_dtype;
+typedef enum { TBIK_SUM = 0, TBIK_MAX = 1, TBIK_LOGSOFTMAX = 2 } tbik_rowop;
+
+#define TBIK_MAX_SHARDS 64
+
+/*
+ * Y[M,N] = X[M,K] * W[K,N] with the whole K on this device (tensor-parallel size 1, the
+ * training-side call).  Sec. 3.3 states the product; Sec. 4.2 and App. D.1 (Alg. 1) state the
+ * order: per output element, each superleaf's bf16 x bf16 products are accumulated in fp32 in
+ * ascending k starting from +0, and the n_s superleaf sums are combined by T (App. C).  The
+ * result is rounded once to y_dtype (round-to-nearest-even for TBIK_BF16).
+ *
+ *   X   device, bf16, [M, ldx], ldx >= K     W   device, bf16, [K, ldw], ldw >= N
+ *   Y   device, y_dtype, [M, ldy], ldy >= N
+ *   Alignment: X, W 16 bytes, ldx and ldw multiples of 8; Y 4 bytes (TBIK_F32) / 2 bytes (TBIK_BF16).
+ *   workspace  device scratch of at least tbik_gemm_workspace_bytes(M,N,K,leaf,k_first) bytes,
+ *              256-byte aligned; may be NULL when that size is 0.  Contents are undefined afterwards.
+ * Errors: NULL, SHAPE, DTYPE, ALIGN, WORKSPACE, HIP.
+ */
+int tbik_gemm(const void *X, int64_t ldx, const void *W, int64_t ldw, void *Y, int64_t ldy,
+              tbik_dtype y_dtype, int M, int N, int K, int leaf, int k_first,
+              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Tensor-parallel emulation, local stage (Sec. 3.3 row-parallel split; Sec. 4.2 "Intra-GPU
+ * reduction"): shard p owns k in [p*K/P, (p+1)*K/P), i.e. n_s/P whole superleaves, and
+ *   partials[p][m][n] = T(superleaf sums of shard p)            (fp32, never rounded to bf16)
+ * which is exactly what rank p of a P-way tensor-parallel group would hold before the
+ * all-reduce.  A real rank calls this with P = 1 on its own X_p [M, K/P], W_p [K/P, N].
+ *
+ *   partials   device, fp32, dense [P, M, N]
+ *   workspace  at least tbik_gemm_workspace_bytes(...) bytes (same rule as tbik_gemm)
+ * Errors: NULL, SHAPE, SHARDS, ALIGN, WORKSPACE, HIP.
+ */
+int tbik_gemm_shard_partials(const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
+                             int M, int N, int K, int leaf, int k_first, int P,
+                             void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Tensor-parallel emulation, top of the tree (Sec. 4.2 "Inter-GPU reduction"; App. D.2, Alg. 2):
+ *   Y = T(partials[0], ..., partials[P-1]) elementwise, in the order of Alg. 2's reduce phase
+ * (level l adds buffer r + 2^l into buffer r for r mod 2^(l+1) == 0), followed by the one
+ * rounding to y_dtype.  The partial buffers stand in for what the ranks would exchange.
+ *
+ *   partials   device, fp32, dense [P, M, N], 16-byte aligned     Y   device, [M, ldy], ldy >= N
+ * Errors: NULL, SHAPE, SHARDS, DTYPE, ALIGN, HIP.
+ */
+int tbik_tree_combine(const float *partials, int P, void *Y, int64_t ldy, tbik_dtype y_dtype,
+                      int M, int N, void *hip_stream);
+
+/*
+ * Batch-invariant RMSNorm (App. B: every row is reduced on its own in a fixed order), with the
+ * tree order of App. C along the row:
+ *   ss = TreeSum_i(x_i^2),  r = 1 / sqrt(ss / H + eps),  y_i = bf16((x_i * r) * w_i)
+ * TreeSum: leaves are in-order fp32 sums of 8 consecutive elements (16 bytes of bf16), the leaf
+ * count is padded with +0 leaves to a power of two, then T.  All arithmetic in fp32, one
+ * rounding to bf16 at the end.
+ *
+ *   x, y   device, bf16, dense [M, H]     weight   device, bf16, [H]
+ *   Alignment: x, y, weight 16 bytes; H a multiple of 8.  H <= 65536.
+ * Errors: NULL, SHAPE, ALIGN, HIP.
+ */
+int tbik_rmsnorm(const void *x, const void *weight, void *y, int M, int H, float eps, void *hip_stream);
+
+/*
+ * Batch-invariant row reductions over dense rows x[M, V] (App. B; softmax in fp32 per Sec. 2.1):
+ *   TBIK_SUM         out[m]   = TreeSum_i x[m,i]                                   out fp32 [M]
+ *   TBIK_MAX         out[m]   = max_i x[m,i]                                       out fp32 [M]
+ *   TBIK_LOGSOFTMAX  out[m,i] = (x[m,i] - mx) - log(TreeSum_j exp(x[m,j] - mx)),   out fp32 [M, V]
+ *                    mx = max_j x[m,j]
+ * TreeSum leaves are in-order fp32 sums of one 16-byte chunk of the row (4 fp32 or 8 bf16
+ * elements; the last leaf may be short), padded with +0 leaves to a power of two, then T.
+ * x_dtype TBIK_BF16 inputs are widened to fp32 first.  V == 0 is TBIK_ERR_SHAPE.
+ *
+ *   x          device, x_dtype, dense [M, V], 16-byte aligned, V a multiple of 4 (fp32) / 8 (bf16)
+ *   workspace  at least tbik_row_reduce_workspace_bytes(M, V, op) bytes, 256-byte aligned
+ * Errors: NULL, SHAPE, DTYPE, ALIGN, WORKSPACE, HIP.
+ */
+int tbik_row_reduce(const void *x, tbik_dtype x_dtype, void *out, tbik_rowop op, int M, int64_t V,
+                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Scratch sizes (pure host functions; 0 if the arguments are illegal or no scratch is needed).
+ * tbik_gemm_workspace_bytes covers tbik_gemm and tbik_gemm_shard_partials for any legal P. */
+size_t tbik_gemm_workspace_bytes(int M, int N, int K, int leaf, int k_first);
+size_t tbik_row_reduce_workspace_bytes(int M, int64_t V, tbik_rowop op);
+
+/* Reference kernel of tbik_gemm_shard_partials / tbik_gemm: one wavefront per 32x32 output tile,
+ * operands read straight from global memory, no workspace.  Slow, but its schedule is trivially
+ * independent of M and P; the tuned kernels must reproduce its bits.  Same arguments and errors
+ * as tbik_gemm_shard_partials; with y != NULL and P == 1 it also writes the rounded output. */
+int tbik_gemm_reference(const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
+                        void *Y, int64_t ldy, tbik_dtype y_dtype,
+                        int M, int N, int K, int leaf, int k_first, int P, void *hip_stream);
+
+/* Forces an internal GEMM variant (testing and tuning only; the bits never depend on it).
+ * 0 = choose from the shape (default); other values are listed in tbik_variant_name(). */
+int tbik_set_gemm_variant(int variant);
+const char *tbik_variant_name(int variant);      /* NULL past the last variant */
+
+const char *tbik_status_string(int status);
+int tbik_last_hip_error(void);                    /* hipError_t of the last TBIK_ERR_HIP, as int */
+const char *tbik_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TBIK_H */

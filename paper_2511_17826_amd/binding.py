@@ -1,0 +1,222 @@
+"""Thin Python binding of libtbik (argument marshalling only).
+
+Every function has the name of the C entry point it calls (``include/tbik.h``) and takes
+``torch`` tensors that already live on the GPU: PyTorch provides device memory and the current
+HIP stream, nothing else.  No arithmetic of the method happens in Python, and there is no CPU
+fallback: if ``libtbik.so`` is missing the import of the library fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtbik.so")
+
+TBIK_F32, TBIK_BF16 = 0, 1
+TBIK_SUM, TBIK_MAX, TBIK_LOGSOFTMAX = 0, 1, 2
+OK = 0
+
+VARIANT_AUTO, VARIANT_REFERENCE, VARIANT_T128, VARIANT_T32 = 0, 1, 2, 3
+
+# name -> (restype, argtypes); mirrors include/tbik.h
+SIGNATURES = {
+    "tbik_gemm": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int,
+                            C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tbik_gemm_shard_partials": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p,
+                                           C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                           C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tbik_tree_combine": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p]),
+    "tbik_rmsnorm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_void_p]),
+    "tbik_row_reduce": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int64,
+                                  C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tbik_gemm_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]),
+    "tbik_row_reduce_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int64, C.c_int]),
+    "tbik_gemm_reference": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64,
+                                      C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
+    "tbik_set_gemm_variant": (C.c_int, [C.c_int]),
+    "tbik_variant_name": (C.c_char_p, [C.c_int]),
+    "tbik_status_string": (C.c_char_p, [C.c_int]),
+    "tbik_last_hip_error": (C.c_int, []),
+    "tbik_version": (C.c_char_p, []),
+}
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads libtbik.so (built by ``python -m paper_2511_17826_amd.build``); raises if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libtbik.so is not built: run `python -m paper_2511_17826_amd.build` "
+                               "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = L
+    return _lib
+
+
+class TbikError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().tbik_status_string(status).decode()
+        if status == 8:
+            msg += " (hipError %d)" % lib().tbik_last_hip_error()
+        super().__init__("%s: %s" % (where, msg))
+
+
+def _check(status: int, where: str):
+    if status != OK:
+        raise TbikError(status, where)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return TBIK_F32
+    if t.dtype == torch.bfloat16:
+        return TBIK_BF16
+    raise TypeError("only float32 and bfloat16 tensors are supported, got %s" % t.dtype)
+
+
+def _rowmajor(t: torch.Tensor, name: str):
+    if t.dim() != 2 or t.stride(1) != 1 or not t.is_cuda:
+        raise ValueError("%s must be a 2-D row-major GPU tensor" % name)
+
+
+_ws_cache = {}
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    """A caller-side scratch tensor (the library itself never allocates)."""
+    key = str(device)
+    w = _ws_cache.get(key)
+    if w is None or w.numel() < nbytes:
+        w = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+        _ws_cache[key] = w
+    return w
+
+
+def gemm_workspace_bytes(M, N, K, leaf, k_first=1) -> int:
+    return int(lib().tbik_gemm_workspace_bytes(M, N, K, leaf, k_first))
+
+
+def tbik_gemm(X: torch.Tensor, W: torch.Tensor, leaf: int, k_first: int = 1, out_dtype=torch.bfloat16,
+              out: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Y = X @ W in the tree order, whole K on this device."""
+    _rowmajor(X, "X"); _rowmajor(W, "W")
+    assert X.dtype == torch.bfloat16 and W.dtype == torch.bfloat16
+    M, K = X.shape
+    K2, N = W.shape
+    assert K == K2
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=X.device)
+    _rowmajor(out, "out")
+    need = gemm_workspace_bytes(M, N, K, leaf, k_first)
+    if workspace is None and need:
+        workspace = _workspace(need, X.device)
+    st = lib().tbik_gemm(X.data_ptr(), X.stride(0), W.data_ptr(), W.stride(0), out.data_ptr(), out.stride(0),
+                         _dt(out), M, N, K, leaf, k_first,
+                         workspace.data_ptr() if workspace is not None else None,
+                         workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream())
+    _check(st, "tbik_gemm")
+    return out
+
+
+def tbik_gemm_shard_partials(X: torch.Tensor, W: torch.Tensor, leaf: int, k_first: int, P: int,
+                             out: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """partials[p] = subtree sum of K-shard p (fp32 [P, M, N])."""
+    _rowmajor(X, "X"); _rowmajor(W, "W")
+    assert X.dtype == torch.bfloat16 and W.dtype == torch.bfloat16
+    M, K = X.shape
+    N = W.shape[1]
+    assert W.shape[0] == K
+    if out is None:
+        out = torch.empty((max(P, 1), M, N), dtype=torch.float32, device=X.device)
+    assert out.is_contiguous() and out.dtype == torch.float32
+    need = gemm_workspace_bytes(M, N, K, leaf, k_first)
+    if workspace is None and need:
+        workspace = _workspace(need, X.device)
+    st = lib().tbik_gemm_shard_partials(X.data_ptr(), X.stride(0), W.data_ptr(), W.stride(0), out.data_ptr(),
+                                        M, N, K, leaf, k_first, P,
+                                        workspace.data_ptr() if workspace is not None else None,
+                                        workspace.numel() * workspace.element_size() if workspace is not None else 0,
+                                        _stream())
+    _check(st, "tbik_gemm_shard_partials")
+    return out
+
+
+def tbik_tree_combine(partials: torch.Tensor, out_dtype=torch.bfloat16, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Y = T(partials[0..P)) elementwise, one rounding to the output type."""
+    assert partials.dim() == 3 and partials.is_contiguous() and partials.dtype == torch.float32
+    P, M, N = partials.shape
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=partials.device)
+    _rowmajor(out, "out")
+    st = lib().tbik_tree_combine(partials.data_ptr(), P, out.data_ptr(), out.stride(0), _dt(out), M, N, _stream())
+    _check(st, "tbik_tree_combine")
+    return out
+
+
+def tbik_rmsnorm(x: torch.Tensor, weight: torch.Tensor, eps: float = 1e-6, out: torch.Tensor | None = None) -> torch.Tensor:
+    assert x.dim() == 2 and x.is_contiguous() and x.dtype == torch.bfloat16
+    assert weight.is_contiguous() and weight.dtype == torch.bfloat16 and weight.numel() == x.shape[1]
+    if out is None:
+        out = torch.empty_like(x)
+    st = lib().tbik_rmsnorm(x.data_ptr(), weight.data_ptr(), out.data_ptr(), x.shape[0], x.shape[1], eps, _stream())
+    _check(st, "tbik_rmsnorm")
+    return out
+
+
+def tbik_row_reduce(x: torch.Tensor, op: int, out: torch.Tensor | None = None,
+                    workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """op = TBIK_SUM / TBIK_MAX -> fp32 [M]; TBIK_LOGSOFTMAX -> fp32 [M, V]."""
+    assert x.dim() == 2 and x.is_contiguous()
+    M, V = x.shape
+    if out is None:
+        out = torch.empty((M, V) if op == TBIK_LOGSOFTMAX else (M,), dtype=torch.float32, device=x.device)
+    need = int(lib().tbik_row_reduce_workspace_bytes(M, V, op))
+    if workspace is None:
+        workspace = _workspace(need, x.device)
+    st = lib().tbik_row_reduce(x.data_ptr(), _dt(x), out.data_ptr(), op, M, V, workspace.data_ptr(),
+                               workspace.numel() * workspace.element_size(), _stream())
+    _check(st, "tbik_row_reduce")
+    return out
+
+
+def tbik_gemm_reference(X: torch.Tensor, W: torch.Tensor, leaf: int, k_first: int = 1, P: int = 1,
+                        out_dtype=torch.float32):
+    """The reference kernel: returns (partials [P,M,N] fp32, Y or None); Y only for P == 1."""
+    _rowmajor(X, "X"); _rowmajor(W, "W")
+    M, K = X.shape
+    N = W.shape[1]
+    parts = torch.empty((P, M, N), dtype=torch.float32, device=X.device)
+    Y = torch.empty((M, N), dtype=out_dtype, device=X.device) if P == 1 else None
+    st = lib().tbik_gemm_reference(X.data_ptr(), X.stride(0), W.data_ptr(), W.stride(0), parts.data_ptr(),
+                                   Y.data_ptr() if Y is not None else None, Y.stride(0) if Y is not None else 0,
+                                   _dt(Y) if Y is not None else TBIK_F32, M, N, K, leaf, k_first, P, _stream())
+    _check(st, "tbik_gemm_reference")
+    return parts, Y
+
+
+def tbik_set_gemm_variant(variant: int):
+    _check(lib().tbik_set_gemm_variant(variant), "tbik_set_gemm_variant")
+
+
+def variant_names():
+    out, i = [], 0
+    while True:
+        n = lib().tbik_variant_name(i)
+        if n is None:
+            return out
+        out.append(n.decode())
+        i += 1

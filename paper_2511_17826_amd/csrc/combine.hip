@@ -1,0 +1,111 @@
+// Top-of-tree combine (Sec. 4.2 "Inter-GPU reduction"; App. D.2, Alg. 2 reduce phase) on one GPU.
+//
+// The P partial tensors stand in for the ranks' buffers.  Per element the kernel performs exactly
+// the additions of Alg. 2: at level l, buffer r (r mod 2^(l+1) == 0) receives buffer r + 2^l.
+// Then the single rounding to the output type.  HBM-bound: 4*P bytes read + 2 or 4 written per element.
+#include "tbik_device.hpp"
+#include "tbik_internal.hpp"
+
+namespace tbik {
+
+template <int P>
+__device__ __forceinline__ float tree_of(float (&v)[P]) {
+#pragma unroll
+    for (int s = 1; s < P; s *= 2) {
+#pragma unroll
+        for (int r = 0; r < P; r += 2 * s) v[r] = v[r] + v[r + s];
+    }
+    return v[0];
+}
+
+// Vector path: N % 4 == 0; each thread owns 4 consecutive columns of one row.
+template <int P, bool OUT_BF16>
+__global__ __launch_bounds__(256) void tree_combine_vec4_kernel(const float *__restrict__ partials, void *__restrict__ Y,
+                                                                int64_t ldy, int64_t M, int64_t N) {
+    const int64_t quads_per_row = N >> 2;
+    const int64_t total = M * quads_per_row;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t plane = M * N;
+    for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < total; q += stride) {
+        const int64_t row = q / quads_per_row;
+        const int64_t col = (q - row * quads_per_row) << 2;
+        const float *src = partials + row * N + col;
+        float4 in[P];
+#pragma unroll
+        for (int p = 0; p < P; ++p) in[p] = *reinterpret_cast<const float4 *>(src + (int64_t)p * plane);
+        float vx[P], vy[P], vz[P], vw[P];
+#pragma unroll
+        for (int p = 0; p < P; ++p) { vx[p] = in[p].x; vy[p] = in[p].y; vz[p] = in[p].z; vw[p] = in[p].w; }
+        const float x = tree_of<P>(vx), y = tree_of<P>(vy), z = tree_of<P>(vz), w = tree_of<P>(vw);
+        if (OUT_BF16) {
+            uint16_t *dst = reinterpret_cast<uint16_t *>(Y) + row * ldy + col;
+            const uint32_t lo = f32_to_bf16_bits(x) | (f32_to_bf16_bits(y) << 16);
+            const uint32_t hi = f32_to_bf16_bits(z) | (f32_to_bf16_bits(w) << 16);
+            if ((reinterpret_cast<uintptr_t>(dst) & 7) == 0) {
+                *reinterpret_cast<uint2 *>(dst) = make_uint2(lo, hi);
+            } else {
+                dst[0] = (uint16_t)lo; dst[1] = (uint16_t)(lo >> 16); dst[2] = (uint16_t)hi; dst[3] = (uint16_t)(hi >> 16);
+            }
+        } else {
+            float *dst = reinterpret_cast<float *>(Y) + row * ldy + col;
+            if ((reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
+                *reinterpret_cast<float4 *>(dst) = make_float4(x, y, z, w);
+            } else {
+                dst[0] = x; dst[1] = y; dst[2] = z; dst[3] = w;
+            }
+        }
+    }
+}
+
+// Scalar path for any N.
+template <int P, bool OUT_BF16>
+__global__ __launch_bounds__(256) void tree_combine_scalar_kernel(const float *__restrict__ partials, void *__restrict__ Y,
+                                                                  int64_t ldy, int64_t M, int64_t N) {
+    const int64_t total = M * N;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += stride) {
+        const int64_t row = e / N, col = e - row * N;
+        float v[P];
+#pragma unroll
+        for (int p = 0; p < P; ++p) v[p] = partials[(int64_t)p * total + e];
+        const float y = tree_of<P>(v);
+        if (OUT_BF16) reinterpret_cast<uint16_t *>(Y)[row * ldy + col] = (uint16_t)f32_to_bf16_bits(y);
+        else reinterpret_cast<float *>(Y)[row * ldy + col] = y;
+    }
+}
+
+template <int P>
+static hipError_t launch_p(const float *partials, void *Y, int64_t ldy, int y_dtype, int M, int N, hipStream_t s) {
+    const bool bf = (y_dtype == TBIK_BF16);
+    const bool vec = (N % 4 == 0) && ((reinterpret_cast<uintptr_t>(partials) & 15) == 0);
+    const int64_t work = vec ? (int64_t)M * (N / 4) : (int64_t)M * N;
+    int64_t blocks = (work + 255) / 256;
+    if (blocks > 256 * 64) blocks = 256 * 64;   // grid-stride beyond 64 blocks per CU
+    if (blocks < 1) blocks = 1;
+    dim3 grid((unsigned)blocks), block(256);
+    if (vec) {
+        if (bf) hipLaunchKernelGGL((tree_combine_vec4_kernel<P, true>), grid, block, 0, s, partials, Y, ldy, (int64_t)M, (int64_t)N);
+        else hipLaunchKernelGGL((tree_combine_vec4_kernel<P, false>), grid, block, 0, s, partials, Y, ldy, (int64_t)M, (int64_t)N);
+    } else {
+        if (bf) hipLaunchKernelGGL((tree_combine_scalar_kernel<P, true>), grid, block, 0, s, partials, Y, ldy, (int64_t)M, (int64_t)N);
+        else hipLaunchKernelGGL((tree_combine_scalar_kernel<P, false>), grid, block, 0, s, partials, Y, ldy, (int64_t)M, (int64_t)N);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_tree_combine(const float *partials, int P, void *Y, int64_t ldy, int y_dtype, int M, int N,
+                               hipStream_t s) {
+    if (M <= 0 || N <= 0) return hipSuccess;
+    switch (P) {
+        case 1: return launch_p<1>(partials, Y, ldy, y_dtype, M, N, s);
+        case 2: return launch_p<2>(partials, Y, ldy, y_dtype, M, N, s);
+        case 4: return launch_p<4>(partials, Y, ldy, y_dtype, M, N, s);
+        case 8: return launch_p<8>(partials, Y, ldy, y_dtype, M, N, s);
+        case 16: return launch_p<16>(partials, Y, ldy, y_dtype, M, N, s);
+        case 32: return launch_p<32>(partials, Y, ldy, y_dtype, M, N, s);
+        case 64: return launch_p<64>(partials, Y, ldy, y_dtype, M, N, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace tbik

@@ -1,0 +1,76 @@
+// Batch-invariant RMSNorm (App. B) with the tree order of App. C along the row.
+//
+// One wavefront owns one row, whatever M is, so a row's arithmetic cannot depend on the batch.
+// Leaf c of the row's tree is the in-order fp32 sum of the squares of elements 8c..8c+7 (one
+// 16-byte load).  Leaves 64s..64s+63 sit in the 64 lanes of the wavefront: tree levels 0..5 are
+// lane-pair additions, the higher levels combine the per-segment sums in registers by the
+// carry-over scheme.  Leaves past the end of the row are +0, as in the definition.
+// HBM-bound: 2H bytes read + 2H written per row (the second read of x hits in cache).
+#include "tbik_device.hpp"
+#include "tbik_internal.hpp"
+
+namespace tbik {
+
+constexpr int RMS_ROWS_PER_BLOCK = 4;
+constexpr int RMS_MAX_SEG_LEVELS = 8;   // up to 2^7 = 128 segments of 64 leaves of 8 elements = 65536 columns
+
+__device__ __forceinline__ void unpack8(const uint4 &v, float (&f)[8]) {
+    f[0] = bf16_bits_to_f32(v.x & 0xffffu); f[1] = bf16_bits_to_f32(v.x >> 16);
+    f[2] = bf16_bits_to_f32(v.y & 0xffffu); f[3] = bf16_bits_to_f32(v.y >> 16);
+    f[4] = bf16_bits_to_f32(v.z & 0xffffu); f[5] = bf16_bits_to_f32(v.z >> 16);
+    f[6] = bf16_bits_to_f32(v.w & 0xffffu); f[7] = bf16_bits_to_f32(v.w >> 16);
+}
+
+__global__ __launch_bounds__(64 * RMS_ROWS_PER_BLOCK) void rmsnorm_kernel(
+        const uint16_t *__restrict__ x, const uint16_t *__restrict__ w, uint16_t *__restrict__ y,
+        int M, int H, float eps, int nseg2) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * RMS_ROWS_PER_BLOCK + (threadIdx.x >> 6);
+    if (row >= M) return;                              // whole wavefront leaves together
+    const int nchunks = H >> 3;
+    const uint4 *xr = reinterpret_cast<const uint4 *>(x + (int64_t)row * H);
+    const uint4 *wr = reinterpret_cast<const uint4 *>(w);
+    uint4 *yr = reinterpret_cast<uint4 *>(y + (int64_t)row * H);
+
+    TreeStash<RMS_MAX_SEG_LEVELS> st;
+    float ss = 0.0f;
+    for (int seg = 0; seg < nseg2; ++seg) {
+        const int c = seg * 64 + lane;
+        float leaf = 0.0f;
+        if (c < nchunks) {
+            float f[8];
+            unpack8(xr[c], f);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) leaf = leaf + f[e] * f[e];
+        }
+        ss = st.push(wave_tree_sum(leaf), (unsigned)seg);
+    }
+    const float ms = ss / (float)H;
+    const float r = 1.0f / sqrtf(ms + eps);
+
+    for (int c = lane; c < nchunks; c += 64) {
+        float f[8], g[8];
+        unpack8(xr[c], f);
+        unpack8(wr[c], g);
+        uint32_t o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float t = f[e] * r;
+            o[e] = f32_to_bf16_bits(t * g[e]);
+        }
+        yr[c] = make_uint4(o[0] | (o[1] << 16), o[2] | (o[3] << 16), o[4] | (o[5] << 16), o[6] | (o[7] << 16));
+    }
+}
+
+hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int M, int H, float eps, hipStream_t s) {
+    if (M <= 0) return hipSuccess;
+    const int nchunks = H / 8;
+    int n2 = 1;
+    while (n2 < nchunks) n2 *= 2;
+    const int nseg2 = n2 < 64 ? 1 : n2 / 64;
+    dim3 grid((M + RMS_ROWS_PER_BLOCK - 1) / RMS_ROWS_PER_BLOCK), block(64 * RMS_ROWS_PER_BLOCK);
+    hipLaunchKernelGGL(rmsnorm_kernel, grid, block, 0, s, x, w, y, M, H, eps, nseg2);
+    return hipGetLastError();
+}
+
+}  // namespace tbik

@@ -1,0 +1,216 @@
+// Batch-invariant row reductions (App. B) in the tree order of App. C: sum, max, log-softmax.
+//
+// A row is cut into blocks of 2048 leaves (one leaf = one 16-byte chunk = 4 fp32 or 8 bf16
+// elements).  One workgroup of 256 threads reduces one block of one row: leaf number
+// 256*seg + tid (seg = 0..7) of the block belongs to thread tid, so tree levels 0..5 are lane-pair
+// additions, levels 6..7 combine the four wavefronts, levels 8..10 the eight segments; the block
+// sums of a row are then combined by the same tree (blocks past the end of the row count as +0).
+// Which workgroup handles which (row, block) depends only on the row length, never on M, so a
+// row's bits cannot depend on the batch.  Log-softmax keeps the plain two-pass definition:
+// exact max first, then TreeSum(exp(x - max)).
+#include "tbik_device.hpp"
+#include "tbik_internal.hpp"
+
+namespace tbik {
+
+constexpr int RR_THREADS = 256;
+constexpr int RR_SEGS = 8;
+constexpr int RR_BLOCK_LEAVES = RR_THREADS * RR_SEGS;   // 2048
+
+enum { MODE_SUM = 0, MODE_MAX = 1, MODE_EXPSUM = 2 };
+
+template <bool BF16> struct Elem;
+template <> struct Elem<false> {
+    static constexpr int EPL = 4;   // elements per leaf
+    __device__ static __forceinline__ void load(const void *row, int64_t leaf, float (&f)[8]) {
+        const float4 v = reinterpret_cast<const float4 *>(row)[leaf];
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    }
+};
+template <> struct Elem<true> {
+    static constexpr int EPL = 8;
+    __device__ static __forceinline__ void load(const void *row, int64_t leaf, float (&f)[8]) {
+        const uint4 v = reinterpret_cast<const uint4 *>(row)[leaf];
+        f[0] = bf16_bits_to_f32(v.x & 0xffffu); f[1] = bf16_bits_to_f32(v.x >> 16);
+        f[2] = bf16_bits_to_f32(v.y & 0xffffu); f[3] = bf16_bits_to_f32(v.y >> 16);
+        f[4] = bf16_bits_to_f32(v.z & 0xffffu); f[5] = bf16_bits_to_f32(v.z >> 16);
+        f[6] = bf16_bits_to_f32(v.w & 0xffffu); f[7] = bf16_bits_to_f32(v.w >> 16);
+    }
+};
+
+// T over n2 (power of two) values of which the first n are stored at p and the rest are +0.
+// Executed by one whole wavefront; every lane returns the result.
+__device__ __forceinline__ float wave_tree_of_array(const float *p, int n, int n2, int lane) {
+    TreeStash<26> st;
+    float tot = 0.0f;
+    const int nseg = n2 < 64 ? 1 : n2 >> 6;
+    for (int seg = 0; seg < nseg; ++seg) {
+        const int i = seg * 64 + lane;
+        const float v = (i < n) ? p[i] : 0.0f;
+        tot = st.push(wave_tree_sum(v), (unsigned)seg);
+    }
+    return tot;
+}
+
+__device__ __forceinline__ float wave_max_of_array(const float *p, int n, int lane) {
+    float m = -INFINITY;
+    for (int i = lane; i < n; i += 64) m = fmaxf(m, p[i]);
+    return wave_max(m);
+}
+
+// Combines the per-thread leaf values L[seg] of a block in tree order; result valid in every thread.
+__device__ __forceinline__ float block_tree_sum(float (&L)[RR_SEGS], float *lds) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int seg = 0; seg < RR_SEGS; ++seg) {
+        const float w = wave_tree_sum(L[seg]);                      // levels 0..5
+        if (lane == 0) lds[seg * 4 + wave] = w;
+    }
+    __syncthreads();
+    float t[RR_SEGS];
+#pragma unroll
+    for (int seg = 0; seg < RR_SEGS; ++seg)                          // levels 6..7: the four wavefronts
+        t[seg] = (lds[seg * 4 + 0] + lds[seg * 4 + 1]) + (lds[seg * 4 + 2] + lds[seg * 4 + 3]);
+    const float r = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));   // levels 8..10
+    __syncthreads();
+    return r;
+}
+
+__device__ __forceinline__ float block_max(float m, float *lds) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    m = wave_max(m);
+    if (lane == 0) lds[wave] = m;
+    __syncthreads();
+    const float r = fmaxf(fmaxf(lds[0], lds[1]), fmaxf(lds[2], lds[3]));
+    __syncthreads();
+    return r;
+}
+
+// Pass over one (row, block): MODE_SUM -> block tree sum; MODE_MAX -> block max;
+// MODE_EXPSUM -> block tree sum of exp(x - rowmax), rowmax taken from the block maxima in wsmax.
+template <bool BF16, int MODE>
+__global__ __launch_bounds__(RR_THREADS) void row_block_kernel(const void *__restrict__ x, int64_t V, int nb,
+                                                               const float *__restrict__ wsmax, float *__restrict__ wsout) {
+    __shared__ float lds[RR_SEGS * 4];
+    constexpr int EPL = Elem<BF16>::EPL;
+    const int b = blockIdx.x, row = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int64_t nleaves = V / EPL;
+    const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * (BF16 ? 2 : 4);
+
+    float rowmax = 0.0f;
+    if (MODE == MODE_EXPSUM) rowmax = wave_max_of_array(wsmax + (int64_t)row * nb, nb, lane);
+
+    float L[RR_SEGS];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int seg = 0; seg < RR_SEGS; ++seg) {
+        const int64_t leaf = (int64_t)b * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
+        float acc = 0.0f;
+        if (leaf < nleaves) {
+            float f[8];
+            Elem<BF16>::load(rowp, leaf, f);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+                if (MODE == MODE_SUM) acc = acc + f[e];
+                else if (MODE == MODE_MAX) mx = fmaxf(mx, f[e]);
+                else acc = acc + expf(f[e] - rowmax);
+            }
+        }
+        L[seg] = acc;
+    }
+    float r;
+    if (MODE == MODE_MAX) r = block_max(mx, lds);
+    else r = block_tree_sum(L, lds);
+    if (threadIdx.x == 0) wsout[(int64_t)row * nb + b] = r;
+}
+
+// out[row] = tree (or max) over the nb block results of the row.  One wavefront per row.
+template <int MODE>
+__global__ __launch_bounds__(64) void row_finish_kernel(const float *__restrict__ ws, int nb, int nb2, float *__restrict__ out) {
+    const int row = blockIdx.x, lane = threadIdx.x;
+    const float *p = ws + (int64_t)row * nb;
+    const float r = (MODE == MODE_MAX) ? wave_max_of_array(p, nb, lane) : wave_tree_of_array(p, nb, nb2, lane);
+    if (lane == 0) out[row] = r;
+}
+
+// out[row, i] = (x[row, i] - rowmax) - log(S), S = tree over the row's block sums.
+template <bool BF16>
+__global__ __launch_bounds__(RR_THREADS) void logsoftmax_write_kernel(const void *__restrict__ x, int64_t V, int nb, int nb2,
+                                                                     const float *__restrict__ wsmax,
+                                                                     const float *__restrict__ wssum, float *__restrict__ out) {
+    constexpr int EPL = Elem<BF16>::EPL;
+    const int b = blockIdx.x, row = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int64_t nleaves = V / EPL;
+    const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * (BF16 ? 2 : 4);
+    float *orow = out + (int64_t)row * V;
+    const float rowmax = wave_max_of_array(wsmax + (int64_t)row * nb, nb, lane);
+    const float S = wave_tree_of_array(wssum + (int64_t)row * nb, nb, nb2, lane);
+    const float lg = logf(S);
+#pragma unroll
+    for (int seg = 0; seg < RR_SEGS; ++seg) {
+        const int64_t leaf = (int64_t)b * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
+        if (leaf < nleaves) {
+            float f[8];
+            Elem<BF16>::load(rowp, leaf, f);
+            float o[8];
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) o[e] = (f[e] - rowmax) - lg;
+            float4 *dst = reinterpret_cast<float4 *>(orow + leaf * EPL);
+            dst[0] = make_float4(o[0], o[1], o[2], o[3]);
+            if (EPL == 8) dst[1] = make_float4(o[4], o[5], o[6], o[7]);
+        }
+    }
+}
+
+static int blocks_of(int64_t V, int x_dtype) {
+    const int epl = (x_dtype == TBIK_BF16) ? 8 : 4;
+    const int64_t nleaves = V / epl;
+    return (int)((nleaves + RR_BLOCK_LEAVES - 1) / RR_BLOCK_LEAVES);
+}
+
+size_t row_reduce_workspace(int M, int64_t V, int x_dtype, int op) {
+    if (M <= 0 || V <= 0) return 0;
+    const size_t per = (size_t)M * blocks_of(V, x_dtype) * sizeof(float);
+    return (op == TBIK_LOGSOFTMAX) ? 2 * per : per;
+}
+
+template <bool BF16>
+static hipError_t run(const void *x, void *out, int op, int M, int64_t V, void *ws, hipStream_t s) {
+    const int nb = blocks_of(V, BF16 ? TBIK_BF16 : TBIK_F32);
+    int nb2 = 1;
+    while (nb2 < nb) nb2 *= 2;
+    float *ws0 = reinterpret_cast<float *>(ws);
+    float *ws1 = ws0 + (size_t)M * nb;
+    float *o = reinterpret_cast<float *>(out);
+    // gridDim.y is limited to 65535 rows per launch
+    for (int m0 = 0; m0 < M; m0 += 65535) {
+        const int mc = (M - m0) < 65535 ? (M - m0) : 65535;
+        const char *xp = reinterpret_cast<const char *>(x) + (int64_t)m0 * V * (BF16 ? 2 : 4);
+        float *w0 = ws0 + (size_t)m0 * nb, *w1 = ws1 + (size_t)m0 * nb;
+        dim3 grid(nb, mc), block(RR_THREADS);
+        if (op == TBIK_SUM) {
+            hipLaunchKernelGGL((row_block_kernel<BF16, MODE_SUM>), grid, block, 0, s, xp, V, nb, (const float *)nullptr, w0);
+            hipLaunchKernelGGL((row_finish_kernel<MODE_SUM>), dim3(mc), dim3(64), 0, s, w0, nb, nb2, o + m0);
+        } else if (op == TBIK_MAX) {
+            hipLaunchKernelGGL((row_block_kernel<BF16, MODE_MAX>), grid, block, 0, s, xp, V, nb, (const float *)nullptr, w0);
+            hipLaunchKernelGGL((row_finish_kernel<MODE_MAX>), dim3(mc), dim3(64), 0, s, w0, nb, nb2, o + m0);
+        } else {
+            hipLaunchKernelGGL((row_block_kernel<BF16, MODE_MAX>), grid, block, 0, s, xp, V, nb, (const float *)nullptr, w0);
+            hipLaunchKernelGGL((row_block_kernel<BF16, MODE_EXPSUM>), grid, block, 0, s, xp, V, nb, (const float *)w0, w1);
+            hipLaunchKernelGGL((logsoftmax_write_kernel<BF16>), grid, block, 0, s, xp, V, nb, nb2, (const float *)w0,
+                               (const float *)w1, o + (int64_t)m0 * V);
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_row_reduce(const void *x, int x_dtype, void *out, int op, int M, int64_t V, void *ws, hipStream_t s) {
+    if (M <= 0) return hipSuccess;
+    return (x_dtype == TBIK_BF16) ? run<true>(x, out, op, M, V, ws, s) : run<false>(x, out, op, M, V, ws, s);
+}
+
+}  // namespace tbik

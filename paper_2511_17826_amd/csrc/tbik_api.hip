@@ -1,0 +1,218 @@
+// C ABI of libtbik: argument validation, variant choice, launches.  No device memory is allocated here.
+#include <atomic>
+
+#include "tbik_internal.hpp"
+
+using namespace tbik;
+
+namespace {
+
+std::atomic<int> g_last_hip_error{0};
+std::atomic<int> g_forced_variant{VARIANT_AUTO};
+
+const char *const kVariantNames[VARIANT_COUNT] = {"auto", "reference", "tile128x128", "tile32x128"};
+
+inline bool is_pow2(int64_t v) { return v >= 1 && (v & (v - 1)) == 0; }
+inline bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int hip_fail(hipError_t e) {
+    g_last_hip_error.store((int)e);
+    return TBIK_ERR_HIP;
+}
+
+// Shape rules common to the GEMM entry points; fills superleaf / ns.
+int check_tree(int M, int N, int K, int leaf, int k_first, int P, int *superleaf, int *ns) {
+    if (M < 0 || N < 0 || K <= 0 || leaf <= 0 || k_first <= 0) return TBIK_ERR_SHAPE;
+    const int64_t sl = (int64_t)leaf * k_first;
+    if (sl > K || K % sl != 0 || sl % 16 != 0) return TBIK_ERR_SHAPE;
+    const int64_t n = K / sl;
+    if (!is_pow2(n)) return TBIK_ERR_SHAPE;
+    if (P < 1 || !is_pow2(P) || P > n || P > TBIK_MAX_SHARDS) return TBIK_ERR_SHARDS;
+    *superleaf = (int)sl;
+    *ns = (int)n;
+    return TBIK_OK;
+}
+
+int check_operands(const void *X, int64_t ldx, const void *W, int64_t ldw, int N, int K) {
+    if (!X || !W) return TBIK_ERR_NULL;
+    if (ldx < K || ldw < N) return TBIK_ERR_SHAPE;
+    if (!aligned(X, 16) || !aligned(W, 16) || ldx % 8 != 0 || ldw % 8 != 0) return TBIK_ERR_ALIGN;
+    return TBIK_OK;
+}
+
+// Internal split of K across workgroups for shapes with too few output tiles to fill the GPU.
+// Returns the shard count the tiled kernel is launched with when the caller asked for P shards.
+// Depends on the shape only; the result bits do not depend on it (Theorem 1).
+int internal_split(int M, int N, int ns) {
+    (void)M; (void)N; (void)ns;
+    return 1;
+}
+
+int pick_variant(const GemmArgs &a) {
+    const int forced = g_forced_variant.load();
+    if (forced != VARIANT_AUTO) return (forced == VARIANT_REFERENCE || gemm_tiled_supports(a, forced)) ? forced : VARIANT_REFERENCE;
+    if (a.M > 32 && gemm_tiled_supports(a, VARIANT_T128)) return VARIANT_T128;
+    if (gemm_tiled_supports(a, VARIANT_T32)) return VARIANT_T32;
+    if (gemm_tiled_supports(a, VARIANT_T128)) return VARIANT_T128;
+    return VARIANT_REFERENCE;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t tbik_gemm_workspace_bytes(int M, int N, int K, int leaf, int k_first) {
+    int sl, ns;
+    if (check_tree(M, N, K, leaf, k_first, 1, &sl, &ns) != TBIK_OK) return 0;
+    // fp32 partials of the internal K split, if this shape uses one
+    const int split = internal_split(M, N, ns);
+    return split > 1 ? (size_t)split * (size_t)M * (size_t)N * sizeof(float) : 0;
+}
+
+int tbik_gemm_shard_partials(const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
+                             int M, int N, int K, int leaf, int k_first, int P,
+                             void *workspace, size_t workspace_bytes, void *hip_stream) {
+    (void)workspace; (void)workspace_bytes;
+    int sl, ns;
+    int rc = check_tree(M, N, K, leaf, k_first, P, &sl, &ns);
+    if (rc != TBIK_OK) return rc;
+    if (M == 0 || N == 0) return TBIK_OK;
+    rc = check_operands(X, ldx, W, ldw, N, K);
+    if (rc != TBIK_OK) return rc;
+    if (!partials) return TBIK_ERR_NULL;
+    if (!aligned(partials, 16)) return TBIK_ERR_ALIGN;
+    GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)W, ldw, partials, nullptr, 0, TBIK_F32, M, N, K, sl, ns, P};
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int v = pick_variant(a);
+    hipError_t e = (v == VARIANT_REFERENCE) ? launch_gemm_reference(a, s) : launch_gemm_tiled(a, v, s);
+    return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
+int tbik_gemm(const void *X, int64_t ldx, const void *W, int64_t ldw, void *Y, int64_t ldy,
+              tbik_dtype y_dtype, int M, int N, int K, int leaf, int k_first,
+              void *workspace, size_t workspace_bytes, void *hip_stream) {
+    int sl, ns;
+    int rc = check_tree(M, N, K, leaf, k_first, 1, &sl, &ns);
+    if (rc != TBIK_OK) return rc;
+    if (y_dtype != TBIK_F32 && y_dtype != TBIK_BF16) return TBIK_ERR_DTYPE;
+    if (M == 0 || N == 0) return TBIK_OK;
+    rc = check_operands(X, ldx, W, ldw, N, K);
+    if (rc != TBIK_OK) return rc;
+    if (!Y) return TBIK_ERR_NULL;
+    if (ldy < N) return TBIK_ERR_SHAPE;
+    if (!aligned(Y, y_dtype == TBIK_F32 ? 4 : 2)) return TBIK_ERR_ALIGN;
+    const size_t need = tbik_gemm_workspace_bytes(M, N, K, leaf, k_first);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return TBIK_ERR_WORKSPACE;
+    if (workspace && !aligned(workspace, 256)) return TBIK_ERR_ALIGN;
+
+    hipStream_t s = (hipStream_t)hip_stream;
+    GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)W, ldw, nullptr, Y, ldy, (int)y_dtype, M, N, K, sl, ns, 1};
+    const int v = pick_variant(a);
+    const int split = (v == VARIANT_REFERENCE) ? 1 : internal_split(M, N, ns);
+    hipError_t e;
+    if (split == 1) {
+        e = (v == VARIANT_REFERENCE) ? launch_gemm_reference(a, s) : launch_gemm_tiled(a, v, s);
+    } else {
+        a.partials = reinterpret_cast<float *>(workspace);
+        a.Y = nullptr;
+        a.P = split;
+        e = launch_gemm_tiled(a, v, s);
+        if (e == hipSuccess) e = launch_tree_combine(a.partials, split, Y, ldy, (int)y_dtype, M, N, s);
+    }
+    return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
+int tbik_gemm_reference(const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
+                        void *Y, int64_t ldy, tbik_dtype y_dtype,
+                        int M, int N, int K, int leaf, int k_first, int P, void *hip_stream) {
+    int sl, ns;
+    int rc = check_tree(M, N, K, leaf, k_first, P, &sl, &ns);
+    if (rc != TBIK_OK) return rc;
+    if (y_dtype != TBIK_F32 && y_dtype != TBIK_BF16) return TBIK_ERR_DTYPE;
+    if (M == 0 || N == 0) return TBIK_OK;
+    rc = check_operands(X, ldx, W, ldw, N, K);
+    if (rc != TBIK_OK) return rc;
+    if (!partials && !Y) return TBIK_ERR_NULL;
+    if (Y && P != 1) return TBIK_ERR_SHARDS;
+    if (Y && ldy < N) return TBIK_ERR_SHAPE;
+    if (Y && !aligned(Y, y_dtype == TBIK_F32 ? 4 : 2)) return TBIK_ERR_ALIGN;
+    GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)W, ldw, partials, Y, ldy, (int)y_dtype, M, N, K, sl, ns, P};
+    hipError_t e = launch_gemm_reference(a, (hipStream_t)hip_stream);
+    return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
+int tbik_tree_combine(const float *partials, int P, void *Y, int64_t ldy, tbik_dtype y_dtype,
+                      int M, int N, void *hip_stream) {
+    if (M < 0 || N < 0) return TBIK_ERR_SHAPE;
+    if (P < 1 || !is_pow2(P) || P > TBIK_MAX_SHARDS) return TBIK_ERR_SHARDS;
+    if (y_dtype != TBIK_F32 && y_dtype != TBIK_BF16) return TBIK_ERR_DTYPE;
+    if (M == 0 || N == 0) return TBIK_OK;
+    if (!partials || !Y) return TBIK_ERR_NULL;
+    if (ldy < N) return TBIK_ERR_SHAPE;
+    if (!aligned(partials, 16) || !aligned(Y, y_dtype == TBIK_F32 ? 4 : 2)) return TBIK_ERR_ALIGN;
+    hipError_t e = launch_tree_combine(partials, P, Y, ldy, (int)y_dtype, M, N, (hipStream_t)hip_stream);
+    return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
+int tbik_rmsnorm(const void *x, const void *weight, void *y, int M, int H, float eps, void *hip_stream) {
+    if (M < 0 || H <= 0 || H % 8 != 0 || H > 65536) return TBIK_ERR_SHAPE;
+    if (M == 0) return TBIK_OK;
+    if (!x || !weight || !y) return TBIK_ERR_NULL;
+    if (!aligned(x, 16) || !aligned(weight, 16) || !aligned(y, 16)) return TBIK_ERR_ALIGN;
+    hipError_t e = launch_rmsnorm((const uint16_t *)x, (const uint16_t *)weight, (uint16_t *)y, M, H, eps,
+                                  (hipStream_t)hip_stream);
+    return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
+size_t tbik_row_reduce_workspace_bytes(int M, int64_t V, tbik_rowop op) {
+    if (op != TBIK_SUM && op != TBIK_MAX && op != TBIK_LOGSOFTMAX) return 0;
+    // sized for the finer of the two input types (fp32 rows have twice the leaves of bf16 rows)
+    return row_reduce_workspace(M, V, TBIK_F32, (int)op);
+}
+
+int tbik_row_reduce(const void *x, tbik_dtype x_dtype, void *out, tbik_rowop op, int M, int64_t V,
+                    void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (x_dtype != TBIK_F32 && x_dtype != TBIK_BF16) return TBIK_ERR_DTYPE;
+    if (op != TBIK_SUM && op != TBIK_MAX && op != TBIK_LOGSOFTMAX) return TBIK_ERR_DTYPE;
+    const int epl = (x_dtype == TBIK_BF16) ? 8 : 4;
+    if (M < 0 || V <= 0 || V % epl != 0) return TBIK_ERR_SHAPE;
+    if (M == 0) return TBIK_OK;
+    if (!x || !out) return TBIK_ERR_NULL;
+    if (!aligned(x, 16) || !aligned(out, op == TBIK_LOGSOFTMAX ? 16 : 4)) return TBIK_ERR_ALIGN;
+    const size_t need = row_reduce_workspace(M, V, (int)x_dtype, (int)op);
+    if (!workspace || workspace_bytes < need) return TBIK_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return TBIK_ERR_ALIGN;
+    hipError_t e = launch_row_reduce(x, (int)x_dtype, out, (int)op, M, V, workspace, (hipStream_t)hip_stream);
+    return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
+int tbik_set_gemm_variant(int variant) {
+    if (variant < 0 || variant >= VARIANT_COUNT) return TBIK_ERR_UNSUPPORTED;
+    g_forced_variant.store(variant);
+    return TBIK_OK;
+}
+
+const char *tbik_variant_name(int variant) {
+    return (variant >= 0 && variant < VARIANT_COUNT) ? kVariantNames[variant] : nullptr;
+}
+
+const char *tbik_status_string(int status) {
+    switch (status) {
+        case TBIK_OK: return "ok";
+        case TBIK_ERR_NULL: return "null pointer";
+        case TBIK_ERR_SHAPE: return "illegal shape or tree parameters";
+        case TBIK_ERR_SHARDS: return "illegal shard count";
+        case TBIK_ERR_DTYPE: return "illegal dtype or op";
+        case TBIK_ERR_ALIGN: return "misaligned pointer or leading dimension";
+        case TBIK_ERR_WORKSPACE: return "workspace missing or too small";
+        case TBIK_ERR_UNSUPPORTED: return "unsupported";
+        case TBIK_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int tbik_last_hip_error(void) { return g_last_hip_error.load(); }
+
+const char *tbik_version(void) { return "tbik-gfx950 0.1"; }
+
+}  // extern "C"

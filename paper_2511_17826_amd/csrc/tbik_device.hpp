@@ -1,0 +1,63 @@
+// Device-side helpers shared by the TBIK kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tbik {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+// bf16 (bit pattern) -> fp32, exact.
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+// fp32 -> bf16 bit pattern, round to nearest even (the single rounding of an output element).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x0040u;   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// Streaming evaluation of the tree operator T (App. C) by the carry-over scheme of App. D.1:
+// values arrive in index order; slot l holds a finished subtree of 2^l values that waits for its
+// right sibling.  push(v, idx) folds value number idx in and returns the running value, which after
+// the last value (idx = 2^t - 1) is T of all of them.  `idx` must be wave-uniform so that the
+// slots are addressed statically (they stay in registers).
+template <int LEVELS>
+struct TreeStash {
+    float s[LEVELS > 0 ? LEVELS : 1];
+    __device__ __forceinline__ float push(float v, unsigned idx) {
+        const int t = __builtin_ctz(~idx);          // number of trailing one bits of idx
+#pragma unroll
+        for (int l = 0; l < LEVELS; ++l)
+            if (l < t) v = s[l] + v;                // left sibling (earlier) + right sibling (later)
+#pragma unroll
+        for (int l = 0; l < LEVELS; ++l)
+            if (l == t) s[l] = v;
+        return v;
+    }
+};
+
+// One level of the tree across lanes: lane i and lane i^mask hold sibling subtrees; both get the sum.
+__device__ __forceinline__ float lane_pair_add(float v, int mask) { return v + __shfl_xor(v, mask, 64); }
+
+// T over the 64 lanes of a wavefront (lane index = leaf index): levels 0..5.  Every lane gets the result.
+__device__ __forceinline__ float wave_tree_sum(float v) {
+    v = lane_pair_add(v, 1);
+    v = lane_pair_add(v, 2);
+    v = lane_pair_add(v, 4);
+    v = lane_pair_add(v, 8);
+    v = lane_pair_add(v, 16);
+    v = lane_pair_add(v, 32);
+    return v;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+    return v;
+}
+
+}  // namespace tbik

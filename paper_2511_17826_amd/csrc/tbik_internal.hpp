@@ -1,0 +1,47 @@
+// Host-side declarations shared between the translation units of libtbik.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/tbik.h"
+
+namespace tbik {
+
+// Resolved description of one GEMM request; validated by the C ABI layer before any launch.
+struct GemmArgs {
+    const uint16_t *X;   // bf16 [M, ldx]
+    int64_t ldx;
+    const uint16_t *W;   // bf16 [K, ldw]
+    int64_t ldw;
+    float *partials;     // fp32 [P, M, N] or nullptr
+    void *Y;             // [M, ldy] of y_dtype or nullptr
+    int64_t ldy;
+    int y_dtype;         // tbik_dtype
+    int M, N, K;
+    int superleaf;       // leaf * k_first
+    int ns;              // number of superleaves (power of two)
+    int P;               // shards (power of two, <= ns)
+};
+
+// Reference kernel: one wavefront per 32x32 tile and shard.  Writes partials (if set) and, when P == 1
+// and Y is set, the rounded output.
+hipError_t launch_gemm_reference(const GemmArgs &a, hipStream_t s);
+
+// Tiled kernels.  `variant` selects the tile shape (see kVariantNames); returns hipErrorInvalidValue
+// if the variant cannot run this shape.  Same outputs as the reference kernel.
+hipError_t launch_gemm_tiled(const GemmArgs &a, int variant, hipStream_t s);
+bool gemm_tiled_supports(const GemmArgs &a, int variant);
+
+// Y = T(partials[0..P)) elementwise + one rounding.
+hipError_t launch_tree_combine(const float *partials, int P, void *Y, int64_t ldy, int y_dtype, int M, int N,
+                               hipStream_t s);
+
+hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int M, int H, float eps, hipStream_t s);
+
+size_t row_reduce_workspace(int M, int64_t V, int x_dtype, int op);
+hipError_t launch_row_reduce(const void *x, int x_dtype, void *out, int op, int M, int64_t V, void *ws, hipStream_t s);
+
+enum { VARIANT_AUTO = 0, VARIANT_REFERENCE = 1, VARIANT_T128 = 2, VARIANT_T32 = 3, VARIANT_COUNT = 4 };
+
+}  // namespace tbik

@@ -1,0 +1,119 @@
+"""The C-ABI library loads, exports every function declared in include/tbik.h, and rejects bad
+arguments before touching the device (CPU only: no kernel is launched here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2511_17826_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2511_17826_amd import build
+        build.build()
+    return binding.lib()
+
+
+def declared_functions():
+    src = open(os.path.join(ROOT, "include", "tbik.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    names = re.findall(r"\b(tbik_[a-z0-9_]+)\s*\(", src)
+    return sorted(set(names))
+
+
+def test_every_declared_symbol_is_exported_and_bound(L):
+    from paper_2511_17826_amd import binding
+    names = declared_functions()
+    assert {"tbik_gemm", "tbik_gemm_shard_partials", "tbik_tree_combine", "tbik_rmsnorm", "tbik_row_reduce"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+        assert n in binding.SIGNATURES, "binding lacks a signature for " + n
+
+
+def test_status_strings_and_version(L):
+    assert L.tbik_status_string(0) == b"ok"
+    assert all(L.tbik_status_string(i) for i in range(0, 10))
+    assert L.tbik_version().startswith(b"tbik")
+    assert L.tbik_variant_name(0) == b"auto" and L.tbik_variant_name(99) is None
+
+
+def test_workspace_sizes_are_pure_and_zero_for_illegal_shapes(L):
+    assert L.tbik_gemm_workspace_bytes(4, 256, 512, 64, 1) == L.tbik_gemm_workspace_bytes(4, 256, 512, 64, 1)
+    assert L.tbik_gemm_workspace_bytes(4, 256, 500, 64, 1) == 0
+    assert L.tbik_row_reduce_workspace_bytes(512, 151936, 2) >= 2 * 512 * 19 * 4
+    assert L.tbik_row_reduce_workspace_bytes(4, 100, 7) == 0
+
+
+GOOD = 0x1000  # a fake, aligned, non-null "device pointer": validation must fail before it is ever used
+
+
+def gemm(L, **kw):
+    a = dict(X=GOOD, ldx=512, W=GOOD, ldw=256, Y=GOOD, ldy=256, dt=1, M=4, N=256, K=512, leaf=64, g=1, ws=None, wsb=0)
+    a.update(kw)
+    return L.tbik_gemm(a["X"], a["ldx"], a["W"], a["ldw"], a["Y"], a["ldy"], a["dt"], a["M"], a["N"], a["K"],
+                       a["leaf"], a["g"], a["ws"], a["wsb"], None)
+
+
+def test_gemm_argument_validation(L):
+    assert gemm(L, M=0) == 0 and gemm(L, N=0) == 0                    # empty problem: OK, nothing launched
+    assert gemm(L, X=None) == 1 and gemm(L, W=None) == 1 and gemm(L, Y=None) == 1
+    assert gemm(L, K=500) == 2                                         # K not a multiple of the superleaf
+    assert gemm(L, K=384, ldx=384) == 2                                # 6 superleaves: not a power of two
+    assert gemm(L, leaf=8, g=1, K=512) == 2                            # superleaf not a multiple of 16
+    assert gemm(L, M=-1) == 2 and gemm(L, leaf=0) == 2
+    assert gemm(L, ldx=504) == 2 and gemm(L, ldy=100) == 2             # leading dimension too small
+    assert gemm(L, dt=5) == 4
+    assert gemm(L, X=GOOD + 2) == 5 and gemm(L, ldw=260) == 5          # misaligned pointer / leading dimension
+
+
+def test_shard_and_combine_validation(L):
+    sp = L.tbik_gemm_shard_partials
+    args = lambda P, part=GOOD: (GOOD, 512, GOOD, 256, part, 4, 256, 512, 64, 1, P, None, 0, None)
+    assert sp(*args(3)) == 3 and sp(*args(0)) == 3 and sp(*args(16)) == 3      # not a power of two / > n_s = 8
+    assert sp(*args(2, None)) == 1
+    tc = L.tbik_tree_combine
+    assert tc(GOOD, 3, GOOD, 256, 1, 4, 256, None) == 3
+    assert tc(GOOD, 128, GOOD, 256, 1, 4, 256, None) == 3
+    assert tc(None, 2, GOOD, 256, 1, 4, 256, None) == 1
+    assert tc(GOOD, 2, GOOD, 100, 1, 4, 256, None) == 2
+    assert tc(GOOD, 2, GOOD, 256, 9, 4, 256, None) == 4
+    assert tc(GOOD, 2, GOOD, 256, 1, 0, 256, None) == 0
+
+
+def test_reduction_validation(L):
+    rn = L.tbik_rmsnorm
+    assert rn(GOOD, GOOD, GOOD, 0, 4096, 1e-6, None) == 0
+    assert rn(None, GOOD, GOOD, 4, 4096, 1e-6, None) == 1
+    assert rn(GOOD, GOOD, GOOD, 4, 4100, 1e-6, None) == 2
+    assert rn(GOOD + 8, GOOD, GOOD, 4, 4096, 1e-6, None) == 5
+    rr = L.tbik_row_reduce
+    assert rr(GOOD, 0, GOOD, 2, 0, 1024, GOOD, 1 << 20, None) == 0
+    assert rr(GOOD, 0, GOOD, 2, 4, 1022, GOOD, 1 << 20, None) == 2
+    assert rr(GOOD, 0, GOOD, 2, 4, 0, GOOD, 1 << 20, None) == 2
+    assert rr(GOOD, 3, GOOD, 2, 4, 1024, GOOD, 1 << 20, None) == 4
+    assert rr(GOOD, 0, GOOD, 5, 4, 1024, GOOD, 1 << 20, None) == 4
+    assert rr(GOOD, 0, GOOD, 2, 4, 1024, None, 0, None) == 6
+    assert rr(GOOD, 0, GOOD, 2, 4, 1024, GOOD, 8, None) == 6
+    assert rr(None, 0, GOOD, 0, 4, 1024, GOOD, 1 << 20, None) == 1
+
+
+def test_variant_switch(L):
+    assert L.tbik_set_gemm_variant(99) == 7
+    assert L.tbik_set_gemm_variant(1) == 0
+    assert L.tbik_set_gemm_variant(0) == 0
+
+
+def test_product_path_does_not_import_the_oracle():
+    """The binding and the sources of the library never reference oracle/ (the oracle is test infrastructure)."""
+    pkg = os.path.join(ROOT, "paper_2511_17826_amd")
+    for dirpath, _, files in os.walk(pkg):
+        if "_build" in dirpath:
+            continue
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "tbik_oracle" not in text and "from oracle" not in text and "import oracle" not in text, f

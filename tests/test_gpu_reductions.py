@@ -1,0 +1,134 @@
+"""GPU parity and invariance tests of the tree-ordered row reductions (through the C ABI).
+
+Bars: RMSNorm, row sum and row max are bit-exact against the oracle (all their arithmetic is IEEE fp32
+in a fixed order).  Log-softmax uses the device's exp/log, so it is checked within
+|o_gpu - o_oracle| <= 1e-5 * max(1, |o|); GPU against GPU (any M, any row position) is always 0 bits.
+"""
+import numpy as np
+import pytest
+import torch
+
+import gpu_util as gu
+from oracle import tbik_oracle as orc
+from paper_2511_17826_amd import binding as tb
+from paper_2511_17826_amd import synthetic as syn
+
+pytestmark = pytest.mark.gpu
+
+
+# ----------------------------------------------------------------------------- RMSNorm
+
+@pytest.mark.parametrize("H", [4096, 5120, 24, 1000, 8192])
+def test_rmsnorm_bit_exact_and_batch_invariant(H):
+    Mmax = 8192 if H in (4096, 5120) else 300
+    x, w = syn.rmsnorm_inputs(Mmax, H)
+    xd, wd = gu.dev_bf16(x), gu.dev_bf16(w)
+    full = tb.tbik_rmsnorm(xd, wd, 1e-6)
+    torch.cuda.synchronize()
+    n_check = min(Mmax, 1024)
+    want = orc.rmsnorm(x[:n_check], w, 1e-6)
+    assert np.array_equal(gu.host_bf16_bits(full[:n_check]), want)
+    want_tail = orc.rmsnorm(x[-64:], w, 1e-6)
+    assert np.array_equal(gu.host_bf16_bits(full[-64:]), want_tail)
+    for M in (1, 2, 3, 7, 16, 64, 255, 256, 1024, 4096, 8192):
+        if M > Mmax:
+            continue
+        y = tb.tbik_rmsnorm(xd[:M].contiguous(), wd, 1e-6)
+        assert torch.equal(y.view(torch.int16), full[:M].view(torch.int16)), M
+    # shifted position: rows 100..163 run as their own batch
+    if Mmax >= 200:
+        y = tb.tbik_rmsnorm(xd[100:164].contiguous(), wd, 1e-6)
+        assert torch.equal(y.view(torch.int16), full[100:164].view(torch.int16))
+
+
+def test_rmsnorm_closed_form():
+    H = 4096
+    x = syn.f32_to_bf16_bits(np.ones((5, H), dtype=np.float32))
+    w = syn.f32_to_bf16_bits(np.ones(H, dtype=np.float32))
+    y = gu.host_bf16_bits(tb.tbik_rmsnorm(gu.dev_bf16(x), gu.dev_bf16(w), 1e-6))
+    r = np.float32(1.0) / np.sqrt(np.float32(1.0) + np.float32(1e-6), dtype=np.float32)
+    assert np.all(y == syn.f32_to_bf16_bits(np.array([r]))[0])
+
+
+# ----------------------------------------------------------------------------- sum / max
+
+@pytest.mark.parametrize("V", [4, 1024, 8192, 8196, 151936, 300000])
+def test_row_sum_and_max_bit_exact(V):
+    M = 9
+    rng = np.random.default_rng(V)
+    x = (rng.standard_normal((M, V)) * np.exp2(rng.integers(-6, 7, (M, V)))).astype(np.float32)
+    xd = gu.dev_f32(x)
+    s = gu.host_f32(tb.tbik_row_reduce(xd, tb.TBIK_SUM))
+    assert np.array_equal(gu.u32(s), gu.u32(orc.row_sum(x, orc.LEAF_F32)))
+    m = gu.host_f32(tb.tbik_row_reduce(xd, tb.TBIK_MAX))
+    assert np.array_equal(m, x.max(axis=1))
+    # batch invariance
+    s1 = gu.host_f32(tb.tbik_row_reduce(xd[4:5].contiguous(), tb.TBIK_SUM))
+    assert gu.u32(s1)[0] == gu.u32(s)[4]
+
+
+def test_row_sum_bf16_input_bit_exact():
+    M, V = 5, 20000
+    xb = syn.normal_bf16(np.random.Generator(np.random.PCG64(1)), (M, V), 2.0)
+    s = gu.host_f32(tb.tbik_row_reduce(gu.dev_bf16(xb), tb.TBIK_SUM))
+    want = orc.row_sum(syn.bf16_bits_to_f32(xb), orc.LEAF_BF16)
+    assert np.array_equal(gu.u32(s), gu.u32(want))
+
+
+def test_row_sum_hand_value():
+    """Leaves [1,0,0,0 | t,t,0,0 | ...]: (1) + (2^-23) at the first tree level = 1 + 2^-23; strict left-to-right gives 1."""
+    t = 2.0 ** -24
+    x = np.zeros((1, 16), dtype=np.float32)
+    x[0, 0], x[0, 4], x[0, 5] = 1.0, t, t
+    s = gu.host_f32(tb.tbik_row_reduce(gu.dev_f32(x), tb.TBIK_SUM))
+    assert int(gu.u32(s)[0]) == 0x3F800001
+    x2 = np.zeros((1, 16), dtype=np.float32)
+    x2[0, 0], x2[0, 1], x2[0, 2] = 1.0, t, t        # same leaf: sequential inside the leaf -> ties -> 1.0
+    s2 = gu.host_f32(tb.tbik_row_reduce(gu.dev_f32(x2), tb.TBIK_SUM))
+    assert int(gu.u32(s2)[0]) == 0x3F800000
+
+
+# ----------------------------------------------------------------------------- log-softmax
+
+def test_logsoftmax_parity_and_invariance():
+    V = 151936
+    x = syn.logits_f32(64, V)
+    xd = gu.dev_f32(x)
+    full = tb.tbik_row_reduce(xd, tb.TBIK_LOGSOFTMAX)
+    torch.cuda.synchronize()
+    o = gu.host_f32(full)
+    want = orc.row_logsoftmax(x[:16], orc.LEAF_F32)
+    assert np.max(np.abs(o[:16] - want) / np.maximum(1.0, np.abs(want))) <= 1e-5
+    assert np.all(np.abs(np.exp(o.astype(np.float64)).sum(axis=1) - 1.0) <= 1e-5)
+    for (a, b) in [(0, 1), (5, 6), (0, 64), (17, 40)]:
+        y = tb.tbik_row_reduce(xd[a:b].contiguous(), tb.TBIK_LOGSOFTMAX)
+        assert torch.equal(y.view(torch.int32), full[a:b].view(torch.int32)), (a, b)
+    # twice the same call: same bits
+    again = tb.tbik_row_reduce(xd, tb.TBIK_LOGSOFTMAX)
+    assert torch.equal(again.view(torch.int32), full.view(torch.int32))
+
+
+def test_logsoftmax_constant_row_and_small_V():
+    for V in (4, 1024, 4096):
+        x = np.full((3, V), 1.25, dtype=np.float32)
+        o = gu.host_f32(tb.tbik_row_reduce(gu.dev_f32(x), tb.TBIK_LOGSOFTMAX))
+        assert np.max(np.abs(o + np.log(V))) <= 1e-5 * max(1.0, np.log(V))
+    x = syn.logits_f32(7, 4096)
+    o = gu.host_f32(tb.tbik_row_reduce(gu.dev_f32(x), tb.TBIK_LOGSOFTMAX))
+    want = orc.row_logsoftmax(x)
+    assert np.max(np.abs(o - want) / np.maximum(1.0, np.abs(want))) <= 1e-5
+
+
+def test_logsoftmax_512_rows_sampled():
+    """The full 512 x 151936 case in the launch shape the benchmark times; rows sampled for the oracle."""
+    V = 151936
+    x = syn.logits_f32(512, V)
+    xd = gu.dev_f32(x)
+    o = tb.tbik_row_reduce(xd, tb.TBIK_LOGSOFTMAX)
+    torch.cuda.synchronize()
+    rows = [0, 63, 200, 511]
+    want = orc.row_logsoftmax(x[rows])
+    got = gu.host_f32(o[rows])
+    assert np.max(np.abs(got - want) / np.maximum(1.0, np.abs(want))) <= 1e-5
+    one = tb.tbik_row_reduce(xd[200:201].contiguous(), tb.TBIK_LOGSOFTMAX)
+    assert torch.equal(one.view(torch.int32), o[200:201].view(torch.int32))
