@@ -13,7 +13,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libtbik.so")
+# TBIK_LIB_PATH points development runs at an alternative build of the same library.
+LIB_PATH = os.environ.get("TBIK_LIB_PATH") or os.path.join(_HERE, "libtbik.so")
 
 TBIK_F32, TBIK_BF16 = 0, 1
 TBIK_SUM, TBIK_MAX, TBIK_LOGSOFTMAX = 0, 1, 2

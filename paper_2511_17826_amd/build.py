@@ -21,7 +21,9 @@ SOURCES = ["tbik_api.hip", "gemm_reference.hip", "gemm_tiled.hip", "combine.hip"
 
 # -ffp-contract=off: a tree addition or an RMSNorm multiply must never be fused into an FMA.
 # packed-fp32 ops are switched off for the device pass (known-bad forms on the test machines).
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-fno-fast-math",
+# -amdgpu-mfma-vgpr-form: MFMA accumulators are allocated as ordinary VGPRs, so the tree additions (VALU) work
+# on them in place and the allocator parks the cold stash levels in AGPRs instead of spilling to scratch.
+FLAGS = ["--offload-arch=gfx950", "-mllvm", "-amdgpu-mfma-vgpr-form", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-fno-fast-math",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument",
          "-Wno-unknown-attributes"]
 
@@ -45,16 +47,16 @@ def _compile(src: str, extra) -> str:
     return obj
 
 
-def build(save_temps: bool = False, jobs: int = 8) -> str:
+def build(save_temps: bool = False, jobs: int = 8, defines=(), lib_path: str = LIB) -> str:
     os.makedirs(BUILD, exist_ok=True)
-    extra = ["-save-temps=obj"] if save_temps else []
+    extra = (["-save-temps=obj"] if save_temps else []) + ["-D" + d for d in defines]
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(lambda s: _compile(s, extra), SOURCES))
-    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib_path, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout + r.stderr)
-    return LIB
+    return lib_path
 
 
 if __name__ == "__main__":

@@ -1,23 +1,37 @@
 // Tiled Tree-Based MatMul kernels (App. D.1, Alg. 1) for gfx950.
 //
-// A workgroup of 4 wavefronts owns one BM x BN output tile of one K-shard and walks the shard's
+// A workgroup of 4 wavefronts owns one BM x 128 output tile of one K-shard and walks the shard's
 // superleaves in ascending k.  Per superleaf each wavefront chains v_mfma_f32_32x32x16_bf16 over
 // ascending groups of 16 k into accumulators that start at +0 (the same opcode and k -> (step,
 // slot) map as the reference kernel, which is what makes all variants bit-identical); when a
 // superleaf ends, the carry-over step folds the accumulators into the stash of waiting subtrees,
 // which lives in registers (one wavefront per SIMD, up to 512 VGPR+AGPR per lane).
 //
-// Operands are staged through LDS in K-steps of 64 with double buffering: X rows keep their
-// K-contiguous order; W ([K,N], N contiguous) is transposed in registers on the way in, so both
-// MFMA operands are read from LDS as 16-byte, K-contiguous fragments.  Rows are padded to
-// 144 bytes, which spreads a fragment read of 16 rows over all 64 LDS banks.
+// Operands are staged through LDS in K-steps of 64 with double buffering, both in their global
+// orientation, written with 16-byte stores:
+//   X tile [BM][64]  rows of 128 B; the 16-byte chunk c of row r sits at position c ^ ((r>>1)&7),
+//                    so the 16 rows of a fragment read (ds_read_b128) hit all 64 banks once;
+//   W tile [64][128] rows of 256 B; chunk c of row k sits at position c ^ (4*(k&3)); the MFMA's
+//                    B operand (8 consecutive k of one column per lane) is fetched with the
+//                    transposing LDS read ds_read_b64_tr_b16, whose 16-lane groups read 4 rows x
+//                    16 columns: with the swizzle the 4 rows fall into different banks.
 #include "tbik_device.hpp"
 #include "tbik_internal.hpp"
 
 namespace tbik {
 
 constexpr int BK = 64;                 // K-elements per LDS stage
-constexpr int PITCH = BK * 2 + 16;     // bytes per LDS row (64 bf16 + 16 pad)
+constexpr int BN_TILE = 128;           // columns per workgroup tile
+constexpr int A_ROW = BK * 2;          // bytes per LDS row of the X tile
+constexpr int B_ROW = BN_TILE * 2;     // bytes per LDS row of the W tile
+
+// Stash levels kept in registers by the 128x128 tile (the rest go to LDS).
+#ifndef TBIK_MAX_REG_LEVELS
+#define TBIK_MAX_REG_LEVELS 4
+#endif
+
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 template <int MT, int NT>              // 32x32 MFMA tiles per wavefront
 struct Acc {
@@ -25,9 +39,39 @@ struct Acc {
 };
 
 // Stash of finished subtrees (App. D.1: accumulator buffer S[level]); every slot is addressed statically.
-template <int LEVELS, int MT, int NT>
+// Levels below REG_LEVELS live in registers; the levels above (written and read once per 2^level
+// superleaves) live in LDS, 16 floats per lane and slot-row, each lane owning its own 16-byte columns.
+template <int REG_LEVELS, int MT, int NT>
 struct TileStash {
-    Acc<MT, NT> s[LEVELS > 0 ? LEVELS : 1];
+    Acc<MT, NT> s[REG_LEVELS > 0 ? REG_LEVELS : 1];
+    unsigned char *lds;          // base of the LDS stash area (per workgroup)
+    static constexpr int LDS_LEVEL_BYTES = MT * NT * 16 * 4 * 256;
+
+    __device__ __forceinline__ void lds_store(int level, const Acc<MT, NT> &acc) const {
+        f32x4 *dst = reinterpret_cast<f32x4 *>(lds + (level - REG_LEVELS) * LDS_LEVEL_BYTES) + threadIdx.x;
+#pragma unroll
+        for (int a = 0; a < MT; ++a)
+#pragma unroll
+            for (int b = 0; b < NT; ++b)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    f32x4 v = {acc.t[a][b][4 * q], acc.t[a][b][4 * q + 1], acc.t[a][b][4 * q + 2], acc.t[a][b][4 * q + 3]};
+                    dst[((a * NT + b) * 4 + q) * 256] = v;
+                }
+    }
+    __device__ __forceinline__ void lds_add_left(int level, Acc<MT, NT> &acc) const {
+        const f32x4 *src = reinterpret_cast<const f32x4 *>(lds + (level - REG_LEVELS) * LDS_LEVEL_BYTES) + threadIdx.x;
+#pragma unroll
+        for (int a = 0; a < MT; ++a)
+#pragma unroll
+            for (int b = 0; b < NT; ++b)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x4 v = src[((a * NT + b) * 4 + q) * 256];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc.t[a][b][4 * q + e] = v[e] + acc.t[a][b][4 * q + e];
+                }
+    }
 };
 
 template <int MT, int NT>
@@ -41,22 +85,27 @@ __device__ __forceinline__ void add_left_sibling(Acc<MT, NT> &acc, const Acc<MT,
 }
 
 // Evaluates T over 2^L consecutive superleaves into acc (App. C), leaves in ascending k.
-template <int L>
+template <int L, int REG_LEVELS>
 struct SubtreeWalker {
     template <class Leaf, class A, class S>
     __device__ __forceinline__ static void run(Leaf &leaf, A &acc, S &stash) {
 #pragma nounroll
         for (int half = 0; half < 2; ++half) {
-            SubtreeWalker<L - 1>::run(leaf, acc, stash);
-            if (half == 0) stash.s[L - 1] = acc;
-            else add_left_sibling(acc, stash.s[L - 1]);
+            SubtreeWalker<L - 1, REG_LEVELS>::run(leaf, acc, stash);
+            if constexpr (L - 1 < REG_LEVELS) {
+                if (half == 0) stash.s[L - 1] = acc;
+                else add_left_sibling(acc, stash.s[L - 1]);
+            } else {
+                if (half == 0) stash.lds_store(L - 1, acc);
+                else stash.lds_add_left(L - 1, acc);
+            }
         }
     }
 };
-template <>
-struct SubtreeWalker<0> {
+template <int REG_LEVELS>
+struct SubtreeWalker<0, REG_LEVELS> {
     template <class Leaf, class A, class S>
-    __device__ __forceinline__ static void run(Leaf &leaf, A &acc, S &) { leaf(); }
+    __device__ __forceinline__ static void run(Leaf &leaf, A &, S &) { leaf(); }
 };
 
 struct TiledParams {
@@ -79,15 +128,14 @@ template <int LEVELS, int WM, int WN, int MT, int NT>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_tiled_kernel(const TiledParams p) {
     constexpr int BM = 32 * MT * WM, BN = 32 * NT * WN;
-    constexpr int A_BYTES = BM * PITCH, B_BYTES = BN * PITCH;
+    static_assert(BN == BN_TILE && WM * WN == 4, "tile shape");
+    constexpr int A_BYTES = BM * A_ROW, B_BYTES = BK * B_ROW;
+    constexpr int STAGE_BYTES = A_BYTES + B_BYTES;          // stage layout: [X tile | W tile]
     constexpr int A_CHUNKS = BM * (BK / 8);                 // 16-byte chunks of the X tile
     constexpr int A_PER_THREAD = (A_CHUNKS + 255) / 256;
-    constexpr int B_BLOCKS = (BK / 4) * (BN / 8);           // 4(k) x 8(n) blocks of the W tile
-    constexpr int B_PER_THREAD = (B_BLOCKS + 255) / 256;
-    static_assert(WM * WN == 4, "four wavefronts");
+    constexpr int B_PER_THREAD = BK * (BN / 8) / 256;       // 16-byte chunks of the W tile per thread (4)
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    constexpr int STAGE_BYTES = A_BYTES + B_BYTES;          // stage layout: [X tile | W tile]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -101,66 +149,72 @@ void gemm_tiled_kernel(const TiledParams p) {
     const int64_t kbase = (int64_t)shard * p.k_per_shard;
 
     // ---- global -> register staging ----
-    uint4 areg[A_PER_THREAD];
-    uint4 breg[B_PER_THREAD][4];
+    u32x4 areg[A_PER_THREAD];
+    u32x4 breg[B_PER_THREAD];
 
     // Rows past M and columns past N are never stored, and an output element depends only on its own
     // row of X and column of W, so out-of-range lanes simply re-read the last valid row / column block.
-    auto gload = [&](int64_t k0) {
+    const uint16_t *agp[A_PER_THREAD];
+    int alds[A_PER_THREAD];
 #pragma unroll
-        for (int i = 0; i < A_PER_THREAD; ++i) {
-            const int c = tid + 256 * i;
-            const int row = min(m0 + (c >> 3), p.M - 1), kc = c & 7;
-            if (A_CHUNKS % 256 == 0 || c < A_CHUNKS)
-                areg[i] = *reinterpret_cast<const uint4 *>(p.X + (int64_t)row * p.ldx + k0 + kc * 8);
-        }
+    for (int i = 0; i < A_PER_THREAD; ++i) {
+        const int c = tid + 256 * i;
+        const int r = c >> 3, kc = c & 7;
+        agp[i] = p.X + (int64_t)min(m0 + r, p.M - 1) * p.ldx + kbase + kc * 8;
+        alds[i] = r * A_ROW + ((kc ^ ((r >> 1) & 7)) << 4);
+    }
+    const uint16_t *bgp[B_PER_THREAD];
+    int blds[B_PER_THREAD];
 #pragma unroll
-        for (int i = 0; i < B_PER_THREAD; ++i) {
-            const int b = tid + 256 * i;
-            const int nblk = b % (BN / 8), kblk = b / (BN / 8);
-            const int col = min(n0 + nblk * 8, p.N - 8);
-            if (B_BLOCKS % 256 == 0 || b < B_BLOCKS) {
+    for (int i = 0; i < B_PER_THREAD; ++i) {
+        const int b = tid + 256 * i;
+        const int kk = b >> 4, nc = b & 15;
+        bgp[i] = p.W + (kbase + kk) * p.ldw + min(n0 + nc * 8, p.N - 8);
+        blds[i] = A_BYTES + kk * B_ROW + ((nc ^ ((kk & 3) << 2)) << 4);
+    }
+    const int64_t bstep = (int64_t)BK * p.ldw;
+
+    auto gload = [&](int stage) {
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    breg[i][t] = *reinterpret_cast<const uint4 *>(p.W + (k0 + kblk * 4 + t) * p.ldw + col);
-            }
-        }
+        for (int i = 0; i < A_PER_THREAD; ++i)
+            if (A_CHUNKS % 256 == 0 || tid + 256 * i < A_CHUNKS)
+                areg[i] = *reinterpret_cast<const u32x4 *>(agp[i] + (int64_t)stage * BK);
+#pragma unroll
+        for (int i = 0; i < B_PER_THREAD; ++i)
+            breg[i] = *reinterpret_cast<const u32x4 *>(bgp[i] + (int64_t)stage * bstep);
     };
 
     auto lstore = [&](int buf) {
+        unsigned char *base = smem + buf * STAGE_BYTES;
 #pragma unroll
-        for (int i = 0; i < A_PER_THREAD; ++i) {
-            const int c = tid + 256 * i;
-            const int row = c >> 3, kc = c & 7;
-            if (c < A_CHUNKS) *reinterpret_cast<uint4 *>((smem + buf * STAGE_BYTES) + row * PITCH + kc * 16) = areg[i];
-        }
+        for (int i = 0; i < A_PER_THREAD; ++i)
+            if (A_CHUNKS % 256 == 0 || tid + 256 * i < A_CHUNKS)
+                *reinterpret_cast<u32x4 *>(base + alds[i]) = areg[i];
 #pragma unroll
-        for (int i = 0; i < B_PER_THREAD; ++i) {
-            const int b = tid + 256 * i;
-            const int nblk = b % (BN / 8), kblk = b / (BN / 8);
-            if (b < B_BLOCKS) {
-                const uint32_t r0[4] = {breg[i][0].x, breg[i][0].y, breg[i][0].z, breg[i][0].w};
-                const uint32_t r1[4] = {breg[i][1].x, breg[i][1].y, breg[i][1].z, breg[i][1].w};
-                const uint32_t r2[4] = {breg[i][2].x, breg[i][2].y, breg[i][2].z, breg[i][2].w};
-                const uint32_t r3[4] = {breg[i][3].x, breg[i][3].y, breg[i][3].z, breg[i][3].w};
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    // column 2q: low halves of word q of the four k rows; column 2q+1: high halves
-                    const uint2 even = make_uint2((r0[q] & 0xffffu) | (r1[q] << 16), (r2[q] & 0xffffu) | (r3[q] << 16));
-                    const uint2 odd = make_uint2((r0[q] >> 16) | (r1[q] & 0xffff0000u), (r2[q] >> 16) | (r3[q] & 0xffff0000u));
-                    unsigned char *dst = (smem + buf * STAGE_BYTES + A_BYTES) + (nblk * 8 + 2 * q) * PITCH + kblk * 8;
-                    *reinterpret_cast<uint2 *>(dst) = even;
-                    *reinterpret_cast<uint2 *>(dst + PITCH) = odd;
-                }
-            }
-        }
+        for (int i = 0; i < B_PER_THREAD; ++i) *reinterpret_cast<u32x4 *>(base + blds[i]) = breg[i];
     };
 
+    // ---- LDS fragment addresses (bytes inside a stage) ----
+    // X fragment a: row wm*MT*32 + a*32 + li, chunk 2*ks + lg  ->  position (2*ks) ^ (lg ^ ((li>>1)&7)).
+    const int a_row_off = (wm * MT * 32 + li) * A_ROW;
+    const int a_sw = (lg ^ ((li >> 1) & 7)) << 4;
+    // W fragment b, half h: a 16-lane group reads rows k0..k0+3 (k0 = 16*ks + 8*lg + 4*h), 16 columns.
+    const int l16 = lane & 15, e = l16 >> 2;
+    int b_off[NT];
+#pragma unroll
+    for (int b = 0; b < NT; ++b) {
+        const int col = (wn * NT + b) * 32 + ((lane >> 4) & 1) * 16 + (l16 & 3) * 4;
+        b_off[b] = A_BYTES + (lg * 8 + e) * B_ROW + ((((col >> 3) ^ (e << 2))) << 4) + ((col >> 2) & 1) * 8;
+    }
+
+    // big tiles keep at most three stash levels in registers, the rest in LDS behind the stage buffers
+    constexpr int REG_LEVELS = (MT * NT >= 4 && LEVELS > TBIK_MAX_REG_LEVELS) ? TBIK_MAX_REG_LEVELS : LEVELS;
     Acc<MT, NT> acc;
-    TileStash<LEVELS, MT, NT> stash;
+    TileStash<REG_LEVELS, MT, NT> stash;
+    stash.lds = smem + 2 * STAGE_BYTES;
 
     const int total_stages = p.ns_per_shard * p.stages_per_superleaf;
-    gload(kbase);
+    gload(0);
     lstore(0);
     __syncthreads();
 
@@ -177,23 +231,30 @@ void gemm_tiled_kernel(const TiledParams p) {
 #pragma nounroll
         for (int q = 0; q < p.stages_per_superleaf; ++q, ++s) {
             const int buf = s & 1;
-            if (s + 1 < total_stages) gload(kbase + (int64_t)(s + 1) * BK);
-            const unsigned char *Ab = (smem + buf * STAGE_BYTES) + (wm * MT * 32 + li) * PITCH + lg * 16;
-            const unsigned char *Bb = (smem + buf * STAGE_BYTES + A_BYTES) + (wn * NT * 32 + li) * PITCH + lg * 16;
+            gload(min(s + 1, total_stages - 1));      // the last stage re-reads itself (never consumed)
+            const unsigned char *sb = smem + buf * STAGE_BYTES;
 #pragma unroll
             for (int ks = 0; ks < BK / 16; ++ks) {
                 bf16x8 af[MT], bfr[NT];
 #pragma unroll
-                for (int a = 0; a < MT; ++a) af[a] = *reinterpret_cast<const bf16x8 *>(Ab + a * 32 * PITCH + ks * 32);
+                for (int a = 0; a < MT; ++a)
+                    af[a] = *reinterpret_cast<const bf16x8 *>(sb + a_row_off + a * 32 * A_ROW + (a_sw ^ (ks << 5)));
 #pragma unroll
-                for (int b = 0; b < NT; ++b) bfr[b] = *reinterpret_cast<const bf16x8 *>(Bb + b * 32 * PITCH + ks * 32);
+                for (int b = 0; b < NT; ++b) {
+                    union { v4i16 h[2]; bf16x8 v; } u;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+                        u.h[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (__attribute__((address_space(3))) v4i16 *)(sb + b_off[b] + ks * 16 * B_ROW + h * 4 * B_ROW));
+                    bfr[b] = u.v;
+                }
 #pragma unroll
                 for (int a = 0; a < MT; ++a)
 #pragma unroll
                     for (int b = 0; b < NT; ++b)
                         acc.t[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc.t[a][b], 0, 0, 0);
             }
-            if (s + 1 < total_stages) lstore(buf ^ 1);
+            lstore(buf ^ 1);
             __syncthreads();
         }
     };
@@ -201,7 +262,7 @@ void gemm_tiled_kernel(const TiledParams p) {
     // The shard's subtree of depth LEVELS, walked as nested two-trip loops: the first trip of the
     // loop at level l leaves its subtree sum in the stash slot of that level, the second trip adds
     // the slot to its own sum (left sibling + right sibling).  Every slot is named statically.
-    SubtreeWalker<LEVELS>::run(superleaf, acc, stash);
+    SubtreeWalker<LEVELS, REG_LEVELS>::run(superleaf, acc, stash);
 
     // ---- epilogue: acc holds T(superleaves of this shard) ----
     float *part = p.partials ? p.partials + (int64_t)shard * p.M * p.N : nullptr;
@@ -257,8 +318,9 @@ static hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
     const int64_t tiles = (int64_t)p.tiles_n * ((a.M + BM - 1) / BM);
     if (tiles > 0x7fffffff) return hipErrorInvalidValue;
     dim3 grid((unsigned)tiles, a.P), block(256);
-    const size_t lds = 2 * (size_t)(BM + BN) * PITCH;
     const int levels = levels_for(p.ns_per_shard);
+    const int lds_levels = (MT * NT >= 4 && levels > TBIK_MAX_REG_LEVELS) ? levels - TBIK_MAX_REG_LEVELS : 0;
+    const size_t lds = 2 * ((size_t)BM * A_ROW + (size_t)BK * B_ROW) + (size_t)lds_levels * MT * NT * 16 * 4 * 256;
 #define TBIK_LAUNCH(L)                                                                                   \
     case L: {                                                                                            \
         auto k = gemm_tiled_kernel<L, WM, WN, MT, NT>;                                                   \
