@@ -7,7 +7,7 @@
 // superleaf ends, the carry-over step folds the accumulators into the stash of waiting subtrees,
 // which lives in registers (one wavefront per SIMD, up to 512 VGPR+AGPR per lane).
 //
-// Operands are staged through LDS in K-steps of 64 with double buffering, both in their global
+// Operands are staged through LDS in K-steps of 64 (three stage buffers), both in their global
 // orientation, written with 16-byte stores:
 //   X tile [BM][64]  rows of 128 B; the 16-byte chunk c of row r sits at position c ^ ((r>>1)&7),
 //                    so the 16 rows of a fragment read (ds_read_b128) hit all 64 banks once;
@@ -26,6 +26,9 @@ constexpr int A_ROW = BK * 2;          // bytes per LDS row of the X tile
 constexpr int B_ROW = BN_TILE * 2;     // bytes per LDS row of the W tile
 
 // Stash levels kept in registers by the 128x128 tile (the rest go to LDS).
+#ifndef TBIK_ABLATE
+#define TBIK_ABLATE 0   // development only: bit mask that removes pipeline pieces for timing experiments
+#endif
 #ifndef TBIK_MAX_REG_LEVELS
 #define TBIK_MAX_REG_LEVELS 4
 #endif
@@ -211,14 +214,42 @@ void gemm_tiled_kernel(const TiledParams p) {
     constexpr int REG_LEVELS = (MT * NT >= 4 && LEVELS > TBIK_MAX_REG_LEVELS) ? TBIK_MAX_REG_LEVELS : LEVELS;
     Acc<MT, NT> acc;
     TileStash<REG_LEVELS, MT, NT> stash;
-    stash.lds = smem + 2 * STAGE_BYTES;
+    stash.lds = smem + 3 * STAGE_BYTES;
 
     const int total_stages = p.ns_per_shard * p.stages_per_superleaf;
+
+    // Fragment registers, double buffered over the K-steps of 16: while the MFMAs of one step run,
+    // the LDS reads of the next step (or of the first step of the next stage) are in flight.
+    bf16x8 af[2][MT], bfr[2][NT];
+    auto read_frags = [&](int set, int buf, int ks) {
+        const unsigned char *sb = smem + buf * STAGE_BYTES;
+#pragma unroll
+        for (int a = 0; a < MT; ++a)
+            af[set][a] = *reinterpret_cast<const bf16x8 *>(sb + a_row_off + a * 32 * A_ROW + (a_sw ^ (ks << 5)));
+#pragma unroll
+        for (int b = 0; b < NT; ++b) {
+            union { v4i16 h[2]; bf16x8 v; } u;
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                u.h[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) v4i16 *)(sb + b_off[b] + ks * 16 * B_ROW + h * 4 * B_ROW));
+            bfr[set][b] = u.v;
+        }
+    };
+
+    // Software pipeline over three LDS stage buffers.  At the top of stage s the staging registers
+    // hold stage s+1 (loaded from global memory during stage s-1); they are written to buffer
+    // (s+1)%3, the loads of stage s+2 are issued, and one barrier makes buffer (s+1)%3 visible.
+    // That buffer was last read in stage s-2, which every wavefront left before the barrier of
+    // stage s-1, so one barrier per stage orders both hazards.
     gload(0);
     lstore(0);
+    gload(min(1, total_stages - 1));
     __syncthreads();
+    read_frags(0, 0, 0);
 
     int s = 0;             // global stage counter of the software pipeline (runs across superleaves)
+    int cur = 0;           // LDS buffer of stage s
 
     // One superleaf: accumulators start at +0, then stages_per_superleaf LDS stages of MFMA chains.
     auto superleaf = [&]() {
@@ -230,32 +261,31 @@ void gemm_tiled_kernel(const TiledParams p) {
                 for (int r = 0; r < 16; ++r) acc.t[a][b][r] = 0.0f;
 #pragma nounroll
         for (int q = 0; q < p.stages_per_superleaf; ++q, ++s) {
-            const int buf = s & 1;
-            gload(min(s + 1, total_stages - 1));      // the last stage re-reads itself (never consumed)
-            const unsigned char *sb = smem + buf * STAGE_BYTES;
+            const int nxt = (cur == 2) ? 0 : cur + 1;
+#if !(TBIK_ABLATE & 1)
+            lstore(nxt);                                  // stage s+1 (past the end: a harmless repeat)
+            gload(min(s + 2, total_stages - 1));
+#endif
+#if !(TBIK_ABLATE & 2)
+            __syncthreads();
+#endif
 #pragma unroll
             for (int ks = 0; ks < BK / 16; ++ks) {
-                bf16x8 af[MT], bfr[NT];
-#pragma unroll
-                for (int a = 0; a < MT; ++a)
-                    af[a] = *reinterpret_cast<const bf16x8 *>(sb + a_row_off + a * 32 * A_ROW + (a_sw ^ (ks << 5)));
-#pragma unroll
-                for (int b = 0; b < NT; ++b) {
-                    union { v4i16 h[2]; bf16x8 v; } u;
-#pragma unroll
-                    for (int h = 0; h < 2; ++h)
-                        u.h[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (__attribute__((address_space(3))) v4i16 *)(sb + b_off[b] + ks * 16 * B_ROW + h * 4 * B_ROW));
-                    bfr[b] = u.v;
-                }
+#if !(TBIK_ABLATE & 4)
+                if (ks + 1 < BK / 16) read_frags((ks + 1) & 1, cur, ks + 1);
+                else read_frags(0, nxt, 0);
+#endif
+#if !(TBIK_ABLATE & 8)
 #pragma unroll
                 for (int a = 0; a < MT; ++a)
 #pragma unroll
                     for (int b = 0; b < NT; ++b)
-                        acc.t[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc.t[a][b], 0, 0, 0);
+                        acc.t[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][a], bfr[ks & 1][b], acc.t[a][b], 0, 0, 0);
+#else
+                acc.t[0][0][0] += (float)af[ks & 1][0][0] + (float)bfr[ks & 1][0][0];
+#endif
             }
-            lstore(buf ^ 1);
-            __syncthreads();
+            cur = nxt;
         }
     };
 
@@ -320,7 +350,7 @@ static hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
     dim3 grid((unsigned)tiles, a.P), block(256);
     const int levels = levels_for(p.ns_per_shard);
     const int lds_levels = (MT * NT >= 4 && levels > TBIK_MAX_REG_LEVELS) ? levels - TBIK_MAX_REG_LEVELS : 0;
-    const size_t lds = 2 * ((size_t)BM * A_ROW + (size_t)BK * B_ROW) + (size_t)lds_levels * MT * NT * 16 * 4 * 256;
+    const size_t lds = 3 * ((size_t)BM * A_ROW + (size_t)BK * B_ROW) + (size_t)lds_levels * MT * NT * 16 * 4 * 256;
 #define TBIK_LAUNCH(L)                                                                                   \
     case L: {                                                                                            \
         auto k = gemm_tiled_kernel<L, WM, WN, MT, NT>;                                                   \
