@@ -25,7 +25,7 @@ SOURCES = ["tbik_api.hip", "gemm_reference.hip", "gemm_tiled.hip", "combine.hip"
 # on them in place and the allocator parks the cold stash levels in AGPRs instead of spilling to scratch.
 FLAGS = ["--offload-arch=gfx950", "-mllvm", "-amdgpu-mfma-vgpr-form", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-fno-fast-math",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument",
-         "-Wno-unknown-attributes"]
+         "-Wno-unknown-attributes", "-Wno-inline-asm"]
 
 
 def _hipcc() -> str:

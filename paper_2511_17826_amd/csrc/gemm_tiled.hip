@@ -36,6 +36,21 @@ constexpr int B_ROW = BN_TILE * 2;     // bytes per LDS row of the W tile
 typedef short v4i16 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+// Waits until at most N of this wavefront's vector-memory loads are outstanding, then joins the workgroup
+// barrier.  Deliberately not __syncthreads(): its fence would wait for all loads.
+template <int N>
+__device__ __forceinline__ void wait_loads_and_barrier() {
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+// global_load_lds_dwordx4: every lane fetches 16 bytes from its own global address; lane i's bytes land at
+// LDS address m0 + 16*i.  Written in assembly so that the compiler does not see an LDS write it would
+// guard with a full wait before later LDS reads; completion is tracked by hand with vmcnt (above).
+__device__ __forceinline__ void load_16B_per_lane_to_lds(const void *gptr, unsigned lds_wave_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_wave_base), "v"(gptr) : "memory", "m0");
+}
+
 template <int MT, int NT>              // 32x32 MFMA tiles per wavefront
 struct Acc {
     f32x16 t[MT][NT];
@@ -134,9 +149,6 @@ void gemm_tiled_kernel(const TiledParams p) {
     static_assert(BN == BN_TILE && WM * WN == 4, "tile shape");
     constexpr int A_BYTES = BM * A_ROW, B_BYTES = BK * B_ROW;
     constexpr int STAGE_BYTES = A_BYTES + B_BYTES;          // stage layout: [X tile | W tile]
-    constexpr int A_CHUNKS = BM * (BK / 8);                 // 16-byte chunks of the X tile
-    constexpr int A_PER_THREAD = (A_CHUNKS + 255) / 256;
-    constexpr int B_PER_THREAD = BK * (BN / 8) / 256;       // 16-byte chunks of the W tile per thread (4)
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -151,51 +163,42 @@ void gemm_tiled_kernel(const TiledParams p) {
     const int shard = blockIdx.y;
     const int64_t kbase = (int64_t)shard * p.k_per_shard;
 
-    // ---- global -> register staging ----
-    u32x4 areg[A_PER_THREAD];
-    u32x4 breg[B_PER_THREAD];
-
-    // Rows past M and columns past N are never stored, and an output element depends only on its own
-    // row of X and column of W, so out-of-range lanes simply re-read the last valid row / column block.
-    const uint16_t *agp[A_PER_THREAD];
-    int alds[A_PER_THREAD];
+    // ---- global -> LDS, without passing through registers (global_load_lds_dwordx4) ----
+    // One such instruction moves 64 x 16 bytes: lane i's chunk lands at LDS base + 16*i, so a
+    // wavefront fills 1 KiB of consecutive LDS = 8 rows of the X tile or 4 rows of the W tile, and
+    // the swizzle is applied on the global side (which chunk a lane fetches).  Rows past M and
+    // columns past N are never stored, and an output element depends only on its own row of X and
+    // column of W, so out-of-range lanes simply re-read the last valid row / column block.
+    constexpr int A_LOADS = BM / 32;          // per wavefront and stage (BM rows / 8 rows / 4 wavefronts)
+    constexpr int B_LOADS = BK / 16;          // 64 rows / 4 rows / 4 wavefronts
+    const uint16_t *agp[A_LOADS];
 #pragma unroll
-    for (int i = 0; i < A_PER_THREAD; ++i) {
-        const int c = tid + 256 * i;
-        const int r = c >> 3, kc = c & 7;
-        agp[i] = p.X + (int64_t)min(m0 + r, p.M - 1) * p.ldx + kbase + kc * 8;
-        alds[i] = r * A_ROW + ((kc ^ ((r >> 1) & 7)) << 4);
+    for (int j = 0; j < A_LOADS; ++j) {
+        const int r = (wave * A_LOADS + j) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((r >> 1) & 7);
+        agp[j] = p.X + (int64_t)min(m0 + r, p.M - 1) * p.ldx + kbase + c * 8;
     }
-    const uint16_t *bgp[B_PER_THREAD];
-    int blds[B_PER_THREAD];
+    const uint16_t *bgp[B_LOADS];
 #pragma unroll
-    for (int i = 0; i < B_PER_THREAD; ++i) {
-        const int b = tid + 256 * i;
-        const int kk = b >> 4, nc = b & 15;
-        bgp[i] = p.W + (kbase + kk) * p.ldw + min(n0 + nc * 8, p.N - 8);
-        blds[i] = A_BYTES + kk * B_ROW + ((nc ^ ((kk & 3) << 2)) << 4);
+    for (int j = 0; j < B_LOADS; ++j) {
+        const int kk = (wave * B_LOADS + j) * 4 + (lane >> 4);
+        const int c = (lane & 15) ^ ((lane >> 4) << 2);
+        bgp[j] = p.W + (kbase + kk) * p.ldw + min(n0 + c * 8, p.N - 8);
     }
     const int64_t bstep = (int64_t)BK * p.ldw;
 
-    auto gload = [&](int stage) {
+    const unsigned smem_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    auto issue_stage = [&](int stage, int buf) {
+        const unsigned base = smem_lds + buf * STAGE_BYTES;
 #pragma unroll
-        for (int i = 0; i < A_PER_THREAD; ++i)
-            if (A_CHUNKS % 256 == 0 || tid + 256 * i < A_CHUNKS)
-                areg[i] = *reinterpret_cast<const u32x4 *>(agp[i] + (int64_t)stage * BK);
+        for (int j = 0; j < A_LOADS; ++j)
+            load_16B_per_lane_to_lds(agp[j] + (int64_t)stage * BK, base + (wave_u * A_LOADS + j) * 1024);
 #pragma unroll
-        for (int i = 0; i < B_PER_THREAD; ++i)
-            breg[i] = *reinterpret_cast<const u32x4 *>(bgp[i] + (int64_t)stage * bstep);
+        for (int j = 0; j < B_LOADS; ++j)
+            load_16B_per_lane_to_lds(bgp[j] + (int64_t)stage * bstep, base + A_BYTES + (wave_u * B_LOADS + j) * 1024);
     };
-
-    auto lstore = [&](int buf) {
-        unsigned char *base = smem + buf * STAGE_BYTES;
-#pragma unroll
-        for (int i = 0; i < A_PER_THREAD; ++i)
-            if (A_CHUNKS % 256 == 0 || tid + 256 * i < A_CHUNKS)
-                *reinterpret_cast<u32x4 *>(base + alds[i]) = areg[i];
-#pragma unroll
-        for (int i = 0; i < B_PER_THREAD; ++i) *reinterpret_cast<u32x4 *>(base + blds[i]) = breg[i];
-    };
+    constexpr int LOADS_PER_STAGE = A_LOADS + B_LOADS;
 
     // ---- LDS fragment addresses (bytes inside a stage) ----
     // X fragment a: row wm*MT*32 + a*32 + li, chunk 2*ks + lg  ->  position (2*ks) ^ (lg ^ ((li>>1)&7)).
@@ -214,7 +217,7 @@ void gemm_tiled_kernel(const TiledParams p) {
     constexpr int REG_LEVELS = (MT * NT >= 4 && LEVELS > TBIK_MAX_REG_LEVELS) ? TBIK_MAX_REG_LEVELS : LEVELS;
     Acc<MT, NT> acc;
     TileStash<REG_LEVELS, MT, NT> stash;
-    stash.lds = smem + 3 * STAGE_BYTES;
+    stash.lds = smem + 4 * STAGE_BYTES;
 
     const int total_stages = p.ns_per_shard * p.stages_per_superleaf;
 
@@ -237,19 +240,19 @@ void gemm_tiled_kernel(const TiledParams p) {
         }
     };
 
-    // Software pipeline over three LDS stage buffers.  At the top of stage s the staging registers
-    // hold stage s+1 (loaded from global memory during stage s-1); they are written to buffer
-    // (s+1)%3, the loads of stage s+2 are issued, and one barrier makes buffer (s+1)%3 visible.
-    // That buffer was last read in stage s-2, which every wavefront left before the barrier of
-    // stage s-1, so one barrier per stage orders both hazards.
-    gload(0);
-    lstore(0);
-    gload(min(1, total_stages - 1));
-    __syncthreads();
+    // Software pipeline over a ring of four LDS stage buffers.  At the top of stage s: wait until this
+    // wavefront's loads of stage s+1 have landed (those of stage s+2 may still be in flight), meet the
+    // other wavefronts at a barrier -- now stage s+1 is complete in LDS and nobody reads the buffer of
+    // stage s-1 any more -- and start the loads of stage s+3 into that buffer.  The barrier is written
+    // in assembly on purpose: a fence would make the compiler drain every outstanding load.
+    issue_stage(0, 0);
+    issue_stage(min(1, total_stages - 1), 1);
+    issue_stage(min(2, total_stages - 1), 2);
+    wait_loads_and_barrier<LOADS_PER_STAGE * 2>();      // stage 0 landed everywhere
     read_frags(0, 0, 0);
 
     int s = 0;             // global stage counter of the software pipeline (runs across superleaves)
-    int cur = 0;           // LDS buffer of stage s
+    int cur = 0;           // ring slot of stage s
 
     // One superleaf: accumulators start at +0, then stages_per_superleaf LDS stages of MFMA chains.
     auto superleaf = [&]() {
@@ -261,29 +264,18 @@ void gemm_tiled_kernel(const TiledParams p) {
                 for (int r = 0; r < 16; ++r) acc.t[a][b][r] = 0.0f;
 #pragma nounroll
         for (int q = 0; q < p.stages_per_superleaf; ++q, ++s) {
-            const int nxt = (cur == 2) ? 0 : cur + 1;
-#if !(TBIK_ABLATE & 1)
-            lstore(nxt);                                  // stage s+1 (past the end: a harmless repeat)
-            gload(min(s + 2, total_stages - 1));
-#endif
-#if !(TBIK_ABLATE & 2)
-            __syncthreads();
-#endif
+            const int nxt = (cur + 1) & 3;
+            wait_loads_and_barrier<LOADS_PER_STAGE>();    // stage s+1 landed; stage s-1's buffer is free
+            issue_stage(min(s + 3, total_stages - 1), (cur + 3) & 3);
 #pragma unroll
             for (int ks = 0; ks < BK / 16; ++ks) {
-#if !(TBIK_ABLATE & 4)
                 if (ks + 1 < BK / 16) read_frags((ks + 1) & 1, cur, ks + 1);
                 else read_frags(0, nxt, 0);
-#endif
-#if !(TBIK_ABLATE & 8)
 #pragma unroll
                 for (int a = 0; a < MT; ++a)
 #pragma unroll
                     for (int b = 0; b < NT; ++b)
                         acc.t[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][a], bfr[ks & 1][b], acc.t[a][b], 0, 0, 0);
-#else
-                acc.t[0][0][0] += (float)af[ks & 1][0][0] + (float)bfr[ks & 1][0][0];
-#endif
             }
             cur = nxt;
         }
@@ -293,6 +285,7 @@ void gemm_tiled_kernel(const TiledParams p) {
     // loop at level l leaves its subtree sum in the stash slot of that level, the second trip adds
     // the slot to its own sum (left sibling + right sibling).  Every slot is named statically.
     SubtreeWalker<LEVELS, REG_LEVELS>::run(superleaf, acc, stash);
+    wait_loads_and_barrier<0>();                          // no load may still be writing LDS when the workgroup ends
 
     // ---- epilogue: acc holds T(superleaves of this shard) ----
     float *part = p.partials ? p.partials + (int64_t)shard * p.M * p.N : nullptr;
@@ -350,7 +343,7 @@ static hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
     dim3 grid((unsigned)tiles, a.P), block(256);
     const int levels = levels_for(p.ns_per_shard);
     const int lds_levels = (MT * NT >= 4 && levels > TBIK_MAX_REG_LEVELS) ? levels - TBIK_MAX_REG_LEVELS : 0;
-    const size_t lds = 3 * ((size_t)BM * A_ROW + (size_t)BK * B_ROW) + (size_t)lds_levels * MT * NT * 16 * 4 * 256;
+    const size_t lds = 4 * ((size_t)BM * A_ROW + (size_t)BK * B_ROW) + (size_t)lds_levels * MT * NT * 16 * 4 * 256;
 #define TBIK_LAUNCH(L)                                                                                   \
     case L: {                                                                                            \
         auto k = gemm_tiled_kernel<L, WM, WN, MT, NT>;                                                   \
