@@ -52,6 +52,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU oracle timing leg")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the workload the CPU oracle computes (0 = auto)")
     ap.add_argument("--extras", action="store_true", help="also time each kernel on the other configured shapes")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also launch one plain 1 GiB device-to-device copy (a known-size reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (tensor parallelism is emulated on it by per-shard "
@@ -98,6 +100,13 @@ def main():
             tb.tbik_tree_combine(parts[P], out=yP[P])
         tb.tbik_tree_combine(parts[8], out=y8f)
         tb.tbik_row_reduce(y8f, tb.TBIK_LOGSOFTMAX, out=lsm, workspace=ws_rr)
+
+    if args.calibration_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
@@ -183,7 +192,7 @@ def cpu_baseline(c, leaf, g, rows):
         t0 = time.perf_counter()
         orc.gemm(c["X"][:4], c["W"], leaf, g)                 # calibration: 4 rows
         per_row = (time.perf_counter() - t0) / 4
-        rows = int(max(8, min(512, 15.0 / max(per_row, 1e-6))))
+        rows = int(max(8, min(4096, 15.0 / max(per_row, 1e-6))))
     t0 = time.perf_counter()
     orc.gemm(c["X"][:rows], c["W"], leaf, g)
     dt = time.perf_counter() - t0

@@ -15,6 +15,8 @@
 //                    B operand (8 consecutive k of one column per lane) is fetched with the
 //                    transposing LDS read ds_read_b64_tr_b16, whose 16-lane groups read 4 rows x
 //                    16 columns: with the swizzle the 4 rows fall into different banks.
+#include <type_traits>
+
 #include "tbik_device.hpp"
 #include "tbik_internal.hpp"
 
@@ -24,14 +26,6 @@ constexpr int BK = 64;                 // K-elements per LDS stage
 constexpr int BN_TILE = 128;           // columns per workgroup tile
 constexpr int A_ROW = BK * 2;          // bytes per LDS row of the X tile
 constexpr int B_ROW = BN_TILE * 2;     // bytes per LDS row of the W tile
-
-// Stash levels kept in registers by the 128x128 tile (the rest go to LDS).
-#ifndef TBIK_ABLATE
-#define TBIK_ABLATE 0   // development only: bit mask that removes pipeline pieces for timing experiments
-#endif
-#ifndef TBIK_MAX_REG_LEVELS
-#define TBIK_MAX_REG_LEVELS 4
-#endif
 
 typedef short v4i16 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -56,40 +50,12 @@ struct Acc {
     f32x16 t[MT][NT];
 };
 
-// Stash of finished subtrees (App. D.1: accumulator buffer S[level]); every slot is addressed statically.
-// Levels below REG_LEVELS live in registers; the levels above (written and read once per 2^level
-// superleaves) live in LDS, 16 floats per lane and slot-row, each lane owning its own 16-byte columns.
-template <int REG_LEVELS, int MT, int NT>
+// Stash of finished subtrees (App. D.1: accumulator buffer S[level]) for tree levels 1 and up; every slot
+// is addressed statically, so the slots are registers.  Level 0 needs no slot: two consecutive superleaves
+// are accumulated in two different register sets and added.
+template <int SLOTS, int MT, int NT>
 struct TileStash {
-    Acc<MT, NT> s[REG_LEVELS > 0 ? REG_LEVELS : 1];
-    unsigned char *lds;          // base of the LDS stash area (per workgroup)
-    static constexpr int LDS_LEVEL_BYTES = MT * NT * 16 * 4 * 256;
-
-    __device__ __forceinline__ void lds_store(int level, const Acc<MT, NT> &acc) const {
-        f32x4 *dst = reinterpret_cast<f32x4 *>(lds + (level - REG_LEVELS) * LDS_LEVEL_BYTES) + threadIdx.x;
-#pragma unroll
-        for (int a = 0; a < MT; ++a)
-#pragma unroll
-            for (int b = 0; b < NT; ++b)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    f32x4 v = {acc.t[a][b][4 * q], acc.t[a][b][4 * q + 1], acc.t[a][b][4 * q + 2], acc.t[a][b][4 * q + 3]};
-                    dst[((a * NT + b) * 4 + q) * 256] = v;
-                }
-    }
-    __device__ __forceinline__ void lds_add_left(int level, Acc<MT, NT> &acc) const {
-        const f32x4 *src = reinterpret_cast<const f32x4 *>(lds + (level - REG_LEVELS) * LDS_LEVEL_BYTES) + threadIdx.x;
-#pragma unroll
-        for (int a = 0; a < MT; ++a)
-#pragma unroll
-            for (int b = 0; b < NT; ++b)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const f32x4 v = src[((a * NT + b) * 4 + q) * 256];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) acc.t[a][b][4 * q + e] = v[e] + acc.t[a][b][4 * q + e];
-                }
-    }
+    Acc<MT, NT> s[SLOTS > 0 ? SLOTS : 1];
 };
 
 template <int MT, int NT>
@@ -102,28 +68,35 @@ __device__ __forceinline__ void add_left_sibling(Acc<MT, NT> &acc, const Acc<MT,
             for (int r = 0; r < 16; ++r) acc.t[a][b][r] = left.t[a][b][r] + acc.t[a][b][r];
 }
 
-// Evaluates T over 2^L consecutive superleaves into acc (App. C), leaves in ascending k.
-template <int L, int REG_LEVELS>
+// Evaluates T over 2^L consecutive superleaves into acc (App. C), leaves in ascending k.  The walk is a
+// nest of two-trip loops: the first trip of the loop at level l parks its subtree sum in slot l, the
+// second trip adds the slot to its own sum (left sibling + right sibling).
+template <int L>
 struct SubtreeWalker {
     template <class Leaf, class A, class S>
-    __device__ __forceinline__ static void run(Leaf &leaf, A &acc, S &stash) {
+    __device__ __forceinline__ static void run(Leaf &leaf, A &acc, A &acc2, S &stash) {
 #pragma nounroll
         for (int half = 0; half < 2; ++half) {
-            SubtreeWalker<L - 1, REG_LEVELS>::run(leaf, acc, stash);
-            if constexpr (L - 1 < REG_LEVELS) {
-                if (half == 0) stash.s[L - 1] = acc;
-                else add_left_sibling(acc, stash.s[L - 1]);
-            } else {
-                if (half == 0) stash.lds_store(L - 1, acc);
-                else stash.lds_add_left(L - 1, acc);
-            }
+            SubtreeWalker<L - 1>::run(leaf, acc, acc2, stash);
+            if (half == 0) stash.s[L - 2] = acc;
+            else add_left_sibling(acc, stash.s[L - 2]);
         }
     }
 };
-template <int REG_LEVELS>
-struct SubtreeWalker<0, REG_LEVELS> {
+template <>
+struct SubtreeWalker<1> {
     template <class Leaf, class A, class S>
-    __device__ __forceinline__ static void run(Leaf &leaf, A &, S &) { leaf(); }
+    __device__ __forceinline__ static void run(Leaf &leaf, A &acc, A &acc2, S &) {
+        leaf(acc);                       // superleaf 2i   -> first register set
+        leaf(acc2);                      // superleaf 2i+1 -> second register set
+        add_left_sibling(acc2, acc);     // left + right
+        acc = acc2;
+    }
+};
+template <>
+struct SubtreeWalker<0> {
+    template <class Leaf, class A, class S>
+    __device__ __forceinline__ static void run(Leaf &leaf, A &acc, A &, S &) { leaf(acc); }
 };
 
 struct TiledParams {
@@ -137,11 +110,16 @@ struct TiledParams {
     int stages_per_superleaf;   // superleaf / BK
     int ns_per_shard;
     int64_t k_per_shard;
-    int tiles_n;
+    int tiles_n;                // column tiles
+    int tiles;                  // output tiles per shard
+    int work;                   // tiles * shards
 };
 
 // ---------------------------------------------------------------------------------------------
 // BM = 32*MT*WM rows, BN = 32*NT*WN columns, WM*WN = 4 wavefronts.
+// Persistent workgroups: workgroup g handles work items g, g + gridDim.x, ... (item = tile + tiles * shard).
+// The global->LDS load stream runs ahead of the MFMA stream across item boundaries, so the first stages
+// of the next tile are already in flight while the current tile is finished and stored.
 template <int LEVELS, int WM, int WN, int MT, int NT>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_tiled_kernel(const TiledParams p) {
@@ -156,12 +134,7 @@ void gemm_tiled_kernel(const TiledParams p) {
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, lg = lane >> 5;
-
-    const int tile = blockIdx.x;
-    const int tm = tile / p.tiles_n, tn = tile % p.tiles_n;
-    const int m0 = tm * BM, n0 = tn * BN;
-    const int shard = blockIdx.y;
-    const int64_t kbase = (int64_t)shard * p.k_per_shard;
+    const int stages_per_item = p.ns_per_shard * p.stages_per_superleaf;
 
     // ---- global -> LDS, without passing through registers (global_load_lds_dwordx4) ----
     // One such instruction moves 64 x 16 bytes: lane i's chunk lands at LDS base + 16*i, so a
@@ -171,34 +144,54 @@ void gemm_tiled_kernel(const TiledParams p) {
     // column of W, so out-of-range lanes simply re-read the last valid row / column block.
     constexpr int A_LOADS = BM / 32;          // per wavefront and stage (BM rows / 8 rows / 4 wavefronts)
     constexpr int B_LOADS = BK / 16;          // 64 rows / 4 rows / 4 wavefronts
+    constexpr int LOADS_PER_STAGE = A_LOADS + B_LOADS;
     const uint16_t *agp[A_LOADS];
-#pragma unroll
-    for (int j = 0; j < A_LOADS; ++j) {
-        const int r = (wave * A_LOADS + j) * 8 + (lane >> 3);
-        const int c = (lane & 7) ^ ((r >> 1) & 7);
-        agp[j] = p.X + (int64_t)min(m0 + r, p.M - 1) * p.ldx + kbase + c * 8;
-    }
     const uint16_t *bgp[B_LOADS];
-#pragma unroll
-    for (int j = 0; j < B_LOADS; ++j) {
-        const int kk = (wave * B_LOADS + j) * 4 + (lane >> 4);
-        const int c = (lane & 15) ^ ((lane >> 4) << 2);
-        bgp[j] = p.W + (kbase + kk) * p.ldw + min(n0 + c * 8, p.N - 8);
-    }
     const int64_t bstep = (int64_t)BK * p.ldw;
+    int issue_item = blockIdx.x;               // work item whose stages are being loaded
+    int issue_stage = 0;                       // next stage of that item to load
+
+    auto point_loads_at = [&](int item) {
+        const int tile = item % p.tiles, shard = item / p.tiles;
+        const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
+        const int64_t kbase = (int64_t)shard * p.k_per_shard;
+#pragma unroll
+        for (int j = 0; j < A_LOADS; ++j) {
+            const int r = (wave * A_LOADS + j) * 8 + (lane >> 3);
+            const int c = (lane & 7) ^ ((r >> 1) & 7);
+            agp[j] = p.X + (int64_t)min(m0 + r, p.M - 1) * p.ldx + kbase + c * 8;
+        }
+#pragma unroll
+        for (int j = 0; j < B_LOADS; ++j) {
+            const int kk = (wave * B_LOADS + j) * 4 + (lane >> 4);
+            const int c = (lane & 15) ^ ((lane >> 4) << 2);
+            bgp[j] = p.W + (kbase + kk) * p.ldw + min(n0 + c * 8, p.N - 8);
+        }
+    };
 
     const unsigned smem_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    auto issue_stage = [&](int stage, int buf) {
-        const unsigned base = smem_lds + buf * STAGE_BYTES;
+    // Loads the next stage of the stream into ring slot `slot`.  Past the last stage of the last item the
+    // last stage is simply loaded again (nobody consumes it).
+    auto issue_next_stage = [&](int slot) {
+        if (issue_stage == stages_per_item) {
+            if (issue_item + (int)gridDim.x < p.work) {
+                issue_item += gridDim.x;
+                point_loads_at(issue_item);
+                issue_stage = 0;
+            } else {
+                issue_stage = stages_per_item - 1;
+            }
+        }
+        const unsigned base = smem_lds + slot * STAGE_BYTES;
 #pragma unroll
         for (int j = 0; j < A_LOADS; ++j)
-            load_16B_per_lane_to_lds(agp[j] + (int64_t)stage * BK, base + (wave_u * A_LOADS + j) * 1024);
+            load_16B_per_lane_to_lds(agp[j] + (int64_t)issue_stage * BK, base + (wave_u * A_LOADS + j) * 1024);
 #pragma unroll
         for (int j = 0; j < B_LOADS; ++j)
-            load_16B_per_lane_to_lds(bgp[j] + (int64_t)stage * bstep, base + A_BYTES + (wave_u * B_LOADS + j) * 1024);
+            load_16B_per_lane_to_lds(bgp[j] + (int64_t)issue_stage * bstep, base + A_BYTES + (wave_u * B_LOADS + j) * 1024);
+        ++issue_stage;
     };
-    constexpr int LOADS_PER_STAGE = A_LOADS + B_LOADS;
 
     // ---- LDS fragment addresses (bytes inside a stage) ----
     // X fragment a: row wm*MT*32 + a*32 + li, chunk 2*ks + lg  ->  position (2*ks) ^ (lg ^ ((li>>1)&7)).
@@ -213,19 +206,11 @@ void gemm_tiled_kernel(const TiledParams p) {
         b_off[b] = A_BYTES + (lg * 8 + e) * B_ROW + ((((col >> 3) ^ (e << 2))) << 4) + ((col >> 2) & 1) * 8;
     }
 
-    // big tiles keep at most three stash levels in registers, the rest in LDS behind the stage buffers
-    constexpr int REG_LEVELS = (MT * NT >= 4 && LEVELS > TBIK_MAX_REG_LEVELS) ? TBIK_MAX_REG_LEVELS : LEVELS;
-    Acc<MT, NT> acc;
-    TileStash<REG_LEVELS, MT, NT> stash;
-    stash.lds = smem + 4 * STAGE_BYTES;
-
-    const int total_stages = p.ns_per_shard * p.stages_per_superleaf;
-
     // Fragment registers, double buffered over the K-steps of 16: while the MFMAs of one step run,
     // the LDS reads of the next step (or of the first step of the next stage) are in flight.
     bf16x8 af[2][MT], bfr[2][NT];
-    auto read_frags = [&](int set, int buf, int ks) {
-        const unsigned char *sb = smem + buf * STAGE_BYTES;
+    auto read_frags = [&](int set, int slot, int ks) {
+        const unsigned char *sb = smem + slot * STAGE_BYTES;
 #pragma unroll
         for (int a = 0; a < MT; ++a)
             af[set][a] = *reinterpret_cast<const bf16x8 *>(sb + a_row_off + a * 32 * A_ROW + (a_sw ^ (ks << 5)));
@@ -240,74 +225,90 @@ void gemm_tiled_kernel(const TiledParams p) {
         }
     };
 
-    // Software pipeline over a ring of four LDS stage buffers.  At the top of stage s: wait until this
+    Acc<MT, NT> acc, acc2;
+    TileStash<LEVELS - 1, MT, NT> stash;
+
+    // Software pipeline over a ring of four LDS stage slots.  At the top of stage s: wait until this
     // wavefront's loads of stage s+1 have landed (those of stage s+2 may still be in flight), meet the
-    // other wavefronts at a barrier -- now stage s+1 is complete in LDS and nobody reads the buffer of
-    // stage s-1 any more -- and start the loads of stage s+3 into that buffer.  The barrier is written
+    // other wavefronts at a barrier -- now stage s+1 is complete in LDS and nobody reads the slot of
+    // stage s-1 any more -- and start the loads of stage s+3 into that slot.  The barrier is written
     // in assembly on purpose: a fence would make the compiler drain every outstanding load.
-    issue_stage(0, 0);
-    issue_stage(min(1, total_stages - 1), 1);
-    issue_stage(min(2, total_stages - 1), 2);
+    point_loads_at(issue_item);
+    issue_next_stage(0);
+    issue_next_stage(1);
+    issue_next_stage(2);
     wait_loads_and_barrier<LOADS_PER_STAGE * 2>();      // stage 0 landed everywhere
     read_frags(0, 0, 0);
 
-    int s = 0;             // global stage counter of the software pipeline (runs across superleaves)
-    int cur = 0;           // ring slot of stage s
+    int cur = 0;             // ring slot of the stage being multiplied
+    bool stores_pending = false;   // output stores share the load counter: after them, wait for everything once
 
-    // One superleaf: accumulators start at +0, then stages_per_superleaf LDS stages of MFMA chains.
-    auto superleaf = [&]() {
-#pragma unroll
-        for (int a = 0; a < MT; ++a)
-#pragma unroll
-            for (int b = 0; b < NT; ++b)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc.t[a][b][r] = 0.0f;
-#pragma nounroll
-        for (int q = 0; q < p.stages_per_superleaf; ++q, ++s) {
-            const int nxt = (cur + 1) & 3;
-            wait_loads_and_barrier<LOADS_PER_STAGE>();    // stage s+1 landed; stage s-1's buffer is free
-            issue_stage(min(s + 3, total_stages - 1), (cur + 3) & 3);
-#pragma unroll
-            for (int ks = 0; ks < BK / 16; ++ks) {
-                if (ks + 1 < BK / 16) read_frags((ks + 1) & 1, cur, ks + 1);
-                else read_frags(0, nxt, 0);
-#pragma unroll
-                for (int a = 0; a < MT; ++a)
-#pragma unroll
-                    for (int b = 0; b < NT; ++b)
-                        acc.t[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][a], bfr[ks & 1][b], acc.t[a][b], 0, 0, 0);
-            }
-            cur = nxt;
+    // One LDS stage of MFMA chains into `a`.  FIRST: the accumulators start at +0 (zero C operand).
+    auto stage = [&](auto first, Acc<MT, NT> &a) {
+        constexpr bool FIRST = decltype(first)::value;
+        const int nxt = (cur + 1) & 3;
+        if (stores_pending) {
+            wait_loads_and_barrier<0>();
+            stores_pending = false;
+        } else {
+            wait_loads_and_barrier<LOADS_PER_STAGE>();    // stage s+1 landed; the slot of stage s-1 is free
         }
+        issue_next_stage((cur + 3) & 3);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            if (ks + 1 < BK / 16) read_frags((ks + 1) & 1, cur, ks + 1);
+            else read_frags(0, nxt, 0);
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    if (FIRST && ks == 0) {
+                        const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                        a.t[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[0][i], bfr[0][j], zero, 0, 0, 0);
+                    } else {
+                        a.t[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], a.t[i][j], 0, 0, 0);
+                    }
+                }
+        }
+        cur = nxt;
     };
 
-    // The shard's subtree of depth LEVELS, walked as nested two-trip loops: the first trip of the
-    // loop at level l leaves its subtree sum in the stash slot of that level, the second trip adds
-    // the slot to its own sum (left sibling + right sibling).  Every slot is named statically.
-    SubtreeWalker<LEVELS, REG_LEVELS>::run(superleaf, acc, stash);
-    wait_loads_and_barrier<0>();                          // no load may still be writing LDS when the workgroup ends
+    // One superleaf: stages_per_superleaf stages chained in ascending k.
+    auto superleaf = [&](Acc<MT, NT> &a) {
+        stage(std::true_type{}, a);
+#pragma nounroll
+        for (int q = 1; q < p.stages_per_superleaf; ++q) stage(std::false_type{}, a);
+    };
 
-    // ---- epilogue: acc holds T(superleaves of this shard) ----
-    float *part = p.partials ? p.partials + (int64_t)shard * p.M * p.N : nullptr;
+    for (int item = blockIdx.x; item < p.work; item += gridDim.x) {
+        SubtreeWalker<LEVELS>::run(superleaf, acc, acc2, stash);
+
+        // ---- acc holds T(superleaves of this shard) for this tile: store it ----
+        const int tile = item % p.tiles, shard = item / p.tiles;
+        const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
+        float *part = p.partials ? p.partials + (int64_t)shard * p.M * p.N : nullptr;
 #pragma unroll
-    for (int a = 0; a < MT; ++a) {
+        for (int a = 0; a < MT; ++a) {
 #pragma unroll
-        for (int b = 0; b < NT; ++b) {
-            const int col = n0 + (wn * NT + b) * 32 + li;
-            if (col >= p.N) continue;
+            for (int b = 0; b < NT; ++b) {
+                const int col = n0 + (wn * NT + b) * 32 + li;
+                if (col >= p.N) continue;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + (wm * MT + a) * 32 + 8 * (r >> 2) + 4 * lg + (r & 3);
-                if (row >= p.M) continue;
-                const float v = acc.t[a][b][r];
-                if (part) part[(int64_t)row * p.N + col] = v;
-                if (p.Y) {
-                    if (p.y_bf16) reinterpret_cast<uint16_t *>(p.Y)[(int64_t)row * p.ldy + col] = (uint16_t)f32_to_bf16_bits(v);
-                    else reinterpret_cast<float *>(p.Y)[(int64_t)row * p.ldy + col] = v;
+                for (int r = 0; r < 16; ++r) {
+                    const int row = m0 + (wm * MT + a) * 32 + 8 * (r >> 2) + 4 * lg + (r & 3);
+                    if (row >= p.M) continue;
+                    const float v = acc.t[a][b][r];
+                    if (part) part[(int64_t)row * p.N + col] = v;
+                    if (p.Y) {
+                        if (p.y_bf16) reinterpret_cast<uint16_t *>(p.Y)[(int64_t)row * p.ldy + col] = (uint16_t)f32_to_bf16_bits(v);
+                        else reinterpret_cast<float *>(p.Y)[(int64_t)row * p.ldy + col] = v;
+                    }
                 }
             }
         }
+        stores_pending = true;
     }
+    wait_loads_and_barrier<0>();                          // no load may still be writing LDS when the workgroup ends
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -322,8 +323,20 @@ bool gemm_tiled_supports(const GemmArgs &a, int variant) {
     if (variant != VARIANT_T128 && variant != VARIANT_T32) return false;
     if (a.N % 8 != 0 || a.superleaf % BK != 0) return false;
     if (levels_for(a.ns / a.P) > 4) return false;
-    if ((int64_t)a.P > 65535) return false;
     return true;
+}
+
+static int compute_units() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
 }
 
 template <int WM, int WN, int MT, int NT>
@@ -339,11 +352,13 @@ static hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
     p.k_per_shard = (int64_t)a.K / a.P;
     p.tiles_n = (a.N + BN - 1) / BN;
     const int64_t tiles = (int64_t)p.tiles_n * ((a.M + BM - 1) / BM);
-    if (tiles > 0x7fffffff) return hipErrorInvalidValue;
-    dim3 grid((unsigned)tiles, a.P), block(256);
+    if (tiles * a.P > 0x7fffffff) return hipErrorInvalidValue;
+    p.tiles = (int)tiles;
+    p.work = (int)(tiles * a.P);
+    const int grid_x = p.work < compute_units() ? p.work : compute_units();
+    dim3 grid((unsigned)grid_x), block(256);
+    const size_t lds = 4 * ((size_t)BM * A_ROW + (size_t)BK * B_ROW);
     const int levels = levels_for(p.ns_per_shard);
-    const int lds_levels = (MT * NT >= 4 && levels > TBIK_MAX_REG_LEVELS) ? levels - TBIK_MAX_REG_LEVELS : 0;
-    const size_t lds = 4 * ((size_t)BM * A_ROW + (size_t)BK * B_ROW) + (size_t)lds_levels * MT * NT * 16 * 4 * 256;
 #define TBIK_LAUNCH(L)                                                                                   \
     case L: {                                                                                            \
         auto k = gemm_tiled_kernel<L, WM, WN, MT, NT>;                                                   \
