@@ -31,6 +31,9 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+# HBM bytes per launch of the dominant kernel (tbik_gemm, P=1, M=K=N=4096) from the rocprofv3 FETCH_SIZE / WRITE_SIZE
+# runs summarised in profiles/bench_step_oproj_m4096_pmc.md (384.5 MiB read + 32.0 MiB written).
+GEMM_P1_HBM_TRAFFIC_BYTES = int((384.5 + 32.0) * (1 << 20))
 
 
 def time_region(fn, iters, torch):
@@ -131,7 +134,9 @@ def main():
     gemm_tflops = 2.0 * M * K * N / (gemm_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "gemm_tiled_kernel (tbik_gemm, P=1, M=4096)", "achieved": round(gemm_tflops, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
-                "launch_ms": round(gemm_ms, 4), "traffic": None}
+                "launch_ms": round(gemm_ms, 4), "traffic": GEMM_P1_HBM_TRAFFIC_BYTES,
+                "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, KiB)",
+                "algorithmic_bytes": 2 * M * K + 2 * K * N + 2 * M * N}
 
     # ---- non-invariant baseline GEMM (hipBLASLt / rocBLAS through torch.matmul) on the same operands ----
     base = lambda: torch.matmul(X, W)
