@@ -162,3 +162,32 @@ def sample_elements(seed: int, M: int, N: int, n_rows: int = 64, n_cols: int = 2
     cols = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, size=max(0, min(n_cols, N) - 2))]))
     rr, cc = np.meshgrid(rows, cols, indexing="ij")
     return rr.ravel().astype(np.int64), cc.ravel().astype(np.int64)
+
+
+# ----------------------------------------------------------------------------
+# 32B-class decoder-layer chain (hidden 5120, intermediate 25600, 40 query / 8 KV heads of 128, vocabulary 151936)
+# ----------------------------------------------------------------------------
+
+CHAIN_DIMS = dict(hidden=5120, inter=25600, q_heads=40, kv_heads=8, head_dim=128, vocab=151936, tokens=512, leaf=128)
+
+
+def chain_tensors(device, seed: int = 4):
+    """Random-init weights ~N(0,0.02) (bf16), norm weights 1, input x [512,5120] ~N(0,1) (bf16), drawn on `device`
+    with a seeded torch generator (the lm_head alone is 1.5 GB, too slow to draw on the host)."""
+    import torch
+    d = CHAIN_DIMS
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+
+    def w(k, n):
+        return (torch.randn((k, n), generator=g, device=device, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+
+    qkv_out = (d["q_heads"] + 2 * d["kv_heads"]) * d["head_dim"]
+    return dict(
+        x=torch.randn((d["tokens"], d["hidden"]), generator=g, device=device, dtype=torch.float32).to(torch.bfloat16),
+        norm1=torch.ones(d["hidden"], device=device, dtype=torch.bfloat16),
+        norm2=torch.ones(d["hidden"], device=device, dtype=torch.bfloat16),
+        w_qkv=w(d["hidden"], qkv_out), w_o=w(d["q_heads"] * d["head_dim"], d["hidden"]),
+        w_gate=w(d["hidden"], d["inter"]), w_up=w(d["hidden"], d["inter"]), w_down=w(d["inter"], d["hidden"]),
+        w_lm=w(d["hidden"], d["vocab"]),
+    )
