@@ -21,6 +21,58 @@ __device__ __forceinline__ void unpack8(const uint4 &v, float (&f)[8]) {
     f[6] = bf16_bits_to_f32(v.w & 0xffffu); f[7] = bf16_bits_to_f32(v.w >> 16);
 }
 
+// Register-resident variant for rows of at most 64*CPL chunks (H <= 512*CPL): the row is read once, kept as packed
+// bf16 in registers across the reduction and normalised from there.  Same leaves, same tree, same bits as the
+// two-pass kernel below.
+template <int CPL>
+__global__ __launch_bounds__(64 * RMS_ROWS_PER_BLOCK) void rmsnorm_regs_kernel(
+        const uint16_t *__restrict__ x, const uint16_t *__restrict__ w, uint16_t *__restrict__ y,
+        int M, int H, float eps, int nseg2) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * RMS_ROWS_PER_BLOCK + (threadIdx.x >> 6);
+    if (row >= M) return;                              // whole wavefront leaves together
+    const int nchunks = H >> 3;
+    const uint4 *xr = reinterpret_cast<const uint4 *>(x + (int64_t)row * H);
+    const uint4 *wr = reinterpret_cast<const uint4 *>(w);
+    uint4 *yr = reinterpret_cast<uint4 *>(y + (int64_t)row * H);
+
+    uint4 xv[CPL];
+#pragma unroll
+    for (int s = 0; s < CPL; ++s) {
+        const int c = s * 64 + lane;
+        xv[s] = (c < nchunks) ? xr[c] : make_uint4(0, 0, 0, 0);
+    }
+    TreeStash<RMS_MAX_SEG_LEVELS> st;
+    float ss = 0.0f;
+#pragma unroll
+    for (int s = 0; s < CPL; ++s) {
+        float f[8], leaf = 0.0f;
+        unpack8(xv[s], f);                             // a chunk past the row is all +0: its leaf is +0
+#pragma unroll
+        for (int e = 0; e < 8; ++e) leaf = leaf + f[e] * f[e];
+        if (s < nseg2) ss = st.push(wave_tree_sum(leaf), (unsigned)s);
+    }
+    for (int s = CPL; s < nseg2; ++s) ss = st.push(wave_tree_sum(0.0f), (unsigned)s);   // padding segments
+    const float ms = ss / (float)H;
+    const float r = 1.0f / sqrtf(ms + eps);
+#pragma unroll
+    for (int s = 0; s < CPL; ++s) {
+        const int c = s * 64 + lane;
+        if (c < nchunks) {
+            float f[8], g[8];
+            unpack8(xv[s], f);
+            unpack8(wr[c], g);
+            uint32_t o[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float t = f[e] * r;
+                o[e] = f32_to_bf16_bits(t * g[e]);
+            }
+            yr[c] = make_uint4(o[0] | (o[1] << 16), o[2] | (o[3] << 16), o[4] | (o[5] << 16), o[6] | (o[7] << 16));
+        }
+    }
+}
+
 __global__ __launch_bounds__(64 * RMS_ROWS_PER_BLOCK) void rmsnorm_kernel(
         const uint16_t *__restrict__ x, const uint16_t *__restrict__ w, uint16_t *__restrict__ y,
         int M, int H, float eps, int nseg2) {
@@ -69,7 +121,13 @@ hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int
     while (n2 < nchunks) n2 *= 2;
     const int nseg2 = n2 < 64 ? 1 : n2 / 64;
     dim3 grid((M + RMS_ROWS_PER_BLOCK - 1) / RMS_ROWS_PER_BLOCK), block(64 * RMS_ROWS_PER_BLOCK);
-    hipLaunchKernelGGL(rmsnorm_kernel, grid, block, 0, s, x, w, y, M, H, eps, nseg2);
+    const int cpl = (nchunks + 63) / 64;
+    if (cpl <= 2) hipLaunchKernelGGL(rmsnorm_regs_kernel<2>, grid, block, 0, s, x, w, y, M, H, eps, nseg2);
+    else if (cpl <= 4) hipLaunchKernelGGL(rmsnorm_regs_kernel<4>, grid, block, 0, s, x, w, y, M, H, eps, nseg2);
+    else if (cpl <= 8) hipLaunchKernelGGL(rmsnorm_regs_kernel<8>, grid, block, 0, s, x, w, y, M, H, eps, nseg2);
+    else if (cpl <= 10) hipLaunchKernelGGL(rmsnorm_regs_kernel<10>, grid, block, 0, s, x, w, y, M, H, eps, nseg2);
+    else if (cpl <= 16) hipLaunchKernelGGL(rmsnorm_regs_kernel<16>, grid, block, 0, s, x, w, y, M, H, eps, nseg2);
+    else hipLaunchKernelGGL(rmsnorm_kernel, grid, block, 0, s, x, w, y, M, H, eps, nseg2);
     return hipGetLastError();
 }
 

@@ -93,7 +93,10 @@ __global__ __launch_bounds__(RR_THREADS) void row_block_kernel(const void *__res
                                                                const float *__restrict__ wsmax, float *__restrict__ wsout) {
     __shared__ float lds[RR_SEGS * 4];
     constexpr int EPL = Elem<BF16>::EPL;
-    const int b = blockIdx.x, row = blockIdx.y;
+    // The second pass of log-softmax walks the (row, block) grid backwards: what the first pass read last is
+    // what the caches still hold.  Which workgroup handles a (row, block) never affects its arithmetic.
+    const int b = (MODE == MODE_EXPSUM) ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
+    const int row = (MODE == MODE_EXPSUM) ? (int)(gridDim.y - 1 - blockIdx.y) : (int)blockIdx.y;
     const int lane = threadIdx.x & 63;
     const int64_t nleaves = V / EPL;
     const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * (BF16 ? 2 : 4);
@@ -184,10 +187,11 @@ static hipError_t run(const void *x, void *out, int op, int M, int64_t V, void *
     float *ws0 = reinterpret_cast<float *>(ws);
     float *ws1 = ws0 + (size_t)M * nb;
     float *o = reinterpret_cast<float *>(out);
-    // gridDim.y is limited to 65535 rows per launch
-    for (int m0 = 0; m0 < M; m0 += 65535) {
-        const int mc = (M - m0) < 65535 ? (M - m0) : 65535;
-        const char *xp = reinterpret_cast<const char *>(x) + (int64_t)m0 * V * (BF16 ? 2 : 4);
+    // gridDim.y is limited to 65535 rows per launch.
+    const int64_t group = 65535;
+    for (int64_t m0 = 0; m0 < M; m0 += group) {
+        const int mc = (int)((M - m0) < group ? (M - m0) : group);
+        const char *xp = reinterpret_cast<const char *>(x) + m0 * V * (BF16 ? 2 : 4);
         float *w0 = ws0 + (size_t)m0 * nb, *w1 = ws1 + (size_t)m0 * nb;
         dim3 grid(nb, mc), block(RR_THREADS);
         if (op == TBIK_SUM) {
@@ -200,7 +204,7 @@ static hipError_t run(const void *x, void *out, int op, int M, int64_t V, void *
             hipLaunchKernelGGL((row_block_kernel<BF16, MODE_MAX>), grid, block, 0, s, xp, V, nb, (const float *)nullptr, w0);
             hipLaunchKernelGGL((row_block_kernel<BF16, MODE_EXPSUM>), grid, block, 0, s, xp, V, nb, (const float *)w0, w1);
             hipLaunchKernelGGL((logsoftmax_write_kernel<BF16>), grid, block, 0, s, xp, V, nb, nb2, (const float *)w0,
-                               (const float *)w1, o + (int64_t)m0 * V);
+                               (const float *)w1, o + m0 * V);
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;

@@ -40,12 +40,17 @@ int check_operands(const void *X, int64_t ldx, const void *W, int64_t ldw, int N
     return TBIK_OK;
 }
 
-// Internal split of K across workgroups for shapes with too few output tiles to fill the GPU.
-// Returns the shard count the tiled kernel is launched with when the caller asked for P shards.
-// Depends on the shape only; the result bits do not depend on it (Theorem 1).
+// Internal split of K across workgroups for shapes with too few output tiles to fill the GPU: the kernel is
+// launched as if the caller had asked for `split` shards (fp32 partials into the workspace) and the partials are
+// combined by the same tree (Theorem 1: identical bits).  A pure function of the shape, so that
+// tbik_gemm_workspace_bytes() can be evaluated without a device.
 int internal_split(int M, int N, int ns) {
-    (void)M; (void)N; (void)ns;
-    return 1;
+    const int64_t bm = (M > 32) ? 128 : 32;
+    const int64_t tiles = ((M + bm - 1) / bm) * (((int64_t)N + 127) / 128);
+    if (tiles >= 128) return 1;                 // at least half of the 256 compute units already have a tile
+    int split = 1;
+    while (split < ns && split < 16 && tiles * split < 256) split *= 2;
+    return split;
 }
 
 int pick_variant(const GemmArgs &a) {
