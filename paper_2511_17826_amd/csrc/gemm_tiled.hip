@@ -24,6 +24,13 @@ namespace tbik {
 
 constexpr int BK = 64;                 // K-elements per LDS stage
 constexpr int BN_TILE = 128;           // columns per workgroup tile
+#ifndef TBIK_SPREAD_LOADS
+#define TBIK_SPREAD_LOADS 1
+#endif
+#ifndef TBIK_RING
+#define TBIK_RING 4
+#endif
+constexpr int RING = TBIK_RING;        // LDS stage slots (RING - 2 stages of loads are in flight)
 constexpr int A_ROW = BK * 2;          // bytes per LDS row of the X tile
 constexpr int B_ROW = BN_TILE * 2;     // bytes per LDS row of the W tile
 
@@ -171,10 +178,12 @@ void gemm_tiled_kernel(const TiledParams p) {
 
     const unsigned smem_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    // Loads the next stage of the stream into ring slot `slot`.  Past the last stage of the last item the
-    // last stage is simply loaded again (nobody consumes it).
-    auto issue_next_stage = [&](int slot) {
-        if (issue_stage == stages_per_item) {
+    // Loads the next stage of the stream into ring slot `slot`, in BK/16 parts that the caller spreads over the
+    // K-steps of the stage it is multiplying (part 0 first; a burst of loads would keep the LDS write port busy
+    // while fragment reads wait).  Past the last stage of the last item the last stage is simply loaded again
+    // (nobody consumes it).
+    auto issue_next_stage_part = [&](int slot, int part) {
+        if (part == 0 && issue_stage == stages_per_item) {
             if (issue_item + (int)gridDim.x < p.work) {
                 issue_item += gridDim.x;
                 point_loads_at(issue_item);
@@ -186,11 +195,17 @@ void gemm_tiled_kernel(const TiledParams p) {
         const unsigned base = smem_lds + slot * STAGE_BYTES;
 #pragma unroll
         for (int j = 0; j < A_LOADS; ++j)
-            load_16B_per_lane_to_lds(agp[j] + (int64_t)issue_stage * BK, base + (wave_u * A_LOADS + j) * 1024);
+            if (j % (BK / 16) == part)
+                load_16B_per_lane_to_lds(agp[j] + (int64_t)issue_stage * BK, base + (wave_u * A_LOADS + j) * 1024);
 #pragma unroll
         for (int j = 0; j < B_LOADS; ++j)
-            load_16B_per_lane_to_lds(bgp[j] + (int64_t)issue_stage * bstep, base + A_BYTES + (wave_u * B_LOADS + j) * 1024);
-        ++issue_stage;
+            if (j % (BK / 16) == part)
+                load_16B_per_lane_to_lds(bgp[j] + (int64_t)issue_stage * bstep, base + A_BYTES + (wave_u * B_LOADS + j) * 1024);
+        if (part == BK / 16 - 1) ++issue_stage;
+    };
+    auto issue_next_stage = [&](int slot) {
+#pragma unroll
+        for (int part = 0; part < BK / 16; ++part) issue_next_stage_part(slot, part);
     };
 
     // ---- LDS fragment addresses (bytes inside a stage) ----
@@ -228,16 +243,15 @@ void gemm_tiled_kernel(const TiledParams p) {
     Acc<MT, NT> acc, acc2;
     TileStash<LEVELS - 1, MT, NT> stash;
 
-    // Software pipeline over a ring of four LDS stage slots.  At the top of stage s: wait until this
-    // wavefront's loads of stage s+1 have landed (those of stage s+2 may still be in flight), meet the
+    // Software pipeline over a ring of RING LDS stage slots.  At the top of stage s: wait until this
+    // wavefront's loads of stage s+1 have landed (those of later stages may still be in flight), meet the
     // other wavefronts at a barrier -- now stage s+1 is complete in LDS and nobody reads the slot of
-    // stage s-1 any more -- and start the loads of stage s+3 into that slot.  The barrier is written
+    // stage s-1 any more -- and start the loads of stage s+RING-1 into that slot.  The barrier is written
     // in assembly on purpose: a fence would make the compiler drain every outstanding load.
     point_loads_at(issue_item);
-    issue_next_stage(0);
-    issue_next_stage(1);
-    issue_next_stage(2);
-    wait_loads_and_barrier<LOADS_PER_STAGE * 2>();      // stage 0 landed everywhere
+#pragma unroll
+    for (int i = 0; i < RING - 1; ++i) issue_next_stage(i);
+    wait_loads_and_barrier<LOADS_PER_STAGE * (RING - 2)>();      // stage 0 landed everywhere
     read_frags(0, 0, 0);
 
     int cur = 0;             // ring slot of the stage being multiplied
@@ -246,16 +260,21 @@ void gemm_tiled_kernel(const TiledParams p) {
     // One LDS stage of MFMA chains into `a`.  FIRST: the accumulators start at +0 (zero C operand).
     auto stage = [&](auto first, Acc<MT, NT> &a) {
         constexpr bool FIRST = decltype(first)::value;
-        const int nxt = (cur + 1) & 3;
+        const int nxt = (cur + 1 == RING) ? 0 : cur + 1;
         if (stores_pending) {
             wait_loads_and_barrier<0>();
             stores_pending = false;
         } else {
-            wait_loads_and_barrier<LOADS_PER_STAGE>();    // stage s+1 landed; the slot of stage s-1 is free
+            wait_loads_and_barrier<LOADS_PER_STAGE * (RING - 3)>();    // stage s+1 landed; the slot of stage s-1 is free
         }
-        issue_next_stage((cur + 3) & 3);
+        const int free_slot = cur == 0 ? RING - 1 : cur - 1;  // the slot of stage s-1
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
+#if TBIK_SPREAD_LOADS
+            issue_next_stage_part(free_slot, ks);
+#else
+            if (ks == 0) issue_next_stage(free_slot);
+#endif
             if (ks + 1 < BK / 16) read_frags((ks + 1) & 1, cur, ks + 1);
             else read_frags(0, nxt, 0);
 #pragma unroll
@@ -357,7 +376,7 @@ static hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
     p.work = (int)(tiles * a.P);
     const int grid_x = p.work < compute_units() ? p.work : compute_units();
     dim3 grid((unsigned)grid_x), block(256);
-    const size_t lds = 4 * ((size_t)BM * A_ROW + (size_t)BK * B_ROW);
+    const size_t lds = RING * ((size_t)BM * A_ROW + (size_t)BK * B_ROW);
     const int levels = levels_for(p.ns_per_shard);
 #define TBIK_LAUNCH(L)                                                                                   \
     case L: {                                                                                            \

@@ -47,8 +47,9 @@ int check_operands(const void *X, int64_t ldx, const void *W, int64_t ldw, int N
 int internal_split(int M, int N, int ns) {
     const int64_t bm = (M > 32) ? 128 : 32;
     const int64_t tiles = ((M + bm - 1) / bm) * (((int64_t)N + 127) / 128);
-    if (tiles >= 128) return 1;                 // at least half of the 256 compute units already have a tile
     int split = 1;
+    while (ns / split > 16 && split < TBIK_MAX_SHARDS) split *= 2;   // the tiled kernel walks at most 16 superleaves per shard
+    if (tiles >= 128) return split;             // at least half of the 256 compute units already have a tile
     while (split < ns && split < 16 && tiles * split < 256) split *= 2;
     return split;
 }
@@ -112,10 +113,12 @@ int tbik_gemm(const void *X, int64_t ldx, const void *W, int64_t ldw, void *Y, i
 
     hipStream_t s = (hipStream_t)hip_stream;
     GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)W, ldw, nullptr, Y, ldy, (int)y_dtype, M, N, K, sl, ns, 1};
-    const int v = pick_variant(a);
-    const int split = (v == VARIANT_REFERENCE) ? 1 : internal_split(M, N, ns);
+    const int split = internal_split(M, N, ns);
+    GemmArgs probe = a;
+    probe.P = split;
+    const int v = pick_variant(probe);
     hipError_t e;
-    if (split == 1) {
+    if (split == 1 || v == VARIANT_REFERENCE) {
         e = (v == VARIANT_REFERENCE) ? launch_gemm_reference(a, s) : launch_gemm_tiled(a, v, s);
     } else {
         a.partials = reinterpret_cast<float *>(workspace);
