@@ -24,9 +24,10 @@ namespace tbik {
 
 constexpr int BK = 64;                 // K-elements per LDS stage
 constexpr int BN_TILE = 128;           // columns per workgroup tile
-#ifndef TBIK_SPREAD_LOADS
-#define TBIK_SPREAD_LOADS 1
+#ifndef TBIK_FRAG_AHEAD
+#define TBIK_FRAG_AHEAD 2
 #endif
+constexpr int FRAG_AHEAD = TBIK_FRAG_AHEAD;   // K-steps between an LDS fragment read and its MFMAs (1..3)
 #ifndef TBIK_RING
 #define TBIK_RING 4
 #endif
@@ -182,7 +183,7 @@ void gemm_tiled_kernel(const TiledParams p) {
     // K-steps of the stage it is multiplying (part 0 first; a burst of loads would keep the LDS write port busy
     // while fragment reads wait).  Past the last stage of the last item the last stage is simply loaded again
     // (nobody consumes it).
-    auto issue_next_stage_part = [&](int slot, int part) {
+    auto issue_part_a = [&](int slot, int part) {
         if (part == 0 && issue_stage == stages_per_item) {
             if (issue_item + (int)gridDim.x < p.work) {
                 issue_item += gridDim.x;
@@ -197,6 +198,9 @@ void gemm_tiled_kernel(const TiledParams p) {
         for (int j = 0; j < A_LOADS; ++j)
             if (j % (BK / 16) == part)
                 load_16B_per_lane_to_lds(agp[j] + (int64_t)issue_stage * BK, base + (wave_u * A_LOADS + j) * 1024);
+    };
+    auto issue_part_b = [&](int slot, int part) {
+        const unsigned base = smem_lds + slot * STAGE_BYTES;
 #pragma unroll
         for (int j = 0; j < B_LOADS; ++j)
             if (j % (BK / 16) == part)
@@ -205,7 +209,10 @@ void gemm_tiled_kernel(const TiledParams p) {
     };
     auto issue_next_stage = [&](int slot) {
 #pragma unroll
-        for (int part = 0; part < BK / 16; ++part) issue_next_stage_part(slot, part);
+        for (int part = 0; part < BK / 16; ++part) {
+            issue_part_a(slot, part);
+            issue_part_b(slot, part);
+        }
     };
 
     // ---- LDS fragment addresses (bytes inside a stage) ----
@@ -221,23 +228,32 @@ void gemm_tiled_kernel(const TiledParams p) {
         b_off[b] = A_BYTES + (lg * 8 + e) * B_ROW + ((((col >> 3) ^ (e << 2))) << 4) + ((col >> 2) & 1) * 8;
     }
 
-    // Fragment registers, double buffered over the K-steps of 16: while the MFMAs of one step run,
-    // the LDS reads of the next step (or of the first step of the next stage) are in flight.
-    bf16x8 af[2][MT], bfr[2][NT];
-    auto read_frags = [&](int set, int slot, int ks) {
+    // Fragment registers: the LDS reads run FRAG_AHEAD K-steps ahead of the MFMAs that consume them (into the
+    // next stage's slot near the end of a stage: that slot is complete since the barrier at the top of this stage).
+    constexpr int KSTEPS = BK / 16;
+    bf16x8 af[KSTEPS][MT];                        // one register set per K-step of a stage
+    v4i16 bh[KSTEPS][NT][2];                      // W fragments arrive as two transposed 8-byte halves
+    constexpr int READS_PER_KSTEP = MT + 2 * NT;  // LDS read instructions per K-step
+    // LDS read number r of a K-step: the X fragments first, then the halves of the W fragments.
+    auto read_frag_op = [&](int r, int set, int slot, int ks) {
         const unsigned char *sb = smem + slot * STAGE_BYTES;
-#pragma unroll
-        for (int a = 0; a < MT; ++a)
-            af[set][a] = *reinterpret_cast<const bf16x8 *>(sb + a_row_off + a * 32 * A_ROW + (a_sw ^ (ks << 5)));
-#pragma unroll
-        for (int b = 0; b < NT; ++b) {
-            union { v4i16 h[2]; bf16x8 v; } u;
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-                u.h[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) v4i16 *)(sb + b_off[b] + ks * 16 * B_ROW + h * 4 * B_ROW));
-            bfr[set][b] = u.v;
+        if (r < MT) {
+            af[set][r] = *reinterpret_cast<const bf16x8 *>(sb + a_row_off + r * 32 * A_ROW + (a_sw ^ (ks << 5)));
+        } else {
+            const int b = (r - MT) >> 1, h = (r - MT) & 1;
+            bh[set][b][h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) v4i16 *)(sb + b_off[b] + ks * 16 * B_ROW + h * 4 * B_ROW));
         }
+    };
+    auto read_frags = [&](int set, int slot, int ks) {
+#pragma unroll
+        for (int r = 0; r < READS_PER_KSTEP; ++r) read_frag_op(r, set, slot, ks);
+    };
+    auto w_frag = [&](int set, int b) {
+        union { v4i16 h[2]; bf16x8 v; } u;
+        u.h[0] = bh[set][b][0];
+        u.h[1] = bh[set][b][1];
+        return u.v;
     };
 
     Acc<MT, NT> acc, acc2;
@@ -252,7 +268,8 @@ void gemm_tiled_kernel(const TiledParams p) {
 #pragma unroll
     for (int i = 0; i < RING - 1; ++i) issue_next_stage(i);
     wait_loads_and_barrier<LOADS_PER_STAGE * (RING - 2)>();      // stage 0 landed everywhere
-    read_frags(0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < FRAG_AHEAD; ++i) read_frags(i, 0, i);
 
     int cur = 0;             // ring slot of the stage being multiplied
     bool stores_pending = false;   // output stores share the load counter: after them, wait for everything once
@@ -268,26 +285,32 @@ void gemm_tiled_kernel(const TiledParams p) {
             wait_loads_and_barrier<LOADS_PER_STAGE * (RING - 3)>();    // stage s+1 landed; the slot of stage s-1 is free
         }
         const int free_slot = cur == 0 ? RING - 1 : cur - 1;  // the slot of stage s-1
+        // A wavefront issues in order, one instruction per four cycles at best, and it is alone on its SIMD: every
+        // non-MFMA instruction that is not placed between two MFMAs leaves the matrix pipe idle.  So the K-step is
+        // written as one group per MFMA -- the MFMA, then its share of the LDS reads (FRAG_AHEAD steps ahead) and of
+        // the global->LDS loads of the stage being fetched -- and the scheduler may not move anything across groups.
+        constexpr int NM = MT * NT;
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-#if TBIK_SPREAD_LOADS
-            issue_next_stage_part(free_slot, ks);
-#else
-            if (ks == 0) issue_next_stage(free_slot);
-#endif
-            if (ks + 1 < BK / 16) read_frags((ks + 1) & 1, cur, ks + 1);
-            else read_frags(0, nxt, 0);
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            const bool ahead_in_stage = ks + FRAG_AHEAD < KSTEPS;
+            const int t_set = ahead_in_stage ? ks + FRAG_AHEAD : ks + FRAG_AHEAD - KSTEPS;
+            const int t_slot = ahead_in_stage ? cur : nxt;
 #pragma unroll
-            for (int i = 0; i < MT; ++i)
-#pragma unroll
-                for (int j = 0; j < NT; ++j) {
-                    if (FIRST && ks == 0) {
-                        const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-                        a.t[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[0][i], bfr[0][j], zero, 0, 0, 0);
-                    } else {
-                        a.t[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], a.t[i][j], 0, 0, 0);
-                    }
+            for (int m = 0; m < NM; ++m) {
+                const int i = m / NT, j = m % NT;
+                if (FIRST && ks == 0) {
+                    const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                    a.t[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[0][i], w_frag(0, j), zero, 0, 0, 0);
+                } else {
+                    a.t[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][i], w_frag(ks, j), a.t[i][j], 0, 0, 0);
                 }
+#pragma unroll
+                for (int r = m * READS_PER_KSTEP / NM; r < (m + 1) * READS_PER_KSTEP / NM; ++r)
+                    read_frag_op(r, t_set, t_slot, t_set);
+                if (m == 1 % NM) issue_part_a(free_slot, ks);
+                if (m == 2 % NM) issue_part_b(free_slot, ks);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
         cur = nxt;
     };
