@@ -121,6 +121,7 @@ struct TiledParams {
     int tiles_n;                // column tiles
     int tiles;                  // output tiles per shard
     int work;                   // tiles * shards
+    int vector_stores;          // outputs are 16-byte aligned with 16-byte aligned rows
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -153,6 +154,10 @@ void gemm_tiled_kernel(const TiledParams p) {
     constexpr int A_LOADS = BM / 32;          // per wavefront and stage (BM rows / 8 rows / 4 wavefronts)
     constexpr int B_LOADS = BK / 16;          // 64 rows / 4 rows / 4 wavefronts
     constexpr int LOADS_PER_STAGE = A_LOADS + B_LOADS;
+    constexpr int WCOLS = 32 * NT;                         // columns of a wavefront's tile
+    constexpr int STORES_F32 = MT * (32 * WCOLS / 4 / 64);   // 16-byte store instructions per wavefront and tile
+    constexpr int STORES_BF16 = MT * (32 * WCOLS / 8 / 64);
+    static_assert(LOADS_PER_STAGE * (RING - 3) + STORES_F32 < 64 && STORES_F32 != STORES_BF16, "vmcnt range");
     const uint16_t *agp[A_LOADS];
     const uint16_t *bgp[B_LOADS];
     const int64_t bstep = (int64_t)BK * p.ldw;
@@ -272,18 +277,21 @@ void gemm_tiled_kernel(const TiledParams p) {
     for (int i = 0; i < FRAG_AHEAD; ++i) read_frags(i, 0, i);
 
     int cur = 0;             // ring slot of the stage being multiplied
-    bool stores_pending = false;   // output stores share the load counter: after them, wait for everything once
+    // Output stores share the load counter (vmcnt counts loads and stores in issue order).  -1: an unknown number of
+    // stores was issued (edge tile): wait for everything once.  n >= 0: exactly n store instructions follow the loads
+    // that are in flight, so they are simply added to the allowance of the next wait.
+    int stores_in_flight = 0;
 
     // One LDS stage of MFMA chains into `a`.  FIRST: the accumulators start at +0 (zero C operand).
     auto stage = [&](auto first, Acc<MT, NT> &a) {
         constexpr bool FIRST = decltype(first)::value;
         const int nxt = (cur + 1 == RING) ? 0 : cur + 1;
-        if (stores_pending) {
-            wait_loads_and_barrier<0>();
-            stores_pending = false;
-        } else {
-            wait_loads_and_barrier<LOADS_PER_STAGE * (RING - 3)>();    // stage s+1 landed; the slot of stage s-1 is free
-        }
+        constexpr int ALLOW = LOADS_PER_STAGE * (RING - 3);  // loads of stage s+2.. may still be in flight
+        if (stores_in_flight == 0) wait_loads_and_barrier<ALLOW>();   // stage s+1 landed; the slot of stage s-1 is free
+        else if (stores_in_flight == STORES_F32) wait_loads_and_barrier<ALLOW + STORES_F32>();
+        else if (stores_in_flight == STORES_BF16) wait_loads_and_barrier<ALLOW + STORES_BF16>();
+        else wait_loads_and_barrier<0>();
+        stores_in_flight = 0;
         const int free_slot = cur == 0 ? RING - 1 : cur - 1;  // the slot of stage s-1
         // A wavefront issues in order, one instruction per four cycles at best, and it is alone on its SIMD: every
         // non-MFMA instruction that is not placed between two MFMAs leaves the matrix pipe idle.  So the K-step is
@@ -329,26 +337,68 @@ void gemm_tiled_kernel(const TiledParams p) {
         const int tile = item % p.tiles, shard = item / p.tiles;
         const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
         float *part = p.partials ? p.partials + (int64_t)shard * p.M * p.N : nullptr;
+        const bool interior = (m0 + BM <= p.M) && (n0 + BN <= p.N);
+        if (interior && p.vector_stores) {
+            // Full tile, 16-byte aligned rows: each wavefront turns its 32 x (32*NT) blocks around in its private LDS
+            // patch, so that a lane holds 4 (fp32) or 8 (bf16) consecutive columns and stores 16 bytes.  The number of
+            // store instructions is fixed (no lane masks, no branches), which the load accounting above relies on.
+            float *patch = reinterpret_cast<float *>(smem + RING * STAGE_BYTES) + wave * (32 * WCOLS);
+            const bool to_bf16 = (part == nullptr) && p.y_bf16;
 #pragma unroll
-        for (int a = 0; a < MT; ++a) {
+            for (int a = 0; a < MT; ++a) {
 #pragma unroll
-            for (int b = 0; b < NT; ++b) {
-                const int col = n0 + (wn * NT + b) * 32 + li;
-                if (col >= p.N) continue;
+                for (int b = 0; b < NT; ++b)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = m0 + (wm * MT + a) * 32 + 8 * (r >> 2) + 4 * lg + (r & 3);
-                    if (row >= p.M) continue;
-                    const float v = acc.t[a][b][r];
-                    if (part) part[(int64_t)row * p.N + col] = v;
-                    if (p.Y) {
-                        if (p.y_bf16) reinterpret_cast<uint16_t *>(p.Y)[(int64_t)row * p.ldy + col] = (uint16_t)f32_to_bf16_bits(v);
-                        else reinterpret_cast<float *>(p.Y)[(int64_t)row * p.ldy + col] = v;
+                    for (int r = 0; r < 16; ++r)
+                        patch[(8 * (r >> 2) + 4 * lg + (r & 3)) * WCOLS + b * 32 + li] = acc.t[a][b][r];
+                const int row0 = m0 + (wm * MT + a) * 32, col0 = n0 + wn * WCOLS;
+                if (to_bf16) {
+#pragma unroll
+                    for (int it = 0; it < 32 * WCOLS / 8 / 64; ++it) {
+                        const int idx = it * 64 + lane, row = idx / (WCOLS / 8), c8 = idx % (WCOLS / 8);
+                        const f32x4 lo = *reinterpret_cast<const f32x4 *>(patch + row * WCOLS + c8 * 8);
+                        const f32x4 hi = *reinterpret_cast<const f32x4 *>(patch + row * WCOLS + c8 * 8 + 4);
+                        u32x4 o;
+                        o[0] = f32_to_bf16_bits(lo[0]) | (f32_to_bf16_bits(lo[1]) << 16);
+                        o[1] = f32_to_bf16_bits(lo[2]) | (f32_to_bf16_bits(lo[3]) << 16);
+                        o[2] = f32_to_bf16_bits(hi[0]) | (f32_to_bf16_bits(hi[1]) << 16);
+                        o[3] = f32_to_bf16_bits(hi[2]) | (f32_to_bf16_bits(hi[3]) << 16);
+                        *reinterpret_cast<u32x4 *>(reinterpret_cast<uint16_t *>(p.Y) + (int64_t)(row0 + row) * p.ldy + col0 + c8 * 8) = o;
+                    }
+                } else {
+                    float *dst = part ? part : reinterpret_cast<float *>(p.Y);
+                    const int64_t ld = part ? p.N : p.ldy;
+#pragma unroll
+                    for (int it = 0; it < 32 * WCOLS / 4 / 64; ++it) {
+                        const int idx = it * 64 + lane, row = idx / (WCOLS / 4), c4 = idx % (WCOLS / 4);
+                        *reinterpret_cast<f32x4 *>(dst + (int64_t)(row0 + row) * ld + col0 + c4 * 4) =
+                            *reinterpret_cast<const f32x4 *>(patch + row * WCOLS + c4 * 4);
                     }
                 }
             }
+            stores_in_flight = to_bf16 ? STORES_BF16 : STORES_F32;
+        } else {
+#pragma unroll
+            for (int a = 0; a < MT; ++a) {
+#pragma unroll
+                for (int b = 0; b < NT; ++b) {
+                    const int col = n0 + (wn * NT + b) * 32 + li;
+                    if (col >= p.N) continue;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int row = m0 + (wm * MT + a) * 32 + 8 * (r >> 2) + 4 * lg + (r & 3);
+                        if (row >= p.M) continue;
+                        const float v = acc.t[a][b][r];
+                        if (part) part[(int64_t)row * p.N + col] = v;
+                        if (p.Y) {
+                            if (p.y_bf16) reinterpret_cast<uint16_t *>(p.Y)[(int64_t)row * p.ldy + col] = (uint16_t)f32_to_bf16_bits(v);
+                            else reinterpret_cast<float *>(p.Y)[(int64_t)row * p.ldy + col] = v;
+                        }
+                    }
+                }
+            }
+            stores_in_flight = -1;
         }
-        stores_pending = true;
     }
     wait_loads_and_barrier<0>();                          // no load may still be writing LDS when the workgroup ends
 }
@@ -399,7 +449,12 @@ static hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
     p.work = (int)(tiles * a.P);
     const int grid_x = p.work < compute_units() ? p.work : compute_units();
     dim3 grid((unsigned)grid_x), block(256);
-    const size_t lds = RING * ((size_t)BM * A_ROW + (size_t)BK * B_ROW);
+    const size_t lds = RING * ((size_t)BM * A_ROW + (size_t)BK * B_ROW) + 4 * 32 * (32 * NT) * sizeof(float);
+    {
+        const void *out = p.partials ? (const void *)p.partials : p.Y;
+        const int64_t ld_bytes = p.partials ? (int64_t)a.N * 4 : a.ldy * (p.y_bf16 ? 2 : 4);
+        p.vector_stores = ((reinterpret_cast<uintptr_t>(out) & 15) == 0) && (ld_bytes % 16 == 0);
+    }
     const int levels = levels_for(p.ns_per_shard);
 #define TBIK_LAUNCH(L)                                                                                   \
     case L: {                                                                                            \
