@@ -49,8 +49,10 @@ __device__ __forceinline__ void wait_loads_and_barrier() {
 // global_load_lds_dwordx4: every lane fetches 16 bytes from its own global address; lane i's bytes land at
 // LDS address m0 + 16*i.  Written in assembly so that the compiler does not see an LDS write it would
 // guard with a full wait before later LDS reads; completion is tracked by hand with vmcnt (above).
-__device__ __forceinline__ void load_16B_per_lane_to_lds(const void *gptr, unsigned lds_wave_base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_wave_base), "v"(gptr) : "memory", "m0");
+// The global address is a wave-uniform base (SGPR pair) plus a 32-bit byte offset per lane.
+__device__ __forceinline__ void load_16B_per_lane_to_lds(const void *uniform_base, unsigned lane_offset, unsigned lds_wave_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 ::"s"(lds_wave_base), "v"(lane_offset), "s"(uniform_base) : "memory", "m0");
 }
 
 template <int MT, int NT>              // 32x32 MFMA tiles per wavefront
@@ -158,8 +160,8 @@ void gemm_tiled_kernel(const TiledParams p) {
     constexpr int STORES_F32 = MT * (32 * WCOLS / 4 / 64);   // 16-byte store instructions per wavefront and tile
     constexpr int STORES_BF16 = MT * (32 * WCOLS / 8 / 64);
     static_assert(LOADS_PER_STAGE * (RING - 3) + STORES_F32 < 64 && STORES_F32 != STORES_BF16, "vmcnt range");
-    const uint16_t *agp[A_LOADS];
-    const uint16_t *bgp[B_LOADS];
+    unsigned aoff[A_LOADS], boff[B_LOADS];     // per-lane byte offsets from the item's uniform bases
+    const uint16_t *a_base = p.X, *b_base = p.W;
     const int64_t bstep = (int64_t)BK * p.ldw;
     int issue_item = blockIdx.x;               // work item whose stages are being loaded
     int issue_stage = 0;                       // next stage of that item to load
@@ -168,17 +170,19 @@ void gemm_tiled_kernel(const TiledParams p) {
         const int tile = item % p.tiles, shard = item / p.tiles;
         const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
         const int64_t kbase = (int64_t)shard * p.k_per_shard;
+        a_base = p.X + (int64_t)m0 * p.ldx + kbase;
+        b_base = p.W + kbase * p.ldw + n0;
 #pragma unroll
         for (int j = 0; j < A_LOADS; ++j) {
             const int r = (wave * A_LOADS + j) * 8 + (lane >> 3);
             const int c = (lane & 7) ^ ((r >> 1) & 7);
-            agp[j] = p.X + (int64_t)min(m0 + r, p.M - 1) * p.ldx + kbase + c * 8;
+            aoff[j] = (unsigned)(min(r, p.M - 1 - m0) * (int)p.ldx + c * 8) * 2u;
         }
 #pragma unroll
         for (int j = 0; j < B_LOADS; ++j) {
             const int kk = (wave * B_LOADS + j) * 4 + (lane >> 4);
             const int c = (lane & 15) ^ ((lane >> 4) << 2);
-            bgp[j] = p.W + (kbase + kk) * p.ldw + min(n0 + c * 8, p.N - 8);
+            boff[j] = (unsigned)(kk * (int)p.ldw + min(c * 8, p.N - 8 - n0)) * 2u;
         }
     };
 
@@ -202,14 +206,14 @@ void gemm_tiled_kernel(const TiledParams p) {
 #pragma unroll
         for (int j = 0; j < A_LOADS; ++j)
             if (j % (BK / 16) == part)
-                load_16B_per_lane_to_lds(agp[j] + (int64_t)issue_stage * BK, base + (wave_u * A_LOADS + j) * 1024);
+                load_16B_per_lane_to_lds(a_base + (int64_t)issue_stage * BK, aoff[j], base + (wave_u * A_LOADS + j) * 1024);
     };
     auto issue_part_b = [&](int slot, int part) {
         const unsigned base = smem_lds + slot * STAGE_BYTES;
 #pragma unroll
         for (int j = 0; j < B_LOADS; ++j)
             if (j % (BK / 16) == part)
-                load_16B_per_lane_to_lds(bgp[j] + (int64_t)issue_stage * bstep, base + A_BYTES + (wave_u * B_LOADS + j) * 1024);
+                load_16B_per_lane_to_lds(b_base + (int64_t)issue_stage * bstep, boff[j], base + A_BYTES + (wave_u * B_LOADS + j) * 1024);
         if (part == BK / 16 - 1) ++issue_stage;
     };
     auto issue_next_stage = [&](int slot) {
@@ -415,6 +419,7 @@ bool gemm_tiled_supports(const GemmArgs &a, int variant) {
     if (variant != VARIANT_T128 && variant != VARIANT_T32) return false;
     if (a.N % 8 != 0 || a.superleaf % BK != 0) return false;
     if (levels_for(a.ns / a.P) > 4) return false;
+    if (a.ldx >= (1 << 22) || a.ldw >= (1 << 22)) return false;   // per-lane byte offsets of a tile stay below 2^31
     return true;
 }
 
