@@ -7,20 +7,24 @@
 // superleaf ends, the carry-over step folds the accumulators into the stash of waiting subtrees,
 // which lives in registers (one wavefront per SIMD, up to 512 VGPR+AGPR per lane).
 //
-// Operands are staged through LDS in K-steps of 64 (three stage buffers), both in their global
-// orientation, written with 16-byte stores:
-//   X tile [BM][64]  rows of 128 B; the 16-byte chunk c of row r sits at position c ^ ((r>>1)&7),
-//                    so the 16 rows of a fragment read (ds_read_b128) hit all 64 banks once;
-//   W tile [64][128] rows of 256 B; chunk c of row k sits at position c ^ (4*(k&3)); the MFMA's
-//                    B operand (8 consecutive k of one column per lane) is fetched with the
-//                    transposing LDS read ds_read_b64_tr_b16, whose 16-lane groups read 4 rows x
-//                    16 columns: with the swizzle the 4 rows fall into different banks.
+// Operands are staged through LDS in K-steps of 64 (a ring of stage slots filled by direct global->LDS
+// loads), both in their global orientation.  A stage slot is cut into four regions, one per wavefront
+// (the wavefront that loads it): [BM/4 rows of the X tile | 16 rows of the W tile].
+//   X rows are 128 B; the 16-byte chunk c of row r sits at position c ^ ((r>>1)&7), so the 16 rows
+//                    of a fragment read (ds_read_b128) hit all 64 banks once;
+//   W rows are 256 B; chunk c of row k sits at position c ^ (4*(k&3)); the MFMA's B operand (8
+//                    consecutive k of one column per lane) is fetched with the transposing LDS read
+//                    ds_read_b64_tr_b16, whose 16-lane groups read 4 rows x 16 columns: with the
+//                    swizzle the 4 rows fall into different banks.
 #include <type_traits>
 
 #include "tbik_device.hpp"
 #include "tbik_internal.hpp"
 
 namespace tbik {
+
+template <int V>
+using Int = std::integral_constant<int, V>;
 
 constexpr int BK = 64;                 // K-elements per LDS stage
 constexpr int BN_TILE = 128;           // columns per workgroup tile
@@ -46,13 +50,27 @@ __device__ __forceinline__ void wait_loads_and_barrier() {
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-// global_load_lds_dwordx4: every lane fetches 16 bytes from its own global address; lane i's bytes land at
-// LDS address m0 + 16*i.  Written in assembly so that the compiler does not see an LDS write it would
-// guard with a full wait before later LDS reads; completion is tracked by hand with vmcnt (above).
-// The global address is a wave-uniform base (SGPR pair) plus a 32-bit byte offset per lane.
-__device__ __forceinline__ void load_16B_per_lane_to_lds(const void *uniform_base, unsigned lane_offset, unsigned lds_wave_base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 ::"s"(lds_wave_base), "v"(lane_offset), "s"(uniform_base) : "memory", "m0");
+// global_load_lds_dwordx4: every lane fetches 16 bytes from uniform base + its own 32-bit byte offset + OFFSET;
+// lane i's bytes land at LDS address m0 + OFFSET + 16*i (the instruction offset moves both addresses).  Written in
+// assembly so that the compiler does not see an LDS write it would guard with a full wait before later LDS reads;
+// completion is tracked by hand with vmcnt (above).  m0 is an operand, so one value serves all loads of a stage.
+// AFTER_M0_WRITE: the instruction may directly follow the write of m0, which needs one wait state.
+template <int OFFSET, bool AFTER_M0_WRITE>
+__device__ __forceinline__ void load_16B_per_lane_to_lds(const void *uniform_base, unsigned lane_offset, unsigned m0_value) {
+    static_assert(OFFSET >= -4096 && OFFSET < 4096, "13-bit signed instruction offset");
+    if (AFTER_M0_WRITE)
+        asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 offset:%2"
+                     ::"v"(lane_offset), "s"(uniform_base), "n"(OFFSET), "{m0}"(m0_value) : "memory");
+    else
+        asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2"
+                     ::"v"(lane_offset), "s"(uniform_base), "n"(OFFSET), "{m0}"(m0_value) : "memory");
+}
+
+// Tells the compiler that a pointer is the same in every lane (it then lives in scalar registers).
+__device__ __forceinline__ const char *uniform_pointer(const char *p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const char *>(((uint64_t)hi << 32) | lo);
 }
 
 template <int MT, int NT>              // 32x32 MFMA tiles per wavefront
@@ -136,8 +154,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_tiled_kernel(const TiledParams p) {
     constexpr int BM = 32 * MT * WM, BN = 32 * NT * WN;
     static_assert(BN == BN_TILE && WM * WN == 4, "tile shape");
-    constexpr int A_BYTES = BM * A_ROW, B_BYTES = BK * B_ROW;
-    constexpr int STAGE_BYTES = A_BYTES + B_BYTES;          // stage layout: [X tile | W tile]
+    constexpr int A_LOADS = BM / 32;          // 1 KiB loads per wavefront and stage: BM rows / 8 rows / 4 wavefronts
+    constexpr int B_LOADS = BK / 16;          // 64 rows / 4 rows / 4 wavefronts
+    static_assert(B_LOADS == 4 && A_LOADS <= 4, "one W load and at most one X load per K-step");
+    constexpr int REGION_BYTES = (A_LOADS + B_LOADS) * 1024;   // stage layout: one region per loading wavefront,
+    constexpr int STAGE_BYTES = 4 * REGION_BYTES;               // [8*A_LOADS rows of X | 16 rows of W]
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -153,88 +174,95 @@ void gemm_tiled_kernel(const TiledParams p) {
     // the swizzle is applied on the global side (which chunk a lane fetches).  Rows past M and
     // columns past N are never stored, and an output element depends only on its own row of X and
     // column of W, so out-of-range lanes simply re-read the last valid row / column block.
-    constexpr int A_LOADS = BM / 32;          // per wavefront and stage (BM rows / 8 rows / 4 wavefronts)
-    constexpr int B_LOADS = BK / 16;          // 64 rows / 4 rows / 4 wavefronts
+    // All loads of a wavefront and stage share one m0 (the start of the W part of its region) and differ in
+    // their instruction offsets, -A_LOADS KiB .. -1 KiB for X and 0 .. 3 KiB for W; the lane offsets are biased
+    // so that the global side of the instruction offset cancels.
     constexpr int LOADS_PER_STAGE = A_LOADS + B_LOADS;
     constexpr int WCOLS = 32 * NT;                         // columns of a wavefront's tile
     constexpr int STORES_F32 = MT * (32 * WCOLS / 4 / 64);   // 16-byte store instructions per wavefront and tile
     constexpr int STORES_BF16 = MT * (32 * WCOLS / 8 / 64);
     static_assert(LOADS_PER_STAGE * (RING - 3) + STORES_F32 < 64 && STORES_F32 != STORES_BF16, "vmcnt range");
-    unsigned aoff[A_LOADS], boff[B_LOADS];     // per-lane byte offsets from the item's uniform bases
-    const uint16_t *a_base = p.X, *b_base = p.W;
-    const int64_t bstep = (int64_t)BK * p.ldw;
+    constexpr int LANE_BIAS = 4096;            // keeps every biased lane offset non-negative
+    unsigned aoff[A_LOADS], boff[B_LOADS];     // per-lane byte offsets from the uniform stage pointers
+    const char *a_ptr = nullptr, *b_ptr = nullptr;   // stage pointers of the stage to load next (b_ptr: minus LANE_BIAS)
+    const int64_t b_stage_bytes = (int64_t)BK * p.ldw * 2;
     int issue_item = blockIdx.x;               // work item whose stages are being loaded
     int issue_stage = 0;                       // next stage of that item to load
 
-    auto point_loads_at = [&](int item) {
+    auto point_loads_at = [&](int item) __attribute__((always_inline)) {
         const int tile = item % p.tiles, shard = item / p.tiles;
         const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
         const int64_t kbase = (int64_t)shard * p.k_per_shard;
-        a_base = p.X + (int64_t)m0 * p.ldx + kbase;
-        b_base = p.W + kbase * p.ldw + n0;
+        a_ptr = uniform_pointer(reinterpret_cast<const char *>(p.X + (int64_t)m0 * p.ldx + kbase));
+        b_ptr = uniform_pointer(reinterpret_cast<const char *>(p.W + kbase * p.ldw + n0) - LANE_BIAS);
 #pragma unroll
         for (int j = 0; j < A_LOADS; ++j) {
             const int r = (wave * A_LOADS + j) * 8 + (lane >> 3);
             const int c = (lane & 7) ^ ((r >> 1) & 7);
-            aoff[j] = (unsigned)(min(r, p.M - 1 - m0) * (int)p.ldx + c * 8) * 2u;
+            aoff[j] = (unsigned)(min(r, p.M - 1 - m0) * (int)p.ldx + c * 8) * 2u + (unsigned)((A_LOADS - j) * 1024);
         }
 #pragma unroll
         for (int j = 0; j < B_LOADS; ++j) {
             const int kk = (wave * B_LOADS + j) * 4 + (lane >> 4);
             const int c = (lane & 15) ^ ((lane >> 4) << 2);
-            boff[j] = (unsigned)(kk * (int)p.ldw + min(c * 8, p.N - 8 - n0)) * 2u;
+            boff[j] = (unsigned)(kk * (int)p.ldw + min(c * 8, p.N - 8 - n0)) * 2u + (unsigned)(LANE_BIAS - j * 1024);
         }
     };
 
     const unsigned smem_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const unsigned m0_in_stage = smem_lds + wave_u * REGION_BYTES + A_LOADS * 1024;
     // Loads the next stage of the stream into ring slot `slot`, in BK/16 parts that the caller spreads over the
     // K-steps of the stage it is multiplying (part 0 first; a burst of loads would keep the LDS write port busy
     // while fragment reads wait).  Past the last stage of the last item the last stage is simply loaded again
     // (nobody consumes it).
-    auto issue_part_a = [&](int slot, int part) {
-        if (part == 0 && issue_stage == stages_per_item) {
+    auto issue_part = [&](int slot, auto part_c) __attribute__((always_inline)) {
+        constexpr int PART = decltype(part_c)::value;
+        if (PART == 0 && __builtin_expect(issue_stage == stages_per_item, 0)) {
             if (issue_item + (int)gridDim.x < p.work) {
                 issue_item += gridDim.x;
                 point_loads_at(issue_item);
                 issue_stage = 0;
             } else {
                 issue_stage = stages_per_item - 1;
+                a_ptr -= BK * 2;
+                b_ptr -= b_stage_bytes;
             }
         }
-        const unsigned base = smem_lds + slot * STAGE_BYTES;
-#pragma unroll
-        for (int j = 0; j < A_LOADS; ++j)
-            if (j % (BK / 16) == part)
-                load_16B_per_lane_to_lds(a_base + (int64_t)issue_stage * BK, aoff[j], base + (wave_u * A_LOADS + j) * 1024);
-    };
-    auto issue_part_b = [&](int slot, int part) {
-        const unsigned base = smem_lds + slot * STAGE_BYTES;
-#pragma unroll
-        for (int j = 0; j < B_LOADS; ++j)
-            if (j % (BK / 16) == part)
-                load_16B_per_lane_to_lds(b_base + (int64_t)issue_stage * bstep, boff[j], base + A_BYTES + (wave_u * B_LOADS + j) * 1024);
-        if (part == BK / 16 - 1) ++issue_stage;
+        const unsigned m0v = m0_in_stage + slot * STAGE_BYTES;
+        if constexpr (PART < A_LOADS) load_16B_per_lane_to_lds<(PART - A_LOADS) * 1024, PART == 0>(a_ptr, aoff[PART], m0v);
+        load_16B_per_lane_to_lds<PART * 1024, (PART == 0 && A_LOADS == 0)>(b_ptr, boff[PART], m0v);
+        if (PART == BK / 16 - 1) {
+            ++issue_stage;
+            a_ptr += BK * 2;
+            b_ptr += b_stage_bytes;
+        }
     };
     auto issue_next_stage = [&](int slot) {
-#pragma unroll
-        for (int part = 0; part < BK / 16; ++part) {
-            issue_part_a(slot, part);
-            issue_part_b(slot, part);
-        }
+        issue_part(slot, Int<0>{});
+        issue_part(slot, Int<1>{});
+        issue_part(slot, Int<2>{});
+        issue_part(slot, Int<3>{});
     };
 
     // ---- LDS fragment addresses (bytes inside a stage) ----
-    // X fragment a: row wm*MT*32 + a*32 + li, chunk 2*ks + lg  ->  position (2*ks) ^ (lg ^ ((li>>1)&7)).
-    const int a_row_off = (wm * MT * 32 + li) * A_ROW;
+    // X fragment a: row R = wm*MT*32 + a*32 + li lies in region R / (8*A_LOADS); chunk 2*ks + lg of it sits at
+    // position (2*ks) ^ (lg ^ ((li>>1)&7)).
+    int a_off[MT];
+#pragma unroll
+    for (int a = 0; a < MT; ++a) {
+        const int R = (wm * MT + a) * 32 + li;
+        a_off[a] = (R / (8 * A_LOADS)) * REGION_BYTES + (R % (8 * A_LOADS)) * A_ROW;
+    }
     const int a_sw = (lg ^ ((li >> 1) & 7)) << 4;
-    // W fragment b, half h: a 16-lane group reads rows k0..k0+3 (k0 = 16*ks + 8*lg + 4*h), 16 columns.
+    // W fragment b, half h, K-step ks: region ks holds rows 16*ks .. 16*ks+15; a 16-lane group reads rows
+    // 8*lg + 4*h + (0..3) of it, 16 columns.
     const int l16 = lane & 15, e = l16 >> 2;
     int b_off[NT];
 #pragma unroll
     for (int b = 0; b < NT; ++b) {
         const int col = (wn * NT + b) * 32 + ((lane >> 4) & 1) * 16 + (l16 & 3) * 4;
-        b_off[b] = A_BYTES + (lg * 8 + e) * B_ROW + ((((col >> 3) ^ (e << 2))) << 4) + ((col >> 2) & 1) * 8;
+        b_off[b] = A_LOADS * 1024 + (lg * 8 + e) * B_ROW + ((((col >> 3) ^ (e << 2))) << 4) + ((col >> 2) & 1) * 8;
     }
 
     // Fragment registers: the LDS reads run FRAG_AHEAD K-steps ahead of the MFMAs that consume them (into the
@@ -247,11 +275,11 @@ void gemm_tiled_kernel(const TiledParams p) {
     auto read_frag_op = [&](int r, int set, int slot, int ks) {
         const unsigned char *sb = smem + slot * STAGE_BYTES;
         if (r < MT) {
-            af[set][r] = *reinterpret_cast<const bf16x8 *>(sb + a_row_off + r * 32 * A_ROW + (a_sw ^ (ks << 5)));
+            af[set][r] = *reinterpret_cast<const bf16x8 *>(sb + a_off[r] + (a_sw ^ (ks << 5)));
         } else {
             const int b = (r - MT) >> 1, h = (r - MT) & 1;
             bh[set][b][h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) v4i16 *)(sb + b_off[b] + ks * 16 * B_ROW + h * 4 * B_ROW));
+                (__attribute__((address_space(3))) v4i16 *)(sb + b_off[b] + ks * REGION_BYTES + h * 4 * B_ROW));
         }
     };
     auto read_frags = [&](int set, int slot, int ks) {
@@ -291,11 +319,14 @@ void gemm_tiled_kernel(const TiledParams p) {
         constexpr bool FIRST = decltype(first)::value;
         const int nxt = (cur + 1 == RING) ? 0 : cur + 1;
         constexpr int ALLOW = LOADS_PER_STAGE * (RING - 3);  // loads of stage s+2.. may still be in flight
-        if (stores_in_flight == 0) wait_loads_and_barrier<ALLOW>();   // stage s+1 landed; the slot of stage s-1 is free
-        else if (stores_in_flight == STORES_F32) wait_loads_and_barrier<ALLOW + STORES_F32>();
-        else if (stores_in_flight == STORES_BF16) wait_loads_and_barrier<ALLOW + STORES_BF16>();
-        else wait_loads_and_barrier<0>();
-        stores_in_flight = 0;
+        if (__builtin_expect(stores_in_flight == 0, 1)) {
+            wait_loads_and_barrier<ALLOW>();                         // stage s+1 landed; the slot of stage s-1 is free
+        } else {                                                     // first stage after an epilogue
+            if (stores_in_flight == STORES_F32) wait_loads_and_barrier<ALLOW + STORES_F32>();
+            else if (stores_in_flight == STORES_BF16) wait_loads_and_barrier<ALLOW + STORES_BF16>();
+            else wait_loads_and_barrier<0>();
+            stores_in_flight = 0;
+        }
         const int free_slot = cur == 0 ? RING - 1 : cur - 1;  // the slot of stage s-1
         // A wavefront issues in order, one instruction per four cycles at best, and it is alone on its SIMD: every
         // non-MFMA instruction that is not placed between two MFMAs leaves the matrix pipe idle.  So the K-step is
@@ -319,8 +350,12 @@ void gemm_tiled_kernel(const TiledParams p) {
 #pragma unroll
                 for (int r = m * READS_PER_KSTEP / NM; r < (m + 1) * READS_PER_KSTEP / NM; ++r)
                     read_frag_op(r, t_set, t_slot, t_set);
-                if (m == 1 % NM) issue_part_a(free_slot, ks);
-                if (m == 2 % NM) issue_part_b(free_slot, ks);
+                if (m == 1 % NM) {
+                    if (ks == 0) issue_part(free_slot, Int<0>{});
+                    if (ks == 1) issue_part(free_slot, Int<1>{});
+                    if (ks == 2) issue_part(free_slot, Int<2>{});
+                    if (ks == 3) issue_part(free_slot, Int<3>{});
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
