@@ -143,8 +143,14 @@ def main():
     for _ in range(3):
         base()
     base_ms = min(time_region(base, 20, torch) for _ in range(3))
+    # the same library splitting K by hand (what two tensor-parallel ranks would compute) does not reproduce its own bits
+    whole = torch.matmul(X, W)
+    halves = (torch.matmul(X[:, :K // 2], W[:K // 2]).float() + torch.matmul(X[:, K // 2:], W[K // 2:]).float()).to(torch.bfloat16)
+    base_mismatch = int((whole.view(torch.int16) != halves.view(torch.int16)).sum().item())
+    del whole, halves
     baseline_gemm = {"kind": "torch.matmul bf16 (hipBLASLt/rocBLAS), not shard-invariant", "ms": round(base_ms, 4),
-                     "tflops": round(2.0 * M * K * N / (base_ms * 1e-3) / 1e12, 2)}
+                     "tflops": round(2.0 * M * K * N / (base_ms * 1e-3) / 1e12, 2),
+                     "elements_changed_by_splitting_K_in_two": base_mismatch, "elements": M * N}
 
     # ---- per-row kernels of the step, timed alone (HBM-bound) ----
     kernels = {}
@@ -162,6 +168,15 @@ def main():
         t = min(time_region(lambda: tb.tbik_gemm_shard_partials(X, W, leaf, g, P, out=parts[P], workspace=ws_gemm), 10, torch)
                 for _ in range(2))
         kernels["shard_partials_P%d" % P] = {"ms": round(t, 4), "tflops": round(2.0 * M * K * N / (t * 1e-3) / 1e12, 2)}
+
+    # one rank's share under real tensor parallelism: the shard kernel alone at its real shape [M, K/P] x [K/P, N]
+    # (fp32 partial out); the wire and the other P-1 GPUs are what this leaves out
+    for P in Ps:
+        Xp, Wp = X[:, :K // P], W[:K // P]
+        f = lambda: tb.tbik_gemm_shard_partials(Xp, Wp, leaf, g, 1, out=parts[P][:1], workspace=ws_gemm)
+        f()
+        t = min(time_region(f, 20, torch) for _ in range(3))
+        kernels["one_rank_share_P%d" % P] = {"ms": round(t, 4), "tflops": round(2.0 * M * (K // P) * N / (t * 1e-3) / 1e12, 2)}
 
     if args.extras:
         kernels.update(extras(tb, syn, torch, np, to_dev))

@@ -167,6 +167,58 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_write_kernel(const void
     }
 }
 
+// Log-softmax of rows that fit one block: the row stays in registers between the three steps, so it is read once.
+// Same leaves, same block tree and the same elementwise arithmetic as the three-kernel path (whose trees over a
+// single block value add only +0), hence the same bits.
+template <bool BF16>
+__global__ __launch_bounds__(RR_THREADS) void logsoftmax_one_block_kernel(const void *__restrict__ x, int64_t V,
+                                                                         float *__restrict__ out) {
+    __shared__ float lds[RR_SEGS * 4];
+    constexpr int EPL = Elem<BF16>::EPL;
+    const int row = blockIdx.x;
+    const int64_t nleaves = V / EPL;
+    const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * (BF16 ? 2 : 4);
+    float *orow = out + (int64_t)row * V;
+
+    float f[RR_SEGS][8];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int seg = 0; seg < RR_SEGS; ++seg) {
+        const int64_t leaf = seg * RR_THREADS + threadIdx.x;
+        if (leaf < nleaves) {
+            Elem<BF16>::load(rowp, leaf, f[seg]);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) mx = fmaxf(mx, f[seg][e]);
+        }
+    }
+    const float rowmax = block_max(mx, lds);
+    float L[RR_SEGS];
+#pragma unroll
+    for (int seg = 0; seg < RR_SEGS; ++seg) {
+        const int64_t leaf = seg * RR_THREADS + threadIdx.x;
+        float acc = 0.0f;
+        if (leaf < nleaves) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc = acc + expf(f[seg][e] - rowmax);
+        }
+        L[seg] = acc;
+    }
+    const float S = block_tree_sum(L, lds);
+    const float lg = logf(S);
+#pragma unroll
+    for (int seg = 0; seg < RR_SEGS; ++seg) {
+        const int64_t leaf = seg * RR_THREADS + threadIdx.x;
+        if (leaf < nleaves) {
+            float o[8];
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) o[e] = (f[seg][e] - rowmax) - lg;
+            float4 *dst = reinterpret_cast<float4 *>(orow + leaf * EPL);
+            dst[0] = make_float4(o[0], o[1], o[2], o[3]);
+            if (EPL == 8) dst[1] = make_float4(o[4], o[5], o[6], o[7]);
+        }
+    }
+}
+
 static int blocks_of(int64_t V, int x_dtype) {
     const int epl = (x_dtype == TBIK_BF16) ? 8 : 4;
     const int64_t nleaves = V / epl;
@@ -200,6 +252,8 @@ static hipError_t run(const void *x, void *out, int op, int M, int64_t V, void *
         } else if (op == TBIK_MAX) {
             hipLaunchKernelGGL((row_block_kernel<BF16, MODE_MAX>), grid, block, 0, s, xp, V, nb, (const float *)nullptr, w0);
             hipLaunchKernelGGL((row_finish_kernel<MODE_MAX>), dim3(mc), dim3(64), 0, s, w0, nb, nb2, o + m0);
+        } else if (nb == 1) {
+            hipLaunchKernelGGL((logsoftmax_one_block_kernel<BF16>), dim3(mc), block, 0, s, xp, V, o + m0 * V);
         } else {
             hipLaunchKernelGGL((row_block_kernel<BF16, MODE_MAX>), grid, block, 0, s, xp, V, nb, (const float *)nullptr, w0);
             hipLaunchKernelGGL((row_block_kernel<BF16, MODE_EXPSUM>), grid, block, 0, s, xp, V, nb, (const float *)w0, w1);

@@ -119,6 +119,22 @@ def test_logsoftmax_constant_row_and_small_V():
     assert np.max(np.abs(o - want) / np.maximum(1.0, np.abs(want))) <= 1e-5
 
 
+@pytest.mark.parametrize("V", [8192, 8196])
+def test_logsoftmax_one_block_and_two_block_rows(V):
+    """V = 8192 is the longest fp32 row that one block holds (read once, kept in registers); V = 8196 takes the
+    general path with two blocks.  Both: oracle parity, sum of exp = 1, and a row's bits do not depend on the batch."""
+    x = syn.logits_f32(9, V, seed=11)
+    xd = gu.dev_f32(x)
+    full = tb.tbik_row_reduce(xd, tb.TBIK_LOGSOFTMAX)
+    o = gu.host_f32(full)
+    want = orc.row_logsoftmax(x, orc.LEAF_F32)
+    assert np.max(np.abs(o - want) / np.maximum(1.0, np.abs(want))) <= 1e-5
+    assert np.all(np.abs(np.exp(o.astype(np.float64)).sum(axis=1) - 1.0) <= 1e-5)
+    for (a, b) in [(0, 1), (8, 9), (3, 7)]:
+        y = tb.tbik_row_reduce(xd[a:b].contiguous(), tb.TBIK_LOGSOFTMAX)
+        assert torch.equal(y.view(torch.int32), full[a:b].view(torch.int32)), (a, b)
+
+
 def test_logsoftmax_512_rows_sampled():
     """The full 512 x 151936 case in the launch shape the benchmark times; rows sampled for the oracle."""
     V = 151936
