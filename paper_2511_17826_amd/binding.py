@@ -77,7 +77,13 @@ def _check(status: int, where: str):
         raise TbikError(status, where)
 
 
+_raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+
+
 def _stream() -> int:
+    """Handle of torch's current stream on the current device (the raw getter saves about a microsecond per call)."""
+    if _raw_stream is not None:
+        return _raw_stream(torch.cuda.current_device())
     return torch.cuda.current_stream().cuda_stream
 
 
@@ -122,9 +128,10 @@ def tbik_gemm(X: torch.Tensor, W: torch.Tensor, leaf: int, k_first: int = 1, out
     if out is None:
         out = torch.empty((M, N), dtype=out_dtype, device=X.device)
     _rowmajor(out, "out")
-    need = gemm_workspace_bytes(M, N, K, leaf, k_first)
-    if workspace is None and need:
-        workspace = _workspace(need, X.device)
+    if workspace is None:
+        need = gemm_workspace_bytes(M, N, K, leaf, k_first)
+        if need:
+            workspace = _workspace(need, X.device)
     st = lib().tbik_gemm(X.data_ptr(), X.stride(0), W.data_ptr(), W.stride(0), out.data_ptr(), out.stride(0),
                          _dt(out), M, N, K, leaf, k_first,
                          workspace.data_ptr() if workspace is not None else None,

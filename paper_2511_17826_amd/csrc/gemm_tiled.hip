@@ -16,6 +16,7 @@
 //                    consecutive k of one column per lane) is fetched with the transposing LDS read
 //                    ds_read_b64_tr_b16, whose 16-lane groups read 4 rows x 16 columns: with the
 //                    swizzle the 4 rows fall into different banks.
+#include <atomic>
 #include <type_traits>
 
 #include "tbik_device.hpp"
@@ -32,10 +33,6 @@ constexpr int BN_TILE = 128;           // columns per workgroup tile
 #define TBIK_FRAG_AHEAD 2
 #endif
 constexpr int FRAG_AHEAD = TBIK_FRAG_AHEAD;   // K-steps between an LDS fragment read and its MFMAs (1..3)
-#ifndef TBIK_RING
-#define TBIK_RING 4
-#endif
-constexpr int RING = TBIK_RING;        // LDS stage slots (RING - 2 stages of loads are in flight)
 constexpr int A_ROW = BK * 2;          // bytes per LDS row of the X tile
 constexpr int B_ROW = BN_TILE * 2;     // bytes per LDS row of the W tile
 
@@ -149,7 +146,8 @@ struct TiledParams {
 // Persistent workgroups: workgroup g handles work items g, g + gridDim.x, ... (item = tile + tiles * shard).
 // The global->LDS load stream runs ahead of the MFMA stream across item boundaries, so the first stages
 // of the next tile are already in flight while the current tile is finished and stored.
-template <int LEVELS, int WM, int WN, int MT, int NT>
+// RING: LDS stage slots; RING - 3 stages of loads are in flight at a stage's entry, one more is issued during it.
+template <int LEVELS, int WM, int WN, int MT, int NT, int RING>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_tiled_kernel(const TiledParams p) {
     constexpr int BM = 32 * MT * WM, BN = 32 * NT * WN;
@@ -471,7 +469,7 @@ static int compute_units() {
     return cus;
 }
 
-template <int WM, int WN, int MT, int NT>
+template <int WM, int WN, int MT, int NT, int RING>
 static hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
     constexpr int BM = 32 * MT * WM, BN = 32 * NT * WN;
     TiledParams p;
@@ -496,11 +494,17 @@ static hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
         p.vector_stores = ((reinterpret_cast<uintptr_t>(out) & 15) == 0) && (ld_bytes % 16 == 0);
     }
     const int levels = levels_for(p.ns_per_shard);
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 32) dev = 32;   // 32: not remembered, set every time
 #define TBIK_LAUNCH(L)                                                                                   \
     case L: {                                                                                            \
-        auto k = gemm_tiled_kernel<L, WM, WN, MT, NT>;                                                   \
-        hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-        if (e != hipSuccess) return e;                                                                   \
+        auto k = gemm_tiled_kernel<L, WM, WN, MT, NT, RING>;                                             \
+        static std::atomic<unsigned> lds_allowed{0};   /* bit d: the attribute is set on device d */     \
+        if (dev >= 32 || !((lds_allowed.load(std::memory_order_relaxed) >> dev) & 1u)) {                 \
+            hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+            if (e != hipSuccess) return e;                                                               \
+            if (dev < 32) lds_allowed.fetch_or(1u << dev, std::memory_order_relaxed);                    \
+        }                                                                                                \
         hipLaunchKernelGGL(k, grid, block, lds, s, p);                                                   \
         break;                                                                                           \
     }
@@ -519,8 +523,8 @@ static hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
 hipError_t launch_gemm_tiled(const GemmArgs &a, int variant, hipStream_t s) {
     if (a.M <= 0 || a.N <= 0) return hipSuccess;
     if (!gemm_tiled_supports(a, variant)) return hipErrorInvalidValue;
-    if (variant == VARIANT_T128) return launch_shape<2, 2, 2, 2>(a, s);   // 128 x 128, wave tile 64 x 64
-    return launch_shape<1, 4, 1, 1>(a, s);                                // 32 x 128, wave tile 32 x 32
+    if (variant == VARIANT_T128) return launch_shape<2, 2, 2, 2, 4>(a, s);   // 128 x 128, wave tile 64 x 64, 4 x 32 KiB stage slots
+    return launch_shape<1, 4, 1, 1, 6>(a, s);                                // 32 x 128, wave tile 32 x 32, 6 x 20 KiB: deep prefetch for weight streaming
 }
 
 }  // namespace tbik
