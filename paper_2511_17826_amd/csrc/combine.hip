@@ -39,8 +39,8 @@ __global__ __launch_bounds__(256) void tree_combine_vec4_kernel(const float *__r
         const float x = tree_of<P>(vx), y = tree_of<P>(vy), z = tree_of<P>(vz), w = tree_of<P>(vw);
         if (OUT_BF16) {
             uint16_t *dst = reinterpret_cast<uint16_t *>(Y) + row * ldy + col;
-            const uint32_t lo = f32_to_bf16_bits(x) | (f32_to_bf16_bits(y) << 16);
-            const uint32_t hi = f32_to_bf16_bits(z) | (f32_to_bf16_bits(w) << 16);
+            const uint32_t lo = pack_bf16x2(x, y);
+            const uint32_t hi = pack_bf16x2(z, w);
             if ((reinterpret_cast<uintptr_t>(dst) & 7) == 0) {
                 *reinterpret_cast<uint2 *>(dst) = make_uint2(lo, hi);
             } else {

@@ -396,10 +396,10 @@ void gemm_tiled_kernel(const TiledParams p) {
                         const f32x4 lo = *reinterpret_cast<const f32x4 *>(patch + row * WCOLS + c8 * 8);
                         const f32x4 hi = *reinterpret_cast<const f32x4 *>(patch + row * WCOLS + c8 * 8 + 4);
                         u32x4 o;
-                        o[0] = f32_to_bf16_bits(lo[0]) | (f32_to_bf16_bits(lo[1]) << 16);
-                        o[1] = f32_to_bf16_bits(lo[2]) | (f32_to_bf16_bits(lo[3]) << 16);
-                        o[2] = f32_to_bf16_bits(hi[0]) | (f32_to_bf16_bits(hi[1]) << 16);
-                        o[3] = f32_to_bf16_bits(hi[2]) | (f32_to_bf16_bits(hi[3]) << 16);
+                        o[0] = pack_bf16x2(lo[0], lo[1]);
+                        o[1] = pack_bf16x2(lo[2], lo[3]);
+                        o[2] = pack_bf16x2(hi[0], hi[1]);
+                        o[3] = pack_bf16x2(hi[2], hi[3]);
                         *reinterpret_cast<u32x4 *>(reinterpret_cast<uint16_t *>(p.Y) + (int64_t)(row0 + row) * p.ldy + col0 + c8 * 8) = o;
                     }
                 } else {

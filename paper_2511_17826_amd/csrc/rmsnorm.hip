@@ -62,13 +62,13 @@ __global__ __launch_bounds__(64 * RMS_ROWS_PER_BLOCK) void rmsnorm_regs_kernel(
             float f[8], g[8];
             unpack8(xv[s], f);
             unpack8(wr[c], g);
-            uint32_t o[8];
+            float o[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float t = f[e] * r;
-                o[e] = f32_to_bf16_bits(t * g[e]);
+                o[e] = t * g[e];
             }
-            yr[c] = make_uint4(o[0] | (o[1] << 16), o[2] | (o[3] << 16), o[4] | (o[5] << 16), o[6] | (o[7] << 16));
+            yr[c] = make_uint4(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7]));
         }
     }
 }
@@ -104,13 +104,13 @@ __global__ __launch_bounds__(64 * RMS_ROWS_PER_BLOCK) void rmsnorm_kernel(
         float f[8], g[8];
         unpack8(xr[c], f);
         unpack8(wr[c], g);
-        uint32_t o[8];
+        float o[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const float t = f[e] * r;
-            o[e] = f32_to_bf16_bits(t * g[e]);
+            o[e] = t * g[e];
         }
-        yr[c] = make_uint4(o[0] | (o[1] << 16), o[2] | (o[3] << 16), o[4] | (o[5] << 16), o[6] | (o[7] << 16));
+        yr[c] = make_uint4(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7]));
     }
 }
 

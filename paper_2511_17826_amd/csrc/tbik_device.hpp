@@ -12,13 +12,15 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 // bf16 (bit pattern) -> fp32, exact.
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
 
-// fp32 -> bf16 bit pattern, round to nearest even (the single rounding of an output element).
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x0040u;   // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
+// fp32 -> bf16, round to nearest even (the single rounding of an output element), done by the conversion
+// instruction of gfx950 (v_cvt_pk_bf16_f32 under the default rounding mode); two values per instruction.
+typedef __bf16 tbik_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float tbik_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    const tbik_f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, tbik_bf16x2));
 }
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) { return pack_bf16x2(f, 0.0f) & 0xffffu; }
 
 // Streaming evaluation of the tree operator T (App. C) by the carry-over scheme of App. D.1:
 // values arrive in index order; slot l holds a finished subtree of 2^l values that waits for its
