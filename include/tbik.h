@@ -152,6 +152,12 @@ int tbik_gemm_reference(const void *X, int64_t ldx, const void *W, int64_t ldw, 
 int tbik_set_gemm_variant(int variant);
 const char *tbik_variant_name(int variant);      /* NULL past the last variant */
 
+/* Log-softmax of rows longer than one block lets the workgroups of a row wait for each other a bounded number of
+ * polls; a row whose wait runs out is recomputed by a second kernel of the same call, with the same bits.  This
+ * sets the bound (testing only: 0 makes the waits run out, so that the second kernel is exercised).  Returns the
+ * previous bound; negative values are taken as 0. */
+int tbik_set_row_wait_limit(int polls);
+
 const char *tbik_status_string(int status);
 int tbik_last_hip_error(void);                    /* hipError_t of the last TBIK_ERR_HIP, as int */
 const char *tbik_version(void);

@@ -38,6 +38,7 @@ SIGNATURES = {
     "tbik_gemm_reference": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64,
                                       C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
     "tbik_set_gemm_variant": (C.c_int, [C.c_int]),
+    "tbik_set_row_wait_limit": (C.c_int, [C.c_int]),
     "tbik_variant_name": (C.c_char_p, [C.c_int]),
     "tbik_status_string": (C.c_char_p, [C.c_int]),
     "tbik_last_hip_error": (C.c_int, []),
@@ -214,6 +215,11 @@ def tbik_gemm_reference(X: torch.Tensor, W: torch.Tensor, leaf: int, k_first: in
                                    _dt(Y) if Y is not None else TBIK_F32, M, N, K, leaf, k_first, P, _stream())
     _check(st, "tbik_gemm_reference")
     return parts, Y
+
+
+def tbik_set_row_wait_limit(polls: int) -> int:
+    """Bound of the inter-workgroup waits of the long-row log-softmax (testing); returns the previous bound."""
+    return int(lib().tbik_set_row_wait_limit(polls))
 
 
 def tbik_set_gemm_variant(variant: int):

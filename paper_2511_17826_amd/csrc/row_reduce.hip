@@ -7,7 +7,11 @@
 // sums of a row are then combined by the same tree (blocks past the end of the row count as +0).
 // Which workgroup handles which (row, block) depends only on the row length, never on M, so a
 // row's bits cannot depend on the batch.  Log-softmax keeps the plain two-pass definition:
-// exact max first, then TreeSum(exp(x - max)).
+// exact max first, then TreeSum(exp(x - max)).  Rows of several blocks are handled by one launch in which every
+// workgroup keeps its block in registers and the blocks of a row exchange their maxima and sums through memory
+// (bounded waits; a row whose wait runs out is redone by a second, normally idle, kernel), so a row is read once.
+#include <atomic>
+
 #include "tbik_device.hpp"
 #include "tbik_internal.hpp"
 
@@ -219,6 +223,216 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_one_block_kernel(const 
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Log-softmax of rows of 2..RR_MAX_COOP_BLOCKS blocks, one launch, one workgroup per (row, block), block index
+// fastest.  Each workgroup loads its block once and keeps it in registers; the blocks of a row publish their
+// maxima, wait for each other, publish their sums of exp(x - rowmax), wait again, and write.  The waits are on
+// per-row arrival counters.  Workgroups are started in index order and a row's workgroups are consecutive, so
+// the ones a workgroup waits for are running or about to be started as long as a row has fewer blocks than
+// the device has workgroup slots.  Nothing here relies on that for correctness: every wait is bounded, a
+// workgroup whose wait runs out marks its row and leaves, and logsoftmax_redo_kernel recomputes marked rows.
+// Arithmetic (leaves, block tree, tree over blocks, expf, logf) is that of the three-kernel path: same bits.
+constexpr int RR_MAX_COOP_BLOCKS = 256;
+constexpr int RR_SYNC_WORDS = 64;        // per row: arrival counters at words 0 and 16, flag at word 32 (own 256 bytes)
+
+__device__ __forceinline__ bool wait_for_row(const unsigned *counter, unsigned want, const unsigned *rowflag, int limit,
+                                             unsigned *lds_flag) {
+    if (threadIdx.x == 0) {
+        bool ok = false;
+        for (int it = 0; it <= limit; ++it) {
+            if (__hip_atomic_fetch_or(const_cast<unsigned *>(counter), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= want) { ok = true; break; }
+            if ((it & 15) == 15 && __hip_atomic_load(rowflag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
+            __builtin_amdgcn_s_sleep(8);
+        }
+        *lds_flag = ok ? 1u : 0u;
+    }
+    __syncthreads();
+    const bool ok = (*lds_flag != 0u);
+    __syncthreads();
+    return ok;
+}
+
+// One value per workgroup travels through memory, between workgroups that may sit on different chiplets with
+// separate L2 caches.  No cache is flushed or invalidated for it (a release/acquire pair at device scope would write
+// back and invalidate a chiplet's whole L2 on every call): the value is written and read with read-modify-write
+// atomics of device scope, which are performed where all chiplets meet, and the writer has its atomic's return
+// value in hand -- so the value is in place -- before it counts its arrival with another such atomic.
+__device__ __forceinline__ void publish(float *slot, float v, unsigned *counter) {
+    const unsigned old = __hip_atomic_exchange(reinterpret_cast<unsigned *>(slot), __float_as_uint(v), __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("" ::"v"(old));                                    // needs the returned value: waits for the exchange
+    __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float coherent_load(const float *p) {
+    return __uint_as_float(__hip_atomic_fetch_or(reinterpret_cast<unsigned *>(const_cast<float *>(p)), 0u, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT));
+}
+__device__ __forceinline__ float wave_max_of_published(const float *p, int n, int lane) {
+    float m = -INFINITY;
+    for (int i = lane; i < n; i += 64) m = fmaxf(m, coherent_load(p + i));
+    return wave_max(m);
+}
+__device__ __forceinline__ float wave_tree_of_published(const float *p, int n, int n2, int lane) {
+    TreeStash<26> st;
+    float tot = 0.0f;
+    const int nseg = n2 < 64 ? 1 : n2 >> 6;
+    for (int seg = 0; seg < nseg; ++seg) {
+        const int i = seg * 64 + lane;
+        const float v = (i < n) ? coherent_load(p + i) : 0.0f;
+        tot = st.push(wave_tree_sum(v), (unsigned)seg);
+    }
+    return tot;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(RR_THREADS) void logsoftmax_coop_kernel(const void *__restrict__ x, int64_t V, int nb, int nb2,
+                                                                    float *wsmax, float *wssum, unsigned *sync_words,
+                                                                    int wait_limit, float *__restrict__ out) {
+    __shared__ float lds[RR_SEGS * 4];
+    __shared__ unsigned lds_flag;
+    constexpr int EPL = Elem<BF16>::EPL;
+    const int row = (int)(blockIdx.x / (unsigned)nb), b = (int)(blockIdx.x % (unsigned)nb);
+    const int lane = threadIdx.x & 63;
+    const int64_t nleaves = V / EPL;
+    const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * (BF16 ? 2 : 4);
+    float *orow = out + (int64_t)row * V;
+    unsigned *counters = sync_words + (int64_t)row * RR_SYNC_WORDS, *rowflag = counters + 32;
+
+    float f[RR_SEGS][8];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int seg = 0; seg < RR_SEGS; ++seg) {
+        const int64_t leaf = (int64_t)b * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
+        if (leaf < nleaves) {
+            Elem<BF16>::load(rowp, leaf, f[seg]);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) mx = fmaxf(mx, f[seg][e]);
+        }
+    }
+    const float bm = block_max(mx, lds);
+    if (threadIdx.x == 0) {
+        publish(wsmax + (int64_t)row * nb + b, bm, counters);
+    }
+    if (!wait_for_row(counters, (unsigned)nb, rowflag, wait_limit, &lds_flag)) {
+        if (threadIdx.x == 0) __hip_atomic_store(rowflag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
+    const float rowmax = wave_max_of_published(wsmax + (int64_t)row * nb, nb, lane);
+
+    float L[RR_SEGS];
+#pragma unroll
+    for (int seg = 0; seg < RR_SEGS; ++seg) {
+        const int64_t leaf = (int64_t)b * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
+        float acc = 0.0f;
+        if (leaf < nleaves) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc = acc + expf(f[seg][e] - rowmax);
+        }
+        L[seg] = acc;
+    }
+    const float bs = block_tree_sum(L, lds);
+    if (threadIdx.x == 0) {
+        publish(wssum + (int64_t)row * nb + b, bs, counters + 16);
+    }
+    if (!wait_for_row(counters + 16, (unsigned)nb, rowflag, wait_limit, &lds_flag)) {
+        if (threadIdx.x == 0) __hip_atomic_store(rowflag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
+    const float S = wave_tree_of_published(wssum + (int64_t)row * nb, nb, nb2, lane);
+    const float lg = logf(S);
+#pragma unroll
+    for (int seg = 0; seg < RR_SEGS; ++seg) {
+        const int64_t leaf = (int64_t)b * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
+        if (leaf < nleaves) {
+            float o[8];
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) o[e] = (f[seg][e] - rowmax) - lg;
+            float4 *dst = reinterpret_cast<float4 *>(orow + leaf * EPL);
+            dst[0] = make_float4(o[0], o[1], o[2], o[3]);
+            if (EPL == 8) dst[1] = make_float4(o[4], o[5], o[6], o[7]);
+        }
+    }
+}
+
+// Recomputes the rows that logsoftmax_coop_kernel marked (normally none): one workgroup walks all blocks of its row
+// three times.  Same leaves, block trees and tree over blocks, hence the same bits.
+template <bool BF16>
+__global__ __launch_bounds__(RR_THREADS) void logsoftmax_redo_kernel(const void *__restrict__ x, int64_t V, int nb, int nb2,
+                                                                    const unsigned *__restrict__ sync_words,
+                                                                    float *__restrict__ out) {
+    __shared__ float lds[RR_SEGS * 4];
+    __shared__ float per_block[RR_MAX_COOP_BLOCKS];
+    const int row = blockIdx.x;
+    if (sync_words[(int64_t)row * RR_SYNC_WORDS + 32] == 0u) return;   // uniform over the workgroup
+    constexpr int EPL = Elem<BF16>::EPL;
+    const int lane = threadIdx.x & 63;
+    const int64_t nleaves = V / EPL;
+    const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * (BF16 ? 2 : 4);
+    float *orow = out + (int64_t)row * V;
+
+    for (int b = 0; b < nb; ++b) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int seg = 0; seg < RR_SEGS; ++seg) {
+            const int64_t leaf = (int64_t)b * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
+            if (leaf < nleaves) {
+                float f[8];
+                Elem<BF16>::load(rowp, leaf, f);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) mx = fmaxf(mx, f[e]);
+            }
+        }
+        const float bm = block_max(mx, lds);
+        if (threadIdx.x == 0) per_block[b] = bm;
+    }
+    __syncthreads();
+    const float rowmax = wave_max_of_array(per_block, nb, lane);
+    __syncthreads();
+    for (int b = 0; b < nb; ++b) {
+        float L[RR_SEGS];
+#pragma unroll
+        for (int seg = 0; seg < RR_SEGS; ++seg) {
+            const int64_t leaf = (int64_t)b * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
+            float acc = 0.0f;
+            if (leaf < nleaves) {
+                float f[8];
+                Elem<BF16>::load(rowp, leaf, f);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc = acc + expf(f[e] - rowmax);
+            }
+            L[seg] = acc;
+        }
+        const float bs = block_tree_sum(L, lds);
+        if (threadIdx.x == 0) per_block[b] = bs;
+    }
+    __syncthreads();
+    const float S = wave_tree_of_array(per_block, nb, nb2, lane);
+    const float lg = logf(S);
+    for (int b = 0; b < nb; ++b) {
+#pragma unroll
+        for (int seg = 0; seg < RR_SEGS; ++seg) {
+            const int64_t leaf = (int64_t)b * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
+            if (leaf < nleaves) {
+                float f[8], o[8];
+                Elem<BF16>::load(rowp, leaf, f);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) o[e] = (f[e] - rowmax) - lg;
+                float4 *dst = reinterpret_cast<float4 *>(orow + leaf * EPL);
+                dst[0] = make_float4(o[0], o[1], o[2], o[3]);
+                if (EPL == 8) dst[1] = make_float4(o[4], o[5], o[6], o[7]);
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void zero_words_kernel(unsigned *p, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+static std::atomic<int> g_wait_limit{1 << 14};   // polls per wait: tens of milliseconds at most
+int set_row_wait_limit(int limit) { return g_wait_limit.exchange(limit < 0 ? 0 : limit); }
+
 static int blocks_of(int64_t V, int x_dtype) {
     const int epl = (x_dtype == TBIK_BF16) ? 8 : 4;
     const int64_t nleaves = V / epl;
@@ -228,7 +442,8 @@ static int blocks_of(int64_t V, int x_dtype) {
 size_t row_reduce_workspace(int M, int64_t V, int x_dtype, int op) {
     if (M <= 0 || V <= 0) return 0;
     const size_t per = (size_t)M * blocks_of(V, x_dtype) * sizeof(float);
-    return (op == TBIK_LOGSOFTMAX) ? 2 * per : per;
+    // log-softmax: block maxima, block sums, two arrival counters and one flag per row
+    return (op == TBIK_LOGSOFTMAX) ? 2 * per + (size_t)M * RR_SYNC_WORDS * sizeof(unsigned) : per;
 }
 
 template <bool BF16>
@@ -254,6 +469,14 @@ static hipError_t run(const void *x, void *out, int op, int M, int64_t V, void *
             hipLaunchKernelGGL((row_finish_kernel<MODE_MAX>), dim3(mc), dim3(64), 0, s, w0, nb, nb2, o + m0);
         } else if (nb == 1) {
             hipLaunchKernelGGL((logsoftmax_one_block_kernel<BF16>), dim3(mc), block, 0, s, xp, V, o + m0 * V);
+        } else if (nb <= RR_MAX_COOP_BLOCKS && (int64_t)mc * nb <= 0x7fffffff) {
+            unsigned *words = reinterpret_cast<unsigned *>(ws1 + (size_t)M * nb) + (size_t)m0 * RR_SYNC_WORDS;
+            const int64_t nwords = (int64_t)mc * RR_SYNC_WORDS;
+            hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((nwords + 255) / 256)), dim3(256), 0, s, words, nwords);
+            hipLaunchKernelGGL((logsoftmax_coop_kernel<BF16>), dim3((unsigned)((int64_t)mc * nb)), block, 0, s, xp, V, nb, nb2,
+                               w0, w1, words, g_wait_limit.load(), o + m0 * V);
+            hipLaunchKernelGGL((logsoftmax_redo_kernel<BF16>), dim3(mc), block, 0, s, xp, V, nb, nb2,
+                               (const unsigned *)words, o + m0 * V);
         } else {
             hipLaunchKernelGGL((row_block_kernel<BF16, MODE_MAX>), grid, block, 0, s, xp, V, nb, (const float *)nullptr, w0);
             hipLaunchKernelGGL((row_block_kernel<BF16, MODE_EXPSUM>), grid, block, 0, s, xp, V, nb, (const float *)w0, w1);

@@ -194,6 +194,8 @@ int tbik_row_reduce(const void *x, tbik_dtype x_dtype, void *out, tbik_rowop op,
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }
 
+int tbik_set_row_wait_limit(int polls) { return set_row_wait_limit(polls); }
+
 int tbik_set_gemm_variant(int variant) {
     if (variant < 0 || variant >= VARIANT_COUNT) return TBIK_ERR_UNSUPPORTED;
     g_forced_variant.store(variant);

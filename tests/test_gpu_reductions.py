@@ -135,6 +135,55 @@ def test_logsoftmax_one_block_and_two_block_rows(V):
         assert torch.equal(y.view(torch.int32), full[a:b].view(torch.int32)), (a, b)
 
 
+def test_logsoftmax_bounded_wait_runs_out_same_bits():
+    """Long rows: the workgroups of a row wait for each other a bounded number of polls.  With the bound forced to 0
+    from the host the waits run out, the rows are marked and the second kernel of the call recomputes them: the bits
+    must be those of the normal run (two implementations of the same arithmetic), and every kernel exits normally."""
+    V = 151936
+    x = syn.logits_f32(24, V, seed=5)
+    xd = gu.dev_f32(x)
+    normal = tb.tbik_row_reduce(xd, tb.TBIK_LOGSOFTMAX)
+    torch.cuda.synchronize()
+    prev = tb.tbik_set_row_wait_limit(0)
+    try:
+        forced = tb.tbik_row_reduce(xd, tb.TBIK_LOGSOFTMAX)
+        torch.cuda.synchronize()
+    finally:
+        tb.tbik_set_row_wait_limit(prev)
+    assert prev > 0
+    assert torch.equal(forced.view(torch.int32), normal.view(torch.int32))
+    xb = syn.normal_bf16(np.random.Generator(np.random.PCG64(2)), (6, 40000), 3.0)
+    xbd = gu.dev_bf16(xb)
+    normal = tb.tbik_row_reduce(xbd, tb.TBIK_LOGSOFTMAX)
+    prev = tb.tbik_set_row_wait_limit(0)
+    try:
+        forced = tb.tbik_row_reduce(xbd, tb.TBIK_LOGSOFTMAX)
+        torch.cuda.synchronize()
+    finally:
+        tb.tbik_set_row_wait_limit(prev)
+    assert torch.equal(forced.view(torch.int32), normal.view(torch.int32))
+    want = orc.row_logsoftmax(syn.bf16_bits_to_f32(xb), orc.LEAF_BF16)
+    o = gu.host_f32(normal)
+    assert np.max(np.abs(o - want) / np.maximum(1.0, np.abs(want))) <= 1e-5
+
+
+def test_logsoftmax_long_rows_repeatable_under_load():
+    """The workgroups of a long row hand their maxima and sums to each other through memory, across chiplets: with
+    all compute units busy (512 rows), repeated runs and runs on slices of the batch must keep giving the same bits."""
+    V = 151936
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7)
+    x = torch.randn((512, V), generator=g, device="cuda") * 3.0
+    full = tb.tbik_row_reduce(x, tb.TBIK_LOGSOFTMAX)
+    for _ in range(25):
+        again = tb.tbik_row_reduce(x, tb.TBIK_LOGSOFTMAX)
+        assert torch.equal(again.view(torch.int32), full.view(torch.int32))
+    for (a, b) in [(0, 1), (17, 40), (100, 300), (511, 512), (3, 260)]:
+        for _ in range(3):
+            y = tb.tbik_row_reduce(x[a:b].contiguous(), tb.TBIK_LOGSOFTMAX)
+            assert torch.equal(y.view(torch.int32), full[a:b].view(torch.int32)), (a, b)
+
+
 def test_logsoftmax_512_rows_sampled():
     """The full 512 x 151936 case in the launch shape the benchmark times; rows sampled for the oracle."""
     V = 151936
