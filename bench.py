@@ -32,8 +32,8 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM bytes per launch of the dominant kernel (tbik_gemm, P=1, M=K=N=4096) from the rocprofv3 FETCH_SIZE / WRITE_SIZE
-# runs summarised in profiles/bench_step_oproj_m4096_pmc.md (384.3 MiB read + 32.0 MiB written).
-GEMM_P1_HBM_TRAFFIC_BYTES = int((384.3 + 32.0) * (1 << 20))
+# runs summarised in profiles/bench_step_oproj_m4096_pmc.md (384.2 MiB read + 32.0 MiB written).
+GEMM_P1_HBM_TRAFFIC_BYTES = int((384.2 + 32.0) * (1 << 20))
 
 
 def time_region(fn, iters, torch):
