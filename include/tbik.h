@@ -9,6 +9,7 @@
  * Vocabulary (Sec. 4.2, App. D.1):
  *   leaf        number of consecutive K-elements in one tile of the K dimension (Block_K)
  *   k_first     number of leaves accumulated in one chain before the first tree level (K_first)
+ *               0 selects the odd part of K / leaf, the smallest value that leaves a power of two of superleaves
  *   superleaf   leaf * k_first consecutive k; its products are accumulated in ascending k from +0
  *   n_s         K / (leaf * k_first), the number of superleaves; must be a power of two
  *   P           number of K-shards (the tensor-parallel size C); a power of two, P <= n_s

@@ -22,7 +22,13 @@ int hip_fail(hipError_t e) {
 
 // Shape rules common to the GEMM entry points; fills superleaf / ns.
 int check_tree(int M, int N, int K, int leaf, int k_first, int P, int *superleaf, int *ns) {
-    if (M < 0 || N < 0 || K <= 0 || leaf <= 0 || k_first <= 0) return TBIK_ERR_SHAPE;
+    if (M < 0 || N < 0 || K <= 0 || leaf <= 0 || k_first < 0) return TBIK_ERR_SHAPE;
+    if (k_first == 0) {                       // the smallest legal choice: the odd part of the number of leaves
+        if (K % leaf != 0) return TBIK_ERR_SHAPE;
+        int64_t q = K / leaf;
+        while (q % 2 == 0) q /= 2;
+        k_first = (int)q;
+    }
     const int64_t sl = (int64_t)leaf * k_first;
     if (sl > K || K % sl != 0 || sl % 16 != 0) return TBIK_ERR_SHAPE;
     const int64_t n = K / sl;

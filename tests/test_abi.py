@@ -64,6 +64,9 @@ def test_gemm_argument_validation(L):
     assert gemm(L, K=500) == 2                                         # K not a multiple of the superleaf
     assert gemm(L, K=384, ldx=384) == 2                                # 6 superleaves: not a power of two
     assert gemm(L, leaf=8, g=1, K=512) == 2                            # superleaf not a multiple of 16
+    assert gemm(L, K=384, ldx=384, g=0, M=0) == 0                      # k_first 0 = odd part of 6 leaves = 3: two superleaves
+    assert gemm(L, K=500, g=0) == 2 and gemm(L, g=-1) == 2             # k_first 0 needs K % leaf == 0; negative is illegal
+    assert L.tbik_gemm_workspace_bytes(4, 256, 384, 64, 0) == L.tbik_gemm_workspace_bytes(4, 256, 384, 64, 3)
     assert gemm(L, M=-1) == 2 and gemm(L, leaf=0) == 2
     assert gemm(L, ldx=504) == 2 and gemm(L, ldy=100) == 2             # leading dimension too small
     assert gemm(L, dt=5) == 4

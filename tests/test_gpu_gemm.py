@@ -86,6 +86,19 @@ def test_leaf_sparse_bit_exact_against_oracle(M, K, N, leaf, g):
     assert np.array_equal(gu.host_bf16_bits(ybf), ybf_orc)
 
 
+@pytest.mark.parametrize("M,K,N,leaf,g,Ps", [(9, 16384, 72, 64, 1, (1, 16, 64)), (3, 65536, 40, 64, 1, (1, 2, 64)),
+                                             (5, 8192, 24, 16, 1, (1, 8, 64))])
+def test_deep_trees_and_many_shards(M, K, N, leaf, g, Ps):
+    """256, 1024 and 512 superleaves (trees deeper than one kernel walks in registers: the K cut inside tbik_gemm and
+    the reference kernel take over) and the largest shard count, on leaf-sparse inputs: bit-exact against the oracle."""
+    Xb, Wb = syn.gemm_leaf_sparse(300 + M, M, K, N, leaf * g)
+    y_orc, _ = orc.gemm(Xb, Wb, leaf, g)
+    Xd, Wd = gu.dev_bf16(Xb), gu.dev_bf16(Wb)
+    outs = run_all_routes(Xd, Wd, leaf, g, list(Ps))
+    for key, y in outs.items():
+        assert np.array_equal(gu.u32(gu.host_f32(y)), gu.u32(y_orc)), key
+
+
 @pytest.mark.parametrize("M,K,N,leaf,g", [(70, 1024, 136, 64, 1), (33, 768, 264, 64, 3), (1, 512, 8, 64, 1),
                                           (129, 2048, 128, 128, 2)])
 def test_small_integer_inputs_exact(M, K, N, leaf, g):
@@ -116,6 +129,18 @@ def test_strided_operands_and_outputs():
         torch.cuda.synchronize()
         assert np.array_equal(gu.host_f32(Yw[:, :N]), want), v
         assert torch.all(Yw[:, N:] == -1.0)          # nothing written past N
+
+
+def test_k_first_zero_is_the_odd_part():
+    """k_first = 0 asks for the smallest legal K_first (App. D.1): K = 12288, leaf 256 -> 48 leaves -> 3."""
+    c = syn.gemm_downproj(64)
+    Xd, Wd = gu.dev_bf16(c["X"]), gu.dev_bf16(c["W"])
+    a = tb.tbik_gemm(Xd, Wd, 256, 3, out_dtype=torch.float32)
+    b = tb.tbik_gemm(Xd, Wd, 256, 0, out_dtype=torch.float32)
+    assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+    pa = tb.tbik_gemm_shard_partials(Xd, Wd, 256, 0, 4)
+    pb = tb.tbik_gemm_shard_partials(Xd, Wd, 256, 3, 4)
+    assert torch.equal(pa.view(torch.int32), pb.view(torch.int32))
 
 
 # ----------------------------------------------------------------------------- tiny config: full parity
