@@ -379,7 +379,12 @@ void gemm_tiled_kernel(const TiledParams p) {
             // Full tile, 16-byte aligned rows: each wavefront turns its 32 x (32*NT) blocks around in its private LDS
             // patch, so that a lane holds 4 (fp32) or 8 (bf16) consecutive columns and stores 16 bytes.  The number of
             // store instructions is fixed (no lane masks, no branches), which the load accounting above relies on.
-            float *patch = reinterpret_cast<float *>(smem + RING * STAGE_BYTES) + wave * (32 * WCOLS);
+            // The patch is the wavefront's own region of the stage slot that was multiplied last: nothing is loaded
+            // into that slot before the next stage's barrier, but the other wavefronts may still be reading it.
+            static_assert(REGION_BYTES >= 32 * WCOLS * 4, "the output patch must fit a wavefront's region of a slot");
+            const int last_slot = cur == 0 ? RING - 1 : cur - 1;
+            float *patch = reinterpret_cast<float *>(smem + last_slot * STAGE_BYTES + wave * REGION_BYTES);
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
             const bool to_bf16 = (part == nullptr) && p.y_bf16;
 #pragma unroll
             for (int a = 0; a < MT; ++a) {
@@ -487,7 +492,7 @@ static hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
     p.work = (int)(tiles * a.P);
     const int grid_x = p.work < compute_units() ? p.work : compute_units();
     dim3 grid((unsigned)grid_x), block(256);
-    const size_t lds = RING * ((size_t)BM * A_ROW + (size_t)BK * B_ROW) + 4 * 32 * (32 * NT) * sizeof(float);
+    const size_t lds = RING * ((size_t)BM * A_ROW + (size_t)BK * B_ROW);   // the output patch reuses a stage slot
     {
         const void *out = p.partials ? (const void *)p.partials : p.Y;
         const int64_t ld_bytes = p.partials ? (int64_t)a.N * 4 : a.ldy * (p.y_bf16 ? 2 : 4);
@@ -523,7 +528,7 @@ static hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
 hipError_t launch_gemm_tiled(const GemmArgs &a, int variant, hipStream_t s) {
     if (a.M <= 0 || a.N <= 0) return hipSuccess;
     if (!gemm_tiled_supports(a, variant)) return hipErrorInvalidValue;
-    if (variant == VARIANT_T128) return launch_shape<2, 2, 2, 2, 4>(a, s);   // 128 x 128, wave tile 64 x 64, 4 x 32 KiB stage slots
+    if (variant == VARIANT_T128) return launch_shape<2, 2, 2, 2, 5>(a, s);   // 128 x 128, wave tile 64 x 64, 5 x 32 KiB stage slots = all of LDS
     return launch_shape<1, 4, 1, 1, 6>(a, s);                                // 32 x 128, wave tile 32 x 32, 6 x 20 KiB: deep prefetch for weight streaming
 }
 
