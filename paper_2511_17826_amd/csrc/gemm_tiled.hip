@@ -386,36 +386,65 @@ void gemm_tiled_kernel(const TiledParams p) {
             float *patch = reinterpret_cast<float *>(smem + last_slot * STAGE_BYTES + wave * REGION_BYTES);
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
             const bool to_bf16 = (part == nullptr) && p.y_bf16;
+            // All patch reads of a 32-row block are issued before its first store (one LDS latency per block, not one
+            // per store), and a store's address is a wave-uniform base plus a 32-bit lane offset.
+            const int wm_u = wave_u / WN, wn_u = wave_u % WN;          // the same numbers as wm, wn, known to be uniform
+            const int col0 = n0 + wn_u * WCOLS;
+            if (to_bf16) {
+                constexpr int CPR = WCOLS / 8, RPI = 64 / CPR, N_IT = 32 / RPI;      // 16-byte chunks per row, rows per store
+                const int lrow = lane / CPR, lc = lane % CPR;
+                const float *rd = patch + lrow * WCOLS + lc * 8;
+                const unsigned lane_off = (unsigned)(lrow * (int)p.ldy + lc * 8) * 2u;
+                const int64_t it_step = (int64_t)RPI * p.ldy * 2;
 #pragma unroll
-            for (int a = 0; a < MT; ++a) {
+                for (int a = 0; a < MT; ++a) {
 #pragma unroll
-                for (int b = 0; b < NT; ++b)
+                    for (int b = 0; b < NT; ++b)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        patch[(8 * (r >> 2) + 4 * lg + (r & 3)) * WCOLS + b * 32 + li] = acc.t[a][b][r];
-                const int row0 = m0 + (wm * MT + a) * 32, col0 = n0 + wn * WCOLS;
-                if (to_bf16) {
+                        for (int r = 0; r < 16; ++r)
+                            patch[(8 * (r >> 2) + 4 * lg + (r & 3)) * WCOLS + b * 32 + li] = acc.t[a][b][r];
+                    f32x4 lo[N_IT], hi[N_IT];
 #pragma unroll
-                    for (int it = 0; it < 32 * WCOLS / 8 / 64; ++it) {
-                        const int idx = it * 64 + lane, row = idx / (WCOLS / 8), c8 = idx % (WCOLS / 8);
-                        const f32x4 lo = *reinterpret_cast<const f32x4 *>(patch + row * WCOLS + c8 * 8);
-                        const f32x4 hi = *reinterpret_cast<const f32x4 *>(patch + row * WCOLS + c8 * 8 + 4);
+                    for (int it = 0; it < N_IT; ++it) {
+                        lo[it] = *reinterpret_cast<const f32x4 *>(rd + it * RPI * WCOLS);
+                        hi[it] = *reinterpret_cast<const f32x4 *>(rd + it * RPI * WCOLS + 4);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    char *base = reinterpret_cast<char *>(reinterpret_cast<uint16_t *>(p.Y) +
+                                                          (int64_t)(m0 + (wm_u * MT + a) * 32) * p.ldy + col0);
+#pragma unroll
+                    for (int it = 0; it < N_IT; ++it) {
                         u32x4 o;
-                        o[0] = pack_bf16x2(lo[0], lo[1]);
-                        o[1] = pack_bf16x2(lo[2], lo[3]);
-                        o[2] = pack_bf16x2(hi[0], hi[1]);
-                        o[3] = pack_bf16x2(hi[2], hi[3]);
-                        *reinterpret_cast<u32x4 *>(reinterpret_cast<uint16_t *>(p.Y) + (int64_t)(row0 + row) * p.ldy + col0 + c8 * 8) = o;
+                        o[0] = pack_bf16x2(lo[it][0], lo[it][1]);
+                        o[1] = pack_bf16x2(lo[it][2], lo[it][3]);
+                        o[2] = pack_bf16x2(hi[it][0], hi[it][1]);
+                        o[3] = pack_bf16x2(hi[it][2], hi[it][3]);
+                        *reinterpret_cast<u32x4 *>(base + it * it_step + lane_off) = o;
                     }
-                } else {
-                    float *dst = part ? part : reinterpret_cast<float *>(p.Y);
-                    const int64_t ld = part ? p.N : p.ldy;
+                }
+            } else {
+                constexpr int CPR = WCOLS / 4, RPI = 64 / CPR, N_IT = 32 / RPI;
+                float *dst = part ? part : reinterpret_cast<float *>(p.Y);
+                const int64_t ld = part ? p.N : p.ldy;
+                const int lrow = lane / CPR, lc = lane % CPR;
+                const float *rd = patch + lrow * WCOLS + lc * 4;
+                const unsigned lane_off = (unsigned)(lrow * (int)ld + lc * 4) * 4u;
+                const int64_t it_step = (int64_t)RPI * ld * 4;
 #pragma unroll
-                    for (int it = 0; it < 32 * WCOLS / 4 / 64; ++it) {
-                        const int idx = it * 64 + lane, row = idx / (WCOLS / 4), c4 = idx % (WCOLS / 4);
-                        *reinterpret_cast<f32x4 *>(dst + (int64_t)(row0 + row) * ld + col0 + c4 * 4) =
-                            *reinterpret_cast<const f32x4 *>(patch + row * WCOLS + c4 * 4);
-                    }
+                for (int a = 0; a < MT; ++a) {
+#pragma unroll
+                    for (int b = 0; b < NT; ++b)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            patch[(8 * (r >> 2) + 4 * lg + (r & 3)) * WCOLS + b * 32 + li] = acc.t[a][b][r];
+                    f32x4 v[N_IT];
+#pragma unroll
+                    for (int it = 0; it < N_IT; ++it) v[it] = *reinterpret_cast<const f32x4 *>(rd + it * RPI * WCOLS);
+                    __builtin_amdgcn_sched_barrier(0);
+                    char *base = reinterpret_cast<char *>(dst + (int64_t)(m0 + (wm_u * MT + a) * 32) * ld + col0);
+#pragma unroll
+                    for (int it = 0; it < N_IT; ++it)
+                        *reinterpret_cast<f32x4 *>(base + it * it_step + lane_off) = v[it];
                 }
             }
             stores_in_flight = to_bf16 ? STORES_BF16 : STORES_F32;
