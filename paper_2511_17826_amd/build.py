@@ -47,11 +47,35 @@ def _compile(src: str, extra) -> str:
     return obj
 
 
-def build(save_temps: bool = False, jobs: int = 8, defines=(), lib_path: str = LIB) -> str:
+def check_generated_code(asm_path: str) -> None:
+    """What the tiled GEMM's hand-kept bookkeeping assumes about the code the compiler generated for it:
+    no private-memory (scratch) traffic, whose loads and stores would share the counter that the kernel uses for its
+    direct global->LDS loads, and a wait state between a write of m0 and the direct load that reads it."""
+    import re
+    lines = [l.strip() for l in open(asm_path) if l.strip() and not l.strip().startswith(";")]
+    kernel = None
+    for i, l in enumerate(lines):
+        if l.endswith(":") and "gemm_tiled_kernel" in l:
+            kernel = l
+        if l.startswith("scratch_") and kernel:
+            raise RuntimeError("%s: scratch access in %s: %s" % (asm_path, kernel, l))
+        if re.match(r"s_\w+\s+m0,", l):
+            j = i + 1
+            while lines[j].startswith(".") or lines[j].endswith(":"):
+                j += 1
+            if "global_load_lds" in lines[j]:
+                raise RuntimeError("%s: m0 written directly before a direct load in %s" % (asm_path, kernel))
+        if l.startswith("s_endpgm"):
+            kernel = None
+
+
+def build(save_temps: bool = True, jobs: int = 8, defines=(), lib_path: str = LIB) -> str:
     os.makedirs(BUILD, exist_ok=True)
     extra = (["-save-temps=obj"] if save_temps else []) + ["-D" + d for d in defines]
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(lambda s: _compile(s, extra), SOURCES))
+    if save_temps:
+        check_generated_code(os.path.join(BUILD, "gemm_tiled-hip-amdgcn-amd-amdhsa-gfx950.s"))
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib_path, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
@@ -60,4 +84,4 @@ def build(save_temps: bool = False, jobs: int = 8, defines=(), lib_path: str = L
 
 
 if __name__ == "__main__":
-    print(build(save_temps="--save-temps" in sys.argv))
+    print(build())
