@@ -274,6 +274,20 @@ def extras(tb, syn, torch, np, to_dev):
         res["downproj_M%d" % M] = {"ms": round(t, 4), "tflops": round(2.0 * M * 12288 * 4096 / (t * 1e-3) / 1e12, 2),
                                    "GBps_weights": round(2.0 * 12288 * 4096 / (t * 1e-3) / 1e9, 1), "baseline_ms": round(tb_ms, 4)}
     del X, W
+    # second 8B-class shape set: K = 14336 = 7 * 2^11 (leaf 256, K_first 7, 8 superleaves of 1792)
+    c = syn.gemm_downproj(4096, seed=5, K=14336, N=4096, leaf=256, k_first=7)
+    X, W = to_dev(c["X"]), to_dev(c["W"])
+    for M in (64, 4096):
+        y = torch.empty((M, 4096), dtype=torch.bfloat16, device=X.device)
+        f = lambda: tb.tbik_gemm(X[:M], W, 256, 7, out=y)
+        f(); f()
+        t = min(time_region(f, 10, torch) for _ in range(3))
+        b = lambda: torch.matmul(X[:M], W)
+        b(); b()
+        tb_ms = min(time_region(b, 10, torch) for _ in range(3))
+        res["downproj_k14336_M%d" % M] = {"ms": round(t, 4), "tflops": round(2.0 * M * 14336 * 4096 / (t * 1e-3) / 1e12, 2),
+                                          "baseline_ms": round(tb_ms, 4)}
+    del X, W
     for H in (4096, 5120):
         xb, wb = syn.rmsnorm_inputs(8192, H)
         x, w = to_dev(xb), to_dev(wb)

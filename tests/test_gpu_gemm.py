@@ -196,10 +196,13 @@ def test_tree_combine_alone_bit_exact():
 def _big_case(name):
     if name == "oproj":
         return syn.gemm_oproj(4096), [1, 16, 64, 256, 1024, 4096]
-    return syn.gemm_downproj(4096), [1, 64, 512, 4096]
+    if name == "downproj":
+        return syn.gemm_downproj(4096), [1, 64, 512, 4096]
+    # a second 8B-class shape set (Sec. 4.1's Llama-3.1-8B / Mistral-7B): K = 14336 = 7 * 2^11 -> leaf 256, K_first 7
+    return syn.gemm_downproj(4096, seed=5, K=14336, N=4096, leaf=256, k_first=7), [1, 64, 512, 4096]
 
 
-@pytest.mark.parametrize("name", ["oproj", "downproj"])
+@pytest.mark.parametrize("name", ["oproj", "downproj", "downproj_k14336"])
 def test_8b_shapes_invariance_and_sampled_parity(name):
     """Row r of Y has the same bits for every M, every P in {1,2,4,8}, every kernel variant and every repetition;
     sampled elements match the oracle within the stated tolerance."""
