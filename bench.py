@@ -296,6 +296,28 @@ def extras(tb, syn, torch, np, to_dev):
         f(); f()
         t = min(time_region(f, 20, torch) for _ in range(3))
         res["rmsnorm_8192x%d" % H] = {"ms": round(t, 4), "GBps": round(4.0 * 8192 * H / (t * 1e-3) / 1e9, 1)}
+    # fused tail of a row-parallel layer (combine + residual add + RMSNorm) against the three separate calls
+    M, H = 4096, 4096
+    xb, wb = syn.rmsnorm_inputs(M, H)
+    resid, wn = to_dev(xb), to_dev(wb)
+    for P in (2, 8):
+        parts = torch.randn((P, M, H), device="cuda:0", dtype=torch.float32)
+        hid, out, ybf = torch.empty_like(resid), torch.empty_like(resid), torch.empty_like(resid)
+        fused = lambda: tb.tbik_combine_residual_rmsnorm(parts, resid, wn, 1e-6, hidden=hid, normed=out)
+
+        def separate():
+            tb.tbik_tree_combine(parts, out=ybf)
+            torch.add(ybf, resid, out=hid)
+            tb.tbik_rmsnorm(hid, wn, 1e-6, out=out)
+
+        fused(); separate()
+        t = min(time_region(fused, 20, torch) for _ in range(3))
+        t3 = min(time_region(separate, 20, torch) for _ in range(3))
+        byts = (4.0 * P + 2 + 2 + 2) * M * H
+        res["fused_tail_P%d_4096x4096" % P] = {"ms": round(t, 4), "GBps": round(byts / (t * 1e-3) / 1e9, 1),
+                                               "frac_hbm": round(byts / (t * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                                               "three_calls_ms": round(t3, 4)}
+        del parts
     V = 151936
     for M in (1, 64, 512):
         x = torch.from_numpy(syn.logits_f32(M, V)).to("cuda:0")

@@ -119,6 +119,23 @@ int tbik_tree_combine(const float *partials, int P, void *Y, int64_t ldy, tbik_d
 int tbik_rmsnorm(const void *x, const void *weight, void *y, int M, int H, float eps, void *hip_stream);
 
 /*
+ * Fused tail of a row-parallel layer (one of the "next" fusions that keep the contract): what a decoder layer does
+ * with the tree all-reduce's result (Sec. 3.3, Alg. 2) before the next block,
+ *   Y = bf16(T(partials[0..P)))      exactly tbik_tree_combine with a bf16 output,
+ *   Hd = bf16(Y + R)                 the residual add in fp32, rounded once,
+ *   O = RMSNorm(Hd; weight, eps)     exactly tbik_rmsnorm,
+ * in one pass over the partials.  The bits of Hd and O are those of the three steps done one after the other.
+ *
+ *   partials   device, fp32, dense [P, M, H]         residual   device, bf16, dense [M, H]
+ *   weight     device, bf16, [H]                     hidden, normed   device, bf16, dense [M, H] (written)
+ *   hidden may be the same buffer as residual (updated in place); normed may not share a buffer with either.
+ *   P a power of two, P <= 16 (larger legal P: TBIK_ERR_UNSUPPORTED).  H a multiple of 8, H <= 65536; 16-byte alignment.
+ * Errors: NULL, SHAPE, SHARDS, UNSUPPORTED, ALIGN, HIP.
+ */
+int tbik_combine_residual_rmsnorm(const float *partials, int P, const void *residual, const void *weight, float eps,
+                                  void *hidden, void *normed, int M, int H, void *hip_stream);
+
+/*
  * Batch-invariant row reductions over dense rows x[M, V] (App. B; softmax in fp32 per Sec. 2.1):
  *   TBIK_SUM         out[m]   = TreeSum_i x[m,i]                                   out fp32 [M]
  *   TBIK_MAX         out[m]   = max_i x[m,i]                                       out fp32 [M]

@@ -227,6 +227,17 @@ def rmsnorm(x, w, eps: float = 1e-6, leaf: int = LEAF_BF16) -> np.ndarray:
     return y
 
 
+def combine_residual_rmsnorm(partials, residual_bits, weight_bits, eps: float = 1e-6):
+    """The tail of a row-parallel layer, one step after the other: Y = bf16(T(partials)) by the reduce phase of Alg. 2
+    (Sec. 3.3); Hd = bf16(Y + R), the sum formed in fp32 and rounded once; O = RMSNorm(Hd) (App. B).
+    Returns (Hd bits, O bits), uint16 [M, H]."""
+    _, ybf = tree_combine(partials)
+    widen = lambda b: (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+    h32 = (widen(ybf) + widen(residual_bits)).astype(np.float32)          # one IEEE binary32 addition per element
+    hbits = f32_to_bf16_bits(h32)
+    return hbits, rmsnorm(hbits, weight_bits, eps)
+
+
 def sumsq_bf16(row, leaf: int = LEAF_BF16) -> np.float32:
     row, rp = _u16(row)
     return np.float32(lib().tbik_oracle_sumsq_bf16(rp, row.size, leaf))

@@ -37,6 +37,8 @@ SIGNATURES = {
     "tbik_row_reduce_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int64, C.c_int]),
     "tbik_gemm_reference": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64,
                                       C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
+    "tbik_combine_residual_rmsnorm": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p,
+                                                C.c_int, C.c_int, C.c_void_p]),
     "tbik_set_gemm_variant": (C.c_int, [C.c_int]),
     "tbik_set_row_wait_limit": (C.c_int, [C.c_int]),
     "tbik_variant_name": (C.c_char_p, [C.c_int]),
@@ -184,6 +186,24 @@ def tbik_rmsnorm(x: torch.Tensor, weight: torch.Tensor, eps: float = 1e-6, out: 
     st = lib().tbik_rmsnorm(x.data_ptr(), weight.data_ptr(), out.data_ptr(), x.shape[0], x.shape[1], eps, _stream())
     _check(st, "tbik_rmsnorm")
     return out
+
+
+def tbik_combine_residual_rmsnorm(partials: torch.Tensor, residual: torch.Tensor, weight: torch.Tensor, eps: float = 1e-6,
+                                  hidden: torch.Tensor | None = None, normed: torch.Tensor | None = None):
+    """(hidden, normed): hidden = bf16(bf16(T(partials)) + residual), normed = RMSNorm(hidden); one kernel."""
+    assert partials.dim() == 3 and partials.is_contiguous() and partials.dtype == torch.float32
+    P, M, H = partials.shape
+    assert residual.shape == (M, H) and residual.is_contiguous() and residual.dtype == torch.bfloat16
+    assert weight.shape == (H,) and weight.dtype == torch.bfloat16
+    if hidden is None:
+        hidden = torch.empty_like(residual)
+    if normed is None:
+        normed = torch.empty_like(residual)
+    assert hidden.is_contiguous() and normed.is_contiguous() and hidden.dtype == normed.dtype == torch.bfloat16
+    st = lib().tbik_combine_residual_rmsnorm(partials.data_ptr(), P, residual.data_ptr(), weight.data_ptr(), eps,
+                                             hidden.data_ptr(), normed.data_ptr(), M, H, _stream())
+    _check(st, "tbik_combine_residual_rmsnorm")
+    return hidden, normed
 
 
 def tbik_row_reduce(x: torch.Tensor, op: int, out: torch.Tensor | None = None,

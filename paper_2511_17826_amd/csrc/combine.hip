@@ -8,16 +8,6 @@
 
 namespace tbik {
 
-template <int P>
-__device__ __forceinline__ float tree_of(float (&v)[P]) {
-#pragma unroll
-    for (int s = 1; s < P; s *= 2) {
-#pragma unroll
-        for (int r = 0; r < P; r += 2 * s) v[r] = v[r] + v[r + s];
-    }
-    return v[0];
-}
-
 // Vector path: N % 4 == 0; each thread owns 4 consecutive columns of one row.
 template <int P, bool OUT_BF16>
 __global__ __launch_bounds__(256) void tree_combine_vec4_kernel(const float *__restrict__ partials, void *__restrict__ Y,

@@ -114,6 +114,127 @@ __global__ __launch_bounds__(64 * RMS_ROWS_PER_BLOCK) void rmsnorm_kernel(
     }
 }
 
+// Fused tail of a row-parallel layer: per element Y = bf16(T(partials[0..P))) as the top-of-tree combine does
+// (Alg. 2's additions, one rounding), H = bf16(Y + R) with the residual R, then the RMSNorm above over the row of H.
+// One wavefront per row; first pass: combine, add, store H, leaf sums of squares; second pass: re-read H (the
+// wavefront's own stores, served by the cache) and scale.  Bit for bit the three separate calls.
+template <int P>
+__global__ __launch_bounds__(64 * RMS_ROWS_PER_BLOCK) void combine_residual_rmsnorm_kernel(
+        const float *__restrict__ partials, const uint16_t *res, const uint16_t *__restrict__ w,
+        uint16_t *hidden, uint16_t *__restrict__ normed, int M, int H, float eps, int nseg2) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * RMS_ROWS_PER_BLOCK + (threadIdx.x >> 6);
+    if (row >= M) return;                              // whole wavefront leaves together
+    const int nchunks = H >> 3;
+    const int64_t plane = (int64_t)M * H;
+    const float *pr = partials + (int64_t)row * H;
+    const uint4 *rr = reinterpret_cast<const uint4 *>(res + (int64_t)row * H);
+    const uint4 *wr = reinterpret_cast<const uint4 *>(w);
+    uint4 *hr = reinterpret_cast<uint4 *>(hidden + (int64_t)row * H);
+    uint4 *yr = reinterpret_cast<uint4 *>(normed + (int64_t)row * H);
+
+    TreeStash<RMS_MAX_SEG_LEVELS> st;
+    float ss = 0.0f;
+    for (int seg = 0; seg < nseg2; ++seg) {
+        const int c = seg * 64 + lane;
+        float leaf = 0.0f;
+        if (c < nchunks) {
+            float4 lo[P], hi[P];
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                lo[p] = *reinterpret_cast<const float4 *>(pr + (int64_t)p * plane + c * 8);
+                hi[p] = *reinterpret_cast<const float4 *>(pr + (int64_t)p * plane + c * 8 + 4);
+            }
+            float y[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float v[P];
+#pragma unroll
+                for (int p = 0; p < P; ++p) {
+                    const float4 &q = (e < 4) ? lo[p] : hi[p];
+                    v[p] = (e & 3) == 0 ? q.x : (e & 3) == 1 ? q.y : (e & 3) == 2 ? q.z : q.w;
+                }
+                y[e] = tree_of<P>(v);
+            }
+            float r[8], yb[8], h[8];
+            unpack8(rr[c], r);
+            unpack8(make_uint4(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]), pack_bf16x2(y[6], y[7])), yb);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) h[e] = yb[e] + r[e];
+            const uint4 hv = make_uint4(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]), pack_bf16x2(h[4], h[5]), pack_bf16x2(h[6], h[7]));
+            hr[c] = hv;
+            float f[8];
+            unpack8(hv, f);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) leaf = leaf + f[e] * f[e];
+        }
+        ss = st.push(wave_tree_sum(leaf), (unsigned)seg);
+    }
+    const float ms = ss / (float)H;
+    const float rinv = 1.0f / sqrtf(ms + eps);
+
+    for (int c = lane; c < nchunks; c += 64) {
+        float f[8], g[8];
+        unpack8(hr[c], f);
+        unpack8(wr[c], g);
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float t = f[e] * rinv;
+            o[e] = t * g[e];
+        }
+        yr[c] = make_uint4(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7]));
+    }
+}
+
+// hidden = bf16(y + residual), 8 elements per thread (the middle step of the unfused route below).
+__global__ __launch_bounds__(256) void residual_add_kernel(const uint16_t *__restrict__ y, const uint16_t *res,
+                                                           uint16_t *hidden, int64_t nchunks) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < nchunks; c += stride) {
+        float a[8], b[8];
+        unpack8(reinterpret_cast<const uint4 *>(y)[c], a);
+        unpack8(reinterpret_cast<const uint4 *>(res)[c], b);
+        float h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = a[e] + b[e];
+        reinterpret_cast<uint4 *>(hidden)[c] =
+            make_uint4(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]), pack_bf16x2(h[4], h[5]), pack_bf16x2(h[6], h[7]));
+    }
+}
+
+hipError_t launch_combine_residual_rmsnorm(const float *partials, int P, const uint16_t *res, const uint16_t *w,
+                                           uint16_t *hidden, uint16_t *normed, int M, int H, float eps, hipStream_t s) {
+    if (M <= 0) return hipSuccess;
+    const int nchunks = H / 8;
+    int n2 = 1;
+    while (n2 < nchunks) n2 *= 2;
+    const int nseg2 = n2 < 64 ? 1 : n2 / 64;
+    // With many partial tensors and a large batch the row-per-wavefront walk over P planes falls behind the plain
+    // combine kernel; then the three steps run one after the other (the normed buffer holds Y in between).  Same bits.
+    if (P > 4 && (int64_t)M * H * P > (int64_t)32 << 20) {
+        hipError_t e = launch_tree_combine(partials, P, normed, H, TBIK_BF16, M, H, s);
+        if (e != hipSuccess) return e;
+        const int64_t chunks = (int64_t)M * H / 8;
+        const int64_t blocks = (chunks + 255) / 256;
+        hipLaunchKernelGGL(residual_add_kernel, dim3((unsigned)(blocks < 65536 ? blocks : 65536)), dim3(256), 0, s, normed, res,
+                           hidden, chunks);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        return launch_rmsnorm(hidden, w, normed, M, H, eps, s);
+    }
+    dim3 grid((M + RMS_ROWS_PER_BLOCK - 1) / RMS_ROWS_PER_BLOCK), block(64 * RMS_ROWS_PER_BLOCK);
+    switch (P) {
+        case 1: hipLaunchKernelGGL(combine_residual_rmsnorm_kernel<1>, grid, block, 0, s, partials, res, w, hidden, normed, M, H, eps, nseg2); break;
+        case 2: hipLaunchKernelGGL(combine_residual_rmsnorm_kernel<2>, grid, block, 0, s, partials, res, w, hidden, normed, M, H, eps, nseg2); break;
+        case 4: hipLaunchKernelGGL(combine_residual_rmsnorm_kernel<4>, grid, block, 0, s, partials, res, w, hidden, normed, M, H, eps, nseg2); break;
+        case 8: hipLaunchKernelGGL(combine_residual_rmsnorm_kernel<8>, grid, block, 0, s, partials, res, w, hidden, normed, M, H, eps, nseg2); break;
+        case 16: hipLaunchKernelGGL(combine_residual_rmsnorm_kernel<16>, grid, block, 0, s, partials, res, w, hidden, normed, M, H, eps, nseg2); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int M, int H, float eps, hipStream_t s) {
     if (M <= 0) return hipSuccess;
     const int nchunks = H / 8;

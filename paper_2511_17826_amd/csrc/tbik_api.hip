@@ -184,6 +184,21 @@ size_t tbik_row_reduce_workspace_bytes(int M, int64_t V, tbik_rowop op) {
     return row_reduce_workspace(M, V, TBIK_F32, (int)op);
 }
 
+int tbik_combine_residual_rmsnorm(const float *partials, int P, const void *residual, const void *weight, float eps,
+                                  void *hidden, void *normed, int M, int H, void *hip_stream) {
+    if (M < 0 || H <= 0 || H % 8 != 0 || H > 65536) return TBIK_ERR_SHAPE;
+    if (P < 1 || !is_pow2(P) || P > TBIK_MAX_SHARDS) return TBIK_ERR_SHARDS;
+    if (P > 16) return TBIK_ERR_UNSUPPORTED;
+    if (M == 0) return TBIK_OK;
+    if (!partials || !residual || !weight || !hidden || !normed) return TBIK_ERR_NULL;
+    if (!aligned(partials, 16) || !aligned(residual, 16) || !aligned(weight, 16) || !aligned(hidden, 16) || !aligned(normed, 16))
+        return TBIK_ERR_ALIGN;
+    if (normed == hidden || normed == residual) return TBIK_ERR_SHAPE;      // only hidden may share residual's buffer
+    hipError_t e = launch_combine_residual_rmsnorm(partials, P, (const uint16_t *)residual, (const uint16_t *)weight,
+                                                   (uint16_t *)hidden, (uint16_t *)normed, M, H, eps, (hipStream_t)hip_stream);
+    return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
 int tbik_row_reduce(const void *x, tbik_dtype x_dtype, void *out, tbik_rowop op, int M, int64_t V,
                     void *workspace, size_t workspace_bytes, void *hip_stream) {
     if (x_dtype != TBIK_F32 && x_dtype != TBIK_BF16) return TBIK_ERR_DTYPE;

@@ -22,6 +22,18 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 }
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) { return pack_bf16x2(f, 0.0f) & 0xffffu; }
 
+// T over P = 2^t values held in registers, in the order of Alg. 2's reduce phase: at level l, value r
+// (r mod 2^(l+1) == 0) receives value r + 2^l.  The array is used as scratch.
+template <int P>
+__device__ __forceinline__ float tree_of(float (&v)[P]) {
+#pragma unroll
+    for (int s = 1; s < P; s *= 2) {
+#pragma unroll
+        for (int r = 0; r < P; r += 2 * s) v[r] = v[r] + v[r + s];
+    }
+    return v[0];
+}
+
 // Streaming evaluation of the tree operator T (App. C) by the carry-over scheme of App. D.1:
 // values arrive in index order; slot l holds a finished subtree of 2^l values that waits for its
 // right sibling.  push(v, idx) folds value number idx in and returns the running value, which after

@@ -38,6 +38,8 @@ hipError_t launch_tree_combine(const float *partials, int P, void *Y, int64_t ld
                                hipStream_t s);
 
 hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int M, int H, float eps, hipStream_t s);
+hipError_t launch_combine_residual_rmsnorm(const float *partials, int P, const uint16_t *res, const uint16_t *w,
+                                           uint16_t *hidden, uint16_t *normed, int M, int H, float eps, hipStream_t s);
 
 size_t row_reduce_workspace(int M, int64_t V, int x_dtype, int op);
 hipError_t launch_row_reduce(const void *x, int x_dtype, void *out, int op, int M, int64_t V, void *ws, hipStream_t s);

@@ -120,3 +120,19 @@ def test_product_path_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "tbik_oracle" not in text and "from oracle" not in text and "import oracle" not in text, f
+
+
+def test_fused_tail_argument_validation(L):
+    f = L.tbik_combine_residual_rmsnorm
+    ok = (GOOD, 2, GOOD, GOOD, 1e-6, GOOD + 0x10000, GOOD + 0x20000, 4, 4096, None)
+    def call(**kw):
+        names = ("partials", "P", "residual", "weight", "eps", "hidden", "normed", "M", "H", "stream")
+        a = dict(zip(names, ok)); a.update(kw)
+        return f(*[a[n] for n in names])
+    assert call(M=0) == 0
+    assert call(partials=None) == 1 and call(normed=None) == 1
+    assert call(H=4100) == 2 and call(M=-1) == 2
+    assert call(P=3) == 3 and call(P=0) == 3
+    assert call(P=32) == 7                                   # legal shard count, not built into the fused kernel
+    assert call(residual=GOOD + 2) == 5
+    assert call(normed=GOOD, residual=GOOD) == 2             # normed may not share the residual's buffer

@@ -197,3 +197,51 @@ def test_logsoftmax_512_rows_sampled():
     assert np.max(np.abs(got - want) / np.maximum(1.0, np.abs(want))) <= 1e-5
     one = tb.tbik_row_reduce(xd[200:201].contiguous(), tb.TBIK_LOGSOFTMAX)
     assert torch.equal(one.view(torch.int32), o[200:201].view(torch.int32))
+
+
+# ----------------------------------------------------------------------------- fused tail: combine + residual + RMSNorm
+
+@pytest.mark.parametrize("P,M,H", [(1, 5, 4096), (2, 33, 5120), (4, 64, 4096), (8, 7, 24), (16, 3, 1000), (8, 130, 8192),
+                                   (8, 1100, 4096)])          # the last one is large enough for the three-kernel route
+def test_fused_tail_equals_the_three_steps_and_the_oracle(P, M, H):
+    """tbik_combine_residual_rmsnorm against (a) tbik_tree_combine -> bf16 add -> tbik_rmsnorm on the GPU and (b) the
+    oracle's step-by-step definition: bit for bit, also when the hidden state is updated in place."""
+    rng = np.random.Generator(np.random.PCG64(100 + P + H))
+    parts = (rng.standard_normal((P, M, H), dtype=np.float32) * np.float32(1.0 / np.sqrt(P)))
+    res_b = syn.normal_bf16(rng, (M, H), 1.0)
+    w_b = syn.normal_bf16(rng, (H,), 0.1, mean=1.0)
+    pd = torch.from_numpy(parts).to("cuda:0")
+    rd, wd = gu.dev_bf16(res_b), gu.dev_bf16(w_b)
+
+    hid, out = tb.tbik_combine_residual_rmsnorm(pd, rd, wd, 1e-6)
+    y = tb.tbik_tree_combine(pd, out_dtype=torch.bfloat16)
+    hid3 = (y.float() + rd.float()).to(torch.bfloat16)                  # fp32 add, one RNE rounding
+    out3 = tb.tbik_rmsnorm(hid3, wd, 1e-6)
+    assert torch.equal(hid.view(torch.int16), hid3.view(torch.int16))
+    assert torch.equal(out.view(torch.int16), out3.view(torch.int16))
+
+    if M * H <= 300000:
+        hid_o, out_o = orc.combine_residual_rmsnorm(parts, res_b, w_b, 1e-6)
+        assert np.array_equal(gu.host_bf16_bits(hid), hid_o)
+        assert np.array_equal(gu.host_bf16_bits(out), out_o)
+
+    inplace = rd.clone()
+    hid2, out2 = tb.tbik_combine_residual_rmsnorm(pd, inplace, wd, 1e-6, hidden=inplace)
+    assert hid2.data_ptr() == inplace.data_ptr()
+    assert torch.equal(inplace.view(torch.int16), hid.view(torch.int16))
+    assert torch.equal(out2.view(torch.int16), out.view(torch.int16))
+    # a row alone gives the same bits
+    h1, o1 = tb.tbik_combine_residual_rmsnorm(pd[:, M - 1:M].contiguous(), rd[M - 1:M].contiguous(), wd, 1e-6)
+    assert torch.equal(o1.view(torch.int16), out[M - 1:M].view(torch.int16))
+
+
+def test_fused_tail_hand_value():
+    H = 8
+    parts = np.zeros((2, 1, H), dtype=np.float32)
+    parts[0, 0, :] = 1.0
+    parts[1, 0, :] = 2.0 ** -8 + 2.0 ** -12
+    res = np.full((1, H), 0x3B80, dtype=np.uint16)
+    w = np.full((H,), 0x3F80, dtype=np.uint16)
+    hid, out = tb.tbik_combine_residual_rmsnorm(torch.from_numpy(parts).to("cuda:0"), gu.dev_bf16(res), gu.dev_bf16(w), 0.0)
+    assert np.all(gu.host_bf16_bits(hid) == 0x3F82)
+    assert np.all(gu.host_bf16_bits(out) == 0x3F80)

@@ -166,3 +166,21 @@ def test_logsoftmax_rows_independent_of_batch():
     full = orc.row_logsoftmax(x)
     assert np.array_equal(u32(orc.row_logsoftmax(x[2:3])), u32(full[2:3]))
     assert np.array_equal(u32(orc.row_logsoftmax(x[::-1].copy())), u32(full[::-1]))
+
+
+def test_fused_tail_rounds_the_combined_value_before_the_residual_add():
+    """Y = 1 + 2^-8 + 2^-12 rounds to bf16 1 + 2^-7; adding R = 2^-8 gives the tie 1 + 2^-7 + 2^-8, which goes to the
+    even neighbour 1 + 2^-6 (0x3F82).  One rounding of Y + R = 1 + 2^-7 + 2^-12 would give 1 + 2^-7 (0x3F81) instead."""
+    H = 8
+    parts = np.zeros((2, 1, H), dtype=np.float32)
+    parts[0, 0, :] = 1.0
+    parts[1, 0, :] = 2.0 ** -8 + 2.0 ** -12
+    res = np.full((1, H), 0x3B80, dtype=np.uint16)             # bf16 2^-8
+    w = np.full((H,), 0x3F80, dtype=np.uint16)                 # bf16 1.0
+    hid, out = orc.combine_residual_rmsnorm(parts, res, w, eps=0.0)
+    assert np.all(hid == 0x3F82)
+    # every element equal: x / sqrt(x^2) = 1 exactly or within one rounding; here ss/H = x^2 exactly, so 1.0
+    assert np.all(out == 0x3F80)
+    # the pieces are the public ones: same result as calling them one after the other
+    _, ybf = orc.tree_combine(parts)
+    assert np.all(ybf == 0x3F81)
