@@ -65,6 +65,47 @@ static uint16_t f32_to_bf16(float f) {
 uint16_t tbik_oracle_f32_to_bf16(float f) { return f32_to_bf16(f); }
 float tbik_oracle_bf16_to_f32(uint16_t h) { return bf16_to_f32(h); }
 
+/* ------------------------------------------------------------------ fp16 (IEEE binary16) */
+
+/* binary16 -> binary32, exact: 1 sign, 5 exponent (bias 15), 10 fraction bits; subnormals are f * 2^-24. */
+static float f16_to_f32(uint16_t h) {
+    const int sign = h >> 15, e = (h >> 10) & 31, f = h & 1023;
+    float v;
+    if (e == 0) v = ldexpf((float)f, -24);
+    else if (e == 31) v = f ? NAN : INFINITY;
+    else v = ldexpf((float)(1024 + f), e - 25);
+    return sign ? -v : v;
+}
+
+/* binary32 -> binary16, round to nearest, ties to even; overflow goes to infinity, the subnormal
+ * range rounds on the fixed grid of 2^-24.  Written on the value, not on the bit pattern: the
+ * number of half-precision grid steps is formed exactly and rounded once by nearbyintf (which
+ * rounds ties to even under the default rounding mode). */
+static uint16_t f32_to_f16(float x) {
+    const uint16_t sign = signbit(x) ? 0x8000u : 0u;
+    if (isnan(x)) return (uint16_t)(sign | 0x7e00u);
+    float a = fabsf(x);
+    if (isinf(a)) return (uint16_t)(sign | 0x7c00u);
+    int ex;
+    (void)frexpf(a, &ex);                       /* a = m * 2^ex, m in [0.5, 1)  ->  exponent of a is ex - 1 */
+    int e = (a == 0.0f) ? -14 : ex - 1;
+    if (e < -14) e = -14;                       /* subnormal range shares the grid of the smallest normal binade */
+    const float steps = nearbyintf(ldexpf(a, 10 - e));     /* exact scaling, one rounding; in [0, 2048] */
+    long n = (long)steps;
+    if (n == 2048) { n = 1024; ++e; }           /* rounded up into the next binade */
+    if (e > 15) return (uint16_t)(sign | 0x7c00u);
+    if (n < 1024) return (uint16_t)(sign | (uint16_t)n);                 /* subnormal or zero (e == -14) */
+    return (uint16_t)(sign | (uint16_t)((e + 15) << 10) | (uint16_t)(n - 1024));
+}
+
+uint16_t tbik_oracle_f32_to_f16(float f) { return f32_to_f16(f); }
+float tbik_oracle_f16_to_f32(uint16_t h) { return f16_to_f32(h); }
+
+/* Storage formats of 16-bit operands and outputs (Table "Block size setting for TBIK" lists both). */
+enum { FMT_BF16 = 0, FMT_F16 = 1 };
+static float widen16(uint16_t h, int fmt) { return fmt == FMT_F16 ? f16_to_f32(h) : bf16_to_f32(h); }
+static uint16_t round16(float f, int fmt) { return fmt == FMT_F16 ? f32_to_f16(f) : f32_to_bf16(f); }
+
 static int is_pow2(long n) { return n >= 1 && (n & (n - 1)) == 0; }
 
 /* ------------------------------------------------------------------ the tree */
@@ -184,12 +225,12 @@ static float combine_superleaves(const float *s, long ns, int evaluator, int P, 
 /*
  * One output element, written as plainly as possible (Sec. 3.3 for the sum
  * over k; Sec. 4.2 / App. D.1 for leaves and K_first):
- *   p_k  = x[m,k] * w[k,n]                 (exact in fp32 for bf16 operands)
+ *   p_k  = x[m,k] * w[k,n]                 (exact in fp32: 8- or 11-bit significands, exponents in range)
  *   s_j  = ((+0 + p_a) + p_{a+1}) + ...    over superleaf j = leaf*k_first consecutive k
  *   y    = T(s_0 .. s_{n_s-1})
  */
 float tbik_oracle_gemm_element(const uint16_t *X, long ldx, const uint16_t *W, long ldw,
-                               long m, long n, int K, int leaf, int k_first, int evaluator, int P) {
+                               long m, long n, int K, int leaf, int k_first, int evaluator, int P, int fmt) {
     long ns = superleaf_count(K, leaf, k_first, P);
     if (ns < 0) return NAN;
     long sl = (long)leaf * k_first;
@@ -197,7 +238,7 @@ float tbik_oracle_gemm_element(const uint16_t *X, long ldx, const uint16_t *W, l
     for (long j = 0; j < ns; ++j) {
         float acc = 0.0f;
         for (long k = j * sl; k < (j + 1) * sl; ++k) {
-            float p = bf16_to_f32(X[m * ldx + k]) * bf16_to_f32(W[k * ldw + n]);
+            float p = widen16(X[m * ldx + k], fmt) * widen16(W[k * ldw + n], fmt);
             acc = acc + p;
         }
         s[j] = acc;
@@ -215,7 +256,7 @@ float tbik_oracle_gemm_element(const uint16_t *X, long ldx, const uint16_t *W, l
  * (l >= 1) hold a finished subtree of 2^(l-1) superleaves.
  */
 float tbik_oracle_gemm_element_alg1(const uint16_t *X, long ldx, const uint16_t *W, long ldw,
-                                    long m, long n, int K, int leaf, int k_first) {
+                                    long m, long n, int K, int leaf, int k_first, int fmt) {
     long ns = superleaf_count(K, leaf, k_first, 1);
     if (ns < 0) return NAN;
     const long T = K / leaf;
@@ -226,7 +267,7 @@ float tbik_oracle_gemm_element_alg1(const uint16_t *X, long ldx, const uint16_t 
     int tiles_in_acc = 0;
     for (long t = 0; t < T; ++t) {
         for (long k = t * leaf; k < (t + 1) * leaf; ++k) {        /* acc <- acc + A_t B_t */
-            float p = bf16_to_f32(X[m * ldx + k]) * bf16_to_f32(W[k * ldw + n]);
+            float p = widen16(X[m * ldx + k], fmt) * widen16(W[k * ldw + n], fmt);
             acc = acc + p;
         }
         if (++tiles_in_acc < k_first) continue;                   /* level 0 not full yet */
@@ -250,11 +291,11 @@ float tbik_oracle_gemm_element_alg1(const uint16_t *X, long ldx, const uint16_t 
 /* A list of elements (spot checks at big shapes). */
 int tbik_oracle_gemm_elements(const uint16_t *X, long ldx, const uint16_t *W, long ldw,
                               const int64_t *rows, const int64_t *cols, long count,
-                              int K, int leaf, int k_first, int evaluator, int P, float *out) {
+                              int K, int leaf, int k_first, int evaluator, int P, int fmt, float *out) {
     if (superleaf_count(K, leaf, k_first, P) < 0) return -1;
 #pragma omp parallel for schedule(dynamic, 16)
     for (long i = 0; i < count; ++i)
-        out[i] = tbik_oracle_gemm_element(X, ldx, W, ldw, rows[i], cols[i], K, leaf, k_first, evaluator, P);
+        out[i] = tbik_oracle_gemm_element(X, ldx, W, ldw, rows[i], cols[i], K, leaf, k_first, evaluator, P, fmt);
     return 0;
 }
 
@@ -265,12 +306,12 @@ int tbik_oracle_gemm_elements(const uint16_t *X, long ldx, const uint16_t *W, lo
  * sequence of additions untouched and lets the compiler use SIMD across
  * independent elements.  Parallel over (row, column block) only.
  *   Y32  [M,ldy] fp32 result (may be NULL)
- *   Ybf  [M,ldy] bf16 = single RNE rounding of the fp32 result (may be NULL)
+ *   Ybf  [M,ldy] 16-bit output in the operands' format = single RNE rounding of the fp32 result (may be NULL)
  *   partials [P,M,N] fp32 per-shard subtree sums, only for EVAL_SHARDED (may be NULL)
  */
 int tbik_oracle_gemm(const uint16_t *X, long ldx, const uint16_t *W, long ldw,
                      float *Y32, uint16_t *Ybf, long ldy, int M, int N, int K,
-                     int leaf, int k_first, int evaluator, int P, float *partials) {
+                     int leaf, int k_first, int evaluator, int P, int fmt, float *partials) {
     long ns = superleaf_count(K, leaf, k_first, P);
     if (ns < 0) return -1;
     if (M <= 0 || N <= 0) return 0;
@@ -291,10 +332,10 @@ int tbik_oracle_gemm(const uint16_t *X, long ldx, const uint16_t *W, long ldw,
                     float *acc = S + j * NB;
                     for (int c = 0; c < nb; ++c) acc[c] = 0.0f;
                     for (long k = j * sl; k < (j + 1) * sl; ++k) {
-                        const float xv = bf16_to_f32(X[m * ldx + k]);
+                        const float xv = widen16(X[m * ldx + k], fmt);
                         const uint16_t *wrow = W + k * ldw + n0;
                         for (int c = 0; c < nb; ++c) {
-                            float p = xv * bf16_to_f32(wrow[c]);
+                            float p = xv * widen16(wrow[c], fmt);
                             acc[c] = acc[c] + p;
                         }
                     }
@@ -303,7 +344,7 @@ int tbik_oracle_gemm(const uint16_t *X, long ldx, const uint16_t *W, long ldw,
                     for (long j = 0; j < ns; ++j) col[j] = S[j * NB + c];
                     float y = combine_superleaves(col, ns, evaluator, P, part);
                     if (Y32) Y32[m * ldy + n0 + c] = y;
-                    if (Ybf) Ybf[m * ldy + n0 + c] = f32_to_bf16(y);
+                    if (Ybf) Ybf[m * ldy + n0 + c] = round16(y, fmt);
                     if (partials && evaluator == EVAL_SHARDED)
                         for (int p = 0; p < P; ++p)
                             partials[((size_t)p * M + m) * N + n0 + c] = part[p];
@@ -320,14 +361,14 @@ int tbik_oracle_gemm(const uint16_t *X, long ldx, const uint16_t *W, long ldw,
  * Top-of-tree combine on its own (Alg. 2's reduce phase applied to P partial
  * tensors [P][count], followed by the one rounding to the output type).
  */
-int tbik_oracle_tree_combine(const float *partials, int P, long count, float *Y32, uint16_t *Ybf) {
+int tbik_oracle_tree_combine(const float *partials, int P, long count, float *Y32, uint16_t *Ybf, int fmt) {
     if (!is_pow2(P) || P > 64) return -1;
     float bufs[64];
     for (long i = 0; i < count; ++i) {
         for (int p = 0; p < P; ++p) bufs[p] = partials[(size_t)p * count + i];
         tbik_oracle_allreduce(bufs, P, 1);
         if (Y32) Y32[i] = bufs[0];
-        if (Ybf) Ybf[i] = f32_to_bf16(bufs[0]);
+        if (Ybf) Ybf[i] = round16(bufs[0], fmt);
     }
     return 0;
 }

@@ -1,8 +1,8 @@
 """Python face of the CPU oracle (TEST INFRASTRUCTURE ONLY).
 
 Loads ``oracle/libtbik_oracle.so`` (plain C, ``oracle/tbik_oracle.c``; compiled
-on demand with gcc) and exposes its functions on numpy arrays.  bf16 tensors are
-``uint16`` bit patterns.  Nothing here touches a GPU or the HIP library, and the
+on demand with gcc) and exposes its functions on numpy arrays.  bf16 and fp16 tensors
+are ``uint16`` bit patterns.  Nothing here touches a GPU or the HIP library, and the
 HIP path never imports this module: only tests, the smoke check and the
 benchmark's CPU-baseline leg do.
 
@@ -23,6 +23,9 @@ _SRC = os.path.join(_HERE, "tbik_oracle.c")
 _LIB = os.path.join(_HERE, "libtbik_oracle.so")
 
 EVAL_RECURSIVE, EVAL_COUNTER, EVAL_SHARDED = 0, 1, 2
+
+# 16-bit storage formats of GEMM operands and outputs (values of the C side's enum).
+FORMATS = {"bf16": 0, "fp16": 1}
 
 # Leaf sizes of the row reductions: one 16-byte chunk of the row per leaf.
 LEAF_BF16 = 8
@@ -54,18 +57,18 @@ def lib():
         L.tbik_oracle_allreduce.argtypes = [f32p, C.c_int, C.c_long]
         L.tbik_oracle_gemm_element.restype = C.c_float
         L.tbik_oracle_gemm_element.argtypes = [u16p, C.c_long, u16p, C.c_long, C.c_long, C.c_long,
-                                               C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]
+                                               C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]
         L.tbik_oracle_gemm_element_alg1.restype = C.c_float
         L.tbik_oracle_gemm_element_alg1.argtypes = [u16p, C.c_long, u16p, C.c_long, C.c_long, C.c_long,
-                                                    C.c_int, C.c_int, C.c_int]
+                                                    C.c_int, C.c_int, C.c_int, C.c_int]
         L.tbik_oracle_gemm_elements.restype = C.c_int
         L.tbik_oracle_gemm_elements.argtypes = [u16p, C.c_long, u16p, C.c_long, i64p, i64p, C.c_long,
-                                                C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f32p]
+                                                C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f32p]
         L.tbik_oracle_gemm.restype = C.c_int
         L.tbik_oracle_gemm.argtypes = [u16p, C.c_long, u16p, C.c_long, f32p, u16p, C.c_long,
-                                       C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f32p]
+                                       C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f32p]
         L.tbik_oracle_tree_combine.restype = C.c_int
-        L.tbik_oracle_tree_combine.argtypes = [f32p, C.c_int, C.c_long, f32p, u16p]
+        L.tbik_oracle_tree_combine.argtypes = [f32p, C.c_int, C.c_long, f32p, u16p, C.c_int]
         L.tbik_oracle_treesum.restype = C.c_float
         L.tbik_oracle_treesum.argtypes = [f32p, C.c_long, C.c_int]
         L.tbik_oracle_rmsnorm.restype = C.c_int
@@ -80,6 +83,10 @@ def lib():
         L.tbik_oracle_row_logsoftmax.argtypes = [f32p, f32p, C.c_int, C.c_long, C.c_int]
         L.tbik_oracle_f32_to_bf16.restype = C.c_uint16
         L.tbik_oracle_f32_to_bf16.argtypes = [C.c_float]
+        L.tbik_oracle_f32_to_f16.restype = C.c_uint16
+        L.tbik_oracle_f32_to_f16.argtypes = [C.c_float]
+        L.tbik_oracle_f16_to_f32.restype = C.c_float
+        L.tbik_oracle_f16_to_f32.argtypes = [C.c_uint16]
         _lib = L
     return _lib
 
@@ -139,8 +146,9 @@ def allreduce(bufs: np.ndarray) -> np.ndarray:
 # ------------------------------------------------------------------ GEMM
 
 def gemm(X, W, leaf: int, k_first: int = 1, evaluator: int = EVAL_RECURSIVE, P: int = 1,
-         want_partials: bool = False):
-    """Y = X W in the tree order.  Returns (Y fp32 [M,N], Y bf16 bits [M,N][, partials [P,M,N])."""
+         want_partials: bool = False, fmt: str = "bf16"):
+    """Y = X W in the tree order.  X, W are 16-bit patterns in format `fmt` ("bf16" or "fp16").
+    Returns (Y fp32 [M,N], Y 16-bit patterns in `fmt` [M,N][, partials [P,M,N])."""
     X, xp = _u16(X)
     W, wp = _u16(W)
     M, K = X.shape
@@ -151,7 +159,7 @@ def gemm(X, W, leaf: int, k_first: int = 1, evaluator: int = EVAL_RECURSIVE, P: 
     parts = np.zeros((P, M, N), dtype=np.float32) if want_partials else None
     rc = lib().tbik_oracle_gemm(xp, K, wp, N, Y32.ctypes.data_as(C.POINTER(C.c_float)),
                                 Ybf.ctypes.data_as(C.POINTER(C.c_uint16)), N, M, N, K, leaf, k_first,
-                                evaluator, P,
+                                evaluator, P, FORMATS[fmt],
                                 parts.ctypes.data_as(C.POINTER(C.c_float)) if want_partials else None)
     if rc != 0:
         raise ValueError("oracle gemm: illegal tree parameters (K, leaf, k_first, P)")
@@ -159,22 +167,22 @@ def gemm(X, W, leaf: int, k_first: int = 1, evaluator: int = EVAL_RECURSIVE, P: 
 
 
 def gemm_element(X, W, m: int, n: int, leaf: int, k_first: int = 1, evaluator: int = EVAL_RECURSIVE,
-                 P: int = 1) -> np.float32:
+                 P: int = 1, fmt: str = "bf16") -> np.float32:
     X, xp = _u16(X)
     W, wp = _u16(W)
     return np.float32(lib().tbik_oracle_gemm_element(xp, X.shape[1], wp, W.shape[1], m, n, X.shape[1],
-                                                     leaf, k_first, evaluator, P))
+                                                     leaf, k_first, evaluator, P, FORMATS[fmt]))
 
 
-def gemm_element_alg1(X, W, m: int, n: int, leaf: int, k_first: int = 1) -> np.float32:
+def gemm_element_alg1(X, W, m: int, n: int, leaf: int, k_first: int = 1, fmt: str = "bf16") -> np.float32:
     X, xp = _u16(X)
     W, wp = _u16(W)
     return np.float32(lib().tbik_oracle_gemm_element_alg1(xp, X.shape[1], wp, W.shape[1], m, n,
-                                                          X.shape[1], leaf, k_first))
+                                                          X.shape[1], leaf, k_first, FORMATS[fmt]))
 
 
 def gemm_elements(X, W, rows, cols, leaf: int, k_first: int = 1, evaluator: int = EVAL_RECURSIVE,
-                  P: int = 1) -> np.ndarray:
+                  P: int = 1, fmt: str = "bf16") -> np.ndarray:
     """fp32 results at the listed (row, col) positions."""
     X, xp = _u16(X)
     W, wp = _u16(W)
@@ -182,22 +190,22 @@ def gemm_elements(X, W, rows, cols, leaf: int, k_first: int = 1, evaluator: int 
     cols, cp = _i64(cols)
     out = np.empty(rows.size, dtype=np.float32)
     rc = lib().tbik_oracle_gemm_elements(xp, X.shape[1], wp, W.shape[1], rp, cp, rows.size, X.shape[1],
-                                         leaf, k_first, evaluator, P,
+                                         leaf, k_first, evaluator, P, FORMATS[fmt],
                                          out.ctypes.data_as(C.POINTER(C.c_float)))
     if rc != 0:
         raise ValueError("oracle gemm: illegal tree parameters (K, leaf, k_first, P)")
     return out
 
 
-def tree_combine(partials: np.ndarray):
-    """Top-of-tree combine of [P, ...] fp32 partials: (Y fp32, Y bf16 bits), shaped like partials[0]."""
+def tree_combine(partials: np.ndarray, fmt: str = "bf16"):
+    """Top-of-tree combine of [P, ...] fp32 partials: (Y fp32, Y 16-bit patterns in `fmt`), shaped like partials[0]."""
     a, p = _f32(partials)
     P = a.shape[0]
     count = int(np.prod(a.shape[1:]))
     Y32 = np.empty(a.shape[1:], dtype=np.float32)
     Ybf = np.empty(a.shape[1:], dtype=np.uint16)
     rc = lib().tbik_oracle_tree_combine(p, P, count, Y32.ctypes.data_as(C.POINTER(C.c_float)),
-                                        Ybf.ctypes.data_as(C.POINTER(C.c_uint16)))
+                                        Ybf.ctypes.data_as(C.POINTER(C.c_uint16)), FORMATS[fmt])
     if rc != 0:
         raise ValueError("oracle tree_combine: P must be a power of two <= 64")
     return Y32, Ybf
@@ -208,6 +216,20 @@ def f32_to_bf16_bits(a) -> np.ndarray:
     a = np.ascontiguousarray(a, dtype=np.float32)
     f = lib().tbik_oracle_f32_to_bf16
     return np.array([f(float(v)) for v in a.ravel()], dtype=np.uint16).reshape(a.shape)
+
+
+def f32_to_f16_bits(a) -> np.ndarray:
+    """fp32 -> IEEE binary16 patterns by the oracle's own rounding routine (RNE), elementwise."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    f = lib().tbik_oracle_f32_to_f16
+    return np.array([f(float(v)) for v in a.ravel()], dtype=np.uint16).reshape(a.shape)
+
+
+def f16_bits_to_f32(h) -> np.ndarray:
+    """IEEE binary16 patterns -> fp32 by the oracle's own widening routine, elementwise."""
+    h = np.ascontiguousarray(h, dtype=np.uint16)
+    f = lib().tbik_oracle_f16_to_f32
+    return np.array([f(int(v)) for v in h.ravel()], dtype=np.float32).reshape(h.shape)
 
 
 # ------------------------------------------------------------------ row reductions

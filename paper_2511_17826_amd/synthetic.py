@@ -34,14 +34,42 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
+def f32_to_f16_bits(a: np.ndarray) -> np.ndarray:
+    """Round fp32 values to IEEE binary16 storage (numpy's cast: round-to-nearest-even), as uint16 bit patterns."""
+    return np.ascontiguousarray(a, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def f16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Widen binary16 bit patterns (uint16) to the fp32 values they denote (exact)."""
+    return np.ascontiguousarray(b, dtype=np.uint16).view(np.float16).astype(np.float32)
+
+
+def to_storage(a: np.ndarray, fmt: str = "bf16") -> np.ndarray:
+    """fp32 values -> 16-bit storage patterns of format ``fmt`` ("bf16" or "fp16")."""
+    if fmt == "bf16":
+        return f32_to_bf16_bits(a)
+    if fmt == "fp16":
+        return f32_to_f16_bits(a)
+    raise ValueError(fmt)
+
+
+def from_storage(b: np.ndarray, fmt: str = "bf16") -> np.ndarray:
+    """16-bit storage patterns of format ``fmt`` -> the fp32 values they denote (exact)."""
+    if fmt == "bf16":
+        return bf16_bits_to_f32(b)
+    if fmt == "fp16":
+        return f16_bits_to_f32(b)
+    raise ValueError(fmt)
+
+
 def _rng(seed: int) -> np.random.Generator:
     return np.random.Generator(np.random.PCG64(seed))
 
 
-def normal_bf16(rng: np.random.Generator, shape, std: float, mean: float = 0.0) -> np.ndarray:
-    """N(mean, std) drawn in fp32, stored as bf16 bits."""
+def normal_bf16(rng: np.random.Generator, shape, std: float, mean: float = 0.0, fmt: str = "bf16") -> np.ndarray:
+    """N(mean, std) drawn in fp32, stored as bf16 bits (or, with ``fmt="fp16"``, as binary16 bits)."""
     v = rng.standard_normal(size=shape, dtype=np.float32) * np.float32(std) + np.float32(mean)
-    return f32_to_bf16_bits(v)
+    return to_storage(v, fmt)
 
 
 # ----------------------------------------------------------------------------
@@ -58,15 +86,16 @@ def gemm_tiny(seed: int = 0):
     return dict(X=X, W=W, M=4, K=512, N=256, leaf=64, k_first=1)
 
 
-def gemm_oproj(M: int = 4096, seed: int = 1, K: int = 4096, N: int = 4096, leaf: int = 256, k_first: int = 1):
+def gemm_oproj(M: int = 4096, seed: int = 1, K: int = 4096, N: int = 4096, leaf: int = 256, k_first: int = 1,
+               fmt: str = "bf16"):
     """8B-class attention output projection: X [M,4096] ~ N(0,1), W [4096,4096] ~ N(0,0.02).
 
     The tensor is always drawn at M_max=4096 rows and the first M rows are
     returned, so row r holds the same bits for every M.
     """
     rng = _rng(seed)
-    X = normal_bf16(rng, (4096, K), 1.0)[:M]
-    W = normal_bf16(rng, (K, N), 0.02)
+    X = normal_bf16(rng, (4096, K), 1.0, fmt=fmt)[:M]
+    W = normal_bf16(rng, (K, N), 0.02, fmt=fmt)
     return dict(X=np.ascontiguousarray(X), W=W, M=M, K=K, N=N, leaf=leaf, k_first=k_first)
 
 
@@ -88,13 +117,13 @@ def gemm_downproj(M: int = 4096, seed: int = 2, K: int = 12288, N: int = 4096, l
     return dict(X=np.ascontiguousarray(X), W=W, M=M, K=K, N=N, leaf=leaf, k_first=k_first)
 
 
-def gemm_random(seed: int, M: int, K: int, N: int, x_std: float = 1.0, w_std: float = 0.02):
+def gemm_random(seed: int, M: int, K: int, N: int, x_std: float = 1.0, w_std: float = 0.02, fmt: str = "bf16"):
     """Generic random GEMM operands of the same distributions, any shape."""
     rng = _rng(seed)
-    return normal_bf16(rng, (M, K), x_std), normal_bf16(rng, (K, N), w_std)
+    return normal_bf16(rng, (M, K), x_std, fmt=fmt), normal_bf16(rng, (K, N), w_std, fmt=fmt)
 
 
-def gemm_small_integers(seed: int, M: int, K: int, N: int, mag: int = 8):
+def gemm_small_integers(seed: int, M: int, K: int, N: int, mag: int = 8, fmt: str = "bf16"):
     """Integer-valued operands with |x|,|w| <= mag.
 
     Every partial sum stays far below 2**24, so any summation order gives the
@@ -103,10 +132,10 @@ def gemm_small_integers(seed: int, M: int, K: int, N: int, mag: int = 8):
     rng = _rng(seed)
     X = rng.integers(-mag, mag + 1, size=(M, K)).astype(np.float32)
     W = rng.integers(-mag, mag + 1, size=(K, N)).astype(np.float32)
-    return f32_to_bf16_bits(X), f32_to_bf16_bits(W)
+    return to_storage(X, fmt), to_storage(W, fmt)
 
 
-def gemm_leaf_sparse(seed: int, M: int, K: int, N: int, superleaf: int, exp_spread: int = 12):
+def gemm_leaf_sparse(seed: int, M: int, K: int, N: int, superleaf: int, exp_spread: int = 12, fmt: str = "bf16"):
     """Operands with exactly one non-zero product per (row, column, superleaf).
 
     In every superleaf (``superleaf`` consecutive k) X has one non-zero column
@@ -115,6 +144,8 @@ def gemm_leaf_sparse(seed: int, M: int, K: int, N: int, superleaf: int, exp_spre
     the order inside the leaf, and only the tree between superleaves rounds.
     Magnitudes are random bf16 values scaled by 2**e, e uniform in
     [-exp_spread, exp_spread], which makes the tree's roundings visible.
+    (binary16 storage has a 5-bit exponent: use exp_spread <= 6 with ``fmt="fp16"``
+    to keep every value a normal number.)
     """
     assert K % superleaf == 0
     rng = _rng(seed)
@@ -128,7 +159,7 @@ def gemm_leaf_sparse(seed: int, M: int, K: int, N: int, superleaf: int, exp_spre
             rng.integers(-exp_spread, exp_spread + 1, size=M)).astype(np.float32)
         W[k, :] = rng.standard_normal(N).astype(np.float32) * np.exp2(
             rng.integers(-exp_spread, exp_spread + 1, size=N)).astype(np.float32)
-    return f32_to_bf16_bits(X), f32_to_bf16_bits(W)
+    return to_storage(X, fmt), to_storage(W, fmt)
 
 
 # ----------------------------------------------------------------------------

@@ -1,0 +1,165 @@
+"""Pins for the oracle's fp16 (IEEE binary16) operand format (CPU only).
+
+The paper's kernel table lists FP16 beside BF16 with the same block sizes, and the method itself
+(Sec. 4.2, App. C, App. D.1) does not depend on the storage format: operands are widened exactly,
+products and sums are fp32, the output is rounded once.  What is format-specific is the widening
+and the final rounding, pinned here against numpy's float16 (an independent implementation of the
+IEEE format), and the GEMM is pinned again with values that only binary16 can hold.
+"""
+import numpy as np
+import pytest
+
+from oracle import tbik_oracle as orc
+from paper_2511_17826_amd import synthetic as syn
+
+U = 2.0 ** -24
+
+
+def u32(a):
+    return np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+
+
+# ----------------------------------------------------------------------------- the format itself
+
+def test_widening_matches_numpy_on_every_pattern():
+    h = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    mine = orc.f16_bits_to_f32(h)
+    ref = h.view(np.float16).astype(np.float32)
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(mine), nan)
+    assert np.array_equal(u32(mine[~nan]), u32(ref[~nan]))          # includes -0, subnormals, infinities
+
+
+def _rounding_cases():
+    h = np.arange(0x7C00, dtype=np.uint32).astype(np.uint16)        # every finite non-negative half
+    v = h.view(np.float16).astype(np.float32)
+    mid = (v[:-1].astype(np.float64) + v[1:].astype(np.float64)) / 2   # exact ties between neighbours (fit fp32)
+    mid = mid.astype(np.float32)
+    cases = [v, mid, np.nextafter(mid, np.float32(0)), np.nextafter(mid, np.float32(np.inf)),
+             np.nextafter(v, np.float32(np.inf)), np.nextafter(v[1:], np.float32(0))]
+    edge = np.array([65504.0, 65519.996, 65520.0, 65536.0, 1e38, np.inf, 2.0 ** -24, 2.0 ** -25,
+                     np.nextafter(np.float32(2.0 ** -25), np.float32(1)), 2.0 ** -26, 1e-45, 0.0,
+                     2.0 ** -14, np.nextafter(np.float32(2.0 ** -14), np.float32(0))], dtype=np.float32)
+    cases.append(edge)
+    rng = np.random.Generator(np.random.PCG64(11))
+    bits = rng.integers(0, 2 ** 32, size=40000, dtype=np.uint64).astype(np.uint32)
+    rnd = bits.view(np.float32)
+    cases.append(rnd[np.isfinite(rnd)])
+    cases.append((rng.standard_normal(20000) * np.exp2(rng.integers(-26, 17, size=20000))).astype(np.float32))
+    pos = np.concatenate(cases)
+    return np.concatenate([pos, -pos])
+
+
+def test_rounding_matches_numpy_ties_subnormals_overflow():
+    x = _rounding_cases()
+    with np.errstate(over="ignore"):
+        ref = x.astype(np.float16).view(np.uint16)
+    mine = orc.f32_to_f16_bits(x)
+    bad = np.nonzero(mine != ref)[0]
+    assert bad.size == 0, [(float(x[i]), hex(mine[i]), hex(ref[i])) for i in bad[:5]]
+
+
+def test_rounding_hand_values():
+    """1 + 2^-11 is a tie between 1 and 1 + 2^-10: goes to the even one (1).  1 + 3*2^-11 ties up to 1 + 2^-9."""
+    def f(v):
+        return int(orc.f32_to_f16_bits(v).ravel()[0])
+
+    assert (f(np.float32(1.0))) == 0x3C00
+    assert (f(np.float32(1.0 + 2.0 ** -11))) == 0x3C00
+    assert (f(np.float32(1.0 + 2.0 ** -11 + 2.0 ** -23))) == 0x3C01
+    assert (f(np.float32(1.0 + 3 * 2.0 ** -11))) == 0x3C02
+    assert (f(np.float32(-2.0))) == 0xC000
+    assert (f(np.float32(65520.0))) == 0x7C00                    # tie at the top rounds to infinity
+    assert (f(np.float32(2.0 ** -24))) == 0x0001                 # smallest subnormal
+    assert (f(np.float32(2.0 ** -25))) == 0x0000                 # tie with zero: even
+    assert (f(np.float32(np.nan))) & 0x7C00 == 0x7C00 and (f(np.float32(np.nan))) & 0x3FF != 0
+
+
+# ----------------------------------------------------------------------------- the GEMM on fp16 operands
+
+def test_same_bits_mean_different_numbers_in_the_two_formats():
+    """0x3C00 is 1.0 as binary16 and 2^-7 as bf16; a product of two of them tells the formats apart."""
+    K = 16
+    X = np.zeros((1, K), dtype=np.uint16)
+    W = np.zeros((K, 1), dtype=np.uint16)
+    X[0, 3] = 0x3C00
+    W[3, 0] = 0x3C00
+    y16, _ = orc.gemm(X, W, 16, 1, fmt="fp16")
+    ybf, _ = orc.gemm(X, W, 16, 1, fmt="bf16")
+    assert float(y16[0, 0]) == 1.0 and float(ybf[0, 0]) == 2.0 ** -14
+
+
+def test_products_of_eleven_bit_significands_are_exact():
+    """(1 + 2^-10)^2 = 1 + 2^-9 + 2^-20 needs 21 bits: exact in fp32, and only reachable with binary16 operands.
+    One such product per superleaf, four superleaves: T = ((p + p) + (p + p)) = 4p exactly."""
+    leaf, ns = 32, 4
+    K = leaf * ns
+    a = np.float32(1.0 + 2.0 ** -10)
+    X = np.zeros((2, K), dtype=np.float32)
+    W = np.zeros((K, 2), dtype=np.float32)
+    for j in range(ns):
+        X[:, j * leaf + 7] = a
+        W[j * leaf + 7, :] = a
+    Xh, Wh = syn.f32_to_f16_bits(X), syn.f32_to_f16_bits(W)
+    assert np.array_equal(syn.f16_bits_to_f32(Xh), X)
+    for ev, P in [(orc.EVAL_RECURSIVE, 1), (orc.EVAL_COUNTER, 1), (orc.EVAL_SHARDED, 2), (orc.EVAL_SHARDED, 4)]:
+        y32, y16 = orc.gemm(Xh, Wh, leaf, 1, ev, P, fmt="fp16")
+        assert np.all(y32 == np.float32(4.0 * (1.0 + 2.0 ** -9 + 2.0 ** -20))), (ev, P)
+        assert np.all(y16 == 0x4402)                                # 4 * (1 + 2^-9 + 2^-20) -> 4 * (1 + 2*2^-10)
+    assert float(orc.gemm_element_alg1(Xh, Wh, 1, 1, leaf, 1, fmt="fp16")) == 4.0 * (1.0 + 2.0 ** -9 + 2.0 ** -20)
+    assert float(orc.gemm_element(Xh, Wh, 0, 1, leaf, 1, fmt="fp16")) == 4.0 * (1.0 + 2.0 ** -9 + 2.0 ** -20)
+
+
+def test_subnormal_operands_are_numbers_not_zeros():
+    """2^-24 (smallest binary16 subnormal) times 2^10 is 2^-14 exactly."""
+    K = 16
+    X = np.zeros((1, K), dtype=np.uint16)
+    W = np.zeros((K, 1), dtype=np.uint16)
+    X[0, 0] = 0x0001
+    W[0, 0] = 0x6400                                                # 1024.0
+    y32, y16 = orc.gemm(X, W, 16, 1, fmt="fp16")
+    assert float(y32[0, 0]) == 2.0 ** -14 and int(y16[0, 0]) == 0x0400
+
+
+@pytest.mark.parametrize("leaf,k_first,K", [(16, 1, 256), (64, 3, 768), (32, 5, 1280)])
+def test_small_integers_against_int64(leaf, k_first, K):
+    X, W = syn.gemm_small_integers(5, 5, K, 33, fmt="fp16")
+    exact = syn.f16_bits_to_f32(X).astype(np.int64) @ syn.f16_bits_to_f32(W).astype(np.int64)
+    for ev, P in [(orc.EVAL_RECURSIVE, 1), (orc.EVAL_COUNTER, 1), (orc.EVAL_SHARDED, 2)]:
+        y32, y16 = orc.gemm(X, W, leaf, k_first, ev, P, fmt="fp16")
+        assert np.array_equal(y32.astype(np.int64), exact)
+        with np.errstate(over="ignore"):
+            assert np.array_equal(y16, exact.astype(np.float32).astype(np.float16).view(np.uint16))
+
+
+def test_fp64_brute_force_within_the_tree_bound_and_theorem_1():
+    M, K, N, leaf = 6, 1024, 40, 64
+    X, W = syn.gemm_random(21, M, K, N, fmt="fp16")
+    xf, wf = syn.f16_bits_to_f32(X).astype(np.float64), syn.f16_bits_to_f32(W).astype(np.float64)
+    exact = xf @ wf
+    mag = np.abs(xf) @ np.abs(wf)
+    y32, y16 = orc.gemm(X, W, leaf, 1, fmt="fp16")
+    depth = leaf + int(np.log2(K // leaf))                           # additions on the longest path
+    assert np.all(np.abs(y32 - exact) <= depth * U * mag * 1.01)
+    for P in (2, 4, 8, 16):
+        ys, y16s, parts = orc.gemm(X, W, leaf, 1, orc.EVAL_SHARDED, P, want_partials=True, fmt="fp16")
+        assert np.array_equal(u32(ys), u32(y32)) and np.array_equal(y16s, y16)
+        yc, y16c = orc.tree_combine(parts, fmt="fp16")
+        assert np.array_equal(u32(yc), u32(y32)) and np.array_equal(y16c, y16)
+    with np.errstate(over="ignore"):
+        assert np.array_equal(y16, y32.astype(np.float16).view(np.uint16))     # one RNE rounding of the fp32 value
+    rows, cols = np.array([0, 3, 5]), np.array([1, 39, 17])
+    assert np.array_equal(u32(orc.gemm_elements(X, W, rows, cols, leaf, 1, fmt="fp16")), u32(y32[rows, cols]))
+
+
+def test_one_superleaf_is_the_sequential_sum():
+    M, K, N = 3, 96, 5
+    X, W = syn.gemm_random(22, M, K, N, fmt="fp16")
+    xf, wf = syn.f16_bits_to_f32(X), syn.f16_bits_to_f32(W)
+    y32, _ = orc.gemm(X, W, 32, 3, fmt="fp16")
+    for m in range(M):
+        for n in range(N):
+            acc = np.float32(0)
+            for k in range(K):
+                acc = np.float32(acc + np.float32(xf[m, k] * wf[k, n]))
+            assert u32(acc) == u32(y32[m, n])
