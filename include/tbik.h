@@ -19,7 +19,7 @@
  *   - All data pointers are DEVICE pointers owned by the caller.  The library never
  *     allocates, frees or keeps device memory; scratch space is passed in as `workspace`.
  *   - Matrices are row-major; leading dimensions (ld*) are in ELEMENTS.
- *   - bf16 is the 16-bit brain-float storage format (upper half of an IEEE binary32).
+ *   - bf16 is the 16-bit brain-float storage format (upper half of an IEEE binary32); fp16 is IEEE binary16.
  *   - `hip_stream` is a hipStream_t cast to void* (NULL = the default stream).  All work is
  *     enqueued on it; no call synchronises.  Outputs are valid once the stream reaches that point.
  *   - Every call returns a tbik_status.  Arguments are validated before the first launch,
@@ -54,7 +54,7 @@ typedef enum {
     TBIK_ERR_HIP = 8          /* a HIP runtime call failed; see tbik_last_hip_error()                  */
 } tbik_status;
 
-typedef enum { TBIK_F32 = 0, TBIK_BF16 = 1 } tbik_dtype;
+typedef enum { TBIK_F32 = 0, TBIK_BF16 = 1, TBIK_F16 = 2 } tbik_dtype;
 typedef enum { TBIK_SUM = 0, TBIK_MAX = 1, TBIK_LOGSOFTMAX = 2 } tbik_rowop;
 
 #define TBIK_MAX_SHARDS 64
@@ -99,6 +99,7 @@ int tbik_gemm_shard_partials(const void *X, int64_t ldx, const void *W, int64_t 
  * rounding to y_dtype.  The partial buffers stand in for what the ranks would exchange.
  *
  *   partials   device, fp32, dense [P, M, N], 16-byte aligned     Y   device, [M, ldy], ldy >= N
+ *   y_dtype    TBIK_F32, TBIK_BF16 or TBIK_F16 (both 16-bit roundings are to nearest, ties to even)
  * Errors: NULL, SHAPE, SHARDS, DTYPE, ALIGN, HIP.
  */
 int tbik_tree_combine(const float *partials, int P, void *Y, int64_t ldy, tbik_dtype y_dtype,
@@ -164,6 +165,25 @@ size_t tbik_row_reduce_workspace_bytes(int M, int64_t V, tbik_rowop op);
 int tbik_gemm_reference(const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
                         void *Y, int64_t ldy, tbik_dtype y_dtype,
                         int M, int N, int K, int leaf, int k_first, int P, void *hip_stream);
+
+/*
+ * The same three calls for fp16 operands (the kernel table of the paper, "Block size setting for TBIK", lists FP16
+ * beside BF16 with the same blocks; Sec. 4.2, App. C and App. D.1 do not depend on the storage format):
+ * X and W hold IEEE binary16 values (subnormals included), every product is exact in fp32, the order of the
+ * fp32 additions is the one stated for tbik_gemm, and y_dtype is TBIK_F32 or TBIK_F16 (one rounding to
+ * nearest-even; overflow gives infinity).  Arguments, alignment, workspace rule (tbik_gemm_workspace_bytes),
+ * determinism contract and errors are those of tbik_gemm, tbik_gemm_shard_partials and tbik_gemm_reference;
+ * partials of fp16 operands are combined by tbik_tree_combine like any others.
+ */
+int tbik_gemm_f16(const void *X, int64_t ldx, const void *W, int64_t ldw, void *Y, int64_t ldy,
+                  tbik_dtype y_dtype, int M, int N, int K, int leaf, int k_first,
+                  void *workspace, size_t workspace_bytes, void *hip_stream);
+int tbik_gemm_shard_partials_f16(const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
+                                 int M, int N, int K, int leaf, int k_first, int P,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
+int tbik_gemm_reference_f16(const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
+                            void *Y, int64_t ldy, tbik_dtype y_dtype,
+                            int M, int N, int K, int leaf, int k_first, int P, void *hip_stream);
 
 /* Forces an internal GEMM variant (testing and tuning only; the bits never depend on it).
  * 0 = choose from the shape (default); other values are listed in tbik_variant_name(). */

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 # TBIK_LIB_PATH points development runs at an alternative build of the same library.
 LIB_PATH = os.environ.get("TBIK_LIB_PATH") or os.path.join(_HERE, "libtbik.so")
 
-TBIK_F32, TBIK_BF16 = 0, 1
+TBIK_F32, TBIK_BF16, TBIK_F16 = 0, 1, 2
 TBIK_SUM, TBIK_MAX, TBIK_LOGSOFTMAX = 0, 1, 2
 OK = 0
 
@@ -37,6 +37,13 @@ SIGNATURES = {
     "tbik_row_reduce_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int64, C.c_int]),
     "tbik_gemm_reference": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64,
                                       C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
+    "tbik_gemm_f16": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int,
+                                C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tbik_gemm_shard_partials_f16": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p,
+                                               C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                               C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tbik_gemm_reference_f16": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64,
+                                          C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
     "tbik_combine_residual_rmsnorm": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p,
                                                 C.c_int, C.c_int, C.c_void_p]),
     "tbik_set_gemm_variant": (C.c_int, [C.c_int]),
@@ -95,7 +102,9 @@ def _dt(t: torch.Tensor) -> int:
         return TBIK_F32
     if t.dtype == torch.bfloat16:
         return TBIK_BF16
-    raise TypeError("only float32 and bfloat16 tensors are supported, got %s" % t.dtype)
+    if t.dtype == torch.float16:
+        return TBIK_F16
+    raise TypeError("only float32, bfloat16 and float16 tensors are supported, got %s" % t.dtype)
 
 
 def _rowmajor(t: torch.Tensor, name: str):
@@ -120,11 +129,9 @@ def gemm_workspace_bytes(M, N, K, leaf, k_first=1) -> int:
     return int(lib().tbik_gemm_workspace_bytes(M, N, K, leaf, k_first))
 
 
-def tbik_gemm(X: torch.Tensor, W: torch.Tensor, leaf: int, k_first: int = 1, out_dtype=torch.bfloat16,
-              out: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
-    """Y = X @ W in the tree order, whole K on this device."""
+def _gemm(entry: str, in_dtype, X, W, leaf, k_first, out_dtype, out, workspace):
     _rowmajor(X, "X"); _rowmajor(W, "W")
-    assert X.dtype == torch.bfloat16 and W.dtype == torch.bfloat16
+    assert X.dtype == in_dtype and W.dtype == in_dtype
     M, K = X.shape
     K2, N = W.shape
     assert K == K2
@@ -135,19 +142,29 @@ def tbik_gemm(X: torch.Tensor, W: torch.Tensor, leaf: int, k_first: int = 1, out
         need = gemm_workspace_bytes(M, N, K, leaf, k_first)
         if need:
             workspace = _workspace(need, X.device)
-    st = lib().tbik_gemm(X.data_ptr(), X.stride(0), W.data_ptr(), W.stride(0), out.data_ptr(), out.stride(0),
-                         _dt(out), M, N, K, leaf, k_first,
-                         workspace.data_ptr() if workspace is not None else None,
-                         workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream())
-    _check(st, "tbik_gemm")
+    st = getattr(lib(), entry)(X.data_ptr(), X.stride(0), W.data_ptr(), W.stride(0), out.data_ptr(), out.stride(0),
+                               _dt(out), M, N, K, leaf, k_first,
+                               workspace.data_ptr() if workspace is not None else None,
+                               workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream())
+    _check(st, entry)
     return out
 
 
-def tbik_gemm_shard_partials(X: torch.Tensor, W: torch.Tensor, leaf: int, k_first: int, P: int,
-                             out: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
-    """partials[p] = subtree sum of K-shard p (fp32 [P, M, N])."""
+def tbik_gemm(X: torch.Tensor, W: torch.Tensor, leaf: int, k_first: int = 1, out_dtype=torch.bfloat16,
+              out: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Y = X @ W in the tree order, whole K on this device (bf16 operands)."""
+    return _gemm("tbik_gemm", torch.bfloat16, X, W, leaf, k_first, out_dtype, out, workspace)
+
+
+def tbik_gemm_f16(X: torch.Tensor, W: torch.Tensor, leaf: int, k_first: int = 1, out_dtype=torch.float16,
+                  out: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Y = X @ W in the tree order, whole K on this device (fp16 operands; fp16 or fp32 output)."""
+    return _gemm("tbik_gemm_f16", torch.float16, X, W, leaf, k_first, out_dtype, out, workspace)
+
+
+def _gemm_shard_partials(entry: str, in_dtype, X, W, leaf, k_first, P, out, workspace):
     _rowmajor(X, "X"); _rowmajor(W, "W")
-    assert X.dtype == torch.bfloat16 and W.dtype == torch.bfloat16
+    assert X.dtype == in_dtype and W.dtype == in_dtype
     M, K = X.shape
     N = W.shape[1]
     assert W.shape[0] == K
@@ -157,13 +174,25 @@ def tbik_gemm_shard_partials(X: torch.Tensor, W: torch.Tensor, leaf: int, k_firs
     need = gemm_workspace_bytes(M, N, K, leaf, k_first)
     if workspace is None and need:
         workspace = _workspace(need, X.device)
-    st = lib().tbik_gemm_shard_partials(X.data_ptr(), X.stride(0), W.data_ptr(), W.stride(0), out.data_ptr(),
-                                        M, N, K, leaf, k_first, P,
-                                        workspace.data_ptr() if workspace is not None else None,
-                                        workspace.numel() * workspace.element_size() if workspace is not None else 0,
-                                        _stream())
-    _check(st, "tbik_gemm_shard_partials")
+    st = getattr(lib(), entry)(X.data_ptr(), X.stride(0), W.data_ptr(), W.stride(0), out.data_ptr(),
+                               M, N, K, leaf, k_first, P,
+                               workspace.data_ptr() if workspace is not None else None,
+                               workspace.numel() * workspace.element_size() if workspace is not None else 0,
+                               _stream())
+    _check(st, entry)
     return out
+
+
+def tbik_gemm_shard_partials(X: torch.Tensor, W: torch.Tensor, leaf: int, k_first: int, P: int,
+                             out: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """partials[p] = subtree sum of K-shard p (fp32 [P, M, N]); bf16 operands."""
+    return _gemm_shard_partials("tbik_gemm_shard_partials", torch.bfloat16, X, W, leaf, k_first, P, out, workspace)
+
+
+def tbik_gemm_shard_partials_f16(X: torch.Tensor, W: torch.Tensor, leaf: int, k_first: int, P: int,
+                                 out: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """partials[p] = subtree sum of K-shard p (fp32 [P, M, N]); fp16 operands."""
+    return _gemm_shard_partials("tbik_gemm_shard_partials_f16", torch.float16, X, W, leaf, k_first, P, out, workspace)
 
 
 def tbik_tree_combine(partials: torch.Tensor, out_dtype=torch.bfloat16, out: torch.Tensor | None = None) -> torch.Tensor:
@@ -225,15 +254,26 @@ def tbik_row_reduce(x: torch.Tensor, op: int, out: torch.Tensor | None = None,
 def tbik_gemm_reference(X: torch.Tensor, W: torch.Tensor, leaf: int, k_first: int = 1, P: int = 1,
                         out_dtype=torch.float32):
     """The reference kernel: returns (partials [P,M,N] fp32, Y or None); Y only for P == 1."""
+    return _gemm_reference("tbik_gemm_reference", torch.bfloat16, X, W, leaf, k_first, P, out_dtype)
+
+
+def tbik_gemm_reference_f16(X: torch.Tensor, W: torch.Tensor, leaf: int, k_first: int = 1, P: int = 1,
+                            out_dtype=torch.float32):
+    """The reference kernel on fp16 operands."""
+    return _gemm_reference("tbik_gemm_reference_f16", torch.float16, X, W, leaf, k_first, P, out_dtype)
+
+
+def _gemm_reference(entry: str, in_dtype, X, W, leaf, k_first, P, out_dtype):
     _rowmajor(X, "X"); _rowmajor(W, "W")
+    assert X.dtype == in_dtype and W.dtype == in_dtype
     M, K = X.shape
     N = W.shape[1]
     parts = torch.empty((P, M, N), dtype=torch.float32, device=X.device)
     Y = torch.empty((M, N), dtype=out_dtype, device=X.device) if P == 1 else None
-    st = lib().tbik_gemm_reference(X.data_ptr(), X.stride(0), W.data_ptr(), W.stride(0), parts.data_ptr(),
-                                   Y.data_ptr() if Y is not None else None, Y.stride(0) if Y is not None else 0,
-                                   _dt(Y) if Y is not None else TBIK_F32, M, N, K, leaf, k_first, P, _stream())
-    _check(st, "tbik_gemm_reference")
+    st = getattr(lib(), entry)(X.data_ptr(), X.stride(0), W.data_ptr(), W.stride(0), parts.data_ptr(),
+                               Y.data_ptr() if Y is not None else None, Y.stride(0) if Y is not None else 0,
+                               _dt(Y) if Y is not None else TBIK_F32, M, N, K, leaf, k_first, P, _stream())
+    _check(st, entry)
     return parts, Y
 
 

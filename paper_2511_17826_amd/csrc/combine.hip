@@ -9,7 +9,7 @@
 namespace tbik {
 
 // Vector path: N % 4 == 0; each thread owns 4 consecutive columns of one row.
-template <int P, bool OUT_BF16>
+template <int P, int OUT>   // OUT: tbik_dtype of Y
 __global__ __launch_bounds__(256) void tree_combine_vec4_kernel(const float *__restrict__ partials, void *__restrict__ Y,
                                                                 int64_t ldy, int64_t M, int64_t N) {
     const int64_t quads_per_row = N >> 2;
@@ -27,10 +27,10 @@ __global__ __launch_bounds__(256) void tree_combine_vec4_kernel(const float *__r
 #pragma unroll
         for (int p = 0; p < P; ++p) { vx[p] = in[p].x; vy[p] = in[p].y; vz[p] = in[p].z; vw[p] = in[p].w; }
         const float x = tree_of<P>(vx), y = tree_of<P>(vy), z = tree_of<P>(vz), w = tree_of<P>(vw);
-        if (OUT_BF16) {
+        if (OUT != TBIK_F32) {
             uint16_t *dst = reinterpret_cast<uint16_t *>(Y) + row * ldy + col;
-            const uint32_t lo = pack_bf16x2(x, y);
-            const uint32_t hi = pack_bf16x2(z, w);
+            const uint32_t lo = pack_16x2<OUT == TBIK_F16>(x, y);
+            const uint32_t hi = pack_16x2<OUT == TBIK_F16>(z, w);
             if ((reinterpret_cast<uintptr_t>(dst) & 7) == 0) {
                 *reinterpret_cast<uint2 *>(dst) = make_uint2(lo, hi);
             } else {
@@ -48,7 +48,7 @@ __global__ __launch_bounds__(256) void tree_combine_vec4_kernel(const float *__r
 }
 
 // Scalar path for any N.
-template <int P, bool OUT_BF16>
+template <int P, int OUT>   // OUT: tbik_dtype of Y
 __global__ __launch_bounds__(256) void tree_combine_scalar_kernel(const float *__restrict__ partials, void *__restrict__ Y,
                                                                   int64_t ldy, int64_t M, int64_t N) {
     const int64_t total = M * N;
@@ -59,28 +59,32 @@ __global__ __launch_bounds__(256) void tree_combine_scalar_kernel(const float *_
 #pragma unroll
         for (int p = 0; p < P; ++p) v[p] = partials[(int64_t)p * total + e];
         const float y = tree_of<P>(v);
-        if (OUT_BF16) reinterpret_cast<uint16_t *>(Y)[row * ldy + col] = (uint16_t)f32_to_bf16_bits(y);
+        if (OUT != TBIK_F32) reinterpret_cast<uint16_t *>(Y)[row * ldy + col] = (uint16_t)f32_to_16_bits<OUT == TBIK_F16>(y);
         else reinterpret_cast<float *>(Y)[row * ldy + col] = y;
     }
 }
 
-template <int P>
-static hipError_t launch_p(const float *partials, void *Y, int64_t ldy, int y_dtype, int M, int N, hipStream_t s) {
-    const bool bf = (y_dtype == TBIK_BF16);
+template <int P, int OUT>
+static hipError_t launch_p_out(const float *partials, void *Y, int64_t ldy, int M, int N, hipStream_t s) {
     const bool vec = (N % 4 == 0) && ((reinterpret_cast<uintptr_t>(partials) & 15) == 0);
     const int64_t work = vec ? (int64_t)M * (N / 4) : (int64_t)M * N;
     int64_t blocks = (work + 255) / 256;
     if (blocks > 256 * 64) blocks = 256 * 64;   // grid-stride beyond 64 blocks per CU
     if (blocks < 1) blocks = 1;
     dim3 grid((unsigned)blocks), block(256);
-    if (vec) {
-        if (bf) hipLaunchKernelGGL((tree_combine_vec4_kernel<P, true>), grid, block, 0, s, partials, Y, ldy, (int64_t)M, (int64_t)N);
-        else hipLaunchKernelGGL((tree_combine_vec4_kernel<P, false>), grid, block, 0, s, partials, Y, ldy, (int64_t)M, (int64_t)N);
-    } else {
-        if (bf) hipLaunchKernelGGL((tree_combine_scalar_kernel<P, true>), grid, block, 0, s, partials, Y, ldy, (int64_t)M, (int64_t)N);
-        else hipLaunchKernelGGL((tree_combine_scalar_kernel<P, false>), grid, block, 0, s, partials, Y, ldy, (int64_t)M, (int64_t)N);
-    }
+    if (vec) hipLaunchKernelGGL((tree_combine_vec4_kernel<P, OUT>), grid, block, 0, s, partials, Y, ldy, (int64_t)M, (int64_t)N);
+    else hipLaunchKernelGGL((tree_combine_scalar_kernel<P, OUT>), grid, block, 0, s, partials, Y, ldy, (int64_t)M, (int64_t)N);
     return hipGetLastError();
+}
+
+template <int P>
+static hipError_t launch_p(const float *partials, void *Y, int64_t ldy, int y_dtype, int M, int N, hipStream_t s) {
+    switch (y_dtype) {
+        case TBIK_F32: return launch_p_out<P, TBIK_F32>(partials, Y, ldy, M, N, s);
+        case TBIK_BF16: return launch_p_out<P, TBIK_BF16>(partials, Y, ldy, M, N, s);
+        case TBIK_F16: return launch_p_out<P, TBIK_F16>(partials, Y, ldy, M, N, s);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t launch_tree_combine(const float *partials, int P, void *Y, int64_t ldy, int y_dtype, int M, int N,

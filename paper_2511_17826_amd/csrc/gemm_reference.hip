@@ -3,8 +3,8 @@
 // One wavefront computes one 32x32 output tile of one K-shard.  Operands come straight from
 // global memory, so there is no tiling schedule to reason about: the kernel loops over the
 // shard's superleaves in ascending k; inside a superleaf it chains
-// v_mfma_f32_32x32x16_bf16 over ascending groups of 16 k into an accumulator that starts at +0;
-// after each superleaf the carry-over step of Alg. 1 folds the accumulator into the stash of
+// v_mfma_f32_32x32x16_bf16 (v_mfma_f32_32x32x16_f16 for binary16 operands) over ascending groups
+// of 16 k into an accumulator that starts at +0; after each superleaf the carry-over step of Alg. 1 folds the accumulator into the stash of
 // waiting subtrees.  The tuned kernels issue the same MFMA opcode over the same k -> (step, slot)
 // map and the same fp32 additions, so they must reproduce this kernel's bits.
 #include "tbik_device.hpp"
@@ -14,6 +14,7 @@ namespace tbik {
 
 constexpr int REF_MAX_LEVELS = 28;
 
+template <bool F16>
 __global__ __launch_bounds__(64) void gemm_reference_kernel(
         const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ W, int64_t ldw,
         float *__restrict__ partials, void *__restrict__ Y, int64_t ldy, int y_dtype,
@@ -46,7 +47,7 @@ __global__ __launch_bounds__(64) void gemm_reference_kernel(
 #pragma unroll
             for (int t = 0; t < 8; ++t) w[t] = col_ok ? (uint32_t)wcol[(k + t) * ldw] : 0u;
             b.u = make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, b.v, acc, 0, 0, 0);
+            acc = mfma_32x32x16<F16>(a.v, b.v, acc);
         }
         // carry-over: superleaf j completes as many subtrees as j has trailing one bits
         const int t = __builtin_ctz(~(unsigned)j);
@@ -70,7 +71,7 @@ __global__ __launch_bounds__(64) void gemm_reference_kernel(
         if (partials) partials[((int64_t)p * M + row) * N + col] = acc[r];
         if (Y) {
             if (y_dtype == TBIK_F32) reinterpret_cast<float *>(Y)[(int64_t)row * ldy + col] = acc[r];
-            else reinterpret_cast<uint16_t *>(Y)[(int64_t)row * ldy + col] = (uint16_t)f32_to_bf16_bits(acc[r]);
+            else reinterpret_cast<uint16_t *>(Y)[(int64_t)row * ldy + col] = (uint16_t)f32_to_16_bits<F16>(acc[r]);
         }
     }
 }
@@ -80,7 +81,8 @@ hipError_t launch_gemm_reference(const GemmArgs &a, hipStream_t s) {
     dim3 grid((a.N + 31) / 32, (a.M + 31) / 32, a.P);
     if (grid.y > 65535u || grid.z > 65535u) return hipErrorInvalidValue;
     void *Y = (a.P == 1) ? a.Y : nullptr;
-    hipLaunchKernelGGL(gemm_reference_kernel, grid, dim3(64), 0, s, a.X, a.ldx, a.W, a.ldw, a.partials, Y, a.ldy,
+    auto kernel = (a.x_dtype == TBIK_F16) ? gemm_reference_kernel<true> : gemm_reference_kernel<false>;
+    hipLaunchKernelGGL(kernel, grid, dim3(64), 0, s, a.X, a.ldx, a.W, a.ldw, a.partials, Y, a.ldy,
                        a.y_dtype, a.M, a.N, a.K, a.superleaf, a.ns / a.P);
     return hipGetLastError();
 }

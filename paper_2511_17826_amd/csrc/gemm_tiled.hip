@@ -147,7 +147,9 @@ struct TiledParams {
 // The global->LDS load stream runs ahead of the MFMA stream across item boundaries, so the first stages
 // of the next tile are already in flight while the current tile is finished and stored.
 // RING: LDS stage slots; RING - 3 stages of loads are in flight at a stage's entry, one more is issued during it.
-template <int LEVELS, int WM, int WN, int MT, int NT, int RING>
+// F16: the operands (and a 16-bit output) are IEEE binary16 instead of bf16; only the MFMA opcode and the output
+// conversion differ.
+template <int LEVELS, int WM, int WN, int MT, int NT, int RING, bool F16>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_tiled_kernel(const TiledParams p) {
     constexpr int BM = 32 * MT * WM, BN = 32 * NT * WN;
@@ -341,9 +343,9 @@ void gemm_tiled_kernel(const TiledParams p) {
                 const int i = m / NT, j = m % NT;
                 if (FIRST && ks == 0) {
                     const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-                    a.t[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[0][i], w_frag(0, j), zero, 0, 0, 0);
+                    a.t[i][j] = mfma_32x32x16<F16>(af[0][i], w_frag(0, j), zero);
                 } else {
-                    a.t[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][i], w_frag(ks, j), a.t[i][j], 0, 0, 0);
+                    a.t[i][j] = mfma_32x32x16<F16>(af[ks][i], w_frag(ks, j), a.t[i][j]);
                 }
 #pragma unroll
                 for (int r = m * READS_PER_KSTEP / NM; r < (m + 1) * READS_PER_KSTEP / NM; ++r)
@@ -415,10 +417,10 @@ void gemm_tiled_kernel(const TiledParams p) {
 #pragma unroll
                     for (int it = 0; it < N_IT; ++it) {
                         u32x4 o;
-                        o[0] = pack_bf16x2(lo[it][0], lo[it][1]);
-                        o[1] = pack_bf16x2(lo[it][2], lo[it][3]);
-                        o[2] = pack_bf16x2(hi[it][0], hi[it][1]);
-                        o[3] = pack_bf16x2(hi[it][2], hi[it][3]);
+                        o[0] = pack_16x2<F16>(lo[it][0], lo[it][1]);
+                        o[1] = pack_16x2<F16>(lo[it][2], lo[it][3]);
+                        o[2] = pack_16x2<F16>(hi[it][0], hi[it][1]);
+                        o[3] = pack_16x2<F16>(hi[it][2], hi[it][3]);
                         *reinterpret_cast<u32x4 *>(base + it * it_step + lane_off) = o;
                     }
                 }
@@ -462,7 +464,7 @@ void gemm_tiled_kernel(const TiledParams p) {
                         const float v = acc.t[a][b][r];
                         if (part) part[(int64_t)row * p.N + col] = v;
                         if (p.Y) {
-                            if (p.y_bf16) reinterpret_cast<uint16_t *>(p.Y)[(int64_t)row * p.ldy + col] = (uint16_t)f32_to_bf16_bits(v);
+                            if (p.y_bf16) reinterpret_cast<uint16_t *>(p.Y)[(int64_t)row * p.ldy + col] = (uint16_t)f32_to_16_bits<F16>(v);
                             else reinterpret_cast<float *>(p.Y)[(int64_t)row * p.ldy + col] = v;
                         }
                     }
@@ -503,14 +505,14 @@ static int compute_units() {
     return cus;
 }
 
-template <int WM, int WN, int MT, int NT, int RING>
+template <int WM, int WN, int MT, int NT, int RING, bool F16>
 static hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
     constexpr int BM = 32 * MT * WM, BN = 32 * NT * WN;
     TiledParams p;
     p.X = a.X; p.W = a.W; p.partials = a.partials; p.Y = (a.P == 1) ? a.Y : nullptr;
     p.ldx = a.ldx; p.ldw = a.ldw; p.ldy = a.ldy;
     p.M = a.M; p.N = a.N;
-    p.y_bf16 = (a.y_dtype == TBIK_BF16);
+    p.y_bf16 = (a.y_dtype != TBIK_F32);                  // 16-bit output, in the operands' format
     p.stages_per_superleaf = a.superleaf / BK;
     p.ns_per_shard = a.ns / a.P;
     p.k_per_shard = (int64_t)a.K / a.P;
@@ -532,7 +534,7 @@ static hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 32) dev = 32;   // 32: not remembered, set every time
 #define TBIK_LAUNCH(L)                                                                                   \
     case L: {                                                                                            \
-        auto k = gemm_tiled_kernel<L, WM, WN, MT, NT, RING>;                                             \
+        auto k = gemm_tiled_kernel<L, WM, WN, MT, NT, RING, F16>;                                            \
         static std::atomic<unsigned> lds_allowed{0};   /* bit d: the attribute is set on device d */     \
         if (dev >= 32 || !((lds_allowed.load(std::memory_order_relaxed) >> dev) & 1u)) {                 \
             hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
@@ -557,8 +559,11 @@ static hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
 hipError_t launch_gemm_tiled(const GemmArgs &a, int variant, hipStream_t s) {
     if (a.M <= 0 || a.N <= 0) return hipSuccess;
     if (!gemm_tiled_supports(a, variant)) return hipErrorInvalidValue;
-    if (variant == VARIANT_T128) return launch_shape<2, 2, 2, 2, 5>(a, s);   // 128 x 128, wave tile 64 x 64, 5 x 32 KiB stage slots = all of LDS
-    return launch_shape<1, 4, 1, 1, 6>(a, s);                                // 32 x 128, wave tile 32 x 32, 6 x 20 KiB: deep prefetch for weight streaming
+    const bool f16 = (a.x_dtype == TBIK_F16);
+    // 128 x 128, wave tile 64 x 64, 5 x 32 KiB stage slots = all of LDS
+    if (variant == VARIANT_T128) return f16 ? launch_shape<2, 2, 2, 2, 5, true>(a, s) : launch_shape<2, 2, 2, 2, 5, false>(a, s);
+    // 32 x 128, wave tile 32 x 32, 6 x 20 KiB: deep prefetch for weight streaming
+    return f16 ? launch_shape<1, 4, 1, 1, 6, true>(a, s) : launch_shape<1, 4, 1, 1, 6, false>(a, s);
 }
 
 }  // namespace tbik

@@ -69,6 +69,9 @@ int pick_variant(const GemmArgs &a) {
     return VARIANT_REFERENCE;
 }
 
+// 16-bit output type that goes with an operand format.
+inline bool legal_y_dtype(int y_dtype, int x_dtype) { return y_dtype == TBIK_F32 || y_dtype == x_dtype; }
+
 }  // namespace
 
 extern "C" {
@@ -81,10 +84,12 @@ size_t tbik_gemm_workspace_bytes(int M, int N, int K, int leaf, int k_first) {
     return split > 1 ? (size_t)split * (size_t)M * (size_t)N * sizeof(float) : 0;
 }
 
-int tbik_gemm_shard_partials(const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
-                             int M, int N, int K, int leaf, int k_first, int P,
-                             void *workspace, size_t workspace_bytes, void *hip_stream) {
-    (void)workspace; (void)workspace_bytes;
+}  // extern "C"
+
+namespace {
+
+int gemm_shard_partials(int x_dtype, const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
+                        int M, int N, int K, int leaf, int k_first, int P, void *hip_stream) {
     int sl, ns;
     int rc = check_tree(M, N, K, leaf, k_first, P, &sl, &ns);
     if (rc != TBIK_OK) return rc;
@@ -93,20 +98,20 @@ int tbik_gemm_shard_partials(const void *X, int64_t ldx, const void *W, int64_t 
     if (rc != TBIK_OK) return rc;
     if (!partials) return TBIK_ERR_NULL;
     if (!aligned(partials, 16)) return TBIK_ERR_ALIGN;
-    GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)W, ldw, partials, nullptr, 0, TBIK_F32, M, N, K, sl, ns, P};
+    GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)W, ldw, partials, nullptr, 0, TBIK_F32, M, N, K, sl, ns, P, x_dtype};
     hipStream_t s = (hipStream_t)hip_stream;
     const int v = pick_variant(a);
     hipError_t e = (v == VARIANT_REFERENCE) ? launch_gemm_reference(a, s) : launch_gemm_tiled(a, v, s);
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }
 
-int tbik_gemm(const void *X, int64_t ldx, const void *W, int64_t ldw, void *Y, int64_t ldy,
-              tbik_dtype y_dtype, int M, int N, int K, int leaf, int k_first,
-              void *workspace, size_t workspace_bytes, void *hip_stream) {
+int gemm(int x_dtype, const void *X, int64_t ldx, const void *W, int64_t ldw, void *Y, int64_t ldy,
+         int y_dtype, int M, int N, int K, int leaf, int k_first,
+         void *workspace, size_t workspace_bytes, void *hip_stream) {
     int sl, ns;
     int rc = check_tree(M, N, K, leaf, k_first, 1, &sl, &ns);
     if (rc != TBIK_OK) return rc;
-    if (y_dtype != TBIK_F32 && y_dtype != TBIK_BF16) return TBIK_ERR_DTYPE;
+    if (!legal_y_dtype(y_dtype, x_dtype)) return TBIK_ERR_DTYPE;
     if (M == 0 || N == 0) return TBIK_OK;
     rc = check_operands(X, ldx, W, ldw, N, K);
     if (rc != TBIK_OK) return rc;
@@ -118,7 +123,7 @@ int tbik_gemm(const void *X, int64_t ldx, const void *W, int64_t ldw, void *Y, i
     if (workspace && !aligned(workspace, 256)) return TBIK_ERR_ALIGN;
 
     hipStream_t s = (hipStream_t)hip_stream;
-    GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)W, ldw, nullptr, Y, ldy, (int)y_dtype, M, N, K, sl, ns, 1};
+    GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)W, ldw, nullptr, Y, ldy, y_dtype, M, N, K, sl, ns, 1, x_dtype};
     const int split = internal_split(M, N, ns);
     GemmArgs probe = a;
     probe.P = split;
@@ -131,18 +136,18 @@ int tbik_gemm(const void *X, int64_t ldx, const void *W, int64_t ldw, void *Y, i
         a.Y = nullptr;
         a.P = split;
         e = launch_gemm_tiled(a, v, s);
-        if (e == hipSuccess) e = launch_tree_combine(a.partials, split, Y, ldy, (int)y_dtype, M, N, s);
+        if (e == hipSuccess) e = launch_tree_combine(a.partials, split, Y, ldy, y_dtype, M, N, s);
     }
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }
 
-int tbik_gemm_reference(const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
-                        void *Y, int64_t ldy, tbik_dtype y_dtype,
-                        int M, int N, int K, int leaf, int k_first, int P, void *hip_stream) {
+int gemm_reference(int x_dtype, const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
+                   void *Y, int64_t ldy, int y_dtype,
+                   int M, int N, int K, int leaf, int k_first, int P, void *hip_stream) {
     int sl, ns;
     int rc = check_tree(M, N, K, leaf, k_first, P, &sl, &ns);
     if (rc != TBIK_OK) return rc;
-    if (y_dtype != TBIK_F32 && y_dtype != TBIK_BF16) return TBIK_ERR_DTYPE;
+    if (!legal_y_dtype(y_dtype, x_dtype)) return TBIK_ERR_DTYPE;
     if (M == 0 || N == 0) return TBIK_OK;
     rc = check_operands(X, ldx, W, ldw, N, K);
     if (rc != TBIK_OK) return rc;
@@ -150,16 +155,58 @@ int tbik_gemm_reference(const void *X, int64_t ldx, const void *W, int64_t ldw, 
     if (Y && P != 1) return TBIK_ERR_SHARDS;
     if (Y && ldy < N) return TBIK_ERR_SHAPE;
     if (Y && !aligned(Y, y_dtype == TBIK_F32 ? 4 : 2)) return TBIK_ERR_ALIGN;
-    GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)W, ldw, partials, Y, ldy, (int)y_dtype, M, N, K, sl, ns, P};
+    GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)W, ldw, partials, Y, ldy, y_dtype, M, N, K, sl, ns, P, x_dtype};
     hipError_t e = launch_gemm_reference(a, (hipStream_t)hip_stream);
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
+}  // namespace
+
+extern "C" {
+
+int tbik_gemm(const void *X, int64_t ldx, const void *W, int64_t ldw, void *Y, int64_t ldy,
+              tbik_dtype y_dtype, int M, int N, int K, int leaf, int k_first,
+              void *workspace, size_t workspace_bytes, void *hip_stream) {
+    return gemm(TBIK_BF16, X, ldx, W, ldw, Y, ldy, (int)y_dtype, M, N, K, leaf, k_first, workspace, workspace_bytes, hip_stream);
+}
+
+int tbik_gemm_f16(const void *X, int64_t ldx, const void *W, int64_t ldw, void *Y, int64_t ldy,
+                  tbik_dtype y_dtype, int M, int N, int K, int leaf, int k_first,
+                  void *workspace, size_t workspace_bytes, void *hip_stream) {
+    return gemm(TBIK_F16, X, ldx, W, ldw, Y, ldy, (int)y_dtype, M, N, K, leaf, k_first, workspace, workspace_bytes, hip_stream);
+}
+
+int tbik_gemm_shard_partials(const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
+                             int M, int N, int K, int leaf, int k_first, int P,
+                             void *workspace, size_t workspace_bytes, void *hip_stream) {
+    (void)workspace; (void)workspace_bytes;
+    return gemm_shard_partials(TBIK_BF16, X, ldx, W, ldw, partials, M, N, K, leaf, k_first, P, hip_stream);
+}
+
+int tbik_gemm_shard_partials_f16(const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
+                                 int M, int N, int K, int leaf, int k_first, int P,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream) {
+    (void)workspace; (void)workspace_bytes;
+    return gemm_shard_partials(TBIK_F16, X, ldx, W, ldw, partials, M, N, K, leaf, k_first, P, hip_stream);
+}
+
+int tbik_gemm_reference(const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
+                        void *Y, int64_t ldy, tbik_dtype y_dtype,
+                        int M, int N, int K, int leaf, int k_first, int P, void *hip_stream) {
+    return gemm_reference(TBIK_BF16, X, ldx, W, ldw, partials, Y, ldy, (int)y_dtype, M, N, K, leaf, k_first, P, hip_stream);
+}
+
+int tbik_gemm_reference_f16(const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
+                            void *Y, int64_t ldy, tbik_dtype y_dtype,
+                            int M, int N, int K, int leaf, int k_first, int P, void *hip_stream) {
+    return gemm_reference(TBIK_F16, X, ldx, W, ldw, partials, Y, ldy, (int)y_dtype, M, N, K, leaf, k_first, P, hip_stream);
 }
 
 int tbik_tree_combine(const float *partials, int P, void *Y, int64_t ldy, tbik_dtype y_dtype,
                       int M, int N, void *hip_stream) {
     if (M < 0 || N < 0) return TBIK_ERR_SHAPE;
     if (P < 1 || !is_pow2(P) || P > TBIK_MAX_SHARDS) return TBIK_ERR_SHARDS;
-    if (y_dtype != TBIK_F32 && y_dtype != TBIK_BF16) return TBIK_ERR_DTYPE;
+    if (y_dtype != TBIK_F32 && y_dtype != TBIK_BF16 && y_dtype != TBIK_F16) return TBIK_ERR_DTYPE;
     if (M == 0 || N == 0) return TBIK_OK;
     if (!partials || !Y) return TBIK_ERR_NULL;
     if (ldy < N) return TBIK_ERR_SHAPE;

@@ -22,6 +22,28 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 }
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) { return pack_bf16x2(f, 0.0f) & 0xffffu; }
 
+// The same for IEEE binary16 outputs (v_cvt_f16_f32 under the default rounding mode, fp16 denormals kept).
+typedef _Float16 tbik_f16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
+    const tbik_f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, tbik_f16x2));
+}
+template <bool F16>
+__device__ __forceinline__ uint32_t pack_16x2(float lo, float hi) { return F16 ? pack_f16x2(lo, hi) : pack_bf16x2(lo, hi); }
+template <bool F16>
+__device__ __forceinline__ uint32_t f32_to_16_bits(float f) { return pack_16x2<F16>(f, 0.0f) & 0xffffu; }
+
+// One MFMA of the GEMM kernels: D = A(32x16) * B(16x32) + C with 16-bit operands of either format held as
+// eight 16-bit patterns per lane.  Both opcodes share the operand layout.
+typedef _Float16 f16x8 __attribute__((__vector_size__(8 * sizeof(_Float16))));
+template <bool F16>
+__device__ __forceinline__ f32x16 mfma_32x32x16(bf16x8 a, bf16x8 b, f32x16 c) {
+    if constexpr (F16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
 // T over P = 2^t values held in registers, in the order of Alg. 2's reduce phase: at level l, value r
 // (r mod 2^(l+1) == 0) receives value r + 2^l.  The array is used as scratch.
 template <int P>

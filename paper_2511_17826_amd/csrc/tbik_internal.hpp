@@ -10,9 +10,9 @@ namespace tbik {
 
 // Resolved description of one GEMM request; validated by the C ABI layer before any launch.
 struct GemmArgs {
-    const uint16_t *X;   // bf16 [M, ldx]
+    const uint16_t *X;   // x_dtype [M, ldx]
     int64_t ldx;
-    const uint16_t *W;   // bf16 [K, ldw]
+    const uint16_t *W;   // x_dtype [K, ldw]
     int64_t ldw;
     float *partials;     // fp32 [P, M, N] or nullptr
     void *Y;             // [M, ldy] of y_dtype or nullptr
@@ -22,6 +22,7 @@ struct GemmArgs {
     int superleaf;       // leaf * k_first
     int ns;              // number of superleaves (power of two)
     int P;               // shards (power of two, <= ns)
+    int x_dtype;         // TBIK_BF16 or TBIK_F16: storage format of X, W and of a 16-bit Y
 };
 
 // Reference kernel: one wavefront per 32x32 tile and shard.  Writes partials (if set) and, when P == 1

@@ -73,6 +73,26 @@ def test_gemm_argument_validation(L):
     assert gemm(L, X=GOOD + 2) == 5 and gemm(L, ldw=260) == 5          # misaligned pointer / leading dimension
 
 
+def test_fp16_entry_points_validate_like_the_bf16_ones(L):
+    def g16(**kw):
+        a = dict(X=GOOD, ldx=512, W=GOOD, ldw=256, Y=GOOD, ldy=256, dt=2, M=0, N=256, K=512, leaf=64, g=1)
+        a.update(kw)
+        return L.tbik_gemm_f16(a["X"], a["ldx"], a["W"], a["ldw"], a["Y"], a["ldy"], a["dt"], a["M"], a["N"], a["K"],
+                               a["leaf"], a["g"], None, 0, None)
+    assert g16() == 0 and g16(dt=0) == 0
+    assert g16(dt=1) == 4                                              # bf16 output does not go with fp16 operands
+    assert gemm(L, dt=2) == 4                                          # nor fp16 output with bf16 operands
+    assert g16(M=4, X=None) == 1 and g16(K=500) == 2 and g16(M=4, X=GOOD + 2) == 5
+    sp = L.tbik_gemm_shard_partials_f16
+    assert sp(GOOD, 512, GOOD, 256, GOOD, 4, 256, 512, 64, 1, 3, None, 0, None) == 3
+    assert sp(GOOD, 512, GOOD, 256, None, 4, 256, 512, 64, 1, 2, None, 0, None) == 1
+    rf = L.tbik_gemm_reference_f16
+    assert rf(GOOD, 512, GOOD, 256, GOOD, GOOD, 256, 1, 4, 256, 512, 64, 1, 1, None) == 4
+    assert rf(GOOD, 512, GOOD, 256, GOOD, GOOD, 256, 2, 4, 256, 512, 64, 1, 2, None) == 3      # Y only with P == 1
+    assert L.tbik_tree_combine(GOOD, 2, GOOD, 256, 2, 0, 256, None) == 0                       # fp16 output is offered
+    assert L.tbik_row_reduce(GOOD, 2, GOOD, 0, 4, 1024, GOOD, 1 << 20, None) == 4              # fp16 rows are not
+
+
 def test_shard_and_combine_validation(L):
     sp = L.tbik_gemm_shard_partials
     args = lambda P, part=GOOD: (GOOD, 512, GOOD, 256, part, 4, 256, 512, 64, 1, P, None, 0, None)
