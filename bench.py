@@ -288,6 +288,21 @@ def extras(tb, syn, torch, np, to_dev):
         res["downproj_k14336_M%d" % M] = {"ms": round(t, 4), "tflops": round(2.0 * M * 14336 * 4096 / (t * 1e-3) / 1e12, 2),
                                           "baseline_ms": round(tb_ms, 4)}
     del X, W
+    # fp16 operands at the o_proj shape (same kernel, the other MFMA opcode)
+    c = syn.gemm_oproj(4096, fmt="fp16")
+    X = torch.from_numpy(c["X"].view(np.int16)).view(torch.float16).to("cuda:0")
+    W = torch.from_numpy(c["W"].view(np.int16)).view(torch.float16).to("cuda:0")
+    for M in (1, 64, 4096):
+        y = torch.empty((M, 4096), dtype=torch.float16, device=X.device)
+        f = lambda: tb.tbik_gemm_f16(X[:M], W, 256, 1, out=y)
+        f(); f()
+        t = min(time_region(f, 20, torch) for _ in range(3))
+        b = lambda: torch.matmul(X[:M], W)
+        b(); b()
+        tb_ms = min(time_region(b, 20, torch) for _ in range(3))
+        res["oproj_fp16_M%d" % M] = {"ms": round(t, 4), "tflops": round(2.0 * M * 4096 * 4096 / (t * 1e-3) / 1e12, 2),
+                                     "baseline_ms": round(tb_ms, 4)}
+    del X, W
     for H in (4096, 5120):
         xb, wb = syn.rmsnorm_inputs(8192, H)
         x, w = to_dev(xb), to_dev(wb)
