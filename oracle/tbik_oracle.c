@@ -26,12 +26,19 @@
  *   tbik_oracle_row_*        App. B (one row = one fixed reduction order,
  *                            independent of the batch) with the tree order of
  *                            App. C applied along the row.
+ *   tbik_oracle_attention    the attention rule of the implementation appendix (fixed
+ *                            key tile, one routine for prefill and decode), as the
+ *                            streaming-softmax recurrence over tiles at absolute positions.
+ *   16-bit operands are bf16 or IEEE binary16 (the kernel table lists both); the
+ *   format only changes the exact widening and the one output rounding.
  *
  * Pins (tests marked "not gpu"): hand-derived tree values, Theorem 1 across
  * P and M, exact-integer inputs against int64 arithmetic, fp64 brute force
  * within the summation-tree error bound, one-superleaf == sequential sum,
  * leaf 1 == level-by-level pairwise sum, closed forms for RMSNorm and
- * log-softmax.  No function here is "parity unpinned".
+ * log-softmax, numpy's float16 for the binary16 conversions, the fp64 softmax
+ * definition and exact special cases for attention.  No function here is
+ * "parity unpinned".
  */
 #include <float.h>
 #include <math.h>
@@ -475,6 +482,97 @@ int tbik_oracle_row_logsoftmax(const float *x, float *out, int M, long V, int le
             for (long i = 0; i < V; ++i) out[m * V + i] = (row[i] - mx) - lg;
         }
         free(e);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ attention with a fixed key tile */
+
+/*
+ * Batch-invariant attention (App. "Framework Modifications": the attention kernel works with a FIXED tile
+ * size, and prefill and decode run the same kernel; Sec. 2.1: fp32 accumulators in Flash-Attention).
+ * The paper names the rule, not the arithmetic; the arithmetic below is the streaming-softmax recurrence of
+ * Flash-Attention with the key axis cut into tiles of `kv_tile` keys at ABSOLUTE positions
+ * [t*kv_tile, (t+1)*kv_tile) of the sequence, visited in ascending order, one query row at a time, so that
+ * a query's result depends on its own row of Q and on the keys it may see -- never on what else is in the
+ * batch, on how many queries arrive together, or on whether the call is a prefill or a decode step.
+ *
+ * Packed variable-length layout: sequence b owns query tokens cu_q[b]..cu_q[b+1]-1 and key tokens
+ * cu_k[b]..cu_k[b+1]-1; token t, head h, channel d of Q is Q[t*q_stride + h*D + d] (bf16); K and V
+ * likewise with Hkv heads; query head h reads key/value head h / (Hq/Hkv).  With Lq queries and Lk keys
+ * the queries are the LAST Lq positions of the sequence: query i sees key j iff j < Lk and (not causal or
+ * j <= i + Lk - Lq).
+ *
+ * Per (sequence, head, query), with c = fl(scale * log2 e) in fp32:
+ *   m = -inf, l = 0, o[0..D) = 0
+ *   for each tile t that holds at least one visible key, ascending:
+ *     s_j   = fl( (sum_d q_d k_jd) * c )            dot product in fp32, ascending d from +0; visible j only
+ *     m'    = max(m, max_j s_j)
+ *     a     = exp2(m - m')                          (0 for the first tile)
+ *     p_j   = exp2(s_j - m')
+ *     l     = l*a + (sum_j p_j)                     ascending j from +0, fp32 p_j
+ *     o_d   = (o_d*a) + sum_j bf16(p_j) * v_jd      ascending j, added one by one to o_d*a; p rounded to bf16 (RNE)
+ *     m     = m'
+ *   O_d = bf16(o_d / l), or 0 if the query sees no key.
+ * O32 (optional) receives o_d / l before the rounding.
+ */
+int tbik_oracle_attention(const uint16_t *Q, const uint16_t *K, const uint16_t *V, uint16_t *O, float *O32,
+                          const int32_t *cu_q, const int32_t *cu_k, int batch, int Hq, int Hkv, int D,
+                          long q_stride, long k_stride, long v_stride, long o_stride,
+                          float scale, int causal, int kv_tile) {
+    if (batch < 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || D <= 0 || kv_tile <= 0) return -1;
+    const float c = scale * 1.44269504088896340736f;
+    const int group = Hq / Hkv;
+#pragma omp parallel
+    {
+        float *s = (float *)malloc((size_t)kv_tile * sizeof(float));
+        float *o = (float *)malloc((size_t)D * sizeof(float));
+#pragma omp for schedule(dynamic, 1) collapse(2)
+        for (int b = 0; b < batch; ++b) {
+            for (int h = 0; h < Hq; ++h) {
+                const long q0 = cu_q[b], Lq = cu_q[b + 1] - q0, k0 = cu_k[b], Lk = cu_k[b + 1] - k0;
+                const int hk = h / group;
+                for (long i = 0; i < Lq; ++i) {
+                    const uint16_t *q = Q + (q0 + i) * q_stride + (long)h * D;
+                    long last = causal ? i + Lk - Lq : Lk - 1;          /* last visible key */
+                    if (last > Lk - 1) last = Lk - 1;
+                    float m = -INFINITY, l = 0.0f;
+                    for (int d = 0; d < D; ++d) o[d] = 0.0f;
+                    for (long j0 = 0; j0 <= last; j0 += kv_tile) {
+                        long j1 = j0 + kv_tile - 1;
+                        if (j1 > last) j1 = last;
+                        float tm = -INFINITY;
+                        for (long j = j0; j <= j1; ++j) {
+                            const uint16_t *k = K + (k0 + j) * k_stride + (long)hk * D;
+                            float dot = 0.0f;
+                            for (int d = 0; d < D; ++d) dot = dot + bf16_to_f32(q[d]) * bf16_to_f32(k[d]);
+                            s[j - j0] = dot * c;
+                            tm = s[j - j0] > tm ? s[j - j0] : tm;
+                        }
+                        const float m2 = tm > m ? tm : m;
+                        const float a = exp2f(m - m2);
+                        float psum = 0.0f;
+                        for (int d = 0; d < D; ++d) o[d] = o[d] * a;
+                        for (long j = j0; j <= j1; ++j) {
+                            const float p = exp2f(s[j - j0] - m2);
+                            psum = psum + p;
+                            const float pb = bf16_to_f32(f32_to_bf16(p));
+                            const uint16_t *v = V + (k0 + j) * v_stride + (long)hk * D;
+                            for (int d = 0; d < D; ++d) o[d] = o[d] + pb * bf16_to_f32(v[d]);
+                        }
+                        l = l * a + psum;
+                        m = m2;
+                    }
+                    for (int d = 0; d < D; ++d) {
+                        const float r = (l > 0.0f) ? o[d] / l : 0.0f;
+                        if (O32) O32[((q0 + i) * Hq + h) * (long)D + d] = r;
+                        if (O) O[(q0 + i) * o_stride + (long)h * D + d] = f32_to_bf16(r);
+                    }
+                }
+            }
+        }
+        free(s);
+        free(o);
     }
     return 0;
 }

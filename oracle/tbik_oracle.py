@@ -81,6 +81,10 @@ def lib():
         L.tbik_oracle_row_max.argtypes = [f32p, f32p, C.c_int, C.c_long]
         L.tbik_oracle_row_logsoftmax.restype = C.c_int
         L.tbik_oracle_row_logsoftmax.argtypes = [f32p, f32p, C.c_int, C.c_long, C.c_int]
+        i32p = C.POINTER(C.c_int32)
+        L.tbik_oracle_attention.restype = C.c_int
+        L.tbik_oracle_attention.argtypes = [u16p, u16p, u16p, u16p, f32p, i32p, i32p, C.c_int, C.c_int, C.c_int, C.c_int,
+                                            C.c_long, C.c_long, C.c_long, C.c_long, C.c_float, C.c_int, C.c_int]
         L.tbik_oracle_f32_to_bf16.restype = C.c_uint16
         L.tbik_oracle_f32_to_bf16.argtypes = [C.c_float]
         L.tbik_oracle_f32_to_f16.restype = C.c_uint16
@@ -287,3 +291,32 @@ def row_logsoftmax(x, leaf: int = LEAF_F32) -> np.ndarray:
     out = np.empty((M, V), dtype=np.float32)
     lib().tbik_oracle_row_logsoftmax(xp, out.ctypes.data_as(C.POINTER(C.c_float)), M, V, leaf)
     return out
+
+
+# ------------------------------------------------------------------ attention
+
+KV_TILE = 64
+
+
+def attention(Q, K, V, cu_q, cu_k, scale: float, causal: bool = True, kv_tile: int = KV_TILE):
+    """Fixed-tile attention on packed sequences.  Q [Tq, Hq, D], K and V [Tk, Hkv, D] as bf16 bit patterns;
+    cu_q, cu_k int32 [batch + 1].  Returns (O bf16 bits [Tq, Hq, D], O fp32 before the rounding)."""
+    Q, qp = _u16(Q)
+    K, kp = _u16(K)
+    V, vp = _u16(V)
+    cu_q = np.ascontiguousarray(cu_q, dtype=np.int32)
+    cu_k = np.ascontiguousarray(cu_k, dtype=np.int32)
+    Tq, Hq, D = Q.shape
+    Tk, Hkv, D2 = K.shape
+    assert D == D2 and V.shape == K.shape and cu_q.size == cu_k.size
+    assert cu_q[-1] <= Tq and cu_k[-1] <= Tk and np.all(np.diff(cu_q) >= 0) and np.all(np.diff(cu_k) >= 0)
+    O = np.zeros((Tq, Hq, D), dtype=np.uint16)
+    O32 = np.zeros((Tq, Hq, D), dtype=np.float32)
+    i32p = C.POINTER(C.c_int32)
+    rc = lib().tbik_oracle_attention(qp, kp, vp, O.ctypes.data_as(C.POINTER(C.c_uint16)),
+                                     O32.ctypes.data_as(C.POINTER(C.c_float)), cu_q.ctypes.data_as(i32p),
+                                     cu_k.ctypes.data_as(i32p), cu_q.size - 1, Hq, Hkv, D, Hq * D, Hkv * D, Hkv * D,
+                                     Hq * D, scale, int(causal), kv_tile)
+    if rc != 0:
+        raise ValueError("oracle attention: illegal head counts or tile")
+    return O, O32
