@@ -153,6 +153,35 @@ int tbik_combine_residual_rmsnorm(const float *partials, int P, const void *resi
 int tbik_row_reduce(const void *x, tbik_dtype x_dtype, void *out, tbik_rowop op, int M, int64_t V,
                     void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Batch-invariant attention on packed variable-length sequences (implementation appendix, "Framework Modifications
+ * for vLLM and FSDP": the attention kernel uses a FIXED tile size, and prefill and decode run the same kernel;
+ * Sec. 2.1: fp32 accumulators).  For sequence b, query head h, query i (of Lq = cu_q[b+1] - cu_q[b] queries, which
+ * are the LAST Lq positions of a sequence with Lk = cu_k[b+1] - cu_k[b] keys):
+ *     O = softmax_j( scale * q . k_j ) applied to v_j  over the visible keys j,
+ *     visible: j < Lk and (causal == 0 or j <= i + Lk - Lq);   a query that sees no key gives 0.
+ * Order of the arithmetic (fixed, part of the contract): keys in tiles of 64 at absolute positions [64 t, 64 t + 64),
+ * ascending; per tile the streaming-softmax step in fp32 with base-2 exponentials (scores scaled by
+ * scale * log2 e), the tile's weights rounded to bf16 for the product with V, fp32 accumulation; one division by
+ * the sum of weights and one rounding to bf16 at the end.  The bits of a query's output depend only on its own
+ * row of Q and on the keys and values it sees -- not on the batch, on the number of queries per sequence in the
+ * call (prefill, decode step, chunk), or on the query's position in the packed tensor.
+ *
+ *   Q, O   device, bf16, token t / head h / channel d at [t * stride + h * head_dim + d]; Q has heads_q heads
+ *   K, V   device, bf16, same layout with heads_kv heads; query head h reads key/value head h / (heads_q / heads_kv)
+ *   cu_seqlens_q, cu_seqlens_k   DEVICE, int32 [batch + 1], non-decreasing prefix sums of the sequences' query and key
+ *          counts; values are clamped to [0, total_q] / [0, total_k] inside the kernel
+ *   max_seqlen_q   at least the largest Lq (queries past it are not computed); total_q, total_k: tokens in Q/O and K/V
+ *   head_dim 128 (other values: TBIK_ERR_UNSUPPORTED); heads_q a multiple of heads_kv; strides in elements, multiples
+ *   of 8, at least heads * head_dim; pointers 16-byte aligned.  O must not overlap Q, K or V.
+ * Errors: NULL, SHAPE, UNSUPPORTED, ALIGN, HIP.
+ */
+int tbik_attention(const void *Q, const void *K, const void *V, void *O,
+                   const int32_t *cu_seqlens_q, const int32_t *cu_seqlens_k, int batch, int max_seqlen_q,
+                   int total_q, int total_k, int heads_q, int heads_kv, int head_dim,
+                   int64_t q_stride, int64_t k_stride, int64_t v_stride, int64_t o_stride,
+                   float scale, int causal, void *hip_stream);
+
 /* Scratch sizes (pure host functions; 0 if the arguments are illegal or no scratch is needed).
  * tbik_gemm_workspace_bytes covers tbik_gemm and tbik_gemm_shard_partials for any legal P. */
 size_t tbik_gemm_workspace_bytes(int M, int N, int K, int leaf, int k_first);

@@ -1,0 +1,272 @@
+// Batch-invariant attention for gfx950: one kernel for prefill, decode and anything between, with a FIXED key tile
+// (the attention rule of the paper's implementation appendix, "Framework Modifications": fix the tile size, run
+// prefill and decode through the same kernel; Sec. 2.1: fp32 accumulators).
+//
+// A workgroup of 4 wavefronts owns 128 consecutive queries of one (sequence, head); a wavefront owns 32 of them.
+// The keys of the sequence are visited in tiles of ATT_KV = 64 at absolute positions [64 t, 64 t + 64), in
+// ascending order, with the streaming-softmax recurrence per query row:
+//     s_j = (q . k_j) * c            c = scale * log2(e), fp32
+//     m'  = max(m, max_j s_j);  a = exp2(m - m');  p_j = exp2(s_j - m')
+//     l   = l a + sum_j p_j;    o = o a + sum_j bf16(p_j) v_j;    m = m'
+// and O = o / l, rounded once to bf16.  Nothing in a row's arithmetic depends on the other rows of the block, on
+// the number of queries in the call or on the batch: a tile that is masked for a row leaves that row's (m, l, o)
+// unchanged bit for bit (a = 1, p = 0), so the number of tiles a block walks does not matter either.
+//
+// Everything is computed transposed, so that a lane owns ONE query (column lane % 32 of every MFMA result) and
+// the per-query state m, l, a lives in one register per lane:
+//     S^T (keys x queries)  = K (A operand, 16-byte LDS reads)        x Q^T (B operand, in registers for the whole block)
+//     O^T (channels x queries) = V^T (A operand, transposing LDS read) x P^T (B operand = the S^T registers, rounded to bf16)
+// The MFMA's k-slot (g, t) of step s stands for key 32 kb + 16 h + 8 (t / 4) + 4 g + t % 4 (kb = s / 2, h = s % 2): the
+// order in which the result layout of S^T hands the keys to a lane; V^T is fetched in the same order.
+#include <atomic>
+
+#include "tbik_device.hpp"
+#include "tbik_internal.hpp"
+
+namespace tbik {
+
+constexpr int ATT_D = 128;    // head dimension
+constexpr int ATT_BQ = 128;   // queries per workgroup
+constexpr int ATT_KV = 64;    // keys per tile: part of the result, never tuned per call
+constexpr int ATT_TILE_BYTES = ATT_KV * ATT_D * 2;
+
+typedef short att_v4i16 __attribute__((ext_vector_type(4)));
+typedef unsigned int att_u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int att_u32x2 __attribute__((ext_vector_type(2)));
+
+struct AttnParams {
+    const uint16_t *Q, *K, *V;
+    uint16_t *O;
+    const int32_t *cu_q, *cu_k;
+    int64_t q_stride, k_stride, v_stride, o_stride;   // token strides, elements
+    int total_q, total_k;
+    int group;                                        // query heads per key/value head
+    float c;                                          // scale * log2(e)
+};
+
+__device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+template <bool CAUSAL>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void attention_kernel(const AttnParams p) {
+    // LDS: K tile [2][64 keys][256 B], then V tile [2][64 keys][256 B].
+    //   K rows: 16-byte chunk c of key r sits at position c ^ (r & 15): the 16 rows of a fragment read hit all banks.
+    //   V rows: chunk c of key r sits at position c ^ (4 (r & 3)): the 4 rows of a transposing read differ in banks.
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char *const k_lds = smem;
+    unsigned char *const v_lds = smem + 2 * ATT_TILE_BYTES;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 31, lg = lane >> 5;
+    const int seq = blockIdx.z, head = blockIdx.y;
+    const int qb = (int)gridDim.x - 1 - (int)blockIdx.x;          // long (late) blocks first
+
+    // Sequence bounds, clamped so that no value of the offset arrays can lead outside the tensors.
+    const int q0 = clampi(p.cu_q[seq], 0, p.total_q), q1 = clampi(p.cu_q[seq + 1], q0, p.total_q);
+    const int k0 = clampi(p.cu_k[seq], 0, p.total_k), k1 = clampi(p.cu_k[seq + 1], k0, p.total_k);
+    const int Lq = q1 - q0, Lk = k1 - k0;
+    if (qb * ATT_BQ >= Lq) return;                                // uniform: nothing of this sequence in the block
+    const int shift = Lk - Lq;                                    // the queries are the last Lq positions
+    const int hk = head / p.group;
+
+    const int q_last = min(Lq - 1, qb * ATT_BQ + ATT_BQ - 1);
+    const int lim_block = CAUSAL ? min(Lk - 1, q_last + shift) : Lk - 1;
+    const int n_tiles = lim_block >= 0 ? lim_block / ATT_KV + 1 : 0;
+
+    // This lane's query (rows past the sequence repeat its last query; they are never stored).
+    const int qrow = qb * ATT_BQ + wave * 32 + li;
+    const int qpos = min(qrow, Lq - 1);
+    const int lim = CAUSAL ? min(Lk - 1, qpos + shift) : Lk - 1; // last visible key of this query; < 0: none
+    // The wavefront as a whole: tiles it has to multiply, and the keys that every one of its rows sees.
+    const int wave_first = qb * ATT_BQ + wave * 32;
+    const int wave_lim = CAUSAL ? min(Lk - 1, min(Lq - 1, wave_first + 31) + shift) : Lk - 1;
+    const int wave_tiles = (wave_first < Lq && wave_lim >= 0) ? wave_lim / ATT_KV + 1 : 0;
+    const int wave_full = CAUSAL ? min(Lk - 1, min(Lq - 1, wave_first) + shift) : Lk - 1;
+
+    // Q^T fragments: lane (query li, half lg) holds channels 16 ks + 8 lg .. + 7 of its query.
+    bf16x8 bq[ATT_D / 16];
+    {
+        const uint16_t *qptr = p.Q + (int64_t)(q0 + qpos) * p.q_stride + (int64_t)head * ATT_D + lg * 8;
+#pragma unroll
+        for (int ks = 0; ks < ATT_D / 16; ++ks) bq[ks] = *reinterpret_cast<const bf16x8 *>(qptr + ks * 16);
+    }
+
+    // Tile loader: thread -> (key ld_row + 16 pass, 16-byte chunk ld_chunk); keys past the sequence repeat the last key
+    // (they are masked).
+    const int ld_chunk = tid & 15, ld_row = tid >> 4;
+    const uint16_t *kbase = p.K + (int64_t)k0 * p.k_stride + (int64_t)hk * ATT_D + ld_chunk * 8;
+    const uint16_t *vbase = p.V + (int64_t)k0 * p.v_stride + (int64_t)hk * ATT_D + ld_chunk * 8;
+    const int k_wr = ld_row * 256 + ((ld_chunk ^ ld_row) << 4);               // + pass * 4096; (key & 15) == ld_row
+    const int v_wr = ld_row * 256 + ((ld_chunk ^ ((ld_row & 3) << 2)) << 4);
+    att_u32x4 kr[4], vr[4];
+    auto fetch = [&](int t) {
+#pragma unroll
+        for (int ps = 0; ps < 4; ++ps) {
+            const int key = min(t * ATT_KV + ps * 16 + ld_row, Lk - 1);
+            kr[ps] = *reinterpret_cast<const att_u32x4 *>(kbase + (int64_t)key * p.k_stride);
+            vr[ps] = *reinterpret_cast<const att_u32x4 *>(vbase + (int64_t)key * p.v_stride);
+        }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int ps = 0; ps < 4; ++ps) {
+            *reinterpret_cast<att_u32x4 *>(k_lds + buf * ATT_TILE_BYTES + ps * 4096 + k_wr) = kr[ps];
+            *reinterpret_cast<att_u32x4 *>(v_lds + buf * ATT_TILE_BYTES + ps * 4096 + v_wr) = vr[ps];
+        }
+    };
+
+    // Fragment addresses inside a tile.
+    //   K, block kb, step ks: key 32 kb + li, chunk 2 ks + lg.
+    const int k_rd = li * 256;                                   // + kb * 8192; chunk swizzled per step: (2 ks + lg) ^ (li & 15)
+    //   V^T, channel block db, step s (kb = s / 2, h = s % 2), half hh: rows 32 kb + 16 h + 8 hh + 4 lg + e, e = l16 / 4,
+    //   columns 32 db + 16 ((lane / 16) % 2) + 4 (l16 % 4) .. + 3 before the transpose.
+    const int l16 = lane & 15, e = l16 >> 2;
+    int v_rd[ATT_D / 32];
+#pragma unroll
+    for (int db = 0; db < ATT_D / 32; ++db) {
+        const int col = db * 32 + ((lane >> 4) & 1) * 16 + (l16 & 3) * 4;
+        v_rd[db] = (4 * lg + e) * 256 + ((((col >> 3) ^ (e << 2))) << 4) + ((col >> 2) & 1) * 8;
+    }
+
+    f32x16 o[ATT_D / 32];
+#pragma unroll
+    for (int db = 0; db < ATT_D / 32; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] = 0.0f;
+    float m = -INFINITY, l = 0.0f;
+
+    if (n_tiles > 0) {
+        fetch(0);
+        stash(0);
+    }
+    __syncthreads();
+
+    for (int t = 0; t < n_tiles; ++t) {
+        const int buf = t & 1;
+        const bool more = t + 1 < n_tiles;
+        if (more) fetch(t + 1);                                   // in flight while this tile is multiplied
+
+        if (t < wave_tiles) {
+            const unsigned char *kt = k_lds + buf * ATT_TILE_BYTES;
+            const unsigned char *vt = v_lds + buf * ATT_TILE_BYTES;
+            // ---- S^T = K Q^T ----
+            f32x16 s[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[kb][r] = 0.0f;
+#pragma unroll
+                for (int ks = 0; ks < ATT_D / 16; ++ks) {
+                    const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kt + kb * 8192 + k_rd + (((2 * ks + lg) ^ (li & 15)) << 4));
+                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, bq[ks], s[kb], 0, 0, 0);
+                }
+            }
+            // ---- scale, mask, running maximum ----
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[kb][r] = s[kb][r] * p.c;
+            if (t * ATT_KV + ATT_KV - 1 > wave_full) {            // uniform: some row of the wavefront does not see the whole tile
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = t * ATT_KV + kb * 32 + 8 * (r >> 2) + 4 * lg + (r & 3);
+                        if (key > lim) s[kb][r] = -INFINITY;
+                    }
+            }
+            float tmax = s[0][0];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[kb][r]);
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));          // the other half of this query's keys
+            const float m_new = fmaxf(m, tmax);
+            const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;   // a query that has seen no key yet
+            const float alpha = __builtin_amdgcn_exp2f(m - m_use);
+            float psum = 0.0f;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    s[kb][r] = __builtin_amdgcn_exp2f(s[kb][r] - m_use);
+                    psum = psum + s[kb][r];
+                }
+            psum = psum + __shfl_xor(psum, 32, 64);
+            l = l * alpha + psum;
+            m = m_new;
+#pragma unroll
+            for (int db = 0; db < ATT_D / 32; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[db][r] = o[db][r] * alpha;
+            // ---- O^T += V^T P^T ----
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                const int kb = st >> 1, h = st & 1;
+                union { uint32_t u[4]; bf16x8 v; } pb;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) pb.u[i] = pack_bf16x2(s[kb][8 * h + 2 * i], s[kb][8 * h + 2 * i + 1]);
+#pragma unroll
+                for (int db = 0; db < ATT_D / 32; ++db) {
+                    union { att_v4i16 h2[2]; bf16x8 v; } vf;
+#pragma unroll
+                    for (int hh = 0; hh < 2; ++hh)
+                        vf.h2[hh] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (__attribute__((address_space(3))) att_v4i16 *)(vt + (32 * kb + 16 * h + 8 * hh) * 256 + v_rd[db]));
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pb.v, o[db], 0, 0, 0);
+                }
+            }
+        }
+
+        if (more) stash(buf ^ 1);                                 // that buffer was last read before the previous barrier
+        __syncthreads();
+    }
+
+    // ---- O = o / l, one rounding to bf16; lane (query li, half lg) holds channels 32 db + 8 q + 4 lg + (0..3) ----
+    if (qrow < Lq) {
+        uint16_t *optr = p.O + (int64_t)(q0 + qrow) * p.o_stride + (int64_t)head * ATT_D + 4 * lg;
+#pragma unroll
+        for (int db = 0; db < ATT_D / 32; ++db)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float v[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = (l > 0.0f) ? o[db][4 * q + i] / l : 0.0f;
+                att_u32x2 w;
+                w[0] = pack_bf16x2(v[0], v[1]);
+                w[1] = pack_bf16x2(v[2], v[3]);
+                *reinterpret_cast<att_u32x2 *>(optr + db * 32 + 8 * q) = w;
+            }
+    }
+}
+
+hipError_t launch_attention(const AttnArgs &a, hipStream_t s) {
+    if (a.batch <= 0 || a.max_seqlen_q <= 0 || a.total_q <= 0) return hipSuccess;
+    AttnParams p;
+    p.Q = a.Q; p.K = a.K; p.V = a.V; p.O = a.O;
+    p.cu_q = a.cu_q; p.cu_k = a.cu_k;
+    p.q_stride = a.q_stride; p.k_stride = a.k_stride; p.v_stride = a.v_stride; p.o_stride = a.o_stride;
+    p.total_q = a.total_q; p.total_k = a.total_k;
+    p.group = a.heads_q / a.heads_kv;
+    p.c = a.scale * 1.44269504088896340736f;
+    const int64_t q_blocks = ((int64_t)a.max_seqlen_q + ATT_BQ - 1) / ATT_BQ;
+    if (q_blocks > 0x7fffffff || a.heads_q > 65535 || a.batch > 65535) return hipErrorInvalidValue;
+    dim3 grid((unsigned)q_blocks, (unsigned)a.heads_q, (unsigned)a.batch), block(256);
+    constexpr int lds = 4 * ATT_TILE_BYTES;
+    auto kernel = a.causal ? attention_kernel<true> : attention_kernel<false>;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 32) dev = 32;
+    static std::atomic<unsigned> lds_allowed[2] = {{0}, {0}};    // bit d: the attribute is set on device d
+    std::atomic<unsigned> &done = lds_allowed[a.causal ? 1 : 0];
+    if (dev >= 32 || !((done.load(std::memory_order_relaxed) >> dev) & 1u)) {
+        hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        if (dev < 32) done.fetch_or(1u << dev, std::memory_order_relaxed);
+    }
+    hipLaunchKernelGGL(kernel, grid, block, lds, s, p);
+    return hipGetLastError();
+}
+
+}  // namespace tbik

@@ -42,6 +42,19 @@ hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int
 hipError_t launch_combine_residual_rmsnorm(const float *partials, int P, const uint16_t *res, const uint16_t *w,
                                            uint16_t *hidden, uint16_t *normed, int M, int H, float eps, hipStream_t s);
 
+// Resolved description of one attention call; validated by the C ABI layer.
+struct AttnArgs {
+    const uint16_t *Q, *K, *V;    // bf16, token-major: [tokens, heads, 128]
+    uint16_t *O;
+    const int32_t *cu_q, *cu_k;   // device, [batch + 1]
+    int batch, max_seqlen_q, total_q, total_k;
+    int heads_q, heads_kv;
+    int64_t q_stride, k_stride, v_stride, o_stride;
+    float scale;
+    int causal;
+};
+hipError_t launch_attention(const AttnArgs &a, hipStream_t s);
+
 size_t row_reduce_workspace(int M, int64_t V, int x_dtype, int op);
 hipError_t launch_row_reduce(const void *x, int x_dtype, void *out, int op, int M, int64_t V, void *ws, hipStream_t s);
 int set_row_wait_limit(int polls);   // returns the previous limit

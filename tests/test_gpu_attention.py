@@ -1,0 +1,171 @@
+"""GPU parity and invariance tests of the fixed-tile attention (all calls go through the C ABI).
+
+Bars:
+  * GPU vs GPU: 0 bits between prefill, decode steps, chunks, batch compositions, packed positions and repetitions.
+  * Exact cases (one visible key, a dominant key, uniform weights over small integers): 0 bits against the oracle.
+  * Random data: the device's base-2 exponential and the MFMA's summation order inside a tile differ from the
+    oracle's libm and left-to-right sums in the last fp32 bits.  That moves the bf16 rounding of a weight p_j now and
+    then (by one bf16 spacing, at most 2^-7 p_j) and with it every channel of that row by up to 2^-7 p_j |v_jd| / l,
+    and it moves the rounding of an output that sits on a boundary.  With B = sum_j p_j |v_jd| / l (the magnitude
+    the weights' roundings act on), stated tolerance against the oracle:
+        every output:  |O_gpu - O_oracle| <= 2^-7 B + 2 bf16 steps of the output   (every weight flipped: cannot be exceeded)
+        in the mean:   rms(O_gpu - O_oracle) <= 2^-13 rms(B),  and at least 98 % of the outputs bit-equal
+    and against the plain definition in fp64: |O_gpu - O_fp64| <= 2^-8 B + 2^-8 |O_fp64|.
+"""
+import numpy as np
+import pytest
+import torch
+
+import gpu_util as gu
+from oracle import tbik_oracle as orc
+from paper_2511_17826_amd import binding as tb
+from paper_2511_17826_amd import synthetic as syn
+from test_oracle_attention import plain_attention_fp64
+
+pytestmark = pytest.mark.gpu
+
+
+def i32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to("cuda:0")
+
+
+def run(c, causal=True, max_q=None):
+    Q, K, V = gu.dev_bf16(c["Q"]), gu.dev_bf16(c["K"]), gu.dev_bf16(c["V"])
+    if max_q is None:
+        max_q = int(np.max(np.diff(c["cu_q"]))) if len(c["cu_q"]) > 1 else 0
+    O = tb.tbik_attention(Q, K, V, i32(c["cu_q"]), i32(c["cu_k"]), max_q, c["scale"], causal)
+    torch.cuda.synchronize()
+    return gu.host_bf16_bits(O)
+
+
+def check_against_oracle(O, c, causal):
+    Oo, O32 = orc.attention(c["Q"], c["K"], c["V"], c["cu_q"], c["cu_k"], c["scale"], causal)
+    want64, B = plain_attention_fp64(c, causal)
+    g = syn.bf16_bits_to_f32(O).astype(np.float64)
+    o = syn.bf16_bits_to_f32(Oo).astype(np.float64)
+    assert np.all(np.abs(g - want64) <= 2.0 ** -8 * B + 2.0 ** -8 * np.abs(want64) + 1e-30)
+    mag = np.maximum(np.abs(g), np.abs(o))
+    step = 2.0 ** (np.floor(np.log2(np.maximum(mag, 2.0 ** -126))) - 7)
+    assert np.all(np.abs(g - o) <= 2.0 ** -7 * B + 2 * step), float(np.max(np.abs(g - o) / (2.0 ** -7 * B + 2 * step)))
+    equal = np.count_nonzero(O == Oo) / O.size
+    rms = float(np.sqrt(np.mean((g - o) ** 2)) / max(np.sqrt(np.mean(B ** 2)), 1e-30))
+    print("attention vs oracle: %.4f of the outputs bit-equal, rms difference / rms B = 2^%.1f" % (equal, np.log2(max(rms, 1e-30))))
+    assert rms <= 2.0 ** -13 and equal >= 0.98, (rms, equal)
+    return equal
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_mixed_batch_against_oracle(causal):
+    """Prefill, decode, chunk and ragged lengths in one call; 8 query heads over 2 key/value heads."""
+    c = syn.attention_inputs(51, [300, 1, 130, 17, 64], [300, 257, 200, 17, 64], Hq=8, Hkv=2, D=128)
+    O = run(c, causal)
+    check_against_oracle(O, c, causal)
+
+
+def test_one_visible_key_dominant_key_and_uniform_weights_exact():
+    c = syn.attention_inputs(52, [5, 130], [5, 130], Hq=4, Hkv=2, D=128)
+    O = run(c)
+    for b in range(2):
+        q0, k0 = c["cu_q"][b], c["cu_k"][b]
+        for h in range(4):
+            assert np.array_equal(O[q0, h], c["V"][k0, h // 2])
+    # dominant key in the second tile
+    D, Lk = 128, 150
+    c = syn.attention_inputs(53, [1], [Lk], Hq=1, Hkv=1, D=D, std=0.25)
+    q = np.zeros(D, dtype=np.float32); q[0] = 32.0
+    K = syn.bf16_bits_to_f32(c["K"]).copy(); K[:, 0, 0] = 0.0; K[100, 0, 0] = 64.0
+    c["Q"][0, 0] = syn.f32_to_bf16_bits(q)
+    c["K"] = syn.f32_to_bf16_bits(K)
+    c["scale"] = 1.0
+    assert np.array_equal(run(c)[0, 0], c["V"][100, 0])
+    # uniform weights
+    for Lk in (64, 256):
+        rng = np.random.Generator(np.random.PCG64(54))
+        V = rng.integers(-8, 9, size=(Lk, 1, D)).astype(np.float32)
+        Kr = rng.standard_normal((Lk, 1, D)).astype(np.float32)
+        c = dict(Q=syn.f32_to_bf16_bits(np.zeros((1, 1, D), dtype=np.float32)), K=syn.f32_to_bf16_bits(Kr),
+                 V=syn.f32_to_bf16_bits(V), cu_q=np.array([0, 1], dtype=np.int32), cu_k=np.array([0, Lk], dtype=np.int32), scale=0.5)
+        want = syn.f32_to_bf16_bits((V.sum(axis=0) / Lk).astype(np.float32))
+        assert np.array_equal(run(c)[0], want)
+
+
+def test_prefill_decode_chunks_batch_and_repetition_give_the_same_bits():
+    L = 700
+    c = syn.attention_inputs(55, [L], [L], Hq=8, Hkv=2, D=128)
+    O = run(c)
+    assert np.array_equal(run(c), O)
+    Q, K, V = gu.dev_bf16(c["Q"]), gu.dev_bf16(c["K"]), gu.dev_bf16(c["V"])
+    # decode steps: one query, i + 1 keys -- several of them in one call, each a sequence of its own
+    steps = [0, 1, 63, 64, 127, 128, 300, 699]
+    Qd = torch.cat([Q[i:i + 1] for i in steps])
+    Kd = torch.cat([K[:i + 1] for i in steps])
+    Vd = torch.cat([V[:i + 1] for i in steps])
+    cu_q = np.arange(len(steps) + 1)
+    cu_k = np.concatenate([[0], np.cumsum([i + 1 for i in steps])])
+    Od = gu.host_bf16_bits(tb.tbik_attention(Qd, Kd, Vd, i32(cu_q), i32(cu_k), 1, c["scale"], True))
+    for n, i in enumerate(steps):
+        assert np.array_equal(Od[n], O[i]), i
+    # a chunk in the middle (queries 250..449 against keys 0..449), at an odd place of a larger batch
+    other = syn.attention_inputs(56, [40, 7], [40, 90], Hq=8, Hkv=2, D=128)
+    Qo, Ko, Vo = gu.dev_bf16(other["Q"]), gu.dev_bf16(other["K"]), gu.dev_bf16(other["V"])
+    Qb = torch.cat([Qo[:40], Q[250:450], Qo[40:]])
+    Kb = torch.cat([Ko[:40], K[:450], Ko[40:]])
+    Vb = torch.cat([Vo[:40], V[:450], Vo[40:]])
+    Ob = gu.host_bf16_bits(tb.tbik_attention(Qb, Kb, Vb, i32([0, 40, 240, 247]), i32([0, 40, 490, 580]), 200, c["scale"], True))
+    assert np.array_equal(Ob[40:240], O[250:450])
+    # the rest of that batch is the other two sequences on their own
+    assert np.array_equal(np.concatenate([Ob[:40], Ob[240:]]), run(other))
+
+
+def test_strided_tokens_and_queries_without_keys():
+    """Q, K, V as slices of one fused projection output (token stride larger than heads * 128); more queries than keys."""
+    Hq, Hkv, D = 4, 2, 128
+    c = syn.attention_inputs(57, [70, 6], [70, 4], Hq=Hq, Hkv=Hkv, D=D)
+    T = c["Q"].shape[0]
+    Tk = c["K"].shape[0]
+    fused = torch.zeros((max(T, Tk), (Hq + 2 * Hkv) * D), dtype=torch.bfloat16, device="cuda:0")
+    fused[:T, :Hq * D] = gu.dev_bf16(c["Q"]).reshape(T, -1)
+    fused[:Tk, Hq * D:(Hq + Hkv) * D] = gu.dev_bf16(c["K"]).reshape(Tk, -1)
+    fused[:Tk, (Hq + Hkv) * D:] = gu.dev_bf16(c["V"]).reshape(Tk, -1)
+    Qv = torch.as_strided(fused, (T, Hq, D), (fused.stride(0), D, 1), 0)
+    Kv = torch.as_strided(fused, (Tk, Hkv, D), (fused.stride(0), D, 1), Hq * D)
+    Vv = torch.as_strided(fused, (Tk, Hkv, D), (fused.stride(0), D, 1), (Hq + Hkv) * D)
+    O = gu.host_bf16_bits(tb.tbik_attention(Qv, Kv, Vv, i32(c["cu_q"]), i32(c["cu_k"]), 70, c["scale"], True))
+    assert np.array_equal(O, run(c))
+    assert not O[70:72].any()                                          # queries that precede every key
+    Oo, _ = orc.attention(c["Q"], c["K"], c["V"], c["cu_q"], c["cu_k"], c["scale"], True)
+    assert np.array_equal(O[72, 0], Oo[72, 0])                         # sees one key: exact
+
+
+def test_8b_shape_sampled_parity():
+    """32 query heads over 8 key/value heads, head dimension 128, a 2048-token prefill next to decode steps with long
+    contexts: the oracle on a sample of (sequence, query) rows, every head and channel of them."""
+    c = syn.attention_inputs(58, [2048, 1, 1, 333], [2048, 4096, 1000, 333], Hq=32, Hkv=8, D=128)
+    O = run(c)
+    rng = np.random.Generator(np.random.PCG64(59))
+    picks = [(0, int(i)) for i in rng.integers(0, 2048, size=6)] + [(0, 0), (0, 2047), (1, 0), (2, 0), (3, 332), (3, 100)]
+    for b, i in picks:
+        q0, k0 = int(c["cu_q"][b]), int(c["cu_k"][b])
+        Lq, Lk = int(c["cu_q"][b + 1]) - q0, int(c["cu_k"][b + 1]) - k0
+        nk = i + Lk - Lq + 1
+        sub = dict(Q=c["Q"][q0 + i:q0 + i + 1], K=c["K"][k0:k0 + nk], V=c["V"][k0:k0 + nk],
+                   cu_q=np.array([0, 1], dtype=np.int32), cu_k=np.array([0, nk], dtype=np.int32),
+                   Hq=32, Hkv=8, D=128, scale=c["scale"])
+        check_against_oracle(O[q0 + i:q0 + i + 1], sub, True)
+
+
+def test_argument_validation_on_the_device():
+    Q = torch.zeros((4, 2, 64), dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(tb.TbikError) as e:
+        tb.tbik_attention(Q, Q, Q, i32([0, 4]), i32([0, 4]), 4, 1.0)
+    assert e.value.status == 7                                         # head dimension 64 is not offered
+    Q = torch.zeros((4, 3, 128), dtype=torch.bfloat16, device="cuda:0")
+    K = torch.zeros((4, 2, 128), dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(tb.TbikError) as e:
+        tb.tbik_attention(Q, K, K, i32([0, 4]), i32([0, 4]), 4, 1.0)
+    assert e.value.status == 2
+    # offsets that point outside the tensors are clamped, not followed
+    Q = torch.randn((8, 2, 128), device="cuda:0").to(torch.bfloat16)
+    O = tb.tbik_attention(Q, Q, Q, i32([0, 1 << 30]), i32([-5, 1 << 30]), 8, 1.0)
+    torch.cuda.synchronize()
+    assert torch.equal(O, tb.tbik_attention(Q, Q, Q, i32([0, 8]), i32([0, 8]), 8, 1.0))
