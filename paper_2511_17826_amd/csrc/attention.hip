@@ -2,7 +2,12 @@
 // (the attention rule of the paper's implementation appendix, "Framework Modifications": fix the tile size, run
 // prefill and decode through the same kernel; Sec. 2.1: fp32 accumulators).
 //
-// A workgroup of 4 wavefronts owns 128 consecutive queries of one (sequence, head); a wavefront owns 32 of them.
+// A workgroup of 4 wavefronts owns 128 query rows of one sequence that share ONE key/value head, so that a key tile
+// is fetched once for all of them: with `pack` query heads per key/value head packed into a workgroup, row slot s
+// is query (128 / pack) * block + s % (128 / pack) of query head pack * kvhead + s / (128 / pack).  (pack = the size
+// of a head group when that is a power of two up to 128, else 1.)  A decode step (one query per sequence) then
+// costs one pass over the keys per key/value head instead of one per query head.  Which slot a query lands in has
+// no influence on its bits.
 // The keys of the sequence are visited in tiles of ATT_KV = 64 at absolute positions [64 t, 64 t + 64), in
 // ascending order, with the streaming-softmax recurrence per query row:
 //     s_j = (q . k_j) * c            c = scale * log2(e), fp32
@@ -41,6 +46,8 @@ struct AttnParams {
     int64_t q_stride, k_stride, v_stride, o_stride;   // token strides, elements
     int total_q, total_k;
     int group;                                        // query heads per key/value head
+    int pack;                                         // query heads per workgroup (group or 1)
+    int rows;                                         // queries per head and workgroup: 128 / pack
     float c;                                          // scale * log2(e)
 };
 
@@ -60,28 +67,31 @@ void attention_kernel(const AttnParams p) {
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 31, lg = lane >> 5;
-    const int seq = blockIdx.z, head = blockIdx.y;
+    const int seq = blockIdx.z;
     const int qb = (int)gridDim.x - 1 - (int)blockIdx.x;          // long (late) blocks first
+    const int R = p.rows;
 
     // Sequence bounds, clamped so that no value of the offset arrays can lead outside the tensors.
     const int q0 = clampi(p.cu_q[seq], 0, p.total_q), q1 = clampi(p.cu_q[seq + 1], q0, p.total_q);
     const int k0 = clampi(p.cu_k[seq], 0, p.total_k), k1 = clampi(p.cu_k[seq + 1], k0, p.total_k);
     const int Lq = q1 - q0, Lk = k1 - k0;
-    if (qb * ATT_BQ >= Lq) return;                                // uniform: nothing of this sequence in the block
+    if (qb * R >= Lq) return;                                     // uniform: nothing of this sequence in the block
     const int shift = Lk - Lq;                                    // the queries are the last Lq positions
-    const int hk = head / p.group;
+    const int slot = wave * 32 + li;
+    const int head = (int)blockIdx.y * p.pack + slot / R;
+    const int hk = ((int)blockIdx.y * p.pack) / p.group;
 
-    const int q_last = min(Lq - 1, qb * ATT_BQ + ATT_BQ - 1);
+    const int q_last = min(Lq - 1, qb * R + R - 1);
     const int lim_block = CAUSAL ? min(Lk - 1, q_last + shift) : Lk - 1;
     const int n_tiles = lim_block >= 0 ? lim_block / ATT_KV + 1 : 0;
 
     // This lane's query (rows past the sequence repeat its last query; they are never stored).
-    const int qrow = qb * ATT_BQ + wave * 32 + li;
+    const int qrow = qb * R + slot % R;
     const int qpos = min(qrow, Lq - 1);
     const int lim = CAUSAL ? min(Lk - 1, qpos + shift) : Lk - 1; // last visible key of this query; < 0: none
     // The wavefront as a whole: tiles it has to multiply, and the keys that every one of its rows sees.
-    const int wave_first = qb * ATT_BQ + wave * 32;
-    const int wave_lim = CAUSAL ? min(Lk - 1, min(Lq - 1, wave_first + 31) + shift) : Lk - 1;
+    const int wave_first = qb * R + (wave * 32) % R;              // R >= 32: 32 consecutive queries; R < 32: all R of the block
+    const int wave_lim = CAUSAL ? min(Lk - 1, min(Lq - 1, wave_first + min(R, 32) - 1) + shift) : Lk - 1;
     const int wave_tiles = (wave_first < Lq && wave_lim >= 0) ? wave_lim / ATT_KV + 1 : 0;
     const int wave_full = CAUSAL ? min(Lk - 1, min(Lq - 1, wave_first) + shift) : Lk - 1;
 
@@ -250,10 +260,12 @@ hipError_t launch_attention(const AttnArgs &a, hipStream_t s) {
     p.q_stride = a.q_stride; p.k_stride = a.k_stride; p.v_stride = a.v_stride; p.o_stride = a.o_stride;
     p.total_q = a.total_q; p.total_k = a.total_k;
     p.group = a.heads_q / a.heads_kv;
+    p.pack = (p.group <= ATT_BQ && (p.group & (p.group - 1)) == 0) ? p.group : 1;
+    p.rows = ATT_BQ / p.pack;
     p.c = a.scale * 1.44269504088896340736f;
-    const int64_t q_blocks = ((int64_t)a.max_seqlen_q + ATT_BQ - 1) / ATT_BQ;
+    const int64_t q_blocks = ((int64_t)a.max_seqlen_q + p.rows - 1) / p.rows;
     if (q_blocks > 0x7fffffff || a.heads_q > 65535 || a.batch > 65535) return hipErrorInvalidValue;
-    dim3 grid((unsigned)q_blocks, (unsigned)a.heads_q, (unsigned)a.batch), block(256);
+    dim3 grid((unsigned)q_blocks, (unsigned)(a.heads_q / p.pack), (unsigned)a.batch), block(256);
     constexpr int lds = 4 * ATT_TILE_BYTES;
     auto kernel = a.causal ? attention_kernel<true> : attention_kernel<false>;
     int dev = 0;
