@@ -173,7 +173,7 @@ int tbik_row_reduce(const void *x, tbik_dtype x_dtype, void *out, tbik_rowop op,
  *          counts; values are clamped to [0, total_q] / [0, total_k] inside the kernel
  *   max_seqlen_q   at least the largest Lq (queries past it are not computed); total_q, total_k: tokens in Q/O and K/V
  *   head_dim 128 (other values: TBIK_ERR_UNSUPPORTED); heads_q a multiple of heads_kv; strides in elements, multiples
- *   of 8, at least heads * head_dim; pointers 16-byte aligned.  O must not overlap Q, K or V.
+ *   of 8, at least heads * head_dim, below 2^24; pointers 16-byte aligned.  O must not overlap Q, K or V.
  * Errors: NULL, SHAPE, UNSUPPORTED, ALIGN, HIP.
  */
 int tbik_attention(const void *Q, const void *K, const void *V, void *O,

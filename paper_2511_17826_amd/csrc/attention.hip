@@ -24,6 +24,7 @@
 // The MFMA's k-slot (g, t) of step s stands for key 32 kb + 16 h + 8 (t / 4) + 4 g + t % 4 (kb = s / 2, h = s % 2): the
 // order in which the result layout of S^T hands the keys to a lane; V^T is fetched in the same order.
 #include <atomic>
+#include <type_traits>
 
 #include "tbik_device.hpp"
 #include "tbik_internal.hpp"
@@ -106,17 +107,34 @@ void attention_kernel(const AttnParams p) {
     // Tile loader: thread -> (key ld_row + 16 pass, 16-byte chunk ld_chunk); keys past the sequence repeat the last key
     // (they are masked).
     const int ld_chunk = tid & 15, ld_row = tid >> 4;
-    const uint16_t *kbase = p.K + (int64_t)k0 * p.k_stride + (int64_t)hk * ATT_D + ld_chunk * 8;
-    const uint16_t *vbase = p.V + (int64_t)k0 * p.v_stride + (int64_t)hk * ATT_D + ld_chunk * 8;
+    const uint16_t *kbase = p.K + (int64_t)k0 * p.k_stride + (int64_t)hk * ATT_D;     // wave-uniform
+    const uint16_t *vbase = p.V + (int64_t)k0 * p.v_stride + (int64_t)hk * ATT_D;
     const int k_wr = ld_row * 256 + ((ld_chunk ^ ld_row) << 4);               // + pass * 4096; (key & 15) == ld_row
     const int v_wr = ld_row * 256 + ((ld_chunk ^ ((ld_row & 3) << 2)) << 4);
+    // A load's address is a uniform tile base plus a 32-bit lane offset (token strides are below 2^24 elements).
+    unsigned k_ld[4], v_ld[4];
+#pragma unroll
+    for (int ps = 0; ps < 4; ++ps) {
+        k_ld[ps] = (unsigned)(ps * 16 + ld_row) * (unsigned)p.k_stride + ld_chunk * 8;
+        v_ld[ps] = (unsigned)(ps * 16 + ld_row) * (unsigned)p.v_stride + ld_chunk * 8;
+    }
     att_u32x4 kr[4], vr[4];
     auto fetch = [&](int t) {
+        const uint16_t *kt = kbase + (int64_t)t * ATT_KV * p.k_stride;
+        const uint16_t *vt = vbase + (int64_t)t * ATT_KV * p.v_stride;
+        if (__builtin_expect(t * ATT_KV + ATT_KV <= Lk, 1)) {      // uniform: the whole tile lies inside the sequence
 #pragma unroll
-        for (int ps = 0; ps < 4; ++ps) {
-            const int key = min(t * ATT_KV + ps * 16 + ld_row, Lk - 1);
-            kr[ps] = *reinterpret_cast<const att_u32x4 *>(kbase + (int64_t)key * p.k_stride);
-            vr[ps] = *reinterpret_cast<const att_u32x4 *>(vbase + (int64_t)key * p.v_stride);
+            for (int ps = 0; ps < 4; ++ps) {
+                kr[ps] = *reinterpret_cast<const att_u32x4 *>(kt + k_ld[ps]);
+                vr[ps] = *reinterpret_cast<const att_u32x4 *>(vt + v_ld[ps]);
+            }
+        } else {
+#pragma unroll
+            for (int ps = 0; ps < 4; ++ps) {
+                const int key = min(ps * 16 + ld_row, Lk - 1 - t * ATT_KV);    // >= 0: the tile holds at least one key
+                kr[ps] = *reinterpret_cast<const att_u32x4 *>(kt + (unsigned)key * (unsigned)p.k_stride + ld_chunk * 8);
+                vr[ps] = *reinterpret_cast<const att_u32x4 *>(vt + (unsigned)key * (unsigned)p.v_stride + ld_chunk * 8);
+            }
         }
     };
     auto stash = [&](int buf) {
@@ -147,20 +165,27 @@ void attention_kernel(const AttnParams p) {
         for (int r = 0; r < 16; ++r) o[db][r] = 0.0f;
     float m = -INFINITY, l = 0.0f;
 
-    if (n_tiles > 0) {
-        fetch(0);
-        stash(0);
+    if (n_tiles == 0) {                                           // uniform: no query of the block sees a key
+        if (qrow < Lq) {
+            uint16_t *optr = p.O + (int64_t)(q0 + qrow) * p.o_stride + (int64_t)head * ATT_D + lg * 64;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) *reinterpret_cast<att_u32x4 *>(optr + 8 * i) = att_u32x4{0, 0, 0, 0};
+        }
+        return;
     }
+    fetch(0);
+    stash(0);
     __syncthreads();
 
-    for (int t = 0; t < n_tiles; ++t) {
-        const int buf = t & 1;
+    // One key tile out of LDS buffer BUF; the next tile is fetched meanwhile and parked in the other buffer.
+    auto tile = [&](auto buf_tag, int t) {
+        constexpr int BUF = decltype(buf_tag)::value;
         const bool more = t + 1 < n_tiles;
         if (more) fetch(t + 1);                                   // in flight while this tile is multiplied
 
         if (t < wave_tiles) {
-            const unsigned char *kt = k_lds + buf * ATT_TILE_BYTES;
-            const unsigned char *vt = v_lds + buf * ATT_TILE_BYTES;
+            const unsigned char *kt = k_lds + BUF * ATT_TILE_BYTES;
+            const unsigned char *vt = v_lds + BUF * ATT_TILE_BYTES;
             // ---- S^T = K Q^T ----
             f32x16 s[2];
 #pragma unroll
@@ -207,10 +232,12 @@ void attention_kernel(const AttnParams p) {
             psum = psum + __shfl_xor(psum, 32, 64);
             l = l * alpha + psum;
             m = m_new;
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {   // uniform: o * 1 is o, so skipping changes no bit
 #pragma unroll
-            for (int db = 0; db < ATT_D / 32; ++db)
+                for (int db = 0; db < ATT_D / 32; ++db)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) o[db][r] = o[db][r] * alpha;
+                    for (int r = 0; r < 16; ++r) o[db][r] = o[db][r] * alpha;
+            }
             // ---- O^T += V^T P^T ----
 #pragma unroll
             for (int st = 0; st < 4; ++st) {
@@ -230,8 +257,13 @@ void attention_kernel(const AttnParams p) {
             }
         }
 
-        if (more) stash(buf ^ 1);                                 // that buffer was last read before the previous barrier
+
+        if (more) stash(BUF ^ 1);                                 // that buffer was last read before the previous barrier
         __syncthreads();
+    };
+    for (int t = 0; t < n_tiles; t += 2) {
+        tile(std::integral_constant<int, 0>{}, t);
+        if (t + 1 < n_tiles) tile(std::integral_constant<int, 1>{}, t + 1);
     }
 
     // ---- O = o / l, one rounding to bf16; lane (query li, half lg) holds channels 32 db + 8 q + 4 lg + (0..3) ----

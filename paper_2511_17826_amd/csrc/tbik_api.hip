@@ -234,6 +234,7 @@ int tbik_attention(const void *Q, const void *K, const void *V, void *O,
         return TBIK_ERR_SHAPE;
     if (heads_q % heads_kv != 0 || heads_q > 65535 || batch > 65535) return TBIK_ERR_SHAPE;
     if (head_dim != 128) return TBIK_ERR_UNSUPPORTED;
+    if (q_stride >= (1 << 24) || k_stride >= (1 << 24) || v_stride >= (1 << 24) || o_stride >= (1 << 24)) return TBIK_ERR_SHAPE;
     if (q_stride < (int64_t)heads_q * head_dim || o_stride < (int64_t)heads_q * head_dim ||
         k_stride < (int64_t)heads_kv * head_dim || v_stride < (int64_t)heads_kv * head_dim)
         return TBIK_ERR_SHAPE;
