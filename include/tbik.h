@@ -171,7 +171,8 @@ int tbik_row_reduce(const void *x, tbik_dtype x_dtype, void *out, tbik_rowop op,
  *   K, V   device, bf16, same layout with heads_kv heads; query head h reads key/value head h / (heads_q / heads_kv)
  *   cu_seqlens_q, cu_seqlens_k   DEVICE, int32 [batch + 1], non-decreasing prefix sums of the sequences' query and key
  *          counts; values are clamped to [0, total_q] / [0, total_k] inside the kernel
- *   max_seqlen_q   at least the largest Lq (queries past it are not computed); total_q, total_k: tokens in Q/O and K/V
+ *   max_seqlen_q   at least the largest Lq (with a smaller value some queries past it are left unwritten);
+ *          total_q, total_k: tokens in Q/O and in K/V
  *   head_dim 128 (other values: TBIK_ERR_UNSUPPORTED); heads_q a multiple of heads_kv; strides in elements, multiples
  *   of 8, at least heads * head_dim, below 2^24; pointers 16-byte aligned.  O must not overlap Q, K or V.
  * Errors: NULL, SHAPE, UNSUPPORTED, ALIGN, HIP.

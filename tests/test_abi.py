@@ -93,6 +93,21 @@ def test_fp16_entry_points_validate_like_the_bf16_ones(L):
     assert L.tbik_row_reduce(GOOD, 2, GOOD, 0, 4, 1024, GOOD, 1 << 20, None) == 4              # fp16 rows are not
 
 
+def test_attention_argument_validation(L):
+    def att(**kw):
+        a = dict(Q=GOOD, K=GOOD, V=GOOD, O=GOOD, cq=GOOD, ck=GOOD, batch=2, mq=8, tq=16, tk=16, hq=4, hkv=2, d=128,
+                 sq=512, sk=256, sv=256, so=512, scale=0.1, causal=1)
+        a.update(kw)
+        return L.tbik_attention(a["Q"], a["K"], a["V"], a["O"], a["cq"], a["ck"], a["batch"], a["mq"], a["tq"], a["tk"],
+                                a["hq"], a["hkv"], a["d"], a["sq"], a["sk"], a["sv"], a["so"], a["scale"], a["causal"], None)
+    assert att(batch=0) == 0 and att(mq=0) == 0 and att(tq=0) == 0            # nothing to do: OK before any pointer is looked at
+    assert att(batch=-1) == 2 and att(hq=5) == 2 and att(hkv=0) == 2          # heads_q must be a multiple of heads_kv
+    assert att(sq=500) == 2 and att(sk=128) == 2 and att(so=1 << 24) == 2     # token stride below heads * 128, or too large
+    assert att(d=64) == 7                                                     # only head dimension 128 is built
+    assert att(Q=None) == 1 and att(cq=None) == 1 and att(K=None) == 1
+    assert att(Q=GOOD + 2) == 5 and att(sk=260) == 5 and att(ck=GOOD + 2) == 5
+
+
 def test_shard_and_combine_validation(L):
     sp = L.tbik_gemm_shard_partials
     args = lambda P, part=GOOD: (GOOD, 512, GOOD, 256, part, 4, 256, 512, 64, 1, P, None, 0, None)

@@ -62,6 +62,42 @@ def test_mixed_batch_against_oracle(causal):
     check_against_oracle(O, c, causal)
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (4, 2), (8, 1), (6, 2), (16, 1), (3, 3)])
+def test_head_groupings_against_oracle_and_each_other(Hq, Hkv):
+    """Every way the query heads of a group are packed into a workgroup (1, 2, 4, 8, 16 heads; a group of 3 is not
+    packed): parity with the oracle, and the bits of a head do not depend on the packing -- the same Q head against
+    the same K/V head gives the same output when it is the only head of the call."""
+    c = syn.attention_inputs(60 + Hq, [150, 1, 40], [150, 99, 70], Hq=Hq, Hkv=Hkv, D=128)
+    for causal in (True, False):
+        O = run(c, causal)
+        check_against_oracle(O, c, causal)
+        h = Hq - 1
+        hk = h // (Hq // Hkv)
+        one = dict(c, Q=np.ascontiguousarray(c["Q"][:, h:h + 1]), K=np.ascontiguousarray(c["K"][:, hk:hk + 1]),
+                   V=np.ascontiguousarray(c["V"][:, hk:hk + 1]), Hq=1, Hkv=1)
+        assert np.array_equal(run(one, causal)[:, 0], O[:, h]), causal
+
+
+def test_empty_calls_and_sequences_without_keys():
+    Q = torch.zeros((0, 4, 128), dtype=torch.bfloat16, device="cuda:0")
+    K = torch.zeros((0, 2, 128), dtype=torch.bfloat16, device="cuda:0")
+    assert tb.tbik_attention(Q, K, K, i32([0]), i32([0]), 0, 1.0).shape == (0, 4, 128)           # no sequence at all
+    assert tb.tbik_attention(Q, K, K, i32([0, 0]), i32([0, 0]), 0, 1.0).shape == (0, 4, 128)     # one empty sequence
+    # a sequence with queries but no keys between two ordinary ones: zeros for it, the neighbours untouched by it
+    c = syn.attention_inputs(70, [33, 5, 20], [33, 0, 64], Hq=4, Hkv=2, D=128)
+    O = torch.full((58, 4, 128), 7.0, dtype=torch.bfloat16, device="cuda:0")
+    tb.tbik_attention(gu.dev_bf16(c["Q"]), gu.dev_bf16(c["K"]), gu.dev_bf16(c["V"]), i32(c["cu_q"]), i32(c["cu_k"]), 33,
+                      c["scale"], True, out=O)
+    O = gu.host_bf16_bits(O)
+    assert not O[33:38].any()
+    Oo, _ = orc.attention(c["Q"], c["K"], c["V"], c["cu_q"], c["cu_k"], c["scale"], True)
+    assert not Oo[33:38].any()
+    keep = np.r_[0:33, 38:58]
+    sub = syn.attention_inputs(70, [33, 5, 20], [33, 0, 64], Hq=4, Hkv=2, D=128)
+    two = dict(sub, Q=sub["Q"][keep], cu_q=np.array([0, 33, 53], dtype=np.int32), cu_k=np.array([0, 33, 97], dtype=np.int32))
+    assert np.array_equal(run(two), O[keep])
+
+
 def test_one_visible_key_dominant_key_and_uniform_weights_exact():
     c = syn.attention_inputs(52, [5, 130], [5, 130], Hq=4, Hkv=2, D=128)
     O = run(c)
