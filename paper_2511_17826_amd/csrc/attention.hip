@@ -104,44 +104,48 @@ void attention_kernel(const AttnParams p) {
         for (int ks = 0; ks < ATT_D / 16; ++ks) bq[ks] = *reinterpret_cast<const bf16x8 *>(qptr + ks * 16);
     }
 
-    // Tile loader: thread -> (key ld_row + 16 pass, 16-byte chunk ld_chunk); keys past the sequence repeat the last key
-    // (they are masked).
-    const int ld_chunk = tid & 15, ld_row = tid >> 4;
+    // Tile loader: direct global->LDS loads (no staging registers).  Wavefront w fills key rows 16 w .. 16 w + 15 of a
+    // tile with 4 loads for K and 4 for V; load i covers rows 16 w + 4 i .. + 3: lane -> row r = 16 w + 4 i + lane / 16
+    // and chunk POSITION lane % 16 of that row in LDS, which holds chunk (lane % 16) ^ (r & 15) of the key's channels for K
+    // and (lane % 16) ^ 4 (r & 3) for V (the swizzle is applied on the global side).  Keys past the sequence repeat its
+    // last key (they are masked).  Token strides are below 2^24 elements, so a lane's byte offset fits 32 bits.
+    const int ld_pos = lane & 15, ld_sub = lane >> 4;
     const uint16_t *kbase = p.K + (int64_t)k0 * p.k_stride + (int64_t)hk * ATT_D;     // wave-uniform
     const uint16_t *vbase = p.V + (int64_t)k0 * p.v_stride + (int64_t)hk * ATT_D;
-    const int k_wr = ld_row * 256 + ((ld_chunk ^ ld_row) << 4);               // + pass * 4096; (key & 15) == ld_row
-    const int v_wr = ld_row * 256 + ((ld_chunk ^ ((ld_row & 3) << 2)) << 4);
-    // A load's address is a uniform tile base plus a 32-bit lane offset (token strides are below 2^24 elements).
-    unsigned k_ld[4], v_ld[4];
+    unsigned k_ld[4], v_ld[4];                                   // minus the instruction offset 1024 i, which the load adds back
 #pragma unroll
-    for (int ps = 0; ps < 4; ++ps) {
-        k_ld[ps] = (unsigned)(ps * 16 + ld_row) * (unsigned)p.k_stride + ld_chunk * 8;
-        v_ld[ps] = (unsigned)(ps * 16 + ld_row) * (unsigned)p.v_stride + ld_chunk * 8;
+    for (int i = 0; i < 4; ++i) {
+        const unsigned r = 16 * wave + 4 * i + ld_sub;
+        k_ld[i] = (r * (unsigned)p.k_stride + ((ld_pos ^ (r & 15)) << 3)) * 2u - 1024u * i;
+        v_ld[i] = (r * (unsigned)p.v_stride + ((ld_pos ^ ((r & 3) << 2)) << 3)) * 2u - 1024u * i;
     }
-    att_u32x4 kr[4], vr[4];
-    auto fetch = [&](int t) {
-        const uint16_t *kt = kbase + (int64_t)t * ATT_KV * p.k_stride;
-        const uint16_t *vt = vbase + (int64_t)t * ATT_KV * p.v_stride;
+    const unsigned smem_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    const unsigned k_m0 = smem_lds + wave * 4096;                // + buffer offset
+    const unsigned v_m0 = smem_lds + 2 * ATT_TILE_BYTES + wave * 4096;
+    // Starts the loads of tile t into the K buffer at k_off and the V buffer at v_off; they are complete (for this
+    // wavefront) after an s_waitcnt vmcnt(0).
+    auto fetch = [&](int t, int k_off, int v_off) __attribute__((always_inline)) {
+        const char *kt = uniform_pointer(reinterpret_cast<const char *>(kbase + (int64_t)t * ATT_KV * p.k_stride));
+        const char *vt = uniform_pointer(reinterpret_cast<const char *>(vbase + (int64_t)t * ATT_KV * p.v_stride));
+        const unsigned km = __builtin_amdgcn_readfirstlane(k_m0 + k_off), vm = __builtin_amdgcn_readfirstlane(v_m0 + v_off);
         if (__builtin_expect(t * ATT_KV + ATT_KV <= Lk, 1)) {      // uniform: the whole tile lies inside the sequence
-#pragma unroll
-            for (int ps = 0; ps < 4; ++ps) {
-                kr[ps] = *reinterpret_cast<const att_u32x4 *>(kt + k_ld[ps]);
-                vr[ps] = *reinterpret_cast<const att_u32x4 *>(vt + v_ld[ps]);
-            }
+            load_16B_per_lane_to_lds<0, true>(kt, k_ld[0], km);
+            load_16B_per_lane_to_lds<1024, false>(kt, k_ld[1], km);
+            load_16B_per_lane_to_lds<2048, false>(kt, k_ld[2], km);
+            load_16B_per_lane_to_lds<3072, false>(kt, k_ld[3], km);
+            load_16B_per_lane_to_lds<0, true>(vt, v_ld[0], vm);
+            load_16B_per_lane_to_lds<1024, false>(vt, v_ld[1], vm);
+            load_16B_per_lane_to_lds<2048, false>(vt, v_ld[2], vm);
+            load_16B_per_lane_to_lds<3072, false>(vt, v_ld[3], vm);
         } else {
+            const int last = Lk - 1 - t * ATT_KV;                  // >= 0: the tile holds at least one key
 #pragma unroll
-            for (int ps = 0; ps < 4; ++ps) {
-                const int key = min(ps * 16 + ld_row, Lk - 1 - t * ATT_KV);    // >= 0: the tile holds at least one key
-                kr[ps] = *reinterpret_cast<const att_u32x4 *>(kt + (unsigned)key * (unsigned)p.k_stride + ld_chunk * 8);
-                vr[ps] = *reinterpret_cast<const att_u32x4 *>(vt + (unsigned)key * (unsigned)p.v_stride + ld_chunk * 8);
+            for (int i = 0; i < 4; ++i) {
+                const unsigned r = 16 * wave + 4 * i + ld_sub;
+                const unsigned rg = min((int)r, last);           // row fetched; it still lands in row r's place
+                load_16B_per_lane_to_lds<0, true>(kt, (rg * (unsigned)p.k_stride + ((ld_pos ^ (r & 15)) << 3)) * 2u, km + 1024 * i);
+                load_16B_per_lane_to_lds<0, true>(vt, (rg * (unsigned)p.v_stride + ((ld_pos ^ ((r & 3) << 2)) << 3)) * 2u, vm + 1024 * i);
             }
-        }
-    };
-    auto stash = [&](int buf) {
-#pragma unroll
-        for (int ps = 0; ps < 4; ++ps) {
-            *reinterpret_cast<att_u32x4 *>(k_lds + buf * ATT_TILE_BYTES + ps * 4096 + k_wr) = kr[ps];
-            *reinterpret_cast<att_u32x4 *>(v_lds + buf * ATT_TILE_BYTES + ps * 4096 + v_wr) = vr[ps];
         }
     };
 
@@ -173,15 +177,16 @@ void attention_kernel(const AttnParams p) {
         }
         return;
     }
-    fetch(0);
-    stash(0);
+    fetch(0, 0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     // One key tile out of LDS buffer BUF; the next tile is fetched meanwhile and parked in the other buffer.
     auto tile = [&](auto buf_tag, int t) {
         constexpr int BUF = decltype(buf_tag)::value;
         const bool more = t + 1 < n_tiles;
-        if (more) fetch(t + 1);                                   // in flight while this tile is multiplied
+        if (more) fetch(t + 1, (BUF ^ 1) * ATT_TILE_BYTES, (BUF ^ 1) * ATT_TILE_BYTES);   // lands while this tile is multiplied;
+                                                                  // that buffer was last read before the previous barrier
 
         if (t < wave_tiles) {
             const unsigned char *kt = k_lds + BUF * ATT_TILE_BYTES;
@@ -258,7 +263,7 @@ void attention_kernel(const AttnParams p) {
         }
 
 
-        if (more) stash(BUF ^ 1);                                 // that buffer was last read before the previous barrier
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // this wavefront's part of the next tile has landed
         __syncthreads();
     };
     for (int t = 0; t < n_tiles; t += 2) {

@@ -47,29 +47,6 @@ __device__ __forceinline__ void wait_loads_and_barrier() {
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-// global_load_lds_dwordx4: every lane fetches 16 bytes from uniform base + its own 32-bit byte offset + OFFSET;
-// lane i's bytes land at LDS address m0 + OFFSET + 16*i (the instruction offset moves both addresses).  Written in
-// assembly so that the compiler does not see an LDS write it would guard with a full wait before later LDS reads;
-// completion is tracked by hand with vmcnt (above).  m0 is an operand, so one value serves all loads of a stage.
-// AFTER_M0_WRITE: the instruction may directly follow the write of m0, which needs one wait state.
-template <int OFFSET, bool AFTER_M0_WRITE>
-__device__ __forceinline__ void load_16B_per_lane_to_lds(const void *uniform_base, unsigned lane_offset, unsigned m0_value) {
-    static_assert(OFFSET >= -4096 && OFFSET < 4096, "13-bit signed instruction offset");
-    if (AFTER_M0_WRITE)
-        asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 offset:%2"
-                     ::"v"(lane_offset), "s"(uniform_base), "n"(OFFSET), "{m0}"(m0_value) : "memory");
-    else
-        asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2"
-                     ::"v"(lane_offset), "s"(uniform_base), "n"(OFFSET), "{m0}"(m0_value) : "memory");
-}
-
-// Tells the compiler that a pointer is the same in every lane (it then lives in scalar registers).
-__device__ __forceinline__ const char *uniform_pointer(const char *p) {
-    const uint64_t v = reinterpret_cast<uint64_t>(p);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return reinterpret_cast<const char *>(((uint64_t)hi << 32) | lo);
-}
-
 template <int MT, int NT>              // 32x32 MFMA tiles per wavefront
 struct Acc {
     f32x16 t[MT][NT];
