@@ -48,15 +48,15 @@ def _compile(src: str, extra) -> str:
     return obj
 
 
-def check_generated_code(asm_path: str) -> None:
-    """What the tiled GEMM's hand-kept bookkeeping assumes about the code the compiler generated for it:
-    no private-memory (scratch) traffic, whose loads and stores would share the counter that the kernel uses for its
-    direct global->LDS loads, and a wait state between a write of m0 and the direct load that reads it."""
+def check_generated_code(asm_path: str, kernel_name: str = "gemm_tiled_kernel") -> None:
+    """What the hand-kept bookkeeping of a kernel with direct global->LDS loads assumes about the code the compiler
+    generated for it: no private-memory (scratch) traffic, whose loads and stores would share the counter that the
+    kernel uses for its direct loads, and a wait state between a write of m0 and the direct load that reads it."""
     import re
     lines = [l.strip() for l in open(asm_path) if l.strip() and not l.strip().startswith(";")]
     kernel = None
     for i, l in enumerate(lines):
-        if l.endswith(":") and "gemm_tiled_kernel" in l:
+        if l.endswith(":") and kernel_name in l:
             kernel = l
         if l.startswith("scratch_") and kernel:
             raise RuntimeError("%s: scratch access in %s: %s" % (asm_path, kernel, l))
@@ -76,7 +76,8 @@ def build(save_temps: bool = True, jobs: int = 8, defines=(), lib_path: str = LI
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(lambda s: _compile(s, extra), SOURCES))
     if save_temps:
-        check_generated_code(os.path.join(BUILD, "gemm_tiled-hip-amdgcn-amd-amdhsa-gfx950.s"))
+        check_generated_code(os.path.join(BUILD, "gemm_tiled-hip-amdgcn-amd-amdhsa-gfx950.s"), "gemm_tiled_kernel")
+        check_generated_code(os.path.join(BUILD, "attention-hip-amdgcn-amd-amdhsa-gfx950.s"), "attention_kernel")
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib_path, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:

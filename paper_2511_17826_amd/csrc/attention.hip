@@ -54,6 +54,15 @@ struct AttnParams {
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
+// A lane and its partner lane ^ 32 hold the two halves of one query's keys.  v_permlane32_swap exchanges the upper
+// half of its first operand with the lower half of its second: from (v, v) it makes (lower half's values, upper
+// half's values) in every lane, i.e. {mine, partner's} in some order -- enough for a maximum or a sum of the two.
+__device__ __forceinline__ void both_halves(float v, float &a, float &b) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    a = __uint_as_float(r[0]);
+    b = __uint_as_float(r[1]);
+}
+
 template <bool CAUSAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attention_kernel(const AttnParams p) {
@@ -222,7 +231,11 @@ void attention_kernel(const AttnParams p) {
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[kb][r]);
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));          // the other half of this query's keys
+            {
+                float a, b;
+                both_halves(tmax, a, b);
+                tmax = fmaxf(a, b);                               // with the other half of this query's keys
+            }
             const float m_new = fmaxf(m, tmax);
             const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;   // a query that has seen no key yet
             const float alpha = __builtin_amdgcn_exp2f(m - m_use);
@@ -234,7 +247,11 @@ void attention_kernel(const AttnParams p) {
                     s[kb][r] = __builtin_amdgcn_exp2f(s[kb][r] - m_use);
                     psum = psum + s[kb][r];
                 }
-            psum = psum + __shfl_xor(psum, 32, 64);
+            {
+                float a, b;
+                both_halves(psum, a, b);
+                psum = a + b;                                     // lower half's sum + upper half's sum, in both lanes
+            }
             l = l * alpha + psum;
             m = m_new;
             if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {   // uniform: o * 1 is o, so skipping changes no bit
