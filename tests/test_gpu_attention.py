@@ -190,6 +190,30 @@ def test_8b_shape_sampled_parity():
         check_against_oracle(O[q0 + i:q0 + i + 1], sub, True)
 
 
+def test_long_context_and_many_short_sequences():
+    """A decode step over 40000 keys (625 tiles) and a 3000-token chunk at the end of it; and 1500 sequences of 1-40
+    tokens in one call (more workgroups in z than any other test)."""
+    Hq, Hkv = 8, 2
+    c = syn.attention_inputs(80, [1, 3000], [40000, 40000], Hq=Hq, Hkv=Hkv, D=128)
+    O = run(c)
+    dec = dict(c, Q=c["Q"][:1], K=c["K"][:40000], V=c["V"][:40000], cu_q=np.array([0, 1], dtype=np.int32),
+               cu_k=np.array([0, 40000], dtype=np.int32))
+    check_against_oracle(O[:1], dec, True)
+    for i in (0, 1500, 2999):                                      # rows of the chunk, each as its own decode step
+        nk = 40000 - 3000 + i + 1
+        one = dict(c, Q=c["Q"][1 + i:2 + i], K=c["K"][40000:40000 + nk], V=c["V"][40000:40000 + nk],
+                   cu_q=np.array([0, 1], dtype=np.int32), cu_k=np.array([0, nk], dtype=np.int32))
+        assert np.array_equal(run(one)[0], O[1 + i]), i
+    rng = np.random.Generator(np.random.PCG64(81))
+    lens = rng.integers(1, 41, size=1500)
+    c = syn.attention_inputs(82, lens, lens, Hq=4, Hkv=4, D=128)
+    O = run(c)
+    Oo, _ = orc.attention(c["Q"], c["K"], c["V"], c["cu_q"], c["cu_k"], c["scale"], True)
+    assert np.count_nonzero(O != Oo) <= O.size // 100
+    firsts = c["cu_q"][:-1]
+    assert np.array_equal(O[firsts], np.repeat(c["V"][c["cu_k"][:-1]], 1, axis=1))          # first token of each: its own value
+
+
 def test_argument_validation_on_the_device():
     Q = torch.zeros((4, 2, 64), dtype=torch.bfloat16, device="cuda:0")
     with pytest.raises(tb.TbikError) as e:

@@ -268,6 +268,29 @@ def test_small_m_full_parity_oproj():
     assert n_exc <= y_gpu.size // 100
 
 
+def test_large_batch_and_ragged_width():
+    """M = 40000 rows (313 row tiles, the last one ragged) and N = 4104 (one ragged column tile): a row's bits do not
+    depend on the batch it sits in, and sampled elements match the oracle."""
+    M, K, N, leaf = 40000, 2048, 4104, 256
+    Xb, Wb = syn.gemm_random(77, M, K, N)
+    Xd, Wd = gu.dev_bf16(Xb), gu.dev_bf16(Wb)
+    full = tb.tbik_gemm(Xd, Wd, leaf, 1, out_dtype=torch.float32)
+    for lo, hi in ((0, 1), (39999, 40000), (12345, 12345 + 77), (39936, 40000)):
+        part = tb.tbik_gemm(Xd[lo:hi], Wd, leaf, 1, out_dtype=torch.float32)
+        assert torch.equal(part.view(torch.int32), full[lo:hi].view(torch.int32)), (lo, hi)
+    parts = tb.tbik_gemm_shard_partials(Xd, Wd, leaf, 1, 4)
+    assert torch.equal(tb.tbik_tree_combine(parts, out_dtype=torch.float32).view(torch.int32), full.view(torch.int32))
+    del parts
+    rng = np.random.Generator(np.random.PCG64(78))
+    rows = np.concatenate([rng.integers(0, M, size=500), [0, M - 1, M - 1]])
+    cols = np.concatenate([rng.integers(0, N, size=500), [0, N - 1, 4096]])
+    y_orc = orc.gemm_elements(Xb, Wb, rows, cols, leaf, 1)
+    y64, A = gu.fp64_ref(Xb, Wb, rows, cols)
+    y_gpu = gu.host_f32(full)[rows, cols]
+    gu.check_fp32_against_fp64(y_gpu, y64, A)
+    assert np.all(np.abs(y_gpu.astype(np.float64) - y_orc) <= 2 * (leaf + 8) * 2.0 ** -24 * A)
+
+
 def test_baseline_gemm_is_not_shard_invariant():
     """Context for the method (Sec. 3.3): with an ordinary GEMM, summing per-shard results differs in bits
     from the whole-K result, while the tree route does not."""
