@@ -220,6 +220,11 @@ int tbik_gemm_reference_f16(const void *X, int64_t ldx, const void *W, int64_t l
 int tbik_set_gemm_variant(int variant);
 const char *tbik_variant_name(int variant);      /* NULL past the last variant */
 
+/* Forces one of the two attention kernels (testing and tuning only; the bits never depend on it):
+ * 0 = default, 1 = two independent workgroups per compute unit, 2 = one workgroup whose two groups of wavefronts take
+ * turns at the matrix and vector pipes.  Other values: TBIK_ERR_DTYPE. */
+int tbik_set_attention_variant(int variant);
+
 /* Log-softmax of rows longer than one block lets the workgroups of a row wait for each other a bounded number of
  * polls; a row whose wait runs out is recomputed by a second kernel of the same call, with the same bits.  This
  * sets the bound (testing only: 0 makes the waits run out, so that the second kernel is exercised).  Returns the

@@ -50,6 +50,7 @@ SIGNATURES = {
                                  C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_int64,
                                  C.c_float, C.c_int, C.c_void_p]),
     "tbik_set_gemm_variant": (C.c_int, [C.c_int]),
+    "tbik_set_attention_variant": (C.c_int, [C.c_int]),
     "tbik_set_row_wait_limit": (C.c_int, [C.c_int]),
     "tbik_variant_name": (C.c_char_p, [C.c_int]),
     "tbik_status_string": (C.c_char_p, [C.c_int]),
@@ -310,6 +311,10 @@ def _gemm_reference(entry: str, in_dtype, X, W, leaf, k_first, P, out_dtype):
 def tbik_set_row_wait_limit(polls: int) -> int:
     """Bound of the inter-workgroup waits of the long-row log-softmax (testing); returns the previous bound."""
     return int(lib().tbik_set_row_wait_limit(polls))
+
+
+def tbik_set_attention_variant(variant: int):
+    _check(lib().tbik_set_attention_variant(variant), "tbik_set_attention_variant")
 
 
 def tbik_set_gemm_variant(variant: int):

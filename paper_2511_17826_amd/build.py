@@ -53,7 +53,8 @@ def check_generated_code(asm_path: str, kernel_name: str = "gemm_tiled_kernel") 
     generated for it: no private-memory (scratch) traffic, whose loads and stores would share the counter that the
     kernel uses for its direct loads, and a wait state between a write of m0 and the direct load that reads it."""
     import re
-    lines = [l.strip() for l in open(asm_path) if l.strip() and not l.strip().startswith(";")]
+    lines = [l.split(";")[0].strip() for l in open(asm_path)]      # without comments (a label line carries one)
+    lines = [l for l in lines if l]
     kernel = None
     for i, l in enumerate(lines):
         if l.endswith(":") and kernel_name in l:
@@ -77,7 +78,7 @@ def build(save_temps: bool = True, jobs: int = 8, defines=(), lib_path: str = LI
         objs = list(ex.map(lambda s: _compile(s, extra), SOURCES))
     if save_temps:
         check_generated_code(os.path.join(BUILD, "gemm_tiled-hip-amdgcn-amd-amdhsa-gfx950.s"), "gemm_tiled_kernel")
-        check_generated_code(os.path.join(BUILD, "attention-hip-amdgcn-amd-amdhsa-gfx950.s"), "attention_kernel")
+        check_generated_code(os.path.join(BUILD, "attention-hip-amdgcn-amd-amdhsa-gfx950.s"), "attention_")
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib_path, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:

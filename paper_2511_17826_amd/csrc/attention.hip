@@ -111,6 +111,10 @@ void attention_kernel(const AttnParams p) {
         const uint16_t *qptr = p.Q + (int64_t)(q0 + qpos) * p.q_stride + (int64_t)head * ATT_D + lg * 8;
 #pragma unroll
         for (int ks = 0; ks < ATT_D / 16; ++ks) bq[ks] = *reinterpret_cast<const bf16x8 *>(qptr + ks * 16);
+        // A use the compiler can see: it waits for these loads here, once, and not later among the direct loads whose
+        // counter values it does not know.
+#pragma unroll
+        for (int ks = 0; ks < ATT_D / 16; ++ks) asm volatile("" ::"v"(bq[ks]));
     }
 
     // Tile loader: direct global->LDS loads (no staging registers).  Wavefront w fills key rows 16 w .. 16 w + 15 of a
@@ -306,6 +310,337 @@ void attention_kernel(const AttnParams p) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same arithmetic with two groups of wavefronts taking turns at the two pipes of a SIMD.
+//
+// A workgroup of 8 wavefronts (two per SIMD) owns 256 row slots that share one key/value head; wavefronts 0-3 are group
+// A, 4-7 group B, so each SIMD holds one wavefront of each group.  Per key tile a wavefront has an MFMA half -- the
+// product P_{t-1} V_{t-1} of the tile before, then the scores S_t = K_t Q^T -- and a vector half -- the softmax step
+// of tile t (scale, mask, maximum, exponentials, sums, rescale of o, weights rounded to bf16).  The two groups run
+// these halves in opposite phase, with a workgroup barrier between half-slots:
+//     half-slot 2t      A: MFMA half t          B: vector half t - 1
+//     half-slot 2t + 1  A: vector half t        B: MFMA half t
+// so the matrix pipe and the vector ALU of a SIMD are both busy all the time instead of whenever two independent
+// workgroups happen to be out of phase.  K_t is read in half-slots 2t and 2t + 1, V_t in 2t + 2 and 2t + 3; tile t lives
+// in slot t % RING of a ring of (K, V) pairs that direct global->LDS loads fill RING - 2 tiles ahead.  A row's
+// arithmetic is exactly that of attention_kernel (the order of its operations is unchanged), so are its bits.
+template <bool CAUSAL, int RING>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void attention_pingpong_kernel(const AttnParams p) {
+    static_assert(RING == 3 || RING == 4, "the prologue and the load counting below are written for these depths");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char *const k_lds = smem;                            // [RING][64 keys][256 B], swizzled as in attention_kernel
+    unsigned char *const v_lds = smem + RING * ATT_TILE_BYTES;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // 0..7
+    const int group = wave >> 2;
+    const int li = lane & 31, lg = lane >> 5;
+    const int seq = blockIdx.z;
+    const int qb = (int)gridDim.x - 1 - (int)blockIdx.x;          // long (late) blocks first
+    const int R = 2 * p.rows;                                     // queries per head and workgroup: 256 / pack
+
+    const int q0 = clampi(p.cu_q[seq], 0, p.total_q), q1 = clampi(p.cu_q[seq + 1], q0, p.total_q);
+    const int k0 = clampi(p.cu_k[seq], 0, p.total_k), k1 = clampi(p.cu_k[seq + 1], k0, p.total_k);
+    const int Lq = q1 - q0, Lk = k1 - k0;
+    if (qb * R >= Lq) return;                                     // uniform: nothing of this sequence in the block
+    const int shift = Lk - Lq;
+    const int slot = wave * 32 + li;
+    const int head = (int)blockIdx.y * p.pack + slot / R;
+    const int hk = ((int)blockIdx.y * p.pack) / p.group;
+
+    const int q_last = min(Lq - 1, qb * R + R - 1);
+    const int lim_block = CAUSAL ? min(Lk - 1, q_last + shift) : Lk - 1;
+    const int n_tiles = lim_block >= 0 ? lim_block / ATT_KV + 1 : 0;
+
+    const int qrow = qb * R + slot % R;
+    const int qpos = min(qrow, Lq - 1);
+    const int lim = CAUSAL ? min(Lk - 1, qpos + shift) : Lk - 1;
+    const int wave_first = qb * R + (wave * 32) % R;
+    const int wave_lim = CAUSAL ? min(Lk - 1, min(Lq - 1, wave_first + min(R, 32) - 1) + shift) : Lk - 1;
+    const int wave_tiles = (wave_first < Lq && wave_lim >= 0) ? wave_lim / ATT_KV + 1 : 0;
+    const int wave_full = CAUSAL ? min(Lk - 1, min(Lq - 1, wave_first) + shift) : Lk - 1;
+
+    bf16x8 bq[ATT_D / 16];
+    {
+        const uint16_t *qptr = p.Q + (int64_t)(q0 + qpos) * p.q_stride + (int64_t)head * ATT_D + lg * 8;
+#pragma unroll
+        for (int ks = 0; ks < ATT_D / 16; ++ks) bq[ks] = *reinterpret_cast<const bf16x8 *>(qptr + ks * 16);
+        // A use the compiler can see: it waits for these loads here, once, and not later among the direct loads whose
+        // counter values it does not know.
+#pragma unroll
+        for (int ks = 0; ks < ATT_D / 16; ++ks) asm volatile("" ::"v"(bq[ks]));
+    }
+
+    f32x16 o[ATT_D / 32];
+#pragma unroll
+    for (int db = 0; db < ATT_D / 32; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] = 0.0f;
+    float m = -INFINITY, l = 0.0f;
+
+    if (n_tiles == 0) {                                           // uniform: no query of the block sees a key
+        if (qrow < Lq) {
+            uint16_t *optr = p.O + (int64_t)(q0 + qrow) * p.o_stride + (int64_t)head * ATT_D + lg * 64;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) *reinterpret_cast<att_u32x4 *>(optr + 8 * i) = att_u32x4{0, 0, 0, 0};
+        }
+        return;
+    }
+
+    // Tile loader: wavefront w fills key rows 8 w .. 8 w + 7 of a tile with 2 direct loads for K and 2 for V.
+    const int ld_pos = lane & 15, ld_sub = lane >> 4;
+    const uint16_t *kbase = p.K + (int64_t)k0 * p.k_stride + (int64_t)hk * ATT_D;
+    const uint16_t *vbase = p.V + (int64_t)k0 * p.v_stride + (int64_t)hk * ATT_D;
+    unsigned k_ld[2], v_ld[2];                                   // minus the instruction offset 1024 i, which the load adds back
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const unsigned r = 8 * wave + 4 * i + ld_sub;
+        k_ld[i] = (r * (unsigned)p.k_stride + ((ld_pos ^ (r & 15)) << 3)) * 2u - 1024u * i;
+        v_ld[i] = (r * (unsigned)p.v_stride + ((ld_pos ^ ((r & 3) << 2)) << 3)) * 2u - 1024u * i;
+    }
+    const unsigned smem_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    const unsigned k_m0 = smem_lds + wave * 2048;
+    const unsigned v_m0 = smem_lds + RING * ATT_TILE_BYTES + wave * 2048;
+    constexpr int LOADS_PER_TILE = 4;                             // per wavefront: these and nothing else count in vmcnt inside the loop
+    auto fetch = [&](int t) __attribute__((always_inline)) {      // tile t -> ring slot t % RING
+        const int off = (t % RING) * ATT_TILE_BYTES;
+        const char *kt = uniform_pointer(reinterpret_cast<const char *>(kbase + (int64_t)t * ATT_KV * p.k_stride));
+        const char *vt = uniform_pointer(reinterpret_cast<const char *>(vbase + (int64_t)t * ATT_KV * p.v_stride));
+        const unsigned km = __builtin_amdgcn_readfirstlane(k_m0 + off), vm = __builtin_amdgcn_readfirstlane(v_m0 + off);
+        if (__builtin_expect(t * ATT_KV + ATT_KV <= Lk, 1)) {      // uniform: the whole tile lies inside the sequence
+            load_16B_per_lane_to_lds<0, true>(kt, k_ld[0], km);
+            load_16B_per_lane_to_lds<1024, false>(kt, k_ld[1], km);
+            load_16B_per_lane_to_lds<0, true>(vt, v_ld[0], vm);
+            load_16B_per_lane_to_lds<1024, false>(vt, v_ld[1], vm);
+        } else {
+            const int last = Lk - 1 - t * ATT_KV;                  // >= 0: the tile holds at least one key
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const unsigned r = 8 * wave + 4 * i + ld_sub;
+                const unsigned rg = min((int)r, last);           // row fetched; it still lands in row r's place
+                load_16B_per_lane_to_lds<0, true>(kt, (rg * (unsigned)p.k_stride + ((ld_pos ^ (r & 15)) << 3)) * 2u, km + 1024 * i);
+                load_16B_per_lane_to_lds<0, true>(vt, (rg * (unsigned)p.v_stride + ((ld_pos ^ ((r & 3) << 2)) << 3)) * 2u, vm + 1024 * i);
+            }
+        }
+    };
+
+    const int k_rd = li * 256 + ((lg ^ (li & 15)) << 4);         // ^ (ks << 5), + kb * 8192: ((2 ks + lg) ^ (li & 15)) << 4
+    const int l16 = lane & 15, e = l16 >> 2;
+    int v_rd[ATT_D / 32];
+#pragma unroll
+    for (int db = 0; db < ATT_D / 32; ++db) {
+        const int col = db * 32 + ((lane >> 4) & 1) * 16 + (l16 & 3) * 4;
+        v_rd[db] = (4 * lg + e) * 256 + ((((col >> 3) ^ (e << 2))) << 4) + ((col >> 2) & 1) * 8;
+    }
+
+    f32x16 s[2];                                                  // S_t between the two halves of tile t
+    bf16x8 pw[4];                                                 // P_t^T rounded to bf16, from the vector half of t to the MFMA half of t + 1
+
+    // MFMA half of tile t: o += V_{t-1}^T P_{t-1}^T, then S_t = K_t Q^T.  The fragments of a group of MFMAs are read
+    // while earlier groups are multiplied, and nothing is allowed to move across the groups, which bounds the fragment
+    // registers in flight (the register budget is 256 per lane: two wavefronts per SIMD).  Product: 4 groups of 4 MFMAs
+    // (one k-step each), fragments read two groups ahead; scores: 8 groups of 2 MFMAs, fragments read three groups
+    // ahead, the first ones already during the product.  (Reading the very first fragments before the barrier that
+    // opens the half, which the residency of the tiles would allow, was tried and did not pay.)
+    typedef union { att_v4i16 h2[2]; bf16x8 v; } vfrag;
+    vfrag vf[2][ATT_D / 32];
+    bf16x8 kf[4][2];
+    auto read_v = [&](vfrag (&f)[ATT_D / 32], int t, int st) __attribute__((always_inline)) {
+        const unsigned char *vt = v_lds + ((t + RING - 1) % RING) * ATT_TILE_BYTES;      // V_{t-1}
+        const int kb = st >> 1, h = st & 1;
+#pragma unroll
+        for (int db = 0; db < ATT_D / 32; ++db)
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh)
+                f[db].h2[hh] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) att_v4i16 *)(vt + (32 * kb + 16 * h + 8 * hh) * 256 + v_rd[db]));
+    };
+    auto read_k = [&](bf16x8 (&f)[2], int k_rd_here, int ks) __attribute__((always_inline)) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) f[kb] = *reinterpret_cast<const bf16x8 *>(k_lds + kb * 8192 + (k_rd_here ^ (ks << 5)));
+    };
+    auto k_base = [&](int t) __attribute__((always_inline)) {
+        int k_rd_here = k_rd + (t % RING) * ATT_TILE_BYTES;      // the tile offset leaves the bits of the swizzle alone
+        asm volatile("" : "+v"(k_rd_here));                       // per-step addresses are formed where they are used, not kept
+        return k_rd_here;
+    };
+    auto mfma_prefetch = [&](int t) __attribute__((always_inline)) {
+        const bool do_product = t >= 1 && t - 1 < wave_tiles, do_scores = t < wave_tiles;
+        if (do_product) {
+            read_v(vf[0], t, 0);
+            read_v(vf[1], t, 1);
+        } else if (do_scores) {
+            const int kr = k_base(t);
+            read_k(kf[0], kr, 0);
+            read_k(kf[1], kr, 1);
+            read_k(kf[2], kr, 2);
+        }
+    };
+    auto mfma_half = [&](int t) __attribute__((always_inline)) {
+        const bool do_product = t >= 1 && t - 1 < wave_tiles, do_scores = t < wave_tiles;
+        const int kr = k_base(t);
+        mfma_prefetch(t);
+        if (do_product) {
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+#pragma unroll
+                for (int db = 0; db < ATT_D / 32; ++db)
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[st & 1][db].v, pw[st], o[db], 0, 0, 0);
+                if (st + 2 < 4) read_v(vf[st & 1], t, st + 2);
+                if (st >= 1 && do_scores) read_k(kf[st - 1], kr, st - 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        if (do_scores) {
+            const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int ks = 0; ks < ATT_D / 16; ++ks) {
+                if (ks + 3 < ATT_D / 16) read_k(kf[(ks + 3) & 3], kr, ks + 3);
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks & 3][kb], bq[ks], ks == 0 ? zero : s[kb], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+
+    // Vector half of tile t: the softmax step on S_t; o is rescaled here (it holds everything up to tile t - 1).
+    auto vector_half = [&](int t) __attribute__((always_inline)) {
+        if (t < 0 || t >= wave_tiles) return;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[kb][r] = s[kb][r] * p.c;
+        if (t * ATT_KV + ATT_KV - 1 > wave_full) {                // uniform: some row of the wavefront does not see the whole tile
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = t * ATT_KV + kb * 32 + 8 * (r >> 2) + 4 * lg + (r & 3);
+                    if (key > lim) s[kb][r] = -INFINITY;
+                }
+        }
+        float tmax = s[0][0];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[kb][r]);
+        {
+            float a, b;
+            both_halves(tmax, a, b);
+            tmax = fmaxf(a, b);                                   // with the other half of this query's keys
+        }
+        const float m_new = fmaxf(m, tmax);
+        const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;   // a query that has seen no key yet
+        const float alpha = __builtin_amdgcn_exp2f(m - m_use);
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {     // uniform: o * 1 is o, so skipping changes no bit
+#pragma unroll
+            for (int db = 0; db < ATT_D / 32; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[db][r] = o[db][r] * alpha;
+        }
+        // Weights in key order, eight at a time: summed in fp32 and rounded to bf16 as they are formed, so that only a
+        // few of them are in registers at once (k-step st of the product takes elements 8 st .. 8 st + 7).
+        float psum = 0.0f;
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            union { uint32_t u[4]; bf16x8 v; } pb;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float p0 = __builtin_amdgcn_exp2f(s[st >> 1][8 * (st & 1) + 2 * i] - m_use);
+                const float p1 = __builtin_amdgcn_exp2f(s[st >> 1][8 * (st & 1) + 2 * i + 1] - m_use);
+                psum = psum + p0;
+                psum = psum + p1;
+                pb.u[i] = pack_bf16x2(p0, p1);
+            }
+            pw[st] = pb.v;
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        {
+            float a, b;
+            both_halves(psum, a, b);
+            psum = a + b;                                         // lower half's sum + upper half's sum, in both lanes
+        }
+        l = l * alpha + psum;
+        m = m_new;
+    };
+
+    // Every wavefront of the workgroup passes the same barriers: 1 + 2 n_tiles + 1, whatever its own number of tiles.
+    // The two groups run separate copies of the loop (one branch at the top, none inside), which differ only in which
+    // half comes first.
+    fetch(0);
+    if (RING > 3 && n_tiles > 1) fetch(1);
+    if (RING > 3 && n_tiles > 1) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LOADS_PER_TILE) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    // End of iteration t: tile t + 1 must have landed before half-slot 2t + 2; tiles t + 2 .. t + RING - 2 may still be
+    // on their way.
+    auto end_of_iteration = [&](int t) __attribute__((always_inline)) {
+        if (RING > 3 && t + 2 < n_tiles) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((RING - 3) * LOADS_PER_TILE) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    };
+    if (group == 0) {
+        for (int t = 0; t < n_tiles; ++t) {
+            // The slot of tile t - 2 was last read in half-slot 2t - 1: free since the barrier that ended it.
+            if (t + RING - 2 < n_tiles) fetch(t + RING - 2);
+            mfma_half(t);
+            asm volatile("s_barrier" ::: "memory");
+            vector_half(t);
+            end_of_iteration(t);
+        }
+        mfma_half(n_tiles);                                       // the product of the last tile (no scores: n_tiles >= wave_tiles)
+        asm volatile("s_barrier" ::: "memory");
+    } else {
+        for (int t = 0; t < n_tiles; ++t) {
+            if (t + RING - 2 < n_tiles) fetch(t + RING - 2);
+            vector_half(t - 1);
+            asm volatile("s_barrier" ::: "memory");
+            mfma_half(t);
+            end_of_iteration(t);
+        }
+        vector_half(n_tiles - 1);
+        asm volatile("s_barrier" ::: "memory");
+        mfma_half(n_tiles);
+    }
+
+    if (qrow < Lq) {
+        uint16_t *optr = p.O + (int64_t)(q0 + qrow) * p.o_stride + (int64_t)head * ATT_D + 4 * lg;
+#pragma unroll
+        for (int db = 0; db < ATT_D / 32; ++db)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float v[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = (l > 0.0f) ? o[db][4 * q + i] / l : 0.0f;
+                att_u32x2 w;
+                w[0] = pack_bf16x2(v[0], v[1]);
+                w[1] = pack_bf16x2(v[2], v[3]);
+                *reinterpret_cast<att_u32x2 *>(optr + db * 32 + 8 * q) = w;
+            }
+    }
+}
+
+static std::atomic<int> g_attention_variant{0};
+int set_attention_variant(int v) {
+    if (v < 0 || v > 2) return -1;
+    return g_attention_variant.exchange(v);
+}
+
+template <class Kernel>
+static hipError_t launch_with_lds(Kernel kernel, std::atomic<unsigned> &done, dim3 grid, dim3 block, int lds, const AttnParams &p,
+                                  hipStream_t s) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 32) dev = 32;      // 32: not remembered, set every time
+    if (dev >= 32 || !((done.load(std::memory_order_relaxed) >> dev) & 1u)) {  // bit d: the attribute is set on device d
+        hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        if (dev < 32) done.fetch_or(1u << dev, std::memory_order_relaxed);
+    }
+    hipLaunchKernelGGL(kernel, grid, block, lds, s, p);
+    return hipGetLastError();
+}
+
 hipError_t launch_attention(const AttnArgs &a, hipStream_t s) {
     if (a.batch <= 0 || a.max_seqlen_q <= 0 || a.total_q <= 0) return hipSuccess;
     AttnParams p;
@@ -317,22 +652,24 @@ hipError_t launch_attention(const AttnArgs &a, hipStream_t s) {
     p.pack = (p.group <= ATT_BQ && (p.group & (p.group - 1)) == 0) ? p.group : 1;
     p.rows = ATT_BQ / p.pack;
     p.c = a.scale * 1.44269504088896340736f;
-    const int64_t q_blocks = ((int64_t)a.max_seqlen_q + p.rows - 1) / p.rows;
-    if (q_blocks > 0x7fffffff || a.heads_q > 65535 || a.batch > 65535) return hipErrorInvalidValue;
-    dim3 grid((unsigned)q_blocks, (unsigned)(a.heads_q / p.pack), (unsigned)a.batch), block(256);
-    constexpr int lds = 4 * ATT_TILE_BYTES;
-    auto kernel = a.causal ? attention_kernel<true> : attention_kernel<false>;
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 32) dev = 32;
-    static std::atomic<unsigned> lds_allowed[2] = {{0}, {0}};    // bit d: the attribute is set on device d
-    std::atomic<unsigned> &done = lds_allowed[a.causal ? 1 : 0];
-    if (dev >= 32 || !((done.load(std::memory_order_relaxed) >> dev) & 1u)) {
-        hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        if (dev < 32) done.fetch_or(1u << dev, std::memory_order_relaxed);
+    if (a.heads_q > 65535 || a.batch > 65535) return hipErrorInvalidValue;
+    // Same bits either way, so the choice is free: the wavefront groups that take turns pay two barriers per tile, which
+    // only very long prefills earn back (1 x 16384 tokens: 985 against 940 TFLOP/s; 2 x 8192: 857 against 896;
+    // 4 x 4096: 694 against 781; decode steps: 4.1 against 5.1 TB/s).
+    const int variant = g_attention_variant.load();
+    const bool pingpong = (variant == 2) || (variant == 0 && a.max_seqlen_q >= 16384);
+    const int rows = pingpong ? 2 * p.rows : p.rows;             // queries per head and workgroup
+    const int64_t q_blocks = ((int64_t)a.max_seqlen_q + rows - 1) / rows;
+    if (q_blocks > 0x7fffffff) return hipErrorInvalidValue;
+    dim3 grid((unsigned)q_blocks, (unsigned)(a.heads_q / p.pack), (unsigned)a.batch);
+    static std::atomic<unsigned> done[4] = {{0}, {0}, {0}, {0}};
+    if (pingpong) {
+        constexpr int RING = 4;
+        if (a.causal) return launch_with_lds(attention_pingpong_kernel<true, RING>, done[0], grid, dim3(512), 2 * RING * ATT_TILE_BYTES, p, s);
+        return launch_with_lds(attention_pingpong_kernel<false, RING>, done[1], grid, dim3(512), 2 * RING * ATT_TILE_BYTES, p, s);
     }
-    hipLaunchKernelGGL(kernel, grid, block, lds, s, p);
-    return hipGetLastError();
+    if (a.causal) return launch_with_lds(attention_kernel<true>, done[2], grid, dim3(256), 4 * ATT_TILE_BYTES, p, s);
+    return launch_with_lds(attention_kernel<false>, done[3], grid, dim3(256), 4 * ATT_TILE_BYTES, p, s);
 }
 
 }  // namespace tbik

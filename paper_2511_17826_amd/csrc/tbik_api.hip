@@ -251,6 +251,8 @@ int tbik_attention(const void *Q, const void *K, const void *V, void *O,
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }
 
+int tbik_set_attention_variant(int variant) { return set_attention_variant(variant) < 0 ? TBIK_ERR_DTYPE : TBIK_OK; }
+
 size_t tbik_row_reduce_workspace_bytes(int M, int64_t V, tbik_rowop op) {
     if (op != TBIK_SUM && op != TBIK_MAX && op != TBIK_LOGSOFTMAX) return 0;
     // sized for the finer of the two input types (fp32 rows have twice the leaves of bf16 rows)

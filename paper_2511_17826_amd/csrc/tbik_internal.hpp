@@ -54,6 +54,7 @@ struct AttnArgs {
     int causal;
 };
 hipError_t launch_attention(const AttnArgs &a, hipStream_t s);
+int set_attention_variant(int v);   // 0 = default, 1 = two workgroups per CU, 2 = two groups of wavefronts taking turns; returns the previous value, -1 if illegal
 
 size_t row_reduce_workspace(int M, int64_t V, int x_dtype, int op);
 hipError_t launch_row_reduce(const void *x, int x_dtype, void *out, int op, int M, int64_t V, void *ws, hipStream_t s);

@@ -139,6 +139,12 @@ def test_reduction_validation(L):
     assert rr(None, 0, GOOD, 0, 4, 1024, GOOD, 1 << 20, None) == 1
 
 
+def test_attention_variant_switch(L):
+    assert L.tbik_set_attention_variant(2) == 0 and L.tbik_set_attention_variant(1) == 0
+    assert L.tbik_set_attention_variant(3) == 4 and L.tbik_set_attention_variant(-1) == 4
+    assert L.tbik_set_attention_variant(0) == 0
+
+
 def test_variant_switch(L):
     assert L.tbik_set_gemm_variant(99) == 7
     assert L.tbik_set_gemm_variant(1) == 0

@@ -25,6 +25,14 @@ from test_oracle_attention import plain_attention_fp64
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=[2, 1], ids=["wavefront-groups-taking-turns", "two-workgroups"])
+def _both_kernels(request):
+    """Every test runs once with each attention kernel; the default is restored afterwards."""
+    tb.tbik_set_attention_variant(request.param)
+    yield
+    tb.tbik_set_attention_variant(0)
+
+
 def i32(a):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to("cuda:0")
 
@@ -212,6 +220,15 @@ def test_long_context_and_many_short_sequences():
     assert np.count_nonzero(O != Oo) <= O.size // 100
     firsts = c["cu_q"][:-1]
     assert np.array_equal(O[firsts], np.repeat(c["V"][c["cu_k"][:-1]], 1, axis=1))          # first token of each: its own value
+
+
+def test_the_two_kernels_give_the_same_bits():
+    c = syn.attention_inputs(90, [700, 1, 130, 17], [700, 1000, 200, 17], Hq=8, Hkv=2, D=128)
+    outs = []
+    for v in (1, 2):
+        tb.tbik_set_attention_variant(v)
+        outs.append((run(c, True), run(c, False)))
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
 
 
 def test_argument_validation_on_the_device():
