@@ -6,6 +6,11 @@ down_proj (tree GEMM, P shards) -> lm_head GEMM -> log-softmax, M = 512 tokens. 
 lm_head) have no cross-shard sum, so they run as whole-K calls (Sec. 3.3).  leaf = 128 with k_first = 5 (K = 5120) and
 25 (K = 25600) gives 8 superleaves, so P <= 8 is legal.  The attention here is a plain fp32 softmax(QK^T)V written with
 torch ops: it is test scaffolding, computed once and fed to every P, not part of the library.
+
+A second test runs the same layer with every reduction inside the library -- tbik_attention on the fused QKV buffer and
+the fused tail after both row-parallel layers -- on two packed sequences, and checks the claim end to end: the final
+log-probabilities of a token have the same bits for every shard count, with or without the other sequence in the
+batch, and when the token is processed as a decode step against the cached keys and values.
 """
 import numpy as np
 import pytest
@@ -82,4 +87,65 @@ def test_chain_logprobs_bit_identical_across_shard_counts():
     want = orc.row_logsoftmax(lg)
     got = gu.host_f32(stages["logp"][[0, 255, 511]])
     assert np.max(np.abs(got - want) / np.maximum(1.0, np.abs(want))) <= 1e-5
+    assert np.all(np.abs(np.exp(got.astype(np.float64)).sum(axis=1) - 1.0) <= 1e-5)
+
+
+def _layer_logprobs(t, x, cu, max_q, P, kv_cache=None):
+    """One decoder layer + lm_head on packed sequences, every reduction through the library:
+    RMSNorm -> QKV GEMM -> tbik_attention on the fused QKV buffer -> o_proj shard partials -> fused tail (tree combine +
+    residual + RMSNorm) -> gate/up GEMMs -> SiLU*up -> down_proj shard partials -> fused tail -> lm_head GEMM -> log-softmax.
+    kv_cache = (K, V, cu_k): keys and values of the whole sequences (a decode step brings only its own queries)."""
+    d = syn.CHAIN_DIMS
+    leaf, hd, nq, nkv = d["leaf"], d["head_dim"], d["q_heads"], d["kv_heads"]
+    g_h, g_i = d["hidden"] // leaf // 8, d["inter"] // leaf // 8
+    T = x.shape[0]
+    n1 = tb.tbik_rmsnorm(x, t["norm1"], 1e-6)
+    qkv = tb.tbik_gemm(n1, t["w_qkv"], leaf, g_h)
+    row = qkv.stride(0)
+    Q = torch.as_strided(qkv, (T, nq, hd), (row, hd, 1), 0)
+    K = torch.as_strided(qkv, (T, nkv, hd), (row, hd, 1), nq * hd)
+    V = torch.as_strided(qkv, (T, nkv, hd), (row, hd, 1), (nq + nkv) * hd)
+    cu_q = torch.from_numpy(np.asarray(cu, dtype=np.int32)).to("cuda:0")
+    if kv_cache is None:
+        attn = tb.tbik_attention(Q, K, V, cu_q, cu_q, max_q, hd ** -0.5, True)
+    else:
+        Kc, Vc, cu_k = kv_cache
+        attn = tb.tbik_attention(Q, Kc, Vc, cu_q, torch.from_numpy(np.asarray(cu_k, dtype=np.int32)).to("cuda:0"), max_q,
+                                 hd ** -0.5, True)
+    attn = attn.view(T, nq * hd)
+    h1, n2 = tb.tbik_combine_residual_rmsnorm(tb.tbik_gemm_shard_partials(attn, t["w_o"], leaf, g_h, P), x, t["norm2"], 1e-6)
+    gate = tb.tbik_gemm(n2, t["w_gate"], leaf, g_h)
+    up = tb.tbik_gemm(n2, t["w_up"], leaf, g_h)
+    act = (torch.nn.functional.silu(gate.float()) * up.float()).to(torch.bfloat16)       # elementwise: no reduction to order
+    h2, n3 = tb.tbik_combine_residual_rmsnorm(tb.tbik_gemm_shard_partials(act, t["w_down"], leaf, g_i, P), h1, t["norm1"], 1e-6)
+    logits = tb.tbik_gemm(n3, t["w_lm"], leaf, g_h, out_dtype=torch.float32)
+    logp = tb.tbik_row_reduce(logits, tb.TBIK_LOGSOFTMAX)
+    torch.cuda.synchronize()
+    return logp, (K, V)
+
+
+def test_layer_with_library_attention_is_invariant_to_batch_shards_and_call_shape():
+    """The paper's claim end to end (Sec. 1: the same bits across batch sizes and tensor-parallel sizes; implementation
+    appendix: prefill and decode through one attention kernel): two packed sequences of 300 and 212 tokens.
+      (1) P in {1, 2, 4, 8}: one digest of the final log-probabilities;
+      (2) each sequence run on its own gives the rows it has in the batch;
+      (3) the last token of the second sequence run as a decode step (one query, keys and values from the cache of the
+          batched run) gives the row it has in the batch."""
+    t = syn.chain_tensors("cuda:0")
+    x = t["x"]
+    cu = [0, 300, 512]
+    full, (K, V) = _layer_logprobs(t, x, cu, 300, 1)
+    for P in (2, 4, 8):
+        other, _ = _layer_logprobs(t, x, cu, 300, P)
+        assert torch.equal(other.view(torch.int32), full.view(torch.int32)), P
+        del other
+    a, _ = _layer_logprobs(t, x[:300].contiguous(), [0, 300], 300, 2)
+    assert torch.equal(a.view(torch.int32), full[:300].view(torch.int32))
+    b, _ = _layer_logprobs(t, x[300:].contiguous(), [0, 212], 212, 4)
+    assert torch.equal(b.view(torch.int32), full[300:].view(torch.int32))
+    del a, b
+    step, _ = _layer_logprobs(t, x[511:512].contiguous(), [0, 1], 1, 8, kv_cache=(K[300:], V[300:], [0, 212]))
+    assert torch.equal(step.view(torch.int32), full[511:512].view(torch.int32))
+    # and the numbers are log-probabilities
+    got = gu.host_f32(full[[0, 299, 511]])
     assert np.all(np.abs(np.exp(got.astype(np.float64)).sum(axis=1) - 1.0) <= 1e-5)
