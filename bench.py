@@ -288,6 +288,21 @@ def extras(tb, syn, torch, np, to_dev):
         res["downproj_k14336_M%d" % M] = {"ms": round(t, 4), "tflops": round(2.0 * M * 14336 * 4096 / (t * 1e-3) / 1e12, 2),
                                           "baseline_ms": round(tb_ms, 4)}
     del X, W
+    # 32B-class row-parallel shapes: hidden 5120, intermediate 25600; leaf 128 with K_first 5 / 25 gives 8 superleaves
+    for name, K, N, g in (("oproj32b_k5120", 5120, 5120, 5), ("downproj32b_k25600", 25600, 5120, 25)):
+        X = torch.randn((4096, K), device="cuda:0").to(torch.bfloat16)
+        W = (torch.randn((K, N), device="cuda:0") * 0.02).to(torch.bfloat16)
+        for M in (64, 4096):
+            y = torch.empty((M, N), dtype=torch.bfloat16, device=X.device)
+            f = lambda: tb.tbik_gemm(X[:M], W, 128, g, out=y)
+            f(); f()
+            t = min(time_region(f, 10, torch) for _ in range(3))
+            b = lambda: torch.matmul(X[:M], W)
+            b(); b()
+            tb_ms = min(time_region(b, 10, torch) for _ in range(3))
+            res["%s_M%d" % (name, M)] = {"ms": round(t, 4), "tflops": round(2.0 * M * K * N / (t * 1e-3) / 1e12, 2),
+                                         "baseline_ms": round(tb_ms, 4)}
+        del X, W
     # fp16 operands at the o_proj shape (same kernel, the other MFMA opcode)
     c = syn.gemm_oproj(4096, fmt="fp16")
     X = torch.from_numpy(c["X"].view(np.int16)).view(torch.float16).to("cuda:0")
