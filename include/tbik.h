@@ -120,7 +120,7 @@ int tbik_tree_combine(const float *partials, int P, void *Y, int64_t ldy, tbik_d
 int tbik_rmsnorm(const void *x, const void *weight, void *y, int M, int H, float eps, void *hip_stream);
 
 /*
- * Fused tail of a row-parallel layer (one of the "next" fusions that keep the contract): what a decoder layer does
+ * Fused tail of a row-parallel layer (a fusion that keeps the determinism contract): what a decoder layer does
  * with the tree all-reduce's result (Sec. 3.3, Alg. 2) before the next block,
  *   Y = bf16(T(partials[0..P)))      exactly tbik_tree_combine with a bf16 output,
  *   Hd = bf16(Y + R)                 the residual add in fp32, rounded once,
