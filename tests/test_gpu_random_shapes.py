@@ -1,0 +1,90 @@
+"""Randomly drawn shapes (seeded): the invariances that must hold at any size, checked where no hand-picked case looks.
+
+GEMM: every kernel variant and every legal shard count give the bits of the reference kernel; small-integer operands
+give the exact integers.  Attention: the two kernels agree bit for bit, a sequence alone gives the rows it has in the
+batch, and small cases match the oracle within the tolerance stated in test_gpu_attention.py.
+"""
+import numpy as np
+import pytest
+import torch
+
+import gpu_util as gu
+from oracle import tbik_oracle as orc
+from paper_2511_17826_amd import binding as tb
+from paper_2511_17826_amd import synthetic as syn
+from test_gpu_attention import check_against_oracle, i32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _reset():
+    yield
+    tb.tbik_set_gemm_variant(tb.VARIANT_AUTO)
+    tb.tbik_set_attention_variant(0)
+
+
+def test_gemm_random_shapes_all_variants_and_shard_counts():
+    rng = np.random.Generator(np.random.PCG64(1234))
+    for case in range(24):
+        leaf = int(rng.choice([16, 64, 128, 256]))
+        g = int(rng.choice([1, 1, 2, 3, 5]))
+        ns = int(rng.choice([1, 2, 4, 8, 16, 32]))
+        K = leaf * g * ns
+        if K > 16384:
+            continue
+        M = int(rng.choice([1, 2, 7, 31, 32, 33, 64, 100, 129, 257, 600]))
+        N = int(rng.choice([8, 24, 120, 128, 136, 256, 392, 1000]))
+        fmt = "fp16" if case % 3 == 2 else "bf16"
+        Xb, Wb = syn.gemm_small_integers(1000 + case, M, K, N, mag=4, fmt=fmt)
+        want = (syn.from_storage(Xb, fmt).astype(np.int64) @ syn.from_storage(Wb, fmt).astype(np.int64)).astype(np.float32)
+        dev = gu.dev_f16 if fmt == "fp16" else gu.dev_bf16
+        gemm = tb.tbik_gemm_f16 if fmt == "fp16" else tb.tbik_gemm
+        parts_of = tb.tbik_gemm_shard_partials_f16 if fmt == "fp16" else tb.tbik_gemm_shard_partials
+        Xd, Wd = dev(Xb), dev(Wb)
+        for v in (tb.VARIANT_REFERENCE, tb.VARIANT_T128, tb.VARIANT_T32, tb.VARIANT_AUTO):
+            tb.tbik_set_gemm_variant(v)
+            y = gemm(Xd, Wd, leaf, g, out_dtype=torch.float32)
+            assert np.array_equal(gu.host_f32(y), want), (case, M, K, N, leaf, g, v, fmt)
+            for P in (2, 8, 64):
+                if P <= ns:
+                    y = tb.tbik_tree_combine(parts_of(Xd, Wd, leaf, g, P), out_dtype=torch.float32)
+                    assert np.array_equal(gu.host_f32(y), want), (case, M, K, N, leaf, g, v, P, fmt)
+    # rounding orders, not just indexing: random values, variants against the reference kernel's bits
+    for case in range(8):
+        leaf, g, ns = 64, int(rng.choice([1, 3])), int(rng.choice([4, 16]))
+        K, M, N = leaf * g * ns, int(rng.choice([5, 130, 300])), int(rng.choice([136, 512]))
+        Xb, Wb = syn.gemm_random(2000 + case, M, K, N)
+        Xd, Wd = gu.dev_bf16(Xb), gu.dev_bf16(Wb)
+        tb.tbik_set_gemm_variant(tb.VARIANT_REFERENCE)
+        ref = tb.tbik_gemm(Xd, Wd, leaf, g, out_dtype=torch.float32)
+        for v in (tb.VARIANT_T128, tb.VARIANT_T32, tb.VARIANT_AUTO):
+            tb.tbik_set_gemm_variant(v)
+            for P in (1, 2, ns):
+                y = tb.tbik_tree_combine(tb.tbik_gemm_shard_partials(Xd, Wd, leaf, g, P), out_dtype=torch.float32)
+                assert torch.equal(y.view(torch.int32), ref.view(torch.int32)), (case, v, P)
+
+
+def test_attention_random_batches_two_kernels_and_single_sequences():
+    rng = np.random.Generator(np.random.PCG64(4321))
+    for case in range(16):
+        Hkv = int(rng.choice([1, 2, 4]))
+        Hq = Hkv * int(rng.choice([1, 2, 3, 4, 8]))
+        nseq = int(rng.integers(1, 6))
+        k_lens = rng.integers(1, 700, size=nseq)
+        kind = rng.integers(0, 3, size=nseq)                      # prefill, decode step, chunk
+        q_lens = np.where(kind == 0, k_lens, np.where(kind == 1, 1, np.maximum(1, k_lens // 3)))
+        causal = bool(case % 4 != 3)
+        c = syn.attention_inputs(3000 + case, q_lens, k_lens, Hq=Hq, Hkv=Hkv, D=128)
+        Q, K, V = gu.dev_bf16(c["Q"]), gu.dev_bf16(c["K"]), gu.dev_bf16(c["V"])
+        outs = []
+        for v in (1, 2):
+            tb.tbik_set_attention_variant(v)
+            outs.append(gu.host_bf16_bits(tb.tbik_attention(Q, K, V, i32(c["cu_q"]), i32(c["cu_k"]), int(q_lens.max()), c["scale"], causal)))
+        assert np.array_equal(outs[0], outs[1]), (case, Hq, Hkv, list(q_lens), list(k_lens))
+        b = int(rng.integers(0, nseq))                            # one sequence on its own
+        q0, q1, k0, k1 = c["cu_q"][b], c["cu_q"][b + 1], c["cu_k"][b], c["cu_k"][b + 1]
+        alone = tb.tbik_attention(Q[q0:q1], K[k0:k1], V[k0:k1], i32([0, q1 - q0]), i32([0, k1 - k0]), int(q1 - q0), c["scale"], causal)
+        assert np.array_equal(gu.host_bf16_bits(alone), outs[0][q0:q1]), (case, b)
+        if c["Q"].shape[0] * Hq <= 4000:
+            check_against_oracle(outs[0], c, causal)
