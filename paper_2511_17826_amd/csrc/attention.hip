@@ -207,15 +207,16 @@ void attention_kernel(const AttnParams p) {
             // ---- S^T = K Q^T ----
             f32x16 s[2];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) s[kb][r] = 0.0f;
 #pragma unroll
-                for (int ks = 0; ks < ATT_D / 16; ++ks) {
+            for (int ks = 0; ks < ATT_D / 16; ++ks)               // the two key blocks alternate: consecutive MFMAs are independent
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb) {
                     const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kt + kb * 8192 + k_rd + (((2 * ks + lg) ^ (li & 15)) << 4));
                     s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, bq[ks], s[kb], 0, 0, 0);
                 }
-            }
             // ---- scale, mask, running maximum ----
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
