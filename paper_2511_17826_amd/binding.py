@@ -20,7 +20,7 @@ TBIK_F32, TBIK_BF16, TBIK_F16 = 0, 1, 2
 TBIK_SUM, TBIK_MAX, TBIK_LOGSOFTMAX = 0, 1, 2
 OK = 0
 
-VARIANT_AUTO, VARIANT_REFERENCE, VARIANT_T128, VARIANT_T32 = 0, 1, 2, 3
+VARIANT_AUTO, VARIANT_REFERENCE, VARIANT_T128, VARIANT_T32, VARIANT_T64 = 0, 1, 2, 3, 4
 
 # name -> (restype, argtypes); mirrors include/tbik.h
 SIGNATURES = {

@@ -462,7 +462,7 @@ static int levels_for(int ns_per_shard) {
 }
 
 bool gemm_tiled_supports(const GemmArgs &a, int variant) {
-    if (variant != VARIANT_T128 && variant != VARIANT_T32) return false;
+    if (variant != VARIANT_T128 && variant != VARIANT_T32 && variant != VARIANT_T64) return false;
     if (a.N % 8 != 0 || a.superleaf % BK != 0) return false;
     if (levels_for(a.ns / a.P) > 4) return false;
     if (a.ldx >= (1 << 22) || a.ldw >= (1 << 22)) return false;   // per-lane byte offsets of a tile stay below 2^31
@@ -539,6 +539,8 @@ hipError_t launch_gemm_tiled(const GemmArgs &a, int variant, hipStream_t s) {
     const bool f16 = (a.x_dtype == TBIK_F16);
     // 128 x 128, wave tile 64 x 64, 5 x 32 KiB stage slots = all of LDS
     if (variant == VARIANT_T128) return f16 ? launch_shape<2, 2, 2, 2, 5, true>(a, s) : launch_shape<2, 2, 2, 2, 5, false>(a, s);
+    // 64 x 128, wave tile 64 x 32, 6 x 24 KiB: batches of 33..64 rows without the idle upper half of a 128-row tile
+    if (variant == VARIANT_T64) return f16 ? launch_shape<1, 4, 2, 1, 6, true>(a, s) : launch_shape<1, 4, 2, 1, 6, false>(a, s);
     // 32 x 128, wave tile 32 x 32, 6 x 20 KiB: deep prefetch for weight streaming
     return f16 ? launch_shape<1, 4, 1, 1, 6, true>(a, s) : launch_shape<1, 4, 1, 1, 6, false>(a, s);
 }

@@ -10,7 +10,7 @@ namespace {
 std::atomic<int> g_last_hip_error{0};
 std::atomic<int> g_forced_variant{VARIANT_AUTO};
 
-const char *const kVariantNames[VARIANT_COUNT] = {"auto", "reference", "tile128x128", "tile32x128"};
+const char *const kVariantNames[VARIANT_COUNT] = {"auto", "reference", "tile128x128", "tile32x128", "tile64x128"};
 
 inline bool is_pow2(int64_t v) { return v >= 1 && (v & (v - 1)) == 0; }
 inline bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
@@ -51,7 +51,7 @@ int check_operands(const void *X, int64_t ldx, const void *W, int64_t ldw, int N
 // combined by the same tree (Theorem 1: identical bits).  A pure function of the shape, so that
 // tbik_gemm_workspace_bytes() can be evaluated without a device.
 int internal_split(int M, int N, int ns) {
-    const int64_t bm = (M > 32) ? 128 : 32;
+    const int64_t bm = (M > 64) ? 128 : (M > 32) ? 64 : 32;
     const int64_t tiles = ((M + bm - 1) / bm) * (((int64_t)N + 127) / 128);
     int split = 1;
     while (ns / split > 16 && split < TBIK_MAX_SHARDS) split *= 2;   // the tiled kernel walks at most 16 superleaves per shard
@@ -63,7 +63,8 @@ int internal_split(int M, int N, int ns) {
 int pick_variant(const GemmArgs &a) {
     const int forced = g_forced_variant.load();
     if (forced != VARIANT_AUTO) return (forced == VARIANT_REFERENCE || gemm_tiled_supports(a, forced)) ? forced : VARIANT_REFERENCE;
-    if (a.M > 32 && gemm_tiled_supports(a, VARIANT_T128)) return VARIANT_T128;
+    if (a.M > 64 && gemm_tiled_supports(a, VARIANT_T128)) return VARIANT_T128;
+    if (a.M > 32 && gemm_tiled_supports(a, VARIANT_T64)) return VARIANT_T64;
     if (gemm_tiled_supports(a, VARIANT_T32)) return VARIANT_T32;
     if (gemm_tiled_supports(a, VARIANT_T128)) return VARIANT_T128;
     return VARIANT_REFERENCE;

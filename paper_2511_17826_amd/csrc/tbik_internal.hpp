@@ -60,6 +60,6 @@ size_t row_reduce_workspace(int M, int64_t V, int x_dtype, int op);
 hipError_t launch_row_reduce(const void *x, int x_dtype, void *out, int op, int M, int64_t V, void *ws, hipStream_t s);
 int set_row_wait_limit(int polls);   // returns the previous limit
 
-enum { VARIANT_AUTO = 0, VARIANT_REFERENCE = 1, VARIANT_T128 = 2, VARIANT_T32 = 3, VARIANT_COUNT = 4 };
+enum { VARIANT_AUTO = 0, VARIANT_REFERENCE = 1, VARIANT_T128 = 2, VARIANT_T32 = 3, VARIANT_T64 = 4, VARIANT_COUNT = 5 };
 
 }  // namespace tbik

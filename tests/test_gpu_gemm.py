@@ -21,7 +21,7 @@ from paper_2511_17826_amd import synthetic as syn
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = [tb.VARIANT_REFERENCE, tb.VARIANT_T128, tb.VARIANT_T32]
+VARIANTS = [tb.VARIANT_REFERENCE, tb.VARIANT_T128, tb.VARIANT_T32, tb.VARIANT_T64]
 
 
 @pytest.fixture(autouse=True)
@@ -224,7 +224,7 @@ def test_8b_shapes_invariance_and_sampled_parity(name):
     assert len(digests) == 1                      # the analogue of "count of unique outputs = 1"
     # every M (prefix of the batch), default variant and forced variants, P in {whole, 8}
     for M in Ms:
-        for v in ([tb.VARIANT_AUTO, tb.VARIANT_T128, tb.VARIANT_T32] if M <= 1024 else [tb.VARIANT_AUTO]):
+        for v in ([tb.VARIANT_AUTO, tb.VARIANT_T128, tb.VARIANT_T32, tb.VARIANT_T64] if M <= 1024 else [tb.VARIANT_AUTO]):
             tb.tbik_set_gemm_variant(v)
             y = tb.tbik_gemm(Xd[:M], Wd, leaf, g, out_dtype=torch.float32)
             assert torch.equal(y.view(torch.int32), full[:M].view(torch.int32)), (M, v)

@@ -17,7 +17,7 @@ from paper_2511_17826_amd import synthetic as syn
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = [tb.VARIANT_REFERENCE, tb.VARIANT_T128, tb.VARIANT_T32]
+VARIANTS = [tb.VARIANT_REFERENCE, tb.VARIANT_T128, tb.VARIANT_T32, tb.VARIANT_T64]
 
 
 @pytest.fixture(autouse=True)
@@ -156,7 +156,7 @@ def test_oproj_shape_invariance_and_sampled_parity():
         digests.add(gu.digest(tb.tbik_gemm_f16(Xd, Wd, leaf, g, out_dtype=torch.float32)))
     assert len(digests) == 1
     for M in (1, 16, 64, 256, 1024):
-        for v in (tb.VARIANT_AUTO, tb.VARIANT_T128, tb.VARIANT_T32):
+        for v in (tb.VARIANT_AUTO, tb.VARIANT_T128, tb.VARIANT_T32, tb.VARIANT_T64):
             tb.tbik_set_gemm_variant(v)
             y = tb.tbik_gemm_f16(Xd[:M], Wd, leaf, g, out_dtype=torch.float32)
             assert torch.equal(y.view(torch.int32), full[:M].view(torch.int32)), (M, v)

@@ -42,7 +42,7 @@ def test_gemm_random_shapes_all_variants_and_shard_counts():
         gemm = tb.tbik_gemm_f16 if fmt == "fp16" else tb.tbik_gemm
         parts_of = tb.tbik_gemm_shard_partials_f16 if fmt == "fp16" else tb.tbik_gemm_shard_partials
         Xd, Wd = dev(Xb), dev(Wb)
-        for v in (tb.VARIANT_REFERENCE, tb.VARIANT_T128, tb.VARIANT_T32, tb.VARIANT_AUTO):
+        for v in (tb.VARIANT_REFERENCE, tb.VARIANT_T128, tb.VARIANT_T32, tb.VARIANT_T64, tb.VARIANT_AUTO):
             tb.tbik_set_gemm_variant(v)
             y = gemm(Xd, Wd, leaf, g, out_dtype=torch.float32)
             assert np.array_equal(gu.host_f32(y), want), (case, M, K, N, leaf, g, v, fmt)
@@ -58,7 +58,7 @@ def test_gemm_random_shapes_all_variants_and_shard_counts():
         Xd, Wd = gu.dev_bf16(Xb), gu.dev_bf16(Wb)
         tb.tbik_set_gemm_variant(tb.VARIANT_REFERENCE)
         ref = tb.tbik_gemm(Xd, Wd, leaf, g, out_dtype=torch.float32)
-        for v in (tb.VARIANT_T128, tb.VARIANT_T32, tb.VARIANT_AUTO):
+        for v in (tb.VARIANT_T128, tb.VARIANT_T32, tb.VARIANT_T64, tb.VARIANT_AUTO):
             tb.tbik_set_gemm_variant(v)
             for P in (1, 2, ns):
                 y = tb.tbik_tree_combine(tb.tbik_gemm_shard_partials(Xd, Wd, leaf, g, P), out_dtype=torch.float32)
