@@ -142,11 +142,11 @@ int tbik_combine_residual_rmsnorm(const float *partials, int P, const void *resi
  *   TBIK_MAX         out[m]   = max_i x[m,i]                                       out fp32 [M]
  *   TBIK_LOGSOFTMAX  out[m,i] = (x[m,i] - mx) - log(TreeSum_j exp(x[m,j] - mx)),   out fp32 [M, V]
  *                    mx = max_j x[m,j]
- * TreeSum leaves are in-order fp32 sums of one 16-byte chunk of the row (4 fp32 or 8 bf16
+ * TreeSum leaves are in-order fp32 sums of one 16-byte chunk of the row (4 fp32 or 8 bf16 or fp16
  * elements; the last leaf may be short), padded with +0 leaves to a power of two, then T.
- * x_dtype TBIK_BF16 inputs are widened to fp32 first.  V == 0 is TBIK_ERR_SHAPE.
+ * x_dtype TBIK_BF16 and TBIK_F16 inputs are widened to fp32 first (exact).  V == 0 is TBIK_ERR_SHAPE.
  *
- *   x          device, x_dtype, dense [M, V], 16-byte aligned, V a multiple of 4 (fp32) / 8 (bf16)
+ *   x          device, x_dtype, dense [M, V], 16-byte aligned, V a multiple of 4 (fp32) / 8 (bf16, fp16)
  *   workspace  at least tbik_row_reduce_workspace_bytes(M, V, op) bytes, 256-byte aligned
  * Errors: NULL, SHAPE, DTYPE, ALIGN, WORKSPACE, HIP.
  */
@@ -214,6 +214,17 @@ int tbik_gemm_shard_partials_f16(const void *X, int64_t ldx, const void *W, int6
 int tbik_gemm_reference_f16(const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
                             void *Y, int64_t ldy, tbik_dtype y_dtype,
                             int M, int N, int K, int leaf, int k_first, int P, void *hip_stream);
+
+/*
+ * tbik_rmsnorm and tbik_combine_residual_rmsnorm for tensors of IEEE binary16 (App. B and Alg. 2 do not depend on
+ * the storage format): every 16-bit tensor of the call (x, weight, y; residual, hidden, normed) is fp16, widened
+ * exactly, all arithmetic is the fp32 arithmetic stated above in the same order, and each output takes one rounding
+ * to fp16 (nearest-even; overflow gives infinity) where the bf16 calls round to bf16.  Same arguments, limits,
+ * aliasing rule and errors.
+ */
+int tbik_rmsnorm_f16(const void *x, const void *weight, void *y, int M, int H, float eps, void *hip_stream);
+int tbik_combine_residual_rmsnorm_f16(const float *partials, int P, const void *residual, const void *weight, float eps,
+                                      void *hidden, void *normed, int M, int H, void *hip_stream);
 
 /* Forces an internal GEMM variant (testing and tuning only; the bits never depend on it).
  * 0 = choose from the shape (default); other values are listed in tbik_variant_name(). */

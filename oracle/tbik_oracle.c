@@ -403,12 +403,12 @@ float tbik_oracle_treesum(const float *v, long n, int leaf) {
 }
 
 /*
- * RMSNorm of bf16 rows (App. B: each row reduced on its own in a fixed order):
- *   ss = TreeSum_i( x_i * x_i )        squares of bf16 values are exact in fp32
+ * RMSNorm of rows of 16-bit values, bf16 or binary16 (App. B: each row reduced on its own in a fixed order):
+ *   ss = TreeSum_i( x_i * x_i )        squares of values of either format are exact in fp32
  *   r  = 1 / sqrt( ss / H + eps )      correctly rounded fp32 divide and sqrt
- *   y_i = bf16( (x_i * r) * w_i )      one rounding to bf16, at the end
+ *   y_i = round16( (x_i * r) * w_i )   one rounding to the rows' format, at the end
  */
-int tbik_oracle_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int M, int H, float eps, int leaf) {
+int tbik_oracle_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int M, int H, float eps, int leaf, int fmt) {
     if (H <= 0 || leaf <= 0) return -1;
 #pragma omp parallel
     {
@@ -417,15 +417,15 @@ int tbik_oracle_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int M
         for (long m = 0; m < M; ++m) {
             const uint16_t *row = x + m * (long)H;
             for (int i = 0; i < H; ++i) {
-                float xv = bf16_to_f32(row[i]);
+                float xv = widen16(row[i], fmt);
                 sq[i] = xv * xv;
             }
             float ss = tbik_oracle_treesum(sq, H, leaf);
             float ms = ss / (float)H;
             float r = 1.0f / sqrtf(ms + eps);
             for (int i = 0; i < H; ++i) {
-                float t = bf16_to_f32(row[i]) * r;
-                y[m * (long)H + i] = f32_to_bf16(t * bf16_to_f32(w[i]));
+                float t = widen16(row[i], fmt) * r;
+                y[m * (long)H + i] = round16(t * widen16(w[i], fmt), fmt);
             }
         }
         free(sq);
@@ -434,10 +434,10 @@ int tbik_oracle_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int M
 }
 
 /* The sum of squares alone (to pin the reduction separately from the epilogue). */
-float tbik_oracle_sumsq_bf16(const uint16_t *row, int H, int leaf) {
+float tbik_oracle_sumsq16(const uint16_t *row, int H, int leaf, int fmt) {
     float *sq = (float *)malloc((size_t)H * sizeof(float));
     for (int i = 0; i < H; ++i) {
-        float xv = bf16_to_f32(row[i]);
+        float xv = widen16(row[i], fmt);
         sq[i] = xv * xv;
     }
     float ss = tbik_oracle_treesum(sq, H, leaf);

@@ -72,9 +72,9 @@ def lib():
         L.tbik_oracle_treesum.restype = C.c_float
         L.tbik_oracle_treesum.argtypes = [f32p, C.c_long, C.c_int]
         L.tbik_oracle_rmsnorm.restype = C.c_int
-        L.tbik_oracle_rmsnorm.argtypes = [u16p, u16p, u16p, C.c_int, C.c_int, C.c_float, C.c_int]
-        L.tbik_oracle_sumsq_bf16.restype = C.c_float
-        L.tbik_oracle_sumsq_bf16.argtypes = [u16p, C.c_int, C.c_int]
+        L.tbik_oracle_rmsnorm.argtypes = [u16p, u16p, u16p, C.c_int, C.c_int, C.c_float, C.c_int, C.c_int]
+        L.tbik_oracle_sumsq16.restype = C.c_float
+        L.tbik_oracle_sumsq16.argtypes = [u16p, C.c_int, C.c_int, C.c_int]
         L.tbik_oracle_row_sum.restype = C.c_int
         L.tbik_oracle_row_sum.argtypes = [f32p, f32p, C.c_int, C.c_long, C.c_int]
         L.tbik_oracle_row_max.restype = C.c_int
@@ -243,30 +243,39 @@ def treesum(v, leaf: int) -> np.float32:
     return np.float32(lib().tbik_oracle_treesum(p, a.size, leaf))
 
 
-def rmsnorm(x, w, eps: float = 1e-6, leaf: int = LEAF_BF16) -> np.ndarray:
+def rmsnorm(x, w, eps: float = 1e-6, leaf: int = LEAF_BF16, fmt: str = "bf16") -> np.ndarray:
+    """RMSNorm of rows of 16-bit patterns of format `fmt` (weight and output in the same format)."""
     x, xp = _u16(x)
     w, wp = _u16(w)
     M, H = x.shape
     y = np.empty((M, H), dtype=np.uint16)
-    rc = lib().tbik_oracle_rmsnorm(xp, wp, y.ctypes.data_as(C.POINTER(C.c_uint16)), M, H, eps, leaf)
+    rc = lib().tbik_oracle_rmsnorm(xp, wp, y.ctypes.data_as(C.POINTER(C.c_uint16)), M, H, eps, leaf, FORMATS[fmt])
     assert rc == 0
     return y
 
 
-def combine_residual_rmsnorm(partials, residual_bits, weight_bits, eps: float = 1e-6):
-    """The tail of a row-parallel layer, one step after the other: Y = bf16(T(partials)) by the reduce phase of Alg. 2
-    (Sec. 3.3); Hd = bf16(Y + R), the sum formed in fp32 and rounded once; O = RMSNorm(Hd) (App. B).
-    Returns (Hd bits, O bits), uint16 [M, H]."""
-    _, ybf = tree_combine(partials)
-    widen = lambda b: (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
-    h32 = (widen(ybf) + widen(residual_bits)).astype(np.float32)          # one IEEE binary32 addition per element
-    hbits = f32_to_bf16_bits(h32)
-    return hbits, rmsnorm(hbits, weight_bits, eps)
+def combine_residual_rmsnorm(partials, residual_bits, weight_bits, eps: float = 1e-6, fmt: str = "bf16"):
+    """The tail of a row-parallel layer, one step after the other: Y = round16(T(partials)) by the reduce phase of
+    Alg. 2 (Sec. 3.3); Hd = round16(Y + R), the sum formed in fp32 and rounded once; O = RMSNorm(Hd) (App. B).
+    Every 16-bit tensor has the format `fmt`.  Returns (Hd bits, O bits), uint16 [M, H]."""
+    _, y16 = tree_combine(partials, fmt=fmt)
+    if fmt == "bf16":
+        widen = lambda b: (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+        narrow = f32_to_bf16_bits
+    else:
+        widen, narrow = f16_bits_to_f32, f32_to_f16_bits
+    h32 = (widen(y16) + widen(residual_bits)).astype(np.float32)          # one IEEE binary32 addition per element
+    hbits = narrow(h32)
+    return hbits, rmsnorm(hbits, weight_bits, eps, fmt=fmt)
+
+
+def sumsq16(row, leaf: int = LEAF_BF16, fmt: str = "bf16") -> np.float32:
+    row, rp = _u16(row)
+    return np.float32(lib().tbik_oracle_sumsq16(rp, row.size, leaf, FORMATS[fmt]))
 
 
 def sumsq_bf16(row, leaf: int = LEAF_BF16) -> np.float32:
-    row, rp = _u16(row)
-    return np.float32(lib().tbik_oracle_sumsq_bf16(rp, row.size, leaf))
+    return sumsq16(row, leaf, "bf16")
 
 
 def row_sum(x, leaf: int = LEAF_F32) -> np.ndarray:

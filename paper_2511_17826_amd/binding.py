@@ -46,6 +46,9 @@ SIGNATURES = {
                                           C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
     "tbik_combine_residual_rmsnorm": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p,
                                                 C.c_int, C.c_int, C.c_void_p]),
+    "tbik_rmsnorm_f16": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_void_p]),
+    "tbik_combine_residual_rmsnorm_f16": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p,
+                                                    C.c_void_p, C.c_int, C.c_int, C.c_void_p]),
     "tbik_attention": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
                                  C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_int64,
                                  C.c_float, C.c_int, C.c_void_p]),
@@ -211,32 +214,55 @@ def tbik_tree_combine(partials: torch.Tensor, out_dtype=torch.bfloat16, out: tor
     return out
 
 
-def tbik_rmsnorm(x: torch.Tensor, weight: torch.Tensor, eps: float = 1e-6, out: torch.Tensor | None = None) -> torch.Tensor:
-    assert x.dim() == 2 and x.is_contiguous() and x.dtype == torch.bfloat16
-    assert weight.is_contiguous() and weight.dtype == torch.bfloat16 and weight.numel() == x.shape[1]
+def _rmsnorm(name, dtype, x, weight, eps, out):
+    assert x.dim() == 2 and x.is_contiguous() and x.dtype == dtype
+    assert weight.is_contiguous() and weight.dtype == dtype and weight.numel() == x.shape[1]
     if out is None:
         out = torch.empty_like(x)
-    st = lib().tbik_rmsnorm(x.data_ptr(), weight.data_ptr(), out.data_ptr(), x.shape[0], x.shape[1], eps, _stream())
-    _check(st, "tbik_rmsnorm")
+    assert out.shape == x.shape and out.is_contiguous() and out.dtype == dtype
+    st = getattr(lib(), name)(x.data_ptr(), weight.data_ptr(), out.data_ptr(), x.shape[0], x.shape[1], eps, _stream())
+    _check(st, name)
     return out
+
+
+def tbik_rmsnorm(x: torch.Tensor, weight: torch.Tensor, eps: float = 1e-6, out: torch.Tensor | None = None) -> torch.Tensor:
+    return _rmsnorm("tbik_rmsnorm", torch.bfloat16, x, weight, eps, out)
+
+
+def tbik_rmsnorm_f16(x: torch.Tensor, weight: torch.Tensor, eps: float = 1e-6, out: torch.Tensor | None = None) -> torch.Tensor:
+    return _rmsnorm("tbik_rmsnorm_f16", torch.float16, x, weight, eps, out)
+
+
+def _combine_residual_rmsnorm(name, dtype, partials, residual, weight, eps, hidden, normed):
+    assert partials.dim() == 3 and partials.is_contiguous() and partials.dtype == torch.float32
+    P, M, H = partials.shape
+    assert residual.shape == (M, H) and residual.is_contiguous() and residual.dtype == dtype
+    assert weight.shape == (H,) and weight.dtype == dtype
+    if hidden is None:
+        hidden = torch.empty_like(residual)
+    if normed is None:
+        normed = torch.empty_like(residual)
+    assert hidden.is_contiguous() and normed.is_contiguous() and hidden.dtype == normed.dtype == dtype
+    assert hidden.shape == normed.shape == (M, H)
+    st = getattr(lib(), name)(partials.data_ptr(), P, residual.data_ptr(), weight.data_ptr(), eps,
+                              hidden.data_ptr(), normed.data_ptr(), M, H, _stream())
+    _check(st, name)
+    return hidden, normed
 
 
 def tbik_combine_residual_rmsnorm(partials: torch.Tensor, residual: torch.Tensor, weight: torch.Tensor, eps: float = 1e-6,
                                   hidden: torch.Tensor | None = None, normed: torch.Tensor | None = None):
     """(hidden, normed): hidden = bf16(bf16(T(partials)) + residual), normed = RMSNorm(hidden); one kernel."""
-    assert partials.dim() == 3 and partials.is_contiguous() and partials.dtype == torch.float32
-    P, M, H = partials.shape
-    assert residual.shape == (M, H) and residual.is_contiguous() and residual.dtype == torch.bfloat16
-    assert weight.shape == (H,) and weight.dtype == torch.bfloat16
-    if hidden is None:
-        hidden = torch.empty_like(residual)
-    if normed is None:
-        normed = torch.empty_like(residual)
-    assert hidden.is_contiguous() and normed.is_contiguous() and hidden.dtype == normed.dtype == torch.bfloat16
-    st = lib().tbik_combine_residual_rmsnorm(partials.data_ptr(), P, residual.data_ptr(), weight.data_ptr(), eps,
-                                             hidden.data_ptr(), normed.data_ptr(), M, H, _stream())
-    _check(st, "tbik_combine_residual_rmsnorm")
-    return hidden, normed
+    return _combine_residual_rmsnorm("tbik_combine_residual_rmsnorm", torch.bfloat16, partials, residual, weight, eps,
+                                     hidden, normed)
+
+
+def tbik_combine_residual_rmsnorm_f16(partials: torch.Tensor, residual: torch.Tensor, weight: torch.Tensor,
+                                      eps: float = 1e-6, hidden: torch.Tensor | None = None,
+                                      normed: torch.Tensor | None = None):
+    """The same with fp16 residual, weight and outputs."""
+    return _combine_residual_rmsnorm("tbik_combine_residual_rmsnorm_f16", torch.float16, partials, residual, weight, eps,
+                                     hidden, normed)
 
 
 def _token_major(t: torch.Tensor, name: str):

@@ -14,17 +14,13 @@ namespace tbik {
 constexpr int RMS_ROWS_PER_BLOCK = 4;
 constexpr int RMS_MAX_SEG_LEVELS = 8;   // up to 2^7 = 128 segments of 64 leaves of 8 elements = 65536 columns
 
-__device__ __forceinline__ void unpack8(const uint4 &v, float (&f)[8]) {
-    f[0] = bf16_bits_to_f32(v.x & 0xffffu); f[1] = bf16_bits_to_f32(v.x >> 16);
-    f[2] = bf16_bits_to_f32(v.y & 0xffffu); f[3] = bf16_bits_to_f32(v.y >> 16);
-    f[4] = bf16_bits_to_f32(v.z & 0xffffu); f[5] = bf16_bits_to_f32(v.z >> 16);
-    f[6] = bf16_bits_to_f32(v.w & 0xffffu); f[7] = bf16_bits_to_f32(v.w >> 16);
-}
-
+// F16 in the kernels below: the rows, the weight and the outputs are IEEE binary16 instead of bf16 (squares of
+// either are exact in fp32; one rounding to nearest-even at the end).
+//
 // Register-resident variant for rows of at most 64*CPL chunks (H <= 512*CPL): the row is read once, kept as packed
-// bf16 in registers across the reduction and normalised from there.  Same leaves, same tree, same bits as the
+// 16-bit values in registers across the reduction and normalised from there.  Same leaves, same tree, same bits as the
 // two-pass kernel below.
-template <int CPL>
+template <int CPL, bool F16>
 __global__ __launch_bounds__(64 * RMS_ROWS_PER_BLOCK) void rmsnorm_regs_kernel(
         const uint16_t *__restrict__ x, const uint16_t *__restrict__ w, uint16_t *__restrict__ y,
         int M, int H, float eps, int nseg2) {
@@ -47,7 +43,7 @@ __global__ __launch_bounds__(64 * RMS_ROWS_PER_BLOCK) void rmsnorm_regs_kernel(
 #pragma unroll
     for (int s = 0; s < CPL; ++s) {
         float f[8], leaf = 0.0f;
-        unpack8(xv[s], f);                             // a chunk past the row is all +0: its leaf is +0
+        unpack8<F16>(xv[s], f);                             // a chunk past the row is all +0: its leaf is +0
 #pragma unroll
         for (int e = 0; e < 8; ++e) leaf = leaf + f[e] * f[e];
         if (s < nseg2) ss = st.push(wave_tree_sum(leaf), (unsigned)s);
@@ -60,19 +56,20 @@ __global__ __launch_bounds__(64 * RMS_ROWS_PER_BLOCK) void rmsnorm_regs_kernel(
         const int c = s * 64 + lane;
         if (c < nchunks) {
             float f[8], g[8];
-            unpack8(xv[s], f);
-            unpack8(wr[c], g);
+            unpack8<F16>(xv[s], f);
+            unpack8<F16>(wr[c], g);
             float o[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float t = f[e] * r;
                 o[e] = t * g[e];
             }
-            yr[c] = make_uint4(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7]));
+            yr[c] = make_uint4(pack_16x2<F16>(o[0], o[1]), pack_16x2<F16>(o[2], o[3]), pack_16x2<F16>(o[4], o[5]), pack_16x2<F16>(o[6], o[7]));
         }
     }
 }
 
+template <bool F16>
 __global__ __launch_bounds__(64 * RMS_ROWS_PER_BLOCK) void rmsnorm_kernel(
         const uint16_t *__restrict__ x, const uint16_t *__restrict__ w, uint16_t *__restrict__ y,
         int M, int H, float eps, int nseg2) {
@@ -91,7 +88,7 @@ __global__ __launch_bounds__(64 * RMS_ROWS_PER_BLOCK) void rmsnorm_kernel(
         float leaf = 0.0f;
         if (c < nchunks) {
             float f[8];
-            unpack8(xr[c], f);
+            unpack8<F16>(xr[c], f);
 #pragma unroll
             for (int e = 0; e < 8; ++e) leaf = leaf + f[e] * f[e];
         }
@@ -102,15 +99,15 @@ __global__ __launch_bounds__(64 * RMS_ROWS_PER_BLOCK) void rmsnorm_kernel(
 
     for (int c = lane; c < nchunks; c += 64) {
         float f[8], g[8];
-        unpack8(xr[c], f);
-        unpack8(wr[c], g);
+        unpack8<F16>(xr[c], f);
+        unpack8<F16>(wr[c], g);
         float o[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const float t = f[e] * r;
             o[e] = t * g[e];
         }
-        yr[c] = make_uint4(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7]));
+        yr[c] = make_uint4(pack_16x2<F16>(o[0], o[1]), pack_16x2<F16>(o[2], o[3]), pack_16x2<F16>(o[4], o[5]), pack_16x2<F16>(o[6], o[7]));
     }
 }
 
@@ -118,7 +115,7 @@ __global__ __launch_bounds__(64 * RMS_ROWS_PER_BLOCK) void rmsnorm_kernel(
 // (Alg. 2's additions, one rounding), H = bf16(Y + R) with the residual R, then the RMSNorm above over the row of H.
 // One wavefront per row; first pass: combine, add, store H, leaf sums of squares; second pass: re-read H (the
 // wavefront's own stores, served by the cache) and scale.  Bit for bit the three separate calls.
-template <int P>
+template <int P, bool F16>
 __global__ __launch_bounds__(64 * RMS_ROWS_PER_BLOCK) void combine_residual_rmsnorm_kernel(
         const float *__restrict__ partials, const uint16_t *res, const uint16_t *__restrict__ w,
         uint16_t *hidden, uint16_t *__restrict__ normed, int M, int H, float eps, int nseg2) {
@@ -157,14 +154,14 @@ __global__ __launch_bounds__(64 * RMS_ROWS_PER_BLOCK) void combine_residual_rmsn
                 y[e] = tree_of<P>(v);
             }
             float r[8], yb[8], h[8];
-            unpack8(rr[c], r);
-            unpack8(make_uint4(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]), pack_bf16x2(y[6], y[7])), yb);
+            unpack8<F16>(rr[c], r);
+            unpack8<F16>(make_uint4(pack_16x2<F16>(y[0], y[1]), pack_16x2<F16>(y[2], y[3]), pack_16x2<F16>(y[4], y[5]), pack_16x2<F16>(y[6], y[7])), yb);
 #pragma unroll
             for (int e = 0; e < 8; ++e) h[e] = yb[e] + r[e];
-            const uint4 hv = make_uint4(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]), pack_bf16x2(h[4], h[5]), pack_bf16x2(h[6], h[7]));
+            const uint4 hv = make_uint4(pack_16x2<F16>(h[0], h[1]), pack_16x2<F16>(h[2], h[3]), pack_16x2<F16>(h[4], h[5]), pack_16x2<F16>(h[6], h[7]));
             hr[c] = hv;
             float f[8];
-            unpack8(hv, f);
+            unpack8<F16>(hv, f);
 #pragma unroll
             for (int e = 0; e < 8; ++e) leaf = leaf + f[e] * f[e];
         }
@@ -175,36 +172,60 @@ __global__ __launch_bounds__(64 * RMS_ROWS_PER_BLOCK) void combine_residual_rmsn
 
     for (int c = lane; c < nchunks; c += 64) {
         float f[8], g[8];
-        unpack8(hr[c], f);
-        unpack8(wr[c], g);
+        unpack8<F16>(hr[c], f);
+        unpack8<F16>(wr[c], g);
         float o[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const float t = f[e] * rinv;
             o[e] = t * g[e];
         }
-        yr[c] = make_uint4(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7]));
+        yr[c] = make_uint4(pack_16x2<F16>(o[0], o[1]), pack_16x2<F16>(o[2], o[3]), pack_16x2<F16>(o[4], o[5]), pack_16x2<F16>(o[6], o[7]));
     }
 }
 
 // hidden = bf16(y + residual), 8 elements per thread (the middle step of the unfused route below).
+template <bool F16>
 __global__ __launch_bounds__(256) void residual_add_kernel(const uint16_t *__restrict__ y, const uint16_t *res,
                                                            uint16_t *hidden, int64_t nchunks) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < nchunks; c += stride) {
         float a[8], b[8];
-        unpack8(reinterpret_cast<const uint4 *>(y)[c], a);
-        unpack8(reinterpret_cast<const uint4 *>(res)[c], b);
+        unpack8<F16>(reinterpret_cast<const uint4 *>(y)[c], a);
+        unpack8<F16>(reinterpret_cast<const uint4 *>(res)[c], b);
         float h[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) h[e] = a[e] + b[e];
         reinterpret_cast<uint4 *>(hidden)[c] =
-            make_uint4(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]), pack_bf16x2(h[4], h[5]), pack_bf16x2(h[6], h[7]));
+            make_uint4(pack_16x2<F16>(h[0], h[1]), pack_16x2<F16>(h[2], h[3]), pack_16x2<F16>(h[4], h[5]), pack_16x2<F16>(h[6], h[7]));
     }
 }
 
-hipError_t launch_combine_residual_rmsnorm(const float *partials, int P, const uint16_t *res, const uint16_t *w,
-                                           uint16_t *hidden, uint16_t *normed, int M, int H, float eps, hipStream_t s) {
+template <bool F16>
+static hipError_t rmsnorm_of(const uint16_t *x, const uint16_t *w, uint16_t *y, int M, int H, float eps, hipStream_t s) {
+    if (M <= 0) return hipSuccess;
+    const int nchunks = H / 8;
+    int n2 = 1;
+    while (n2 < nchunks) n2 *= 2;
+    const int nseg2 = n2 < 64 ? 1 : n2 / 64;
+    dim3 grid((M + RMS_ROWS_PER_BLOCK - 1) / RMS_ROWS_PER_BLOCK), block(64 * RMS_ROWS_PER_BLOCK);
+    const int cpl = (nchunks + 63) / 64;
+    if (cpl <= 2) hipLaunchKernelGGL((rmsnorm_regs_kernel<2, F16>), grid, block, 0, s, x, w, y, M, H, eps, nseg2);
+    else if (cpl <= 4) hipLaunchKernelGGL((rmsnorm_regs_kernel<4, F16>), grid, block, 0, s, x, w, y, M, H, eps, nseg2);
+    else if (cpl <= 8) hipLaunchKernelGGL((rmsnorm_regs_kernel<8, F16>), grid, block, 0, s, x, w, y, M, H, eps, nseg2);
+    else if (cpl <= 10) hipLaunchKernelGGL((rmsnorm_regs_kernel<10, F16>), grid, block, 0, s, x, w, y, M, H, eps, nseg2);
+    else if (cpl <= 16) hipLaunchKernelGGL((rmsnorm_regs_kernel<16, F16>), grid, block, 0, s, x, w, y, M, H, eps, nseg2);
+    else hipLaunchKernelGGL(rmsnorm_kernel<F16>, grid, block, 0, s, x, w, y, M, H, eps, nseg2);
+    return hipGetLastError();
+}
+
+hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int M, int H, float eps, int dtype, hipStream_t s) {
+    return dtype == TBIK_F16 ? rmsnorm_of<true>(x, w, y, M, H, eps, s) : rmsnorm_of<false>(x, w, y, M, H, eps, s);
+}
+
+template <bool F16>
+static hipError_t tail_of(const float *partials, int P, const uint16_t *res, const uint16_t *w, uint16_t *hidden,
+                          uint16_t *normed, int M, int H, float eps, hipStream_t s) {
     if (M <= 0) return hipSuccess;
     const int nchunks = H / 8;
     int n2 = 1;
@@ -213,43 +234,32 @@ hipError_t launch_combine_residual_rmsnorm(const float *partials, int P, const u
     // With many partial tensors and a large batch the row-per-wavefront walk over P planes falls behind the plain
     // combine kernel; then the three steps run one after the other (the normed buffer holds Y in between).  Same bits.
     if (P > 4 && (int64_t)M * H * P > (int64_t)32 << 20) {
-        hipError_t e = launch_tree_combine(partials, P, normed, H, TBIK_BF16, M, H, s);
+        hipError_t e = launch_tree_combine(partials, P, normed, H, F16 ? TBIK_F16 : TBIK_BF16, M, H, s);
         if (e != hipSuccess) return e;
         const int64_t chunks = (int64_t)M * H / 8;
         const int64_t blocks = (chunks + 255) / 256;
-        hipLaunchKernelGGL(residual_add_kernel, dim3((unsigned)(blocks < 65536 ? blocks : 65536)), dim3(256), 0, s, normed, res,
+        hipLaunchKernelGGL(residual_add_kernel<F16>, dim3((unsigned)(blocks < 65536 ? blocks : 65536)), dim3(256), 0, s, normed, res,
                            hidden, chunks);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
-        return launch_rmsnorm(hidden, w, normed, M, H, eps, s);
+        return rmsnorm_of<F16>(hidden, w, normed, M, H, eps, s);
     }
     dim3 grid((M + RMS_ROWS_PER_BLOCK - 1) / RMS_ROWS_PER_BLOCK), block(64 * RMS_ROWS_PER_BLOCK);
     switch (P) {
-        case 1: hipLaunchKernelGGL(combine_residual_rmsnorm_kernel<1>, grid, block, 0, s, partials, res, w, hidden, normed, M, H, eps, nseg2); break;
-        case 2: hipLaunchKernelGGL(combine_residual_rmsnorm_kernel<2>, grid, block, 0, s, partials, res, w, hidden, normed, M, H, eps, nseg2); break;
-        case 4: hipLaunchKernelGGL(combine_residual_rmsnorm_kernel<4>, grid, block, 0, s, partials, res, w, hidden, normed, M, H, eps, nseg2); break;
-        case 8: hipLaunchKernelGGL(combine_residual_rmsnorm_kernel<8>, grid, block, 0, s, partials, res, w, hidden, normed, M, H, eps, nseg2); break;
-        case 16: hipLaunchKernelGGL(combine_residual_rmsnorm_kernel<16>, grid, block, 0, s, partials, res, w, hidden, normed, M, H, eps, nseg2); break;
+        case 1: hipLaunchKernelGGL((combine_residual_rmsnorm_kernel<1, F16>), grid, block, 0, s, partials, res, w, hidden, normed, M, H, eps, nseg2); break;
+        case 2: hipLaunchKernelGGL((combine_residual_rmsnorm_kernel<2, F16>), grid, block, 0, s, partials, res, w, hidden, normed, M, H, eps, nseg2); break;
+        case 4: hipLaunchKernelGGL((combine_residual_rmsnorm_kernel<4, F16>), grid, block, 0, s, partials, res, w, hidden, normed, M, H, eps, nseg2); break;
+        case 8: hipLaunchKernelGGL((combine_residual_rmsnorm_kernel<8, F16>), grid, block, 0, s, partials, res, w, hidden, normed, M, H, eps, nseg2); break;
+        case 16: hipLaunchKernelGGL((combine_residual_rmsnorm_kernel<16, F16>), grid, block, 0, s, partials, res, w, hidden, normed, M, H, eps, nseg2); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
-hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int M, int H, float eps, hipStream_t s) {
-    if (M <= 0) return hipSuccess;
-    const int nchunks = H / 8;
-    int n2 = 1;
-    while (n2 < nchunks) n2 *= 2;
-    const int nseg2 = n2 < 64 ? 1 : n2 / 64;
-    dim3 grid((M + RMS_ROWS_PER_BLOCK - 1) / RMS_ROWS_PER_BLOCK), block(64 * RMS_ROWS_PER_BLOCK);
-    const int cpl = (nchunks + 63) / 64;
-    if (cpl <= 2) hipLaunchKernelGGL(rmsnorm_regs_kernel<2>, grid, block, 0, s, x, w, y, M, H, eps, nseg2);
-    else if (cpl <= 4) hipLaunchKernelGGL(rmsnorm_regs_kernel<4>, grid, block, 0, s, x, w, y, M, H, eps, nseg2);
-    else if (cpl <= 8) hipLaunchKernelGGL(rmsnorm_regs_kernel<8>, grid, block, 0, s, x, w, y, M, H, eps, nseg2);
-    else if (cpl <= 10) hipLaunchKernelGGL(rmsnorm_regs_kernel<10>, grid, block, 0, s, x, w, y, M, H, eps, nseg2);
-    else if (cpl <= 16) hipLaunchKernelGGL(rmsnorm_regs_kernel<16>, grid, block, 0, s, x, w, y, M, H, eps, nseg2);
-    else hipLaunchKernelGGL(rmsnorm_kernel, grid, block, 0, s, x, w, y, M, H, eps, nseg2);
-    return hipGetLastError();
+hipError_t launch_combine_residual_rmsnorm(const float *partials, int P, const uint16_t *res, const uint16_t *w,
+                                           uint16_t *hidden, uint16_t *normed, int M, int H, float eps, int dtype, hipStream_t s) {
+    return dtype == TBIK_F16 ? tail_of<true>(partials, P, res, w, hidden, normed, M, H, eps, s)
+                             : tail_of<false>(partials, P, res, w, hidden, normed, M, H, eps, s);
 }
 
 }  // namespace tbik

@@ -1,7 +1,7 @@
 // Batch-invariant row reductions (App. B) in the tree order of App. C: sum, max, log-softmax.
 //
-// A row is cut into blocks of 2048 leaves (one leaf = one 16-byte chunk = 4 fp32 or 8 bf16
-// elements).  One workgroup of 256 threads reduces one block of one row: leaf number
+// A row is cut into blocks of 2048 leaves (one leaf = one 16-byte chunk = 4 fp32 or 8 bf16 or
+// fp16 elements).  One workgroup of 256 threads reduces one block of one row: leaf number
 // 256*seg + tid (seg = 0..7) of the block belongs to thread tid, so tree levels 0..5 are lane-pair
 // additions, levels 6..7 combine the four wavefronts, levels 8..10 the eight segments; the block
 // sums of a row are then combined by the same tree (blocks past the end of the row count as +0).
@@ -23,22 +23,20 @@ constexpr int RR_BLOCK_LEAVES = RR_THREADS * RR_SEGS;   // 2048
 
 enum { MODE_SUM = 0, MODE_MAX = 1, MODE_EXPSUM = 2 };
 
-template <bool BF16> struct Elem;
-template <> struct Elem<false> {
-    static constexpr int EPL = 4;   // elements per leaf
+// XT: the rows' element type, a tbik_dtype (TBIK_F32, TBIK_BF16 or TBIK_F16).
+template <int XT> struct Elem {
+    static constexpr int EPL = 8;   // elements per leaf
+    static constexpr int BYTES = 2;
+    __device__ static __forceinline__ void load(const void *row, int64_t leaf, float (&f)[8]) {
+        unpack8<XT == TBIK_F16>(reinterpret_cast<const uint4 *>(row)[leaf], f);
+    }
+};
+template <> struct Elem<TBIK_F32> {
+    static constexpr int EPL = 4;
+    static constexpr int BYTES = 4;
     __device__ static __forceinline__ void load(const void *row, int64_t leaf, float (&f)[8]) {
         const float4 v = reinterpret_cast<const float4 *>(row)[leaf];
         f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
-    }
-};
-template <> struct Elem<true> {
-    static constexpr int EPL = 8;
-    __device__ static __forceinline__ void load(const void *row, int64_t leaf, float (&f)[8]) {
-        const uint4 v = reinterpret_cast<const uint4 *>(row)[leaf];
-        f[0] = bf16_bits_to_f32(v.x & 0xffffu); f[1] = bf16_bits_to_f32(v.x >> 16);
-        f[2] = bf16_bits_to_f32(v.y & 0xffffu); f[3] = bf16_bits_to_f32(v.y >> 16);
-        f[4] = bf16_bits_to_f32(v.z & 0xffffu); f[5] = bf16_bits_to_f32(v.z >> 16);
-        f[6] = bf16_bits_to_f32(v.w & 0xffffu); f[7] = bf16_bits_to_f32(v.w >> 16);
     }
 };
 
@@ -92,18 +90,18 @@ __device__ __forceinline__ float block_max(float m, float *lds) {
 
 // Pass over one (row, block): MODE_SUM -> block tree sum; MODE_MAX -> block max;
 // MODE_EXPSUM -> block tree sum of exp(x - rowmax), rowmax taken from the block maxima in wsmax.
-template <bool BF16, int MODE>
+template <int XT, int MODE>
 __global__ __launch_bounds__(RR_THREADS) void row_block_kernel(const void *__restrict__ x, int64_t V, int nb,
                                                                const float *__restrict__ wsmax, float *__restrict__ wsout) {
     __shared__ float lds[RR_SEGS * 4];
-    constexpr int EPL = Elem<BF16>::EPL;
+    constexpr int EPL = Elem<XT>::EPL;
     // The second pass of log-softmax walks the (row, block) grid backwards: what the first pass read last is
     // what the caches still hold.  Which workgroup handles a (row, block) never affects its arithmetic.
     const int b = (MODE == MODE_EXPSUM) ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
     const int row = (MODE == MODE_EXPSUM) ? (int)(gridDim.y - 1 - blockIdx.y) : (int)blockIdx.y;
     const int lane = threadIdx.x & 63;
     const int64_t nleaves = V / EPL;
-    const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * (BF16 ? 2 : 4);
+    const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * Elem<XT>::BYTES;
 
     float rowmax = 0.0f;
     if (MODE == MODE_EXPSUM) rowmax = wave_max_of_array(wsmax + (int64_t)row * nb, nb, lane);
@@ -116,7 +114,7 @@ __global__ __launch_bounds__(RR_THREADS) void row_block_kernel(const void *__res
         float acc = 0.0f;
         if (leaf < nleaves) {
             float f[8];
-            Elem<BF16>::load(rowp, leaf, f);
+            Elem<XT>::load(rowp, leaf, f);
 #pragma unroll
             for (int e = 0; e < EPL; ++e) {
                 if (MODE == MODE_SUM) acc = acc + f[e];
@@ -142,15 +140,15 @@ __global__ __launch_bounds__(64) void row_finish_kernel(const float *__restrict_
 }
 
 // out[row, i] = (x[row, i] - rowmax) - log(S), S = tree over the row's block sums.
-template <bool BF16>
+template <int XT>
 __global__ __launch_bounds__(RR_THREADS) void logsoftmax_write_kernel(const void *__restrict__ x, int64_t V, int nb, int nb2,
                                                                      const float *__restrict__ wsmax,
                                                                      const float *__restrict__ wssum, float *__restrict__ out) {
-    constexpr int EPL = Elem<BF16>::EPL;
+    constexpr int EPL = Elem<XT>::EPL;
     const int b = blockIdx.x, row = blockIdx.y;
     const int lane = threadIdx.x & 63;
     const int64_t nleaves = V / EPL;
-    const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * (BF16 ? 2 : 4);
+    const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * Elem<XT>::BYTES;
     float *orow = out + (int64_t)row * V;
     const float rowmax = wave_max_of_array(wsmax + (int64_t)row * nb, nb, lane);
     const float S = wave_tree_of_array(wssum + (int64_t)row * nb, nb, nb2, lane);
@@ -160,7 +158,7 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_write_kernel(const void
         const int64_t leaf = (int64_t)b * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
         if (leaf < nleaves) {
             float f[8];
-            Elem<BF16>::load(rowp, leaf, f);
+            Elem<XT>::load(rowp, leaf, f);
             float o[8];
 #pragma unroll
             for (int e = 0; e < EPL; ++e) o[e] = (f[e] - rowmax) - lg;
@@ -174,14 +172,14 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_write_kernel(const void
 // Log-softmax of rows that fit one block: the row stays in registers between the three steps, so it is read once.
 // Same leaves, same block tree and the same elementwise arithmetic as the three-kernel path (whose trees over a
 // single block value add only +0), hence the same bits.
-template <bool BF16>
+template <int XT>
 __global__ __launch_bounds__(RR_THREADS) void logsoftmax_one_block_kernel(const void *__restrict__ x, int64_t V,
                                                                          float *__restrict__ out) {
     __shared__ float lds[RR_SEGS * 4];
-    constexpr int EPL = Elem<BF16>::EPL;
+    constexpr int EPL = Elem<XT>::EPL;
     const int row = blockIdx.x;
     const int64_t nleaves = V / EPL;
-    const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * (BF16 ? 2 : 4);
+    const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * Elem<XT>::BYTES;
     float *orow = out + (int64_t)row * V;
 
     float f[RR_SEGS][8];
@@ -190,7 +188,7 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_one_block_kernel(const 
     for (int seg = 0; seg < RR_SEGS; ++seg) {
         const int64_t leaf = seg * RR_THREADS + threadIdx.x;
         if (leaf < nleaves) {
-            Elem<BF16>::load(rowp, leaf, f[seg]);
+            Elem<XT>::load(rowp, leaf, f[seg]);
 #pragma unroll
             for (int e = 0; e < EPL; ++e) mx = fmaxf(mx, f[seg][e]);
         }
@@ -284,17 +282,17 @@ __device__ __forceinline__ float wave_tree_of_published(const float *p, int n, i
     return tot;
 }
 
-template <bool BF16>
+template <int XT>
 __global__ __launch_bounds__(RR_THREADS) void logsoftmax_coop_kernel(const void *__restrict__ x, int64_t V, int nb, int nb2,
                                                                     float *wsmax, float *wssum, unsigned *sync_words,
                                                                     int wait_limit, float *__restrict__ out) {
     __shared__ float lds[RR_SEGS * 4];
     __shared__ unsigned lds_flag;
-    constexpr int EPL = Elem<BF16>::EPL;
+    constexpr int EPL = Elem<XT>::EPL;
     const int row = (int)(blockIdx.x / (unsigned)nb), b = (int)(blockIdx.x % (unsigned)nb);
     const int lane = threadIdx.x & 63;
     const int64_t nleaves = V / EPL;
-    const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * (BF16 ? 2 : 4);
+    const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * Elem<XT>::BYTES;
     float *orow = out + (int64_t)row * V;
     unsigned *counters = sync_words + (int64_t)row * RR_SYNC_WORDS, *rowflag = counters + 32;
 
@@ -304,7 +302,7 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_coop_kernel(const void 
     for (int seg = 0; seg < RR_SEGS; ++seg) {
         const int64_t leaf = (int64_t)b * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
         if (leaf < nleaves) {
-            Elem<BF16>::load(rowp, leaf, f[seg]);
+            Elem<XT>::load(rowp, leaf, f[seg]);
 #pragma unroll
             for (int e = 0; e < EPL; ++e) mx = fmaxf(mx, f[seg][e]);
         }
@@ -356,7 +354,7 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_coop_kernel(const void 
 
 // Recomputes the rows that logsoftmax_coop_kernel marked (normally none): one workgroup walks all blocks of its row
 // three times.  Same leaves, block trees and tree over blocks, hence the same bits.
-template <bool BF16>
+template <int XT>
 __global__ __launch_bounds__(RR_THREADS) void logsoftmax_redo_kernel(const void *__restrict__ x, int64_t V, int nb, int nb2,
                                                                     const unsigned *__restrict__ sync_words,
                                                                     float *__restrict__ out) {
@@ -364,10 +362,10 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_redo_kernel(const void 
     __shared__ float per_block[RR_MAX_COOP_BLOCKS];
     const int row = blockIdx.x;
     if (sync_words[(int64_t)row * RR_SYNC_WORDS + 32] == 0u) return;   // uniform over the workgroup
-    constexpr int EPL = Elem<BF16>::EPL;
+    constexpr int EPL = Elem<XT>::EPL;
     const int lane = threadIdx.x & 63;
     const int64_t nleaves = V / EPL;
-    const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * (BF16 ? 2 : 4);
+    const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * Elem<XT>::BYTES;
     float *orow = out + (int64_t)row * V;
 
     for (int b = 0; b < nb; ++b) {
@@ -377,7 +375,7 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_redo_kernel(const void 
             const int64_t leaf = (int64_t)b * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
             if (leaf < nleaves) {
                 float f[8];
-                Elem<BF16>::load(rowp, leaf, f);
+                Elem<XT>::load(rowp, leaf, f);
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) mx = fmaxf(mx, f[e]);
             }
@@ -396,7 +394,7 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_redo_kernel(const void 
             float acc = 0.0f;
             if (leaf < nleaves) {
                 float f[8];
-                Elem<BF16>::load(rowp, leaf, f);
+                Elem<XT>::load(rowp, leaf, f);
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) acc = acc + expf(f[e] - rowmax);
             }
@@ -414,7 +412,7 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_redo_kernel(const void 
             const int64_t leaf = (int64_t)b * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
             if (leaf < nleaves) {
                 float f[8], o[8];
-                Elem<BF16>::load(rowp, leaf, f);
+                Elem<XT>::load(rowp, leaf, f);
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) o[e] = (f[e] - rowmax) - lg;
                 float4 *dst = reinterpret_cast<float4 *>(orow + leaf * EPL);
@@ -434,7 +432,7 @@ static std::atomic<int> g_wait_limit{1 << 14};   // polls per wait: tens of mill
 int set_row_wait_limit(int limit) { return g_wait_limit.exchange(limit < 0 ? 0 : limit); }
 
 static int blocks_of(int64_t V, int x_dtype) {
-    const int epl = (x_dtype == TBIK_BF16) ? 8 : 4;
+    const int epl = (x_dtype == TBIK_F32) ? 4 : 8;
     const int64_t nleaves = V / epl;
     return (int)((nleaves + RR_BLOCK_LEAVES - 1) / RR_BLOCK_LEAVES);
 }
@@ -446,9 +444,9 @@ size_t row_reduce_workspace(int M, int64_t V, int x_dtype, int op) {
     return (op == TBIK_LOGSOFTMAX) ? 2 * per + (size_t)M * RR_SYNC_WORDS * sizeof(unsigned) : per;
 }
 
-template <bool BF16>
+template <int XT>
 static hipError_t run(const void *x, void *out, int op, int M, int64_t V, void *ws, hipStream_t s) {
-    const int nb = blocks_of(V, BF16 ? TBIK_BF16 : TBIK_F32);
+    const int nb = blocks_of(V, XT);
     int nb2 = 1;
     while (nb2 < nb) nb2 *= 2;
     float *ws0 = reinterpret_cast<float *>(ws);
@@ -458,29 +456,29 @@ static hipError_t run(const void *x, void *out, int op, int M, int64_t V, void *
     const int64_t group = 65535;
     for (int64_t m0 = 0; m0 < M; m0 += group) {
         const int mc = (int)((M - m0) < group ? (M - m0) : group);
-        const char *xp = reinterpret_cast<const char *>(x) + m0 * V * (BF16 ? 2 : 4);
+        const char *xp = reinterpret_cast<const char *>(x) + m0 * V * Elem<XT>::BYTES;
         float *w0 = ws0 + (size_t)m0 * nb, *w1 = ws1 + (size_t)m0 * nb;
         dim3 grid(nb, mc), block(RR_THREADS);
         if (op == TBIK_SUM) {
-            hipLaunchKernelGGL((row_block_kernel<BF16, MODE_SUM>), grid, block, 0, s, xp, V, nb, (const float *)nullptr, w0);
+            hipLaunchKernelGGL((row_block_kernel<XT, MODE_SUM>), grid, block, 0, s, xp, V, nb, (const float *)nullptr, w0);
             hipLaunchKernelGGL((row_finish_kernel<MODE_SUM>), dim3(mc), dim3(64), 0, s, w0, nb, nb2, o + m0);
         } else if (op == TBIK_MAX) {
-            hipLaunchKernelGGL((row_block_kernel<BF16, MODE_MAX>), grid, block, 0, s, xp, V, nb, (const float *)nullptr, w0);
+            hipLaunchKernelGGL((row_block_kernel<XT, MODE_MAX>), grid, block, 0, s, xp, V, nb, (const float *)nullptr, w0);
             hipLaunchKernelGGL((row_finish_kernel<MODE_MAX>), dim3(mc), dim3(64), 0, s, w0, nb, nb2, o + m0);
         } else if (nb == 1) {
-            hipLaunchKernelGGL((logsoftmax_one_block_kernel<BF16>), dim3(mc), block, 0, s, xp, V, o + m0 * V);
+            hipLaunchKernelGGL((logsoftmax_one_block_kernel<XT>), dim3(mc), block, 0, s, xp, V, o + m0 * V);
         } else if (nb <= RR_MAX_COOP_BLOCKS && (int64_t)mc * nb <= 0x7fffffff) {
             unsigned *words = reinterpret_cast<unsigned *>(ws1 + (size_t)M * nb) + (size_t)m0 * RR_SYNC_WORDS;
             const int64_t nwords = (int64_t)mc * RR_SYNC_WORDS;
             hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((nwords + 255) / 256)), dim3(256), 0, s, words, nwords);
-            hipLaunchKernelGGL((logsoftmax_coop_kernel<BF16>), dim3((unsigned)((int64_t)mc * nb)), block, 0, s, xp, V, nb, nb2,
+            hipLaunchKernelGGL((logsoftmax_coop_kernel<XT>), dim3((unsigned)((int64_t)mc * nb)), block, 0, s, xp, V, nb, nb2,
                                w0, w1, words, g_wait_limit.load(), o + m0 * V);
-            hipLaunchKernelGGL((logsoftmax_redo_kernel<BF16>), dim3(mc), block, 0, s, xp, V, nb, nb2,
+            hipLaunchKernelGGL((logsoftmax_redo_kernel<XT>), dim3(mc), block, 0, s, xp, V, nb, nb2,
                                (const unsigned *)words, o + m0 * V);
         } else {
-            hipLaunchKernelGGL((row_block_kernel<BF16, MODE_MAX>), grid, block, 0, s, xp, V, nb, (const float *)nullptr, w0);
-            hipLaunchKernelGGL((row_block_kernel<BF16, MODE_EXPSUM>), grid, block, 0, s, xp, V, nb, (const float *)w0, w1);
-            hipLaunchKernelGGL((logsoftmax_write_kernel<BF16>), grid, block, 0, s, xp, V, nb, nb2, (const float *)w0,
+            hipLaunchKernelGGL((row_block_kernel<XT, MODE_MAX>), grid, block, 0, s, xp, V, nb, (const float *)nullptr, w0);
+            hipLaunchKernelGGL((row_block_kernel<XT, MODE_EXPSUM>), grid, block, 0, s, xp, V, nb, (const float *)w0, w1);
+            hipLaunchKernelGGL((logsoftmax_write_kernel<XT>), grid, block, 0, s, xp, V, nb, nb2, (const float *)w0,
                                (const float *)w1, o + m0 * V);
         }
         hipError_t e = hipGetLastError();
@@ -491,7 +489,9 @@ static hipError_t run(const void *x, void *out, int op, int M, int64_t V, void *
 
 hipError_t launch_row_reduce(const void *x, int x_dtype, void *out, int op, int M, int64_t V, void *ws, hipStream_t s) {
     if (M <= 0) return hipSuccess;
-    return (x_dtype == TBIK_BF16) ? run<true>(x, out, op, M, V, ws, s) : run<false>(x, out, op, M, V, ws, s);
+    if (x_dtype == TBIK_BF16) return run<TBIK_BF16>(x, out, op, M, V, ws, s);
+    if (x_dtype == TBIK_F16) return run<TBIK_F16>(x, out, op, M, V, ws, s);
+    return run<TBIK_F32>(x, out, op, M, V, ws, s);
 }
 
 }  // namespace tbik

@@ -216,14 +216,22 @@ int tbik_tree_combine(const float *partials, int P, void *Y, int64_t ldy, tbik_d
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }
 
-int tbik_rmsnorm(const void *x, const void *weight, void *y, int M, int H, float eps, void *hip_stream) {
+static int rmsnorm(int dtype, const void *x, const void *weight, void *y, int M, int H, float eps, void *hip_stream) {
     if (M < 0 || H <= 0 || H % 8 != 0 || H > 65536) return TBIK_ERR_SHAPE;
     if (M == 0) return TBIK_OK;
     if (!x || !weight || !y) return TBIK_ERR_NULL;
     if (!aligned(x, 16) || !aligned(weight, 16) || !aligned(y, 16)) return TBIK_ERR_ALIGN;
-    hipError_t e = launch_rmsnorm((const uint16_t *)x, (const uint16_t *)weight, (uint16_t *)y, M, H, eps,
+    hipError_t e = launch_rmsnorm((const uint16_t *)x, (const uint16_t *)weight, (uint16_t *)y, M, H, eps, dtype,
                                   (hipStream_t)hip_stream);
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
+int tbik_rmsnorm(const void *x, const void *weight, void *y, int M, int H, float eps, void *hip_stream) {
+    return rmsnorm(TBIK_BF16, x, weight, y, M, H, eps, hip_stream);
+}
+
+int tbik_rmsnorm_f16(const void *x, const void *weight, void *y, int M, int H, float eps, void *hip_stream) {
+    return rmsnorm(TBIK_F16, x, weight, y, M, H, eps, hip_stream);
 }
 
 int tbik_attention(const void *Q, const void *K, const void *V, void *O,
@@ -256,12 +264,12 @@ int tbik_set_attention_variant(int variant) { return set_attention_variant(varia
 
 size_t tbik_row_reduce_workspace_bytes(int M, int64_t V, tbik_rowop op) {
     if (op != TBIK_SUM && op != TBIK_MAX && op != TBIK_LOGSOFTMAX) return 0;
-    // sized for the finer of the two input types (fp32 rows have twice the leaves of bf16 rows)
+    // sized for the finer of the two input types (fp32 rows have twice the leaves of 16-bit rows)
     return row_reduce_workspace(M, V, TBIK_F32, (int)op);
 }
 
-int tbik_combine_residual_rmsnorm(const float *partials, int P, const void *residual, const void *weight, float eps,
-                                  void *hidden, void *normed, int M, int H, void *hip_stream) {
+static int combine_residual_rmsnorm(int dtype, const float *partials, int P, const void *residual, const void *weight,
+                                    float eps, void *hidden, void *normed, int M, int H, void *hip_stream) {
     if (M < 0 || H <= 0 || H % 8 != 0 || H > 65536) return TBIK_ERR_SHAPE;
     if (P < 1 || !is_pow2(P) || P > TBIK_MAX_SHARDS) return TBIK_ERR_SHARDS;
     if (P > 16) return TBIK_ERR_UNSUPPORTED;
@@ -271,15 +279,26 @@ int tbik_combine_residual_rmsnorm(const float *partials, int P, const void *resi
         return TBIK_ERR_ALIGN;
     if (normed == hidden || normed == residual) return TBIK_ERR_SHAPE;      // only hidden may share residual's buffer
     hipError_t e = launch_combine_residual_rmsnorm(partials, P, (const uint16_t *)residual, (const uint16_t *)weight,
-                                                   (uint16_t *)hidden, (uint16_t *)normed, M, H, eps, (hipStream_t)hip_stream);
+                                                   (uint16_t *)hidden, (uint16_t *)normed, M, H, eps, dtype,
+                                                   (hipStream_t)hip_stream);
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
+int tbik_combine_residual_rmsnorm(const float *partials, int P, const void *residual, const void *weight, float eps,
+                                  void *hidden, void *normed, int M, int H, void *hip_stream) {
+    return combine_residual_rmsnorm(TBIK_BF16, partials, P, residual, weight, eps, hidden, normed, M, H, hip_stream);
+}
+
+int tbik_combine_residual_rmsnorm_f16(const float *partials, int P, const void *residual, const void *weight, float eps,
+                                      void *hidden, void *normed, int M, int H, void *hip_stream) {
+    return combine_residual_rmsnorm(TBIK_F16, partials, P, residual, weight, eps, hidden, normed, M, H, hip_stream);
 }
 
 int tbik_row_reduce(const void *x, tbik_dtype x_dtype, void *out, tbik_rowop op, int M, int64_t V,
                     void *workspace, size_t workspace_bytes, void *hip_stream) {
-    if (x_dtype != TBIK_F32 && x_dtype != TBIK_BF16) return TBIK_ERR_DTYPE;
+    if (x_dtype != TBIK_F32 && x_dtype != TBIK_BF16 && x_dtype != TBIK_F16) return TBIK_ERR_DTYPE;
     if (op != TBIK_SUM && op != TBIK_MAX && op != TBIK_LOGSOFTMAX) return TBIK_ERR_DTYPE;
-    const int epl = (x_dtype == TBIK_BF16) ? 8 : 4;
+    const int epl = (x_dtype == TBIK_F32) ? 4 : 8;
     if (M < 0 || V <= 0 || V % epl != 0) return TBIK_ERR_SHAPE;
     if (M == 0) return TBIK_OK;
     if (!x || !out) return TBIK_ERR_NULL;

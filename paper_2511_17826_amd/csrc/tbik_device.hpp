@@ -33,6 +33,23 @@ __device__ __forceinline__ uint32_t pack_16x2(float lo, float hi) { return F16 ?
 template <bool F16>
 __device__ __forceinline__ uint32_t f32_to_16_bits(float f) { return pack_16x2<F16>(f, 0.0f) & 0xffffu; }
 
+// Eight 16-bit values (one 16-byte chunk) of either format -> fp32, exact.
+template <bool F16>
+__device__ __forceinline__ void unpack8(const uint4 &v, float (&f)[8]) {
+    if constexpr (F16) {
+        typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+        typedef float f8 __attribute__((ext_vector_type(8)));
+        const f8 r = __builtin_convertvector(__builtin_bit_cast(h8, v), f8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = r[e];
+    } else {
+        f[0] = bf16_bits_to_f32(v.x & 0xffffu); f[1] = bf16_bits_to_f32(v.x >> 16);
+        f[2] = bf16_bits_to_f32(v.y & 0xffffu); f[3] = bf16_bits_to_f32(v.y >> 16);
+        f[4] = bf16_bits_to_f32(v.z & 0xffffu); f[5] = bf16_bits_to_f32(v.z >> 16);
+        f[6] = bf16_bits_to_f32(v.w & 0xffffu); f[7] = bf16_bits_to_f32(v.w >> 16);
+    }
+}
+
 // One MFMA of the GEMM kernels: D = A(32x16) * B(16x32) + C with 16-bit operands of either format held as
 // eight 16-bit patterns per lane.  Both opcodes share the operand layout.
 typedef _Float16 f16x8 __attribute__((__vector_size__(8 * sizeof(_Float16))));

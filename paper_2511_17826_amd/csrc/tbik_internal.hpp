@@ -38,9 +38,10 @@ bool gemm_tiled_supports(const GemmArgs &a, int variant);
 hipError_t launch_tree_combine(const float *partials, int P, void *Y, int64_t ldy, int y_dtype, int M, int N,
                                hipStream_t s);
 
-hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int M, int H, float eps, hipStream_t s);
+// dtype: TBIK_BF16 or TBIK_F16, the format of every 16-bit tensor of the call.
+hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int M, int H, float eps, int dtype, hipStream_t s);
 hipError_t launch_combine_residual_rmsnorm(const float *partials, int P, const uint16_t *res, const uint16_t *w,
-                                           uint16_t *hidden, uint16_t *normed, int M, int H, float eps, hipStream_t s);
+                                           uint16_t *hidden, uint16_t *normed, int M, int H, float eps, int dtype, hipStream_t s);
 
 // Resolved description of one attention call; validated by the C ABI layer.
 struct AttnArgs {

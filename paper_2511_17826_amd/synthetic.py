@@ -185,11 +185,11 @@ def attention_inputs(seed: int, q_lens, k_lens, Hq: int = 32, Hkv: int = 8, D: i
 # Reduction workloads
 # ----------------------------------------------------------------------------
 
-def rmsnorm_inputs(M: int, H: int, seed: int = 3):
-    """x [M,H] ~ N(0,1) bf16, weight [H] ~ N(1,0.1) bf16; drawn at 8192 rows, first M returned."""
+def rmsnorm_inputs(M: int, H: int, seed: int = 3, fmt: str = "bf16"):
+    """x [M,H] ~ N(0,1), weight [H] ~ N(1,0.1), both stored in `fmt`; drawn at 8192 rows, first M returned."""
     rng = _rng(seed + 1000 * H)
-    w = normal_bf16(rng, (H,), 0.1, mean=1.0)
-    x = normal_bf16(rng, (8192, H), 1.0)[:M]
+    w = normal_bf16(rng, (H,), 0.1, mean=1.0, fmt=fmt)
+    x = normal_bf16(rng, (8192, H), 1.0, fmt=fmt)[:M]
     return np.ascontiguousarray(x), w
 
 

@@ -90,7 +90,19 @@ def test_fp16_entry_points_validate_like_the_bf16_ones(L):
     assert rf(GOOD, 512, GOOD, 256, GOOD, GOOD, 256, 1, 4, 256, 512, 64, 1, 1, None) == 4
     assert rf(GOOD, 512, GOOD, 256, GOOD, GOOD, 256, 2, 4, 256, 512, 64, 1, 2, None) == 3      # Y only with P == 1
     assert L.tbik_tree_combine(GOOD, 2, GOOD, 256, 2, 0, 256, None) == 0                       # fp16 output is offered
-    assert L.tbik_row_reduce(GOOD, 2, GOOD, 0, 4, 1024, GOOD, 1 << 20, None) == 4              # fp16 rows are not
+    assert L.tbik_row_reduce(GOOD, 2, GOOD, 0, 0, 1024, GOOD, 1 << 20, None) == 0              # and so are fp16 rows
+    assert L.tbik_row_reduce(GOOD, 2, GOOD, 0, 4, 1028, GOOD, 1 << 20, None) == 2              # in leaves of 8
+    for rn in (L.tbik_rmsnorm_f16,):
+        assert rn(GOOD, GOOD, GOOD, 0, 4096, 1e-6, None) == 0
+        assert rn(None, GOOD, GOOD, 4, 4096, 1e-6, None) == 1
+        assert rn(GOOD, GOOD, GOOD, 4, 4100, 1e-6, None) == 2
+        assert rn(GOOD + 8, GOOD, GOOD, 4, 4096, 1e-6, None) == 5
+    for tail in (L.tbik_combine_residual_rmsnorm, L.tbik_combine_residual_rmsnorm_f16):
+        assert tail(GOOD, 2, GOOD, GOOD, 1e-6, GOOD, GOOD + 65536, 0, 4096, None) == 0
+        assert tail(GOOD, 3, GOOD, GOOD, 1e-6, GOOD, GOOD + 65536, 4, 4096, None) == 3
+        assert tail(GOOD, 32, GOOD, GOOD, 1e-6, GOOD, GOOD + 65536, 4, 4096, None) == 7
+        assert tail(GOOD, 2, GOOD, GOOD, 1e-6, GOOD, GOOD, 4, 4096, None) == 2                 # normed may not alias hidden
+        assert tail(GOOD, 2, None, GOOD, 1e-6, GOOD, GOOD + 65536, 4, 4096, None) == 1
 
 
 def test_attention_argument_validation(L):

@@ -163,3 +163,78 @@ def test_one_superleaf_is_the_sequential_sum():
             for k in range(K):
                 acc = np.float32(acc + np.float32(xf[m, k] * wf[k, n]))
             assert u32(acc) == u32(y32[m, n])
+
+
+# ----------------------------------------------------------------------------- RMSNorm and the fused tail on fp16 rows
+
+def _h(v):
+    return np.asarray(v, dtype=np.float16).view(np.uint16)
+
+
+def test_rmsnorm_fp16_closed_forms():
+    """x = 1, w = 1: ss = H exactly, y = fp16(1/sqrt(1 + eps)).  x = 4, eps = 0: (4 * 0.25) * w = w."""
+    for H in (4096, 5120, 24):
+        x, w = _h(np.ones((3, H))), _h(np.ones(H))
+        y = orc.rmsnorm(x, w, 1e-6, fmt="fp16")
+        r = np.float32(1.0) / np.sqrt(np.float32(1.0) + np.float32(1e-6), dtype=np.float32)
+        assert np.all(y == _h(r))
+        assert float(orc.sumsq16(x[0], fmt="fp16")) == float(H)
+    H = 1024
+    w = _h(np.linspace(0.5, 1.5, H))
+    y = orc.rmsnorm(_h(np.full((2, H), 4.0)), w, 0.0, fmt="fp16")
+    assert np.array_equal(y[0], w) and np.array_equal(y[1], w)
+
+
+def test_rmsnorm_fp16_overflow_rounds_to_infinity_and_subnormals_count():
+    """One element of 2 in a row of 64, weight 65504: y = (2 * sqrt(64)/2) * 65504 = 8 * 65504 -> +inf in fp16.
+    A row of the smallest subnormal: squares are 2^-48 (exact in fp32), so the row normalises to 1."""
+    H = 64
+    x = np.zeros((1, H), dtype=np.float16)
+    x[0, 5] = 2.0
+    y = orc.rmsnorm(x.view(np.uint16), _h(np.full(H, 65504.0)), 0.0, fmt="fp16")
+    assert y[0, 5] == 0x7C00 and np.all(np.delete(y[0], 5) == 0)
+    tiny = np.full((1, H), 0x0001, dtype=np.uint16)
+    assert float(orc.sumsq16(tiny[0], fmt="fp16")) == H * 2.0 ** -48
+    y = orc.rmsnorm(tiny, _h(np.ones(H)), 0.0, fmt="fp16")
+    assert np.all(y == 0x3C00)
+
+
+@pytest.mark.parametrize("H", [4096, 5120, 100])
+def test_rmsnorm_fp16_within_one_ulp_of_fp64(H):
+    x, w = syn.rmsnorm_inputs(8, H, fmt="fp16")
+    got = orc.rmsnorm(x, w, 1e-6, fmt="fp16").view(np.float16).astype(np.float64)
+    X, Wt = x.view(np.float16).astype(np.float64), w.view(np.float16).astype(np.float64)
+    ref = X / np.sqrt((X * X).mean(axis=1, keepdims=True) + 1e-6) * Wt
+    ulp = np.maximum(np.abs(ref) * 2.0 ** -10, 2.0 ** -24)
+    assert np.all(np.abs(got - ref) <= ulp)
+    # the same bit patterns read as bf16 are other numbers and give other outputs
+    assert not np.array_equal(orc.rmsnorm(x, w, 1e-6, fmt="bf16"), orc.rmsnorm(x, w, 1e-6, fmt="fp16"))
+
+
+def test_fused_tail_fp16_hand_value_has_two_roundings():
+    """T = 1 + 2^-11 + 2^-15 rounds to 1 + 2^-10 in fp16 (above the tie); adding R = 2^-11 gives a tie that goes to
+    the even neighbour 1 + 2^-9.  One rounding of the whole sum would have given 1 + 2^-10.  The row of eight equal
+    values then normalises to 1 (every fp32 sum of the squares is exact)."""
+    H = 8
+    parts = np.zeros((2, 1, H), dtype=np.float32)
+    parts[0, 0, :] = 1.0
+    parts[1, 0, :] = 2.0 ** -11 + 2.0 ** -15
+    res = _h(np.full((1, H), 2.0 ** -11))
+    hid, out = orc.combine_residual_rmsnorm(parts, res, _h(np.ones(H)), 0.0, fmt="fp16")
+    assert np.all(hid == 0x3C02)
+    assert np.all(out == 0x3C00)
+    assert _h(np.float32(1.0 + 2.0 ** -11 + 2.0 ** -15 + 2.0 ** -11)) == 0x3C01
+
+
+def test_fused_tail_fp16_is_the_three_steps():
+    rng = np.random.Generator(np.random.PCG64(8))
+    P, M, H = 4, 6, 200
+    parts = rng.standard_normal((P, M, H), dtype=np.float32) * np.float32(0.5)
+    res = syn.normal_bf16(rng, (M, H), 1.0, fmt="fp16")
+    w = syn.normal_bf16(rng, (H,), 0.1, mean=1.0, fmt="fp16")
+    hid, out = orc.combine_residual_rmsnorm(parts, res, w, 1e-6, fmt="fp16")
+    y32, y16 = orc.tree_combine(parts, fmt="fp16")
+    assert np.array_equal(y16, y32.astype(np.float16).view(np.uint16))
+    h = (y16.view(np.float16).astype(np.float32) + res.view(np.float16).astype(np.float32)).astype(np.float16)
+    assert np.array_equal(hid, h.view(np.uint16))
+    assert np.array_equal(out, orc.rmsnorm(hid, w, 1e-6, fmt="fp16"))
