@@ -350,13 +350,15 @@ def extras(tb, syn, torch, np, to_dev):
         del parts
     # fixed-tile attention at 8B-class heads (32 query heads over 8 key/value heads, head dimension 128)
     Hq, Hkv, D = 32, 8, 128
-    for B, L in ((4, 4096), (1, 16384)):
-        Q = torch.randn(B * L, Hq, D, device="cuda:0").to(torch.bfloat16)
-        K = torch.randn(B * L, Hkv, D, device="cuda:0").to(torch.bfloat16)
-        Vv = torch.randn(B * L, Hkv, D, device="cuda:0").to(torch.bfloat16)
+    for B, L, dt in ((4, 4096, torch.bfloat16), (1, 16384, torch.bfloat16), (4, 4096, torch.float16)):
+        att = tb.tbik_attention if dt == torch.bfloat16 else tb.tbik_attention_f16
+        tag = "" if dt == torch.bfloat16 else "fp16_"
+        Q = torch.randn(B * L, Hq, D, device="cuda:0").to(dt)
+        K = torch.randn(B * L, Hkv, D, device="cuda:0").to(dt)
+        Vv = torch.randn(B * L, Hkv, D, device="cuda:0").to(dt)
         cu = torch.arange(0, B + 1, dtype=torch.int32, device="cuda:0") * L
         O = torch.empty_like(Q)
-        f = lambda: tb.tbik_attention(Q, K, Vv, cu, cu, L, D ** -0.5, True, out=O)
+        f = lambda: att(Q, K, Vv, cu, cu, L, D ** -0.5, True, out=O)
         f(); f()
         t = min(time_region(f, 10, torch) for _ in range(3))
         q4, k4, v4 = (a.view(B, L, -1, D).transpose(1, 2) for a in (Q, K, Vv))
@@ -364,18 +366,20 @@ def extras(tb, syn, torch, np, to_dev):
         b(); b()
         tb_ms = min(time_region(b, 10, torch) for _ in range(3))
         flops = 4.0 * B * L * L * D * Hq / 2                     # causal: half of the score matrix
-        res["attention_prefill_%dx%d" % (B, L)] = {"ms": round(t, 4), "tflops": round(flops / (t * 1e-3) / 1e12, 1),
+        res["attention_%sprefill_%dx%d" % (tag, B, L)] = {"ms": round(t, 4), "tflops": round(flops / (t * 1e-3) / 1e12, 1),
                                                    "frac_mfma": round(flops / (t * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
                                                    "baseline_ms": round(tb_ms, 4)}
         del Q, K, Vv, O, q4, k4, v4
-    for B, L in ((64, 4096), (256, 2048)):
-        Q = torch.randn(B, Hq, D, device="cuda:0").to(torch.bfloat16)
-        K = torch.randn(B * L, Hkv, D, device="cuda:0").to(torch.bfloat16)
-        Vv = torch.randn(B * L, Hkv, D, device="cuda:0").to(torch.bfloat16)
+    for B, L, dt in ((64, 4096, torch.bfloat16), (256, 2048, torch.bfloat16), (64, 4096, torch.float16)):
+        att = tb.tbik_attention if dt == torch.bfloat16 else tb.tbik_attention_f16
+        tag = "" if dt == torch.bfloat16 else "fp16_"
+        Q = torch.randn(B, Hq, D, device="cuda:0").to(dt)
+        K = torch.randn(B * L, Hkv, D, device="cuda:0").to(dt)
+        Vv = torch.randn(B * L, Hkv, D, device="cuda:0").to(dt)
         cuq = torch.arange(0, B + 1, dtype=torch.int32, device="cuda:0")
         cuk = cuq * L
         O = torch.empty_like(Q)
-        f = lambda: tb.tbik_attention(Q, K, Vv, cuq, cuk, 1, D ** -0.5, True, out=O)
+        f = lambda: att(Q, K, Vv, cuq, cuk, 1, D ** -0.5, True, out=O)
         f(); f()
         t = min(time_region(f, 10, torch) for _ in range(3))
         q4 = Q.view(B, 1, Hq, D).transpose(1, 2)
@@ -384,7 +388,7 @@ def extras(tb, syn, torch, np, to_dev):
         b(); b()
         tb_ms = min(time_region(b, 10, torch) for _ in range(3))
         byts = 2.0 * B * L * Hkv * D * 2                         # K and V read once
-        res["attention_decode_%dx%d" % (B, L)] = {"ms": round(t, 4), "GBps_kv": round(byts / (t * 1e-3) / 1e9, 1),
+        res["attention_%sdecode_%dx%d" % (tag, B, L)] = {"ms": round(t, 4), "GBps_kv": round(byts / (t * 1e-3) / 1e9, 1),
                                                   "frac_hbm": round(byts / (t * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                                                   "baseline_ms": round(tb_ms, 4)}
         del Q, K, Vv, O, q4, k4, v4

@@ -183,6 +183,18 @@ int tbik_attention(const void *Q, const void *K, const void *V, void *O,
                    int64_t q_stride, int64_t k_stride, int64_t v_stride, int64_t o_stride,
                    float scale, int causal, void *hip_stream);
 
+/*
+ * tbik_attention for IEEE binary16 tensors: Q, K, V and O are fp16; the scores, the softmax state and the output
+ * accumulators are fp32 as above, the tile's weights are rounded to fp16 for the product with V (to nearest-even, on
+ * the subnormal grid of 2^-24 below 2^-14, so a weight below 2^-25 of the running maximum's contributes nothing),
+ * and O takes one rounding to fp16.  Same tile, order, arguments, limits and errors.
+ */
+int tbik_attention_f16(const void *Q, const void *K, const void *V, void *O,
+                       const int32_t *cu_seqlens_q, const int32_t *cu_seqlens_k, int batch, int max_seqlen_q,
+                       int total_q, int total_k, int heads_q, int heads_kv, int head_dim,
+                       int64_t q_stride, int64_t k_stride, int64_t v_stride, int64_t o_stride,
+                       float scale, int causal, void *hip_stream);
+
 /* Scratch sizes (pure host functions; 0 if the arguments are illegal or no scratch is needed).
  * tbik_gemm_workspace_bytes covers tbik_gemm and tbik_gemm_shard_partials for any legal P. */
 size_t tbik_gemm_workspace_bytes(int M, int N, int K, int leaf, int k_first);

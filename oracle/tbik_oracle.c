@@ -498,7 +498,7 @@ int tbik_oracle_row_logsoftmax(const float *x, float *out, int M, long V, int le
  * batch, on how many queries arrive together, or on whether the call is a prefill or a decode step.
  *
  * Packed variable-length layout: sequence b owns query tokens cu_q[b]..cu_q[b+1]-1 and key tokens
- * cu_k[b]..cu_k[b+1]-1; token t, head h, channel d of Q is Q[t*q_stride + h*D + d] (bf16); K and V
+ * cu_k[b]..cu_k[b+1]-1; token t, head h, channel d of Q is Q[t*q_stride + h*D + d] (16-bit); K and V
  * likewise with Hkv heads; query head h reads key/value head h / (Hq/Hkv).  With Lq queries and Lk keys
  * the queries are the LAST Lq positions of the sequence: query i sees key j iff j < Lk and (not causal or
  * j <= i + Lk - Lq).
@@ -511,15 +511,16 @@ int tbik_oracle_row_logsoftmax(const float *x, float *out, int M, long V, int le
  *     a     = exp2(m - m')                          (0 for the first tile)
  *     p_j   = exp2(s_j - m')
  *     l     = l*a + (sum_j p_j)                     ascending j from +0, fp32 p_j
- *     o_d   = (o_d*a) + sum_j bf16(p_j) * v_jd      ascending j, added one by one to o_d*a; p rounded to bf16 (RNE)
+ *     o_d   = (o_d*a) + sum_j r16(p_j) * v_jd       ascending j, added one by one to o_d*a; p rounded (RNE) to the
+ *                                                   tensors' 16-bit format (for binary16: on its subnormal grid below 2^-14)
  *     m     = m'
- *   O_d = bf16(o_d / l), or 0 if the query sees no key.
- * O32 (optional) receives o_d / l before the rounding.
+ *   O_d = r16(o_d / l), or 0 if the query sees no key.
+ * O32 (optional) receives o_d / l before the rounding.  fmt: the format of Q, K, V and O (FMT_BF16 or FMT_F16).
  */
 int tbik_oracle_attention(const uint16_t *Q, const uint16_t *K, const uint16_t *V, uint16_t *O, float *O32,
                           const int32_t *cu_q, const int32_t *cu_k, int batch, int Hq, int Hkv, int D,
                           long q_stride, long k_stride, long v_stride, long o_stride,
-                          float scale, int causal, int kv_tile) {
+                          float scale, int causal, int kv_tile, int fmt) {
     if (batch < 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || D <= 0 || kv_tile <= 0) return -1;
     const float c = scale * 1.44269504088896340736f;
     const int group = Hq / Hkv;
@@ -545,7 +546,7 @@ int tbik_oracle_attention(const uint16_t *Q, const uint16_t *K, const uint16_t *
                         for (long j = j0; j <= j1; ++j) {
                             const uint16_t *k = K + (k0 + j) * k_stride + (long)hk * D;
                             float dot = 0.0f;
-                            for (int d = 0; d < D; ++d) dot = dot + bf16_to_f32(q[d]) * bf16_to_f32(k[d]);
+                            for (int d = 0; d < D; ++d) dot = dot + widen16(q[d], fmt) * widen16(k[d], fmt);
                             s[j - j0] = dot * c;
                             tm = s[j - j0] > tm ? s[j - j0] : tm;
                         }
@@ -556,9 +557,9 @@ int tbik_oracle_attention(const uint16_t *Q, const uint16_t *K, const uint16_t *
                         for (long j = j0; j <= j1; ++j) {
                             const float p = exp2f(s[j - j0] - m2);
                             psum = psum + p;
-                            const float pb = bf16_to_f32(f32_to_bf16(p));
+                            const float pb = widen16(round16(p, fmt), fmt);
                             const uint16_t *v = V + (k0 + j) * v_stride + (long)hk * D;
-                            for (int d = 0; d < D; ++d) o[d] = o[d] + pb * bf16_to_f32(v[d]);
+                            for (int d = 0; d < D; ++d) o[d] = o[d] + pb * widen16(v[d], fmt);
                         }
                         l = l * a + psum;
                         m = m2;
@@ -566,7 +567,7 @@ int tbik_oracle_attention(const uint16_t *Q, const uint16_t *K, const uint16_t *
                     for (int d = 0; d < D; ++d) {
                         const float r = (l > 0.0f) ? o[d] / l : 0.0f;
                         if (O32) O32[((q0 + i) * Hq + h) * (long)D + d] = r;
-                        if (O) O[(q0 + i) * o_stride + (long)h * D + d] = f32_to_bf16(r);
+                        if (O) O[(q0 + i) * o_stride + (long)h * D + d] = round16(r, fmt);
                     }
                 }
             }

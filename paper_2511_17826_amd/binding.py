@@ -52,6 +52,9 @@ SIGNATURES = {
     "tbik_attention": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
                                  C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_int64,
                                  C.c_float, C.c_int, C.c_void_p]),
+    "tbik_attention_f16": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
+                                     C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_int64,
+                                     C.c_float, C.c_int, C.c_void_p]),
     "tbik_set_gemm_variant": (C.c_int, [C.c_int]),
     "tbik_set_attention_variant": (C.c_int, [C.c_int]),
     "tbik_set_row_wait_limit": (C.c_int, [C.c_int]),
@@ -265,17 +268,13 @@ def tbik_combine_residual_rmsnorm_f16(partials: torch.Tensor, residual: torch.Te
                                      hidden, normed)
 
 
-def _token_major(t: torch.Tensor, name: str):
-    if t.dim() != 3 or t.stride(2) != 1 or t.stride(1) != t.shape[2] or not t.is_cuda or t.dtype != torch.bfloat16:
-        raise ValueError("%s must be a bf16 GPU tensor [tokens, heads, head_dim] with contiguous heads" % name)
+def _token_major(t: torch.Tensor, name: str, dtype):
+    if t.dim() != 3 or t.stride(2) != 1 or t.stride(1) != t.shape[2] or not t.is_cuda or t.dtype != dtype:
+        raise ValueError("%s must be a %s GPU tensor [tokens, heads, head_dim] with contiguous heads" % (name, dtype))
 
 
-def tbik_attention(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, cu_seqlens_q: torch.Tensor,
-                   cu_seqlens_k: torch.Tensor, max_seqlen_q: int, scale: float, causal: bool = True,
-                   out: torch.Tensor | None = None) -> torch.Tensor:
-    """Fixed-tile attention on packed sequences: Q [Tq, Hq, D], K and V [Tk, Hkv, D] (token stride free),
-    cu_seqlens_* int32 GPU tensors [batch + 1].  Returns O [Tq, Hq, D] bf16."""
-    _token_major(Q, "Q"); _token_major(K, "K"); _token_major(V, "V")
+def _attention(entry, dtype, Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, scale, causal, out):
+    _token_major(Q, "Q", dtype); _token_major(K, "K", dtype); _token_major(V, "V", dtype)
     Tq, Hq, D = Q.shape
     Tk, Hkv, _ = K.shape
     assert V.shape == K.shape and K.shape[2] == D
@@ -283,13 +282,29 @@ def tbik_attention(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, cu_seqlens
     assert cu_seqlens_q.is_cuda and cu_seqlens_k.is_cuda and cu_seqlens_q.is_contiguous() and cu_seqlens_k.is_contiguous()
     assert cu_seqlens_q.numel() == cu_seqlens_k.numel() >= 1
     if out is None:
-        out = torch.empty((Tq, Hq, D), dtype=torch.bfloat16, device=Q.device)
-    _token_major(out, "out")
-    st = lib().tbik_attention(Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(), cu_seqlens_q.data_ptr(),
-                              cu_seqlens_k.data_ptr(), cu_seqlens_q.numel() - 1, max_seqlen_q, Tq, Tk, Hq, Hkv, D,
-                              Q.stride(0), K.stride(0), V.stride(0), out.stride(0), scale, int(causal), _stream())
-    _check(st, "tbik_attention")
+        out = torch.empty((Tq, Hq, D), dtype=dtype, device=Q.device)
+    _token_major(out, "out", dtype)
+    assert out.shape == Q.shape
+    st = getattr(lib(), entry)(Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(), cu_seqlens_q.data_ptr(),
+                               cu_seqlens_k.data_ptr(), cu_seqlens_q.numel() - 1, max_seqlen_q, Tq, Tk, Hq, Hkv, D,
+                               Q.stride(0), K.stride(0), V.stride(0), out.stride(0), scale, int(causal), _stream())
+    _check(st, entry)
     return out
+
+
+def tbik_attention(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, cu_seqlens_q: torch.Tensor,
+                   cu_seqlens_k: torch.Tensor, max_seqlen_q: int, scale: float, causal: bool = True,
+                   out: torch.Tensor | None = None) -> torch.Tensor:
+    """Fixed-tile attention on packed sequences: Q [Tq, Hq, D], K and V [Tk, Hkv, D] (token stride free),
+    cu_seqlens_* int32 GPU tensors [batch + 1].  Returns O [Tq, Hq, D] bf16."""
+    return _attention("tbik_attention", torch.bfloat16, Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, scale, causal, out)
+
+
+def tbik_attention_f16(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, cu_seqlens_q: torch.Tensor,
+                       cu_seqlens_k: torch.Tensor, max_seqlen_q: int, scale: float, causal: bool = True,
+                       out: torch.Tensor | None = None) -> torch.Tensor:
+    """The same on fp16 tensors."""
+    return _attention("tbik_attention_f16", torch.float16, Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, scale, causal, out)
 
 
 def tbik_row_reduce(x: torch.Tensor, op: int, out: torch.Tensor | None = None,

@@ -12,15 +12,16 @@
 // ascending order, with the streaming-softmax recurrence per query row:
 //     s_j = (q . k_j) * c            c = scale * log2(e), fp32
 //     m'  = max(m, max_j s_j);  a = exp2(m - m');  p_j = exp2(s_j - m')
-//     l   = l a + sum_j p_j;    o = o a + sum_j bf16(p_j) v_j;    m = m'
-// and O = o / l, rounded once to bf16.  Nothing in a row's arithmetic depends on the other rows of the block, on
+//     l   = l a + sum_j p_j;    o = o a + sum_j r16(p_j) v_j;    m = m'
+// and O = o / l, rounded once to 16 bits (r16: to the tensors' format, bf16 or with F16 IEEE binary16; the MFMA
+// opcode and the two conversions are all that depends on the format).  Nothing in a row's arithmetic depends on the other rows of the block, on
 // the number of queries in the call or on the batch: a tile that is masked for a row leaves that row's (m, l, o)
 // unchanged bit for bit (a = 1, p = 0), so the number of tiles a block walks does not matter either.
 //
 // Everything is computed transposed, so that a lane owns ONE query (column lane % 32 of every MFMA result) and
 // the per-query state m, l, a lives in one register per lane:
 //     S^T (keys x queries)  = K (A operand, 16-byte LDS reads)        x Q^T (B operand, in registers for the whole block)
-//     O^T (channels x queries) = V^T (A operand, transposing LDS read) x P^T (B operand = the S^T registers, rounded to bf16)
+//     O^T (channels x queries) = V^T (A operand, transposing LDS read) x P^T (B operand = the S^T registers, rounded to 16 bits)
 // The MFMA's k-slot (g, t) of step s stands for key 32 kb + 16 h + 8 (t / 4) + 4 g + t % 4 (kb = s / 2, h = s % 2): the
 // order in which the result layout of S^T hands the keys to a lane; V^T is fetched in the same order.
 #include <atomic>
@@ -63,7 +64,7 @@ __device__ __forceinline__ void both_halves(float v, float &a, float &b) {
     b = __uint_as_float(r[1]);
 }
 
-template <bool CAUSAL>
+template <bool CAUSAL, bool F16>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attention_kernel(const AttnParams p) {
     // LDS: K tile [2][64 keys][256 B], then V tile [2][64 keys][256 B].
@@ -215,7 +216,7 @@ void attention_kernel(const AttnParams p) {
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb) {
                     const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kt + kb * 8192 + k_rd + (((2 * ks + lg) ^ (li & 15)) << 4));
-                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, bq[ks], s[kb], 0, 0, 0);
+                    s[kb] = mfma_32x32x16<F16>(kf, bq[ks], s[kb]);
                 }
             // ---- scale, mask, running maximum ----
 #pragma unroll
@@ -271,7 +272,7 @@ void attention_kernel(const AttnParams p) {
                 const int kb = st >> 1, h = st & 1;
                 union { uint32_t u[4]; bf16x8 v; } pb;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) pb.u[i] = pack_bf16x2(s[kb][8 * h + 2 * i], s[kb][8 * h + 2 * i + 1]);
+                for (int i = 0; i < 4; ++i) pb.u[i] = pack_16x2<F16>(s[kb][8 * h + 2 * i], s[kb][8 * h + 2 * i + 1]);
 #pragma unroll
                 for (int db = 0; db < ATT_D / 32; ++db) {
                     union { att_v4i16 h2[2]; bf16x8 v; } vf;
@@ -279,7 +280,7 @@ void attention_kernel(const AttnParams p) {
                     for (int hh = 0; hh < 2; ++hh)
                         vf.h2[hh] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                             (__attribute__((address_space(3))) att_v4i16 *)(vt + (32 * kb + 16 * h + 8 * hh) * 256 + v_rd[db]));
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pb.v, o[db], 0, 0, 0);
+                    o[db] = mfma_32x32x16<F16>(vf.v, pb.v, o[db]);
                 }
             }
         }
@@ -293,7 +294,7 @@ void attention_kernel(const AttnParams p) {
         if (t + 1 < n_tiles) tile(std::integral_constant<int, 1>{}, t + 1);
     }
 
-    // ---- O = o / l, one rounding to bf16; lane (query li, half lg) holds channels 32 db + 8 q + 4 lg + (0..3) ----
+    // ---- O = o / l, one rounding to the 16-bit format; lane (query li, half lg) holds channels 32 db + 8 q + 4 lg + (0..3) ----
     if (qrow < Lq) {
         uint16_t *optr = p.O + (int64_t)(q0 + qrow) * p.o_stride + (int64_t)head * ATT_D + 4 * lg;
 #pragma unroll
@@ -304,8 +305,8 @@ void attention_kernel(const AttnParams p) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) v[i] = (l > 0.0f) ? o[db][4 * q + i] / l : 0.0f;
                 att_u32x2 w;
-                w[0] = pack_bf16x2(v[0], v[1]);
-                w[1] = pack_bf16x2(v[2], v[3]);
+                w[0] = pack_16x2<F16>(v[0], v[1]);
+                w[1] = pack_16x2<F16>(v[2], v[3]);
                 *reinterpret_cast<att_u32x2 *>(optr + db * 32 + 8 * q) = w;
             }
     }
@@ -317,7 +318,7 @@ void attention_kernel(const AttnParams p) {
 // A workgroup of 8 wavefronts (two per SIMD) owns 256 row slots that share one key/value head; wavefronts 0-3 are group
 // A, 4-7 group B, so each SIMD holds one wavefront of each group.  Per key tile a wavefront has an MFMA half -- the
 // product P_{t-1} V_{t-1} of the tile before, then the scores S_t = K_t Q^T -- and a vector half -- the softmax step
-// of tile t (scale, mask, maximum, exponentials, sums, rescale of o, weights rounded to bf16).  The two groups run
+// of tile t (scale, mask, maximum, exponentials, sums, rescale of o, weights rounded to 16 bits).  The two groups run
 // these halves in opposite phase, with a workgroup barrier between half-slots:
 //     half-slot 2t      A: MFMA half t          B: vector half t - 1
 //     half-slot 2t + 1  A: vector half t        B: MFMA half t
@@ -325,7 +326,7 @@ void attention_kernel(const AttnParams p) {
 // workgroups happen to be out of phase.  K_t is read in half-slots 2t and 2t + 1, V_t in 2t + 2 and 2t + 3; tile t lives
 // in slot t % RING of a ring of (K, V) pairs that direct global->LDS loads fill RING - 2 tiles ahead.  A row's
 // arithmetic is exactly that of attention_kernel (the order of its operations is unchanged), so are its bits.
-template <bool CAUSAL, int RING>
+template <bool CAUSAL, int RING, bool F16>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attention_pingpong_kernel(const AttnParams p) {
     static_assert(RING == 3 || RING == 4, "the prologue and the load counting below are written for these depths");
@@ -488,7 +489,7 @@ void attention_pingpong_kernel(const AttnParams p) {
             for (int st = 0; st < 4; ++st) {
 #pragma unroll
                 for (int db = 0; db < ATT_D / 32; ++db)
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[st & 1][db].v, pw[st], o[db], 0, 0, 0);
+                    o[db] = mfma_32x32x16<F16>(vf[st & 1][db].v, pw[st], o[db]);
                 if (st + 2 < 4) read_v(vf[st & 1], t, st + 2);
                 if (st >= 1 && do_scores) read_k(kf[st - 1], kr, st - 1);
                 __builtin_amdgcn_sched_barrier(0);
@@ -501,7 +502,7 @@ void attention_pingpong_kernel(const AttnParams p) {
                 if (ks + 3 < ATT_D / 16) read_k(kf[(ks + 3) & 3], kr, ks + 3);
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
-                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks & 3][kb], bq[ks], ks == 0 ? zero : s[kb], 0, 0, 0);
+                    s[kb] = mfma_32x32x16<F16>(kf[ks & 3][kb], bq[ks], ks == 0 ? zero : s[kb]);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -542,7 +543,7 @@ void attention_pingpong_kernel(const AttnParams p) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) o[db][r] = o[db][r] * alpha;
         }
-        // Weights in key order, eight at a time: summed in fp32 and rounded to bf16 as they are formed, so that only a
+        // Weights in key order, eight at a time: summed in fp32 and rounded to 16 bits as they are formed, so that only a
         // few of them are in registers at once (k-step st of the product takes elements 8 st .. 8 st + 7).
         float psum = 0.0f;
 #pragma unroll
@@ -554,7 +555,7 @@ void attention_pingpong_kernel(const AttnParams p) {
                 const float p1 = __builtin_amdgcn_exp2f(s[st >> 1][8 * (st & 1) + 2 * i + 1] - m_use);
                 psum = psum + p0;
                 psum = psum + p1;
-                pb.u[i] = pack_bf16x2(p0, p1);
+                pb.u[i] = pack_16x2<F16>(p0, p1);
             }
             pw[st] = pb.v;
             __builtin_amdgcn_sched_barrier(0);
@@ -615,8 +616,8 @@ void attention_pingpong_kernel(const AttnParams p) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) v[i] = (l > 0.0f) ? o[db][4 * q + i] / l : 0.0f;
                 att_u32x2 w;
-                w[0] = pack_bf16x2(v[0], v[1]);
-                w[1] = pack_bf16x2(v[2], v[3]);
+                w[0] = pack_16x2<F16>(v[0], v[1]);
+                w[1] = pack_16x2<F16>(v[2], v[3]);
                 *reinterpret_cast<att_u32x2 *>(optr + db * 32 + 8 * q) = w;
             }
     }
@@ -642,6 +643,18 @@ static hipError_t launch_with_lds(Kernel kernel, std::atomic<unsigned> &done, di
     return hipGetLastError();
 }
 
+template <bool F16>
+static hipError_t launch_of(const AttnArgs &a, const AttnParams &p, dim3 grid, bool pingpong, hipStream_t s) {
+    static std::atomic<unsigned> done[4] = {{0}, {0}, {0}, {0}};     // one set per operand format
+    if (pingpong) {
+        constexpr int RING = 4;
+        if (a.causal) return launch_with_lds(attention_pingpong_kernel<true, RING, F16>, done[0], grid, dim3(512), 2 * RING * ATT_TILE_BYTES, p, s);
+        return launch_with_lds(attention_pingpong_kernel<false, RING, F16>, done[1], grid, dim3(512), 2 * RING * ATT_TILE_BYTES, p, s);
+    }
+    if (a.causal) return launch_with_lds(attention_kernel<true, F16>, done[2], grid, dim3(256), 4 * ATT_TILE_BYTES, p, s);
+    return launch_with_lds(attention_kernel<false, F16>, done[3], grid, dim3(256), 4 * ATT_TILE_BYTES, p, s);
+}
+
 hipError_t launch_attention(const AttnArgs &a, hipStream_t s) {
     if (a.batch <= 0 || a.max_seqlen_q <= 0 || a.total_q <= 0) return hipSuccess;
     AttnParams p;
@@ -663,14 +676,7 @@ hipError_t launch_attention(const AttnArgs &a, hipStream_t s) {
     const int64_t q_blocks = ((int64_t)a.max_seqlen_q + rows - 1) / rows;
     if (q_blocks > 0x7fffffff) return hipErrorInvalidValue;
     dim3 grid((unsigned)q_blocks, (unsigned)(a.heads_q / p.pack), (unsigned)a.batch);
-    static std::atomic<unsigned> done[4] = {{0}, {0}, {0}, {0}};
-    if (pingpong) {
-        constexpr int RING = 4;
-        if (a.causal) return launch_with_lds(attention_pingpong_kernel<true, RING>, done[0], grid, dim3(512), 2 * RING * ATT_TILE_BYTES, p, s);
-        return launch_with_lds(attention_pingpong_kernel<false, RING>, done[1], grid, dim3(512), 2 * RING * ATT_TILE_BYTES, p, s);
-    }
-    if (a.causal) return launch_with_lds(attention_kernel<true>, done[2], grid, dim3(256), 4 * ATT_TILE_BYTES, p, s);
-    return launch_with_lds(attention_kernel<false>, done[3], grid, dim3(256), 4 * ATT_TILE_BYTES, p, s);
+    return a.dtype == TBIK_F16 ? launch_of<true>(a, p, grid, pingpong, s) : launch_of<false>(a, p, grid, pingpong, s);
 }
 
 }  // namespace tbik

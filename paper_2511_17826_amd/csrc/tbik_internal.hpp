@@ -45,8 +45,9 @@ hipError_t launch_combine_residual_rmsnorm(const float *partials, int P, const u
 
 // Resolved description of one attention call; validated by the C ABI layer.
 struct AttnArgs {
-    const uint16_t *Q, *K, *V;    // bf16, token-major: [tokens, heads, 128]
+    const uint16_t *Q, *K, *V;    // token-major: [tokens, heads, 128]
     uint16_t *O;
+    int dtype;                    // TBIK_BF16 or TBIK_F16: the format of Q, K, V and O
     const int32_t *cu_q, *cu_k;   // device, [batch + 1]
     int batch, max_seqlen_q, total_q, total_k;
     int heads_q, heads_kv;

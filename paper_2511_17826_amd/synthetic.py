@@ -167,17 +167,18 @@ def gemm_leaf_sparse(seed: int, M: int, K: int, N: int, superleaf: int, exp_spre
 # (8B-class: 32 query heads, 8 key/value heads, head dimension 128).
 # ----------------------------------------------------------------------------
 
-def attention_inputs(seed: int, q_lens, k_lens, Hq: int = 32, Hkv: int = 8, D: int = 128, std: float = 1.0):
-    """Q [sum(q_lens), Hq, D], K and V [sum(k_lens), Hkv, D] ~ N(0, std) as bf16 bits, plus the int32 prefix sums
+def attention_inputs(seed: int, q_lens, k_lens, Hq: int = 32, Hkv: int = 8, D: int = 128, std: float = 1.0,
+                     fmt: str = "bf16"):
+    """Q [sum(q_lens), Hq, D], K and V [sum(k_lens), Hkv, D] ~ N(0, std) as 16-bit patterns of `fmt`, plus the int32 prefix sums
     cu_q, cu_k [batch + 1].  Sequence b has q_lens[b] query tokens (its last positions) and k_lens[b] keys."""
     rng = _rng(seed)
     q_lens, k_lens = np.asarray(q_lens, dtype=np.int64), np.asarray(k_lens, dtype=np.int64)
     assert q_lens.shape == k_lens.shape
     cu_q = np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32)
     cu_k = np.concatenate([[0], np.cumsum(k_lens)]).astype(np.int32)
-    Q = normal_bf16(rng, (int(cu_q[-1]), Hq, D), std)
-    K = normal_bf16(rng, (int(cu_k[-1]), Hkv, D), std)
-    V = normal_bf16(rng, (int(cu_k[-1]), Hkv, D), std)
+    Q = normal_bf16(rng, (int(cu_q[-1]), Hq, D), std, fmt=fmt)
+    K = normal_bf16(rng, (int(cu_k[-1]), Hkv, D), std, fmt=fmt)
+    V = normal_bf16(rng, (int(cu_k[-1]), Hkv, D), std, fmt=fmt)
     return dict(Q=Q, K=K, V=V, cu_q=cu_q, cu_k=cu_k, Hq=Hq, Hkv=Hkv, D=D, scale=float(D) ** -0.5)
 
 

@@ -105,13 +105,14 @@ def test_fp16_entry_points_validate_like_the_bf16_ones(L):
         assert tail(GOOD, 2, None, GOOD, 1e-6, GOOD, GOOD + 65536, 4, 4096, None) == 1
 
 
-def test_attention_argument_validation(L):
+@pytest.mark.parametrize("entry", ["tbik_attention", "tbik_attention_f16"])
+def test_attention_argument_validation(L, entry):
     def att(**kw):
         a = dict(Q=GOOD, K=GOOD, V=GOOD, O=GOOD, cq=GOOD, ck=GOOD, batch=2, mq=8, tq=16, tk=16, hq=4, hkv=2, d=128,
                  sq=512, sk=256, sv=256, so=512, scale=0.1, causal=1)
         a.update(kw)
-        return L.tbik_attention(a["Q"], a["K"], a["V"], a["O"], a["cq"], a["ck"], a["batch"], a["mq"], a["tq"], a["tk"],
-                                a["hq"], a["hkv"], a["d"], a["sq"], a["sk"], a["sv"], a["so"], a["scale"], a["causal"], None)
+        return getattr(L, entry)(a["Q"], a["K"], a["V"], a["O"], a["cq"], a["ck"], a["batch"], a["mq"], a["tq"], a["tk"],
+                                 a["hq"], a["hkv"], a["d"], a["sq"], a["sk"], a["sv"], a["so"], a["scale"], a["causal"], None)
     assert att(batch=0) == 0 and att(mq=0) == 0 and att(tq=0) == 0            # nothing to do: OK before any pointer is looked at
     assert att(batch=-1) == 2 and att(hq=5) == 2 and att(hkv=0) == 2          # heads_q must be a multiple of heads_kv
     assert att(sq=500) == 2 and att(sk=128) == 2 and att(so=1 << 24) == 2     # token stride below heads * 128, or too large

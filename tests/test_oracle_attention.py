@@ -17,10 +17,10 @@ def f32(b):
     return syn.bf16_bits_to_f32(b)
 
 
-def plain_attention_fp64(c, causal=True):
+def plain_attention_fp64(c, causal=True, fmt="bf16"):
     """softmax(q K^T * scale) V per sequence and head, fp64, written from the definition.
     Returns (O, B) with B = sum_j p_j |v_j| / sum_j p_j, the magnitude the rounding bound is stated in."""
-    Q, K, V = f32(c["Q"]).astype(np.float64), f32(c["K"]).astype(np.float64), f32(c["V"]).astype(np.float64)
+    Q, K, V = (syn.from_storage(c[n], fmt).astype(np.float64) for n in "QKV")
     Hq, Hkv = c["Hq"], c["Hkv"]
     O = np.zeros(Q.shape)
     B = np.zeros(Q.shape)

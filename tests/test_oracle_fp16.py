@@ -238,3 +238,64 @@ def test_fused_tail_fp16_is_the_three_steps():
     h = (y16.view(np.float16).astype(np.float32) + res.view(np.float16).astype(np.float32)).astype(np.float16)
     assert np.array_equal(hid, h.view(np.uint16))
     assert np.array_equal(out, orc.rmsnorm(hid, w, 1e-6, fmt="fp16"))
+
+
+# ----------------------------------------------------------------------------- attention on fp16 tensors
+
+from test_oracle_attention import plain_attention_fp64  # noqa: E402
+
+
+@pytest.mark.parametrize("causal,std", [(True, 1.0), (False, 1.0), (True, 4.0)])
+def test_attention_fp16_plain_definition_within_the_rounding_bound(causal, std):
+    """Error sources: p rounded to fp16 (2^-12 relative, or 2^-25 absolute on the subnormal grid), the output rounded
+    to fp16 (2^-12 relative).  With std 4 the scores spread over tens of binades, so most weights of a row are
+    subnormal or vanish; their absolute roundings sum to at most Lk * 2^-25 * max|v| / l <= 2^-13 here."""
+    c = syn.attention_inputs(31, [70, 1, 200, 33], [70, 150, 200, 64], Hq=4, Hkv=2, D=32, std=std, fmt="fp16")
+    O, O32 = orc.attention(c["Q"], c["K"], c["V"], c["cu_q"], c["cu_k"], c["scale"], causal, fmt="fp16")
+    want, B = plain_attention_fp64(c, causal, fmt="fp16")
+    got = O.view(np.float16).astype(np.float64)
+    assert np.all(np.abs(O32 - want) <= 2.0 ** -11 * B + 2.0 ** -13)
+    assert np.all(np.abs(got - want) <= 2.0 ** -11 * B + 2.0 ** -11 * np.abs(want) + 2.0 ** -13)
+    assert np.array_equal(O, O32.astype(np.float16).view(np.uint16))         # one RNE rounding at the end
+    if std == 1.0:
+        assert np.sqrt(np.mean((O32 - want) ** 2)) <= 2.0 ** -14 * np.sqrt(np.mean(B ** 2))
+
+
+def test_attention_fp16_weights_below_the_subnormal_grid_vanish():
+    """Two keys in one tile, the second scoring about 35 binades lower: its weight 2^-35 is kept by bf16 and is 0 in
+    fp16 (below half of 2^-24).  With v_0 = 1 and v_1 = 2^14 the fp16 result is exactly 1; bf16 operands give more."""
+    D = 8
+    Q = np.zeros((1, 1, D), dtype=np.float32)
+    Q[0, 0, 0] = 8.0
+    K = np.zeros((2, 1, D), dtype=np.float32)
+    K[1, 0, 0] = -3.0                                                # s_1 = -24 * log2(e) = -34.6
+    V = np.zeros((2, 1, D), dtype=np.float32)
+    V[0], V[1] = 1.0, 2.0 ** 14
+    for fmt, exact in (("fp16", True), ("bf16", False)):
+        st = lambda a: syn.to_storage(a, fmt)
+        O, O32 = orc.attention(st(Q), st(K), st(V), [0, 1], [0, 2], 1.0, False, fmt=fmt)
+        assert (O32[0, 0, 0] == 1.0) == exact
+        assert O32[0, 0, 0] < 1.0 + 2.0 ** -19
+    # a weight of about 2^-17.3 is kept in fp16 too, on the grid of 2^-24: 103.08 * 2^-24 -> 103 * 2^-24
+    K[1, 0, 0] = -1.5
+    _, O32 = orc.attention(syn.to_storage(Q, "fp16"), syn.to_storage(K, "fp16"), syn.to_storage(V, "fp16"),
+                           [0, 1], [0, 2], 1.0, False, fmt="fp16")
+    p = np.exp2(np.float64(np.float32(-12.0) * np.float32(1.0 * 1.4426950408889634)))
+    p16 = np.round(p * 2.0 ** 24) * 2.0 ** -24
+    assert abs(O32[0, 0, 0] - (1.0 + p16 * 2.0 ** 14) / (1.0 + p)) <= 2.0 ** -22
+    assert abs(p16 - p) * 2.0 ** 14 > 2.0 ** -16                     # an unrounded weight would miss the bound above
+
+
+def test_attention_fp16_exact_cases_and_invariance():
+    """One visible key returns its value; a decode step, a chunk and the prefill give the same bits."""
+    L = 150
+    c = syn.attention_inputs(36, [L], [L], Hq=4, Hkv=2, D=16, fmt="fp16")
+    O, _ = orc.attention(c["Q"], c["K"], c["V"], c["cu_q"], c["cu_k"], c["scale"], True, fmt="fp16")
+    for h in range(4):
+        assert np.array_equal(O[0, h], c["V"][0, h // 2])
+    for i in (0, 63, 64, 149):
+        Od, _ = orc.attention(c["Q"][i:i + 1], c["K"][:i + 1], c["V"][:i + 1], [0, 1], [0, i + 1], c["scale"], True, fmt="fp16")
+        assert np.array_equal(Od[0], O[i]), i
+    Oc, _ = orc.attention(c["Q"][98:101], c["K"][:101], c["V"][:101], [0, 3], [0, 101], c["scale"], True, fmt="fp16")
+    assert np.array_equal(Oc, O[98:101])
+    assert not np.array_equal(O, orc.attention(c["Q"], c["K"], c["V"], c["cu_q"], c["cu_k"], c["scale"], True)[0])
