@@ -31,6 +31,8 @@
  *                            streaming-softmax recurrence over tiles at absolute positions.
  *   16-bit operands are bf16 or IEEE binary16 (the kernel table lists both); the
  *   format only changes the exact widening and the one output rounding.
+ *   tbik_oracle_gemm_f32*    the same GEMM on fp32 operands (third row of that table): a
+ *                            leaf accumulates by one fused multiply-add per k.
  *
  * Pins (tests marked "not gpu"): hand-derived tree values, Theorem 1 across
  * P and M, exact-integer inputs against int64 arithmetic, fp64 brute force
@@ -360,6 +362,70 @@ int tbik_oracle_gemm(const uint16_t *X, long ldx, const uint16_t *W, long ldw,
         }
         free(S);
         free(col);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ fp32 operands */
+
+/*
+ * The kernel table lists FP32 beside BF16 and FP16; the method (Sec. 4.2, App. C, App. D.1) is the same, but the
+ * product of two fp32 numbers is no longer exact in fp32, so how a leaf accumulates has to be said.  Reading: one
+ * fused multiply-add per k, i.e. a single rounding of the exact x*w + acc,
+ *   s_j = fma(x_b, w_b, ... fma(x_{a+1}, w_{a+1}, fma(x_a, w_a, +0)) ...)      over superleaf j, ascending k
+ *   y   = T(s_0 .. s_{n_s-1})
+ * (for 16-bit operands the same formula holds with every product exact, so this is the one definition).
+ */
+float tbik_oracle_gemm_f32_element(const float *X, long ldx, const float *W, long ldw,
+                                   long m, long n, int K, int leaf, int k_first, int evaluator, int P) {
+    long ns = superleaf_count(K, leaf, k_first, P);
+    if (ns < 0) return NAN;
+    long sl = (long)leaf * k_first;
+    float *s = (float *)malloc((size_t)ns * sizeof(float));
+    for (long j = 0; j < ns; ++j) {
+        float acc = 0.0f;
+        for (long k = j * sl; k < (j + 1) * sl; ++k) acc = fmaf(X[m * ldx + k], W[k * ldw + n], acc);
+        s[j] = acc;
+    }
+    float y = combine_superleaves(s, ns, evaluator, P, NULL);
+    free(s);
+    return y;
+}
+
+int tbik_oracle_gemm_f32_elements(const float *X, long ldx, const float *W, long ldw,
+                                  const int64_t *rows, const int64_t *cols, long count,
+                                  int K, int leaf, int k_first, int evaluator, int P, float *out) {
+    if (superleaf_count(K, leaf, k_first, P) < 0) return -1;
+#pragma omp parallel for schedule(dynamic, 16)
+    for (long i = 0; i < count; ++i)
+        out[i] = tbik_oracle_gemm_f32_element(X, ldx, W, ldw, rows[i], cols[i], K, leaf, k_first, evaluator, P);
+    return 0;
+}
+
+/* Whole matrix, element by element (parallel over rows).  partials [P,M,N] only for EVAL_SHARDED (may be NULL). */
+int tbik_oracle_gemm_f32(const float *X, long ldx, const float *W, long ldw, float *Y32, long ldy,
+                         int M, int N, int K, int leaf, int k_first, int evaluator, int P, float *partials) {
+    long ns = superleaf_count(K, leaf, k_first, P);
+    if (ns < 0) return -1;
+    const long sl = (long)leaf * k_first;
+#pragma omp parallel
+    {
+        float *s = (float *)malloc((size_t)ns * sizeof(float));
+        float part[64];
+#pragma omp for schedule(dynamic, 1)
+        for (long m = 0; m < M; ++m)
+            for (long n = 0; n < N; ++n) {
+                for (long j = 0; j < ns; ++j) {
+                    float acc = 0.0f;
+                    for (long k = j * sl; k < (j + 1) * sl; ++k) acc = fmaf(X[m * ldx + k], W[k * ldw + n], acc);
+                    s[j] = acc;
+                }
+                float y = combine_superleaves(s, ns, evaluator, P, part);
+                if (Y32) Y32[m * ldy + n] = y;
+                if (partials && evaluator == EVAL_SHARDED)
+                    for (int p = 0; p < P; ++p) partials[((size_t)p * M + m) * N + n] = part[p];
+            }
+        free(s);
     }
     return 0;
 }

@@ -67,6 +67,15 @@ def lib():
         L.tbik_oracle_gemm.restype = C.c_int
         L.tbik_oracle_gemm.argtypes = [u16p, C.c_long, u16p, C.c_long, f32p, u16p, C.c_long,
                                        C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f32p]
+        L.tbik_oracle_gemm_f32_element.restype = C.c_float
+        L.tbik_oracle_gemm_f32_element.argtypes = [f32p, C.c_long, f32p, C.c_long, C.c_long, C.c_long,
+                                                   C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]
+        L.tbik_oracle_gemm_f32_elements.restype = C.c_int
+        L.tbik_oracle_gemm_f32_elements.argtypes = [f32p, C.c_long, f32p, C.c_long, i64p, i64p, C.c_long,
+                                                    C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f32p]
+        L.tbik_oracle_gemm_f32.restype = C.c_int
+        L.tbik_oracle_gemm_f32.argtypes = [f32p, C.c_long, f32p, C.c_long, f32p, C.c_long,
+                                           C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f32p]
         L.tbik_oracle_tree_combine.restype = C.c_int
         L.tbik_oracle_tree_combine.argtypes = [f32p, C.c_int, C.c_long, f32p, u16p, C.c_int]
         L.tbik_oracle_treesum.restype = C.c_float
@@ -196,6 +205,44 @@ def gemm_elements(X, W, rows, cols, leaf: int, k_first: int = 1, evaluator: int 
     rc = lib().tbik_oracle_gemm_elements(xp, X.shape[1], wp, W.shape[1], rp, cp, rows.size, X.shape[1],
                                          leaf, k_first, evaluator, P, FORMATS[fmt],
                                          out.ctypes.data_as(C.POINTER(C.c_float)))
+    if rc != 0:
+        raise ValueError("oracle gemm: illegal tree parameters (K, leaf, k_first, P)")
+    return out
+
+
+def gemm_f32(X, W, leaf: int, k_first: int = 1, evaluator: int = EVAL_RECURSIVE, P: int = 1, want_partials: bool = False):
+    """Y = X W in the tree order for fp32 operands (a leaf accumulates by one fused multiply-add per k).
+    Returns Y fp32 [M,N] [, partials [P,M,N]]."""
+    X, xp = _f32(X)
+    W, wp = _f32(W)
+    M, K = X.shape
+    K2, N = W.shape
+    assert K == K2
+    Y32 = np.empty((M, N), dtype=np.float32)
+    parts = np.zeros((P, M, N), dtype=np.float32) if want_partials else None
+    rc = lib().tbik_oracle_gemm_f32(xp, K, wp, N, Y32.ctypes.data_as(C.POINTER(C.c_float)), N, M, N, K, leaf, k_first,
+                                    evaluator, P, parts.ctypes.data_as(C.POINTER(C.c_float)) if want_partials else None)
+    if rc != 0:
+        raise ValueError("oracle gemm: illegal tree parameters (K, leaf, k_first, P)")
+    return (Y32, parts) if want_partials else Y32
+
+
+def gemm_f32_element(X, W, m: int, n: int, leaf: int, k_first: int = 1, evaluator: int = EVAL_RECURSIVE, P: int = 1):
+    X, xp = _f32(X)
+    W, wp = _f32(W)
+    return np.float32(lib().tbik_oracle_gemm_f32_element(xp, X.shape[1], wp, W.shape[1], m, n, X.shape[1],
+                                                         leaf, k_first, evaluator, P))
+
+
+def gemm_f32_elements(X, W, rows, cols, leaf: int, k_first: int = 1, evaluator: int = EVAL_RECURSIVE, P: int = 1):
+    """fp32 results at the listed (row, col) positions, fp32 operands."""
+    X, xp = _f32(X)
+    W, wp = _f32(W)
+    rows, rp = _i64(rows)
+    cols, cp = _i64(cols)
+    out = np.empty(rows.size, dtype=np.float32)
+    rc = lib().tbik_oracle_gemm_f32_elements(xp, X.shape[1], wp, W.shape[1], rp, cp, rows.size, X.shape[1],
+                                             leaf, k_first, evaluator, P, out.ctypes.data_as(C.POINTER(C.c_float)))
     if rc != 0:
         raise ValueError("oracle gemm: illegal tree parameters (K, leaf, k_first, P)")
     return out
