@@ -318,6 +318,23 @@ def extras(tb, syn, torch, np, to_dev):
         res["oproj_fp16_M%d" % M] = {"ms": round(t, 4), "tflops": round(2.0 * M * 4096 * 4096 / (t * 1e-3) / 1e12, 2),
                                      "baseline_ms": round(tb_ms, 4)}
     del X, W
+    # fp32 operands: the shape of the paper's kernel figure (K = 6144, N = 2048; leaf 128 = its FP32 block, K_first 3)
+    # and the o_proj shape; peak of the fp32 matrix instruction: 157.3 TFLOP/s
+    for name, K, N, leaf, g in (("fp32_k6144_n2048", 6144, 2048, 128, 3), ("oproj_fp32", 4096, 4096, 256, 1)):
+        Xf, Wf = syn.gemm_random_f32(4, 4096, K, N)
+        X, W = torch.from_numpy(Xf).to("cuda:0"), torch.from_numpy(Wf).to("cuda:0")
+        for M in (64, 4096):
+            y = torch.empty((M, N), dtype=torch.float32, device=X.device)
+            f = lambda: tb.tbik_gemm_f32(X[:M], W, leaf, g, out=y)
+            f(); f()
+            t = min(time_region(f, 5, torch) for _ in range(3))
+            b = lambda: torch.matmul(X[:M], W)
+            b(); b()
+            tb_ms = min(time_region(b, 5, torch) for _ in range(3))
+            tf = 2.0 * M * K * N / (t * 1e-3) / 1e12
+            res["%s_M%d" % (name, M)] = {"ms": round(t, 4), "tflops": round(tf, 2), "frac_mfma_fp32": round(tf / 157.3, 4),
+                                         "baseline_ms": round(tb_ms, 4)}
+        del X, W
     for H in (4096, 5120):
         xb, wb = syn.rmsnorm_inputs(8192, H)
         x, w = to_dev(xb), to_dev(wb)

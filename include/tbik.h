@@ -228,6 +228,28 @@ int tbik_gemm_reference_f16(const void *X, int64_t ldx, const void *W, int64_t l
                             int M, int N, int K, int leaf, int k_first, int P, void *hip_stream);
 
 /*
+ * The same three calls for fp32 operands (third row of that kernel table).  X and W hold IEEE binary32 values and Y
+ * is fp32.  The product of two fp32 numbers is not exact in fp32 and the paper does not say how a leaf accumulates
+ * then; this library's definition: one fused multiply-add per k (a single rounding of x*w + acc), in ascending k
+ * from +0 inside a superleaf -- the fp32 matrix instruction computes exactly that chain, and so does fmaf on a CPU --
+ * and above the superleaves the tree stated for tbik_gemm.  (For operands that happen to be bf16 or fp16 numbers every
+ * product is exact and the chain is the plain left-to-right fp32 sum; the 16-bit calls add the 16 products of a matrix
+ * instruction in that instruction's own fixed order, so their fp32 output agrees with it closely, not bit for bit.)
+ * ldx and ldw are multiples of 4 here (16 bytes); the other
+ * arguments, the workspace rule (tbik_gemm_workspace_bytes), the determinism contract and the errors are those of
+ * tbik_gemm, tbik_gemm_shard_partials and tbik_gemm_reference.  Superleaves that are not a multiple of 32 run on the
+ * reference kernel.
+ */
+int tbik_gemm_f32(const void *X, int64_t ldx, const void *W, int64_t ldw, void *Y, int64_t ldy,
+                  int M, int N, int K, int leaf, int k_first,
+                  void *workspace, size_t workspace_bytes, void *hip_stream);
+int tbik_gemm_shard_partials_f32(const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
+                                 int M, int N, int K, int leaf, int k_first, int P,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
+int tbik_gemm_reference_f32(const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
+                            void *Y, int64_t ldy, int M, int N, int K, int leaf, int k_first, int P, void *hip_stream);
+
+/*
  * tbik_rmsnorm and tbik_combine_residual_rmsnorm for tensors of IEEE binary16 (App. B and Alg. 2 do not depend on
  * the storage format): every 16-bit tensor of the call (x, weight, y; residual, hidden, normed) is fp16, widened
  * exactly, all arithmetic is the fp32 arithmetic stated above in the same order, and each output takes one rounding

@@ -46,6 +46,13 @@ SIGNATURES = {
                                           C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
     "tbik_combine_residual_rmsnorm": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p,
                                                 C.c_int, C.c_int, C.c_void_p]),
+    "tbik_gemm_f32": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tbik_gemm_shard_partials_f32": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p,
+                                               C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                               C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tbik_gemm_reference_f32": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64,
+                                          C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
     "tbik_rmsnorm_f16": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_void_p]),
     "tbik_combine_residual_rmsnorm_f16": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p,
                                                     C.c_void_p, C.c_int, C.c_int, C.c_void_p]),
@@ -172,6 +179,29 @@ def tbik_gemm_f16(X: torch.Tensor, W: torch.Tensor, leaf: int, k_first: int = 1,
     return _gemm("tbik_gemm_f16", torch.float16, X, W, leaf, k_first, out_dtype, out, workspace)
 
 
+def tbik_gemm_f32(X: torch.Tensor, W: torch.Tensor, leaf: int, k_first: int = 1, out: torch.Tensor | None = None,
+                  workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Y = X @ W in the tree order, whole K on this device (fp32 operands, fp32 output)."""
+    _rowmajor(X, "X"); _rowmajor(W, "W")
+    assert X.dtype == torch.float32 and W.dtype == torch.float32
+    M, K = X.shape
+    K2, N = W.shape
+    assert K == K2
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=X.device)
+    _rowmajor(out, "out")
+    assert out.dtype == torch.float32 and out.shape == (M, N)
+    if workspace is None:
+        need = gemm_workspace_bytes(M, N, K, leaf, k_first)
+        if need:
+            workspace = _workspace(need, X.device)
+    st = lib().tbik_gemm_f32(X.data_ptr(), X.stride(0), W.data_ptr(), W.stride(0), out.data_ptr(), out.stride(0),
+                             M, N, K, leaf, k_first, workspace.data_ptr() if workspace is not None else None,
+                             workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream())
+    _check(st, "tbik_gemm_f32")
+    return out
+
+
 def _gemm_shard_partials(entry: str, in_dtype, X, W, leaf, k_first, P, out, workspace):
     _rowmajor(X, "X"); _rowmajor(W, "W")
     assert X.dtype == in_dtype and W.dtype == in_dtype
@@ -203,6 +233,12 @@ def tbik_gemm_shard_partials_f16(X: torch.Tensor, W: torch.Tensor, leaf: int, k_
                                  out: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
     """partials[p] = subtree sum of K-shard p (fp32 [P, M, N]); fp16 operands."""
     return _gemm_shard_partials("tbik_gemm_shard_partials_f16", torch.float16, X, W, leaf, k_first, P, out, workspace)
+
+
+def tbik_gemm_shard_partials_f32(X: torch.Tensor, W: torch.Tensor, leaf: int, k_first: int, P: int,
+                                 out: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """partials[p] = subtree sum of K-shard p (fp32 [P, M, N]); fp32 operands."""
+    return _gemm_shard_partials("tbik_gemm_shard_partials_f32", torch.float32, X, W, leaf, k_first, P, out, workspace)
 
 
 def tbik_tree_combine(partials: torch.Tensor, out_dtype=torch.bfloat16, out: torch.Tensor | None = None) -> torch.Tensor:
@@ -333,6 +369,21 @@ def tbik_gemm_reference_f16(X: torch.Tensor, W: torch.Tensor, leaf: int, k_first
                             out_dtype=torch.float32):
     """The reference kernel on fp16 operands."""
     return _gemm_reference("tbik_gemm_reference_f16", torch.float16, X, W, leaf, k_first, P, out_dtype)
+
+
+def tbik_gemm_reference_f32(X: torch.Tensor, W: torch.Tensor, leaf: int, k_first: int = 1, P: int = 1):
+    """The reference kernel on fp32 operands: (partials [P,M,N], Y fp32 or None)."""
+    _rowmajor(X, "X"); _rowmajor(W, "W")
+    assert X.dtype == torch.float32 and W.dtype == torch.float32
+    M, K = X.shape
+    N = W.shape[1]
+    parts = torch.empty((P, M, N), dtype=torch.float32, device=X.device)
+    Y = torch.empty((M, N), dtype=torch.float32, device=X.device) if P == 1 else None
+    st = lib().tbik_gemm_reference_f32(X.data_ptr(), X.stride(0), W.data_ptr(), W.stride(0), parts.data_ptr(),
+                                       Y.data_ptr() if Y is not None else None, Y.stride(0) if Y is not None else 0,
+                                       M, N, K, leaf, k_first, P, _stream())
+    _check(st, "tbik_gemm_reference_f32")
+    return parts, Y
 
 
 def _gemm_reference(entry: str, in_dtype, X, W, leaf, k_first, P, out_dtype):

@@ -39,11 +39,23 @@ int check_tree(int M, int N, int K, int leaf, int k_first, int P, int *superleaf
     return TBIK_OK;
 }
 
-int check_operands(const void *X, int64_t ldx, const void *W, int64_t ldw, int N, int K) {
+int check_operands(int x_dtype, const void *X, int64_t ldx, const void *W, int64_t ldw, int N, int K) {
     if (!X || !W) return TBIK_ERR_NULL;
     if (ldx < K || ldw < N) return TBIK_ERR_SHAPE;
-    if (!aligned(X, 16) || !aligned(W, 16) || ldx % 8 != 0 || ldw % 8 != 0) return TBIK_ERR_ALIGN;
+    const int per16 = (x_dtype == TBIK_F32) ? 4 : 8;       // elements per 16 bytes
+    if (!aligned(X, 16) || !aligned(W, 16) || ldx % per16 != 0 || ldw % per16 != 0) return TBIK_ERR_ALIGN;
     return TBIK_OK;
+}
+
+// The kernels of an operand format.
+bool tiled_supports(const GemmArgs &a, int variant) {
+    return a.x_dtype == TBIK_F32 ? gemm_f32_tiled_supports(a) : gemm_tiled_supports(a, variant);
+}
+hipError_t launch_reference(const GemmArgs &a, hipStream_t s) {
+    return a.x_dtype == TBIK_F32 ? launch_gemm_f32_reference(a, s) : launch_gemm_reference(a, s);
+}
+hipError_t launch_tiled(const GemmArgs &a, int variant, hipStream_t s) {
+    return a.x_dtype == TBIK_F32 ? launch_gemm_f32_tiled(a, s) : launch_gemm_tiled(a, variant, s);
 }
 
 // Internal split of K across workgroups for shapes with too few output tiles to fill the GPU: the kernel is
@@ -62,7 +74,8 @@ int internal_split(int M, int N, int ns) {
 
 int pick_variant(const GemmArgs &a) {
     const int forced = g_forced_variant.load();
-    if (forced != VARIANT_AUTO) return (forced == VARIANT_REFERENCE || gemm_tiled_supports(a, forced)) ? forced : VARIANT_REFERENCE;
+    if (forced != VARIANT_AUTO) return (forced == VARIANT_REFERENCE || tiled_supports(a, forced)) ? forced : VARIANT_REFERENCE;
+    if (a.x_dtype == TBIK_F32) return gemm_f32_tiled_supports(a) ? VARIANT_T128 : VARIANT_REFERENCE;   // one tile shape
     if (a.M > 64 && gemm_tiled_supports(a, VARIANT_T128)) return VARIANT_T128;
     if (a.M > 32 && gemm_tiled_supports(a, VARIANT_T64)) return VARIANT_T64;
     if (gemm_tiled_supports(a, VARIANT_T32)) return VARIANT_T32;
@@ -95,14 +108,14 @@ int gemm_shard_partials(int x_dtype, const void *X, int64_t ldx, const void *W, 
     int rc = check_tree(M, N, K, leaf, k_first, P, &sl, &ns);
     if (rc != TBIK_OK) return rc;
     if (M == 0 || N == 0) return TBIK_OK;
-    rc = check_operands(X, ldx, W, ldw, N, K);
+    rc = check_operands(x_dtype, X, ldx, W, ldw, N, K);
     if (rc != TBIK_OK) return rc;
     if (!partials) return TBIK_ERR_NULL;
     if (!aligned(partials, 16)) return TBIK_ERR_ALIGN;
     GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)W, ldw, partials, nullptr, 0, TBIK_F32, M, N, K, sl, ns, P, x_dtype};
     hipStream_t s = (hipStream_t)hip_stream;
     const int v = pick_variant(a);
-    hipError_t e = (v == VARIANT_REFERENCE) ? launch_gemm_reference(a, s) : launch_gemm_tiled(a, v, s);
+    hipError_t e = (v == VARIANT_REFERENCE) ? launch_reference(a, s) : launch_tiled(a, v, s);
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }
 
@@ -114,7 +127,7 @@ int gemm(int x_dtype, const void *X, int64_t ldx, const void *W, int64_t ldw, vo
     if (rc != TBIK_OK) return rc;
     if (!legal_y_dtype(y_dtype, x_dtype)) return TBIK_ERR_DTYPE;
     if (M == 0 || N == 0) return TBIK_OK;
-    rc = check_operands(X, ldx, W, ldw, N, K);
+    rc = check_operands(x_dtype, X, ldx, W, ldw, N, K);
     if (rc != TBIK_OK) return rc;
     if (!Y) return TBIK_ERR_NULL;
     if (ldy < N) return TBIK_ERR_SHAPE;
@@ -131,12 +144,12 @@ int gemm(int x_dtype, const void *X, int64_t ldx, const void *W, int64_t ldw, vo
     const int v = pick_variant(probe);
     hipError_t e;
     if (split == 1 || v == VARIANT_REFERENCE) {
-        e = (v == VARIANT_REFERENCE) ? launch_gemm_reference(a, s) : launch_gemm_tiled(a, v, s);
+        e = (v == VARIANT_REFERENCE) ? launch_reference(a, s) : launch_tiled(a, v, s);
     } else {
         a.partials = reinterpret_cast<float *>(workspace);
         a.Y = nullptr;
         a.P = split;
-        e = launch_gemm_tiled(a, v, s);
+        e = launch_tiled(a, v, s);
         if (e == hipSuccess) e = launch_tree_combine(a.partials, split, Y, ldy, y_dtype, M, N, s);
     }
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
@@ -150,14 +163,14 @@ int gemm_reference(int x_dtype, const void *X, int64_t ldx, const void *W, int64
     if (rc != TBIK_OK) return rc;
     if (!legal_y_dtype(y_dtype, x_dtype)) return TBIK_ERR_DTYPE;
     if (M == 0 || N == 0) return TBIK_OK;
-    rc = check_operands(X, ldx, W, ldw, N, K);
+    rc = check_operands(x_dtype, X, ldx, W, ldw, N, K);
     if (rc != TBIK_OK) return rc;
     if (!partials && !Y) return TBIK_ERR_NULL;
     if (Y && P != 1) return TBIK_ERR_SHARDS;
     if (Y && ldy < N) return TBIK_ERR_SHAPE;
     if (Y && !aligned(Y, y_dtype == TBIK_F32 ? 4 : 2)) return TBIK_ERR_ALIGN;
     GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)W, ldw, partials, Y, ldy, y_dtype, M, N, K, sl, ns, P, x_dtype};
-    hipError_t e = launch_gemm_reference(a, (hipStream_t)hip_stream);
+    hipError_t e = launch_reference(a, (hipStream_t)hip_stream);
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }
 
@@ -201,6 +214,24 @@ int tbik_gemm_reference_f16(const void *X, int64_t ldx, const void *W, int64_t l
                             void *Y, int64_t ldy, tbik_dtype y_dtype,
                             int M, int N, int K, int leaf, int k_first, int P, void *hip_stream) {
     return gemm_reference(TBIK_F16, X, ldx, W, ldw, partials, Y, ldy, (int)y_dtype, M, N, K, leaf, k_first, P, hip_stream);
+}
+
+int tbik_gemm_f32(const void *X, int64_t ldx, const void *W, int64_t ldw, void *Y, int64_t ldy,
+                  int M, int N, int K, int leaf, int k_first,
+                  void *workspace, size_t workspace_bytes, void *hip_stream) {
+    return gemm(TBIK_F32, X, ldx, W, ldw, Y, ldy, TBIK_F32, M, N, K, leaf, k_first, workspace, workspace_bytes, hip_stream);
+}
+
+int tbik_gemm_shard_partials_f32(const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
+                                 int M, int N, int K, int leaf, int k_first, int P,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream) {
+    (void)workspace; (void)workspace_bytes;
+    return gemm_shard_partials(TBIK_F32, X, ldx, W, ldw, partials, M, N, K, leaf, k_first, P, hip_stream);
+}
+
+int tbik_gemm_reference_f32(const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
+                            void *Y, int64_t ldy, int M, int N, int K, int leaf, int k_first, int P, void *hip_stream) {
+    return gemm_reference(TBIK_F32, X, ldx, W, ldw, partials, Y, ldy, TBIK_F32, M, N, K, leaf, k_first, P, hip_stream);
 }
 
 int tbik_tree_combine(const float *partials, int P, void *Y, int64_t ldy, tbik_dtype y_dtype,

@@ -22,7 +22,7 @@ struct GemmArgs {
     int superleaf;       // leaf * k_first
     int ns;              // number of superleaves (power of two)
     int P;               // shards (power of two, <= ns)
-    int x_dtype;         // TBIK_BF16 or TBIK_F16: storage format of X, W and of a 16-bit Y
+    int x_dtype;         // TBIK_BF16, TBIK_F16 or TBIK_F32: storage format of X, W (and of a 16-bit Y)
 };
 
 // Reference kernel: one wavefront per 32x32 tile and shard.  Writes partials (if set) and, when P == 1
@@ -33,6 +33,11 @@ hipError_t launch_gemm_reference(const GemmArgs &a, hipStream_t s);
 // if the variant cannot run this shape.  Same outputs as the reference kernel.
 hipError_t launch_gemm_tiled(const GemmArgs &a, int variant, hipStream_t s);
 bool gemm_tiled_supports(const GemmArgs &a, int variant);
+
+// The same two for fp32 operands (x_dtype TBIK_F32: X and W point to float, Y is fp32); one tile shape.
+hipError_t launch_gemm_f32_reference(const GemmArgs &a, hipStream_t s);
+hipError_t launch_gemm_f32_tiled(const GemmArgs &a, hipStream_t s);
+bool gemm_f32_tiled_supports(const GemmArgs &a);
 
 // Y = T(partials[0..P)) elementwise + one rounding.
 hipError_t launch_tree_combine(const float *partials, int P, void *Y, int64_t ldy, int y_dtype, int M, int N,

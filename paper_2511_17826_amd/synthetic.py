@@ -123,6 +123,18 @@ def gemm_random(seed: int, M: int, K: int, N: int, x_std: float = 1.0, w_std: fl
     return normal_bf16(rng, (M, K), x_std, fmt=fmt), normal_bf16(rng, (K, N), w_std, fmt=fmt)
 
 
+def gemm_random_f32(seed: int, M: int, K: int, N: int, x_std: float = 1.0, w_std: float = 0.02, exp_spread: int = 0):
+    """fp32 operands X [M,K] ~ N(0, x_std), W [K,N] ~ N(0, w_std) with full 24-bit significands; with ``exp_spread`` every
+    element is scaled by a random power of two in [-exp_spread, exp_spread] (cancellation and absorption cases)."""
+    rng = _rng(seed)
+    X = rng.standard_normal(size=(M, K), dtype=np.float32) * np.float32(x_std)
+    W = rng.standard_normal(size=(K, N), dtype=np.float32) * np.float32(w_std)
+    if exp_spread:
+        X = X * np.exp2(rng.integers(-exp_spread, exp_spread + 1, size=(M, K))).astype(np.float32)
+        W = W * np.exp2(rng.integers(-exp_spread, exp_spread + 1, size=(K, N))).astype(np.float32)
+    return np.ascontiguousarray(X, dtype=np.float32), np.ascontiguousarray(W, dtype=np.float32)
+
+
 def gemm_small_integers(seed: int, M: int, K: int, N: int, mag: int = 8, fmt: str = "bf16"):
     """Integer-valued operands with |x|,|w| <= mag.
 

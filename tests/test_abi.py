@@ -190,3 +190,20 @@ def test_fused_tail_argument_validation(L):
     assert call(P=32) == 7                                   # legal shard count, not built into the fused kernel
     assert call(residual=GOOD + 2) == 5
     assert call(normed=GOOD, residual=GOOD) == 2             # normed may not share the residual's buffer
+
+
+def test_fp32_gemm_entry_points_validate_like_the_others(L):
+    g = L.tbik_gemm_f32
+    assert g(GOOD, 512, GOOD, 256, GOOD, 256, 0, 256, 512, 64, 1, None, 0, None) == 0
+    assert g(None, 512, GOOD, 256, GOOD, 256, 4, 256, 512, 64, 1, None, 0, None) == 1
+    assert g(GOOD, 512, GOOD, 256, GOOD, 256, 4, 256, 500, 64, 1, None, 0, None) == 2
+    assert g(GOOD, 508, GOOD, 256, GOOD, 256, 4, 256, 448, 64, 1, None, 0, None) == 2          # 7 superleaves
+    assert g(GOOD, 516, GOOD, 260, GOOD, 260, 0, 256, 512, 64, 1, None, 0, None) == 0          # rows of 4 floats suffice
+    assert g(GOOD, 518, GOOD, 256, GOOD, 256, 4, 256, 512, 64, 1, None, 0, None) == 5          # ldx not a multiple of 4
+    assert g(GOOD, 512, GOOD, 256, GOOD, 256, 4, 256, 512, 64, 1, None, 0, None) == 6          # this shape splits K: workspace
+    sp = L.tbik_gemm_shard_partials_f32
+    assert sp(GOOD, 512, GOOD, 256, GOOD, 4, 256, 512, 64, 1, 3, None, 0, None) == 3
+    assert sp(GOOD, 512, GOOD, 256, None, 4, 256, 512, 64, 1, 2, None, 0, None) == 1
+    rf = L.tbik_gemm_reference_f32
+    assert rf(GOOD, 512, GOOD, 256, GOOD, GOOD, 256, 4, 256, 512, 64, 1, 2, None) == 3         # Y only with P == 1
+    assert rf(GOOD, 512, GOOD, 256, None, None, 256, 4, 256, 512, 64, 1, 1, None) == 1
