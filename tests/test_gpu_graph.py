@@ -53,3 +53,46 @@ def test_hot_path_in_a_hip_graph_replays_bit_identically():
         torch.cuda.synchronize()
         for got, ref in zip((xn, y, yf, lsm, rsum), want):
             assert torch.equal(got.view(torch.uint8), ref.view(torch.uint8)), rep
+
+
+def test_fp32_gemm_fp16_tail_and_attention_in_a_hip_graph():
+    """The later entry points (fp32 GEMM with its K split, fp16 fused tail, fp16 attention) under capture and replay."""
+    dev = "cuda:0"
+    M, K, N = 70, 2048, 512
+    Xf, Wf = syn.gemm_random_f32(31, M, K, N)
+    X32, W32 = gu.dev_f32(Xf), gu.dev_f32(Wf)
+    y32 = torch.empty((M, N), dtype=torch.float32, device=dev)
+    parts = torch.empty((4, M, N), dtype=torch.float32, device=dev)
+    ws = torch.empty(max(256, tb.gemm_workspace_bytes(M, N, K, 128, 1)), dtype=torch.uint8, device=dev)
+    res_b, w_b = syn.rmsnorm_inputs(M, N, seed=5, fmt="fp16")
+    res, wn = gu.dev_f16(res_b), gu.dev_f16(w_b)
+    hid, nrm = torch.empty_like(res), torch.empty_like(res)
+    a = syn.attention_inputs(32, [200, 1, 40], [200, 300, 90], Hq=8, Hkv=2, D=128, fmt="fp16")
+    Q, Kk, V = gu.dev_f16(a["Q"]), gu.dev_f16(a["K"]), gu.dev_f16(a["V"])
+    cu_q = torch.from_numpy(a["cu_q"]).to(dev)
+    cu_k = torch.from_numpy(a["cu_k"]).to(dev)
+    O = torch.empty_like(Q)
+
+    def one_pass():
+        tb.tbik_gemm_f32(X32, W32, 128, 1, out=y32, workspace=ws)
+        tb.tbik_gemm_shard_partials_f32(X32, W32, 128, 1, 4, out=parts, workspace=ws)
+        tb.tbik_combine_residual_rmsnorm_f16(parts, res, wn, 1e-6, hidden=hid, normed=nrm)
+        tb.tbik_attention_f16(Q, Kk, V, cu_q, cu_k, 200, a["scale"], True, out=O)
+
+    one_pass()
+    torch.cuda.synchronize()
+    outs = (y32, parts, hid, nrm, O)
+    want = [t.clone() for t in outs]
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            one_pass()
+    for rep in range(3):
+        for t in outs:
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip(outs, want):
+            assert torch.equal(got.view(torch.uint8), ref.view(torch.uint8)), rep

@@ -65,6 +65,36 @@ def test_gemm_random_shapes_all_variants_and_shard_counts():
                 assert torch.equal(y.view(torch.int32), ref.view(torch.int32)), (case, v, P)
 
 
+def test_fp32_gemm_random_shapes_bit_exact_against_the_oracle():
+    """fp32 operands: random values with spread exponents, every route, 0 bits against the oracle.  Shapes include N not
+    a multiple of 4 and superleaves that are not a multiple of 32 (reference kernel), operands inside wider buffers, and
+    batches small enough for the internal K split."""
+    rng = np.random.Generator(np.random.PCG64(777))
+    for case in range(14):
+        leaf = int(rng.choice([16, 32, 64, 128]))
+        g = int(rng.choice([1, 1, 2, 3]))
+        ns = int(rng.choice([1, 2, 4, 8, 16, 32]))
+        K = leaf * g * ns
+        if K > 8192:
+            continue
+        M = int(rng.choice([1, 3, 33, 64, 100, 129, 260]))
+        N = int(rng.choice([8, 20, 120, 128, 130, 256, 392]))
+        pad_x, pad_w = int(rng.choice([0, 4, 64])), int(rng.choice([0, 0, 8]))
+        ldw = (N + 3) // 4 * 4 + pad_w
+        X, Wfull = syn.gemm_random_f32(5000 + case, M, K + pad_x, ldw, exp_spread=int(rng.choice([0, 8])))
+        Xd = gu.dev_f32(X)[:, :K]
+        Wd = gu.dev_f32(Wfull[:K])[:, :N]
+        want = orc.gemm_f32(np.ascontiguousarray(X[:, :K]), np.ascontiguousarray(Wfull[:K, :N]), leaf, g)
+        for v in (tb.VARIANT_REFERENCE, tb.VARIANT_AUTO):
+            tb.tbik_set_gemm_variant(v)
+            y = tb.tbik_gemm_f32(Xd, Wd, leaf, g)
+            assert np.array_equal(gu.u32(gu.host_f32(y)), gu.u32(want)), (case, M, K, N, leaf, g, v)
+            for P in (2, 8, 32):
+                if P <= ns:
+                    y = tb.tbik_tree_combine(tb.tbik_gemm_shard_partials_f32(Xd, Wd, leaf, g, P), out_dtype=torch.float32)
+                    assert np.array_equal(gu.u32(gu.host_f32(y)), gu.u32(want)), (case, M, K, N, leaf, g, v, P)
+
+
 def test_attention_random_batches_two_kernels_and_single_sequences():
     rng = np.random.Generator(np.random.PCG64(4321))
     for case in range(16):
