@@ -20,12 +20,17 @@ __global__ __launch_bounds__(256) void tree_combine_vec4_kernel(const float *__r
         const int64_t row = q / quads_per_row;
         const int64_t col = (q - row * quads_per_row) << 2;
         const float *src = partials + row * N + col;
-        float4 in[P];
+        // Many planes (hundreds of MiB at the shapes of interest) are read once from HBM: streaming loads; a few planes
+        // are usually still in the memory-side cache of the kernel that wrote them, where plain loads are faster.
+        f32x4 in[P];
 #pragma unroll
-        for (int p = 0; p < P; ++p) in[p] = *reinterpret_cast<const float4 *>(src + (int64_t)p * plane);
+        for (int p = 0; p < P; ++p) {
+            const f32x4 *ptr = reinterpret_cast<const f32x4 *>(src + (int64_t)p * plane);
+            in[p] = (P >= 8) ? __builtin_nontemporal_load(ptr) : *ptr;
+        }
         float vx[P], vy[P], vz[P], vw[P];
 #pragma unroll
-        for (int p = 0; p < P; ++p) { vx[p] = in[p].x; vy[p] = in[p].y; vz[p] = in[p].z; vw[p] = in[p].w; }
+        for (int p = 0; p < P; ++p) { vx[p] = in[p][0]; vy[p] = in[p][1]; vz[p] = in[p][2]; vw[p] = in[p][3]; }
         const float x = tree_of<P>(vx), y = tree_of<P>(vy), z = tree_of<P>(vz), w = tree_of<P>(vw);
         if (OUT != TBIK_F32) {
             uint16_t *dst = reinterpret_cast<uint16_t *>(Y) + row * ldy + col;

@@ -312,7 +312,7 @@ void gemm_f32_tiled_kernel(const F32Params p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int row = m0 + wm * 64 + x * 32 + 8 * (r >> 2) + 4 * lg + (r & 3);
-                if (row < p.M && col < p.N) dst[(int64_t)row * ld + col] = acc.t[x][y][r];
+                if (row < p.M && col < p.N) __builtin_nontemporal_store(acc.t[x][y][r], dst + (int64_t)row * ld + col);   // read by a later kernel, if at all
             }
         }
 }

@@ -369,8 +369,8 @@ void gemm_tiled_kernel(const TiledParams p) {
                     __builtin_amdgcn_sched_barrier(0);
                     char *base = reinterpret_cast<char *>(dst + (int64_t)(m0 + (wm_u * MT + a) * 32) * ld + col0);
 #pragma unroll
-                    for (int it = 0; it < N_IT; ++it)
-                        *reinterpret_cast<f32x4 *>(base + it * it_step + lane_off) = v[it];
+                    for (int it = 0; it < N_IT; ++it)      // streaming stores: partials and fp32 outputs are read by a later kernel, if at all
+                        __builtin_nontemporal_store(v[it], reinterpret_cast<f32x4 *>(base + it * it_step + lane_off));
                 }
             }
             stores_in_flight = to_bf16 ? STORES_BF16 : STORES_F32;
