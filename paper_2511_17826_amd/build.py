@@ -79,6 +79,7 @@ def build(save_temps: bool = True, jobs: int = 8, defines=(), lib_path: str = LI
     if save_temps:
         check_generated_code(os.path.join(BUILD, "gemm_tiled-hip-amdgcn-amd-amdhsa-gfx950.s"), "gemm_tiled_kernel")
         check_generated_code(os.path.join(BUILD, "attention-hip-amdgcn-amd-amdhsa-gfx950.s"), "attention_")
+        check_generated_code(os.path.join(BUILD, "gemm_f32-hip-amdgcn-amd-amdhsa-gfx950.s"), "gemm_f32_tiled_kernel")
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib_path, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:

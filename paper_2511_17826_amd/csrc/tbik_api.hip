@@ -55,7 +55,7 @@ hipError_t launch_reference(const GemmArgs &a, hipStream_t s) {
     return a.x_dtype == TBIK_F32 ? launch_gemm_f32_reference(a, s) : launch_gemm_reference(a, s);
 }
 hipError_t launch_tiled(const GemmArgs &a, int variant, hipStream_t s) {
-    return a.x_dtype == TBIK_F32 ? launch_gemm_f32_tiled(a, s) : launch_gemm_tiled(a, variant, s);
+    return a.x_dtype == TBIK_F32 ? launch_gemm_f32_tiled(a, variant, s) : launch_gemm_tiled(a, variant, s);
 }
 
 // Internal split of K across workgroups for shapes with too few output tiles to fill the GPU: the kernel is
@@ -75,7 +75,7 @@ int internal_split(int M, int N, int ns) {
 int pick_variant(const GemmArgs &a) {
     const int forced = g_forced_variant.load();
     if (forced != VARIANT_AUTO) return (forced == VARIANT_REFERENCE || tiled_supports(a, forced)) ? forced : VARIANT_REFERENCE;
-    if (a.x_dtype == TBIK_F32) return gemm_f32_tiled_supports(a) ? VARIANT_T128 : VARIANT_REFERENCE;   // one tile shape
+    if (a.x_dtype == TBIK_F32) return gemm_f32_tiled_supports(a) ? VARIANT_AUTO : VARIANT_REFERENCE;    // the launcher picks the tile
     if (a.M > 64 && gemm_tiled_supports(a, VARIANT_T128)) return VARIANT_T128;
     if (a.M > 32 && gemm_tiled_supports(a, VARIANT_T64)) return VARIANT_T64;
     if (gemm_tiled_supports(a, VARIANT_T32)) return VARIANT_T32;

@@ -34,9 +34,9 @@ hipError_t launch_gemm_reference(const GemmArgs &a, hipStream_t s);
 hipError_t launch_gemm_tiled(const GemmArgs &a, int variant, hipStream_t s);
 bool gemm_tiled_supports(const GemmArgs &a, int variant);
 
-// The same two for fp32 operands (x_dtype TBIK_F32: X and W point to float, Y is fp32); one tile shape.
+// The same two for fp32 operands (x_dtype TBIK_F32: X and W point to float, Y is fp32); tiles of 128 or 32 rows.
 hipError_t launch_gemm_f32_reference(const GemmArgs &a, hipStream_t s);
-hipError_t launch_gemm_f32_tiled(const GemmArgs &a, hipStream_t s);
+hipError_t launch_gemm_f32_tiled(const GemmArgs &a, int variant, hipStream_t s);   // variant: tile shape, see kVariantNames
 bool gemm_f32_tiled_supports(const GemmArgs &a);
 
 // Y = T(partials[0..P)) elementwise + one rounding.

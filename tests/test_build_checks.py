@@ -56,3 +56,4 @@ def test_the_built_library_passed_the_check():
         pytest.skip("no assembly kept from the last build")
     b.check_generated_code(asm)
     b.check_generated_code(os.path.join(b.BUILD, "attention-hip-amdgcn-amd-amdhsa-gfx950.s"), "attention_")
+    b.check_generated_code(os.path.join(b.BUILD, "gemm_f32-hip-amdgcn-amd-amdhsa-gfx950.s"), "gemm_f32_tiled_kernel")

@@ -2,7 +2,7 @@
 
 The fp32 matrix instruction applies its two k-slots as two chained fused multiply-adds, which is the oracle's
 definition of a leaf, so the bar is 0 bits against the oracle on every input -- random data with full significands,
-wide exponent spreads and hand-built cancellations included -- for both kernels, every shard count and every batch.
+wide exponent spreads and hand-built cancellations included -- for every kernel, every shard count and every batch.
 """
 import numpy as np
 import pytest
@@ -16,7 +16,7 @@ from paper_2511_17826_amd import synthetic as syn
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = [tb.VARIANT_REFERENCE, tb.VARIANT_T128]
+VARIANTS = [tb.VARIANT_REFERENCE, tb.VARIANT_T128, tb.VARIANT_T32]      # reference, 128-row tile, 32-row tile
 
 
 @pytest.fixture(autouse=True)

@@ -85,7 +85,7 @@ def test_fp32_gemm_random_shapes_bit_exact_against_the_oracle():
         Xd = gu.dev_f32(X)[:, :K]
         Wd = gu.dev_f32(Wfull[:K])[:, :N]
         want = orc.gemm_f32(np.ascontiguousarray(X[:, :K]), np.ascontiguousarray(Wfull[:K, :N]), leaf, g)
-        for v in (tb.VARIANT_REFERENCE, tb.VARIANT_AUTO):
+        for v in (tb.VARIANT_REFERENCE, tb.VARIANT_T128, tb.VARIANT_T32, tb.VARIANT_AUTO):
             tb.tbik_set_gemm_variant(v)
             y = tb.tbik_gemm_f32(Xd, Wd, leaf, g)
             assert np.array_equal(gu.u32(gu.host_f32(y)), gu.u32(want)), (case, M, K, N, leaf, g, v)
