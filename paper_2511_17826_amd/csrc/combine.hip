@@ -9,7 +9,7 @@
 namespace tbik {
 
 // Vector path: N % 4 == 0; each thread owns 4 consecutive columns of one row.
-template <int P, int OUT>   // OUT: tbik_dtype of Y
+template <int P, int OUT, bool STREAM>   // OUT: tbik_dtype of Y; STREAM: the planes are read around the caches
 __global__ __launch_bounds__(256) void tree_combine_vec4_kernel(const float *__restrict__ partials, void *__restrict__ Y,
                                                                 int64_t ldy, int64_t M, int64_t N) {
     const int64_t quads_per_row = N >> 2;
@@ -20,13 +20,11 @@ __global__ __launch_bounds__(256) void tree_combine_vec4_kernel(const float *__r
         const int64_t row = q / quads_per_row;
         const int64_t col = (q - row * quads_per_row) << 2;
         const float *src = partials + row * N + col;
-        // Many planes (hundreds of MiB at the shapes of interest) are read once from HBM: streaming loads; a few planes
-        // are usually still in the memory-side cache of the kernel that wrote them, where plain loads are faster.
         f32x4 in[P];
 #pragma unroll
         for (int p = 0; p < P; ++p) {
             const f32x4 *ptr = reinterpret_cast<const f32x4 *>(src + (int64_t)p * plane);
-            in[p] = (P >= 8) ? __builtin_nontemporal_load(ptr) : *ptr;
+            in[p] = STREAM ? __builtin_nontemporal_load(ptr) : *ptr;
         }
         float vx[P], vy[P], vz[P], vw[P];
 #pragma unroll
@@ -77,7 +75,11 @@ static hipError_t launch_p_out(const float *partials, void *Y, int64_t ldy, int 
     if (blocks > 256 * 64) blocks = 256 * 64;   // grid-stride beyond 64 blocks per CU
     if (blocks < 1) blocks = 1;
     dim3 grid((unsigned)blocks), block(256);
-    if (vec) hipLaunchKernelGGL((tree_combine_vec4_kernel<P, OUT>), grid, block, 0, s, partials, Y, ldy, (int64_t)M, (int64_t)N);
+    // Hundreds of MiB of planes come from HBM and are read once: streaming loads (544 MiB at P = 8: 106 -> 101 us).
+    // Smaller sets are usually still in the memory-side cache of the kernel that wrote them, where plain loads are faster.
+    const bool stream = (int64_t)P * M * N * 4 > ((int64_t)192 << 20);
+    if (vec && stream) hipLaunchKernelGGL((tree_combine_vec4_kernel<P, OUT, true>), grid, block, 0, s, partials, Y, ldy, (int64_t)M, (int64_t)N);
+    else if (vec) hipLaunchKernelGGL((tree_combine_vec4_kernel<P, OUT, false>), grid, block, 0, s, partials, Y, ldy, (int64_t)M, (int64_t)N);
     else hipLaunchKernelGGL((tree_combine_scalar_kernel<P, OUT>), grid, block, 0, s, partials, Y, ldy, (int64_t)M, (int64_t)N);
     return hipGetLastError();
 }

@@ -63,6 +63,7 @@ struct TiledParams {
     int tiles;                  // output tiles per shard
     int work;                   // tiles * shards
     int vector_stores;          // outputs are 16-byte aligned with 16-byte aligned rows
+    int stream_stores;          // fp32 outputs bypass the caches (partials too large to stay there until they are combined)
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -368,9 +369,15 @@ void gemm_tiled_kernel(const TiledParams p) {
                     for (int it = 0; it < N_IT; ++it) v[it] = *reinterpret_cast<const f32x4 *>(rd + it * RPI * WCOLS);
                     __builtin_amdgcn_sched_barrier(0);
                     char *base = reinterpret_cast<char *>(dst + (int64_t)(m0 + (wm_u * MT + a) * 32) * ld + col0);
+                    if (p.stream_stores) {                 // uniform; the same number of store instructions either way
+                        // (in assembly: written as two branches of ordinary code the compiler merges them and drops the hint)
 #pragma unroll
-                    for (int it = 0; it < N_IT; ++it)      // streaming stores: partials and fp32 outputs are read by a later kernel, if at all
-                        __builtin_nontemporal_store(v[it], reinterpret_cast<f32x4 *>(base + it * it_step + lane_off));
+                        for (int it = 0; it < N_IT; ++it)
+                            asm volatile("global_store_dwordx4 %0, %1, off nt" ::"v"(base + it * it_step + lane_off), "v"(v[it]) : "memory");
+                    } else {
+#pragma unroll
+                        for (int it = 0; it < N_IT; ++it) *reinterpret_cast<f32x4 *>(base + it * it_step + lane_off) = v[it];
+                    }
                 }
             }
             stores_in_flight = to_bf16 ? STORES_BF16 : STORES_F32;
@@ -452,6 +459,10 @@ static hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
         const void *out = p.partials ? (const void *)p.partials : p.Y;
         const int64_t ld_bytes = p.partials ? (int64_t)a.N * 4 : a.ldy * (p.y_bf16 ? 2 : 4);
         p.vector_stores = ((reinterpret_cast<uintptr_t>(out) & 15) == 0) && (ld_bytes % 16 == 0);
+        // Partials of many shards exceed the 256 MiB memory-side cache before the combine reads them: written around
+        // the caches they do not evict the operands (P = 8 at 4096^2: 257 -> 170 us).  Fewer planes stay cached for
+        // their reader, so those keep ordinary stores.
+        p.stream_stores = a.partials != nullptr && (int64_t)a.P * a.M * a.N * 4 > ((int64_t)192 << 20);
     }
     const int levels = levels_for(p.ns_per_shard);
     int dev = 0;
