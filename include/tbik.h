@@ -4,7 +4,9 @@
  * The library computes matrix products and row reductions whose floating-point
  * summation order is one fixed binary tree, so that the output bits do not depend
  * on the batch size M, on the position of a row in the batch, or on the number P
- * of tensor-parallel shards the reduction dimension K is split into.
+ * of tensor-parallel shards the reduction dimension K is split into; and attention
+ * with a fixed key tile, whose bits do not depend on how queries are batched.
+ * Operands are bf16, fp16 or (matrix products) fp32; all accumulation is fp32.
  *
  * Vocabulary (Sec. 4.2, App. D.1):
  *   leaf        number of consecutive K-elements in one tile of the K dimension (Block_K)
