@@ -683,8 +683,8 @@ hipError_t launch_attention(const AttnArgs &a, hipStream_t s) {
     p.c = a.scale * 1.44269504088896340736f;
     if (a.heads_q > 65535 || a.batch > 65535) return hipErrorInvalidValue;
     // Same bits either way, so the choice is free: the wavefront groups that take turns pay two barriers per tile, which
-    // only very long prefills earn back (1 x 16384 tokens: 985 against 940 TFLOP/s; 2 x 8192: 857 against 896;
-    // 4 x 4096: 694 against 781; decode steps: 4.1 against 5.1 TB/s).
+    // only very long prefills earn back (1 x 16384 tokens: 1028 against 1022 TFLOP/s; 2 x 8192: 984 against 983;
+    // 4 x 4096: 868 against 881; decode steps: 4.1 against 5.1 TB/s).
     const int variant = g_attention_variant.load();
     const bool pingpong = (variant == 2) || (variant == 0 && a.max_seqlen_q >= 16384);
     const int rows = pingpong ? 2 * p.rows : p.rows;             // queries per head and workgroup
