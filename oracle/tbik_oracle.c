@@ -556,12 +556,19 @@ int tbik_oracle_row_logsoftmax(const float *x, float *out, int M, long V, int le
 
 /*
  * Batch-invariant attention (App. "Framework Modifications": the attention kernel works with a FIXED tile
- * size, and prefill and decode run the same kernel; Sec. 2.1: fp32 accumulators in Flash-Attention).
- * The paper names the rule, not the arithmetic; the arithmetic below is the streaming-softmax recurrence of
- * Flash-Attention with the key axis cut into tiles of `kv_tile` keys at ABSOLUTE positions
- * [t*kv_tile, (t+1)*kv_tile) of the sequence, visited in ascending order, one query row at a time, so that
- * a query's result depends on its own row of Q and on the keys it may see -- never on what else is in the
- * batch, on how many queries arrive together, or on whether the call is a prefill or a decode step.
+ * size, prefill and decode run the same kernel, and the decode-side optimisations of the serving stack are
+ * switched off; Sec. 2.1: fp32 accumulators in Flash-Attention).  The paper names the rule, not the
+ * arithmetic.  Where the paper switches the split of the key axis off, this definition makes it part of the
+ * arithmetic instead -- FIXED splits at absolute positions, applied in every phase -- which keeps prefill,
+ * decode and every batching bit-identical and leaves an implementation free to compute the splits of a long
+ * sequence in parallel (an extension of the paper's rule, not a statement of it).  The arithmetic below is the streaming-softmax
+ * recurrence of Flash-Attention with the key axis cut into tiles of `kv_tile` keys at ABSOLUTE positions
+ * [t*kv_tile, (t+1)*kv_tile) of the sequence, visited in ascending order, one query row at a time, and into
+ * SPLITS of `kv_split` consecutive tiles (also at absolute positions) whose states are merged in ascending
+ * order -- so that a query's result depends on its own row of Q and on the keys it may see, never on what
+ * else is in the batch, on how many queries arrive together, on whether the call is a prefill or a decode
+ * step, or on whether the splits of a long sequence were computed by one workgroup after the other or by
+ * many at once.
  *
  * Packed variable-length layout: sequence b owns query tokens cu_q[b]..cu_q[b+1]-1 and key tokens
  * cu_k[b]..cu_k[b+1]-1; token t, head h, channel d of Q is Q[t*q_stride + h*D + d] (16-bit); K and V
@@ -569,9 +576,9 @@ int tbik_oracle_row_logsoftmax(const float *x, float *out, int M, long V, int le
  * the queries are the LAST Lq positions of the sequence: query i sees key j iff j < Lk and (not causal or
  * j <= i + Lk - Lq).
  *
- * Per (sequence, head, query), with c = fl(scale * log2 e) in fp32:
+ * Per (sequence, head, query), with c = fl(scale * log2 e) in fp32, for each split that holds a visible key:
  *   m = -inf, l = 0, o[0..D) = 0
- *   for each tile t that holds at least one visible key, ascending:
+ *   for each tile t of the split that holds at least one visible key, ascending:
  *     s_j   = fl( (sum_d q_d k_jd) * c )            dot product in fp32, ascending d from +0; visible j only
  *     m'    = max(m, max_j s_j)
  *     a     = exp2(m - m')                          (0 for the first tile)
@@ -580,13 +587,17 @@ int tbik_oracle_row_logsoftmax(const float *x, float *out, int M, long V, int le
  *     o_d   = (o_d*a) + sum_j r16(p_j) * v_jd       ascending j, added one by one to o_d*a; p rounded (RNE) to the
  *                                                   tensors' 16-bit format (for binary16: on its subnormal grid below 2^-14)
  *     m     = m'
- *   O_d = r16(o_d / l), or 0 if the query sees no key.
+ * and the splits' states (m, l, o) are folded in ascending order, the first one as it is, every further one by
+ *   M = max(m_acc, m);  A = exp2(m_acc - M);  B = exp2(m - M)
+ *   l_acc = fl(l_acc*A) + fl(l*B);   o_acc,d = fl(o_acc,d*A) + fl(o_d*B);   m_acc = M
+ *   O_d = r16(o_acc,d / l_acc), or 0 if the query sees no key.
+ * A sequence of at most kv_split*kv_tile visible keys has one split and no fold.  kv_split <= 0: no splits.
  * O32 (optional) receives o_d / l before the rounding.  fmt: the format of Q, K, V and O (FMT_BF16 or FMT_F16).
  */
 int tbik_oracle_attention(const uint16_t *Q, const uint16_t *K, const uint16_t *V, uint16_t *O, float *O32,
                           const int32_t *cu_q, const int32_t *cu_k, int batch, int Hq, int Hkv, int D,
                           long q_stride, long k_stride, long v_stride, long o_stride,
-                          float scale, int causal, int kv_tile, int fmt) {
+                          float scale, int causal, int kv_tile, int kv_split, int fmt) {
     if (batch < 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || D <= 0 || kv_tile <= 0) return -1;
     const float c = scale * 1.44269504088896340736f;
     const int group = Hq / Hkv;
@@ -594,6 +605,7 @@ int tbik_oracle_attention(const uint16_t *Q, const uint16_t *K, const uint16_t *
     {
         float *s = (float *)malloc((size_t)kv_tile * sizeof(float));
         float *o = (float *)malloc((size_t)D * sizeof(float));
+        float *oacc = (float *)malloc((size_t)D * sizeof(float));
 #pragma omp for schedule(dynamic, 1) collapse(2)
         for (int b = 0; b < batch; ++b) {
             for (int h = 0; h < Hq; ++h) {
@@ -603,33 +615,57 @@ int tbik_oracle_attention(const uint16_t *Q, const uint16_t *K, const uint16_t *
                     const uint16_t *q = Q + (q0 + i) * q_stride + (long)h * D;
                     long last = causal ? i + Lk - Lq : Lk - 1;          /* last visible key */
                     if (last > Lk - 1) last = Lk - 1;
-                    float m = -INFINITY, l = 0.0f;
-                    for (int d = 0; d < D; ++d) o[d] = 0.0f;
-                    for (long j0 = 0; j0 <= last; j0 += kv_tile) {
-                        long j1 = j0 + kv_tile - 1;
-                        if (j1 > last) j1 = last;
-                        float tm = -INFINITY;
-                        for (long j = j0; j <= j1; ++j) {
-                            const uint16_t *k = K + (k0 + j) * k_stride + (long)hk * D;
-                            float dot = 0.0f;
-                            for (int d = 0; d < D; ++d) dot = dot + widen16(q[d], fmt) * widen16(k[d], fmt);
-                            s[j - j0] = dot * c;
-                            tm = s[j - j0] > tm ? s[j - j0] : tm;
+                    const long split_keys = kv_split > 0 ? (long)kv_split * kv_tile : (last + 1 > 0 ? last + 1 : 1);
+                    float m_acc = -INFINITY, l_acc = 0.0f;
+                    int have = 0;                                       /* a split has been folded in */
+                    for (long s0 = 0; s0 <= last; s0 += split_keys) {   /* one split: its own recurrence from the empty state */
+                        long s1 = s0 + split_keys - 1;
+                        if (s1 > last) s1 = last;
+                        float m = -INFINITY, l = 0.0f;
+                        for (int d = 0; d < D; ++d) o[d] = 0.0f;
+                        for (long j0 = s0; j0 <= s1; j0 += kv_tile) {
+                            long j1 = j0 + kv_tile - 1;
+                            if (j1 > s1) j1 = s1;
+                            float tm = -INFINITY;
+                            for (long j = j0; j <= j1; ++j) {
+                                const uint16_t *k = K + (k0 + j) * k_stride + (long)hk * D;
+                                float dot = 0.0f;
+                                for (int d = 0; d < D; ++d) dot = dot + widen16(q[d], fmt) * widen16(k[d], fmt);
+                                s[j - j0] = dot * c;
+                                tm = s[j - j0] > tm ? s[j - j0] : tm;
+                            }
+                            const float m2 = tm > m ? tm : m;
+                            const float a = exp2f(m - m2);
+                            float psum = 0.0f;
+                            for (int d = 0; d < D; ++d) o[d] = o[d] * a;
+                            for (long j = j0; j <= j1; ++j) {
+                                const float p = exp2f(s[j - j0] - m2);
+                                psum = psum + p;
+                                const float pb = widen16(round16(p, fmt), fmt);
+                                const uint16_t *v = V + (k0 + j) * v_stride + (long)hk * D;
+                                for (int d = 0; d < D; ++d) o[d] = o[d] + pb * widen16(v[d], fmt);
+                            }
+                            l = l * a + psum;
+                            m = m2;
                         }
-                        const float m2 = tm > m ? tm : m;
-                        const float a = exp2f(m - m2);
-                        float psum = 0.0f;
-                        for (int d = 0; d < D; ++d) o[d] = o[d] * a;
-                        for (long j = j0; j <= j1; ++j) {
-                            const float p = exp2f(s[j - j0] - m2);
-                            psum = psum + p;
-                            const float pb = widen16(round16(p, fmt), fmt);
-                            const uint16_t *v = V + (k0 + j) * v_stride + (long)hk * D;
-                            for (int d = 0; d < D; ++d) o[d] = o[d] + pb * widen16(v[d], fmt);
+                        if (!have) {                                    /* the first split as it is */
+                            m_acc = m; l_acc = l;
+                            for (int d = 0; d < D; ++d) oacc[d] = o[d];
+                            have = 1;
+                        } else {
+                            const float M = m_acc > m ? m_acc : m;
+                            const float A = exp2f(m_acc - M), B = exp2f(m - M);
+                            const float la = l_acc * A, lb = l * B;
+                            l_acc = la + lb;
+                            for (int d = 0; d < D; ++d) {
+                                const float ta = oacc[d] * A, tb = o[d] * B;
+                                oacc[d] = ta + tb;
+                            }
+                            m_acc = M;
                         }
-                        l = l * a + psum;
-                        m = m2;
                     }
+                    const float l = l_acc;
+                    for (int d = 0; d < D; ++d) o[d] = have ? oacc[d] : 0.0f;
                     for (int d = 0; d < D; ++d) {
                         const float r = (l > 0.0f) ? o[d] / l : 0.0f;
                         if (O32) O32[((q0 + i) * Hq + h) * (long)D + d] = r;
@@ -640,6 +676,7 @@ int tbik_oracle_attention(const uint16_t *Q, const uint16_t *K, const uint16_t *
         }
         free(s);
         free(o);
+        free(oacc);
     }
     return 0;
 }

@@ -93,7 +93,7 @@ def lib():
         i32p = C.POINTER(C.c_int32)
         L.tbik_oracle_attention.restype = C.c_int
         L.tbik_oracle_attention.argtypes = [u16p, u16p, u16p, u16p, f32p, i32p, i32p, C.c_int, C.c_int, C.c_int, C.c_int,
-                                            C.c_long, C.c_long, C.c_long, C.c_long, C.c_float, C.c_int, C.c_int, C.c_int]
+                                            C.c_long, C.c_long, C.c_long, C.c_long, C.c_float, C.c_int, C.c_int, C.c_int, C.c_int]
         L.tbik_oracle_f32_to_bf16.restype = C.c_uint16
         L.tbik_oracle_f32_to_bf16.argtypes = [C.c_float]
         L.tbik_oracle_f32_to_f16.restype = C.c_uint16
@@ -351,12 +351,15 @@ def row_logsoftmax(x, leaf: int = LEAF_F32) -> np.ndarray:
 
 # ------------------------------------------------------------------ attention
 
-KV_TILE = 64
+KV_TILE = 64        # keys per tile
+KV_SPLIT = 64       # tiles per split: 4096 keys
 
 
-def attention(Q, K, V, cu_q, cu_k, scale: float, causal: bool = True, kv_tile: int = KV_TILE, fmt: str = "bf16"):
-    """Fixed-tile attention on packed sequences.  Q [Tq, Hq, D], K and V [Tk, Hkv, D] as 16-bit patterns of format
-    `fmt`; cu_q, cu_k int32 [batch + 1].  Returns (O bits [Tq, Hq, D] in `fmt`, O fp32 before the rounding)."""
+def attention(Q, K, V, cu_q, cu_k, scale: float, causal: bool = True, kv_tile: int = KV_TILE, fmt: str = "bf16",
+              kv_split: int = KV_SPLIT):
+    """Fixed-tile, fixed-split attention on packed sequences.  Q [Tq, Hq, D], K and V [Tk, Hkv, D] as 16-bit patterns of
+    format `fmt`; cu_q, cu_k int32 [batch + 1]; kv_split tiles per split (0: no splits).
+    Returns (O bits [Tq, Hq, D] in `fmt`, O fp32 before the rounding)."""
     Q, qp = _u16(Q)
     K, kp = _u16(K)
     V, vp = _u16(V)
@@ -372,7 +375,7 @@ def attention(Q, K, V, cu_q, cu_k, scale: float, causal: bool = True, kv_tile: i
     rc = lib().tbik_oracle_attention(qp, kp, vp, O.ctypes.data_as(C.POINTER(C.c_uint16)),
                                      O32.ctypes.data_as(C.POINTER(C.c_float)), cu_q.ctypes.data_as(i32p),
                                      cu_k.ctypes.data_as(i32p), cu_q.size - 1, Hq, Hkv, D, Hq * D, Hkv * D, Hkv * D,
-                                     Hq * D, scale, int(causal), kv_tile, FORMATS[fmt])
+                                     Hq * D, scale, int(causal), kv_tile, kv_split, FORMATS[fmt])
     if rc != 0:
         raise ValueError("oracle attention: illegal head counts or tile")
     return O, O32

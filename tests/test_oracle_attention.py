@@ -158,3 +158,79 @@ def test_queries_without_a_visible_key_give_zero():
     c = syn.attention_inputs(40, [6], [4], Hq=1, Hkv=1, D=8)
     O, _ = orc.attention(c["Q"], c["K"], c["V"], c["cu_q"], c["cu_k"], c["scale"], True)
     assert not O[:2].any() and np.array_equal(O[2, 0], c["V"][0, 0])
+
+
+# ----------------------------------------------------------------------------- fixed splits of the key axis
+
+def test_splits_fold_in_ascending_order_and_match_fp64():
+    """Keys beyond one split (here 4 tiles of 16 = 64 keys per split, 300 keys): still the plain softmax within the
+    rounding bound, and not the bits of the unsplit recurrence (the fold is another order of roundings)."""
+    c = syn.attention_inputs(41, [300, 1, 40], [300, 290, 40], Hq=2, Hkv=1, D=16)
+    O, O32 = orc.attention(c["Q"], c["K"], c["V"], c["cu_q"], c["cu_k"], c["scale"], True, kv_tile=16, kv_split=4)
+    want, B = plain_attention_fp64(c, True)
+    assert np.all(np.abs(O32 - want) <= 2.0 ** -8 * B)
+    assert np.array_equal(O, syn.f32_to_bf16_bits(O32))
+    _, U32 = orc.attention(c["Q"], c["K"], c["V"], c["cu_q"], c["cu_k"], c["scale"], True, kv_tile=16, kv_split=0)
+    assert np.array_equal(O32[:64], U32[:64])                       # queries with at most one split of visible keys: same bits
+    assert np.array_equal(O32[341:], U32[341:])                     # the 40-key sequence likewise
+    assert np.count_nonzero(O32[64:300] != U32[64:300]) > 1000
+    assert np.allclose(O32, U32, rtol=0, atol=2.0 ** -9)
+
+
+def test_splits_by_hand_fold():
+    """Two splits recomputed by two separate oracle calls and folded by the stated formula in numpy fp32."""
+    D, T, S = 8, 16, 2                                              # 32 keys per split
+    c = syn.attention_inputs(42, [1], [50], Hq=1, Hkv=1, D=D)
+    _, O32 = orc.attention(c["Q"], c["K"], c["V"], [0, 1], [0, 50], c["scale"], False, kv_tile=T, kv_split=S)
+    q = f32(c["Q"])[0, 0].astype(np.float32)
+    cc = np.float32(np.float32(c["scale"]) * np.float32(1.44269504088896340736))
+    states = []
+    for lo, hi in ((0, 32), (32, 50)):
+        K, V = f32(c["K"])[lo:hi, 0], f32(c["V"])[lo:hi, 0]
+        m, l, o = np.float32(-np.inf), np.float32(0), np.zeros(D, dtype=np.float32)
+        for t0 in range(0, hi - lo, T):
+            s = []
+            for j in range(t0, min(t0 + T, hi - lo)):
+                dot = np.float32(0)
+                for d in range(D):
+                    dot = np.float32(dot + np.float32(q[d] * K[j, d]))
+                s.append(np.float32(dot * cc))
+            m2 = max(m, max(s))
+            a = np.float32(np.exp2(np.float64(m - m2))) if np.isfinite(m) else np.float32(0)
+            o = (o * a).astype(np.float32)
+            ps = np.float32(0)
+            for j, sj in zip(range(t0, t0 + len(s)), s):
+                p = np.float32(np.exp2(np.float64(np.float32(sj - m2))))
+                ps = np.float32(ps + p)
+                pb = f32(syn.f32_to_bf16_bits(np.array([p], dtype=np.float32)))[0]
+                o = (o + (pb * V[j]).astype(np.float32)).astype(np.float32)
+            l = np.float32(np.float32(l * a) + ps)
+            m = m2
+        states.append((m, l, o))
+    (m1, l1, o1), (m2, l2, o2) = states
+    M = max(m1, m2)
+    A, Bf = np.float32(np.exp2(np.float64(m1 - M))), np.float32(np.exp2(np.float64(m2 - M)))
+    l = np.float32(np.float32(l1 * A) + np.float32(l2 * Bf))
+    o = ((o1 * A).astype(np.float32) + (o2 * Bf).astype(np.float32)).astype(np.float32)
+    assert np.allclose(O32[0, 0], o / l, rtol=3e-7, atol=1e-9)       # exp2 of libm vs numpy may differ in the last bit
+
+
+def test_splits_keep_prefill_decode_and_batch_invariance():
+    """With several splits: a query inside a prefill, as a decode step, in a chunk that starts inside a split, and in
+    a batch with other sequences: one set of bits."""
+    L = 200
+    c = syn.attention_inputs(43, [L], [L], Hq=2, Hkv=1, D=16)
+    kw = dict(kv_tile=16, kv_split=3)                               # 48 keys per split
+    O, _ = orc.attention(c["Q"], c["K"], c["V"], c["cu_q"], c["cu_k"], c["scale"], True, **kw)
+    for i in (0, 47, 48, 95, 96, 150, 199):
+        Od, _ = orc.attention(c["Q"][i:i + 1], c["K"][:i + 1], c["V"][:i + 1], [0, 1], [0, i + 1], c["scale"], True, **kw)
+        assert np.array_equal(Od[0], O[i]), i
+    Oc, _ = orc.attention(c["Q"][70:130], c["K"][:130], c["V"][:130], [0, 60], [0, 130], c["scale"], True, **kw)
+    assert np.array_equal(Oc, O[70:130])
+    other = syn.attention_inputs(44, [30], [120], Hq=2, Hkv=1, D=16)
+    Qb, Kb, Vb = (np.concatenate([other[n], c[n]]) for n in "QKV")
+    Ob, _ = orc.attention(Qb, Kb, Vb, [0, 30, 30 + L], [0, 120, 120 + L], c["scale"], True, **kw)
+    assert np.array_equal(Ob[30:], O)
+    # the split size is part of the result, like the tile size
+    O2, _ = orc.attention(c["Q"], c["K"], c["V"], c["cu_q"], c["cu_k"], c["scale"], True, kv_tile=16, kv_split=4)
+    assert not np.array_equal(O2, O) and np.array_equal(O2[:48], O[:48])
