@@ -157,15 +157,22 @@ int tbik_row_reduce(const void *x, tbik_dtype x_dtype, void *out, tbik_rowop op,
 
 /*
  * Batch-invariant attention on packed variable-length sequences (implementation appendix, "Framework Modifications
- * for vLLM and FSDP": the attention kernel uses a FIXED tile size, and prefill and decode run the same kernel;
- * Sec. 2.1: fp32 accumulators).  For sequence b, query head h, query i (of Lq = cu_q[b+1] - cu_q[b] queries, which
+ * for vLLM and FSDP": the attention kernel uses a FIXED tile size, prefill and decode run the same kernel, and the
+ * serving stack's decode-side optimisations are off; Sec. 2.1: fp32 accumulators).  For sequence b, query head h, query i (of Lq = cu_q[b+1] - cu_q[b] queries, which
  * are the LAST Lq positions of a sequence with Lk = cu_k[b+1] - cu_k[b] keys):
  *     O = softmax_j( scale * q . k_j ) applied to v_j  over the visible keys j,
  *     visible: j < Lk and (causal == 0 or j <= i + Lk - Lq);   a query that sees no key gives 0.
  * Order of the arithmetic (fixed, part of the contract): keys in tiles of 64 at absolute positions [64 t, 64 t + 64),
  * ascending; per tile the streaming-softmax step in fp32 with base-2 exponentials (scores scaled by
  * scale * log2 e), the tile's weights rounded to bf16 for the product with V, fp32 accumulation; one division by
- * the sum of weights and one rounding to bf16 at the end.  The bits of a query's output depend only on its own
+ * the sum of weights and one rounding to bf16 at the end.  Beyond 4096 keys the key axis is also cut into SPLITS of 64
+ * tiles at absolute positions: each split runs the recurrence from the empty state, and the splits' states (running
+ * maximum m, sum l, accumulator o) are folded in ascending order by
+ *     M = max(mA, mB);  a = exp2(mA - M), b = exp2(mB - M);  l = fl(lA a) + fl(lB b);  o = fl(oA a) + fl(oB b).
+ * (Where the paper turns the split of the key axis off to keep decode and prefill identical, a fixed split in every
+ * phase keeps them identical too and lets the splits of a long sequence be computed at once: a decode step on few
+ * long sequences then runs one workgroup per split and a second kernel for the fold; bigger calls let each workgroup
+ * walk its splits itself.  Same bits either way.)  The bits of a query's output depend only on its own
  * row of Q and on the keys and values it sees -- not on the batch, on the number of queries per sequence in the
  * call (prefill, decode step, chunk), or on the query's position in the packed tensor.
  *
@@ -174,28 +181,33 @@ int tbik_row_reduce(const void *x, tbik_dtype x_dtype, void *out, tbik_rowop op,
  *   cu_seqlens_q, cu_seqlens_k   DEVICE, int32 [batch + 1], non-decreasing prefix sums of the sequences' query and key
  *          counts; values are clamped to [0, total_q] / [0, total_k] inside the kernel
  *   max_seqlen_q   at least the largest Lq (with a smaller value some queries past it are left unwritten);
+ *   max_seqlen_k   at least the largest Lk (keys of a sequence past it are left out); decides the workspace and how the
+ *          call is cut into workgroups, never the bits; values above total_k are taken as total_k
  *          total_q, total_k: tokens in Q/O and in K/V
+ *   workspace   at least tbik_attention_workspace_bytes(batch, max_seqlen_q, max_seqlen_k, heads_q, heads_kv) bytes,
+ *          256-byte aligned; that is 0 (and the pointer may be NULL) when max_seqlen_k <= 4096
  *   head_dim 128 (other values: TBIK_ERR_UNSUPPORTED); heads_q a multiple of heads_kv; strides in elements, multiples
  *   of 8, at least heads * head_dim, below 2^24; pointers 16-byte aligned.  O must not overlap Q, K or V.
- * Errors: NULL, SHAPE, UNSUPPORTED, ALIGN, HIP.
+ * Errors: NULL, SHAPE, UNSUPPORTED, ALIGN, WORKSPACE, HIP.
  */
 int tbik_attention(const void *Q, const void *K, const void *V, void *O,
-                   const int32_t *cu_seqlens_q, const int32_t *cu_seqlens_k, int batch, int max_seqlen_q,
+                   const int32_t *cu_seqlens_q, const int32_t *cu_seqlens_k, int batch, int max_seqlen_q, int max_seqlen_k,
                    int total_q, int total_k, int heads_q, int heads_kv, int head_dim,
                    int64_t q_stride, int64_t k_stride, int64_t v_stride, int64_t o_stride,
-                   float scale, int causal, void *hip_stream);
+                   float scale, int causal, void *workspace, size_t workspace_bytes, void *hip_stream);
+size_t tbik_attention_workspace_bytes(int batch, int max_seqlen_q, int max_seqlen_k, int heads_q, int heads_kv);
 
 /*
  * tbik_attention for IEEE binary16 tensors: Q, K, V and O are fp16; the scores, the softmax state and the output
  * accumulators are fp32 as above, the tile's weights are rounded to fp16 for the product with V (to nearest-even, on
  * the subnormal grid of 2^-24 below 2^-14, so a weight below 2^-25 of the running maximum's contributes nothing),
- * and O takes one rounding to fp16.  Same tile, order, arguments, limits and errors.
+ * and O takes one rounding to fp16.  Same tile, splits, order, arguments, workspace, limits and errors.
  */
 int tbik_attention_f16(const void *Q, const void *K, const void *V, void *O,
-                       const int32_t *cu_seqlens_q, const int32_t *cu_seqlens_k, int batch, int max_seqlen_q,
+                       const int32_t *cu_seqlens_q, const int32_t *cu_seqlens_k, int batch, int max_seqlen_q, int max_seqlen_k,
                        int total_q, int total_k, int heads_q, int heads_kv, int head_dim,
                        int64_t q_stride, int64_t k_stride, int64_t v_stride, int64_t o_stride,
-                       float scale, int causal, void *hip_stream);
+                       float scale, int causal, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Scratch sizes (pure host functions; 0 if the arguments are illegal or no scratch is needed).
  * tbik_gemm_workspace_bytes covers tbik_gemm and tbik_gemm_shard_partials for any legal P. */

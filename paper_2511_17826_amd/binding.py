@@ -56,12 +56,13 @@ SIGNATURES = {
     "tbik_rmsnorm_f16": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_void_p]),
     "tbik_combine_residual_rmsnorm_f16": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p,
                                                     C.c_void_p, C.c_int, C.c_int, C.c_void_p]),
-    "tbik_attention": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
+    "tbik_attention": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
                                  C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_int64,
-                                 C.c_float, C.c_int, C.c_void_p]),
-    "tbik_attention_f16": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
-                                     C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_int64,
-                                     C.c_float, C.c_int, C.c_void_p]),
+                                 C.c_float, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tbik_attention_f16": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
+                                 C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_int64,
+                                 C.c_float, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tbik_attention_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]),
     "tbik_set_gemm_variant": (C.c_int, [C.c_int]),
     "tbik_set_attention_variant": (C.c_int, [C.c_int]),
     "tbik_set_row_wait_limit": (C.c_int, [C.c_int]),
@@ -309,7 +310,7 @@ def _token_major(t: torch.Tensor, name: str, dtype):
         raise ValueError("%s must be a %s GPU tensor [tokens, heads, head_dim] with contiguous heads" % (name, dtype))
 
 
-def _attention(entry, dtype, Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, scale, causal, out):
+def _attention(entry, dtype, Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, scale, causal, out, max_seqlen_k, workspace):
     _token_major(Q, "Q", dtype); _token_major(K, "K", dtype); _token_major(V, "V", dtype)
     Tq, Hq, D = Q.shape
     Tk, Hkv, _ = K.shape
@@ -321,26 +322,38 @@ def _attention(entry, dtype, Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, 
         out = torch.empty((Tq, Hq, D), dtype=dtype, device=Q.device)
     _token_major(out, "out", dtype)
     assert out.shape == Q.shape
+    batch = cu_seqlens_q.numel() - 1
+    if max_seqlen_k is None:                          # not given: read it from the device (a synchronisation)
+        max_seqlen_k = int((cu_seqlens_k[1:] - cu_seqlens_k[:-1]).max().item()) if batch > 0 else 0
+    need = int(lib().tbik_attention_workspace_bytes(batch, max_seqlen_q, min(max_seqlen_k, Tk), Hq, Hkv)) if D == 128 else 0
+    if workspace is None and need:
+        workspace = _workspace(need, Q.device)
     st = getattr(lib(), entry)(Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(), cu_seqlens_q.data_ptr(),
-                               cu_seqlens_k.data_ptr(), cu_seqlens_q.numel() - 1, max_seqlen_q, Tq, Tk, Hq, Hkv, D,
-                               Q.stride(0), K.stride(0), V.stride(0), out.stride(0), scale, int(causal), _stream())
+                               cu_seqlens_k.data_ptr(), batch, max_seqlen_q, max_seqlen_k, Tq, Tk, Hq, Hkv, D,
+                               Q.stride(0), K.stride(0), V.stride(0), out.stride(0), scale, int(causal),
+                               workspace.data_ptr() if workspace is not None else None,
+                               workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream())
     _check(st, entry)
     return out
 
 
 def tbik_attention(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, cu_seqlens_q: torch.Tensor,
                    cu_seqlens_k: torch.Tensor, max_seqlen_q: int, scale: float, causal: bool = True,
-                   out: torch.Tensor | None = None) -> torch.Tensor:
-    """Fixed-tile attention on packed sequences: Q [Tq, Hq, D], K and V [Tk, Hkv, D] (token stride free),
+                   out: torch.Tensor | None = None, max_seqlen_k: int | None = None,
+                   workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Fixed-tile, fixed-split attention on packed sequences: Q [Tq, Hq, D], K and V [Tk, Hkv, D] (token stride free),
     cu_seqlens_* int32 GPU tensors [batch + 1].  Returns O [Tq, Hq, D] bf16."""
-    return _attention("tbik_attention", torch.bfloat16, Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, scale, causal, out)
+    return _attention("tbik_attention", torch.bfloat16, Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, scale, causal, out,
+                      max_seqlen_k, workspace)
 
 
 def tbik_attention_f16(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, cu_seqlens_q: torch.Tensor,
                        cu_seqlens_k: torch.Tensor, max_seqlen_q: int, scale: float, causal: bool = True,
-                       out: torch.Tensor | None = None) -> torch.Tensor:
+                       out: torch.Tensor | None = None, max_seqlen_k: int | None = None,
+                       workspace: torch.Tensor | None = None) -> torch.Tensor:
     """The same on fp16 tensors."""
-    return _attention("tbik_attention_f16", torch.float16, Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, scale, causal, out)
+    return _attention("tbik_attention_f16", torch.float16, Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, scale, causal, out,
+                      max_seqlen_k, workspace)
 
 
 def tbik_row_reduce(x: torch.Tensor, op: int, out: torch.Tensor | None = None,

@@ -18,6 +18,14 @@
 // the number of queries in the call or on the batch: a tile that is masked for a row leaves that row's (m, l, o)
 // unchanged bit for bit (a = 1, p = 0), so the number of tiles a block walks does not matter either.
 //
+// Beyond ATT_SPLIT = 64 tiles (4096 keys) the key axis is cut into splits at absolute tile numbers: each split runs
+// the recurrence from the empty state, and the splits' states are folded in ascending order (state_fold below; an
+// empty split is skipped exactly).  This is an extension of the paper's rule, which keeps decode and prefill on one
+// order by leaving the key axis unsplit: a split that is fixed, and used in every phase, keeps them on one order as
+// well, and the splits of a long sequence can run at the same time.  Two forms, same bits: a workgroup walks all its
+// tiles and folds at every 64th through a state kept in the workspace (calls with many workgroups), or one workgroup
+// per split writes its state and attention_merge_kernel folds them (decode steps on few long sequences).
+//
 // Everything is computed transposed, so that a lane owns ONE query (column lane % 32 of every MFMA result) and
 // the per-query state m, l, a lives in one register per lane:
 //     S^T (keys x queries)  = K (A operand, 16-byte LDS reads)        x Q^T (B operand, in registers for the whole block)
@@ -36,6 +44,9 @@ constexpr int ATT_D = 128;    // head dimension
 constexpr int ATT_BQ = 128;   // queries per workgroup
 constexpr int ATT_KV = 64;    // keys per tile: part of the result, never tuned per call
 constexpr int ATT_TILE_BYTES = ATT_KV * ATT_D * 2;
+constexpr int ATT_SPLIT = 64; // key tiles per split (4096 keys): part of the result as well
+constexpr int ATT_THREAD_STATE = 4 + ATT_D / 32 * 16;            // floats of one thread's softmax state: m, l, two unused, o
+constexpr int ATT_STATE_FLOATS = ATT_THREAD_STATE * 256;         // one workgroup's
 
 typedef short att_v4i16 __attribute__((ext_vector_type(4)));
 typedef unsigned int att_u32x4 __attribute__((ext_vector_type(4)));
@@ -53,19 +64,105 @@ struct AttnParams {
     float c;                                          // scale * log2(e)
     int nq, ny, nz;                                   // query blocks, head groups, sequences: the work items of the launch
     int xcd_chunk;                                    // items per XCD when they divide evenly by 8, else 0
+    int n_splits;                                     // 1: an item walks all key tiles (folding its splits as it goes);
+                                                      // > 1: an item is one split of those, its state goes to `states`
+    int max_tiles;                                    // key tiles of a sequence of max_seqlen_k keys: no workgroup walks further
+    float *states;                                    // n_splits == 1: one state per item, scratch of the fold between splits;
+                                                      // n_splits > 1: [item][split] states for attention_merge_kernel
 };
 
 // Work item of this workgroup.  Consecutive workgroups go round the 8 XCDs; the items are numbered with the query
 // block fastest, then the head group, then the sequence, and XCD c takes the c-th eighth of that list, so that the
 // workgroups an XCD runs at a time are query blocks of the same heads and sequence and find its keys and values in
 // that XCD's L2 (dealt round-robin instead, every XCD walks every head's keys: 3.4 times the algorithmic fetch).
-__device__ __forceinline__ void attention_work_item(const AttnParams &p, int &qb, int &by, int &seq) {
+__device__ __forceinline__ void attention_work_item(const AttnParams &p, int &qb, int &by, int &seq, int &split, int &base) {
     int id = blockIdx.x;
     if (p.xcd_chunk) id = (id & 7) * p.xcd_chunk + (id >> 3);
-    const int bx = id % p.nq, t = id / p.nq;
+    const int bx = id % p.nq;
+    int t = id / p.nq;
+    split = t % p.n_splits;
+    t /= p.n_splits;
     qb = p.nq - 1 - bx;                               // long (late) blocks first
     by = t % p.ny;
     seq = t / p.ny;
+    base = (seq * p.ny + by) * p.nq + bx;             // number of the (query block, head group, sequence) triple
+}
+
+// The softmax state of one split of the keys, (m, l, o) per thread, and the fold of two of them (the accumulated one
+// A and the next split's B):  M = max(mA, mB);  a = exp2(mA - M), b = exp2(mB - M);  l = fl(lA a) + fl(lB b);
+// o = fl(oA a) + fl(oB b).  A split in which the query saw no key (l == 0) is skipped: the other state is taken as it
+// is, bit for bit.  The function is symmetric in its two arguments, and every multiplication and addition is a single
+// rounded operation (no contraction), so that the fold gives the same bits wherever it runs.
+// Layout in memory: a thread's 68 floats side by side -- (m, l, -, -), then o[db] as four groups of four -- so that one
+// address register and immediate offsets reach all of it (it is touched once per 64 key tiles; a layout with
+// consecutive lanes side by side measured slower: its many addresses disturb the tile loop's registers).
+__device__ __forceinline__ void state_store(f32x4 *wg, int tid, float m, float l, const f32x16 (&o)[ATT_D / 32]) {
+    f32x4 *v = wg + tid * (ATT_THREAD_STATE / 4);
+    v[0] = f32x4{m, l, 0.0f, 0.0f};
+#pragma unroll
+    for (int db = 0; db < ATT_D / 32; ++db)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[1 + 4 * db + q] = f32x4{o[db][4 * q], o[db][4 * q + 1], o[db][4 * q + 2], o[db][4 * q + 3]};
+}
+
+__device__ __forceinline__ void state_load(const f32x4 *wg, int tid, float &m, float &l, f32x16 (&o)[ATT_D / 32]) {
+    const f32x4 *v = wg + tid * (ATT_THREAD_STATE / 4);
+    const f32x4 h = v[0];
+    m = h[0];
+    l = h[1];
+#pragma unroll
+    for (int db = 0; db < ATT_D / 32; ++db)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 x = v[1 + 4 * db + q];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[db][4 * q + i] = x[i];
+        }
+}
+
+// (m, l, o) <- fold(the state stored at `wg`, (m, l, o))
+__device__ __forceinline__ void state_fold(const f32x4 *wg, int tid, float &m, float &l, f32x16 (&o)[ATT_D / 32]) {
+    const f32x4 *v = wg + tid * (ATT_THREAD_STATE / 4);
+    const f32x4 h = v[0];
+    const float m2 = h[0], l2 = h[1];
+    const float M = fmaxf(m2, m);
+    const float m_use = (M == -INFINITY) ? 0.0f : M;
+    const float a2 = __builtin_amdgcn_exp2f(m2 - m_use), a1 = __builtin_amdgcn_exp2f(m - m_use);
+    const bool mine_empty = (l == 0.0f), other_empty = (l2 == 0.0f);
+#pragma unroll
+    for (int db = 0; db < ATT_D / 32; ++db) {
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {                          // eight values at a time: the callers have few registers to spare
+            const f32x4 x0 = v[1 + 4 * db + 2 * hh], x1 = v[2 + 4 * db + 2 * hh];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const float o2 = r < 4 ? x0[r] : x1[r - 4];
+                const float t = __fadd_rn(__fmul_rn(o2, a2), __fmul_rn(o[db][8 * hh + r], a1));
+                o[db][8 * hh + r] = mine_empty ? o2 : (other_empty ? o[db][8 * hh + r] : t);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    const float lt = __fadd_rn(__fmul_rn(l2, a2), __fmul_rn(l, a1));
+    l = mine_empty ? l2 : (other_empty ? l : lt);
+    m = mine_empty ? m2 : (other_empty ? m : M);
+}
+
+// O = o / l, one rounding to the 16-bit format; lane (query li, half lg) holds channels 32 db + 8 q + 4 lg + (0..3).
+template <bool F16>
+__device__ __forceinline__ void attention_store_output(uint16_t *optr, float l, const f32x16 (&o)[ATT_D / 32]) {
+#pragma unroll
+    for (int db = 0; db < ATT_D / 32; ++db)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            float v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = (l > 0.0f) ? o[db][4 * q + i] / l : 0.0f;
+            att_u32x2 w;
+            w[0] = pack_16x2<F16>(v[0], v[1]);
+            w[1] = pack_16x2<F16>(v[2], v[3]);
+            *reinterpret_cast<att_u32x2 *>(optr + db * 32 + 8 * q) = w;
+        }
 }
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
@@ -93,9 +190,12 @@ void attention_kernel(const AttnParams p) {
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 31, lg = lane >> 5;
-    int qb, by, seq;
-    attention_work_item(p, qb, by, seq);
+    int qb, by, seq, split, base_item;
+    attention_work_item(p, qb, by, seq, split, base_item);
     const int R = p.rows;
+    const bool one_split_each = p.n_splits > 1;                   // uniform: this workgroup computes one split's state
+    f32x4 *const my_state = reinterpret_cast<f32x4 *>(const_cast<char *>(uniform_pointer(           // the workgroup's, in scalar registers
+        reinterpret_cast<const char *>(p.states + ((size_t)base_item * p.n_splits + split) * ATT_STATE_FLOATS))));
 
     // Sequence bounds, clamped so that no value of the offset arrays can lead outside the tensors.
     const int q0 = clampi(p.cu_q[seq], 0, p.total_q), q1 = clampi(p.cu_q[seq + 1], q0, p.total_q);
@@ -109,7 +209,7 @@ void attention_kernel(const AttnParams p) {
 
     const int q_last = min(Lq - 1, qb * R + R - 1);
     const int lim_block = CAUSAL ? min(Lk - 1, q_last + shift) : Lk - 1;
-    const int n_tiles = lim_block >= 0 ? lim_block / ATT_KV + 1 : 0;
+    const int n_tiles = lim_block >= 0 ? min(p.max_tiles, lim_block / ATT_KV + 1) : 0;   // keys past max_seqlen_k are left out
 
     // This lane's query (rows past the sequence repeat its last query; they are never stored).
     const int qrow = qb * R + slot % R;
@@ -198,22 +298,27 @@ void attention_kernel(const AttnParams p) {
         for (int r = 0; r < 16; ++r) o[db][r] = 0.0f;
     float m = -INFINITY, l = 0.0f;
 
-    if (n_tiles == 0) {                                           // uniform: no query of the block sees a key
-        if (qrow < Lq) {
+    // Tiles of this workgroup: all of them, or those of its split.
+    const int t_begin = one_split_each ? split * ATT_SPLIT : 0;
+    const int t_end = one_split_each ? min(n_tiles, t_begin + ATT_SPLIT) : n_tiles;
+    if (t_begin >= t_end) {                                       // uniform: no query of the block sees a key (of this split)
+        if (one_split_each) {
+            my_state[tid * (ATT_THREAD_STATE / 4)] = f32x4{-INFINITY, 0.0f, 0.0f, 0.0f};   // an empty state: only m and l are looked at
+        } else if (qrow < Lq) {
             uint16_t *optr = p.O + (int64_t)(q0 + qrow) * p.o_stride + (int64_t)head * ATT_D + lg * 64;
 #pragma unroll
             for (int i = 0; i < 8; ++i) *reinterpret_cast<att_u32x4 *>(optr + 8 * i) = att_u32x4{0, 0, 0, 0};
         }
         return;
     }
-    fetch(0, 0, 0);
+    fetch(t_begin, 0, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     // One key tile out of LDS buffer BUF; the next tile is fetched meanwhile and parked in the other buffer.
     auto tile = [&](auto buf_tag, int t) {
         constexpr int BUF = decltype(buf_tag)::value;
-        const bool more = t + 1 < n_tiles;
+        const bool more = t + 1 < t_end;
         if (more) fetch(t + 1, (BUF ^ 1) * ATT_TILE_BYTES, (BUF ^ 1) * ATT_TILE_BYTES);   // lands while this tile is multiplied;
                                                                   // that buffer was last read before the previous barrier
 
@@ -304,27 +409,64 @@ void attention_kernel(const AttnParams p) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // this wavefront's part of the next tile has landed
         __syncthreads();
     };
-    for (int t = 0; t < n_tiles; t += 2) {
+    bool folded = false;                                          // uniform: an accumulated state waits in my_state
+    for (int t = t_begin; t < t_end; t += 2) {
+        if (t > t_begin && (t & (ATT_SPLIT - 1)) == 0) {          // uniform: a split ends here (only when one workgroup walks them all)
+            // No direct load is in flight at this point (the tile before waited for its successor), so ordinary
+            // loads and stores, which the compiler counts itself, can be used.
+            if (folded) state_fold(my_state, tid, m, l, o);
+            state_store(my_state, tid, m, l, o);
+            folded = true;
+            m = -INFINITY;
+            l = 0.0f;
+#pragma unroll
+            for (int db = 0; db < ATT_D / 32; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[db][r] = 0.0f;
+        }
         tile(std::integral_constant<int, 0>{}, t);
-        if (t + 1 < n_tiles) tile(std::integral_constant<int, 1>{}, t + 1);
+        if (t + 1 < t_end) tile(std::integral_constant<int, 1>{}, t + 1);
     }
 
-    // ---- O = o / l, one rounding to the 16-bit format; lane (query li, half lg) holds channels 32 db + 8 q + 4 lg + (0..3) ----
-    if (qrow < Lq) {
-        uint16_t *optr = p.O + (int64_t)(q0 + qrow) * p.o_stride + (int64_t)head * ATT_D + 4 * lg;
+    if (one_split_each) {                                         // the state as it is; attention_merge_kernel folds and divides
+        state_store(my_state, tid, m, l, o);
+        return;
+    }
+    if (folded) state_fold(my_state, tid, m, l, o);
+    if (qrow < Lq) attention_store_output<F16>(p.O + (int64_t)(q0 + qrow) * p.o_stride + (int64_t)head * ATT_D + 4 * lg, l, o);
+}
+
+// Folds the states of the splits of each (query block, head group, sequence) triple in ascending order and writes the
+// output: the second kernel of a launch in which every split had its own workgroup.  Thread t of a workgroup here
+// stands for thread t of those workgroups (same query, same channels).
+template <bool F16>
+__global__ __launch_bounds__(256) void attention_merge_kernel(const AttnParams p) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, lg = lane >> 5;
+    const int bx = blockIdx.x % p.nq, t = blockIdx.x / p.nq;
+    const int qb = p.nq - 1 - bx, by = t % p.ny, seq = t / p.ny;
+    const int base_item = (seq * p.ny + by) * p.nq + bx;
+    const int R = p.rows;
+    const int q0 = clampi(p.cu_q[seq], 0, p.total_q), q1 = clampi(p.cu_q[seq + 1], q0, p.total_q);
+    const int Lq = q1 - q0;
+    if (qb * R >= Lq) return;
+    const int slot = wave * 32 + li;
+    const int head = by * p.pack + slot / R;
+    const int qrow = qb * R + slot % R;
+    if (qrow >= Lq) return;
+    const f32x4 *states = reinterpret_cast<const f32x4 *>(p.states + (size_t)base_item * p.n_splits * ATT_STATE_FLOATS);
+    float m, l;
+    f32x16 o[ATT_D / 32];
+    state_load(states, tid, m, l, o);
+    if (l == 0.0f) {                                              // an empty first split carries no o
 #pragma unroll
         for (int db = 0; db < ATT_D / 32; ++db)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float v[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = (l > 0.0f) ? o[db][4 * q + i] / l : 0.0f;
-                att_u32x2 w;
-                w[0] = pack_16x2<F16>(v[0], v[1]);
-                w[1] = pack_16x2<F16>(v[2], v[3]);
-                *reinterpret_cast<att_u32x2 *>(optr + db * 32 + 8 * q) = w;
-            }
+            for (int r = 0; r < 16; ++r) o[db][r] = 0.0f;
     }
+    for (int j = 1; j < p.n_splits; ++j) state_fold(states + (size_t)j * (ATT_STATE_FLOATS / 4), tid, m, l, o);
+    attention_store_output<F16>(p.O + (int64_t)(q0 + qrow) * p.o_stride + (int64_t)head * ATT_D + 4 * lg, l, o);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -355,7 +497,8 @@ void attention_pingpong_kernel(const AttnParams p) {
     const int group = wave >> 2;
     const int li = lane & 31, lg = lane >> 5;
     int qb, by, seq;
-    attention_work_item(p, qb, by, seq);
+    int split_unused, base_unused;
+    attention_work_item(p, qb, by, seq, split_unused, base_unused);      // launched with n_splits == 1 only
     const int R = 2 * p.rows;                                     // queries per head and workgroup: 256 / pack
 
     const int q0 = clampi(p.cu_q[seq], 0, p.total_q), q1 = clampi(p.cu_q[seq + 1], q0, p.total_q);
@@ -369,7 +512,7 @@ void attention_pingpong_kernel(const AttnParams p) {
 
     const int q_last = min(Lq - 1, qb * R + R - 1);
     const int lim_block = CAUSAL ? min(Lk - 1, q_last + shift) : Lk - 1;
-    const int n_tiles = lim_block >= 0 ? lim_block / ATT_KV + 1 : 0;
+    const int n_tiles = lim_block >= 0 ? min(p.max_tiles, lim_block / ATT_KV + 1) : 0;   // keys past max_seqlen_k are left out
 
     const int qrow = qb * R + slot % R;
     const int qpos = min(qrow, Lq - 1);
@@ -658,46 +801,82 @@ static hipError_t launch_with_lds(Kernel kernel, std::atomic<unsigned> &done, di
     return hipGetLastError();
 }
 
+// How a call is cut into work items: a pure function of the host-side arguments, shared by the launcher and by the
+// workspace size the caller is told.
+struct AttnPlan {
+    int pack, rows;          // query heads per workgroup, queries per head and workgroup
+    bool pingpong;
+    int64_t q_blocks, items; // items: (query block, head group, sequence) triples
+    int splits_max;          // splits a sequence of max_seqlen_k keys has
+    int n_splits;            // 1: every workgroup walks all its tiles; else one workgroup per split, then a merge kernel
+    size_t state_bytes;      // workspace: fold scratch (one state per item) or the states of all splits
+};
+
+static AttnPlan plan_attention(int batch, int max_seqlen_q, int max_seqlen_k, int heads_q, int heads_kv, int variant) {
+    AttnPlan pl;
+    const int group = heads_q / heads_kv;
+    pl.pack = (group <= ATT_BQ && (group & (group - 1)) == 0) ? group : 1;
+    pl.rows = ATT_BQ / pl.pack;
+    pl.splits_max = max_seqlen_k > 0 ? (max_seqlen_k + ATT_SPLIT * ATT_KV - 1) / (ATT_SPLIT * ATT_KV) : 1;
+    // The kernel whose wavefront groups take turns keeps one state per workgroup in two groups of wavefronts and has no
+    // fold: it serves sequences of one split (where it is a differently scheduled cross-check of the other kernel).
+    pl.pingpong = (variant == 2) && pl.splits_max == 1;
+    const int rows = pl.pingpong ? 2 * pl.rows : pl.rows;
+    pl.q_blocks = ((int64_t)max_seqlen_q + rows - 1) / rows;
+    pl.items = pl.q_blocks * (heads_q / pl.pack) * batch;
+    // Few items and long sequences (decode steps on long contexts): one workgroup per split, all at once, then the
+    // fold in a second kernel.  Same bits as one workgroup walking the splits, so the choice is free; below two
+    // workgroups per compute unit the parallel form wins.
+    pl.n_splits = (pl.splits_max > 1 && pl.items < 512) ? pl.splits_max : 1;
+    pl.state_bytes = pl.splits_max > 1 ? (size_t)pl.items * pl.n_splits * ATT_STATE_FLOATS * sizeof(float) : 0;
+    return pl;
+}
+
+size_t attention_workspace(int batch, int max_seqlen_q, int max_seqlen_k, int heads_q, int heads_kv) {
+    if (batch <= 0 || max_seqlen_q <= 0 || heads_q <= 0 || heads_kv <= 0 || heads_q % heads_kv) return 0;
+    // the variant switch may only move a call to the other kernel where no workspace is involved, so it does not matter here
+    return plan_attention(batch, max_seqlen_q, max_seqlen_k, heads_q, heads_kv, 0).state_bytes;
+}
+
 template <bool F16>
-static hipError_t launch_of(const AttnArgs &a, const AttnParams &p, dim3 grid, bool pingpong, hipStream_t s) {
+static hipError_t launch_of(const AttnArgs &a, const AttnParams &p, const AttnPlan &pl, hipStream_t s) {
     static std::atomic<unsigned> done[4] = {{0}, {0}, {0}, {0}};     // one set per operand format
-    if (pingpong) {
+    const dim3 grid((unsigned)(pl.items * pl.n_splits));
+    hipError_t e;
+    if (pl.pingpong) {
         constexpr int RING = 4;
         if (a.causal) return launch_with_lds(attention_pingpong_kernel<true, RING, F16>, done[0], grid, dim3(512), 2 * RING * ATT_TILE_BYTES, p, s);
         return launch_with_lds(attention_pingpong_kernel<false, RING, F16>, done[1], grid, dim3(512), 2 * RING * ATT_TILE_BYTES, p, s);
     }
-    if (a.causal) return launch_with_lds(attention_kernel<true, F16>, done[2], grid, dim3(256), 4 * ATT_TILE_BYTES, p, s);
-    return launch_with_lds(attention_kernel<false, F16>, done[3], grid, dim3(256), 4 * ATT_TILE_BYTES, p, s);
+    if (a.causal) e = launch_with_lds(attention_kernel<true, F16>, done[2], grid, dim3(256), 4 * ATT_TILE_BYTES, p, s);
+    else e = launch_with_lds(attention_kernel<false, F16>, done[3], grid, dim3(256), 4 * ATT_TILE_BYTES, p, s);
+    if (e != hipSuccess || pl.n_splits == 1) return e;
+    hipLaunchKernelGGL(attention_merge_kernel<F16>, dim3((unsigned)pl.items), dim3(256), 0, s, p);
+    return hipGetLastError();
 }
 
 hipError_t launch_attention(const AttnArgs &a, hipStream_t s) {
     if (a.batch <= 0 || a.max_seqlen_q <= 0 || a.total_q <= 0) return hipSuccess;
+    const AttnPlan pl = plan_attention(a.batch, a.max_seqlen_q, a.max_seqlen_k, a.heads_q, a.heads_kv, g_attention_variant.load());
+    if (pl.items * pl.n_splits > 0x7fffffff) return hipErrorInvalidValue;
     AttnParams p;
     p.Q = a.Q; p.K = a.K; p.V = a.V; p.O = a.O;
     p.cu_q = a.cu_q; p.cu_k = a.cu_k;
     p.q_stride = a.q_stride; p.k_stride = a.k_stride; p.v_stride = a.v_stride; p.o_stride = a.o_stride;
     p.total_q = a.total_q; p.total_k = a.total_k;
     p.group = a.heads_q / a.heads_kv;
-    p.pack = (p.group <= ATT_BQ && (p.group & (p.group - 1)) == 0) ? p.group : 1;
-    p.rows = ATT_BQ / p.pack;
+    p.pack = pl.pack;
+    p.rows = pl.rows;
     p.c = a.scale * 1.44269504088896340736f;
-    if (a.heads_q > 65535 || a.batch > 65535) return hipErrorInvalidValue;
-    // Same bits either way, so the choice is free: the wavefront groups that take turns pay two barriers per tile, which
-    // only very long prefills earn back (1 x 16384 tokens: 1028 against 1022 TFLOP/s; 2 x 8192: 984 against 983;
-    // 4 x 4096: 868 against 881; decode steps: 4.1 against 5.1 TB/s).
-    const int variant = g_attention_variant.load();
-    const bool pingpong = (variant == 2) || (variant == 0 && a.max_seqlen_q >= 16384);
-    const int rows = pingpong ? 2 * p.rows : p.rows;             // queries per head and workgroup
-    const int64_t q_blocks = ((int64_t)a.max_seqlen_q + rows - 1) / rows;
-    if (q_blocks > 0x7fffffff) return hipErrorInvalidValue;
-    p.nq = (int)q_blocks;
+    p.nq = (int)pl.q_blocks;
     p.ny = a.heads_q / p.pack;
     p.nz = a.batch;
-    const int64_t items = q_blocks * p.ny * p.nz;
-    if (items > 0x7fffffff) return hipErrorInvalidValue;
-    p.xcd_chunk = (items % 8 == 0 && q_blocks > 1) ? (int)(items / 8) : 0;    // one query block: nothing is shared between items
-    dim3 grid((unsigned)items);
-    return a.dtype == TBIK_F16 ? launch_of<true>(a, p, grid, pingpong, s) : launch_of<false>(a, p, grid, pingpong, s);
+    p.n_splits = pl.n_splits;
+    p.max_tiles = pl.splits_max * ATT_SPLIT;
+    p.states = reinterpret_cast<float *>(a.workspace);
+    const int64_t launched = pl.items * pl.n_splits;
+    p.xcd_chunk = (launched % 8 == 0 && pl.q_blocks > 1) ? (int)(launched / 8) : 0;   // one query block: nothing is shared between items
+    return a.dtype == TBIK_F16 ? launch_of<true>(a, p, pl, s) : launch_of<false>(a, p, pl, s);
 }
 
 }  // namespace tbik

@@ -266,11 +266,12 @@ int tbik_rmsnorm_f16(const void *x, const void *weight, void *y, int M, int H, f
 }
 
 static int attention(int dtype, const void *Q, const void *K, const void *V, void *O,
-                     const int32_t *cu_seqlens_q, const int32_t *cu_seqlens_k, int batch, int max_seqlen_q,
+                     const int32_t *cu_seqlens_q, const int32_t *cu_seqlens_k, int batch, int max_seqlen_q, int max_seqlen_k,
                      int total_q, int total_k, int heads_q, int heads_kv, int head_dim,
                      int64_t q_stride, int64_t k_stride, int64_t v_stride, int64_t o_stride,
-                     float scale, int causal, void *hip_stream) {
-    if (batch < 0 || max_seqlen_q < 0 || total_q < 0 || total_k < 0 || heads_q <= 0 || heads_kv <= 0 || head_dim <= 0)
+                     float scale, int causal, void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (batch < 0 || max_seqlen_q < 0 || max_seqlen_k < 0 || total_q < 0 || total_k < 0 || heads_q <= 0 || heads_kv <= 0 ||
+        head_dim <= 0)
         return TBIK_ERR_SHAPE;
     if (heads_q % heads_kv != 0 || heads_q > 65535 || batch > 65535) return TBIK_ERR_SHAPE;
     if (head_dim != 128) return TBIK_ERR_UNSUPPORTED;
@@ -284,29 +285,39 @@ static int attention(int dtype, const void *Q, const void *K, const void *V, voi
     if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) || !aligned(cu_seqlens_q, 4) ||
         !aligned(cu_seqlens_k, 4) || q_stride % 8 || k_stride % 8 || v_stride % 8 || o_stride % 8)
         return TBIK_ERR_ALIGN;
+    if (max_seqlen_k > total_k) max_seqlen_k = total_k;          // no sequence has more keys than the call
+    const size_t need = attention_workspace(batch, max_seqlen_q, max_seqlen_k, heads_q, heads_kv);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return TBIK_ERR_WORKSPACE;
+    if (need > 0 && !aligned(workspace, 256)) return TBIK_ERR_ALIGN;
     AttnArgs a{(const uint16_t *)Q, (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, dtype, cu_seqlens_q, cu_seqlens_k,
-               batch, max_seqlen_q, total_q, total_k, heads_q, heads_kv, q_stride, k_stride, v_stride, o_stride,
-               scale, causal != 0};
+               batch, max_seqlen_q, max_seqlen_k, total_q, total_k, heads_q, heads_kv, q_stride, k_stride, v_stride, o_stride,
+               scale, causal != 0, need > 0 ? workspace : nullptr};
     hipError_t e = launch_attention(a, (hipStream_t)hip_stream);
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }
 
 int tbik_attention(const void *Q, const void *K, const void *V, void *O,
-                   const int32_t *cu_seqlens_q, const int32_t *cu_seqlens_k, int batch, int max_seqlen_q,
+                   const int32_t *cu_seqlens_q, const int32_t *cu_seqlens_k, int batch, int max_seqlen_q, int max_seqlen_k,
                    int total_q, int total_k, int heads_q, int heads_kv, int head_dim,
                    int64_t q_stride, int64_t k_stride, int64_t v_stride, int64_t o_stride,
-                   float scale, int causal, void *hip_stream) {
-    return attention(TBIK_BF16, Q, K, V, O, cu_seqlens_q, cu_seqlens_k, batch, max_seqlen_q, total_q, total_k, heads_q,
-                     heads_kv, head_dim, q_stride, k_stride, v_stride, o_stride, scale, causal, hip_stream);
+                   float scale, int causal, void *workspace, size_t workspace_bytes, void *hip_stream) {
+    return attention(TBIK_BF16, Q, K, V, O, cu_seqlens_q, cu_seqlens_k, batch, max_seqlen_q, max_seqlen_k, total_q, total_k, heads_q,
+                     heads_kv, head_dim, q_stride, k_stride, v_stride, o_stride, scale, causal, workspace, workspace_bytes,
+                     hip_stream);
 }
 
 int tbik_attention_f16(const void *Q, const void *K, const void *V, void *O,
-                       const int32_t *cu_seqlens_q, const int32_t *cu_seqlens_k, int batch, int max_seqlen_q,
+                       const int32_t *cu_seqlens_q, const int32_t *cu_seqlens_k, int batch, int max_seqlen_q, int max_seqlen_k,
                        int total_q, int total_k, int heads_q, int heads_kv, int head_dim,
                        int64_t q_stride, int64_t k_stride, int64_t v_stride, int64_t o_stride,
-                       float scale, int causal, void *hip_stream) {
-    return attention(TBIK_F16, Q, K, V, O, cu_seqlens_q, cu_seqlens_k, batch, max_seqlen_q, total_q, total_k, heads_q,
-                     heads_kv, head_dim, q_stride, k_stride, v_stride, o_stride, scale, causal, hip_stream);
+                       float scale, int causal, void *workspace, size_t workspace_bytes, void *hip_stream) {
+    return attention(TBIK_F16, Q, K, V, O, cu_seqlens_q, cu_seqlens_k, batch, max_seqlen_q, max_seqlen_k, total_q, total_k, heads_q,
+                     heads_kv, head_dim, q_stride, k_stride, v_stride, o_stride, scale, causal, workspace, workspace_bytes,
+                     hip_stream);
+}
+
+size_t tbik_attention_workspace_bytes(int batch, int max_seqlen_q, int max_seqlen_k, int heads_q, int heads_kv) {
+    return attention_workspace(batch, max_seqlen_q, max_seqlen_k, heads_q, heads_kv);
 }
 
 int tbik_set_attention_variant(int variant) { return set_attention_variant(variant) < 0 ? TBIK_ERR_DTYPE : TBIK_OK; }

@@ -54,12 +54,14 @@ struct AttnArgs {
     uint16_t *O;
     int dtype;                    // TBIK_BF16 or TBIK_F16: the format of Q, K, V and O
     const int32_t *cu_q, *cu_k;   // device, [batch + 1]
-    int batch, max_seqlen_q, total_q, total_k;
+    int batch, max_seqlen_q, max_seqlen_k, total_q, total_k;
     int heads_q, heads_kv;
     int64_t q_stride, k_stride, v_stride, o_stride;
     float scale;
     int causal;
+    void *workspace;              // attention_workspace(...) bytes, or nullptr if that is 0
 };
+size_t attention_workspace(int batch, int max_seqlen_q, int max_seqlen_k, int heads_q, int heads_kv);
 hipError_t launch_attention(const AttnArgs &a, hipStream_t s);
 int set_attention_variant(int v);   // 0 = default, 1 = two workgroups per CU, 2 = two groups of wavefronts taking turns; returns the previous value, -1 if illegal
 

@@ -108,17 +108,24 @@ def test_fp16_entry_points_validate_like_the_bf16_ones(L):
 @pytest.mark.parametrize("entry", ["tbik_attention", "tbik_attention_f16"])
 def test_attention_argument_validation(L, entry):
     def att(**kw):
-        a = dict(Q=GOOD, K=GOOD, V=GOOD, O=GOOD, cq=GOOD, ck=GOOD, batch=2, mq=8, tq=16, tk=16, hq=4, hkv=2, d=128,
-                 sq=512, sk=256, sv=256, so=512, scale=0.1, causal=1)
+        a = dict(Q=GOOD, K=GOOD, V=GOOD, O=GOOD, cq=GOOD, ck=GOOD, batch=2, mq=8, mk=8, tq=16, tk=16, hq=4, hkv=2, d=128,
+                 sq=512, sk=256, sv=256, so=512, scale=0.1, causal=1, ws=None, wsb=0)
         a.update(kw)
-        return getattr(L, entry)(a["Q"], a["K"], a["V"], a["O"], a["cq"], a["ck"], a["batch"], a["mq"], a["tq"], a["tk"],
-                                 a["hq"], a["hkv"], a["d"], a["sq"], a["sk"], a["sv"], a["so"], a["scale"], a["causal"], None)
+        return getattr(L, entry)(a["Q"], a["K"], a["V"], a["O"], a["cq"], a["ck"], a["batch"], a["mq"], a["mk"], a["tq"],
+                                 a["tk"], a["hq"], a["hkv"], a["d"], a["sq"], a["sk"], a["sv"], a["so"], a["scale"],
+                                 a["causal"], a["ws"], a["wsb"], None)
     assert att(batch=0) == 0 and att(mq=0) == 0 and att(tq=0) == 0            # nothing to do: OK before any pointer is looked at
     assert att(batch=-1) == 2 and att(hq=5) == 2 and att(hkv=0) == 2          # heads_q must be a multiple of heads_kv
     assert att(sq=500) == 2 and att(sk=128) == 2 and att(so=1 << 24) == 2     # token stride below heads * 128, or too large
     assert att(d=64) == 7                                                     # only head dimension 128 is built
     assert att(Q=None) == 1 and att(cq=None) == 1 and att(K=None) == 1
     assert att(Q=GOOD + 2) == 5 and att(sk=260) == 5 and att(ck=GOOD + 2) == 5
+    assert att(mk=-1) == 2
+    # more than one split of keys (4096): the fold needs a workspace of the advertised size, 256-byte aligned
+    need = L.tbik_attention_workspace_bytes(2, 8, 5000, 4, 2)
+    assert need > 0 and L.tbik_attention_workspace_bytes(2, 8, 4096, 4, 2) == 0
+    assert att(mk=5000, tk=6000) == 6 and att(mk=5000, tk=6000, ws=GOOD, wsb=need - 1) == 6
+    assert att(mk=5000, tk=6000, ws=GOOD + 16, wsb=need) == 5
 
 
 def test_shard_and_combine_validation(L):

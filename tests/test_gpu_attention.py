@@ -246,3 +246,53 @@ def test_argument_validation_on_the_device():
     O = tb.tbik_attention(Q, Q, Q, i32([0, 1 << 30]), i32([-5, 1 << 30]), 8, 1.0)
     torch.cuda.synchronize()
     assert torch.equal(O, tb.tbik_attention(Q, Q, Q, i32([0, 8]), i32([0, 8]), 8, 1.0))
+
+
+def test_splits_one_workgroup_per_split_or_one_for_all_same_bits():
+    """Sequences of several splits (more than 4096 keys).  Small calls give every split its own workgroup and fold in a
+    second kernel; big calls let each workgroup walk its splits and fold as it goes: the same bits, row for row, for a
+    decode step, a chunk and a prefill; and parity with the oracle on sampled rows."""
+    Hq, Hkv = 8, 2
+    long_k = 9500                                                  # three splits, the last one ragged
+    c = syn.attention_inputs(91, [1, 300], [long_k, long_k], Hq=Hq, Hkv=Hkv, D=128)
+    small = run(c)                                                 # 4 query blocks x 2 head groups x 2 sequences: one workgroup per split
+    # the same two sequences inside a call with many others (more than 512 items): workgroups walk their splits
+    fill = syn.attention_inputs(92, [1] * 300, [40] * 300, Hq=Hq, Hkv=Hkv, D=128)
+    big = dict(c, Q=np.concatenate([fill["Q"], c["Q"]]), K=np.concatenate([fill["K"], c["K"]]), V=np.concatenate([fill["V"], c["V"]]),
+               cu_q=np.concatenate([fill["cu_q"], fill["cu_q"][-1] + c["cu_q"][1:]]).astype(np.int32),
+               cu_k=np.concatenate([fill["cu_k"], fill["cu_k"][-1] + c["cu_k"][1:]]).astype(np.int32))
+    Ob = run(big)
+    assert np.array_equal(Ob[300:], small)
+    assert np.array_equal(Ob[:300], run(fill))
+    # oracle: the decode row and three rows of the chunk, each as its own decode problem
+    dec = dict(c, Q=c["Q"][:1], K=c["K"][:long_k], V=c["V"][:long_k], cu_q=np.array([0, 1], dtype=np.int32),
+               cu_k=np.array([0, long_k], dtype=np.int32))
+    check_against_oracle(small[:1], dec, True)
+    for i in (0, 150, 299):
+        nk = long_k - 300 + i + 1
+        one = dict(c, Q=c["Q"][1 + i:2 + i], K=c["K"][long_k:long_k + nk], V=c["V"][long_k:long_k + nk],
+                   cu_q=np.array([0, 1], dtype=np.int32), cu_k=np.array([0, nk], dtype=np.int32))
+        got = run(one)
+        assert np.array_equal(got[0], small[1 + i]), i
+        if i == 299:
+            check_against_oracle(got, one, True)
+    # a prefill across two split boundaries, alone (splits in parallel) and four times in one call (walked)
+    p1 = syn.attention_inputs(93, [8300], [8300], Hq=4, Hkv=2, D=128)
+    O1 = run(p1)
+    p4 = dict(p1, Q=np.concatenate([p1["Q"]] * 8), K=np.concatenate([p1["K"]] * 8), V=np.concatenate([p1["V"]] * 8),
+              cu_q=(np.arange(9) * 8300).astype(np.int32), cu_k=(np.arange(9) * 8300).astype(np.int32))
+    O4 = run(p4)
+    for r in range(8):
+        assert np.array_equal(O4[r * 8300:(r + 1) * 8300], O1), r
+    for i in (4095, 4096, 8191, 8192, 8299):                       # rows next to the split boundaries, as decode steps
+        one = dict(p1, Q=p1["Q"][i:i + 1], K=p1["K"][:i + 1], V=p1["V"][:i + 1], cu_q=np.array([0, 1], dtype=np.int32),
+                   cu_k=np.array([0, i + 1], dtype=np.int32))
+        assert np.array_equal(run(one)[0], O1[i]), i
+
+
+def test_understated_max_seqlen_k_leaves_keys_out_and_stays_in_bounds():
+    c = syn.attention_inputs(94, [1], [6000], Hq=4, Hkv=2, D=128)
+    Q, K, V = gu.dev_bf16(c["Q"]), gu.dev_bf16(c["K"]), gu.dev_bf16(c["V"])
+    O = tb.tbik_attention(Q, K, V, i32(c["cu_q"]), i32(c["cu_k"]), 1, c["scale"], False, max_seqlen_k=4096)
+    short = dict(c, K=c["K"][:4096], V=c["V"][:4096], cu_k=np.array([0, 4096], dtype=np.int32))
+    assert np.array_equal(gu.host_bf16_bits(O), run(short, False))

@@ -77,7 +77,7 @@ def test_fp32_gemm_fp16_tail_and_attention_in_a_hip_graph():
         tb.tbik_gemm_f32(X32, W32, 128, 1, out=y32, workspace=ws)
         tb.tbik_gemm_shard_partials_f32(X32, W32, 128, 1, 4, out=parts, workspace=ws)
         tb.tbik_combine_residual_rmsnorm_f16(parts, res, wn, 1e-6, hidden=hid, normed=nrm)
-        tb.tbik_attention_f16(Q, Kk, V, cu_q, cu_k, 200, a["scale"], True, out=O)
+        tb.tbik_attention_f16(Q, Kk, V, cu_q, cu_k, 200, a["scale"], True, out=O, max_seqlen_k=300)   # given: reading it from the device would synchronise
 
     one_pass()
     torch.cuda.synchronize()
