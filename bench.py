@@ -375,7 +375,8 @@ def extras(tb, syn, torch, np, to_dev):
         Vv = torch.randn(B * L, Hkv, D, device="cuda:0").to(dt)
         cu = torch.arange(0, B + 1, dtype=torch.int32, device="cuda:0") * L
         O = torch.empty_like(Q)
-        f = lambda: att(Q, K, Vv, cu, cu, L, D ** -0.5, True, out=O)
+        ws = torch.empty(max(1, tb.attention_workspace_bytes(B, L, L, Hq, Hkv)), dtype=torch.uint8, device="cuda:0")
+        f = lambda: att(Q, K, Vv, cu, cu, L, D ** -0.5, True, out=O, max_seqlen_k=L, workspace=ws)
         f(); f()
         t = min(time_region(f, 10, torch) for _ in range(3))
         q4, k4, v4 = (a.view(B, L, -1, D).transpose(1, 2) for a in (Q, K, Vv))
@@ -387,7 +388,8 @@ def extras(tb, syn, torch, np, to_dev):
                                                    "frac_mfma": round(flops / (t * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
                                                    "baseline_ms": round(tb_ms, 4)}
         del Q, K, Vv, O, q4, k4, v4
-    for B, L, dt in ((64, 4096, torch.bfloat16), (256, 2048, torch.bfloat16), (64, 4096, torch.float16)):
+    for B, L, dt in ((64, 4096, torch.bfloat16), (256, 2048, torch.bfloat16), (64, 4096, torch.float16),
+                     (1, 32768, torch.bfloat16), (4, 32768, torch.bfloat16), (1, 131072, torch.bfloat16)):
         att = tb.tbik_attention if dt == torch.bfloat16 else tb.tbik_attention_f16
         tag = "" if dt == torch.bfloat16 else "fp16_"
         Q = torch.randn(B, Hq, D, device="cuda:0").to(dt)
@@ -396,7 +398,8 @@ def extras(tb, syn, torch, np, to_dev):
         cuq = torch.arange(0, B + 1, dtype=torch.int32, device="cuda:0")
         cuk = cuq * L
         O = torch.empty_like(Q)
-        f = lambda: att(Q, K, Vv, cuq, cuk, 1, D ** -0.5, True, out=O)
+        ws = torch.empty(max(1, tb.attention_workspace_bytes(B, 1, L, Hq, Hkv)), dtype=torch.uint8, device="cuda:0")
+        f = lambda: att(Q, K, Vv, cuq, cuk, 1, D ** -0.5, True, out=O, max_seqlen_k=L, workspace=ws)
         f(); f()
         t = min(time_region(f, 10, torch) for _ in range(3))
         q4 = Q.view(B, 1, Hq, D).transpose(1, 2)

@@ -310,6 +310,10 @@ def _token_major(t: torch.Tensor, name: str, dtype):
         raise ValueError("%s must be a %s GPU tensor [tokens, heads, head_dim] with contiguous heads" % (name, dtype))
 
 
+def attention_workspace_bytes(batch, max_seqlen_q, max_seqlen_k, heads_q, heads_kv) -> int:
+    return int(lib().tbik_attention_workspace_bytes(batch, max_seqlen_q, max_seqlen_k, heads_q, heads_kv))
+
+
 def _attention(entry, dtype, Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, scale, causal, out, max_seqlen_k, workspace):
     _token_major(Q, "Q", dtype); _token_major(K, "K", dtype); _token_major(V, "V", dtype)
     Tq, Hq, D = Q.shape

@@ -44,7 +44,10 @@ constexpr int ATT_D = 128;    // head dimension
 constexpr int ATT_BQ = 128;   // queries per workgroup
 constexpr int ATT_KV = 64;    // keys per tile: part of the result, never tuned per call
 constexpr int ATT_TILE_BYTES = ATT_KV * ATT_D * 2;
-constexpr int ATT_SPLIT = 64; // key tiles per split (4096 keys): part of the result as well
+#ifndef TBIK_ATT_SPLIT
+#define TBIK_ATT_SPLIT 64     // other values: timing experiments only (the bits change, the oracle's tests fail)
+#endif
+constexpr int ATT_SPLIT = TBIK_ATT_SPLIT;   // key tiles per split (4096 keys): part of the result as well
 constexpr int ATT_THREAD_STATE = 4 + ATT_D / 32 * 16;            // floats of one thread's softmax state: m, l, two unused, o
 constexpr int ATT_STATE_FLOATS = ATT_THREAD_STATE * 256;         // one workgroup's
 
@@ -96,8 +99,11 @@ __device__ __forceinline__ void attention_work_item(const AttnParams &p, int &qb
 // Layout in memory: a thread's 68 floats side by side -- (m, l, -, -), then o[db] as four groups of four -- so that one
 // address register and immediate offsets reach all of it (it is touched once per 64 key tiles; a layout with
 // consecutive lanes side by side measured slower: its many addresses disturb the tile loop's registers).
+// (the workgroup's pointer went through scalar registers as integers: say again that it points to global memory)
+typedef __attribute__((address_space(1))) f32x4 global_f32x4;
+
 __device__ __forceinline__ void state_store(f32x4 *wg, int tid, float m, float l, const f32x16 (&o)[ATT_D / 32]) {
-    f32x4 *v = wg + tid * (ATT_THREAD_STATE / 4);
+    global_f32x4 *v = (global_f32x4 *)(wg + tid * (ATT_THREAD_STATE / 4));
     v[0] = f32x4{m, l, 0.0f, 0.0f};
 #pragma unroll
     for (int db = 0; db < ATT_D / 32; ++db)
@@ -106,7 +112,7 @@ __device__ __forceinline__ void state_store(f32x4 *wg, int tid, float m, float l
 }
 
 __device__ __forceinline__ void state_load(const f32x4 *wg, int tid, float &m, float &l, f32x16 (&o)[ATT_D / 32]) {
-    const f32x4 *v = wg + tid * (ATT_THREAD_STATE / 4);
+    const global_f32x4 *v = (const global_f32x4 *)(wg + tid * (ATT_THREAD_STATE / 4));
     const f32x4 h = v[0];
     m = h[0];
     l = h[1];
@@ -122,14 +128,13 @@ __device__ __forceinline__ void state_load(const f32x4 *wg, int tid, float &m, f
 
 // (m, l, o) <- fold(the state stored at `wg`, (m, l, o))
 __device__ __forceinline__ void state_fold(const f32x4 *wg, int tid, float &m, float &l, f32x16 (&o)[ATT_D / 32]) {
-    const f32x4 *v = wg + tid * (ATT_THREAD_STATE / 4);
+    const global_f32x4 *v = (const global_f32x4 *)(wg + tid * (ATT_THREAD_STATE / 4));
     const f32x4 h = v[0];
     const float m2 = h[0], l2 = h[1];
     const float M = fmaxf(m2, m);
     const float m_use = (M == -INFINITY) ? 0.0f : M;
     const float a2 = __builtin_amdgcn_exp2f(m2 - m_use), a1 = __builtin_amdgcn_exp2f(m - m_use);
     const bool mine_empty = (l == 0.0f), other_empty = (l2 == 0.0f);
-#pragma unroll
     for (int db = 0; db < ATT_D / 32; ++db) {
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) {                          // eight values at a time: the callers have few registers to spare
@@ -303,7 +308,7 @@ void attention_kernel(const AttnParams p) {
     const int t_end = one_split_each ? min(n_tiles, t_begin + ATT_SPLIT) : n_tiles;
     if (t_begin >= t_end) {                                       // uniform: no query of the block sees a key (of this split)
         if (one_split_each) {
-            my_state[tid * (ATT_THREAD_STATE / 4)] = f32x4{-INFINITY, 0.0f, 0.0f, 0.0f};   // an empty state: only m and l are looked at
+            *(global_f32x4 *)(my_state + tid * (ATT_THREAD_STATE / 4)) = f32x4{-INFINITY, 0.0f, 0.0f, 0.0f};   // an empty state: only m and l are looked at
         } else if (qrow < Lq) {
             uint16_t *optr = p.O + (int64_t)(q0 + qrow) * p.o_stride + (int64_t)head * ATT_D + lg * 64;
 #pragma unroll
