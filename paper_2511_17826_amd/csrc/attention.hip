@@ -96,31 +96,37 @@ __device__ __forceinline__ void attention_work_item(const AttnParams &p, int &qb
 // o = fl(oA a) + fl(oB b).  A split in which the query saw no key (l == 0) is skipped: the other state is taken as it
 // is, bit for bit.  The function is symmetric in its two arguments, and every multiplication and addition is a single
 // rounded operation (no contraction), so that the fold gives the same bits wherever it runs.
-// Layout in memory: a thread's 68 floats side by side -- (m, l, -, -), then o[db] as four groups of four -- so that one
-// address register and immediate offsets reach all of it (it is touched once per 64 key tiles; a layout with
-// consecutive lanes side by side measured slower: its many addresses disturb the tile loop's registers).
-// (the workgroup's pointer went through scalar registers as integers: say again that it points to global memory)
+// Layout in memory, in units of 16 bytes: chunk c of thread t at [c * 256 + t] -- chunk 0 is (m, l, -, -), chunk
+// 1 + 4 db + q holds o[db][4 q .. 4 q + 3] -- so that the lanes of a wavefront touch consecutive memory (a thread's 272
+// bytes side by side cost 25 us per fold on a full chip: 64 cache lines per instruction).  The workgroup's base is
+// uniform and the pointer says "global" (it went through scalar registers as integers, which made it a generic one),
+// so the accesses take the scalar base + lane offset form: one address register.
 typedef __attribute__((address_space(1))) f32x4 global_f32x4;
 
+// Chunk c of thread tid: a uniform base (scalar registers) plus an unsigned 32-bit lane offset.
+__device__ __forceinline__ global_f32x4 *state_chunk(const f32x4 *wg, int c, int tid) {
+    typedef __attribute__((address_space(1))) char global_char;
+    global_char *base = (global_char *)const_cast<f32x4 *>(wg + c * 256);
+    return (global_f32x4 *)(base + (uint64_t)((uint32_t)tid * 16u));
+}
+
 __device__ __forceinline__ void state_store(f32x4 *wg, int tid, float m, float l, const f32x16 (&o)[ATT_D / 32]) {
-    global_f32x4 *v = (global_f32x4 *)(wg + tid * (ATT_THREAD_STATE / 4));
-    v[0] = f32x4{m, l, 0.0f, 0.0f};
+    *state_chunk(wg, 0, tid) = f32x4{m, l, 0.0f, 0.0f};
 #pragma unroll
     for (int db = 0; db < ATT_D / 32; ++db)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) v[1 + 4 * db + q] = f32x4{o[db][4 * q], o[db][4 * q + 1], o[db][4 * q + 2], o[db][4 * q + 3]};
+        for (int q = 0; q < 4; ++q) *state_chunk(wg, 1 + 4 * db + q, tid) = f32x4{o[db][4 * q], o[db][4 * q + 1], o[db][4 * q + 2], o[db][4 * q + 3]};
 }
 
 __device__ __forceinline__ void state_load(const f32x4 *wg, int tid, float &m, float &l, f32x16 (&o)[ATT_D / 32]) {
-    const global_f32x4 *v = (const global_f32x4 *)(wg + tid * (ATT_THREAD_STATE / 4));
-    const f32x4 h = v[0];
+    const f32x4 h = *state_chunk(wg, 0, tid);
     m = h[0];
     l = h[1];
 #pragma unroll
     for (int db = 0; db < ATT_D / 32; ++db)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const f32x4 x = v[1 + 4 * db + q];
+            const f32x4 x = *state_chunk(wg, 1 + 4 * db + q, tid);
 #pragma unroll
             for (int i = 0; i < 4; ++i) o[db][4 * q + i] = x[i];
         }
@@ -128,17 +134,17 @@ __device__ __forceinline__ void state_load(const f32x4 *wg, int tid, float &m, f
 
 // (m, l, o) <- fold(the state stored at `wg`, (m, l, o))
 __device__ __forceinline__ void state_fold(const f32x4 *wg, int tid, float &m, float &l, f32x16 (&o)[ATT_D / 32]) {
-    const global_f32x4 *v = (const global_f32x4 *)(wg + tid * (ATT_THREAD_STATE / 4));
-    const f32x4 h = v[0];
+    const f32x4 h = *state_chunk(wg, 0, tid);
     const float m2 = h[0], l2 = h[1];
     const float M = fmaxf(m2, m);
     const float m_use = (M == -INFINITY) ? 0.0f : M;
     const float a2 = __builtin_amdgcn_exp2f(m2 - m_use), a1 = __builtin_amdgcn_exp2f(m - m_use);
     const bool mine_empty = (l == 0.0f), other_empty = (l2 == 0.0f);
+#pragma unroll
     for (int db = 0; db < ATT_D / 32; ++db) {
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) {                          // eight values at a time: the callers have few registers to spare
-            const f32x4 x0 = v[1 + 4 * db + 2 * hh], x1 = v[2 + 4 * db + 2 * hh];
+            const f32x4 x0 = *state_chunk(wg, 1 + 4 * db + 2 * hh, tid), x1 = *state_chunk(wg, 2 + 4 * db + 2 * hh, tid);
 #pragma unroll
             for (int r = 0; r < 8; ++r) {
                 const float o2 = r < 4 ? x0[r] : x1[r - 4];
@@ -308,7 +314,7 @@ void attention_kernel(const AttnParams p) {
     const int t_end = one_split_each ? min(n_tiles, t_begin + ATT_SPLIT) : n_tiles;
     if (t_begin >= t_end) {                                       // uniform: no query of the block sees a key (of this split)
         if (one_split_each) {
-            *(global_f32x4 *)(my_state + tid * (ATT_THREAD_STATE / 4)) = f32x4{-INFINITY, 0.0f, 0.0f, 0.0f};   // an empty state: only m and l are looked at
+            *state_chunk(my_state, 0, tid) = f32x4{-INFINITY, 0.0f, 0.0f, 0.0f};   // an empty state: only m and l are looked at
         } else if (qrow < Lq) {
             uint16_t *optr = p.O + (int64_t)(q0 + qrow) * p.o_stride + (int64_t)head * ATT_D + lg * 64;
 #pragma unroll
@@ -419,8 +425,10 @@ void attention_kernel(const AttnParams p) {
         if (t > t_begin && (t & (ATT_SPLIT - 1)) == 0) {          // uniform: a split ends here (only when one workgroup walks them all)
             // No direct load is in flight at this point (the tile before waited for its successor), so ordinary
             // loads and stores, which the compiler counts itself, can be used.
-            if (folded) state_fold(my_state, tid, m, l, o);
-            state_store(my_state, tid, m, l, o);
+            int me = tid;
+            asm volatile("" : "+v"(me));                          // the addresses are formed here, not kept in registers across the tiles
+            if (folded) state_fold(my_state, me, m, l, o);
+            state_store(my_state, me, m, l, o);
             folded = true;
             m = -INFINITY;
             l = 0.0f;
@@ -433,11 +441,13 @@ void attention_kernel(const AttnParams p) {
         if (t + 1 < t_end) tile(std::integral_constant<int, 1>{}, t + 1);
     }
 
+    int me = tid;
+    asm volatile("" : "+v"(me));
     if (one_split_each) {                                         // the state as it is; attention_merge_kernel folds and divides
-        state_store(my_state, tid, m, l, o);
+        state_store(my_state, me, m, l, o);
         return;
     }
-    if (folded) state_fold(my_state, tid, m, l, o);
+    if (folded) state_fold(my_state, me, m, l, o);
     if (qrow < Lq) attention_store_output<F16>(p.O + (int64_t)(q0 + qrow) * p.o_stride + (int64_t)head * ATT_D + 4 * lg, l, o);
 }
 
