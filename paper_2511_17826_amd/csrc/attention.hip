@@ -118,20 +118,6 @@ __device__ __forceinline__ void state_store(f32x4 *wg, int tid, float m, float l
         for (int q = 0; q < 4; ++q) *state_chunk(wg, 1 + 4 * db + q, tid) = f32x4{o[db][4 * q], o[db][4 * q + 1], o[db][4 * q + 2], o[db][4 * q + 3]};
 }
 
-__device__ __forceinline__ void state_load(const f32x4 *wg, int tid, float &m, float &l, f32x16 (&o)[ATT_D / 32]) {
-    const f32x4 h = *state_chunk(wg, 0, tid);
-    m = h[0];
-    l = h[1];
-#pragma unroll
-    for (int db = 0; db < ATT_D / 32; ++db)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const f32x4 x = *state_chunk(wg, 1 + 4 * db + q, tid);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) o[db][4 * q + i] = x[i];
-        }
-}
-
 // (m, l, o) <- fold(the state stored at `wg`, (m, l, o))
 __device__ __forceinline__ void state_fold(const f32x4 *wg, int tid, float &m, float &l, f32x16 (&o)[ATT_D / 32]) {
     const f32x4 h = *state_chunk(wg, 0, tid);
@@ -453,13 +439,17 @@ void attention_kernel(const AttnParams p) {
 
 // Folds the states of the splits of each (query block, head group, sequence) triple in ascending order and writes the
 // output: the second kernel of a launch in which every split had its own workgroup.  Thread t of a workgroup here
-// stands for thread t of those workgroups (same query, same channels).
+// stands for thread t of those workgroups (same query); blockIdx.y picks one of the four blocks of 32 channels, of
+// which the thread folds its 16.  The loads do not depend on the fold, so the states of four splits are fetched at a
+// time (one trip to memory per four splits instead of several per split); the fold itself runs split by split, with
+// the operations of state_fold.
 template <bool F16>
 __global__ __launch_bounds__(256) void attention_merge_kernel(const AttnParams p) {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, lg = lane >> 5;
     const int bx = blockIdx.x % p.nq, t = blockIdx.x / p.nq;
+    const int db = blockIdx.y;
     const int qb = p.nq - 1 - bx, by = t % p.ny, seq = t / p.ny;
     const int base_item = (seq * p.ny + by) * p.nq + bx;
     const int R = p.rows;
@@ -470,18 +460,53 @@ __global__ __launch_bounds__(256) void attention_merge_kernel(const AttnParams p
     const int head = by * p.pack + slot / R;
     const int qrow = qb * R + slot % R;
     if (qrow >= Lq) return;
-    const f32x4 *states = reinterpret_cast<const f32x4 *>(p.states + (size_t)base_item * p.n_splits * ATT_STATE_FLOATS);
-    float m, l;
-    f32x16 o[ATT_D / 32];
-    state_load(states, tid, m, l, o);
-    if (l == 0.0f) {                                              // an empty first split carries no o
+    const f32x4 *states = reinterpret_cast<const f32x4 *>(uniform_pointer(
+        reinterpret_cast<const char *>(p.states + (size_t)base_item * p.n_splits * ATT_STATE_FLOATS)));
+    float m = -INFINITY, l = 0.0f;                                // the empty state
+    float o[16];
 #pragma unroll
-        for (int db = 0; db < ATT_D / 32; ++db)
+    for (int r = 0; r < 16; ++r) o[r] = 0.0f;
+    constexpr int AHEAD = 4;
+    for (int j0 = 0; j0 < p.n_splits; j0 += AHEAD) {
+        f32x4 h[AHEAD], x[AHEAD][4];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) o[db][r] = 0.0f;
+        for (int u = 0; u < AHEAD; ++u) {
+            const int j = min(j0 + u, p.n_splits - 1);            // past the end: the last one again, not used
+            const f32x4 *st = states + (size_t)j * (ATT_STATE_FLOATS / 4);
+            h[u] = *state_chunk(st, 0, tid);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) x[u][q] = *state_chunk(st, 1 + 4 * db + q, tid);
+        }
+#pragma unroll
+        for (int u = 0; u < AHEAD; ++u) {
+            const float m2 = h[u][0], l2 = h[u][1];
+            if (j0 + u >= p.n_splits || l2 == 0.0f) continue;     // an empty split (its o was never written) changes nothing
+            const float M = fmaxf(m2, m);
+            const float m_use = (M == -INFINITY) ? 0.0f : M;
+            const float a2 = __builtin_amdgcn_exp2f(m2 - m_use), a1 = __builtin_amdgcn_exp2f(m - m_use);
+            const bool mine_empty = (l == 0.0f);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float o2 = x[u][r >> 2][r & 3];
+                const float f = __fadd_rn(__fmul_rn(o2, a2), __fmul_rn(o[r], a1));
+                o[r] = mine_empty ? o2 : f;
+            }
+            const float lt = __fadd_rn(__fmul_rn(l2, a2), __fmul_rn(l, a1));
+            l = mine_empty ? l2 : lt;
+            m = mine_empty ? m2 : M;
+        }
     }
-    for (int j = 1; j < p.n_splits; ++j) state_fold(states + (size_t)j * (ATT_STATE_FLOATS / 4), tid, m, l, o);
-    attention_store_output<F16>(p.O + (int64_t)(q0 + qrow) * p.o_stride + (int64_t)head * ATT_D + 4 * lg, l, o);
+    uint16_t *optr = p.O + (int64_t)(q0 + qrow) * p.o_stride + (int64_t)head * ATT_D + 4 * lg + db * 32;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        float v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = (l > 0.0f) ? o[4 * q + i] / l : 0.0f;
+        att_u32x2 w;
+        w[0] = pack_16x2<F16>(v[0], v[1]);
+        w[1] = pack_16x2<F16>(v[2], v[3]);
+        *reinterpret_cast<att_u32x2 *>(optr + 8 * q) = w;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -866,7 +891,7 @@ static hipError_t launch_of(const AttnArgs &a, const AttnParams &p, const AttnPl
     if (a.causal) e = launch_with_lds(attention_kernel<true, F16>, done[2], grid, dim3(256), 4 * ATT_TILE_BYTES, p, s);
     else e = launch_with_lds(attention_kernel<false, F16>, done[3], grid, dim3(256), 4 * ATT_TILE_BYTES, p, s);
     if (e != hipSuccess || pl.n_splits == 1) return e;
-    hipLaunchKernelGGL(attention_merge_kernel<F16>, dim3((unsigned)pl.items), dim3(256), 0, s, p);
+    hipLaunchKernelGGL(attention_merge_kernel<F16>, dim3((unsigned)pl.items, ATT_D / 32), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 
