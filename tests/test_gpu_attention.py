@@ -290,6 +290,26 @@ def test_splits_one_workgroup_per_split_or_one_for_all_same_bits():
         assert np.array_equal(run(one)[0], O1[i]), i
 
 
+def test_ragged_batch_with_sequences_of_different_split_counts():
+    """One call with sequences of 1 to 4 splits (and one without keys): the workgroups of splits past a sequence's end
+    write the empty state, the fold skips it; every row equals the row of a call with that sequence alone."""
+    Hq, Hkv = 8, 2
+    lens_q = [1, 1, 70, 1, 1, 1]
+    lens_k = [100, 5000, 13000, 1, 0, 4097]
+    for causal in (True, False):
+        c = syn.attention_inputs(95, lens_q, lens_k, Hq=Hq, Hkv=Hkv, D=128)
+        O = run(c, causal)
+        for b in (0, 1, 2, 3, 5):
+            q0, q1, k0, k1 = c["cu_q"][b], c["cu_q"][b + 1], c["cu_k"][b], c["cu_k"][b + 1]
+            one = dict(c, Q=c["Q"][q0:q1], K=c["K"][k0:k1], V=c["V"][k0:k1], cu_q=np.array([0, q1 - q0], dtype=np.int32),
+                       cu_k=np.array([0, k1 - k0], dtype=np.int32))
+            assert np.array_equal(run(one, causal), O[q0:q1]), (causal, b)
+        assert not O[c["cu_q"][4]].any()                           # no key: zeros
+    chunk = dict(c, Q=c["Q"][2:72], K=c["K"][5100:18100], V=c["V"][5100:18100], cu_q=np.array([0, 70], dtype=np.int32),
+                 cu_k=np.array([0, 13000], dtype=np.int32))
+    check_against_oracle(O[2:72], chunk, False)                    # the 70 queries over four splits (no mask: the last loop's call)
+
+
 def test_understated_max_seqlen_k_leaves_keys_out_and_stays_in_bounds():
     c = syn.attention_inputs(94, [1], [6000], Hq=4, Hkv=2, D=128)
     Q, K, V = gu.dev_bf16(c["Q"]), gu.dev_bf16(c["K"]), gu.dev_bf16(c["V"])

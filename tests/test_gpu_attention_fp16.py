@@ -48,7 +48,7 @@ def run(c, causal=True, max_q=None):
     return gu.host_f16_bits(O)
 
 
-def check_against_oracle(O, c, causal):
+def check_against_oracle(O, c, causal, min_equal=0.97):
     Oo, _ = orc.attention(c["Q"], c["K"], c["V"], c["cu_q"], c["cu_k"], c["scale"], causal, fmt="fp16")
     want64, B = plain_attention_fp64(c, causal, fmt="fp16")
     g, o = h2f(O), h2f(Oo)
@@ -62,7 +62,7 @@ def check_against_oracle(O, c, causal):
     equal = np.count_nonzero(O == Oo) / O.size
     rms = float(np.sqrt(np.mean((g - o) ** 2)) / max(np.sqrt(np.mean(B ** 2)), 1e-30))
     print("fp16 attention vs oracle: %.4f of the outputs bit-equal, rms difference / rms B = 2^%.1f" % (equal, np.log2(max(rms, 1e-30))))
-    assert rms <= 2.0 ** -16 and equal >= 0.97, (rms, equal)
+    assert rms <= 2.0 ** -16 and equal >= min_equal, (rms, equal)
 
 
 @pytest.mark.parametrize("causal", [True, False])
@@ -142,6 +142,22 @@ def test_the_two_kernels_give_the_same_bits_and_the_format_matters():
     Q, K, V = gu.dev_bf16(c["Q"]), gu.dev_bf16(c["K"]), gu.dev_bf16(c["V"])
     Ob = gu.host_bf16_bits(tb.tbik_attention(Q, K, V, i32(c["cu_q"]), i32(c["cu_k"]), 700, c["scale"], True))
     assert not np.array_equal(Ob, outs[0][0])
+
+
+def test_splits_of_a_long_sequence():
+    """9000 keys = three splits: a decode step against the oracle, and rows of a prefill (splits walked by one workgroup
+    when the call is big, one workgroup each when it is small) against the same rows as decode steps."""
+    c = syn.attention_inputs(160, [16], [9000], Hq=8, Hkv=2, D=128, fmt="fp16")
+    # Over thousands of keys an output is a small mean whose fp32 sum differs from the oracle's in more of its low bits
+    # (the order inside a tile), and fp16's spacing is 8 times finer than bf16's: more roundings flip (measured: 94 %
+    # bit-equal at rms 2^-19), within the same bounds per output.
+    check_against_oracle(run(c), c, True, min_equal=0.9)
+    p1 = syn.attention_inputs(161, [8300], [8300], Hq=4, Hkv=2, D=128, fmt="fp16")
+    O1 = run(p1)
+    for i in (4095, 4096, 8192, 8299):
+        one = dict(p1, Q=p1["Q"][i:i + 1], K=p1["K"][:i + 1], V=p1["V"][:i + 1], cu_q=np.array([0, 1], dtype=np.int32),
+                   cu_k=np.array([0, i + 1], dtype=np.int32))
+        assert np.array_equal(run(one)[0], O1[i]), i
 
 
 def test_8b_shape_sampled_parity():
