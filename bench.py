@@ -180,6 +180,9 @@ def main():
 
     if args.extras:
         kernels.update(extras(tb, syn, torch, np, to_dev))
+    else:                                                   # three attention lines in every run; --extras has them all
+        kernels.update(attention_lines(tb, torch, ((4, 4096, torch.bfloat16),),
+                                       ((64, 4096, torch.bfloat16), (1, 32768, torch.bfloat16))))
 
     out = {
         "metric": "TBIK GEMM TFLOP/s (% bf16 MFMA peak), bit-identical across P in {1,2,4,8}",
@@ -219,6 +222,58 @@ def cpu_baseline(c, leaf, g, rows):
     return {"value": round(2.0 * rows * K * N / dt / 1e12, 5), "unit": "TFLOP/s", "cores": ncores, "kind": "oracle",
             "seconds": round(dt, 2),
             "sample": "first %d of 4096 rows of the same X against the full W (whole K, all N), fp32 scalar tree order" % rows}
+
+
+def attention_lines(tb, torch, prefill_shapes, decode_shapes):
+    """Fixed-tile attention at 8B-class heads (32 query heads over 8 key/value heads, head dimension 128): causal
+    prefills of B sequences of L tokens and decode steps of B sequences over L cached keys, beside torch's SDPA."""
+    res = {}
+    Hq, Hkv, D = 32, 8, 128
+    for B, L, dt in prefill_shapes:
+        att = tb.tbik_attention if dt == torch.bfloat16 else tb.tbik_attention_f16
+        tag = "" if dt == torch.bfloat16 else "fp16_"
+        Q = torch.randn(B * L, Hq, D, device="cuda:0").to(dt)
+        K = torch.randn(B * L, Hkv, D, device="cuda:0").to(dt)
+        Vv = torch.randn(B * L, Hkv, D, device="cuda:0").to(dt)
+        cu = torch.arange(0, B + 1, dtype=torch.int32, device="cuda:0") * L
+        O = torch.empty_like(Q)
+        ws = torch.empty(max(1, tb.attention_workspace_bytes(B, L, L, Hq, Hkv)), dtype=torch.uint8, device="cuda:0")
+        f = lambda: att(Q, K, Vv, cu, cu, L, D ** -0.5, True, out=O, max_seqlen_k=L, workspace=ws)
+        f(); f()
+        t = min(time_region(f, 10, torch) for _ in range(3))
+        q4, k4, v4 = (a.view(B, L, -1, D).transpose(1, 2) for a in (Q, K, Vv))
+        b = lambda: torch.nn.functional.scaled_dot_product_attention(q4, k4, v4, is_causal=True, enable_gqa=True)
+        b(); b()
+        tb_ms = min(time_region(b, 10, torch) for _ in range(3))
+        flops = 4.0 * B * L * L * D * Hq / 2                     # causal: half of the score matrix
+        res["attention_%sprefill_%dx%d" % (tag, B, L)] = {"ms": round(t, 4), "tflops": round(flops / (t * 1e-3) / 1e12, 1),
+                                                   "frac_mfma": round(flops / (t * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                                                   "baseline_ms": round(tb_ms, 4)}
+        del Q, K, Vv, O, q4, k4, v4
+    for B, L, dt in decode_shapes:
+        att = tb.tbik_attention if dt == torch.bfloat16 else tb.tbik_attention_f16
+        tag = "" if dt == torch.bfloat16 else "fp16_"
+        Q = torch.randn(B, Hq, D, device="cuda:0").to(dt)
+        K = torch.randn(B * L, Hkv, D, device="cuda:0").to(dt)
+        Vv = torch.randn(B * L, Hkv, D, device="cuda:0").to(dt)
+        cuq = torch.arange(0, B + 1, dtype=torch.int32, device="cuda:0")
+        cuk = cuq * L
+        O = torch.empty_like(Q)
+        ws = torch.empty(max(1, tb.attention_workspace_bytes(B, 1, L, Hq, Hkv)), dtype=torch.uint8, device="cuda:0")
+        f = lambda: att(Q, K, Vv, cuq, cuk, 1, D ** -0.5, True, out=O, max_seqlen_k=L, workspace=ws)
+        f(); f()
+        t = min(time_region(f, 10, torch) for _ in range(3))
+        q4 = Q.view(B, 1, Hq, D).transpose(1, 2)
+        k4, v4 = (a.view(B, L, Hkv, D).transpose(1, 2) for a in (K, Vv))
+        b = lambda: torch.nn.functional.scaled_dot_product_attention(q4, k4, v4, is_causal=False, enable_gqa=True)
+        b(); b()
+        tb_ms = min(time_region(b, 10, torch) for _ in range(3))
+        byts = 2.0 * B * L * Hkv * D * 2                         # K and V read once
+        res["attention_%sdecode_%dx%d" % (tag, B, L)] = {"ms": round(t, 4), "GBps_kv": round(byts / (t * 1e-3) / 1e9, 1),
+                                                  "frac_hbm": round(byts / (t * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                                                  "baseline_ms": round(tb_ms, 4)}
+        del Q, K, Vv, O, q4, k4, v4
+    return res
 
 
 def extras(tb, syn, torch, np, to_dev):
@@ -365,53 +420,10 @@ def extras(tb, syn, torch, np, to_dev):
                                                "frac_hbm": round(byts / (t * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                                                "three_calls_ms": round(t3, 4)}
         del parts
-    # fixed-tile attention at 8B-class heads (32 query heads over 8 key/value heads, head dimension 128)
-    Hq, Hkv, D = 32, 8, 128
-    for B, L, dt in ((4, 4096, torch.bfloat16), (1, 16384, torch.bfloat16), (4, 4096, torch.float16)):
-        att = tb.tbik_attention if dt == torch.bfloat16 else tb.tbik_attention_f16
-        tag = "" if dt == torch.bfloat16 else "fp16_"
-        Q = torch.randn(B * L, Hq, D, device="cuda:0").to(dt)
-        K = torch.randn(B * L, Hkv, D, device="cuda:0").to(dt)
-        Vv = torch.randn(B * L, Hkv, D, device="cuda:0").to(dt)
-        cu = torch.arange(0, B + 1, dtype=torch.int32, device="cuda:0") * L
-        O = torch.empty_like(Q)
-        ws = torch.empty(max(1, tb.attention_workspace_bytes(B, L, L, Hq, Hkv)), dtype=torch.uint8, device="cuda:0")
-        f = lambda: att(Q, K, Vv, cu, cu, L, D ** -0.5, True, out=O, max_seqlen_k=L, workspace=ws)
-        f(); f()
-        t = min(time_region(f, 10, torch) for _ in range(3))
-        q4, k4, v4 = (a.view(B, L, -1, D).transpose(1, 2) for a in (Q, K, Vv))
-        b = lambda: torch.nn.functional.scaled_dot_product_attention(q4, k4, v4, is_causal=True, enable_gqa=True)
-        b(); b()
-        tb_ms = min(time_region(b, 10, torch) for _ in range(3))
-        flops = 4.0 * B * L * L * D * Hq / 2                     # causal: half of the score matrix
-        res["attention_%sprefill_%dx%d" % (tag, B, L)] = {"ms": round(t, 4), "tflops": round(flops / (t * 1e-3) / 1e12, 1),
-                                                   "frac_mfma": round(flops / (t * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
-                                                   "baseline_ms": round(tb_ms, 4)}
-        del Q, K, Vv, O, q4, k4, v4
-    for B, L, dt in ((64, 4096, torch.bfloat16), (256, 2048, torch.bfloat16), (64, 4096, torch.float16),
-                     (1, 32768, torch.bfloat16), (4, 32768, torch.bfloat16), (1, 131072, torch.bfloat16)):
-        att = tb.tbik_attention if dt == torch.bfloat16 else tb.tbik_attention_f16
-        tag = "" if dt == torch.bfloat16 else "fp16_"
-        Q = torch.randn(B, Hq, D, device="cuda:0").to(dt)
-        K = torch.randn(B * L, Hkv, D, device="cuda:0").to(dt)
-        Vv = torch.randn(B * L, Hkv, D, device="cuda:0").to(dt)
-        cuq = torch.arange(0, B + 1, dtype=torch.int32, device="cuda:0")
-        cuk = cuq * L
-        O = torch.empty_like(Q)
-        ws = torch.empty(max(1, tb.attention_workspace_bytes(B, 1, L, Hq, Hkv)), dtype=torch.uint8, device="cuda:0")
-        f = lambda: att(Q, K, Vv, cuq, cuk, 1, D ** -0.5, True, out=O, max_seqlen_k=L, workspace=ws)
-        f(); f()
-        t = min(time_region(f, 10, torch) for _ in range(3))
-        q4 = Q.view(B, 1, Hq, D).transpose(1, 2)
-        k4, v4 = (a.view(B, L, Hkv, D).transpose(1, 2) for a in (K, Vv))
-        b = lambda: torch.nn.functional.scaled_dot_product_attention(q4, k4, v4, is_causal=False, enable_gqa=True)
-        b(); b()
-        tb_ms = min(time_region(b, 10, torch) for _ in range(3))
-        byts = 2.0 * B * L * Hkv * D * 2                         # K and V read once
-        res["attention_%sdecode_%dx%d" % (tag, B, L)] = {"ms": round(t, 4), "GBps_kv": round(byts / (t * 1e-3) / 1e9, 1),
-                                                  "frac_hbm": round(byts / (t * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
-                                                  "baseline_ms": round(tb_ms, 4)}
-        del Q, K, Vv, O, q4, k4, v4
+    res.update(attention_lines(tb, torch,
+                               ((4, 4096, torch.bfloat16), (1, 16384, torch.bfloat16), (4, 4096, torch.float16)),
+                               ((64, 4096, torch.bfloat16), (256, 2048, torch.bfloat16), (64, 4096, torch.float16),
+                                (1, 32768, torch.bfloat16), (4, 32768, torch.bfloat16), (1, 131072, torch.bfloat16))))
     V = 151936
     for M in (1, 64, 512):
         x = torch.from_numpy(syn.logits_f32(M, V)).to("cuda:0")
