@@ -56,7 +56,8 @@ def test_hot_path_in_a_hip_graph_replays_bit_identically():
 
 
 def test_fp32_gemm_fp16_tail_and_attention_in_a_hip_graph():
-    """The later entry points (fp32 GEMM with its K split, fp16 fused tail, fp16 attention) under capture and replay."""
+    """The later entry points (fp32 GEMM with its K split, fp16 fused tail, fp16 attention, attention over several splits
+    of the key axis with its workspace) under capture and replay."""
     dev = "cuda:0"
     M, K, N = 70, 2048, 512
     Xf, Wf = syn.gemm_random_f32(31, M, K, N)
@@ -72,8 +73,15 @@ def test_fp32_gemm_fp16_tail_and_attention_in_a_hip_graph():
     cu_q = torch.from_numpy(a["cu_q"]).to(dev)
     cu_k = torch.from_numpy(a["cu_k"]).to(dev)
     O = torch.empty_like(Q)
+    # a decode step over three splits of the key axis (one workgroup per split, then the fold kernel; states in `ws_a`)
+    al = syn.attention_inputs(33, [1], [9000], Hq=8, Hkv=2, D=128)
+    Ql, Kl, Vl = gu.dev_bf16(al["Q"]), gu.dev_bf16(al["K"]), gu.dev_bf16(al["V"])
+    cu_ql, cu_kl = torch.from_numpy(al["cu_q"]).to(dev), torch.from_numpy(al["cu_k"]).to(dev)
+    Ol = torch.empty_like(Ql)
+    ws_a = torch.empty(tb.attention_workspace_bytes(1, 1, 9000, 8, 2), dtype=torch.uint8, device=dev)
 
     def one_pass():
+        tb.tbik_attention(Ql, Kl, Vl, cu_ql, cu_kl, 1, al["scale"], True, out=Ol, max_seqlen_k=9000, workspace=ws_a)
         tb.tbik_gemm_f32(X32, W32, 128, 1, out=y32, workspace=ws)
         tb.tbik_gemm_shard_partials_f32(X32, W32, 128, 1, 4, out=parts, workspace=ws)
         tb.tbik_combine_residual_rmsnorm_f16(parts, res, wn, 1e-6, hidden=hid, normed=nrm)
@@ -81,7 +89,7 @@ def test_fp32_gemm_fp16_tail_and_attention_in_a_hip_graph():
 
     one_pass()
     torch.cuda.synchronize()
-    outs = (y32, parts, hid, nrm, O)
+    outs = (y32, parts, hid, nrm, O, Ol)
     want = [t.clone() for t in outs]
     graph = torch.cuda.CUDAGraph()
     side = torch.cuda.Stream()
@@ -89,7 +97,7 @@ def test_fp32_gemm_fp16_tail_and_attention_in_a_hip_graph():
         with torch.cuda.graph(graph, stream=side):
             one_pass()
     for rep in range(3):
-        for t in outs:
+        for t in outs + (ws_a,):
             t.zero_()
         torch.cuda.synchronize()
         graph.replay()
