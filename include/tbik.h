@@ -185,7 +185,10 @@ int tbik_row_reduce(const void *x, tbik_dtype x_dtype, void *out, tbik_rowop op,
  *          call is cut into workgroups, never the bits; values above total_k are taken as total_k
  *          total_q, total_k: tokens in Q/O and in K/V
  *   workspace   at least tbik_attention_workspace_bytes(batch, max_seqlen_q, max_seqlen_k, heads_q, heads_kv) bytes,
- *          256-byte aligned; that is 0 (and the pointer may be NULL) when max_seqlen_k <= 4096
+ *          256-byte aligned; that is 0 (and the pointer may be NULL) when max_seqlen_k <= 4096, else 68 KiB per
+ *          128 rows of (query, head) and -- in calls of fewer than 512 such blocks -- per split of max_seqlen_k:
+ *          about twice the bytes of Q for a long prefill.  Contents on entry do not matter; calls that share a
+ *          workspace must not overlap in time
  *   head_dim 128 (other values: TBIK_ERR_UNSUPPORTED); heads_q a multiple of heads_kv; strides in elements, multiples
  *   of 8, at least heads * head_dim, below 2^24; pointers 16-byte aligned.  O must not overlap Q, K or V.
  * Errors: NULL, SHAPE, UNSUPPORTED, ALIGN, WORKSPACE, HIP.
