@@ -66,7 +66,6 @@ struct AttnParams {
     int rows;                                         // queries per head and workgroup: 128 / pack
     float c;                                          // scale * log2(e)
     int nq, ny, nz;                                   // query blocks, head groups, sequences: the work items of the launch
-    int xcd_chunk;                                    // items per XCD when they divide evenly by 8, else 0
     int n_splits;                                     // 1: an item walks all key tiles (folding its splits as it goes);
                                                       // > 1: an item is one split of those, its state goes to `states`
     int max_tiles;                                    // key tiles of a sequence of max_seqlen_k keys: no workgroup walks further
@@ -74,21 +73,25 @@ struct AttnParams {
                                                       // n_splits > 1: [item][split] states for attention_merge_kernel
 };
 
-// Work item of this workgroup.  Consecutive workgroups go round the 8 XCDs; the items are numbered with the query
-// block fastest, then the head group, then the sequence, and XCD c takes the c-th eighth of that list, so that the
-// workgroups an XCD runs at a time are query blocks of the same heads and sequence and find its keys and values in
-// that XCD's L2 (dealt round-robin instead, every XCD walks every head's keys: 3.4 times the algorithmic fetch).
-__device__ __forceinline__ void attention_work_item(const AttnParams &p, int &qb, int &by, int &seq, int &split, int &base) {
-    int id = blockIdx.x;
-    if (p.xcd_chunk) id = (id & 7) * p.xcd_chunk + (id >> 3);
-    const int bx = id % p.nq;
-    int t = id / p.nq;
+// Work item of this workgroup; false if it has none (the launch is padded).  Consecutive workgroups go round the 8
+// XCDs.  The items are numbered with the query block fastest, then the split, the head group and the sequence; a run
+// of nq items (the query blocks of one head group, sequence and split) reads the same keys and values, and run u goes
+// to XCD u % 8 as a whole, so that the workgroups an XCD runs at a time find their keys in that XCD's L2 (consecutive
+// query blocks on different XCDs: every XCD walks every head's keys, 3.4 times the algorithmic fetch), while the
+// head groups of one long sequence among short ones are spread over all XCDs (contiguous eighths of the item list
+// put a lone prefill among decode steps on one XCD: 8 times slower).
+__device__ __forceinline__ bool attention_work_item(const AttnParams &p, int &qb, int &by, int &seq, int &split, int &base) {
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    const int run = xcd + 8 * (j / p.nq);
+    const int bx = j % p.nq;
+    int t = run;
     split = t % p.n_splits;
     t /= p.n_splits;
     qb = p.nq - 1 - bx;                               // long (late) blocks first
     by = t % p.ny;
     seq = t / p.ny;
     base = (seq * p.ny + by) * p.nq + bx;             // number of the (query block, head group, sequence) triple
+    return seq < p.nz;
 }
 
 // The softmax state of one split of the keys, (m, l, o) per thread, and the fold of two of them (the accumulated one
@@ -188,7 +191,7 @@ void attention_kernel(const AttnParams p) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 31, lg = lane >> 5;
     int qb, by, seq, split, base_item;
-    attention_work_item(p, qb, by, seq, split, base_item);
+    if (!attention_work_item(p, qb, by, seq, split, base_item)) return;     // uniform
     const int R = p.rows;
     const bool one_split_each = p.n_splits > 1;                   // uniform: this workgroup computes one split's state
     f32x4 *const my_state = reinterpret_cast<f32x4 *>(const_cast<char *>(uniform_pointer(           // the workgroup's, in scalar registers
@@ -538,7 +541,7 @@ void attention_pingpong_kernel(const AttnParams p) {
     const int li = lane & 31, lg = lane >> 5;
     int qb, by, seq;
     int split_unused, base_unused;
-    attention_work_item(p, qb, by, seq, split_unused, base_unused);      // launched with n_splits == 1 only
+    if (!attention_work_item(p, qb, by, seq, split_unused, base_unused)) return;      // uniform; launched with n_splits == 1 only
     const int R = 2 * p.rows;                                     // queries per head and workgroup: 256 / pack
 
     const int q0 = clampi(p.cu_q[seq], 0, p.total_q), q1 = clampi(p.cu_q[seq + 1], q0, p.total_q);
@@ -881,7 +884,8 @@ size_t attention_workspace(int batch, int max_seqlen_q, int max_seqlen_k, int he
 template <bool F16>
 static hipError_t launch_of(const AttnArgs &a, const AttnParams &p, const AttnPlan &pl, hipStream_t s) {
     static std::atomic<unsigned> done[4] = {{0}, {0}, {0}, {0}};     // one set per operand format
-    const dim3 grid((unsigned)(pl.items * pl.n_splits));
+    const int64_t runs = pl.items / pl.q_blocks * pl.n_splits;   // (split, head group, sequence) triples, dealt to the 8 XCDs in turn
+    const dim3 grid((unsigned)((runs + 7) / 8 * 8 * pl.q_blocks));
     hipError_t e;
     if (pl.pingpong) {
         constexpr int RING = 4;
@@ -898,7 +902,7 @@ static hipError_t launch_of(const AttnArgs &a, const AttnParams &p, const AttnPl
 hipError_t launch_attention(const AttnArgs &a, hipStream_t s) {
     if (a.batch <= 0 || a.max_seqlen_q <= 0 || a.total_q <= 0) return hipSuccess;
     const AttnPlan pl = plan_attention(a.batch, a.max_seqlen_q, a.max_seqlen_k, a.heads_q, a.heads_kv, g_attention_variant.load());
-    if (pl.items * pl.n_splits > 0x7fffffff) return hipErrorInvalidValue;
+    if (pl.items * pl.n_splits > 0x7fffffff - 8 * pl.q_blocks) return hipErrorInvalidValue;   // the launch is padded to 8 runs
     AttnParams p;
     p.Q = a.Q; p.K = a.K; p.V = a.V; p.O = a.O;
     p.cu_q = a.cu_q; p.cu_k = a.cu_k;
@@ -914,8 +918,6 @@ hipError_t launch_attention(const AttnArgs &a, hipStream_t s) {
     p.n_splits = pl.n_splits;
     p.max_tiles = pl.splits_max * ATT_SPLIT;
     p.states = reinterpret_cast<float *>(a.workspace);
-    const int64_t launched = pl.items * pl.n_splits;
-    p.xcd_chunk = (launched % 8 == 0 && pl.q_blocks > 1) ? (int)(launched / 8) : 0;   // one query block: nothing is shared between items
     return a.dtype == TBIK_F16 ? launch_of<true>(a, p, pl, s) : launch_of<false>(a, p, pl, s);
 }
 
