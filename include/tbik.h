@@ -180,14 +180,15 @@ int tbik_row_reduce(const void *x, tbik_dtype x_dtype, void *out, tbik_rowop op,
  *   K, V   device, bf16, same layout with heads_kv heads; query head h reads key/value head h / (heads_q / heads_kv)
  *   cu_seqlens_q, cu_seqlens_k   DEVICE, int32 [batch + 1], non-decreasing prefix sums of the sequences' query and key
  *          counts; values are clamped to [0, total_q] / [0, total_k] inside the kernel
- *   max_seqlen_q   at least the largest Lq (with a smaller value some queries past it are left unwritten);
+ *   max_seqlen_q   at least the largest Lq: batch x max_seqlen_q bounds the tokens the launch and the workspace are sized
+ *          for (with a smaller value the last queries of the call may be left unwritten); never the bits;
  *   max_seqlen_k   at least the largest Lk (keys of a sequence past it are left out); decides the workspace and how the
  *          call is cut into workgroups, never the bits; values above total_k are taken as total_k
  *          total_q, total_k: tokens in Q/O and in K/V
  *   workspace   at least tbik_attention_workspace_bytes(batch, max_seqlen_q, max_seqlen_k, heads_q, heads_kv) bytes,
  *          256-byte aligned; that is 0 (and the pointer may be NULL) when max_seqlen_k <= 4096, else 68 KiB per
- *          128 rows of (query, head) and -- in calls of fewer than 512 such blocks -- per split of max_seqlen_k:
- *          about twice the bytes of Q for a long prefill.  Contents on entry do not matter; calls that share a
+ *          128 rows of (query, head) of batch x max_seqlen_q tokens and -- below 512 such blocks -- per split of
+ *          max_seqlen_k: about twice the bytes of Q for a long prefill.  Contents on entry do not matter; calls that share a
  *          workspace must not overlap in time
  *   head_dim 128 (other values: TBIK_ERR_UNSUPPORTED); heads_q a multiple of heads_kv; strides in elements, multiples
  *   of 8, at least heads * head_dim, below 2^24; pointers 16-byte aligned.  O must not overlap Q, K or V.

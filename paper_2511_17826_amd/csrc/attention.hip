@@ -32,7 +32,9 @@
 //     O^T (channels x queries) = V^T (A operand, transposing LDS read) x P^T (B operand = the S^T registers, rounded to 16 bits)
 // The MFMA's k-slot (g, t) of step s stands for key 32 kb + 16 h + 8 (t / 4) + 4 g + t % 4 (kb = s / 2, h = s % 2): the
 // order in which the result layout of S^T hands the keys to a lane; V^T is fetched in the same order.
+#include <algorithm>
 #include <atomic>
+#include <cstdint>
 #include <type_traits>
 
 #include "tbik_device.hpp"
@@ -65,7 +67,9 @@ struct AttnParams {
     int pack;                                         // query heads per workgroup (group or 1)
     int rows;                                         // queries per head and workgroup: 128 / pack
     float c;                                          // scale * log2(e)
-    int nq, ny, nz;                                   // query blocks, head groups, sequences: the work items of the launch
+    int ny, nz;                                       // head groups, sequences
+    int nb;                                           // bound on the query blocks of the call: block ids 0 .. nb - 1 (see attention_work_item)
+    int chunk, nchunks;                               // block ids are dealt to the XCDs in chunks of this many
     int n_splits;                                     // 1: an item walks all key tiles (folding its splits as it goes);
                                                       // > 1: an item is one split of those, its state goes to `states`
     int max_tiles;                                    // key tiles of a sequence of max_seqlen_k keys: no workgroup walks further
@@ -73,25 +77,49 @@ struct AttnParams {
                                                       // n_splits > 1: [item][split] states for attention_merge_kernel
 };
 
-// Work item of this workgroup; false if it has none (the launch is padded).  Consecutive workgroups go round the 8
-// XCDs.  The items are numbered with the query block fastest, then the split, the head group and the sequence; a run
-// of nq items (the query blocks of one head group, sequence and split) reads the same keys and values, and run u goes
-// to XCD u % 8 as a whole, so that the workgroups an XCD runs at a time find their keys in that XCD's L2 (consecutive
-// query blocks on different XCDs: every XCD walks every head's keys, 3.4 times the algorithmic fetch), while the
-// head groups of one long sequence among short ones are spread over all XCDs (contiguous eighths of the item list
-// put a lone prefill among decode steps on one XCD: 8 times slower).
-__device__ __forceinline__ bool attention_work_item(const AttnParams &p, int &qb, int &by, int &seq, int &split, int &base) {
+__device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+// Query blocks are numbered over the whole call without a table: sequence b owns the ids G(b) .. G(b) + blocks(b) - 1
+// with G(b) = cu_q[b] / R + b (R queries per block; G(b + 1) - G(b) >= ceil(Lq_b / R), so the ranges do not overlap,
+// and all ids are below total_q / R + batch).  A few ids between the ranges belong to nobody.  The host needs no
+// sequence length for this (the launch is sized from total_q), and a call of one long chunk and many decode steps
+// launches about as many workgroups as it has blocks -- not batch x blocks of the longest.
+// Returns the sequence of block id g: the largest b with G(b) <= g, by a 64-way search (one or two rounds for any
+// realistic batch); the same value in every lane.  Offsets that do not ascend give some sequence in range, no more.
+__device__ __forceinline__ int sequence_of_block(const AttnParams &p, int R, int g, int lane) {
+    int lo = 0, n = p.nz;
+    while (n > 1) {
+        const int step = (n + 63) >> 6;
+        const int b = lo + lane * step;
+        const bool ok = b < lo + n && clampi(p.cu_q[min(b, p.nz - 1)], 0, p.total_q) / R + b <= g;
+        const int k = max(__builtin_popcountll(__builtin_amdgcn_ballot_w64(ok)) - 1, 0);
+        n = min(step, lo + n - (lo + k * step));
+        lo += k * step;
+    }
+    return __builtin_amdgcn_readfirstlane(lo);
+}
+
+// Work item of this workgroup; false if it has none.  Consecutive workgroups go round the 8 XCDs.  A run is a chunk
+// of consecutive block ids of one head group and split -- mostly query blocks of one sequence, which read the same
+// keys and values -- and run u goes to XCD u % 8 as a whole, so that the workgroups an XCD runs at a time find their
+// keys in that XCD's L2 (consecutive query blocks on different XCDs: every XCD walks every head's keys, 3.4 times the
+// algorithmic fetch); with a multiple of 8 head groups a head group stays on one XCD.  Late chunks, and in a chunk late
+// blocks, come first: under a causal mask they are the long ones.
+__device__ __forceinline__ bool attention_work_item(const AttnParams &p, int R, int lane, int &qb, int &by, int &seq, int &split, int &base) {
     const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-    const int run = xcd + 8 * (j / p.nq);
-    const int bx = j % p.nq;
-    int t = run;
+    const int bx = j % p.chunk;
+    int t = xcd + 8 * (j / p.chunk);
     split = t % p.n_splits;
     t /= p.n_splits;
-    qb = p.nq - 1 - bx;                               // long (late) blocks first
     by = t % p.ny;
-    seq = t / p.ny;
-    base = (seq * p.ny + by) * p.nq + bx;             // number of the (query block, head group, sequence) triple
-    return seq < p.nz;
+    const int ch = p.nchunks - 1 - t / p.ny;
+    if (ch < 0) return false;                         // the launch is padded to a multiple of 8 runs
+    const int g = ch * p.chunk + (p.chunk - 1 - bx);
+    if (g >= p.nb) return false;
+    seq = sequence_of_block(p, R, g, lane);
+    qb = g - (clampi(p.cu_q[seq], 0, p.total_q) / R + seq);
+    base = g * p.ny + by;                             // number of the (block id, head group) pair
+    return true;
 }
 
 // The softmax state of one split of the keys, (m, l, o) per thread, and the fold of two of them (the accumulated one
@@ -165,8 +193,6 @@ __device__ __forceinline__ void attention_store_output(uint16_t *optr, float l, 
         }
 }
 
-__device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
-
 // A lane and its partner lane ^ 32 hold the two halves of one query's keys.  v_permlane32_swap exchanges the upper
 // half of its first operand with the lower half of its second: from (v, v) it makes (lower half's values, upper
 // half's values) in every lane, i.e. {mine, partner's} in some order -- enough for a maximum or a sum of the two.
@@ -191,8 +217,8 @@ void attention_kernel(const AttnParams p) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 31, lg = lane >> 5;
     int qb, by, seq, split, base_item;
-    if (!attention_work_item(p, qb, by, seq, split, base_item)) return;     // uniform
     const int R = p.rows;
+    if (!attention_work_item(p, R, lane, qb, by, seq, split, base_item)) return;     // uniform
     const bool one_split_each = p.n_splits > 1;                   // uniform: this workgroup computes one split's state
     f32x4 *const my_state = reinterpret_cast<f32x4 *>(const_cast<char *>(uniform_pointer(           // the workgroup's, in scalar registers
         reinterpret_cast<const char *>(p.states + ((size_t)base_item * p.n_splits + split) * ATT_STATE_FLOATS))));
@@ -201,7 +227,7 @@ void attention_kernel(const AttnParams p) {
     const int q0 = clampi(p.cu_q[seq], 0, p.total_q), q1 = clampi(p.cu_q[seq + 1], q0, p.total_q);
     const int k0 = clampi(p.cu_k[seq], 0, p.total_k), k1 = clampi(p.cu_k[seq + 1], k0, p.total_k);
     const int Lq = q1 - q0, Lk = k1 - k0;
-    if (qb * R >= Lq) return;                                     // uniform: nothing of this sequence in the block
+    if (qb < 0 || qb * R >= Lq) return;                                     // uniform: nothing of this sequence in the block
     const int shift = Lk - Lq;                                    // the queries are the last Lq positions
     const int slot = wave * 32 + li;
     const int head = by * p.pack + slot / R;
@@ -451,14 +477,15 @@ __global__ __launch_bounds__(256) void attention_merge_kernel(const AttnParams p
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, lg = lane >> 5;
-    const int bx = blockIdx.x % p.nq, t = blockIdx.x / p.nq;
     const int db = blockIdx.y;
-    const int qb = p.nq - 1 - bx, by = t % p.ny, seq = t / p.ny;
-    const int base_item = (seq * p.ny + by) * p.nq + bx;
+    const int by = blockIdx.x % p.ny, g = blockIdx.x / p.ny;     // g: the block id, as in attention_work_item
     const int R = p.rows;
+    const int seq = sequence_of_block(p, R, g, lane);
+    const int qb = g - (clampi(p.cu_q[seq], 0, p.total_q) / R + seq);
+    const int base_item = blockIdx.x;
     const int q0 = clampi(p.cu_q[seq], 0, p.total_q), q1 = clampi(p.cu_q[seq + 1], q0, p.total_q);
     const int Lq = q1 - q0;
-    if (qb * R >= Lq) return;
+    if (qb < 0 || qb * R >= Lq) return;
     const int slot = wave * 32 + li;
     const int head = by * p.pack + slot / R;
     const int qrow = qb * R + slot % R;
@@ -541,13 +568,13 @@ void attention_pingpong_kernel(const AttnParams p) {
     const int li = lane & 31, lg = lane >> 5;
     int qb, by, seq;
     int split_unused, base_unused;
-    if (!attention_work_item(p, qb, by, seq, split_unused, base_unused)) return;      // uniform; launched with n_splits == 1 only
     const int R = 2 * p.rows;                                     // queries per head and workgroup: 256 / pack
+    if (!attention_work_item(p, R, lane, qb, by, seq, split_unused, base_unused)) return;      // uniform; launched with n_splits == 1 only
 
     const int q0 = clampi(p.cu_q[seq], 0, p.total_q), q1 = clampi(p.cu_q[seq + 1], q0, p.total_q);
     const int k0 = clampi(p.cu_k[seq], 0, p.total_k), k1 = clampi(p.cu_k[seq + 1], k0, p.total_k);
     const int Lq = q1 - q0, Lk = k1 - k0;
-    if (qb * R >= Lq) return;                                     // uniform: nothing of this sequence in the block
+    if (qb < 0 || qb * R >= Lq) return;                                     // uniform: nothing of this sequence in the block
     const int shift = Lk - Lq;
     const int slot = wave * 32 + li;
     const int head = by * p.pack + slot / R;
@@ -849,43 +876,57 @@ static hipError_t launch_with_lds(Kernel kernel, std::atomic<unsigned> &done, di
 struct AttnPlan {
     int pack, rows;          // query heads per workgroup, queries per head and workgroup
     bool pingpong;
-    int64_t q_blocks, items; // items: (query block, head group, sequence) triples
+    int ny;                  // head groups
+    int64_t nb;              // bound on the query blocks of the call (block ids 0 .. nb - 1)
+    int64_t items;           // (block id, head group) pairs: a bound on the workgroups that find work, per split
+    int chunk;               // block ids per run (runs are dealt to the XCDs in turn)
+    int64_t nchunks;
     int splits_max;          // splits a sequence of max_seqlen_k keys has
     int n_splits;            // 1: every workgroup walks all its tiles; else one workgroup per split, then a merge kernel
     size_t state_bytes;      // workspace: fold scratch (one state per item) or the states of all splits
 };
 
-static AttnPlan plan_attention(int batch, int max_seqlen_q, int max_seqlen_k, int heads_q, int heads_kv, int variant) {
+// total_q: tokens in Q (or a bound on them); workspace_bytes: what the caller brought (SIZE_MAX: as much as is wanted).
+static AttnPlan plan_attention(int batch, int64_t total_q, int max_seqlen_k, int heads_q, int heads_kv, int variant, size_t workspace_bytes) {
     AttnPlan pl;
     const int group = heads_q / heads_kv;
     pl.pack = (group <= ATT_BQ && (group & (group - 1)) == 0) ? group : 1;
     pl.rows = ATT_BQ / pl.pack;
+    pl.ny = heads_q / pl.pack;
     pl.splits_max = max_seqlen_k > 0 ? (max_seqlen_k + ATT_SPLIT * ATT_KV - 1) / (ATT_SPLIT * ATT_KV) : 1;
     // The kernel whose wavefront groups take turns keeps one state per workgroup in two groups of wavefronts and has no
     // fold: it serves sequences of one split (where it is a differently scheduled cross-check of the other kernel).
     pl.pingpong = (variant == 2) && pl.splits_max == 1;
     const int rows = pl.pingpong ? 2 * pl.rows : pl.rows;
-    pl.q_blocks = ((int64_t)max_seqlen_q + rows - 1) / rows;
-    pl.items = pl.q_blocks * (heads_q / pl.pack) * batch;
-    // Few items and long sequences (decode steps on long contexts): one workgroup per split, all at once, then the
-    // fold in a second kernel.  Same bits as one workgroup walking the splits, so the choice is free; below two
-    // workgroups per compute unit the parallel form wins.
-    pl.n_splits = (pl.splits_max > 1 && pl.items < 512) ? pl.splits_max : 1;
-    pl.state_bytes = pl.splits_max > 1 ? (size_t)pl.items * pl.n_splits * ATT_STATE_FLOATS * sizeof(float) : 0;
+    pl.nb = total_q / rows + batch;
+    pl.items = pl.nb * pl.ny;
+    const size_t state = ATT_STATE_FLOATS * sizeof(float);
+    // Few items and long sequences (decode steps on long contexts, alone or beside a chunk of a prefill): one
+    // workgroup per split, all at once, then the fold in a second kernel.  Same bits as one workgroup walking the
+    // splits, so the choice is free; below two workgroups per compute unit the parallel form wins -- if the caller's
+    // workspace holds its states (sized from a bound on total_q it may not; walking needs less and always fits).
+    pl.n_splits = (pl.splits_max > 1 && pl.items < 512 && (size_t)pl.items * pl.splits_max * state <= workspace_bytes) ? pl.splits_max : 1;
+    pl.state_bytes = pl.splits_max > 1 ? (size_t)pl.items * pl.n_splits * state : 0;
+    // Enough runs to keep every XCD busy (64 or more where the call has that many blocks), chunks of at most 128 blocks.
+    const int64_t spread = (pl.items * pl.n_splits + 63) / 64;
+    pl.chunk = (int)std::max<int64_t>(1, std::min<int64_t>(spread, std::min<int64_t>(128, pl.nb)));   // no chunk longer than the call: its idle
+                                                                  // workgroups would pair the busy ones up on half the compute units
+    pl.nchunks = (pl.nb + pl.chunk - 1) / pl.chunk;
     return pl;
 }
 
+// From the arguments a caller has before the call: batch x max_seqlen_q bounds total_q.
 size_t attention_workspace(int batch, int max_seqlen_q, int max_seqlen_k, int heads_q, int heads_kv) {
     if (batch <= 0 || max_seqlen_q <= 0 || heads_q <= 0 || heads_kv <= 0 || heads_q % heads_kv) return 0;
     // the variant switch may only move a call to the other kernel where no workspace is involved, so it does not matter here
-    return plan_attention(batch, max_seqlen_q, max_seqlen_k, heads_q, heads_kv, 0).state_bytes;
+    return plan_attention(batch, (int64_t)batch * max_seqlen_q, max_seqlen_k, heads_q, heads_kv, 0, SIZE_MAX).state_bytes;
 }
 
 template <bool F16>
 static hipError_t launch_of(const AttnArgs &a, const AttnParams &p, const AttnPlan &pl, hipStream_t s) {
     static std::atomic<unsigned> done[4] = {{0}, {0}, {0}, {0}};     // one set per operand format
-    const int64_t runs = pl.items / pl.q_blocks * pl.n_splits;   // (split, head group, sequence) triples, dealt to the 8 XCDs in turn
-    const dim3 grid((unsigned)((runs + 7) / 8 * 8 * pl.q_blocks));
+    const int64_t runs = pl.nchunks * pl.ny * pl.n_splits;       // (chunk of block ids, head group, split) triples, dealt to the 8 XCDs in turn
+    const dim3 grid((unsigned)((runs + 7) / 8 * 8 * pl.chunk));
     hipError_t e;
     if (pl.pingpong) {
         constexpr int RING = 4;
@@ -901,8 +942,13 @@ static hipError_t launch_of(const AttnArgs &a, const AttnParams &p, const AttnPl
 
 hipError_t launch_attention(const AttnArgs &a, hipStream_t s) {
     if (a.batch <= 0 || a.max_seqlen_q <= 0 || a.total_q <= 0) return hipSuccess;
-    const AttnPlan pl = plan_attention(a.batch, a.max_seqlen_q, a.max_seqlen_k, a.heads_q, a.heads_kv, g_attention_variant.load());
-    if (pl.items * pl.n_splits > 0x7fffffff - 8 * pl.q_blocks) return hipErrorInvalidValue;   // the launch is padded to 8 runs
+    // Blocks past batch x max_seqlen_q tokens are not launched (the workspace was sized from that bound): with
+    // max_seqlen_q below the largest Lq the last queries of the call stay unwritten.
+    const int64_t tokens = std::min<int64_t>(a.total_q, (int64_t)a.batch * a.max_seqlen_q);
+    const AttnPlan pl = plan_attention(a.batch, tokens, a.max_seqlen_k, a.heads_q, a.heads_kv, g_attention_variant.load(),
+                                       a.workspace ? a.workspace_bytes : 0);
+    if (pl.state_bytes > (a.workspace ? a.workspace_bytes : 0)) return hipErrorInvalidValue;
+    if ((pl.nchunks * pl.ny * pl.n_splits + 8) * pl.chunk > 0x7fffffff || pl.items > 0x7fffffff) return hipErrorInvalidValue;
     AttnParams p;
     p.Q = a.Q; p.K = a.K; p.V = a.V; p.O = a.O;
     p.cu_q = a.cu_q; p.cu_k = a.cu_k;
@@ -912,8 +958,10 @@ hipError_t launch_attention(const AttnArgs &a, hipStream_t s) {
     p.pack = pl.pack;
     p.rows = pl.rows;
     p.c = a.scale * 1.44269504088896340736f;
-    p.nq = (int)pl.q_blocks;
-    p.ny = a.heads_q / p.pack;
+    p.ny = pl.ny;
+    p.nb = (int)pl.nb;
+    p.chunk = pl.chunk;
+    p.nchunks = (int)pl.nchunks;
     p.nz = a.batch;
     p.n_splits = pl.n_splits;
     p.max_tiles = pl.splits_max * ATT_SPLIT;

@@ -291,7 +291,7 @@ static int attention(int dtype, const void *Q, const void *K, const void *V, voi
     if (need > 0 && !aligned(workspace, 256)) return TBIK_ERR_ALIGN;
     AttnArgs a{(const uint16_t *)Q, (const uint16_t *)K, (const uint16_t *)V, (uint16_t *)O, dtype, cu_seqlens_q, cu_seqlens_k,
                batch, max_seqlen_q, max_seqlen_k, total_q, total_k, heads_q, heads_kv, q_stride, k_stride, v_stride, o_stride,
-               scale, causal != 0, need > 0 ? workspace : nullptr};
+               scale, causal != 0, need > 0 ? workspace : nullptr, need > 0 ? workspace_bytes : 0};
     hipError_t e = launch_attention(a, (hipStream_t)hip_stream);
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }

@@ -59,7 +59,8 @@ struct AttnArgs {
     int64_t q_stride, k_stride, v_stride, o_stride;
     float scale;
     int causal;
-    void *workspace;              // attention_workspace(...) bytes, or nullptr if that is 0
+    void *workspace;              // attention_workspace(...) bytes or more, or nullptr if that is 0
+    size_t workspace_bytes;
 };
 size_t attention_workspace(int batch, int max_seqlen_q, int max_seqlen_k, int heads_q, int heads_kv);
 hipError_t launch_attention(const AttnArgs &a, hipStream_t s);
