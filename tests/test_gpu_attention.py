@@ -310,6 +310,32 @@ def test_ragged_batch_with_sequences_of_different_split_counts():
     check_against_oracle(O[2:72], chunk, False)                    # the 70 queries over four splits (no mask: the last loop's call)
 
 
+def test_one_chunk_among_many_decode_steps_and_an_understated_max_seqlen_q():
+    """The shape of a serving step: one chunk of a prefill and many decode steps of different lengths in one call (the
+    launch is sized from the token count, not from batch x longest).  Every row equals the row of a call with its
+    sequence alone.  With max_seqlen_q understated the launch covers fewer blocks: what it writes is right, the rest is
+    left as it was, and nothing is touched out of bounds."""
+    Hq, Hkv = 8, 2
+    rng = np.random.Generator(np.random.PCG64(96))
+    lens_q = [1] * 40 + [700] + [1] * 30
+    lens_k = [int(v) for v in rng.integers(1, 6000, size=40)] + [5000] + [int(v) for v in rng.integers(1, 300, size=30)]
+    c = syn.attention_inputs(97, lens_q, lens_k, Hq=Hq, Hkv=Hkv, D=128)
+    O = run(c)
+    for b in (0, 7, 39, 40, 41, 70):
+        q0, q1, k0, k1 = c["cu_q"][b], c["cu_q"][b + 1], c["cu_k"][b], c["cu_k"][b + 1]
+        one = dict(c, Q=c["Q"][q0:q1], K=c["K"][k0:k1], V=c["V"][k0:k1], cu_q=np.array([0, q1 - q0], dtype=np.int32),
+                   cu_k=np.array([0, k1 - k0], dtype=np.int32))
+        assert np.array_equal(run(one), O[q0:q1]), b
+    Q, K, V = gu.dev_bf16(c["Q"]), gu.dev_bf16(c["K"]), gu.dev_bf16(c["V"])
+    out = torch.full_like(Q, 7.0)
+    tb.tbik_attention(Q, K, V, i32(c["cu_q"]), i32(c["cu_k"]), 1, c["scale"], True, out=out)
+    torch.cuda.synchronize()
+    got = gu.host_bf16_bits(out)
+    written = np.any(got != 0x40E0, axis=(1, 2))                   # 7.0 in bf16
+    assert written[:40].all() and not written.all()
+    assert np.array_equal(got[written], O[written])
+
+
 def test_understated_max_seqlen_k_leaves_keys_out_and_stays_in_bounds():
     c = syn.attention_inputs(94, [1], [6000], Hq=4, Hkv=2, D=128)
     Q, K, V = gu.dev_bf16(c["Q"]), gu.dev_bf16(c["K"]), gu.dev_bf16(c["V"])
