@@ -424,6 +424,20 @@ def extras(tb, syn, torch, np, to_dev):
                                ((4, 4096, torch.bfloat16), (1, 16384, torch.bfloat16), (4, 4096, torch.float16)),
                                ((64, 4096, torch.bfloat16), (256, 2048, torch.bfloat16), (64, 4096, torch.float16),
                                 (1, 32768, torch.bfloat16), (4, 32768, torch.bfloat16), (1, 131072, torch.bfloat16))))
+    # a serving step: one 2048-token chunk (over 2048 keys) and 256 decode steps at 2048 keys in one call
+    Hq, Hkv, D = 32, 8, 128
+    lq, lk = [1] * 256 + [2048], [2048] * 257
+    Q = torch.randn(sum(lq), Hq, D, device="cuda:0").to(torch.bfloat16)
+    K = torch.randn(sum(lk), Hkv, D, device="cuda:0").to(torch.bfloat16)
+    Vv = torch.randn(sum(lk), Hkv, D, device="cuda:0").to(torch.bfloat16)
+    cuq = torch.tensor(np.concatenate([[0], np.cumsum(lq)]), dtype=torch.int32, device="cuda:0")
+    cuk = torch.tensor(np.concatenate([[0], np.cumsum(lk)]), dtype=torch.int32, device="cuda:0")
+    O = torch.empty_like(Q)
+    f = lambda: tb.tbik_attention(Q, K, Vv, cuq, cuk, 2048, D ** -0.5, True, out=O, max_seqlen_k=2048)
+    f(); f()
+    t = min(time_region(f, 10, torch) for _ in range(3))
+    res["attention_chunk_2048_plus_256_decodes_at_2048"] = {"ms": round(t, 4), "GBps_kv": round(4.0 * sum(lk) * Hkv * D / (t * 1e-3) / 1e9, 1)}
+    del Q, K, Vv, O
     V = 151936
     for M in (1, 64, 512):
         x = torch.from_numpy(syn.logits_f32(M, V)).to("cuda:0")
