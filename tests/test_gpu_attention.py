@@ -336,6 +336,27 @@ def test_one_chunk_among_many_decode_steps_and_an_understated_max_seqlen_q():
     assert np.array_equal(got[written], O[written])
 
 
+def test_a_hundred_decode_steps_of_two_splits_each():
+    """More sequences than a wavefront has lanes, each of two splits and few enough for one workgroup per split: both
+    kernels (splits, fold) find the sequence of a block in two rounds of the search.  Rows equal single-sequence calls;
+    one of them against the oracle."""
+    Hq, Hkv = 4, 1
+    rng = np.random.Generator(np.random.PCG64(98))
+    lens_k = [int(v) for v in rng.integers(4097, 4200, size=100)]
+    c = syn.attention_inputs(99, [1] * 100, lens_k, Hq=Hq, Hkv=Hkv, D=128)
+    O = run(c)
+    for b in (0, 1, 63, 64, 65, 99):
+        k0, k1 = c["cu_k"][b], c["cu_k"][b + 1]
+        one = dict(c, Q=c["Q"][b:b + 1], K=c["K"][k0:k1], V=c["V"][k0:k1], cu_q=np.array([0, 1], dtype=np.int32),
+                   cu_k=np.array([0, k1 - k0], dtype=np.int32))
+        assert np.array_equal(run(one), O[b:b + 1]), b
+    k0, k1 = c["cu_k"][64], c["cu_k"][65]
+    Oo, _ = orc.attention(c["Q"][64:65], c["K"][k0:k1], c["V"][k0:k1], np.array([0, 1], dtype=np.int32),
+                          np.array([0, k1 - k0], dtype=np.int32), c["scale"], True)
+    assert np.count_nonzero(O[64:65] != Oo) <= Oo.size // 20
+    assert np.max(np.abs(syn.bf16_bits_to_f32(O[64:65]) - syn.bf16_bits_to_f32(Oo))) <= 2.0 ** -8
+
+
 def test_understated_max_seqlen_k_leaves_keys_out_and_stays_in_bounds():
     c = syn.attention_inputs(94, [1], [6000], Hq=4, Hkv=2, D=128)
     Q, K, V = gu.dev_bf16(c["Q"]), gu.dev_bf16(c["K"]), gu.dev_bf16(c["V"])
