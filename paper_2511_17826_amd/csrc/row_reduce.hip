@@ -258,8 +258,12 @@ __device__ __forceinline__ bool wait_for_row(const unsigned *counter, unsigned w
 __device__ __forceinline__ void publish(float *slot, float v, unsigned *counter) {
     const unsigned old = __hip_atomic_exchange(reinterpret_cast<unsigned *>(slot), __float_as_uint(v), __ATOMIC_RELAXED,
                                                __HIP_MEMORY_SCOPE_AGENT);
-    asm volatile("" ::"v"(old));                                    // needs the returned value: waits for the exchange
-    __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // The increment is made to depend on the exchange's return value (through an empty statement the compiler cannot
+    // see through, which also keeps memory operations from moving across it), so the arrival cannot be issued before
+    // the exchange has returned.
+    unsigned one = 1u;
+    asm volatile("" : "+v"(one) : "v"(old) : "memory");
+    __hip_atomic_fetch_add(counter, one, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ float coherent_load(const float *p) {
     return __uint_as_float(__hip_atomic_fetch_or(reinterpret_cast<unsigned *>(const_cast<float *>(p)), 0u, __ATOMIC_RELAXED,
