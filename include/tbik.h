@@ -156,6 +156,22 @@ int tbik_row_reduce(const void *x, tbik_dtype x_dtype, void *out, tbik_rowop op,
                     void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * tbik_row_reduce for callers that cannot allocate device memory and have no workspace to pass: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels, results (bit for
+ * bit) and errors as tbik_row_reduce, except that the scratch is a fixed array of TBIK_STATIC_SCRATCH_BYTES inside
+ * the library's device code, one copy per GPU, held until the process ends.  The call allocates and frees nothing.
+ *   - A shape whose tbik_row_reduce_workspace_bytes(M, V, op) exceeds TBIK_STATIC_SCRATCH_BYTES is refused with
+ *     TBIK_ERR_WORKSPACE and nothing is launched (log-softmax over V = 151936 fp32 logits fits up to 10000 rows).
+ *   - The first call on a device looks the array's address up (with that device current); a call with M == 0 does
+ *     only that, so a caller can make one before it starts capturing a graph.
+ *   - All calls on one GPU share the one array, which keeps the previous call's contents; every call clears what
+ *     it needs at zero itself.  Calls that overlap in time on one GPU (different streams) race: order them.
+ */
+#define TBIK_STATIC_SCRATCH_BYTES (4u << 20)
+int tbik_row_reduce_static(const void *x, tbik_dtype x_dtype, void *out, tbik_rowop op, int M, int64_t V,
+                           void *hip_stream);
+
+/*
  * Batch-invariant attention on packed variable-length sequences (implementation appendix, "Framework Modifications
  * for vLLM and FSDP": the attention kernel uses a FIXED tile size, prefill and decode run the same kernel, and the
  * serving stack's decode-side optimisations are off; Sec. 2.1: fp32 accumulators).  For sequence b, query head h, query i (of Lq = cu_q[b+1] - cu_q[b] queries, which

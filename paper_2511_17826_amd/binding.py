@@ -33,6 +33,7 @@ SIGNATURES = {
     "tbik_rmsnorm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_void_p]),
     "tbik_row_reduce": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int64,
                                   C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tbik_row_reduce_static": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_void_p]),
     "tbik_gemm_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]),
     "tbik_row_reduce_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int64, C.c_int]),
     "tbik_gemm_reference": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64,
@@ -373,6 +374,16 @@ def tbik_row_reduce(x: torch.Tensor, op: int, out: torch.Tensor | None = None,
     st = lib().tbik_row_reduce(x.data_ptr(), _dt(x), out.data_ptr(), op, M, V, workspace.data_ptr(),
                                workspace.numel() * workspace.element_size(), _stream())
     _check(st, "tbik_row_reduce")
+    return out
+
+
+def tbik_row_reduce_static(x: torch.Tensor, op: int, out: torch.Tensor) -> torch.Tensor:
+    """tbik_row_reduce on the library's fixed scratch array: no workspace, no allocation (``out`` is the caller's)."""
+    assert x.dim() == 2 and x.is_contiguous() and out.is_contiguous() and out.dtype == torch.float32
+    M, V = x.shape
+    assert out.numel() == (M * V if op == TBIK_LOGSOFTMAX else M)
+    st = lib().tbik_row_reduce_static(x.data_ptr(), _dt(x), out.data_ptr(), op, M, V, _stream())
+    _check(st, "tbik_row_reduce_static")
     return out
 
 

@@ -498,4 +498,38 @@ hipError_t launch_row_reduce(const void *x, int x_dtype, void *out, int op, int 
     return run<TBIK_F32>(x, out, op, M, V, ws, s);
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Scratch of the library's own for callers that cannot allocate: a fixed array in device memory, one copy per
+// GPU, held until the process ends.  In host code the array's name is only a handle for the runtime; the
+// address the kernels get is looked up once per device with that device current.
+static __device__ __align__(256) unsigned char scratch[TBIK_STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+static std::atomic<void *> g_scratch_of_device[MAX_DEVICES];
+
+hipError_t static_scratch(void **ptr) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    void *p = g_scratch_of_device[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        g_scratch_of_device[dev].store(p, std::memory_order_release);   // two first calls at once look up the same address
+    }
+    *ptr = p;
+    return hipSuccess;
+}
+
+hipError_t launch_row_reduce_static(const void *x, int x_dtype, void *out, int op, int M, int64_t V, hipStream_t s) {
+    void *ws = nullptr;
+    hipError_t e = static_scratch(&ws);
+    if (e != hipSuccess) return e;
+    if (M <= 0) return hipSuccess;
+    if (row_reduce_workspace(M, V, x_dtype, op) > (size_t)TBIK_STATIC_SCRATCH_BYTES) return hipErrorInvalidValue;
+    return launch_row_reduce(x, x_dtype, out, op, M, V, ws, s);
+}
+
 }  // namespace tbik

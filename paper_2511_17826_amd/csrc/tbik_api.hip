@@ -370,6 +370,20 @@ int tbik_row_reduce(const void *x, tbik_dtype x_dtype, void *out, tbik_rowop op,
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }
 
+int tbik_row_reduce_static(const void *x, tbik_dtype x_dtype, void *out, tbik_rowop op, int M, int64_t V, void *hip_stream) {
+    if (x_dtype != TBIK_F32 && x_dtype != TBIK_BF16 && x_dtype != TBIK_F16) return TBIK_ERR_DTYPE;
+    if (op != TBIK_SUM && op != TBIK_MAX && op != TBIK_LOGSOFTMAX) return TBIK_ERR_DTYPE;
+    const int epl = (x_dtype == TBIK_F32) ? 4 : 8;
+    if (M < 0 || V <= 0 || V % epl != 0) return TBIK_ERR_SHAPE;
+    if (M > 0) {
+        if (!x || !out) return TBIK_ERR_NULL;
+        if (!aligned(x, 16) || !aligned(out, op == TBIK_LOGSOFTMAX ? 16 : 4)) return TBIK_ERR_ALIGN;
+        if (row_reduce_workspace(M, V, (int)x_dtype, (int)op) > (size_t)TBIK_STATIC_SCRATCH_BYTES) return TBIK_ERR_WORKSPACE;
+    }
+    hipError_t e = launch_row_reduce_static(x, (int)x_dtype, out, (int)op, M, V, (hipStream_t)hip_stream);
+    return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
 int tbik_set_row_wait_limit(int polls) { return set_row_wait_limit(polls); }
 
 int tbik_set_gemm_variant(int variant) {

@@ -69,6 +69,9 @@ int set_attention_variant(int v);   // 0 = default, 1 = two workgroups per CU, 2
 size_t row_reduce_workspace(int M, int64_t V, int x_dtype, int op);
 hipError_t launch_row_reduce(const void *x, int x_dtype, void *out, int op, int M, int64_t V, void *ws, hipStream_t s);
 int set_row_wait_limit(int polls);   // returns the previous limit
+// The same launches with the library's fixed per-device scratch array (TBIK_STATIC_SCRATCH_BYTES) as workspace; no
+// allocation.  The first call on a device looks the array's address up.  The caller has checked that the shape fits.
+hipError_t launch_row_reduce_static(const void *x, int x_dtype, void *out, int op, int M, int64_t V, hipStream_t s);
 
 enum { VARIANT_AUTO = 0, VARIANT_REFERENCE = 1, VARIANT_T128 = 2, VARIANT_T32 = 3, VARIANT_T64 = 4, VARIANT_COUNT = 5 };
 
