@@ -12,10 +12,15 @@ projection workload (X bf16 [4096,4096] ~ N(0,1), W bf16 [4096,4096] ~ N(0,0.02)
     Y_P    = tbik_tree_combine(part_P)                           top of the tree + single rounding
     log-softmax over the fp32 rows of Y_8                        tree-ordered row reduction
 
-All inputs are resident in HBM before the timed region.  `value` is the GEMM work of a step
-(4 products of 2*M*K*N flop) divided by the wall time of the whole step, in TFLOP/s.  After the
-timed region the outputs for P in {1,2,4,8} are compared bit for bit (`unique_outputs` must be 1).
-Prints ONE JSON line.
+All inputs are resident in HBM before the timed region.  `value` is the metric itself: the rate of the tree GEMM on
+the whole K (tbik_gemm, P = 1, 2*M*K*N flop per call), from HIP events around that call inside every timed step.
+`ms_per_step` is the wall time of the whole step and `step_tflops` the GEMM work of a step (4 products) over it: the
+step also holds the HBM-bound traffic of the emulated shards, so that figure is neither the kernel's rate nor a
+tensor-parallel latency.  After the timed region the outputs for P in {1,2,4,8} are compared bit for bit
+(`unique_outputs` must be 1).  `kernels` carries every shape the metric names (o_proj M in {1024, 4096}, down_proj M in
+{512, 4096}, weight streaming at small M with the weights rotated through more than the 256 MiB memory-side cache,
+RMSNorm 8192 x {4096, 5120}, log-softmax {1, 64, 512} x 151936, tree_combine P in {2, 4, 8}); HBM-bound kernels are
+timed cold (buffers rotated through more than the cache) and warm (one buffer set) side by side.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -31,9 +36,41 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
-# HBM bytes per launch of the dominant kernel (tbik_gemm, P=1, M=K=N=4096) from the rocprofv3 FETCH_SIZE / WRITE_SIZE
-# runs summarised in profiles/bench_step_oproj_m4096_pmc.md (384.2 MiB read + 32.0 MiB written).
-GEMM_P1_HBM_TRAFFIC_BYTES = int((384.2 + 32.0) * (1 << 20))
+CACHE_BYTES = 256 << 20        # memory-side cache: a buffer set a kernel is to find in HBM is rotated through more than this
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "bench_step_oproj_m4096_pmc.md")
+
+
+def profiled_traffic():
+    """HBM bytes per launch of the dominant kernel (tbik_gemm, P = 1, M = K = N = 4096) as the committed rocprofv3
+    FETCH_SIZE / WRITE_SIZE summary states them (line `traffic_bytes_per_launch: N`), or None."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(line.split(":")[1].split()[0])
+    except OSError:
+        pass
+    return None          # the summary did not travel with this copy of the tree: unmeasured here
+
+
+def best_ms(fn, iters, torch, reps=3, warm=2):
+    for _ in range(warm):
+        fn()
+    return min(time_region(fn, iters, torch) for _ in range(reps))
+
+
+def rotating(calls):
+    """One callable that walks through `calls` (the same kernel on distinct buffer sets) in turn."""
+    state = {"i": 0}
+
+    def fn():
+        calls[state["i"] % len(calls)]()
+        state["i"] += 1
+    return fn
+
+
+def sets_for_cold(bytes_per_set):
+    """How many distinct buffer sets it takes to exceed the memory-side cache (at least 2, at most 64)."""
+    return int(max(2, min(64, -(-int(1.5 * CACHE_BYTES) // max(1, bytes_per_set)))))
 
 
 def time_region(fn, iters, torch):
@@ -95,9 +132,13 @@ def main():
     ws_rr = torch.empty(max(256, int(tb.lib().tbik_row_reduce_workspace_bytes(M, N, tb.TBIK_LOGSOFTMAX))),
                         dtype=torch.uint8, device=dev)
 
-    def step():
+    def step(gemm_events=None):
         tb.tbik_rmsnorm(X, wnorm, 1e-6, out=xn)
+        if gemm_events is not None:
+            gemm_events[0].record()
         tb.tbik_gemm(X, W, leaf, g, out=y1, workspace=ws_gemm)
+        if gemm_events is not None:
+            gemm_events[1].record()
         for P in Ps:
             tb.tbik_gemm_shard_partials(X, W, leaf, g, P, out=parts[P], workspace=ws_gemm)
             tb.tbik_tree_combine(parts[P], out=yP[P])
@@ -114,14 +155,17 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    gemm_events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
+    for i in range(args.steps):
+        step(gemm_events[i])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = 1e3 * wall / args.steps
     flop_per_step = 4 * 2.0 * M * K * N
-    value = flop_per_step / (ms_per_step * 1e-3) / 1e12
+    step_tflops = flop_per_step / (ms_per_step * 1e-3) / 1e12
+    gemm_ms_in_step = sum(a.elapsed_time(b) for a, b in gemm_events) / max(1, args.steps)
+    value = 2.0 * M * K * N / (gemm_ms_in_step * 1e-3) / 1e12      # the metric: the tree GEMM's own rate, measured in the timed steps
 
     # invariance check on what the timed steps produced
     unique = len({bytes(y.view(torch.int16).cpu().numpy().tobytes()) for y in [y1] + [yP[P] for P in Ps]})
@@ -134,7 +178,7 @@ def main():
     gemm_tflops = 2.0 * M * K * N / (gemm_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "gemm_tiled_kernel (tbik_gemm, P=1, M=4096)", "achieved": round(gemm_tflops, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
-                "launch_ms": round(gemm_ms, 4), "traffic": GEMM_P1_HBM_TRAFFIC_BYTES,
+                "launch_ms": round(gemm_ms, 4), "traffic": profiled_traffic(),
                 "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, KiB)",
                 "algorithmic_bytes": 2 * M * K + 2 * K * N + 2 * M * N}
 
@@ -152,18 +196,14 @@ def main():
                      "tflops": round(2.0 * M * K * N / (base_ms * 1e-3) / 1e12, 2),
                      "elements_changed_by_splitting_K_in_two": base_mismatch, "elements": M * N}
 
-    # ---- per-row kernels of the step, timed alone (HBM-bound) ----
+    # ---- the other kernels of the step, timed alone on the step's own (cache-resident) buffers ----
     kernels = {}
-    t = min(time_region(lambda: tb.tbik_rmsnorm(X, wnorm, 1e-6, out=xn), 20, torch) for _ in range(3))
-    kernels["rmsnorm_4096x4096"] = {"ms": round(t, 4), "GBps": round(4.0 * M * K / (t * 1e-3) / 1e9, 1),
-                                    "frac_hbm": round(4.0 * M * K / (t * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
-    t = min(time_region(lambda: tb.tbik_tree_combine(parts[8], out=yP[8]), 20, torch) for _ in range(3))
-    byts = (8 * 4 + 2) * M * N
-    kernels["tree_combine_P8_4096x4096"] = {"ms": round(t, 4), "GBps": round(byts / (t * 1e-3) / 1e9, 1),
-                                            "frac_hbm": round(byts / (t * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
-    t = min(time_region(lambda: tb.tbik_row_reduce(y8f, tb.TBIK_LOGSOFTMAX, out=lsm, workspace=ws_rr), 20, torch) for _ in range(3))
-    kernels["logsoftmax_4096x4096"] = {"ms": round(t, 4), "GBps": round(8.0 * M * N / (t * 1e-3) / 1e9, 1),
-                                       "frac_hbm": round(8.0 * M * N / (t * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+    t = best_ms(lambda: tb.tbik_rmsnorm(X, wnorm, 1e-6, out=xn), 20, torch)
+    kernels["rmsnorm_4096x4096_warm"] = {"ms": round(t, 4), "GBps": round(4.0 * M * K / (t * 1e-3) / 1e9, 1),
+                                         "note": "64 MiB of buffers, served by the 256 MiB memory-side cache: not an HBM figure"}
+    t = best_ms(lambda: tb.tbik_row_reduce(y8f, tb.TBIK_LOGSOFTMAX, out=lsm, workspace=ws_rr), 20, torch)
+    kernels["logsoftmax_4096x4096_warm"] = {"ms": round(t, 4), "GBps": round(8.0 * M * N / (t * 1e-3) / 1e9, 1),
+                                            "note": "128 MiB of buffers, cache-assisted"}
     for P in Ps:
         t = min(time_region(lambda: tb.tbik_gemm_shard_partials(X, W, leaf, g, P, out=parts[P], workspace=ws_gemm), 10, torch)
                 for _ in range(2))
@@ -178,6 +218,8 @@ def main():
         t = min(time_region(f, 20, torch) for _ in range(3))
         kernels["one_rank_share_P%d" % P] = {"ms": round(t, 4), "tflops": round(2.0 * M * (K // P) * N / (t * 1e-3) / 1e12, 2)}
 
+    del parts, yP, y8f, lsm, xn
+    kernels.update(metric_shapes(tb, syn, torch, np, to_dev, X, W))
     if args.extras:
         kernels.update(extras(tb, syn, torch, np, to_dev))
     else:                                                   # three attention lines in every run; --extras has them all
@@ -191,9 +233,11 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "8B-class o_proj: X bf16 [4096,4096] ~N(0,1), W bf16 [4096,4096] ~N(0,0.02), leaf 256, "
                                "k_first 1; step = RMSNorm + tbik_gemm(P=1) + shard_partials/tree_combine for P in {2,4,8} "
-                               "+ log-softmax over the fp32 output rows",
+                               "+ log-softmax over the fp32 output rows; value = rate of tbik_gemm(P=1) inside the step",
                    "M": M, "K": K, "N": N, "leaf": leaf, "k_first": g, "P": [1, 2, 4, 8]},
         "pct_of_bf16_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
+        "gemm_ms_in_step": round(gemm_ms_in_step, 4),
+        "step_tflops": round(step_tflops, 2),
         "unique_outputs": unique,
         "roofline": roofline,
         "baseline_gemm": baseline_gemm,
@@ -222,6 +266,100 @@ def cpu_baseline(c, leaf, g, rows):
     return {"value": round(2.0 * rows * K * N / dt / 1e12, 5), "unit": "TFLOP/s", "cores": ncores, "kind": "oracle",
             "seconds": round(dt, 2),
             "sample": "first %d of 4096 rows of the same X against the full W (whole K, all N), fp32 scalar tree order" % rows}
+
+
+def metric_shapes(tb, syn, torch, np, to_dev, X, W):
+    """Every shape the metric names, one line each (in every run).  MFMA-bound lines carry `frac` of the 2.5 PFLOP/s bf16
+    peak and the time of torch.matmul on the same operands; HBM-bound lines carry GB/s and `frac_hbm` of 8 TB/s, cold
+    (buffer sets rotated through more than the memory-side cache) and warm (one set)."""
+    res = {}
+    dev = X.device
+
+    def gemm_line(name, Xd, Wd, M, leaf, g, iters):
+        K, N = Wd.shape
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        ws = torch.empty(max(256, tb.gemm_workspace_bytes(M, N, K, leaf, g)), dtype=torch.uint8, device=dev)
+        t = best_ms(lambda: tb.tbik_gemm(Xd[:M], Wd, leaf, g, out=y, workspace=ws), iters, torch)
+        tbase = best_ms(lambda: torch.matmul(Xd[:M], Wd, out=y), iters, torch)
+        tf = 2.0 * M * K * N / (t * 1e-3) / 1e12
+        res[name] = {"ms": round(t, 4), "tflops": round(tf, 1), "frac": round(tf / PEAK_BF16_TFLOPS, 4),
+                     "baseline_ms": round(tbase, 4)}
+
+    def streaming_line(name, Xd, Wd, M, leaf, g, copies):
+        """Small M: the weights are the traffic.  `copies` distinct copies of W (more than the cache in all) are walked by
+        calls captured in one HIP graph, so neither the host nor the cache stands between the kernel and HBM."""
+        K, N = Wd.shape
+        Ws = [Wd] + [Wd.clone() for _ in range(copies - 1)]
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        ws = torch.empty(max(256, tb.gemm_workspace_bytes(M, N, K, leaf, g)), dtype=torch.uint8, device=dev)
+        side = torch.cuda.Stream()
+        per_call = {}
+        for kind, call in (("tbik", lambda Wc: tb.tbik_gemm(Xd[:M], Wc, leaf, g, out=y, workspace=ws)),
+                           ("baseline", lambda Wc: torch.matmul(Xd[:M], Wc, out=y))):
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                call(Ws[0])
+                torch.cuda.synchronize()
+                with torch.cuda.graph(graph, stream=side):
+                    for Wc in Ws:
+                        call(Wc)
+            graph.replay()
+            torch.cuda.synchronize()
+            per_call[kind] = min(time_region(graph.replay, 5, torch) for _ in range(3)) / len(Ws)
+        warm = best_ms(lambda: tb.tbik_gemm(Xd[:M], Wd, leaf, g, out=y, workspace=ws), 20, torch)
+        t = per_call["tbik"]
+        gbs = 2.0 * K * N / (t * 1e-3) / 1e9
+        res[name] = {"ms_cold_in_graph": round(t, 4), "GBps_weights": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4),
+                     "baseline_ms_cold_in_graph": round(per_call["baseline"], 4), "ms_warm_per_python_call": round(warm, 4)}
+
+    gemm_line("oproj_M1024", X, W, 1024, 256, 1, 20)
+    gemm_line("oproj_M4096", X, W, 4096, 256, 1, 20)
+    for M in (1, 16, 64):
+        streaming_line("oproj_M%d_weights_from_hbm" % M, X, W, M, 256, 1, 10)        # 10 x 32 MiB
+    c = syn.gemm_downproj(4096)
+    Xd, Wd = to_dev(c["X"]), to_dev(c["W"])
+    gemm_line("downproj_M512", Xd, Wd, 512, 256, 3, 10)
+    gemm_line("downproj_M4096", Xd, Wd, 4096, 256, 3, 10)
+    for M in (1, 64):
+        streaming_line("downproj_M%d_weights_from_hbm" % M, Xd, Wd, M, 256, 3, 4)    # 4 x 96 MiB
+    del Xd, Wd
+
+    def hbm_line(name, calls, byts, iters):
+        cold = best_ms(rotating(calls), iters * len(calls), torch, warm=len(calls))
+        warm = best_ms(calls[0], iters, torch)
+        res[name] = {"ms_cold": round(cold, 4), "GBps_cold": round(byts / (cold * 1e-3) / 1e9, 1),
+                     "frac_hbm": round(byts / (cold * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                     "ms_warm": round(warm, 4), "GBps_warm": round(byts / (warm * 1e-3) / 1e9, 1), "buffer_sets": len(calls)}
+
+    for H in (4096, 5120):
+        xb, wb = syn.rmsnorm_inputs(8192, H)
+        x0, w = to_dev(xb), to_dev(wb)
+        n = sets_for_cold(4 * 8192 * H)
+        xs = [x0] + [x0.clone() for _ in range(n - 1)]
+        ys = [torch.empty_like(x0) for _ in range(n)]
+        hbm_line("rmsnorm_8192x%d" % H, [(lambda i=i: tb.tbik_rmsnorm(xs[i], w, 1e-6, out=ys[i])) for i in range(n)],
+                 4.0 * 8192 * H, 10)
+        del xs, ys
+    V = 151936
+    lg = torch.from_numpy(syn.logits_f32(512, V)).to(dev)
+    out = torch.empty_like(lg)
+    ws_rr = torch.empty(max(256, int(tb.lib().tbik_row_reduce_workspace_bytes(512, V, tb.TBIK_LOGSOFTMAX))), dtype=torch.uint8, device=dev)
+    for M in (1, 64, 512):
+        # distinct row blocks of the same 512-row tensor (311 MiB in, 311 MiB out) are the buffer sets
+        n = 512 // M
+        calls = [(lambda i=i: tb.tbik_row_reduce(lg[i * M:(i + 1) * M], tb.TBIK_LOGSOFTMAX, out=out[i * M:(i + 1) * M], workspace=ws_rr))
+                 for i in range(n)]
+        hbm_line("logsoftmax_%dx151936_8V_basis" % M, calls, 8.0 * M * V, max(1, 16 // n) if n > 16 else 10)
+    del lg, out
+    Mc = Nc = 4096
+    for P in (2, 4, 8):
+        n = sets_for_cold((4 * P + 2) * Mc * Nc)
+        ps = [torch.randn((P, Mc, Nc), dtype=torch.float32, device=dev) for _ in range(n)]
+        ys = [torch.empty((Mc, Nc), dtype=torch.bfloat16, device=dev) for _ in range(n)]
+        hbm_line("tree_combine_P%d_4096x4096" % P, [(lambda i=i: tb.tbik_tree_combine(ps[i], out=ys[i])) for i in range(n)],
+                 (4.0 * P + 2) * Mc * Nc, 10)
+        del ps, ys
+    return res
 
 
 def attention_lines(tb, torch, prefill_shapes, decode_shapes):
