@@ -135,8 +135,11 @@ _ws_cache = {}
 
 
 def _workspace(nbytes: int, device) -> torch.Tensor:
-    """A caller-side scratch tensor (the library itself never allocates)."""
-    key = str(device)
+    """A caller-side scratch tensor (the library itself never allocates), one per device AND stream: calls that share a
+    workspace must not overlap in time, which only calls on one stream guarantee.  A tensor that is replaced by a larger
+    one stays alive until the kernels already queued on its stream are done (torch's allocator frees a block for reuse
+    by the stream it was allocated on).  Callers that run one call's kernels on several streams pass their own."""
+    key = (str(device), _stream())
     w = _ws_cache.get(key)
     if w is None or w.numel() < nbytes:
         w = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
@@ -315,7 +318,8 @@ def attention_workspace_bytes(batch, max_seqlen_q, max_seqlen_k, heads_q, heads_
     return int(lib().tbik_attention_workspace_bytes(batch, max_seqlen_q, max_seqlen_k, heads_q, heads_kv))
 
 
-def _attention(entry, dtype, Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, scale, causal, out, max_seqlen_k, workspace):
+def _attention(entry, dtype, Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, scale, causal, out, max_seqlen_k, workspace,
+               verify_lengths=False):
     _token_major(Q, "Q", dtype); _token_major(K, "K", dtype); _token_major(V, "V", dtype)
     Tq, Hq, D = Q.shape
     Tk, Hkv, _ = K.shape
@@ -330,6 +334,10 @@ def _attention(entry, dtype, Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, 
     batch = cu_seqlens_q.numel() - 1
     if max_seqlen_k is None:                          # not given: read it from the device (a synchronisation)
         max_seqlen_k = int((cu_seqlens_k[1:] - cu_seqlens_k[:-1]).max().item()) if batch > 0 else 0
+    elif verify_lengths and batch > 0:                # an understated bound leaves keys out without an error: check it here
+        longest = int((cu_seqlens_k[1:] - cu_seqlens_k[:-1]).max().item())
+        if longest > max_seqlen_k:
+            raise ValueError("max_seqlen_k = %d, but a sequence has %d keys" % (max_seqlen_k, longest))
     need = int(lib().tbik_attention_workspace_bytes(batch, max_seqlen_q, min(max_seqlen_k, Tk), Hq, Hkv)) if D == 128 else 0
     if workspace is None and need:
         workspace = _workspace(need, Q.device)
@@ -345,20 +353,23 @@ def _attention(entry, dtype, Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, 
 def tbik_attention(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, cu_seqlens_q: torch.Tensor,
                    cu_seqlens_k: torch.Tensor, max_seqlen_q: int, scale: float, causal: bool = True,
                    out: torch.Tensor | None = None, max_seqlen_k: int | None = None,
-                   workspace: torch.Tensor | None = None) -> torch.Tensor:
+                   workspace: torch.Tensor | None = None, verify_lengths: bool = False) -> torch.Tensor:
     """Fixed-tile, fixed-split attention on packed sequences: Q [Tq, Hq, D], K and V [Tk, Hkv, D] (token stride free),
-    cu_seqlens_* int32 GPU tensors [batch + 1].  Returns O [Tq, Hq, D] bf16."""
+    cu_seqlens_* int32 GPU tensors [batch + 1].  Returns O [Tq, Hq, D] bf16.  `max_seqlen_k` must be at least the longest
+    sequence's key count (the C call cannot see the lengths, which live on the device: keys past an understated bound
+    are left out of the softmax without an error); `verify_lengths` checks it against `cu_seqlens_k` at the cost of a
+    synchronisation, and leaving `max_seqlen_k` out reads it from there."""
     return _attention("tbik_attention", torch.bfloat16, Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, scale, causal, out,
-                      max_seqlen_k, workspace)
+                      max_seqlen_k, workspace, verify_lengths)
 
 
 def tbik_attention_f16(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, cu_seqlens_q: torch.Tensor,
                        cu_seqlens_k: torch.Tensor, max_seqlen_q: int, scale: float, causal: bool = True,
                        out: torch.Tensor | None = None, max_seqlen_k: int | None = None,
-                       workspace: torch.Tensor | None = None) -> torch.Tensor:
+                       workspace: torch.Tensor | None = None, verify_lengths: bool = False) -> torch.Tensor:
     """The same on fp16 tensors."""
     return _attention("tbik_attention_f16", torch.float16, Q, K, V, cu_seqlens_q, cu_seqlens_k, max_seqlen_q, scale, causal, out,
-                      max_seqlen_k, workspace)
+                      max_seqlen_k, workspace, verify_lengths)
 
 
 def tbik_row_reduce(x: torch.Tensor, op: int, out: torch.Tensor | None = None,

@@ -8,8 +8,11 @@ Bars:
     then (by one bf16 spacing, at most 2^-7 p_j) and with it every channel of that row by up to 2^-7 p_j |v_jd| / l,
     and it moves the rounding of an output that sits on a boundary.  With B = sum_j p_j |v_jd| / l (the magnitude
     the weights' roundings act on), stated tolerance against the oracle:
-        every output:  |O_gpu - O_oracle| <= 2^-7 B + 2 bf16 steps of the output   (every weight flipped: cannot be exceeded)
-        in the mean:   rms(O_gpu - O_oracle) <= 2^-13 rms(B),  and at least 98 % of the outputs bit-equal
+        every output:  |O_gpu - O_oracle| <= 2^-8 B + 1 bf16 step of the output   (half of what flipping EVERY weight of a
+                       row could do; the largest difference measured is a quarter of that worst case)
+        in the mean:   rms(O_gpu - O_oracle) <= 2^-14 rms(B),  and at least 99 % of the outputs bit-equal
+                       (measured over these cases: 99.15 % .. 100 %, rms 2^-14.6 or better); 98 % for single queries
+                       over thousands of keys (several splits), where more weights can flip: measured 98.8 %
     and against the plain definition in fp64: |O_gpu - O_fp64| <= 2^-8 B + 2^-8 |O_fp64|.
 """
 import numpy as np
@@ -46,7 +49,7 @@ def run(c, causal=True, max_q=None):
     return gu.host_bf16_bits(O)
 
 
-def check_against_oracle(O, c, causal):
+def check_against_oracle(O, c, causal, min_equal=0.99):
     Oo, O32 = orc.attention(c["Q"], c["K"], c["V"], c["cu_q"], c["cu_k"], c["scale"], causal)
     want64, B = plain_attention_fp64(c, causal)
     g = syn.bf16_bits_to_f32(O).astype(np.float64)
@@ -54,11 +57,13 @@ def check_against_oracle(O, c, causal):
     assert np.all(np.abs(g - want64) <= 2.0 ** -8 * B + 2.0 ** -8 * np.abs(want64) + 1e-30)
     mag = np.maximum(np.abs(g), np.abs(o))
     step = 2.0 ** (np.floor(np.log2(np.maximum(mag, 2.0 ** -126))) - 7)
-    assert np.all(np.abs(g - o) <= 2.0 ** -7 * B + 2 * step), float(np.max(np.abs(g - o) / (2.0 ** -7 * B + 2 * step)))
+    assert np.all(np.abs(g - o) <= 2.0 ** -8 * B + step), float(np.max(np.abs(g - o) / (2.0 ** -8 * B + step)))
     equal = np.count_nonzero(O == Oo) / O.size
     rms = float(np.sqrt(np.mean((g - o) ** 2)) / max(np.sqrt(np.mean(B ** 2)), 1e-30))
-    print("attention vs oracle: %.4f of the outputs bit-equal, rms difference / rms B = 2^%.1f" % (equal, np.log2(max(rms, 1e-30))))
-    assert rms <= 2.0 ** -13 and equal >= 0.98, (rms, equal)
+    worst = float(np.max(np.abs(g - o) / (2.0 ** -8 * B + step)))
+    print("attention vs oracle: %.4f of the outputs bit-equal, rms difference / rms B = 2^%.1f, worst |g-o| = %.3f of its bar"
+          % (equal, np.log2(max(rms, 1e-30)), worst))
+    assert rms <= 2.0 ** -14 and equal >= min_equal, (rms, equal)
     return equal
 
 
@@ -206,7 +211,7 @@ def test_long_context_and_many_short_sequences():
     O = run(c)
     dec = dict(c, Q=c["Q"][:1], K=c["K"][:40000], V=c["V"][:40000], cu_q=np.array([0, 1], dtype=np.int32),
                cu_k=np.array([0, 40000], dtype=np.int32))
-    check_against_oracle(O[:1], dec, True)
+    check_against_oracle(O[:1], dec, True, min_equal=0.98)
     for i in (0, 1500, 2999):                                      # rows of the chunk, each as its own decode step
         nk = 40000 - 3000 + i + 1
         one = dict(c, Q=c["Q"][1 + i:2 + i], K=c["K"][40000:40000 + nk], V=c["V"][40000:40000 + nk],
@@ -267,7 +272,7 @@ def test_splits_one_workgroup_per_split_or_one_for_all_same_bits():
     # oracle: the decode row and three rows of the chunk, each as its own decode problem
     dec = dict(c, Q=c["Q"][:1], K=c["K"][:long_k], V=c["V"][:long_k], cu_q=np.array([0, 1], dtype=np.int32),
                cu_k=np.array([0, long_k], dtype=np.int32))
-    check_against_oracle(small[:1], dec, True)
+    check_against_oracle(small[:1], dec, True, min_equal=0.98)
     for i in (0, 150, 299):
         nk = long_k - 300 + i + 1
         one = dict(c, Q=c["Q"][1 + i:2 + i], K=c["K"][long_k:long_k + nk], V=c["V"][long_k:long_k + nk],
@@ -275,7 +280,7 @@ def test_splits_one_workgroup_per_split_or_one_for_all_same_bits():
         got = run(one)
         assert np.array_equal(got[0], small[1 + i]), i
         if i == 299:
-            check_against_oracle(got, one, True)
+            check_against_oracle(got, one, True, min_equal=0.98)
     # a prefill across two split boundaries, alone (splits in parallel) and four times in one call (walked)
     p1 = syn.attention_inputs(93, [8300], [8300], Hq=4, Hkv=2, D=128)
     O1 = run(p1)
@@ -307,7 +312,7 @@ def test_ragged_batch_with_sequences_of_different_split_counts():
         assert not O[c["cu_q"][4]].any()                           # no key: zeros
     chunk = dict(c, Q=c["Q"][2:72], K=c["K"][5100:18100], V=c["V"][5100:18100], cu_q=np.array([0, 70], dtype=np.int32),
                  cu_k=np.array([0, 13000], dtype=np.int32))
-    check_against_oracle(O[2:72], chunk, False)                    # the 70 queries over four splits (no mask: the last loop's call)
+    check_against_oracle(O[2:72], chunk, False, min_equal=0.98)                    # the 70 queries over four splits (no mask: the last loop's call)
 
 
 def test_one_chunk_among_many_decode_steps_and_an_understated_max_seqlen_q():
@@ -363,3 +368,6 @@ def test_understated_max_seqlen_k_leaves_keys_out_and_stays_in_bounds():
     O = tb.tbik_attention(Q, K, V, i32(c["cu_q"]), i32(c["cu_k"]), 1, c["scale"], False, max_seqlen_k=4096)
     short = dict(c, K=c["K"][:4096], V=c["V"][:4096], cu_k=np.array([0, 4096], dtype=np.int32))
     assert np.array_equal(gu.host_bf16_bits(O), run(short, False))
+    # the binding's optional check turns the silent truncation into an error
+    with pytest.raises(ValueError):
+        tb.tbik_attention(Q, K, V, i32(c["cu_q"]), i32(c["cu_k"]), 1, c["scale"], False, max_seqlen_k=4096, verify_lengths=True)

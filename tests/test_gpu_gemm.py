@@ -251,7 +251,10 @@ def test_8b_shapes_invariance_and_sampled_parity(name):
     assert np.all(np.abs(y_gpu.astype(np.float64) - y_orc) <= 2 * (leaf * g + 8) * 2.0 ** -24 * A)
     ybf = gu.host_bf16_bits(tb.tbik_gemm(Xd, Wd, leaf, g, out_dtype=torch.bfloat16))[rows, cols]
     n_exc = gu.check_bf16_against_oracle(ybf, y_gpu, y_orc)
-    assert n_exc <= max(2, y_gpu.size // 100), n_exc
+    print("bf16 outputs that differ from bf16(oracle) across a rounding boundary: %d of %d (%s)" % (n_exc, y_gpu.size, name))
+    # ten times the fraction measured on this data (1, 5 and 12 of 15936: the longer the superleaf, the further the MFMA's
+    # order inside it drifts from the oracle's left-to-right sum, and the more often a rounding boundary falls in between)
+    assert n_exc <= {"oproj": 10, "downproj": 50, "downproj_k14336": 120}[name], n_exc
 
 
 def test_small_m_full_parity_oproj():
@@ -265,7 +268,42 @@ def test_small_m_full_parity_oproj():
     assert np.all(np.abs(y_gpu.astype(np.float64) - y_orc) <= 2 * (c["leaf"] + 8) * 2.0 ** -24 * A)
     ybf = gu.host_bf16_bits(tb.tbik_gemm(Xd, Wd, c["leaf"], 1, out_dtype=torch.bfloat16))
     n_exc = gu.check_bf16_against_oracle(ybf, y_gpu, y_orc)
-    assert n_exc <= y_gpu.size // 100
+    print("bf16 outputs that differ from bf16(oracle) across a rounding boundary: %d of %d (o_proj M = 64)" % (n_exc, y_gpu.size))
+    assert n_exc <= 400                           # measured: 39 of 262144
+
+
+def test_small_m_full_parity_downproj():
+    """M = 64 of the down_proj shape (superleaves of 768), every element against the oracle."""
+    c = syn.gemm_downproj(64)
+    leaf, g = c["leaf"], c["k_first"]
+    Xd, Wd = gu.dev_bf16(c["X"]), gu.dev_bf16(c["W"])
+    y_gpu = gu.host_f32(tb.tbik_gemm(Xd, Wd, leaf, g, out_dtype=torch.float32))
+    y_orc, _ = orc.gemm(c["X"], c["W"], leaf, g)
+    y64, A = gu.fp64_ref(c["X"], c["W"])
+    gu.check_fp32_against_fp64(y_gpu, y64, A)
+    assert np.all(np.abs(y_gpu.astype(np.float64) - y_orc) <= 2 * (leaf * g + 8) * 2.0 ** -24 * A)
+    ybf = gu.host_bf16_bits(tb.tbik_gemm(Xd, Wd, leaf, g, out_dtype=torch.bfloat16))
+    n_exc = gu.check_bf16_against_oracle(ybf, y_gpu, y_orc)
+    print("bf16 outputs that differ from bf16(oracle) across a rounding boundary: %d of %d (down_proj M = 64)" % (n_exc, y_gpu.size))
+    assert n_exc <= 1000                          # sampled at M = 4096: 5 of 15936
+
+
+def test_twenty_repetitions_give_one_output():
+    """The race detector: the tuned kernel keeps its own count of loads and stores in flight and reuses live LDS as the
+    output patch, so a race would show as a flipped bit now and then.  Twenty back-to-back calls of tbik_gemm and of
+    shard_partials(P = 8) + tree_combine at the full o_proj shape must all give the first call's bits."""
+    c = syn.gemm_oproj(4096)
+    leaf, g = c["leaf"], c["k_first"]
+    Xd, Wd = gu.dev_bf16(c["X"]), gu.dev_bf16(c["W"])
+    first = tb.tbik_gemm(Xd, Wd, leaf, g, out_dtype=torch.bfloat16).clone()
+    parts = torch.empty((8, 4096, c["N"]), dtype=torch.float32, device="cuda:0")
+    y = torch.empty_like(first)
+    for rep in range(20):
+        tb.tbik_gemm(Xd, Wd, leaf, g, out=y)
+        assert torch.equal(y.view(torch.int16), first.view(torch.int16)), ("tbik_gemm", rep)
+        tb.tbik_gemm_shard_partials(Xd, Wd, leaf, g, 8, out=parts)
+        tb.tbik_tree_combine(parts, out=y)
+        assert torch.equal(y.view(torch.int16), first.view(torch.int16)), ("shard_partials(8) + tree_combine", rep)
 
 
 def test_large_batch_and_ragged_width():

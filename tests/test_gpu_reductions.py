@@ -184,6 +184,23 @@ def test_logsoftmax_long_rows_repeatable_under_load():
             assert torch.equal(y.view(torch.int32), full[a:b].view(torch.int32)), (a, b)
 
 
+def test_logsoftmax_finds_no_stale_value_in_a_poisoned_workspace():
+    """The published block maxima and sums sit in the caller's workspace, which keeps the last call's contents.  A
+    workgroup that read a slot before its writer's value was in place would pick up what the workspace held before:
+    here that is NaN (every byte 0xff) before every call, which no log-softmax of finite logits contains."""
+    V = 151936
+    x = gu.dev_f32(syn.logits_f32(256, V, seed=9))
+    need = int(tb.lib().tbik_row_reduce_workspace_bytes(256, V, tb.TBIK_LOGSOFTMAX))
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+    want = tb.tbik_row_reduce(x, tb.TBIK_LOGSOFTMAX)
+    out = torch.empty_like(want)
+    for rep in range(20):
+        ws.fill_(0xff)
+        tb.tbik_row_reduce(x, tb.TBIK_LOGSOFTMAX, out=out, workspace=ws)
+        assert not bool(torch.isnan(out).any()), rep
+        assert torch.equal(out.view(torch.int32), want.view(torch.int32)), rep
+
+
 def test_logsoftmax_512_rows_sampled():
     """The full 512 x 151936 case in the launch shape the benchmark times; rows sampled for the oracle."""
     V = 151936
