@@ -58,15 +58,42 @@ hipError_t launch_tiled(const GemmArgs &a, int variant, hipStream_t s) {
     return a.x_dtype == TBIK_F32 ? launch_gemm_f32_tiled(a, variant, s) : launch_gemm_tiled(a, variant, s);
 }
 
-// Internal split of K across workgroups for shapes with too few output tiles to fill the GPU: the kernel is
-// launched as if the caller had asked for `split` shards (fp32 partials into the workspace) and the partials are
-// combined by the same tree (Theorem 1: identical bits).  A pure function of the shape, so that
-// tbik_gemm_workspace_bytes() can be evaluated without a device.
-int internal_split(int M, int N, int ns) {
-    const int64_t bm = (M > 64) ? 128 : (M > 32) ? 64 : 32;
+// Rows of the workgroup tile for a shape (pure): 32 for M <= 32, 64 for M <= 64, else 128 -- unless the 128-row tiles
+// would leave a quarter or more of the compute units without one while the 64-row tiles fill exactly one round: then
+// 64, which spares the K split (a second launch and an fp32 round trip of the partial sums).  Measured: o_proj
+// M = 512 30.6 -> 24.1 us, down_proj M = 512 72.7 -> 61.5 us; with two ragged rounds of 64-row tiles it loses.
+int tile_rows(int M, int N) {
+    if (M <= 32) return 32;
+    if (M <= 64) return 64;
+    const int64_t cols = ((int64_t)N + 127) / 128;
+    const int64_t tiles128 = (((int64_t)M + 127) / 128) * cols, tiles64 = (((int64_t)M + 63) / 64) * cols;
+    return (tiles128 < 192 && tiles64 >= 192 && tiles64 <= 256) ? 64 : 128;
+}
+
+// Internal split of K across workgroups (a pure function of the shape, so that tbik_gemm_workspace_bytes() can be
+// evaluated without a device): the kernel is launched as if the caller had asked for `split` shards (fp32 partials into
+// the workspace) and the partials are combined by the same tree (Theorem 1: identical bits).  Reasons to split: a
+// register-resident tree of more than 16 superleaves; fewer than 128 tiles (most compute units idle); and, for very
+// long K, rounds -- 256 compute units take the work items in rounds, so 320 tiles cost two rounds of whole-K tiles
+// unsplit but five rounds of quarter-K items split in four (32B-class down_proj, K = 25600: M = 1024 454 -> 323 us,
+// M = 512 218 -> 189 us, M = 128 78 -> 64 us).  The price of a split is the partials' round trip, the second launch and
+// a pipeline fill per item; at K <= 12288 splitting for rounds measured slower (o_proj M = 768: 31 -> 46 us), so there
+// only the first two reasons apply.
+int internal_split(int M, int N, int K, int ns) {
+    const int64_t bm = tile_rows(M, N);
     const int64_t tiles = ((M + bm - 1) / bm) * (((int64_t)N + 127) / 128);
     int split = 1;
     while (ns / split > 16 && split < TBIK_MAX_SHARDS) split *= 2;   // the tiled kernel walks at most 16 superleaves per shard
+    if (K >= 16384) {
+        int best = split;
+        double best_cost = 0;
+        for (int s = split; s <= ns && s <= 16; s *= 2) {
+            const double rounds = (double)((tiles * s + 255) / 256);
+            const double cost = rounds / s + (s > 1 ? 0.015 + 0.005 * s : 0.0);
+            if (s == split || cost < best_cost - 1e-9) { best = s; best_cost = cost; }
+        }
+        return best;
+    }
     if (tiles >= 128) return split;             // at least half of the 256 compute units already have a tile
     while (split < ns && split < 16 && tiles * split < 256) split *= 2;
     return split;
@@ -76,8 +103,9 @@ int pick_variant(const GemmArgs &a) {
     const int forced = g_forced_variant.load();
     if (forced != VARIANT_AUTO) return (forced == VARIANT_REFERENCE || tiled_supports(a, forced)) ? forced : VARIANT_REFERENCE;
     if (a.x_dtype == TBIK_F32) return gemm_f32_tiled_supports(a) ? VARIANT_AUTO : VARIANT_REFERENCE;    // the launcher picks the tile
-    if (a.M > 64 && gemm_tiled_supports(a, VARIANT_T128)) return VARIANT_T128;
-    if (a.M > 32 && gemm_tiled_supports(a, VARIANT_T64)) return VARIANT_T64;
+    const int rows = tile_rows(a.M, a.N);
+    if (rows == 128 && gemm_tiled_supports(a, VARIANT_T128)) return VARIANT_T128;
+    if (rows >= 64 && gemm_tiled_supports(a, VARIANT_T64)) return VARIANT_T64;
     if (gemm_tiled_supports(a, VARIANT_T32)) return VARIANT_T32;
     if (gemm_tiled_supports(a, VARIANT_T128)) return VARIANT_T128;
     return VARIANT_REFERENCE;
@@ -94,7 +122,7 @@ size_t tbik_gemm_workspace_bytes(int M, int N, int K, int leaf, int k_first) {
     int sl, ns;
     if (check_tree(M, N, K, leaf, k_first, 1, &sl, &ns) != TBIK_OK) return 0;
     // fp32 partials of the internal K split, if this shape uses one
-    const int split = internal_split(M, N, ns);
+    const int split = internal_split(M, N, K, ns);
     return split > 1 ? (size_t)split * (size_t)M * (size_t)N * sizeof(float) : 0;
 }
 
@@ -138,7 +166,7 @@ int gemm(int x_dtype, const void *X, int64_t ldx, const void *W, int64_t ldw, vo
 
     hipStream_t s = (hipStream_t)hip_stream;
     GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)W, ldw, nullptr, Y, ldy, y_dtype, M, N, K, sl, ns, 1, x_dtype};
-    const int split = internal_split(M, N, ns);
+    const int split = internal_split(M, N, K, ns);
     GemmArgs probe = a;
     probe.P = split;
     const int v = pick_variant(probe);
