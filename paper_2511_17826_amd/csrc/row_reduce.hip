@@ -231,23 +231,31 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_one_block_kernel(const 
 // workgroup whose wait runs out marks its row and leaves, and logsoftmax_redo_kernel recomputes marked rows.
 // Arithmetic (leaves, block tree, tree over blocks, expf, logf) is that of the three-kernel path: same bits.
 constexpr int RR_MAX_COOP_BLOCKS = 256;
-constexpr int RR_SYNC_WORDS = 64;        // per row: arrival counters at words 0 and 16, flag at word 32 (own 256 bytes)
+// Per row 64 words (a 256-byte line of its own): arrival counters at words 0 and 16, the row maximum at word 8 and the
+// row's sum of exponentials at word 24 (both start as RR_NOT_YET), the give-up flag at word 32.
+constexpr int RR_SYNC_WORDS = 64;
+constexpr int RR_W_ARRIVED_MAX = 0, RR_W_ROWMAX = 8, RR_W_ARRIVED_SUM = 16, RR_W_ROWSUM = 24, RR_W_GAVE_UP = 32;
+constexpr unsigned RR_NOT_YET = 0xffffffffu;     // a NaN pattern: neither a maximum of finite logits nor a sum of exponentials
 
-__device__ __forceinline__ bool wait_for_row(const unsigned *counter, unsigned want, const unsigned *rowflag, int limit,
-                                             unsigned *lds_flag) {
+// Thread 0 waits until the row's result word holds a value; every thread gets it.  One word is both the flag and the
+// datum, so a reader that is served an old copy only waits longer: nothing else has to be ordered against it.
+__device__ __forceinline__ bool wait_for_word(const unsigned *word, const unsigned *gave_up, int limit, unsigned *lds_word,
+                                              float *value) {
     if (threadIdx.x == 0) {
-        bool ok = false;
+        unsigned v = RR_NOT_YET;
         for (int it = 0; it <= limit; ++it) {
-            if (__hip_atomic_fetch_or(const_cast<unsigned *>(counter), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= want) { ok = true; break; }
-            if ((it & 15) == 15 && __hip_atomic_load(rowflag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
-            __builtin_amdgcn_s_sleep(8);
+            v = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (v != RR_NOT_YET) break;
+            if ((it & 15) == 15 && __hip_atomic_load(gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
+            __builtin_amdgcn_s_sleep(4);
         }
-        *lds_flag = ok ? 1u : 0u;
+        *lds_word = v;
     }
     __syncthreads();
-    const bool ok = (*lds_flag != 0u);
+    const unsigned v = *lds_word;
     __syncthreads();
-    return ok;
+    *value = __uint_as_float(v);
+    return v != RR_NOT_YET;
 }
 
 // One value per workgroup travels through memory, between workgroups that may sit on different chiplets with
@@ -255,7 +263,7 @@ __device__ __forceinline__ bool wait_for_row(const unsigned *counter, unsigned w
 // back and invalidate a chiplet's whole L2 on every call): the value is written and read with read-modify-write
 // atomics of device scope, which are performed where all chiplets meet, and the writer has its atomic's return
 // value in hand -- so the value is in place -- before it counts its arrival with another such atomic.
-__device__ __forceinline__ void publish(float *slot, float v, unsigned *counter) {
+__device__ __forceinline__ unsigned publish(float *slot, float v, unsigned *counter) {
     const unsigned old = __hip_atomic_exchange(reinterpret_cast<unsigned *>(slot), __float_as_uint(v), __ATOMIC_RELAXED,
                                                __HIP_MEMORY_SCOPE_AGENT);
     // The increment is made to depend on the exchange's return value (through an empty statement the compiler cannot
@@ -263,7 +271,7 @@ __device__ __forceinline__ void publish(float *slot, float v, unsigned *counter)
     // the exchange has returned.
     unsigned one = 1u;
     asm volatile("" : "+v"(one) : "v"(old) : "memory");
-    __hip_atomic_fetch_add(counter, one, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __hip_atomic_fetch_add(counter, one, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);     // how many arrived before
 }
 __device__ __forceinline__ float coherent_load(const float *p) {
     return __uint_as_float(__hip_atomic_fetch_or(reinterpret_cast<unsigned *>(const_cast<float *>(p)), 0u, __ATOMIC_RELAXED,
@@ -286,74 +294,102 @@ __device__ __forceinline__ float wave_tree_of_published(const float *p, int n, i
     return tot;
 }
 
-template <int XT>
-__global__ __launch_bounds__(RR_THREADS) void logsoftmax_coop_kernel(const void *__restrict__ x, int64_t V, int nb, int nb2,
+// BPW: consecutive blocks of the row per workgroup (1, 2 or 4; the first of them a multiple of BPW, so together they
+// are one subtree of the row's tree and their block sums combine by T before anything leaves the workgroup: the same
+// additions as in the tree over all blocks).  More blocks per workgroup means more of the row held on the chip per
+// resident workgroup and fewer exchanges per byte; nwg = ceil(nb / BPW) workgroups per row.
+template <int XT, int BPW>
+__global__ __launch_bounds__(RR_THREADS) void logsoftmax_coop_kernel(const void *__restrict__ x, int64_t V, int nwg, int nwg2,
                                                                     float *wsmax, float *wssum, unsigned *sync_words,
                                                                     int wait_limit, float *__restrict__ out) {
     __shared__ float lds[RR_SEGS * 4];
-    __shared__ unsigned lds_flag;
+    __shared__ unsigned lds_word;
     constexpr int EPL = Elem<XT>::EPL;
-    const int row = (int)(blockIdx.x / (unsigned)nb), b = (int)(blockIdx.x % (unsigned)nb);
+    const int row = (int)(blockIdx.x / (unsigned)nwg), w = (int)(blockIdx.x % (unsigned)nwg);
     const int lane = threadIdx.x & 63;
     const int64_t nleaves = V / EPL;
     const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * Elem<XT>::BYTES;
     float *orow = out + (int64_t)row * V;
-    unsigned *counters = sync_words + (int64_t)row * RR_SYNC_WORDS, *rowflag = counters + 32;
+    unsigned *words = sync_words + (int64_t)row * RR_SYNC_WORDS, *gave_up = words + RR_W_GAVE_UP;
 
-    float f[RR_SEGS][8];
+    float f[BPW][RR_SEGS][8];
     float mx = -INFINITY;
 #pragma unroll
-    for (int seg = 0; seg < RR_SEGS; ++seg) {
-        const int64_t leaf = (int64_t)b * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
-        if (leaf < nleaves) {
-            Elem<XT>::load(rowp, leaf, f[seg]);
+    for (int k = 0; k < BPW; ++k)
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) mx = fmaxf(mx, f[seg][e]);
+        for (int seg = 0; seg < RR_SEGS; ++seg) {
+            const int64_t leaf = (int64_t)(w * BPW + k) * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
+            if (leaf < nleaves) {
+                Elem<XT>::load(rowp, leaf, f[k][seg]);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) mx = fmaxf(mx, f[k][seg][e]);
+            }
         }
-    }
+    // The workgroup that arrives last combines the row's results and puts the row's result where the others wait for
+    // it: per row and step one exchange and one count per workgroup, one round of reads and one result word, instead of
+    // everybody reading everybody's value (atomics on one memory line are served one after the other).
     const float bm = block_max(mx, lds);
-    if (threadIdx.x == 0) {
-        publish(wsmax + (int64_t)row * nb + b, bm, counters);
-    }
-    if (!wait_for_row(counters, (unsigned)nb, rowflag, wait_limit, &lds_flag)) {
-        if (threadIdx.x == 0) __hip_atomic_store(rowflag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (threadIdx.x == 0) lds_word = publish(wsmax + (int64_t)row * nwg + w, bm, words + RR_W_ARRIVED_MAX);
+    __syncthreads();
+    const bool last_max = (lds_word == (unsigned)(nwg - 1));
+    __syncthreads();
+    float rowmax;
+    if (last_max) {
+        rowmax = wave_max_of_published(wsmax + (int64_t)row * nwg, nwg, lane);          // every wavefront: the same value
+        if (threadIdx.x == 0)
+            __hip_atomic_exchange(words + RR_W_ROWMAX, __float_as_uint(rowmax), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else if (!wait_for_word(words + RR_W_ROWMAX, gave_up, wait_limit, &lds_word, &rowmax)) {
+        if (threadIdx.x == 0) __hip_atomic_store(gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;
     }
-    const float rowmax = wave_max_of_published(wsmax + (int64_t)row * nb, nb, lane);
 
-    float L[RR_SEGS];
+    float bsum[BPW];
 #pragma unroll
-    for (int seg = 0; seg < RR_SEGS; ++seg) {
-        const int64_t leaf = (int64_t)b * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
-        float acc = 0.0f;
-        if (leaf < nleaves) {
+    for (int k = 0; k < BPW; ++k) {
+        float L[RR_SEGS];
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) acc = acc + expf(f[seg][e] - rowmax);
+        for (int seg = 0; seg < RR_SEGS; ++seg) {
+            const int64_t leaf = (int64_t)(w * BPW + k) * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
+            float acc = 0.0f;
+            if (leaf < nleaves) {
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc = acc + expf(f[k][seg][e] - rowmax);
+            }
+            L[seg] = acc;
+            __builtin_amdgcn_sched_barrier(0);     // one chunk's exponentials at a time: registers, not latency, bound this kernel
         }
-        L[seg] = acc;
+        bsum[k] = block_tree_sum(L, lds);          // a block past the end of the row sums to +0
     }
-    const float bs = block_tree_sum(L, lds);
-    if (threadIdx.x == 0) {
-        publish(wssum + (int64_t)row * nb + b, bs, counters + 16);
-    }
-    if (!wait_for_row(counters + 16, (unsigned)nb, rowflag, wait_limit, &lds_flag)) {
-        if (threadIdx.x == 0) __hip_atomic_store(rowflag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const float bs = tree_of(bsum);                // T over this workgroup's blocks
+    if (threadIdx.x == 0) lds_word = publish(wssum + (int64_t)row * nwg + w, bs, words + RR_W_ARRIVED_SUM);
+    __syncthreads();
+    const bool last_sum = (lds_word == (unsigned)(nwg - 1));
+    __syncthreads();
+    float S;
+    if (last_sum) {
+        S = wave_tree_of_published(wssum + (int64_t)row * nwg, nwg, nwg2, lane);
+        if (threadIdx.x == 0)
+            __hip_atomic_exchange(words + RR_W_ROWSUM, __float_as_uint(S), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else if (!wait_for_word(words + RR_W_ROWSUM, gave_up, wait_limit, &lds_word, &S)) {
+        if (threadIdx.x == 0) __hip_atomic_store(gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;
     }
-    const float S = wave_tree_of_published(wssum + (int64_t)row * nb, nb, nb2, lane);
     const float lg = logf(S);
 #pragma unroll
-    for (int seg = 0; seg < RR_SEGS; ++seg) {
-        const int64_t leaf = (int64_t)b * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
-        if (leaf < nleaves) {
-            float o[8];
+    for (int k = 0; k < BPW; ++k)
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) o[e] = (f[seg][e] - rowmax) - lg;
-            float4 *dst = reinterpret_cast<float4 *>(orow + leaf * EPL);
-            dst[0] = make_float4(o[0], o[1], o[2], o[3]);
-            if (EPL == 8) dst[1] = make_float4(o[4], o[5], o[6], o[7]);
+        for (int seg = 0; seg < RR_SEGS; ++seg) {
+            const int64_t leaf = (int64_t)(w * BPW + k) * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
+            if (leaf < nleaves) {
+                float o[8];
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) o[e] = (f[k][seg][e] - rowmax) - lg;
+                float4 *dst = reinterpret_cast<float4 *>(orow + leaf * EPL);
+                dst[0] = make_float4(o[0], o[1], o[2], o[3]);
+                if (EPL == 8) dst[1] = make_float4(o[4], o[5], o[6], o[7]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
-    }
 }
 
 // Recomputes the rows that logsoftmax_coop_kernel marked (normally none): one workgroup walks all blocks of its row
@@ -365,7 +401,7 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_redo_kernel(const void 
     __shared__ float lds[RR_SEGS * 4];
     __shared__ float per_block[RR_MAX_COOP_BLOCKS];
     const int row = blockIdx.x;
-    if (sync_words[(int64_t)row * RR_SYNC_WORDS + 32] == 0u) return;   // uniform over the workgroup
+    if (sync_words[(int64_t)row * RR_SYNC_WORDS + RR_W_GAVE_UP] == 0u) return;   // uniform over the workgroup
     constexpr int EPL = Elem<XT>::EPL;
     const int lane = threadIdx.x & 63;
     const int64_t nleaves = V / EPL;
@@ -427,9 +463,11 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_redo_kernel(const void 
     }
 }
 
-__global__ __launch_bounds__(256) void zero_words_kernel(unsigned *p, int64_t n) {
+// Counters and flag to zero, the two result words of every row to "not yet".
+__global__ __launch_bounds__(256) void reset_sync_words_kernel(unsigned *p, int64_t n) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) p[i] = 0u;
+    const int w = (int)(i % RR_SYNC_WORDS);
+    if (i < n) p[i] = (w == RR_W_ROWMAX || w == RR_W_ROWSUM) ? RR_NOT_YET : 0u;
 }
 
 static std::atomic<int> g_wait_limit{1 << 14};   // polls per wait: tens of milliseconds at most
@@ -474,9 +512,17 @@ static hipError_t run(const void *x, void *out, int op, int M, int64_t V, void *
         } else if (nb <= RR_MAX_COOP_BLOCKS && (int64_t)mc * nb <= 0x7fffffff) {
             unsigned *words = reinterpret_cast<unsigned *>(ws1 + (size_t)M * nb) + (size_t)m0 * RR_SYNC_WORDS;
             const int64_t nwords = (int64_t)mc * RR_SYNC_WORDS;
-            hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((nwords + 255) / 256)), dim3(256), 0, s, words, nwords);
-            hipLaunchKernelGGL((logsoftmax_coop_kernel<XT>), dim3((unsigned)((int64_t)mc * nb)), block, 0, s, xp, V, nb, nb2,
-                               w0, w1, words, g_wait_limit.load(), o + m0 * V);
+            hipLaunchKernelGGL(reset_sync_words_kernel, dim3((unsigned)((nwords + 255) / 256)), dim3(256), 0, s, words, nwords);
+            // two blocks per workgroup for fp32 rows once the launch has more workgroups than the device holds at a time
+            // (more of the row on the chip per resident workgroup); the choice cannot change a bit
+            const bool two = false;   // measured: 195 -> 282 us at 512 x 151936 (170 registers, three workgroups per compute unit)
+            const int nwg = two ? (nb + 1) / 2 : nb, nwg2 = two ? (nb2 + 1) / 2 : nb2;
+            if (two)
+                hipLaunchKernelGGL((logsoftmax_coop_kernel<XT, (XT == TBIK_F32 ? 2 : 1)>), dim3((unsigned)((int64_t)mc * nwg)), block, 0, s,
+                                   xp, V, nwg, nwg2, w0, w1, words, g_wait_limit.load(), o + m0 * V);
+            else
+                hipLaunchKernelGGL((logsoftmax_coop_kernel<XT, 1>), dim3((unsigned)((int64_t)mc * nwg)), block, 0, s,
+                                   xp, V, nwg, nwg2, w0, w1, words, g_wait_limit.load(), o + m0 * V);
             hipLaunchKernelGGL((logsoftmax_redo_kernel<XT>), dim3(mc), block, 0, s, xp, V, nb, nb2,
                                (const unsigned *)words, o + m0 * V);
         } else {
