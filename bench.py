@@ -324,6 +324,31 @@ def metric_shapes(tb, syn, torch, np, to_dev, X, W):
         streaming_line("downproj_M%d_weights_from_hbm" % M, Xd, Wd, M, 256, 3, 4)    # 4 x 96 MiB
     del Xd, Wd
 
+    # The MLP's first GEMM with the gated activation applied before anything is stored (8B class: K = 4096,
+    # I = 12288), next to the same work as a GEMM into [M, 2 I] followed by the activation kernel.
+    I_mlp = 12288
+    rng_w = torch.Generator(device=dev)
+    rng_w.manual_seed(6)
+    Wgu = (torch.randn((X.shape[1], 2 * I_mlp), generator=rng_w, device=dev, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+    for M in (512, 4096):
+        act = torch.empty((M, I_mlp), dtype=torch.bfloat16, device=dev)
+        gu = torch.empty((M, 2 * I_mlp), dtype=torch.bfloat16, device=dev)
+        ws = torch.empty(max(256, tb.gemm_swiglu_workspace_bytes(M, I_mlp, X.shape[1], 256, 1)), dtype=torch.uint8, device=dev)
+
+        def two_calls():
+            tb.tbik_gemm(X[:M], Wgu, 256, 1, out=gu)
+            tb.tbik_silu_mul(gu[:, :I_mlp], gu[:, I_mlp:], out=act)
+        # interleaved, so that both see the same clocks
+        t_f, t_u = 1e9, 1e9
+        for _ in range(3):
+            t_f = min(t_f, best_ms(lambda: tb.tbik_gemm_swiglu(X[:M], Wgu, 256, 1, out=act, workspace=ws), 4, torch))
+            t_u = min(t_u, best_ms(two_calls, 4, torch))
+        tf = 2.0 * M * X.shape[1] * 2 * I_mlp / (t_f * 1e-3) / 1e12
+        res["gateup_swiglu_M%d" % M] = {"ms": round(t_f, 4), "tflops": round(tf, 1), "frac": round(tf / PEAK_BF16_TFLOPS, 4),
+                                        "ms_gemm_then_activation": round(t_u, 4)}
+        del act, gu, ws
+    del Wgu
+
     def hbm_line(name, calls, byts, iters):
         cold = best_ms(rotating(calls), iters * len(calls), torch, warm=len(calls))
         warm = best_ms(calls[0], iters, torch)

@@ -108,6 +108,47 @@ int tbik_tree_combine(const float *partials, int P, void *Y, int64_t ldy, tbik_d
                       int M, int N, void *hip_stream);
 
 /*
+ * The gated activation between the two GEMMs of the MLP block (implementation appendix, "other kernels":
+ * SiLU is one of the position-wise kernels that every configuration shares):
+ *   act[m][i] = round16( SiLU(gate[m][i]) * up[m][i] ),   SiLU(g) = g / (1 + e^-g)
+ * in fp32: e^-g and the reciprocal are the hardware's approximate instructions (about one fp32 ulp each), the two
+ * products are rounded multiplications, and the result is rounded once to the tensors' format.  An output is one of
+ * the two 16-bit neighbours of the exact value (nearly always the nearest); for gate below about -87 it may be zero
+ * where the exact value is below 1e-36 in magnitude.  Position-wise: an element's bits depend on its own gate and up
+ * only, and every entry point of this library that applies the activation gives the same bits.
+ *
+ *   gate, up, act   device, 16-bit of format `dtype` (TBIK_BF16 or TBIK_F16), [M, I] with leading dimensions
+ *                   ldg, ldu, lda >= I; gate and up may be the two halves of one [M, 2 I] buffer; act may not
+ *                   overlap them unless it is exactly gate or exactly up with the same leading dimension
+ *   16-byte aligned pointers, I and leading dimensions multiples of 8 take the vector path; anything else works.
+ * Errors: NULL, SHAPE, DTYPE, HIP.
+ */
+int tbik_silu_mul(const void *gate, int64_t ldg, const void *up, int64_t ldu, void *act, int64_t lda,
+                  tbik_dtype dtype, int M, int I, void *hip_stream);
+
+/*
+ * The first GEMM of the MLP block with the activation applied before anything is stored (Sec. 3.3: gate_proj and
+ * up_proj are column-parallel, each output element is a whole-K sum; Sec. 4.2 / App. D.1 for the order of that sum):
+ *   gate = round16( X W_gu[:, 0:I] ),  up = round16( X W_gu[:, I:2I] )     each exactly tbik_gemm's output for that half
+ *   act  = tbik_silu_mul(gate, up)                                         bit for bit
+ * gate and up are never stored as 16-bit tensors: for batches that fill the chip with 128-row tiles the activation is
+ * the GEMM kernel's epilogue (the fp32 accumulators of a channel's gate and up columns sit in one lane); for a K split
+ * it is applied by the kernel that combines the fp32 partial sums; other shapes pass through the workspace.  The bits
+ * of row m of act depend only on row m of X and on W_gu, as for tbik_gemm.
+ *
+ *   X      device, 16-bit, [M, ldx], ldx >= K          W_gu   device, 16-bit, [K, ldw], ldw >= 2 I: gate columns, then up
+ *   act    device, 16-bit, [M, lda], lda >= I          dtype  TBIK_BF16 or TBIK_F16: the format of all three
+ *   I      a multiple of 8; ldx, ldw below 2^22
+ *   workspace  device, 256-byte aligned, at least tbik_gemm_swiglu_workspace_bytes(...) bytes (may be NULL if that is 0)
+ *   Alignment as for tbik_gemm; act 2 bytes (16 bytes and lda % 8 == 0 for vector stores).
+ * Errors: NULL, SHAPE, DTYPE, ALIGN, WORKSPACE, HIP.
+ */
+size_t tbik_gemm_swiglu_workspace_bytes(int M, int I, int K, int leaf, int k_first);
+int tbik_gemm_swiglu(const void *X, int64_t ldx, const void *W_gu, int64_t ldw, void *act, int64_t lda,
+                     tbik_dtype dtype, int M, int I, int K, int leaf, int k_first,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Batch-invariant RMSNorm (App. B: every row is reduced on its own in a fixed order), with the
  * tree order of App. C along the row:
  *   ss = TreeSum_i(x_i^2),  r = 1 / sqrt(ss / H + eps),  y_i = bf16((x_i * r) * w_i)

@@ -26,6 +26,9 @@
  *   tbik_oracle_row_*        App. B (one row = one fixed reduction order,
  *                            independent of the batch) with the tree order of
  *                            App. C applied along the row.
+ *   tbik_oracle_silu_mul     the gated activation between the two MLP GEMMs (implementation appendix,
+ *                            "other kernels": SiLU is one of the position-wise kernels both sides share):
+ *                            act = round16( SiLU(gate) * up ), SiLU(g) = g / (1 + e^-g), in fp32.
  *   tbik_oracle_attention    the attention rule of the implementation appendix (fixed
  *                            key tile, one routine for prefill and decode), as the
  *                            streaming-softmax recurrence over tiles at absolute positions.
@@ -38,7 +41,8 @@
  * P and M, exact-integer inputs against int64 arithmetic, fp64 brute force
  * within the summation-tree error bound, one-superleaf == sequential sum,
  * leaf 1 == level-by-level pairwise sum, closed forms for RMSNorm and
- * log-softmax, numpy's float16 for the binary16 conversions, the fp64 softmax
+ * log-softmax, the fp64 definition and exact special cases of the gated activation,
+ * numpy's float16 for the binary16 conversions, the fp64 softmax
  * definition and exact special cases for attention.  No function here is
  * "parity unpinned".
  */
@@ -496,6 +500,27 @@ int tbik_oracle_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int M
         }
         free(sq);
     }
+    return 0;
+}
+
+/*
+ * The gated activation of the MLP block, element by element (implementation appendix, "other kernels"; the
+ * model's MLP is down_proj( SiLU(gate_proj x) * up_proj x )):
+ *   s   = g / (1 + exp(-g))            SiLU, in fp32: expf, one addition, one correctly rounded division
+ *   act = round16( s * u )             one fp32 product, one rounding to the storage format
+ * gate, up and act are [M, I] with leading dimensions ldg, ldu, lda (elements).  Position-wise, so it is
+ * batch invariant whatever the schedule; only the order of the three fp32 roundings is fixed here.
+ */
+int tbik_oracle_silu_mul(const uint16_t *gate, long ldg, const uint16_t *up, long ldu, uint16_t *act, long lda,
+                         int M, int I, int fmt) {
+    if (M < 0 || I < 0) return -1;
+    for (long m = 0; m < M; ++m)
+        for (long i = 0; i < I; ++i) {
+            const float g = widen16(gate[m * ldg + i], fmt);
+            const float u = widen16(up[m * ldu + i], fmt);
+            const float s = g / (1.0f + expf(-g));
+            act[m * lda + i] = round16(s * u, fmt);
+        }
     return 0;
 }
 

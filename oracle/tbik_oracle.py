@@ -82,6 +82,8 @@ def lib():
         L.tbik_oracle_treesum.argtypes = [f32p, C.c_long, C.c_int]
         L.tbik_oracle_rmsnorm.restype = C.c_int
         L.tbik_oracle_rmsnorm.argtypes = [u16p, u16p, u16p, C.c_int, C.c_int, C.c_float, C.c_int, C.c_int]
+        L.tbik_oracle_silu_mul.restype = C.c_int
+        L.tbik_oracle_silu_mul.argtypes = [u16p, C.c_long, u16p, C.c_long, u16p, C.c_long, C.c_int, C.c_int, C.c_int]
         L.tbik_oracle_sumsq16.restype = C.c_float
         L.tbik_oracle_sumsq16.argtypes = [u16p, C.c_int, C.c_int, C.c_int]
         L.tbik_oracle_row_sum.restype = C.c_int
@@ -314,6 +316,18 @@ def combine_residual_rmsnorm(partials, residual_bits, weight_bits, eps: float = 
     h32 = (widen(y16) + widen(residual_bits)).astype(np.float32)          # one IEEE binary32 addition per element
     hbits = narrow(h32)
     return hbits, rmsnorm(hbits, weight_bits, eps, fmt=fmt)
+
+
+def silu_mul(gate, up, fmt: str = "bf16") -> np.ndarray:
+    """act = round16(SiLU(gate) * up) on [M, I] arrays of 16-bit patterns of format `fmt` (fp32 steps)."""
+    gate, gp = _u16(gate)
+    up, upp = _u16(up)
+    assert gate.shape == up.shape and gate.ndim == 2
+    M, I = gate.shape
+    act = np.empty((M, I), dtype=np.uint16)
+    rc = lib().tbik_oracle_silu_mul(gp, I, upp, I, act.ctypes.data_as(C.POINTER(C.c_uint16)), I, M, I, FORMATS[fmt])
+    assert rc == 0
+    return act
 
 
 def sumsq16(row, leaf: int = LEAF_BF16, fmt: str = "bf16") -> np.float32:

@@ -34,6 +34,11 @@ SIGNATURES = {
     "tbik_row_reduce": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int64,
                                   C.c_void_p, C.c_size_t, C.c_void_p]),
     "tbik_row_reduce_static": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_void_p]),
+    "tbik_silu_mul": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int,
+                                C.c_void_p]),
+    "tbik_gemm_swiglu": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int,
+                                   C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tbik_gemm_swiglu_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]),
     "tbik_gemm_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]),
     "tbik_row_reduce_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int64, C.c_int]),
     "tbik_gemm_reference": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64,
@@ -244,6 +249,48 @@ def tbik_gemm_shard_partials_f32(X: torch.Tensor, W: torch.Tensor, leaf: int, k_
                                  out: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
     """partials[p] = subtree sum of K-shard p (fp32 [P, M, N]); fp32 operands."""
     return _gemm_shard_partials("tbik_gemm_shard_partials_f32", torch.float32, X, W, leaf, k_first, P, out, workspace)
+
+
+def tbik_silu_mul(gate: torch.Tensor, up: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """act = SiLU(gate) * up on [M, I] bf16 or fp16 tensors (row-major; views into one [M, 2 I] buffer are fine)."""
+    _rowmajor(gate, "gate"); _rowmajor(up, "up")
+    assert gate.dtype == up.dtype and gate.dtype in (torch.bfloat16, torch.float16) and gate.shape == up.shape
+    M, I = gate.shape
+    if out is None:
+        out = torch.empty((M, I), dtype=gate.dtype, device=gate.device)
+    _rowmajor(out, "out")
+    assert out.dtype == gate.dtype and out.shape == (M, I)
+    st = lib().tbik_silu_mul(gate.data_ptr(), gate.stride(0), up.data_ptr(), up.stride(0), out.data_ptr(), out.stride(0),
+                             _dt(gate), M, I, _stream())
+    _check(st, "tbik_silu_mul")
+    return out
+
+
+def gemm_swiglu_workspace_bytes(M, I, K, leaf, k_first=1) -> int:
+    return int(lib().tbik_gemm_swiglu_workspace_bytes(M, I, K, leaf, k_first))
+
+
+def tbik_gemm_swiglu(X: torch.Tensor, W_gu: torch.Tensor, leaf: int, k_first: int = 1, out: torch.Tensor | None = None,
+                     workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """act = SiLU(X @ W_gu[:, :I]) * (X @ W_gu[:, I:]) in the tree order; W_gu is [K, 2 I], gate columns first."""
+    _rowmajor(X, "X"); _rowmajor(W_gu, "W_gu")
+    assert X.dtype == W_gu.dtype and X.dtype in (torch.bfloat16, torch.float16)
+    M, K = X.shape
+    assert W_gu.shape[0] == K and W_gu.shape[1] % 2 == 0
+    I = W_gu.shape[1] // 2
+    if out is None:
+        out = torch.empty((M, I), dtype=X.dtype, device=X.device)
+    _rowmajor(out, "out")
+    assert out.dtype == X.dtype and out.shape == (M, I)
+    if workspace is None:
+        need = gemm_swiglu_workspace_bytes(M, I, K, leaf, k_first)
+        if need:
+            workspace = _workspace(need, X.device)
+    st = lib().tbik_gemm_swiglu(X.data_ptr(), X.stride(0), W_gu.data_ptr(), W_gu.stride(0), out.data_ptr(), out.stride(0),
+                                _dt(X), M, I, K, leaf, k_first, workspace.data_ptr() if workspace is not None else None,
+                                workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream())
+    _check(st, "tbik_gemm_swiglu")
+    return out
 
 
 def tbik_tree_combine(partials: torch.Tensor, out_dtype=torch.bfloat16, out: torch.Tensor | None = None) -> torch.Tensor:

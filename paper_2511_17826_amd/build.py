@@ -17,7 +17,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtbik.so")
 
-SOURCES = ["tbik_api.hip", "gemm_reference.hip", "gemm_tiled.hip", "gemm_f32.hip", "combine.hip", "rmsnorm.hip", "row_reduce.hip",
+SOURCES = ["tbik_api.hip", "gemm_reference.hip", "gemm_tiled.hip", "gemm_f32.hip", "combine.hip", "activation.hip", "rmsnorm.hip", "row_reduce.hip",
            "attention.hip"]
 
 # -ffp-contract=off: a tree addition or an RMSNorm multiply must never be fused into an FMA.

@@ -64,6 +64,7 @@ struct TiledParams {
     int work;                   // tiles * shards
     int vector_stores;          // outputs are 16-byte aligned with 16-byte aligned rows
     int stream_stores;          // fp32 outputs bypass the caches (partials too large to stay there until they are combined)
+    int swiglu;                 // W is [gate | up] ([K, 2 I], N = 2 I); Y is act [M, I] = SiLU(gate) * up, 16-bit
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -106,7 +107,9 @@ void gemm_tiled_kernel(const TiledParams p) {
     constexpr int WCOLS = 32 * NT;                         // columns of a wavefront's tile
     constexpr int STORES_F32 = MT * (32 * WCOLS / 4 / 64);   // 16-byte store instructions per wavefront and tile
     constexpr int STORES_BF16 = MT * (32 * WCOLS / 8 / 64);
-    static_assert(LOADS_PER_STAGE * (RING - 3) + STORES_F32 < 64 && STORES_F32 != STORES_BF16, "vmcnt range");
+    constexpr int STORES_ACT = NT == 2 ? MT * 2 : -2;         // gated activation (NT == 2 only): 32 x 32 values of 16 bits per block
+    static_assert(LOADS_PER_STAGE * (RING - 3) + STORES_F32 < 64 && STORES_F32 != STORES_BF16 && STORES_BF16 != STORES_ACT,
+                  "vmcnt range");
     constexpr int LANE_BIAS = 4096;            // keeps every biased lane offset non-negative
     unsigned aoff[A_LOADS], boff[B_LOADS];     // per-lane byte offsets from the uniform stage pointers
     const char *a_ptr = nullptr, *b_ptr = nullptr;   // stage pointers of the stage to load next (b_ptr: minus LANE_BIAS)
@@ -119,7 +122,10 @@ void gemm_tiled_kernel(const TiledParams p) {
         const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
         const int64_t kbase = (int64_t)shard * p.k_per_shard;
         a_ptr = uniform_pointer(reinterpret_cast<const char *>(p.X + (int64_t)m0 * p.ldx + kbase));
-        b_ptr = uniform_pointer(reinterpret_cast<const char *>(p.W + kbase * p.ldw + n0) - LANE_BIAS);
+        // Gated activation: the 128 columns of a tile are, per wavefront column, 32 gate channels and the same 32 up
+        // channels (a lane then holds gate and up of one channel in its two column blocks), taken from the two halves
+        // of W; the tile starts at channel n0 / 2.
+        b_ptr = uniform_pointer(reinterpret_cast<const char *>(p.W + kbase * p.ldw + (p.swiglu ? n0 / 2 : n0)) - LANE_BIAS);
 #pragma unroll
         for (int j = 0; j < A_LOADS; ++j) {
             const int r = (wave * A_LOADS + j) * 8 + (lane >> 3);
@@ -130,7 +136,8 @@ void gemm_tiled_kernel(const TiledParams p) {
         for (int j = 0; j < B_LOADS; ++j) {
             const int kk = (wave * B_LOADS + j) * 4 + (lane >> 4);
             const int c = (lane & 15) ^ ((lane >> 4) << 2);
-            boff[j] = (unsigned)(kk * (int)p.ldw + min(c * 8, p.N - 8 - n0)) * 2u + (unsigned)(LANE_BIAS - j * 1024);
+            const int col = p.swiglu ? ((c >> 2) & 1) * (p.N / 2) + (c >> 3) * 32 + (c & 3) * 8 : min(c * 8, p.N - 8 - n0);
+            boff[j] = (unsigned)(kk * (int)p.ldw + col) * 2u + (unsigned)(LANE_BIAS - j * 1024);
         }
     };
 
@@ -249,6 +256,7 @@ void gemm_tiled_kernel(const TiledParams p) {
         } else {                                                     // first stage after an epilogue
             if (stores_in_flight == STORES_F32) wait_loads_and_barrier<ALLOW + STORES_F32>();
             else if (stores_in_flight == STORES_BF16) wait_loads_and_barrier<ALLOW + STORES_BF16>();
+            else if (stores_in_flight == STORES_ACT) wait_loads_and_barrier<ALLOW + STORES_ACT>();
             else wait_loads_and_barrier<0>();
             stores_in_flight = 0;
         }
@@ -317,7 +325,40 @@ void gemm_tiled_kernel(const TiledParams p) {
             // per store), and a store's address is a wave-uniform base plus a 32-bit lane offset.
             const int wm_u = wave_u / WN, wn_u = wave_u % WN;          // the same numbers as wm, wn, known to be uniform
             const int col0 = n0 + wn_u * WCOLS;
-            if (to_bf16) {
+            if (NT == 2 && p.swiglu) {
+                // Gate and up of a channel sit in the lane's two column blocks: both are rounded as the 16-bit outputs
+                // of two separate GEMMs would be, the activation is applied, and the 32 x 32 block goes through the patch.
+                constexpr int CPR = 4, RPI = 16, N_IT = 2;
+                const int lrow = lane / CPR, lc = lane % CPR;
+                const float *rd = patch + lrow * 32 + lc * 8;
+                const unsigned lane_off = (unsigned)(lrow * (int)p.ldy + lc * 8) * 2u;
+                const int64_t it_step = (int64_t)RPI * p.ldy * 2;
+#pragma unroll
+                for (int a = 0; a < MT; ++a) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        patch[(8 * (r >> 2) + 4 * lg + (r & 3)) * 32 + li] =
+                            silu_mul(through_16_bits<F16>(acc.t[a][0][r]), through_16_bits<F16>(acc.t[a][NT - 1][r]));
+                    f32x4 lo[N_IT], hi[N_IT];
+#pragma unroll
+                    for (int it = 0; it < N_IT; ++it) {
+                        lo[it] = *reinterpret_cast<const f32x4 *>(rd + it * RPI * 32);
+                        hi[it] = *reinterpret_cast<const f32x4 *>(rd + it * RPI * 32 + 4);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    char *base = reinterpret_cast<char *>(reinterpret_cast<uint16_t *>(p.Y) +
+                                                          (int64_t)(m0 + (wm_u * MT + a) * 32) * p.ldy + n0 / 2 + wn_u * 32);
+#pragma unroll
+                    for (int it = 0; it < N_IT; ++it) {
+                        u32x4 o;
+                        o[0] = pack_16x2<F16>(lo[it][0], lo[it][1]);
+                        o[1] = pack_16x2<F16>(lo[it][2], lo[it][3]);
+                        o[2] = pack_16x2<F16>(hi[it][0], hi[it][1]);
+                        o[3] = pack_16x2<F16>(hi[it][2], hi[it][3]);
+                        *reinterpret_cast<u32x4 *>(base + it * it_step + lane_off) = o;
+                    }
+                }
+            } else if (to_bf16) {
                 constexpr int CPR = WCOLS / 8, RPI = 64 / CPR, N_IT = 32 / RPI;      // 16-byte chunks per row, rows per store
                 const int lrow = lane / CPR, lc = lane % CPR;
                 const float *rd = patch + lrow * WCOLS + lc * 8;
@@ -380,7 +421,20 @@ void gemm_tiled_kernel(const TiledParams p) {
                     }
                 }
             }
-            stores_in_flight = to_bf16 ? STORES_BF16 : STORES_F32;
+            stores_in_flight = (NT == 2 && p.swiglu) ? STORES_ACT : to_bf16 ? STORES_BF16 : STORES_F32;
+        } else if (NT == 2 && p.swiglu) {                    // ragged last row tile
+            const int col = n0 / 2 + wn * 32 + li;
+#pragma unroll
+            for (int a = 0; a < MT; ++a) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = m0 + (wm * MT + a) * 32 + 8 * (r >> 2) + 4 * lg + (r & 3);
+                    if (row >= p.M) continue;
+                    const float v = silu_mul(through_16_bits<F16>(acc.t[a][0][r]), through_16_bits<F16>(acc.t[a][NT - 1][r]));
+                    reinterpret_cast<uint16_t *>(p.Y)[(int64_t)row * p.ldy + col] = (uint16_t)f32_to_16_bits<F16>(v);
+                }
+            }
+            stores_in_flight = -1;
         } else {
 #pragma unroll
             for (int a = 0; a < MT; ++a) {
@@ -420,6 +474,7 @@ bool gemm_tiled_supports(const GemmArgs &a, int variant) {
     if (a.N % 8 != 0 || a.superleaf % BK != 0) return false;
     if (levels_for(a.ns / a.P) > 4) return false;
     if (a.ldx >= (1 << 22) || a.ldw >= (1 << 22)) return false;   // per-lane byte offsets of a tile stay below 2^31
+    if (a.swiglu && (variant != VARIANT_T128 || a.P != 1 || a.partials || a.N % 128 != 0 || a.y_dtype != a.x_dtype)) return false;
     return true;
 }
 
@@ -443,6 +498,7 @@ static hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
     p.X = a.X; p.W = a.W; p.partials = a.partials; p.Y = (a.P == 1) ? a.Y : nullptr;
     p.ldx = a.ldx; p.ldw = a.ldw; p.ldy = a.ldy;
     p.M = a.M; p.N = a.N;
+    p.swiglu = (NT == 2) ? a.swiglu : 0;
     p.y_bf16 = (a.y_dtype != TBIK_F32);                  // 16-bit output, in the operands' format
     p.stages_per_superleaf = a.superleaf / BK;
     p.ns_per_shard = a.ns / a.P;
@@ -457,7 +513,7 @@ static hipError_t launch_shape(const GemmArgs &a, hipStream_t s) {
     const size_t lds = RING * ((size_t)BM * A_ROW + (size_t)BK * B_ROW);   // the output patch reuses a stage slot
     {
         const void *out = p.partials ? (const void *)p.partials : p.Y;
-        const int64_t ld_bytes = p.partials ? (int64_t)a.N * 4 : a.ldy * (p.y_bf16 ? 2 : 4);
+        const int64_t ld_bytes = p.partials ? (int64_t)a.N * 4 : a.ldy * (p.y_bf16 ? 2 : 4);   // act: 16-byte chunks of 8 channels
         p.vector_stores = ((reinterpret_cast<uintptr_t>(out) & 15) == 0) && (ld_bytes % 16 == 0);
         // Partials of many shards exceed the 256 MiB memory-side cache before the combine reads them: written around
         // the caches they do not evict the operands (P = 8 at 4096^2: 257 -> 170 us).  Fewer planes stay cached for

@@ -275,6 +275,86 @@ int tbik_tree_combine(const float *partials, int P, void *Y, int64_t ldy, tbik_d
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }
 
+// How tbik_gemm_swiglu runs a shape (pure): the K split of the [M, 2 I] GEMM, and whether the unsplit case can end in
+// the 128 x 128 tile's activation epilogue or has to pass gate and up through a 16-bit staging buffer.
+enum { SWIGLU_FUSED = 0, SWIGLU_SPLIT = 1, SWIGLU_STAGED = 2 };
+static int swiglu_route(int dtype, int M, int I, int K, int sl, int ns, int *split) {
+    const int N = 2 * I;
+    GemmArgs probe{nullptr, K, nullptr, N, nullptr, nullptr, I, dtype, M, N, K, sl, ns, 1, dtype, 0};
+    probe.P = *split = internal_split(M, N, K, ns);
+    if (*split > 1) return pick_variant(probe) != VARIANT_REFERENCE ? SWIGLU_SPLIT : SWIGLU_STAGED;
+    probe.swiglu = 1;
+    return (tile_rows(M, N) == 128 && g_forced_variant.load() == VARIANT_AUTO && gemm_tiled_supports(probe, VARIANT_T128))
+               ? SWIGLU_FUSED : SWIGLU_STAGED;
+}
+
+size_t tbik_gemm_swiglu_workspace_bytes(int M, int I, int K, int leaf, int k_first) {
+    int sl, ns, split;
+    if (I <= 0 || I > 0x3fffffff || check_tree(M, 2 * I, K, leaf, k_first, 1, &sl, &ns) != TBIK_OK) return 0;
+    switch (swiglu_route(TBIK_BF16, M, I, K, sl, ns, &split)) {
+        case SWIGLU_FUSED: return 0;
+        case SWIGLU_SPLIT: return (size_t)split * (size_t)M * (size_t)(2 * I) * sizeof(float);
+        default: return (((size_t)M * (size_t)(2 * I) * 2 + 255) & ~(size_t)255) + tbik_gemm_workspace_bytes(M, 2 * I, K, leaf, k_first);
+    }
+}
+
+int tbik_silu_mul(const void *gate, int64_t ldg, const void *up, int64_t ldu, void *act, int64_t lda,
+                  tbik_dtype dtype, int M, int I, void *hip_stream) {
+    if (M < 0 || I < 0) return TBIK_ERR_SHAPE;
+    if (dtype != TBIK_BF16 && dtype != TBIK_F16) return TBIK_ERR_DTYPE;
+    if (M == 0 || I == 0) return TBIK_OK;
+    if (!gate || !up || !act) return TBIK_ERR_NULL;
+    if (ldg < I || ldu < I || lda < I) return TBIK_ERR_SHAPE;
+    hipError_t e = launch_silu_mul((const uint16_t *)gate, ldg, (const uint16_t *)up, ldu, (uint16_t *)act, lda, (int)dtype, M, I,
+                                   (hipStream_t)hip_stream);
+    return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
+int tbik_gemm_swiglu(const void *X, int64_t ldx, const void *W_gu, int64_t ldw, void *act, int64_t lda,
+                     tbik_dtype dtype, int M, int I, int K, int leaf, int k_first,
+                     void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (I < 0 || I > 0x3fffffff || I % 8 != 0) return TBIK_ERR_SHAPE;
+    const int N = 2 * I;
+    int sl, ns;
+    int rc = check_tree(M, N, K, leaf, k_first, 1, &sl, &ns);
+    if (rc != TBIK_OK) return rc;
+    if (dtype != TBIK_BF16 && dtype != TBIK_F16) return TBIK_ERR_DTYPE;
+    if (M == 0 || I == 0) return TBIK_OK;
+    rc = check_operands((int)dtype, X, ldx, W_gu, ldw, N, K);
+    if (rc != TBIK_OK) return rc;
+    if (ldx >= (1 << 22) || ldw >= (1 << 22)) return TBIK_ERR_SHAPE;
+    if (!act) return TBIK_ERR_NULL;
+    if (lda < I) return TBIK_ERR_SHAPE;
+    if (!aligned(act, 2)) return TBIK_ERR_ALIGN;
+    const size_t need = tbik_gemm_swiglu_workspace_bytes(M, I, K, leaf, k_first);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return TBIK_ERR_WORKSPACE;
+    if (workspace && !aligned(workspace, 256)) return TBIK_ERR_ALIGN;
+
+    hipStream_t s = (hipStream_t)hip_stream;
+    int split;
+    const int route = swiglu_route((int)dtype, M, I, K, sl, ns, &split);
+    GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)W_gu, ldw, nullptr, act, lda, (int)dtype, M, N, K, sl, ns, 1, (int)dtype, 0};
+    hipError_t e;
+    if (route == SWIGLU_FUSED) {
+        a.swiglu = 1;
+        e = launch_gemm_tiled(a, VARIANT_T128, s);
+    } else if (route == SWIGLU_SPLIT) {
+        a.partials = reinterpret_cast<float *>(workspace);
+        a.Y = nullptr;
+        a.P = split;
+        e = launch_tiled(a, pick_variant(a), s);
+        if (e == hipSuccess) e = launch_tree_combine_swiglu(a.partials, split, (uint16_t *)act, lda, (int)dtype, M, I, s);
+    } else {
+        uint16_t *staged = reinterpret_cast<uint16_t *>(workspace);
+        const size_t staged_bytes = ((size_t)M * (size_t)N * 2 + 255) & ~(size_t)255;
+        rc = gemm((int)dtype, X, ldx, W_gu, ldw, staged, N, (int)dtype, M, N, K, leaf, k_first,
+                  reinterpret_cast<char *>(workspace) + staged_bytes, workspace_bytes - staged_bytes, hip_stream);
+        if (rc != TBIK_OK) return rc;
+        e = launch_silu_mul(staged, N, staged + I, N, (uint16_t *)act, lda, (int)dtype, M, I, s);
+    }
+    return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
 static int rmsnorm(int dtype, const void *x, const void *weight, void *y, int M, int H, float eps, void *hip_stream) {
     if (M < 0 || H <= 0 || H % 8 != 0 || H > 65536) return TBIK_ERR_SHAPE;
     if (M == 0) return TBIK_OK;

@@ -33,6 +33,29 @@ __device__ __forceinline__ uint32_t pack_16x2(float lo, float hi) { return F16 ?
 template <bool F16>
 __device__ __forceinline__ uint32_t f32_to_16_bits(float f) { return pack_16x2<F16>(f, 0.0f) & 0xffffu; }
 
+// The value a 16-bit tensor element gets when v is stored to it (one rounding, then the exact widening).
+template <bool F16>
+__device__ __forceinline__ float through_16_bits(float v) {
+    if constexpr (F16) return (float)(_Float16)v;
+    else return bf16_bits_to_f32(f32_to_bf16_bits(v));
+}
+
+// The gated activation between the two MLP GEMMs (implementation appendix, "other kernels"): SiLU(g) * u with
+// SiLU(g) = g / (1 + e^-g), in fp32.  The exponential and the reciprocal are the hardware's approximations
+// (v_exp_f32 of g * -log2(e), v_rcp_f32: about one fp32 ulp each), each product is one rounded multiplication.
+// Position-wise, and the one definition for every kernel that applies it, so an element's bits do not depend on the
+// kernel, the batch or the launch.  For g below about -87 the reciprocal leaves the normal range and the result may
+// flush to zero (true magnitude below 1e-36).
+__device__ __forceinline__ float silu_mul(float g, float u) {
+    const float e = __builtin_amdgcn_exp2f(g * -1.4426950408889634f);
+    float act = (g * __builtin_amdgcn_rcpf(1.0f + e)) * u;
+    // The fp32 product is a value of its own: without this the compiler may merge the last multiplication with a
+    // following conversion to binary16 into one mixed-precision instruction, which rounds once where the definition
+    // rounds twice (seen: one element in 10^5 off by a step, and only in the callers where the merge applied).
+    asm("" : "+v"(act));
+    return act;
+}
+
 // Eight 16-bit values (one 16-byte chunk) of either format -> fp32, exact.
 template <bool F16>
 __device__ __forceinline__ void unpack8(const uint4 &v, float (&f)[8]) {

@@ -23,6 +23,8 @@ struct GemmArgs {
     int ns;              // number of superleaves (power of two)
     int P;               // shards (power of two, <= ns)
     int x_dtype;         // TBIK_BF16, TBIK_F16 or TBIK_F32: storage format of X, W (and of a 16-bit Y)
+    int swiglu;          // 1: W is [gate | up], N = 2 I columns; Y is act [M, I] = SiLU(gate) * up in x_dtype.  Only the
+                         // 128 x 128 tile of the 16-bit kernels, P == 1, I % 64 == 0 (gemm_tiled_supports() says).
 };
 
 // Reference kernel: one wavefront per 32x32 tile and shard.  Writes partials (if set) and, when P == 1
@@ -33,6 +35,14 @@ hipError_t launch_gemm_reference(const GemmArgs &a, hipStream_t s);
 // if the variant cannot run this shape.  Same outputs as the reference kernel.
 hipError_t launch_gemm_tiled(const GemmArgs &a, int variant, hipStream_t s);
 bool gemm_tiled_supports(const GemmArgs &a, int variant);
+
+// act = round16(SiLU(gate) * up), elementwise on [M, I] 16-bit tensors of format dtype.
+hipError_t launch_silu_mul(const uint16_t *gate, int64_t ldg, const uint16_t *up, int64_t ldu, uint16_t *act, int64_t lda,
+                           int dtype, int M, int I, hipStream_t s);
+// The same on the tree-combined partials of a [gate | up] GEMM: partials fp32 [P, M, 2 I]; gate = round16(T(..)[m, i]),
+// up = round16(T(..)[m, I + i]).  I % 4 == 0.
+hipError_t launch_tree_combine_swiglu(const float *partials, int P, uint16_t *act, int64_t lda, int dtype, int M, int I,
+                                      hipStream_t s);
 
 // The same two for fp32 operands (x_dtype TBIK_F32: X and W point to float, Y is fp32); tiles of 128 or 32 rows.
 hipError_t launch_gemm_f32_reference(const GemmArgs &a, hipStream_t s);

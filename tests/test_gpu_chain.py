@@ -1,7 +1,7 @@
 """32B-class synthetic decoder-layer chain on one GPU: the final log-probabilities must be bit-identical for
 P in {1,2,4,8} emulated shards of the two row-parallel layers (o_proj, down_proj).
 
-RMSNorm -> QKV GEMM -> reference attention -> o_proj (tree GEMM, P shards) -> RMSNorm -> gate/up GEMM -> SiLU*up ->
+RMSNorm -> QKV GEMM -> reference attention -> o_proj (tree GEMM, P shards) -> RMSNorm -> gate/up GEMM with SiLU*up ->
 down_proj (tree GEMM, P shards) -> lm_head GEMM -> log-softmax, M = 512 tokens.  Column-parallel layers (qkv, gate, up,
 lm_head) have no cross-shard sum, so they run as whole-K calls (Sec. 3.3).  leaf = 128 with k_first = 5 (K = 5120) and
 25 (K = 25600) gives 8 superleaves, so P <= 8 is legal.  The attention here is a plain fp32 softmax(QK^T)V written with
@@ -52,15 +52,21 @@ def test_chain_logprobs_bit_identical_across_shard_counts():
     n1 = tb.tbik_rmsnorm(t["x"], t["norm1"], 1e-6)
     qkv = tb.tbik_gemm(n1, t["w_qkv"], leaf, g_h)
     attn = reference_attention(qkv)
+    w_gu = torch.cat([t["w_gate"], t["w_up"]], dim=1)          # [K, 2 I]: gate columns, then up columns
 
     digests, finals = {}, {}
     stages = {}
     for P in (1, 2, 4, 8):
         h1 = row_parallel(attn, t["w_o"], leaf, g_h, P, torch.bfloat16)
         n2 = tb.tbik_rmsnorm(h1, t["norm2"], 1e-6)
-        gate = tb.tbik_gemm(n2, t["w_gate"], leaf, g_h)
-        up = tb.tbik_gemm(n2, t["w_up"], leaf, g_h)
-        act = (torch.nn.functional.silu(gate.float()) * up.float()).to(torch.bfloat16)
+        act = tb.tbik_gemm_swiglu(n2, w_gu, leaf, g_h)
+        if P == 1:      # the fused call is the two column-parallel GEMMs followed by the activation, bit for bit
+            gate = tb.tbik_gemm(n2, t["w_gate"], leaf, g_h)
+            up = tb.tbik_gemm(n2, t["w_up"], leaf, g_h)
+            assert torch.equal(act.view(torch.int16), tb.tbik_silu_mul(gate, up).view(torch.int16))
+            want = gate.float() / (1 + torch.exp(-gate.float())) * up.float()    # the definition, written out in fp32
+            assert torch.all((act.float() - want).abs() <= want.abs() * 2.0 ** -7 + 1e-30)
+            del gate, up, want
         h2 = row_parallel(act, t["w_down"], leaf, g_i, P, torch.bfloat16)
         logits = tb.tbik_gemm(h2, t["w_lm"], leaf, g_h, out_dtype=torch.float32)
         logp = tb.tbik_row_reduce(logits, tb.TBIK_LOGSOFTMAX)
@@ -93,7 +99,7 @@ def test_chain_logprobs_bit_identical_across_shard_counts():
 def _layer_logprobs(t, x, cu, max_q, P, kv_cache=None):
     """One decoder layer + lm_head on packed sequences, every reduction through the library:
     RMSNorm -> QKV GEMM -> tbik_attention on the fused QKV buffer -> o_proj shard partials -> fused tail (tree combine +
-    residual + RMSNorm) -> gate/up GEMMs -> SiLU*up -> down_proj shard partials -> fused tail -> lm_head GEMM -> log-softmax.
+    residual + RMSNorm) -> gate/up GEMM with SiLU*up (tbik_gemm_swiglu) -> down_proj shard partials -> fused tail -> lm_head GEMM -> log-softmax.
     kv_cache = (K, V, cu_k): keys and values of the whole sequences (a decode step brings only its own queries)."""
     d = syn.CHAIN_DIMS
     leaf, hd, nq, nkv = d["leaf"], d["head_dim"], d["q_heads"], d["kv_heads"]
@@ -114,9 +120,7 @@ def _layer_logprobs(t, x, cu, max_q, P, kv_cache=None):
                                  hd ** -0.5, True)
     attn = attn.view(T, nq * hd)
     h1, n2 = tb.tbik_combine_residual_rmsnorm(tb.tbik_gemm_shard_partials(attn, t["w_o"], leaf, g_h, P), x, t["norm2"], 1e-6)
-    gate = tb.tbik_gemm(n2, t["w_gate"], leaf, g_h)
-    up = tb.tbik_gemm(n2, t["w_up"], leaf, g_h)
-    act = (torch.nn.functional.silu(gate.float()) * up.float()).to(torch.bfloat16)       # elementwise: no reduction to order
+    act = tb.tbik_gemm_swiglu(n2, t["w_gu"], leaf, g_h)       # position-wise after the GEMM: no reduction to order
     h2, n3 = tb.tbik_combine_residual_rmsnorm(tb.tbik_gemm_shard_partials(act, t["w_down"], leaf, g_i, P), h1, t["norm1"], 1e-6)
     logits = tb.tbik_gemm(n3, t["w_lm"], leaf, g_h, out_dtype=torch.float32)
     logp = tb.tbik_row_reduce(logits, tb.TBIK_LOGSOFTMAX)
@@ -132,6 +136,7 @@ def test_layer_with_library_attention_is_invariant_to_batch_shards_and_call_shap
       (3) the last token of the second sequence run as a decode step (one query, keys and values from the cache of the
           batched run) gives the row it has in the batch."""
     t = syn.chain_tensors("cuda:0")
+    t["w_gu"] = torch.cat([t.pop("w_gate"), t.pop("w_up")], dim=1)
     x = t["x"]
     cu = [0, 300, 512]
     full, (K, V) = _layer_logprobs(t, x, cu, 300, 1)

@@ -184,3 +184,52 @@ def test_fused_tail_rounds_the_combined_value_before_the_residual_add():
     # the pieces are the public ones: same result as calling them one after the other
     _, ybf = orc.tree_combine(parts)
     assert np.all(ybf == 0x3F81)
+
+
+# ----------------------------------------------------------------------------- gated activation (SiLU * up)
+
+def _silu_mul_f64(gbits, ubits, fmt):
+    g = syn.from_storage(gbits, fmt).astype(np.float64)
+    u = syn.from_storage(ubits, fmt).astype(np.float64)
+    return g / (1.0 + np.exp(-g)) * u
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "fp16"])
+def test_silu_mul_matches_the_fp64_definition_within_one_step(fmt):
+    """act = SiLU(gate) * up with SiLU(g) = g * sigmoid(g) (implementation appendix, "other kernels"): every output is
+    one of the two 16-bit neighbours of the fp64 value, and all but a few are the nearest one."""
+    rng = np.random.default_rng(11)
+    g = syn.to_storage(rng.standard_normal((64, 1024), dtype=np.float32) * 3, fmt)
+    u = syn.to_storage(rng.standard_normal((64, 1024), dtype=np.float32), fmt)
+    got = syn.from_storage(orc.silu_mul(g, u, fmt), fmt).astype(np.float64)
+    want = _silu_mul_f64(g, u, fmt)
+    nearest = syn.from_storage(syn.to_storage(want.astype(np.float32), fmt), fmt).astype(np.float64)
+    step = np.maximum(np.abs(nearest), 2.0 ** -14 if fmt == "fp16" else 2.0 ** -126) * (2.0 ** -10 if fmt == "fp16" else 2.0 ** -7)
+    assert np.all(np.abs(got - want) <= step)
+    assert np.mean(got != nearest) < 2e-3
+
+
+def test_silu_mul_exact_cases():
+    """Where the definition has an exact value.  g >= 32: e^-g < 2^-46, so 1 + e^-g rounds to 1 and SiLU(g) = g;
+    g = 0 gives 0; g <= -104: e^104 overflows fp32, g / inf = -0; SiLU(-g) - SiLU(g) = -g ties the two branches."""
+    b = lambda v: syn.f32_to_bf16_bits(np.asarray(v, dtype=np.float32))
+    f = syn.bf16_bits_to_f32
+    out = f(orc.silu_mul(b([[32, 64, 48, 0, 0, -104, -200]]), b([[3, -0.5, 1.5, 7, -7, 2, -2]])))
+    assert out[0, :3].tolist() == [96.0, -32.0, 72.0]
+    assert out[0, 3:].tolist() == [0.0] * 4
+    # one hand value: g = 1, u = 1: 1 / (1 + e^-1) = 0.7310585786..., which bf16 rounds to 0.73046875 (0x3F3B)
+    assert int(orc.silu_mul(b([[1.0]]), b([[1.0]]))[0, 0]) == 0x3F3B
+    # the identity SiLU(g) - SiLU(-g) = g, on values where all three are bf16 numbers after rounding within a step
+    g = b(np.linspace(0.125, 8, 64, dtype=np.float32)[None, :])
+    one = b(np.ones((1, 64), dtype=np.float32))
+    pos = f(orc.silu_mul(g, one)).astype(np.float64)
+    neg = f(orc.silu_mul(g ^ np.uint16(0x8000), one)).astype(np.float64)
+    assert np.all(np.abs((pos - neg) - f(g)) <= np.abs(f(g)) * 2.0 ** -7)
+
+
+def test_silu_mul_takes_gate_first_and_up_second():
+    """A swapped operand pair must fail: SiLU(2) * 0.5 != SiLU(0.5) * 2."""
+    b = lambda v: syn.f32_to_bf16_bits(np.asarray(v, dtype=np.float32))
+    a = syn.bf16_bits_to_f32(orc.silu_mul(b([[2.0]]), b([[0.5]])))[0, 0]
+    assert abs(a - 2.0 / (1.0 + math.exp(-2.0)) * 0.5) < 2.0 ** -8
+    assert abs(a - 0.5 / (1.0 + math.exp(-0.5)) * 2.0) > 0.1
