@@ -36,13 +36,18 @@
  *   format only changes the exact widening and the one output rounding.
  *   tbik_oracle_gemm_f32*    the same GEMM on fp32 operands (third row of that table): a
  *                            leaf accumulates by one fused multiply-add per k.
+ *   tbik_oracle_gemm_fp8*    the same GEMM on 8-bit floating-point operands (the paper's outlook: quantised
+ *                            types): OCP E4M3 or E5M2 patterns widened exactly; a product of two of them has
+ *                            at most 8 significant bits, so it is exact in fp32 and the 16-bit contract
+ *                            (ascending-k chain from +0 inside a superleaf, then T) carries over unchanged.
  *
  * Pins (tests marked "not gpu"): hand-derived tree values, Theorem 1 across
  * P and M, exact-integer inputs against int64 arithmetic, fp64 brute force
  * within the summation-tree error bound, one-superleaf == sequential sum,
  * leaf 1 == level-by-level pairwise sum, closed forms for RMSNorm and
  * log-softmax, the fp64 definition and exact special cases of the gated activation,
- * numpy's float16 for the binary16 conversions, the fp64 softmax
+ * numpy's float16 for the binary16 conversions, all 256 patterns of both 8-bit formats
+ * against integer arithmetic and a library's conversion, the fp64 softmax
  * definition and exact special cases for attention.  No function here is
  * "parity unpinned".
  */
@@ -429,6 +434,100 @@ int tbik_oracle_gemm_f32(const float *X, long ldx, const float *W, long ldw, flo
                 if (partials && evaluator == EVAL_SHARDED)
                     for (int p = 0; p < P; ++p) partials[((size_t)p * M + m) * N + n] = part[p];
             }
+        free(s);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ 8-bit floating point (OCP FP8) */
+
+enum { FMT8_E4M3 = 0, FMT8_E5M2 = 1 };
+
+/*
+ * An 8-bit pattern -> fp32, exact.  Both formats are sign | exponent | fraction with an IEEE-style bias
+ * and subnormals:
+ *   E4M3: 4 exponent bits (bias 7), 3 fraction bits; no infinities -- exponent 15 holds ordinary numbers (up to
+ *         1.75 * 2^8 = 448) except fraction 7, which is NaN.
+ *   E5M2: 5 exponent bits (bias 15), 2 fraction bits; exponent 31 is infinity (fraction 0) or NaN, as in binary16.
+ * Written on the value: (fraction [+ hidden one]) * 2^(exponent - bias - fraction bits), by ldexpf (exact here).
+ */
+float tbik_oracle_fp8_to_f32(uint8_t b, int fmt8) {
+    const int ebits = fmt8 == FMT8_E5M2 ? 5 : 4, fbits = 7 - ebits, bias = fmt8 == FMT8_E5M2 ? 15 : 7;
+    const int sign = b >> 7, e = (b >> fbits) & ((1 << ebits) - 1), f = b & ((1 << fbits) - 1);
+    float v;
+    if (fmt8 == FMT8_E5M2 && e == 31) v = f ? NAN : INFINITY;
+    else if (fmt8 == FMT8_E4M3 && e == 15 && f == 7) v = NAN;
+    else if (e == 0) v = ldexpf((float)f, 1 - bias - fbits);                 /* subnormal: no hidden one */
+    else v = ldexpf((float)(f + (1 << fbits)), e - bias - fbits);
+    return sign ? -v : v;
+}
+
+/*
+ * Y = X W on 8-bit operands (Sec. 3.3, Sec. 4.2, App. D.1, App. C as for the 16-bit GEMM above):
+ *   p_k = x[m,k] * w[k,n]      exact in fp32 (<= 4-bit significands, exponents within +-32)
+ *   s_j = ((p_a + p_{a+1}) + ...)   over superleaf j in ascending k, from +0, one rounded fp32 addition per k
+ *   y   = T(s_0 .. s_{n_s-1})
+ * X is [M, ldx], W is [K, ldw] (this file's orientation; the GPU entry point takes W transposed, which is a matter
+ * of storage only).  Outputs as for tbik_oracle_gemm: fp32 and/or bf16 patterns; partials for EVAL_SHARDED.
+ */
+int tbik_oracle_gemm_fp8(const uint8_t *X, long ldx, const uint8_t *W, long ldw, float *Y32, uint16_t *Ybf, long ldy,
+                         int M, int N, int K, int leaf, int k_first, int evaluator, int P, int fmt8, float *partials) {
+    long ns = superleaf_count(K, leaf, k_first, P);
+    if (ns < 0) return -1;
+    const long sl = (long)leaf * k_first;
+    float table[256];
+    for (int b = 0; b < 256; ++b) table[b] = tbik_oracle_fp8_to_f32((uint8_t)b, fmt8);
+#pragma omp parallel
+    {
+        float *s = (float *)malloc((size_t)ns * sizeof(float));
+        float part[64];
+#pragma omp for schedule(dynamic, 1)
+        for (long m = 0; m < M; ++m)
+            for (long n = 0; n < N; ++n) {
+                for (long j = 0; j < ns; ++j) {
+                    float acc = 0.0f;
+                    for (long k = j * sl; k < (j + 1) * sl; ++k) {
+                        float pk = table[X[m * ldx + k]] * table[W[k * ldw + n]];
+                        acc = acc + pk;
+                    }
+                    s[j] = acc;
+                }
+                float y = combine_superleaves(s, ns, evaluator, P, part);
+                if (Y32) Y32[m * ldy + n] = y;
+                if (Ybf) Ybf[m * ldy + n] = f32_to_bf16(y);
+                if (partials && evaluator == EVAL_SHARDED)
+                    for (int p = 0; p < P; ++p) partials[((size_t)p * M + m) * N + n] = part[p];
+            }
+        free(s);
+    }
+    return 0;
+}
+
+/* The same on sampled positions (rows[i], cols[i]). */
+int tbik_oracle_gemm_fp8_elements(const uint8_t *X, long ldx, const uint8_t *W, long ldw,
+                                  const int64_t *rows, const int64_t *cols, long count,
+                                  int K, int leaf, int k_first, int evaluator, int P, int fmt8, float *out) {
+    long ns = superleaf_count(K, leaf, k_first, P);
+    if (ns < 0) return -1;
+    const long sl = (long)leaf * k_first;
+    float table[256];
+    for (int b = 0; b < 256; ++b) table[b] = tbik_oracle_fp8_to_f32((uint8_t)b, fmt8);
+#pragma omp parallel
+    {
+        float *s = (float *)malloc((size_t)ns * sizeof(float));
+#pragma omp for schedule(dynamic, 16)
+        for (long i = 0; i < count; ++i) {
+            const long m = rows[i], n = cols[i];
+            for (long j = 0; j < ns; ++j) {
+                float acc = 0.0f;
+                for (long k = j * sl; k < (j + 1) * sl; ++k) {
+                    float pk = table[X[m * ldx + k]] * table[W[k * ldw + n]];
+                    acc = acc + pk;
+                }
+                s[j] = acc;
+            }
+            out[i] = combine_superleaves(s, ns, evaluator, P, NULL);
+        }
         free(s);
     }
     return 0;

@@ -26,6 +26,7 @@ EVAL_RECURSIVE, EVAL_COUNTER, EVAL_SHARDED = 0, 1, 2
 
 # 16-bit storage formats of GEMM operands and outputs (values of the C side's enum).
 FORMATS = {"bf16": 0, "fp16": 1}
+FORMATS8 = {"e4m3": 0, "e5m2": 1}
 
 # Leaf sizes of the row reductions: one 16-byte chunk of the row per leaf.
 LEAF_BF16 = 8
@@ -76,6 +77,15 @@ def lib():
         L.tbik_oracle_gemm_f32.restype = C.c_int
         L.tbik_oracle_gemm_f32.argtypes = [f32p, C.c_long, f32p, C.c_long, f32p, C.c_long,
                                            C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f32p]
+        u8p = C.POINTER(C.c_uint8)
+        L.tbik_oracle_fp8_to_f32.restype = C.c_float
+        L.tbik_oracle_fp8_to_f32.argtypes = [C.c_uint8, C.c_int]
+        L.tbik_oracle_gemm_fp8.restype = C.c_int
+        L.tbik_oracle_gemm_fp8.argtypes = [u8p, C.c_long, u8p, C.c_long, f32p, u16p, C.c_long,
+                                           C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f32p]
+        L.tbik_oracle_gemm_fp8_elements.restype = C.c_int
+        L.tbik_oracle_gemm_fp8_elements.argtypes = [u8p, C.c_long, u8p, C.c_long, i64p, i64p, C.c_long,
+                                                    C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f32p]
         L.tbik_oracle_tree_combine.restype = C.c_int
         L.tbik_oracle_tree_combine.argtypes = [f32p, C.c_int, C.c_long, f32p, u16p, C.c_int]
         L.tbik_oracle_treesum.restype = C.c_float
@@ -245,6 +255,52 @@ def gemm_f32_elements(X, W, rows, cols, leaf: int, k_first: int = 1, evaluator: 
     out = np.empty(rows.size, dtype=np.float32)
     rc = lib().tbik_oracle_gemm_f32_elements(xp, X.shape[1], wp, W.shape[1], rp, cp, rows.size, X.shape[1],
                                              leaf, k_first, evaluator, P, out.ctypes.data_as(C.POINTER(C.c_float)))
+    if rc != 0:
+        raise ValueError("oracle gemm: illegal tree parameters (K, leaf, k_first, P)")
+    return out
+
+
+def _u8(a):
+    a = np.ascontiguousarray(a, dtype=np.uint8)
+    return a, a.ctypes.data_as(C.POINTER(C.c_uint8))
+
+
+def fp8_to_f32(bits, fmt: str = "e4m3") -> np.ndarray:
+    """8-bit patterns of format `fmt` ("e4m3" or "e5m2") -> the fp32 values they denote (exact)."""
+    L = lib()
+    table = np.array([L.tbik_oracle_fp8_to_f32(b, FORMATS8[fmt]) for b in range(256)], dtype=np.float32)
+    return table[np.asarray(bits, dtype=np.uint8)]
+
+
+def gemm_fp8(X, W, leaf: int, k_first: int = 1, evaluator: int = EVAL_RECURSIVE, P: int = 1,
+             want_partials: bool = False, fmt: str = "e4m3"):
+    """Y = X W in the tree order on 8-bit patterns X [M,K], W [K,N] of format `fmt`.
+    Returns (Y fp32 [M,N], Y bf16 patterns [M,N][, partials [P,M,N]])."""
+    X, xp = _u8(X)
+    W, wp = _u8(W)
+    M, K = X.shape
+    K2, N = W.shape
+    assert K == K2
+    Y32 = np.empty((M, N), dtype=np.float32)
+    Ybf = np.empty((M, N), dtype=np.uint16)
+    parts = np.zeros((P, M, N), dtype=np.float32) if want_partials else None
+    rc = lib().tbik_oracle_gemm_fp8(xp, K, wp, N, Y32.ctypes.data_as(C.POINTER(C.c_float)),
+                                    Ybf.ctypes.data_as(C.POINTER(C.c_uint16)), N, M, N, K, leaf, k_first, evaluator, P,
+                                    FORMATS8[fmt], parts.ctypes.data_as(C.POINTER(C.c_float)) if want_partials else None)
+    if rc != 0:
+        raise ValueError("oracle gemm: illegal tree parameters (K, leaf, k_first, P)")
+    return (Y32, Ybf, parts) if want_partials else (Y32, Ybf)
+
+
+def gemm_fp8_elements(X, W, rows, cols, leaf: int, k_first: int = 1, evaluator: int = EVAL_RECURSIVE, P: int = 1,
+                      fmt: str = "e4m3") -> np.ndarray:
+    X, xp = _u8(X)
+    W, wp = _u8(W)
+    rows, rp = _i64(rows)
+    cols, cp = _i64(cols)
+    out = np.empty(rows.size, dtype=np.float32)
+    rc = lib().tbik_oracle_gemm_fp8_elements(xp, X.shape[1], wp, W.shape[1], rp, cp, rows.size, X.shape[1], leaf, k_first,
+                                             evaluator, P, FORMATS8[fmt], out.ctypes.data_as(C.POINTER(C.c_float)))
     if rc != 0:
         raise ValueError("oracle gemm: illegal tree parameters (K, leaf, k_first, P)")
     return out

@@ -44,21 +44,44 @@ def f16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return np.ascontiguousarray(b, dtype=np.uint16).view(np.float16).astype(np.float32)
 
 
+def _torch_fp8(fmt: str):
+    import torch
+    return {"e4m3": torch.float8_e4m3fn, "e5m2": torch.float8_e5m2}[fmt]
+
+
+def f32_to_fp8_bits(a: np.ndarray, fmt: str = "e4m3") -> np.ndarray:
+    """fp32 -> 8-bit OCP patterns ("e4m3": 4 exponent / 3 fraction bits, no infinities, max 448; "e5m2": 5 / 2), round to
+    nearest even, by torch's CPU conversion.  Callers keep |a| inside the format's range (no saturation relied on)."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(_torch_fp8(fmt))
+    return t.view(torch.uint8).numpy().copy()
+
+
+def fp8_bits_to_f32(b: np.ndarray, fmt: str = "e4m3") -> np.ndarray:
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(b, dtype=np.uint8)).view(_torch_fp8(fmt))
+    return t.to(torch.float32).numpy()
+
+
 def to_storage(a: np.ndarray, fmt: str = "bf16") -> np.ndarray:
-    """fp32 values -> 16-bit storage patterns of format ``fmt`` ("bf16" or "fp16")."""
+    """fp32 values -> storage patterns of format ``fmt``: 16-bit ("bf16", "fp16") or 8-bit ("e4m3", "e5m2")."""
     if fmt == "bf16":
         return f32_to_bf16_bits(a)
     if fmt == "fp16":
         return f32_to_f16_bits(a)
+    if fmt in ("e4m3", "e5m2"):
+        return f32_to_fp8_bits(a, fmt)
     raise ValueError(fmt)
 
 
 def from_storage(b: np.ndarray, fmt: str = "bf16") -> np.ndarray:
-    """16-bit storage patterns of format ``fmt`` -> the fp32 values they denote (exact)."""
+    """Storage patterns of format ``fmt`` -> the fp32 values they denote (exact)."""
     if fmt == "bf16":
         return bf16_bits_to_f32(b)
     if fmt == "fp16":
         return f16_bits_to_f32(b)
+    if fmt in ("e4m3", "e5m2"):
+        return fp8_bits_to_f32(b, fmt)
     raise ValueError(fmt)
 
 
@@ -121,6 +144,15 @@ def gemm_random(seed: int, M: int, K: int, N: int, x_std: float = 1.0, w_std: fl
     """Generic random GEMM operands of the same distributions, any shape."""
     rng = _rng(seed)
     return normal_bf16(rng, (M, K), x_std, fmt=fmt), normal_bf16(rng, (K, N), w_std, fmt=fmt)
+
+
+def gemm_random_fp8(seed: int, M: int, K: int, N: int, fmt: str = "e4m3"):
+    """8-bit operands as a scaled-quantisation flow leaves them: X ~ N(0,1) and W ~ N(0,1) in the scaled domain (the
+    per-tensor scales that bring weights of std 0.02 into the 8-bit range are outside the GEMM), rounded to ``fmt``."""
+    rng = _rng(seed)
+    X = rng.standard_normal(size=(M, K), dtype=np.float32)
+    W = rng.standard_normal(size=(K, N), dtype=np.float32)
+    return f32_to_fp8_bits(X, fmt), f32_to_fp8_bits(W, fmt)
 
 
 def gemm_random_f32(seed: int, M: int, K: int, N: int, x_std: float = 1.0, w_std: float = 0.02, exp_spread: int = 0):
