@@ -35,6 +35,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_FP8_TFLOPS = 5000.0      # MI355X dense fp8 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 CACHE_BYTES = 256 << 20        # memory-side cache: a buffer set a kernel is to find in HBM is rotated through more than this
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "bench_step_oproj_m4096_pmc.md")
@@ -348,6 +349,25 @@ def metric_shapes(tb, syn, torch, np, to_dev, X, W):
                                         "ms_gemm_then_activation": round(t_u, 4)}
         del act, gu, ws
     del Wgu
+
+    # 8-bit floating-point operands (E4M3), the two row-parallel shapes at M = 4096, beside torch._scaled_mm (hipBLASLt).
+    for name, K8, leaf8, g8 in (("fp8_oproj_M4096", 4096, 256, 1), ("fp8_downproj_M4096", 12288, 256, 3)):
+        g8r = torch.Generator(device=dev)
+        g8r.manual_seed(K8)
+        X8 = torch.randn((4096, K8), generator=g8r, device=dev, dtype=torch.float32).to(torch.float8_e4m3fn)
+        Wt8 = torch.randn((4096, K8), generator=g8r, device=dev, dtype=torch.float32).to(torch.float8_e4m3fn)
+        y8 = torch.empty((4096, 4096), dtype=torch.bfloat16, device=dev)
+        ws8 = torch.empty(max(256, tb.gemm_fp8_workspace_bytes(4096, 4096, K8, leaf8, g8)), dtype=torch.uint8, device=dev)
+        t = best_ms(lambda: tb.tbik_gemm_fp8(X8, Wt8, leaf8, g8, "e4m3", out=y8, workspace=ws8), 10, torch)
+        one = torch.ones((), device=dev)
+        try:
+            tbase = best_ms(lambda: torch._scaled_mm(X8, Wt8.t(), scale_a=one, scale_b=one, out_dtype=torch.bfloat16), 10, torch)
+        except Exception:                      # no 8-bit matmul in this torch build: the line carries no baseline
+            tbase = None
+        tf = 2.0 * 4096 * K8 * 4096 / (t * 1e-3) / 1e12
+        res[name] = {"ms": round(t, 4), "tflops": round(tf, 1), "frac_fp8_peak": round(tf / PEAK_FP8_TFLOPS, 4),
+                     "baseline_ms": round(tbase, 4) if tbase else None}
+        del X8, Wt8, y8, ws8
 
     def hbm_line(name, calls, byts, iters):
         cold = best_ms(rotating(calls), iters * len(calls), torch, warm=len(calls))

@@ -56,7 +56,11 @@ typedef enum {
     TBIK_ERR_HIP = 8          /* a HIP runtime call failed; see tbik_last_hip_error()                  */
 } tbik_status;
 
-typedef enum { TBIK_F32 = 0, TBIK_BF16 = 1, TBIK_F16 = 2 } tbik_dtype;
+typedef enum {
+    TBIK_F32 = 0, TBIK_BF16 = 1, TBIK_F16 = 2,
+    TBIK_FP8_E4M3 = 3,        /* OCP 8-bit float, 4 exponent / 3 fraction bits, bias 7, no infinities, max 448 */
+    TBIK_FP8_E5M2 = 4         /* OCP 8-bit float, 5 exponent / 2 fraction bits, bias 15, IEEE-style inf / NaN  */
+} tbik_dtype;
 typedef enum { TBIK_SUM = 0, TBIK_MAX = 1, TBIK_LOGSOFTMAX = 2 } tbik_rowop;
 
 #define TBIK_MAX_SHARDS 64
@@ -323,6 +327,35 @@ int tbik_gemm_shard_partials_f32(const void *X, int64_t ldx, const void *W, int6
                                  void *workspace, size_t workspace_bytes, void *hip_stream);
 int tbik_gemm_reference_f32(const void *X, int64_t ldx, const void *W, int64_t ldw, float *partials,
                             void *Y, int64_t ldy, int M, int N, int K, int leaf, int k_first, int P, void *hip_stream);
+
+/*
+ * The same three calls for 8-bit floating-point operands (the paper's outlook, "Limitations and future work": bringing
+ * the guarantee to quantised types).  X and the weight hold OCP E4M3 or E5M2 patterns (`x_dtype`, the same for both),
+ * widened exactly.  A product of two of them has at most 8 significant bits and is exact in fp32, so the order contract
+ * of tbik_gemm carries over word for word: per output element each superleaf's products are accumulated in fp32 in
+ * ascending k from +0, the superleaf sums are combined by T, the result is rounded once.  (As with the 16-bit calls, the
+ * 64 products of one matrix instruction are added in that instruction's own fixed order.)  Scales of a quantisation
+ * scheme are outside this call: they multiply the output.
+ *
+ * The weight is taken TRANSPOSED: Wt [N, ldwt], ldwt >= K, one row per output channel, k contiguous -- the layout 8-bit
+ * weights are stored in, and the one the matrix instruction wants for both operands.
+ *
+ *   X    device, 8-bit, [M, ldx], ldx >= K         Wt   device, 8-bit, [N, ldwt], ldwt >= K
+ *   Y    device, y_dtype (TBIK_F32 or TBIK_BF16), [M, ldy], ldy >= N        partials  device, fp32, dense [P, M, N]
+ *   leaf * k_first a multiple of 64 (128 for the tiled kernel; else the reference kernel runs); ldx, ldwt multiples
+ *   of 16; X, Wt 16-byte aligned; the other alignment rules, the workspace rule (tbik_gemm_fp8_workspace_bytes), the
+ *   determinism contract and the errors are those of tbik_gemm, tbik_gemm_shard_partials and tbik_gemm_reference.
+ */
+size_t tbik_gemm_fp8_workspace_bytes(int M, int N, int K, int leaf, int k_first);
+int tbik_gemm_fp8(const void *X, int64_t ldx, const void *Wt, int64_t ldwt, void *Y, int64_t ldy,
+                  tbik_dtype y_dtype, tbik_dtype x_dtype, int M, int N, int K, int leaf, int k_first,
+                  void *workspace, size_t workspace_bytes, void *hip_stream);
+int tbik_gemm_shard_partials_fp8(const void *X, int64_t ldx, const void *Wt, int64_t ldwt, float *partials,
+                                 tbik_dtype x_dtype, int M, int N, int K, int leaf, int k_first, int P,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
+int tbik_gemm_reference_fp8(const void *X, int64_t ldx, const void *Wt, int64_t ldwt, float *partials,
+                            void *Y, int64_t ldy, tbik_dtype y_dtype, tbik_dtype x_dtype,
+                            int M, int N, int K, int leaf, int k_first, int P, void *hip_stream);
 
 /*
  * tbik_rmsnorm and tbik_combine_residual_rmsnorm for tensors of IEEE binary16 (App. B and Alg. 2 do not depend on

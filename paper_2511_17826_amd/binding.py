@@ -39,6 +39,14 @@ SIGNATURES = {
     "tbik_gemm_swiglu": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int,
                                    C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
     "tbik_gemm_swiglu_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]),
+    "tbik_gemm_fp8": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_int,
+                                C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tbik_gemm_shard_partials_fp8": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int,
+                                               C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                               C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tbik_gemm_reference_fp8": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64,
+                                          C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
+    "tbik_gemm_fp8_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]),
     "tbik_gemm_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]),
     "tbik_row_reduce_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int64, C.c_int]),
     "tbik_gemm_reference": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64,
@@ -249,6 +257,74 @@ def tbik_gemm_shard_partials_f32(X: torch.Tensor, W: torch.Tensor, leaf: int, k_
                                  out: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
     """partials[p] = subtree sum of K-shard p (fp32 [P, M, N]); fp32 operands."""
     return _gemm_shard_partials("tbik_gemm_shard_partials_f32", torch.float32, X, W, leaf, k_first, P, out, workspace)
+
+
+TBIK_FP8_E4M3, TBIK_FP8_E5M2 = 3, 4
+_FP8 = {"e4m3": TBIK_FP8_E4M3, "e5m2": TBIK_FP8_E5M2}
+
+
+def _fp8_operands(X, Wt, fmt):
+    """8-bit operands travel as uint8 tensors of patterns (or torch's float8 tensors, reinterpreted)."""
+    def as_u8(t):
+        return t if t.dtype == torch.uint8 else t.view(torch.uint8)
+    X, Wt = as_u8(X), as_u8(Wt)
+    _rowmajor(X, "X"); _rowmajor(Wt, "Wt")
+    assert X.shape[1] == Wt.shape[1], "Wt is the transposed weight, [N, K]"
+    return X, Wt, _FP8[fmt]
+
+
+def gemm_fp8_workspace_bytes(M, N, K, leaf, k_first=1) -> int:
+    return int(lib().tbik_gemm_fp8_workspace_bytes(M, N, K, leaf, k_first))
+
+
+def tbik_gemm_fp8(X: torch.Tensor, Wt: torch.Tensor, leaf: int, k_first: int = 1, fmt: str = "e4m3",
+                  out_dtype=torch.bfloat16, out: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+    """Y = X @ Wt.T in the tree order on 8-bit floating-point operands; Wt is [N, K] (one row per output channel)."""
+    X, Wt, dt = _fp8_operands(X, Wt, fmt)
+    M, K = X.shape
+    N = Wt.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=X.device)
+    _rowmajor(out, "out")
+    assert out.shape == (M, N)
+    if workspace is None:
+        need = gemm_fp8_workspace_bytes(M, N, K, leaf, k_first)
+        if need:
+            workspace = _workspace(need, X.device)
+    st = lib().tbik_gemm_fp8(X.data_ptr(), X.stride(0), Wt.data_ptr(), Wt.stride(0), out.data_ptr(), out.stride(0),
+                             _dt(out), dt, M, N, K, leaf, k_first, workspace.data_ptr() if workspace is not None else None,
+                             workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream())
+    _check(st, "tbik_gemm_fp8")
+    return out
+
+
+def tbik_gemm_shard_partials_fp8(X: torch.Tensor, Wt: torch.Tensor, leaf: int, k_first: int, P: int, fmt: str = "e4m3",
+                                 out: torch.Tensor | None = None) -> torch.Tensor:
+    X, Wt, dt = _fp8_operands(X, Wt, fmt)
+    M, K = X.shape
+    N = Wt.shape[0]
+    if out is None:
+        out = torch.empty((max(P, 1), M, N), dtype=torch.float32, device=X.device)
+    assert out.is_contiguous() and out.dtype == torch.float32
+    st = lib().tbik_gemm_shard_partials_fp8(X.data_ptr(), X.stride(0), Wt.data_ptr(), Wt.stride(0), out.data_ptr(), dt,
+                                            M, N, K, leaf, k_first, P, None, 0, _stream())
+    _check(st, "tbik_gemm_shard_partials_fp8")
+    return out
+
+
+def tbik_gemm_reference_fp8(X: torch.Tensor, Wt: torch.Tensor, leaf: int, k_first: int = 1, P: int = 1, fmt: str = "e4m3",
+                            out_dtype=torch.float32):
+    """The reference kernel: (Y, partials) for P == 1, partials alone otherwise."""
+    X, Wt, dt = _fp8_operands(X, Wt, fmt)
+    M, K = X.shape
+    N = Wt.shape[0]
+    parts = torch.empty((P, M, N), dtype=torch.float32, device=X.device)
+    Y = torch.empty((M, N), dtype=out_dtype, device=X.device) if P == 1 else None
+    st = lib().tbik_gemm_reference_fp8(X.data_ptr(), X.stride(0), Wt.data_ptr(), Wt.stride(0), parts.data_ptr(),
+                                       Y.data_ptr() if Y is not None else None, N, _dt(Y) if Y is not None else TBIK_F32, dt,
+                                       M, N, K, leaf, k_first, P, _stream())
+    _check(st, "tbik_gemm_reference_fp8")
+    return (Y, parts) if P == 1 else parts
 
 
 def tbik_silu_mul(gate: torch.Tensor, up: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:

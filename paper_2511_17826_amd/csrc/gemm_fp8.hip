@@ -1,0 +1,516 @@
+// Tree-Based MatMul on 8-bit floating-point operands (OCP E4M3 / E5M2) for gfx950.
+//
+// The method is that of the 16-bit kernels (Sec. 4.2, App. C, App. D.1, Alg. 1): a superleaf's products are accumulated
+// in ascending k from +0, the superleaf sums are combined by the tree T.  A product of two 8-bit floats has at most
+// eight significant bits, so it is exact in fp32 like a product of two bf16 numbers.  The matrix instruction is
+// v_mfma_f32_32x32x64_f8f6f4 (64 k per instruction, both operands 8-bit): lane l carries row (or column) l % 32 and the
+// 32 consecutive k of half l / 32 of the step, for A and for B alike.  Because both operands want k-contiguous bytes,
+// the weight is taken TRANSPOSED, Wt [N, K] -- one row per output channel, the layout 8-bit weights are stored in --
+// and the two operand tiles are staged, swizzled and read in exactly the same way.
+//
+// Two kernels that must agree bit for bit: a reference (one wavefront per 32 x 32 tile and shard, operands straight
+// from global memory) and the tiled kernel (128 x 128 tile, 4 wavefronts of 64 x 64, K-steps of 128 bytes through a ring
+// of 5 LDS slots of 32 KiB filled by direct global->LDS loads, the tree's stash in registers).
+#include <atomic>
+#include <type_traits>
+
+#include "tbik_device.hpp"
+#include "tbik_internal.hpp"
+#include "tree_walk.hpp"
+
+namespace tbik {
+
+namespace {
+
+template <int V>
+using Int = std::integral_constant<int, V>;
+
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// One MFMA: D = A(32 x 64) * B(64 x 32) + C.  FMT: 0 = E4M3 ("fp8"), 1 = E5M2 ("bf8"), for both operands; the block
+// scales of the instruction family are not used (the unscaled opcode is selected for zero scale operands).
+template <int FMT>
+__device__ __forceinline__ f32x16 mfma_32x32x64_8bit(i32x8 a, i32x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, FMT, FMT, 0, 0, 0, 0);
+}
+
+constexpr int REF_MAX_LEVELS = 28;
+
+template <int FMT>
+__global__ __launch_bounds__(64) void gemm_fp8_reference_kernel(
+        const uint8_t *__restrict__ X, int64_t ldx, const uint8_t *__restrict__ Wt, int64_t ldw,
+        float *__restrict__ partials, void *__restrict__ Y, int64_t ldy, int y_dtype,
+        int M, int N, int superleaf, int ns_per_shard) {
+    const int lane = threadIdx.x;
+    const int i = lane & 31;      // row of X / row of Wt (= output column) held by this lane
+    const int g = lane >> 5;      // which half of a step of 64 k
+    const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+    const int p = blockIdx.z;
+    const int64_t kbase = (int64_t)p * ns_per_shard * superleaf;
+    const bool row_ok = (m0 + i) < M;
+    const bool col_ok = (n0 + i) < N;
+    const uint8_t *xrow = X + (int64_t)(row_ok ? m0 + i : 0) * ldx;
+    const uint8_t *wrow = Wt + (int64_t)(col_ok ? n0 + i : 0) * ldw;
+
+    float stash[REF_MAX_LEVELS][16];
+    f32x16 acc;
+    for (int j = 0; j < ns_per_shard; ++j) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+        const int64_t k0 = kbase + (int64_t)j * superleaf;
+        for (int kk = 0; kk < superleaf; kk += 64) {
+            const int64_t k = k0 + kk + 32 * g;
+            union { i32x4 h[2]; i32x8 v; } a, b;
+            a.h[0] = *reinterpret_cast<const i32x4 *>(xrow + k);
+            a.h[1] = *reinterpret_cast<const i32x4 *>(xrow + k + 16);
+            b.h[0] = *reinterpret_cast<const i32x4 *>(wrow + k);
+            b.h[1] = *reinterpret_cast<const i32x4 *>(wrow + k + 16);
+            // rows past M and columns past N compute on a valid row's data and are never stored
+            acc = mfma_32x32x64_8bit<FMT>(a.v, b.v, acc);
+        }
+        const int t = __builtin_ctz(~(unsigned)j);     // carry-over: as many finished subtrees as j has trailing ones
+        for (int l = 0; l < t; ++l) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = stash[l][r] + acc[r];
+        }
+        if (j + 1 < ns_per_shard) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) stash[t][r] = acc[r];
+        }
+    }
+    const int col = n0 + i;
+    if (!col_ok) return;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int row = m0 + 8 * (r >> 2) + 4 * g + (r & 3);
+        if (row >= M) continue;
+        if (partials) partials[((int64_t)p * M + row) * N + col] = acc[r];
+        if (Y) {
+            if (y_dtype == TBIK_F32) reinterpret_cast<float *>(Y)[(int64_t)row * ldy + col] = acc[r];
+            else reinterpret_cast<uint16_t *>(Y)[(int64_t)row * ldy + col] = (uint16_t)f32_to_bf16_bits(acc[r]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Tiled kernel.  A stage is 128 k: a [128 rows x 128 bytes] tile of X and one of Wt.  A stage slot is cut into four
+// regions of 8 KiB, one per loading wavefront: [32 rows of the X tile | 32 rows of the Wt tile].  Rows are 128 bytes;
+// the 16-byte chunk c of row r sits at position c ^ ((r >> 1) & 7), so the 16 rows that a ds_read_b128 pass touches
+// cover all banks.  A lane's operand for one MFMA is 32 consecutive bytes of its row: chunks 4*ks + 2*lg and the next.
+constexpr int BK8 = 128;               // k (= bytes) per LDS stage row
+constexpr int ROW8 = 128;              // bytes per LDS row
+constexpr int KSTEPS8 = BK8 / 64;      // MFMA K-steps per stage
+constexpr int RING8 = 5;
+constexpr int LOADS8 = 4;              // 1 KiB loads per wavefront, stage and operand
+constexpr int REGION8 = 2 * LOADS8 * 1024;
+constexpr int STAGE8 = 4 * REGION8;
+
+template <int N>
+__device__ __forceinline__ void wait_loads_and_barrier() {
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+struct Fp8Params {
+    const uint8_t *X;
+    const uint8_t *Wt;
+    float *partials;
+    void *Y;
+    int64_t ldx, ldw, ldy;
+    int M, N;
+    int y_bf16;
+    int stages_per_superleaf;   // superleaf / 128
+    int ns_per_shard;
+    int64_t k_per_shard;
+    int tiles_n, tiles, work;
+    int vector_stores;
+    int stream_stores;
+};
+
+template <int LEVELS, int FMT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void gemm_fp8_tiled_kernel(const Fp8Params p) {
+    constexpr int MT = 2, NT = 2, WN = 2, BM = 128, BN = 128;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int li = lane & 31, lg = lane >> 5;
+    const int stages_per_item = p.ns_per_shard * p.stages_per_superleaf;
+
+    // ---- global -> LDS (global_load_lds_dwordx4: lane i's 16 bytes land at LDS base + 16 i) ----
+    // Load j of wavefront w brings rows 32 w + 8 j + (lane >> 3) of a tile; the lane fetches the chunk that belongs at
+    // its position (the swizzle is applied on the global side).  All eight loads of a wavefront and stage share one m0
+    // (the start of the Wt part of its region): instruction offsets -4 .. -1 KiB for X and 0 .. 3 KiB for Wt; the lane
+    // offsets are biased so that the global side of the instruction offset cancels.  Rows past M or N re-read the last
+    // valid row: an output depends on its own row of X and of Wt only, and theirs are never stored.
+    constexpr int LOADS_PER_STAGE = 2 * LOADS8;
+    constexpr int WCOLS = 32 * NT;
+    constexpr int STORES_F32 = MT * (32 * WCOLS / 4 / 64);
+    constexpr int STORES_BF16 = MT * (32 * WCOLS / 8 / 64);
+    static_assert(LOADS_PER_STAGE * (RING8 - 3) + STORES_F32 < 64 && STORES_F32 != STORES_BF16, "vmcnt range");
+    constexpr int LANE_BIAS = 4096;
+    unsigned aoff[LOADS8], boff[LOADS8];
+    const char *a_ptr = nullptr, *b_ptr = nullptr;
+    int issue_item = blockIdx.x;
+    int issue_stage = 0;
+
+    auto point_loads_at = [&](int item) __attribute__((always_inline)) {
+        const int tile = item % p.tiles, shard = item / p.tiles;
+        const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
+        const int64_t kbase = (int64_t)shard * p.k_per_shard;
+        a_ptr = uniform_pointer(reinterpret_cast<const char *>(p.X + (int64_t)m0 * p.ldx + kbase));
+        b_ptr = uniform_pointer(reinterpret_cast<const char *>(p.Wt + (int64_t)n0 * p.ldw + kbase) - LANE_BIAS);
+#pragma unroll
+        for (int j = 0; j < LOADS8; ++j) {
+            const int r = (wave * LOADS8 + j) * 8 + (lane >> 3);
+            const int c = (lane & 7) ^ ((r >> 1) & 7);
+            aoff[j] = (unsigned)(min(r, p.M - 1 - m0) * (int)p.ldx + c * 16) + (unsigned)((LOADS8 - j) * 1024);
+            boff[j] = (unsigned)(min(r, p.N - 1 - n0) * (int)p.ldw + c * 16) + (unsigned)(LANE_BIAS - j * 1024);
+        }
+    };
+
+    const unsigned smem_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const unsigned m0_in_stage = smem_lds + wave_u * REGION8 + LOADS8 * 1024;
+    auto issue_part = [&](int slot, auto part_c) __attribute__((always_inline)) {
+        constexpr int PART = decltype(part_c)::value;
+        if (PART == 0 && __builtin_expect(issue_stage == stages_per_item, 0)) {
+            if (issue_item + (int)gridDim.x < p.work) {
+                issue_item += gridDim.x;
+                point_loads_at(issue_item);
+                issue_stage = 0;
+            } else {                                   // past the end: load the last stage again (nobody consumes it)
+                issue_stage = stages_per_item - 1;
+                a_ptr -= BK8;
+                b_ptr -= BK8;
+            }
+        }
+        const unsigned m0v = m0_in_stage + slot * STAGE8;
+        load_16B_per_lane_to_lds<(PART - LOADS8) * 1024, PART == 0>(a_ptr, aoff[PART], m0v);
+        load_16B_per_lane_to_lds<PART * 1024, false>(b_ptr, boff[PART], m0v);
+        if (PART == LOADS8 - 1) {
+            ++issue_stage;
+            a_ptr += BK8;
+            b_ptr += BK8;
+        }
+    };
+    auto issue_next_stage = [&](int slot) {
+        issue_part(slot, Int<0>{});
+        issue_part(slot, Int<1>{});
+        issue_part(slot, Int<2>{});
+        issue_part(slot, Int<3>{});
+    };
+
+    // ---- LDS fragment addresses (bytes inside a stage) ----
+    // Row R of the X tile lies in region R / 32 at row R % 32; row n of the Wt tile likewise, 4 KiB further.
+    int a_off[MT], b_off[NT];
+#pragma unroll
+    for (int a = 0; a < MT; ++a) a_off[a] = (wm * MT + a) * REGION8 + li * ROW8;
+#pragma unroll
+    for (int b = 0; b < NT; ++b) b_off[b] = (wn * NT + b) * REGION8 + LOADS8 * 1024 + li * ROW8;
+    const int sw = (li >> 1) & 7;
+    // chunk positions of the lane's 32 bytes in K-step ks: (4 ks + 2 lg) ^ sw and (4 ks + 2 lg + 1) ^ sw
+    int c_off[KSTEPS8][2];
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS8; ++ks) {
+        c_off[ks][0] = ((4 * ks + 2 * lg) ^ sw) << 4;
+        c_off[ks][1] = ((4 * ks + 2 * lg + 1) ^ sw) << 4;
+    }
+
+    // Fragment registers: one set per K-step of a stage; the reads run one K-step (four MFMAs of 16 passes) ahead.
+    i32x4 fr[KSTEPS8][MT + NT][2];
+    constexpr int READS_PER_KSTEP = 2 * (MT + NT);
+    auto read_frag_op = [&](int r, int set, int slot, int ks) {
+        const unsigned char *sb = smem + slot * STAGE8;
+        const int f = r >> 1, h = r & 1;
+        const int base = f < MT ? a_off[f] : b_off[f - MT];
+        fr[set][f][h] = *reinterpret_cast<const i32x4 *>(sb + base + c_off[ks][h]);
+    };
+    auto read_frags = [&](int set, int slot, int ks) {
+#pragma unroll
+        for (int r = 0; r < READS_PER_KSTEP; ++r) read_frag_op(r, set, slot, ks);
+    };
+    auto frag = [&](int set, int f) {
+        union { i32x4 h[2]; i32x8 v; } u;
+        u.h[0] = fr[set][f][0];
+        u.h[1] = fr[set][f][1];
+        return u.v;
+    };
+
+    Acc<MT, NT> acc, acc2;
+    TileStash<LEVELS - 1, MT, NT> stash;
+
+    // Software pipeline over the ring, as in the 16-bit kernel: at the top of stage s wait until this wavefront's loads
+    // of stage s+1 have landed, meet the other wavefronts -- stage s+1 is complete, nobody reads the slot of stage s-1
+    // any more -- and start the loads of stage s+RING-1 into that slot.
+    point_loads_at(issue_item);
+#pragma unroll
+    for (int i = 0; i < RING8 - 1; ++i) issue_next_stage(i);
+    wait_loads_and_barrier<LOADS_PER_STAGE * (RING8 - 2)>();
+    read_frags(0, 0, 0);
+
+    int cur = 0;
+    int stores_in_flight = 0;          // output stores share the counter of the loads (see the 16-bit kernel)
+
+    auto stage = [&](auto first, Acc<MT, NT> &a) {
+        constexpr bool FIRST = decltype(first)::value;
+        const int nxt = (cur + 1 == RING8) ? 0 : cur + 1;
+        constexpr int ALLOW = LOADS_PER_STAGE * (RING8 - 3);
+        if (__builtin_expect(stores_in_flight == 0, 1)) {
+            wait_loads_and_barrier<ALLOW>();
+        } else {
+            if (stores_in_flight == STORES_F32) wait_loads_and_barrier<ALLOW + STORES_F32>();
+            else if (stores_in_flight == STORES_BF16) wait_loads_and_barrier<ALLOW + STORES_BF16>();
+            else wait_loads_and_barrier<0>();
+            stores_in_flight = 0;
+        }
+        const int free_slot = cur == 0 ? RING8 - 1 : cur - 1;
+        constexpr int NM = MT * NT;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS8; ++ks) {
+            const bool ahead_in_stage = ks + 1 < KSTEPS8;
+            const int t_set = ahead_in_stage ? ks + 1 : 0;
+            const int t_slot = ahead_in_stage ? cur : nxt;
+#pragma unroll
+            for (int m = 0; m < NM; ++m) {
+                const int i = m / NT, j = m % NT;
+                if (FIRST && ks == 0) {
+                    const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                    a.t[i][j] = mfma_32x32x64_8bit<FMT>(frag(0, i), frag(0, MT + j), zero);
+                } else {
+                    a.t[i][j] = mfma_32x32x64_8bit<FMT>(frag(ks, i), frag(ks, MT + j), a.t[i][j]);
+                }
+                // this MFMA's share of the LDS reads of the next K-step and of the loads of the stage being fetched
+#pragma unroll
+                for (int r = m * READS_PER_KSTEP / NM; r < (m + 1) * READS_PER_KSTEP / NM; ++r)
+                    read_frag_op(r, t_set, t_slot, t_set);
+                if (m == 1) {
+                    if (ks == 0) issue_part(free_slot, Int<0>{});
+                    if (ks == 1) issue_part(free_slot, Int<2>{});
+                }
+                if (m == 3) {
+                    if (ks == 0) issue_part(free_slot, Int<1>{});
+                    if (ks == 1) issue_part(free_slot, Int<3>{});
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        cur = nxt;
+    };
+
+    auto superleaf = [&](Acc<MT, NT> &a) {
+        stage(std::true_type{}, a);
+#pragma nounroll
+        for (int q = 1; q < p.stages_per_superleaf; ++q) stage(std::false_type{}, a);
+    };
+
+    for (int item = blockIdx.x; item < p.work; item += gridDim.x) {
+        SubtreeWalker<LEVELS>::run(superleaf, acc, acc2, stash);
+
+        const int tile = item % p.tiles, shard = item / p.tiles;
+        const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
+        float *part = p.partials ? p.partials + (int64_t)shard * p.M * p.N : nullptr;
+        const bool interior = (m0 + BM <= p.M) && (n0 + BN <= p.N);
+        if (interior && p.vector_stores) {
+            // Each wavefront turns its 32 x 64 blocks around in its own region of the slot that was multiplied last
+            // (nothing is loaded into it before the next stage's barrier; the barrier here is for the other wavefronts'
+            // fragment reads), so that a lane stores 16 consecutive bytes.  A fixed number of store instructions.
+            static_assert(REGION8 >= 32 * WCOLS * 4, "the output patch must fit a wavefront's region of a slot");
+            const int last_slot = cur == 0 ? RING8 - 1 : cur - 1;
+            float *patch = reinterpret_cast<float *>(smem + last_slot * STAGE8 + wave * REGION8);
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            const bool to_bf16 = (part == nullptr) && p.y_bf16;
+            const int wm_u = wave_u / WN, wn_u = wave_u % WN;
+            const int col0 = n0 + wn_u * WCOLS;
+            if (to_bf16) {
+                constexpr int CPR = WCOLS / 8, RPI = 64 / CPR, N_IT = 32 / RPI;
+                const int lrow = lane / CPR, lc = lane % CPR;
+                const float *rd = patch + lrow * WCOLS + lc * 8;
+                const unsigned lane_off = (unsigned)(lrow * (int)p.ldy + lc * 8) * 2u;
+                const int64_t it_step = (int64_t)RPI * p.ldy * 2;
+#pragma unroll
+                for (int a = 0; a < MT; ++a) {
+#pragma unroll
+                    for (int b = 0; b < NT; ++b)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            patch[(8 * (r >> 2) + 4 * lg + (r & 3)) * WCOLS + b * 32 + li] = acc.t[a][b][r];
+                    f32x4 lo[N_IT], hi[N_IT];
+#pragma unroll
+                    for (int it = 0; it < N_IT; ++it) {
+                        lo[it] = *reinterpret_cast<const f32x4 *>(rd + it * RPI * WCOLS);
+                        hi[it] = *reinterpret_cast<const f32x4 *>(rd + it * RPI * WCOLS + 4);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    char *base = reinterpret_cast<char *>(reinterpret_cast<uint16_t *>(p.Y) +
+                                                          (int64_t)(m0 + (wm_u * MT + a) * 32) * p.ldy + col0);
+#pragma unroll
+                    for (int it = 0; it < N_IT; ++it) {
+                        u32x4 o;
+                        o[0] = pack_bf16x2(lo[it][0], lo[it][1]);
+                        o[1] = pack_bf16x2(lo[it][2], lo[it][3]);
+                        o[2] = pack_bf16x2(hi[it][0], hi[it][1]);
+                        o[3] = pack_bf16x2(hi[it][2], hi[it][3]);
+                        *reinterpret_cast<u32x4 *>(base + it * it_step + lane_off) = o;
+                    }
+                }
+            } else {
+                constexpr int CPR = WCOLS / 4, RPI = 64 / CPR, N_IT = 32 / RPI;
+                float *dst = part ? part : reinterpret_cast<float *>(p.Y);
+                const int64_t ld = part ? p.N : p.ldy;
+                const int lrow = lane / CPR, lc = lane % CPR;
+                const float *rd = patch + lrow * WCOLS + lc * 4;
+                const unsigned lane_off = (unsigned)(lrow * (int)ld + lc * 4) * 4u;
+                const int64_t it_step = (int64_t)RPI * ld * 4;
+#pragma unroll
+                for (int a = 0; a < MT; ++a) {
+#pragma unroll
+                    for (int b = 0; b < NT; ++b)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            patch[(8 * (r >> 2) + 4 * lg + (r & 3)) * WCOLS + b * 32 + li] = acc.t[a][b][r];
+                    f32x4 v[N_IT];
+#pragma unroll
+                    for (int it = 0; it < N_IT; ++it) v[it] = *reinterpret_cast<const f32x4 *>(rd + it * RPI * WCOLS);
+                    __builtin_amdgcn_sched_barrier(0);
+                    char *base = reinterpret_cast<char *>(dst + (int64_t)(m0 + (wm_u * MT + a) * 32) * ld + col0);
+                    if (p.stream_stores) {
+#pragma unroll
+                        for (int it = 0; it < N_IT; ++it)
+                            asm volatile("global_store_dwordx4 %0, %1, off nt" ::"v"(base + it * it_step + lane_off), "v"(v[it]) : "memory");
+                    } else {
+#pragma unroll
+                        for (int it = 0; it < N_IT; ++it) *reinterpret_cast<f32x4 *>(base + it * it_step + lane_off) = v[it];
+                    }
+                }
+            }
+            stores_in_flight = to_bf16 ? STORES_BF16 : STORES_F32;
+        } else {
+#pragma unroll
+            for (int a = 0; a < MT; ++a) {
+#pragma unroll
+                for (int b = 0; b < NT; ++b) {
+                    const int col = n0 + (wn * NT + b) * 32 + li;
+                    if (col >= p.N) continue;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int row = m0 + (wm * MT + a) * 32 + 8 * (r >> 2) + 4 * lg + (r & 3);
+                        if (row >= p.M) continue;
+                        const float v = acc.t[a][b][r];
+                        if (part) part[(int64_t)row * p.N + col] = v;
+                        if (p.Y) {
+                            if (p.y_bf16) reinterpret_cast<uint16_t *>(p.Y)[(int64_t)row * p.ldy + col] = (uint16_t)f32_to_bf16_bits(v);
+                            else reinterpret_cast<float *>(p.Y)[(int64_t)row * p.ldy + col] = v;
+                        }
+                    }
+                }
+            }
+            stores_in_flight = -1;
+        }
+    }
+    wait_loads_and_barrier<0>();                          // no load may still be writing LDS when the workgroup ends
+}
+
+int levels_for(int ns_per_shard) {
+    int l = 0;
+    while ((1 << l) < ns_per_shard) ++l;
+    return l;
+}
+
+int compute_units() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
+}
+
+template <int FMT>
+hipError_t launch_tiled_fmt(const GemmArgs &a, hipStream_t s) {
+    constexpr int BM = 128, BN = 128;
+    Fp8Params p;
+    p.X = reinterpret_cast<const uint8_t *>(a.X); p.Wt = reinterpret_cast<const uint8_t *>(a.W);
+    p.partials = a.partials; p.Y = (a.P == 1) ? a.Y : nullptr;
+    p.ldx = a.ldx; p.ldw = a.ldw; p.ldy = a.ldy;
+    p.M = a.M; p.N = a.N;
+    p.y_bf16 = (a.y_dtype != TBIK_F32);
+    p.stages_per_superleaf = a.superleaf / BK8;
+    p.ns_per_shard = a.ns / a.P;
+    p.k_per_shard = (int64_t)a.K / a.P;
+    p.tiles_n = (a.N + BN - 1) / BN;
+    const int64_t tiles = (int64_t)p.tiles_n * ((a.M + BM - 1) / BM);
+    if (tiles * a.P > 0x7fffffff) return hipErrorInvalidValue;
+    p.tiles = (int)tiles;
+    p.work = (int)(tiles * a.P);
+    const int grid_x = p.work < compute_units() ? p.work : compute_units();
+    dim3 grid((unsigned)grid_x), block(256);
+    const size_t lds = (size_t)RING8 * STAGE8;
+    const void *out = p.partials ? (const void *)p.partials : p.Y;
+    const int64_t ld_bytes = p.partials ? (int64_t)a.N * 4 : a.ldy * (p.y_bf16 ? 2 : 4);
+    p.vector_stores = ((reinterpret_cast<uintptr_t>(out) & 15) == 0) && (ld_bytes % 16 == 0);
+    p.stream_stores = a.partials != nullptr && (int64_t)a.P * a.M * a.N * 4 > ((int64_t)192 << 20);
+    const int levels = levels_for(p.ns_per_shard);
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 32) dev = 32;
+#define TBIK_LAUNCH8(L)                                                                                  \
+    case L: {                                                                                            \
+        auto k = gemm_fp8_tiled_kernel<L, FMT>;                                                          \
+        static std::atomic<unsigned> lds_allowed{0};                                                     \
+        if (dev >= 32 || !((lds_allowed.load(std::memory_order_relaxed) >> dev) & 1u)) {                 \
+            hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+            if (e != hipSuccess) return e;                                                               \
+            if (dev < 32) lds_allowed.fetch_or(1u << dev, std::memory_order_relaxed);                    \
+        }                                                                                                \
+        hipLaunchKernelGGL(k, grid, block, lds, s, p);                                                   \
+        break;                                                                                           \
+    }
+    switch (levels) {
+        TBIK_LAUNCH8(0)
+        TBIK_LAUNCH8(1)
+        TBIK_LAUNCH8(2)
+        TBIK_LAUNCH8(3)
+        TBIK_LAUNCH8(4)
+        default: return hipErrorInvalidValue;
+    }
+#undef TBIK_LAUNCH8
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool gemm_fp8_tiled_supports(const GemmArgs &a) {
+    if (a.superleaf % BK8 != 0) return false;
+    if (levels_for(a.ns / a.P) > 4) return false;
+    if (a.ldx >= (1 << 22) || a.ldw >= (1 << 22)) return false;     // per-lane byte offsets of a tile stay below 2^31
+    return true;
+}
+
+hipError_t launch_gemm_fp8_tiled(const GemmArgs &a, hipStream_t s) {
+    if (a.M <= 0 || a.N <= 0) return hipSuccess;
+    if (!gemm_fp8_tiled_supports(a)) return hipErrorInvalidValue;
+    return a.x_dtype == TBIK_FP8_E5M2 ? launch_tiled_fmt<1>(a, s) : launch_tiled_fmt<0>(a, s);
+}
+
+hipError_t launch_gemm_fp8_reference(const GemmArgs &a, hipStream_t s) {
+    if (a.M <= 0 || a.N <= 0) return hipSuccess;
+    if (a.superleaf % 64 != 0) return hipErrorInvalidValue;
+    dim3 grid((a.N + 31) / 32, (a.M + 31) / 32, a.P);
+    if (grid.y > 65535u || grid.z > 65535u) return hipErrorInvalidValue;
+    void *Y = (a.P == 1) ? a.Y : nullptr;
+    auto kernel = (a.x_dtype == TBIK_FP8_E5M2) ? gemm_fp8_reference_kernel<1> : gemm_fp8_reference_kernel<0>;
+    hipLaunchKernelGGL(kernel, grid, dim3(64), 0, s, reinterpret_cast<const uint8_t *>(a.X), a.ldx,
+                       reinterpret_cast<const uint8_t *>(a.W), a.ldw, a.partials, Y, a.ldy, a.y_dtype, a.M, a.N,
+                       a.superleaf, a.ns / a.P);
+    return hipGetLastError();
+}
+
+}  // namespace tbik

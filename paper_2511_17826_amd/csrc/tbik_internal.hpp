@@ -10,7 +10,7 @@ namespace tbik {
 
 // Resolved description of one GEMM request; validated by the C ABI layer before any launch.
 struct GemmArgs {
-    const uint16_t *X;   // x_dtype [M, ldx]
+    const uint16_t *X;   // x_dtype [M, ldx] (fp32 and 8-bit operands: the pointer is cast)
     int64_t ldx;
     const uint16_t *W;   // x_dtype [K, ldw]
     int64_t ldw;
@@ -48,6 +48,12 @@ hipError_t launch_tree_combine_swiglu(const float *partials, int P, uint16_t *ac
 hipError_t launch_gemm_f32_reference(const GemmArgs &a, hipStream_t s);
 hipError_t launch_gemm_f32_tiled(const GemmArgs &a, int variant, hipStream_t s);   // variant: tile shape, see kVariantNames
 bool gemm_f32_tiled_supports(const GemmArgs &a);
+
+// The same for 8-bit floating-point operands (x_dtype TBIK_FP8_E4M3 or TBIK_FP8_E5M2): X points to [M, ldx] bytes, W
+// to the TRANSPOSED weight [N, ldw] bytes; Y is fp32 or bf16.  One tile shape (128 x 128).
+hipError_t launch_gemm_fp8_reference(const GemmArgs &a, hipStream_t s);
+hipError_t launch_gemm_fp8_tiled(const GemmArgs &a, hipStream_t s);
+bool gemm_fp8_tiled_supports(const GemmArgs &a);
 
 // Y = T(partials[0..P)) elementwise + one rounding.
 hipError_t launch_tree_combine(const float *partials, int P, void *Y, int64_t ldy, int y_dtype, int M, int N,
