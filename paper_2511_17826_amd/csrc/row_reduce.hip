@@ -231,67 +231,65 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_one_block_kernel(const 
 // workgroup whose wait runs out marks its row and leaves, and logsoftmax_redo_kernel recomputes marked rows.
 // Arithmetic (leaves, block tree, tree over blocks, expf, logf) is that of the three-kernel path: same bits.
 constexpr int RR_MAX_COOP_BLOCKS = 256;
-// Per row 64 words (a 256-byte line of its own): arrival counters at words 0 and 16, the row maximum at word 8 and the
-// row's sum of exponentials at word 24 (both start as RR_NOT_YET), the give-up flag at word 32.
+// Per row 64 words (a 256-byte line of its own), of which one is used: the give-up flag.
 constexpr int RR_SYNC_WORDS = 64;
-constexpr int RR_W_ARRIVED_MAX = 0, RR_W_ROWMAX = 8, RR_W_ARRIVED_SUM = 16, RR_W_ROWSUM = 24, RR_W_GAVE_UP = 32;
+constexpr int RR_W_GAVE_UP = 32;
 constexpr unsigned RR_NOT_YET = 0xffffffffu;     // a NaN pattern: neither a maximum of finite logits nor a sum of exponentials
 
-// Thread 0 waits until the row's result word holds a value; every thread gets it.  One word is both the flag and the
-// datum, so a reader that is served an old copy only waits longer: nothing else has to be ordered against it.
-__device__ __forceinline__ bool wait_for_word(const unsigned *word, const unsigned *gave_up, int limit, unsigned *lds_word,
-                                              float *value) {
-    if (threadIdx.x == 0) {
-        unsigned v = RR_NOT_YET;
+// One value per workgroup travels through memory, between workgroups that may sit on different chiplets with
+// separate L2 caches.  No cache is flushed or invalidated for it (a release/acquire pair at device scope would write
+// back and invalidate a chiplet's whole L2 on every call): the value is written with a read-modify-write atomic of
+// device scope, which is performed where all chiplets meet, into a word that starts the call as "not yet", and read
+// with device-scope atomic loads.  The word is its own arrival flag: there is no counter to order it against.
+// The first wavefront reads the n slots of a row (lane l: slots l, l + 64, ...) until every one holds a value, then
+// combines them -- the maximum, or T over the slots padded with +0 to n2 = 2^t (SUM) -- and every thread of the
+// workgroup gets the result.  Returns false if the wait ran out (or another workgroup of the row has given up).
+constexpr int RR_SLOTS_PER_LANE = 4;             // RR_MAX_COOP_BLOCKS / 64
+
+template <bool SUM>
+__device__ __forceinline__ bool gather_row(const float *slots, int n, int n2, const unsigned *gave_up, int limit, int sleep_units,
+                                           unsigned *lds_word, float *value) {
+    if (threadIdx.x < 64) {
+        const int lane = threadIdx.x;
+        unsigned u[RR_SLOTS_PER_LANE];
+        bool complete = false;
         for (int it = 0; it <= limit; ++it) {
-            v = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (v != RR_NOT_YET) break;
+            bool mine = true;
+#pragma unroll
+            for (int j = 0; j < RR_SLOTS_PER_LANE; ++j) {
+                const int i = j * 64 + lane;
+                u[j] = 0u;
+                if (i < n) {
+                    u[j] = __hip_atomic_load(reinterpret_cast<const unsigned *>(slots + i), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    mine = mine && (u[j] != RR_NOT_YET);
+                }
+            }
+            if (__all(mine)) { complete = true; break; }
             if ((it & 15) == 15 && __hip_atomic_load(gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
-            __builtin_amdgcn_s_sleep(4);
+            for (int z = 0; z < (sleep_units & 255); ++z) __builtin_amdgcn_s_sleep(8);
         }
-        *lds_word = v;
+        float r;
+        if (SUM) {
+            TreeStash<2> st;                          // up to 4 groups of 64 slots
+            r = 0.0f;
+            const int nseg = n2 < 64 ? 1 : n2 >> 6;
+#pragma unroll
+            for (int j = 0; j < RR_SLOTS_PER_LANE; ++j)
+                if (j < nseg) r = st.push(wave_tree_sum((j * 64 + lane < n) ? __uint_as_float(u[j]) : 0.0f), (unsigned)j);
+        } else {
+            float m = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < RR_SLOTS_PER_LANE; ++j)
+                if (j * 64 + lane < n) m = fmaxf(m, __uint_as_float(u[j]));
+            r = wave_max(m);
+        }
+        if (lane == 0) *lds_word = complete ? __float_as_uint(r) : RR_NOT_YET;
     }
     __syncthreads();
     const unsigned v = *lds_word;
     __syncthreads();
     *value = __uint_as_float(v);
     return v != RR_NOT_YET;
-}
-
-// One value per workgroup travels through memory, between workgroups that may sit on different chiplets with
-// separate L2 caches.  No cache is flushed or invalidated for it (a release/acquire pair at device scope would write
-// back and invalidate a chiplet's whole L2 on every call): the value is written and read with read-modify-write
-// atomics of device scope, which are performed where all chiplets meet, and the writer has its atomic's return
-// value in hand -- so the value is in place -- before it counts its arrival with another such atomic.
-__device__ __forceinline__ unsigned publish(float *slot, float v, unsigned *counter) {
-    const unsigned old = __hip_atomic_exchange(reinterpret_cast<unsigned *>(slot), __float_as_uint(v), __ATOMIC_RELAXED,
-                                               __HIP_MEMORY_SCOPE_AGENT);
-    // The increment is made to depend on the exchange's return value (through an empty statement the compiler cannot
-    // see through, which also keeps memory operations from moving across it), so the arrival cannot be issued before
-    // the exchange has returned.
-    unsigned one = 1u;
-    asm volatile("" : "+v"(one) : "v"(old) : "memory");
-    return __hip_atomic_fetch_add(counter, one, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);     // how many arrived before
-}
-__device__ __forceinline__ float coherent_load(const float *p) {
-    return __uint_as_float(__hip_atomic_fetch_or(reinterpret_cast<unsigned *>(const_cast<float *>(p)), 0u, __ATOMIC_RELAXED,
-                                                 __HIP_MEMORY_SCOPE_AGENT));
-}
-__device__ __forceinline__ float wave_max_of_published(const float *p, int n, int lane) {
-    float m = -INFINITY;
-    for (int i = lane; i < n; i += 64) m = fmaxf(m, coherent_load(p + i));
-    return wave_max(m);
-}
-__device__ __forceinline__ float wave_tree_of_published(const float *p, int n, int n2, int lane) {
-    TreeStash<26> st;
-    float tot = 0.0f;
-    const int nseg = n2 < 64 ? 1 : n2 >> 6;
-    for (int seg = 0; seg < nseg; ++seg) {
-        const int i = seg * 64 + lane;
-        const float v = (i < n) ? coherent_load(p + i) : 0.0f;
-        tot = st.push(wave_tree_sum(v), (unsigned)seg);
-    }
-    return tot;
 }
 
 // BPW: consecutive blocks of the row per workgroup (1, 2 or 4; the first of them a multiple of BPW, so together they
@@ -301,12 +299,13 @@ __device__ __forceinline__ float wave_tree_of_published(const float *p, int n, i
 template <int XT, int BPW>
 __global__ __launch_bounds__(RR_THREADS) void logsoftmax_coop_kernel(const void *__restrict__ x, int64_t V, int nwg, int nwg2,
                                                                     float *wsmax, float *wssum, unsigned *sync_words,
-                                                                    int wait_limit, float *__restrict__ out) {
+                                                                    int wait_limit, int sleep_units, float *__restrict__ out) {
+    // sleep_units: bits 8 and up, units of s_sleep 32 before the first look at a row's slots; low byte, units of s_sleep 8
+    // between looks.
     __shared__ float lds[RR_SEGS * 4];
     __shared__ unsigned lds_word;
     constexpr int EPL = Elem<XT>::EPL;
     const int row = (int)(blockIdx.x / (unsigned)nwg), w = (int)(blockIdx.x % (unsigned)nwg);
-    const int lane = threadIdx.x & 63;
     const int64_t nleaves = V / EPL;
     const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * Elem<XT>::BYTES;
     float *orow = out + (int64_t)row * V;
@@ -325,20 +324,18 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_coop_kernel(const void 
                 for (int e = 0; e < EPL; ++e) mx = fmaxf(mx, f[k][seg][e]);
             }
         }
-    // The workgroup that arrives last combines the row's results and puts the row's result where the others wait for
-    // it: per row and step one exchange and one count per workgroup, one round of reads and one result word, instead of
-    // everybody reading everybody's value (atomics on one memory line are served one after the other).
+    // Hand-off: the workgroup puts its block's value into its own slot of the row (one read-modify-write atomic, performed
+    // where all chiplets meet; nobody waits for its return) and its first wavefront then reads the row's slots, all of
+    // them side by side in its lanes, until none holds the "not yet" pattern the call started them with.  A slot is flag
+    // and datum in one word, so a reader that is served an old copy only reads again; the values it ends up with are
+    // final, and every workgroup of the row combines the same values in the same order.
     const float bm = block_max(mx, lds);
-    if (threadIdx.x == 0) lds_word = publish(wsmax + (int64_t)row * nwg + w, bm, words + RR_W_ARRIVED_MAX);
-    __syncthreads();
-    const bool last_max = (lds_word == (unsigned)(nwg - 1));
-    __syncthreads();
+    if (threadIdx.x == 0)
+        __hip_atomic_exchange(reinterpret_cast<unsigned *>(wsmax + (int64_t)row * nwg + w), __float_as_uint(bm), __ATOMIC_RELAXED,
+                              __HIP_MEMORY_SCOPE_AGENT);
+    for (int z = 0; z < (sleep_units >> 8); ++z) __builtin_amdgcn_s_sleep(32);
     float rowmax;
-    if (last_max) {
-        rowmax = wave_max_of_published(wsmax + (int64_t)row * nwg, nwg, lane);          // every wavefront: the same value
-        if (threadIdx.x == 0)
-            __hip_atomic_exchange(words + RR_W_ROWMAX, __float_as_uint(rowmax), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    } else if (!wait_for_word(words + RR_W_ROWMAX, gave_up, wait_limit, &lds_word, &rowmax)) {
+    if (!gather_row<false>(wsmax + (int64_t)row * nwg, nwg, nwg2, gave_up, wait_limit, sleep_units, &lds_word, &rowmax)) {
         if (threadIdx.x == 0) __hip_atomic_store(gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;
     }
@@ -361,16 +358,12 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_coop_kernel(const void 
         bsum[k] = block_tree_sum(L, lds);          // a block past the end of the row sums to +0
     }
     const float bs = tree_of(bsum);                // T over this workgroup's blocks
-    if (threadIdx.x == 0) lds_word = publish(wssum + (int64_t)row * nwg + w, bs, words + RR_W_ARRIVED_SUM);
-    __syncthreads();
-    const bool last_sum = (lds_word == (unsigned)(nwg - 1));
-    __syncthreads();
+    if (threadIdx.x == 0)
+        __hip_atomic_exchange(reinterpret_cast<unsigned *>(wssum + (int64_t)row * nwg + w), __float_as_uint(bs), __ATOMIC_RELAXED,
+                              __HIP_MEMORY_SCOPE_AGENT);
+    for (int z = 0; z < (sleep_units >> 8); ++z) __builtin_amdgcn_s_sleep(32);
     float S;
-    if (last_sum) {
-        S = wave_tree_of_published(wssum + (int64_t)row * nwg, nwg, nwg2, lane);
-        if (threadIdx.x == 0)
-            __hip_atomic_exchange(words + RR_W_ROWSUM, __float_as_uint(S), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    } else if (!wait_for_word(words + RR_W_ROWSUM, gave_up, wait_limit, &lds_word, &S)) {
+    if (!gather_row<true>(wssum + (int64_t)row * nwg, nwg, nwg2, gave_up, wait_limit, sleep_units, &lds_word, &S)) {
         if (threadIdx.x == 0) __hip_atomic_store(gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;
     }
@@ -463,11 +456,15 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_redo_kernel(const void 
     }
 }
 
-// Counters and flag to zero, the two result words of every row to "not yet".
-__global__ __launch_bounds__(256) void reset_sync_words_kernel(unsigned *p, int64_t n) {
+// Before every call: the slots of both hand-offs to "not yet", the rows' flags to zero.
+__global__ __launch_bounds__(256) void reset_sync_words_kernel(unsigned *slots_max, unsigned *slots_sum, int64_t nslots,
+                                                                unsigned *words, int64_t nwords) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int w = (int)(i % RR_SYNC_WORDS);
-    if (i < n) p[i] = (w == RR_W_ROWMAX || w == RR_W_ROWSUM) ? RR_NOT_YET : 0u;
+    if (i < nslots) {
+        slots_max[i] = RR_NOT_YET;
+        slots_sum[i] = RR_NOT_YET;
+    }
+    if (i < nwords) words[i] = 0u;
 }
 
 static std::atomic<int> g_wait_limit{1 << 14};   // polls per wait: tens of milliseconds at most
@@ -512,17 +509,25 @@ static hipError_t run(const void *x, void *out, int op, int M, int64_t V, void *
         } else if (nb <= RR_MAX_COOP_BLOCKS && (int64_t)mc * nb <= 0x7fffffff) {
             unsigned *words = reinterpret_cast<unsigned *>(ws1 + (size_t)M * nb) + (size_t)m0 * RR_SYNC_WORDS;
             const int64_t nwords = (int64_t)mc * RR_SYNC_WORDS;
-            hipLaunchKernelGGL(reset_sync_words_kernel, dim3((unsigned)((nwords + 255) / 256)), dim3(256), 0, s, words, nwords);
+            const int64_t nslots = (int64_t)mc * nb, nreset = nslots > nwords ? nslots : nwords;
+            hipLaunchKernelGGL(reset_sync_words_kernel, dim3((unsigned)((nreset + 255) / 256)), dim3(256), 0, s,
+                               reinterpret_cast<unsigned *>(w0), reinterpret_cast<unsigned *>(w1), nslots, words, nwords);
             // two blocks per workgroup for fp32 rows once the launch has more workgroups than the device holds at a time
             // (more of the row on the chip per resident workgroup); the choice cannot change a bit
+            // Waiting costs the others bandwidth: a wavefront that polls takes issue slots and memory requests from the
+            // workgroups that stream.  When the launch fills the device, a workgroup sleeps about 2 us (2 x s_sleep 32)
+            // before its first look -- no hand-off completes sooner -- and about 0.5 us between looks (measured at
+            // 512 x 151936: 200 us without the first sleep, 171 us with it, 191 us with twice as long; M = 1 loses 3 us
+            // with it, so small launches look at once).
+            const int sleep_units = (((int64_t)mc * nb >= 256 ? 2 : 0) << 8) | 2;
             const bool two = false;   // measured: 195 -> 282 us at 512 x 151936 (170 registers, three workgroups per compute unit)
             const int nwg = two ? (nb + 1) / 2 : nb, nwg2 = two ? (nb2 + 1) / 2 : nb2;
             if (two)
                 hipLaunchKernelGGL((logsoftmax_coop_kernel<XT, (XT == TBIK_F32 ? 2 : 1)>), dim3((unsigned)((int64_t)mc * nwg)), block, 0, s,
-                                   xp, V, nwg, nwg2, w0, w1, words, g_wait_limit.load(), o + m0 * V);
+                                   xp, V, nwg, nwg2, w0, w1, words, g_wait_limit.load(), sleep_units, o + m0 * V);
             else
                 hipLaunchKernelGGL((logsoftmax_coop_kernel<XT, 1>), dim3((unsigned)((int64_t)mc * nwg)), block, 0, s,
-                                   xp, V, nwg, nwg2, w0, w1, words, g_wait_limit.load(), o + m0 * V);
+                                   xp, V, nwg, nwg2, w0, w1, words, g_wait_limit.load(), sleep_units, o + m0 * V);
             hipLaunchKernelGGL((logsoftmax_redo_kernel<XT>), dim3(mc), block, 0, s, xp, V, nb, nb2,
                                (const unsigned *)words, o + m0 * V);
         } else {

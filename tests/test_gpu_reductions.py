@@ -185,9 +185,10 @@ def test_logsoftmax_long_rows_repeatable_under_load():
 
 
 def test_logsoftmax_finds_no_stale_value_in_a_poisoned_workspace():
-    """The published block maxima and sums sit in the caller's workspace, which keeps the last call's contents.  A
-    workgroup that read a slot before its writer's value was in place would pick up what the workspace held before:
-    here that is NaN (every byte 0xff) before every call, which no log-softmax of finite logits contains."""
+    """The published block maxima and sums sit in the caller's workspace, which keeps the last call's contents.  Every
+    call first sets its slots to a "not yet" pattern, and a slot counts as written once it holds anything else -- so
+    whatever the workspace held before must be gone by then.  Here that is, in turn, NaN (every byte 0xff) and a
+    plausible finite number (every byte 0x42: 48.56), which as a stale block maximum or sum would change the result."""
     V = 151936
     x = gu.dev_f32(syn.logits_f32(256, V, seed=9))
     need = int(tb.lib().tbik_row_reduce_workspace_bytes(256, V, tb.TBIK_LOGSOFTMAX))
@@ -195,7 +196,7 @@ def test_logsoftmax_finds_no_stale_value_in_a_poisoned_workspace():
     want = tb.tbik_row_reduce(x, tb.TBIK_LOGSOFTMAX)
     out = torch.empty_like(want)
     for rep in range(20):
-        ws.fill_(0xff)
+        ws.fill_(0xff if rep % 2 == 0 else 0x42)
         tb.tbik_row_reduce(x, tb.TBIK_LOGSOFTMAX, out=out, workspace=ws)
         assert not bool(torch.isnan(out).any()), rep
         assert torch.equal(out.view(torch.int32), want.view(torch.int32)), rep
