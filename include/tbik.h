@@ -249,8 +249,9 @@ int tbik_row_reduce_static(const void *x, tbik_dtype x_dtype, void *out, tbik_ro
  *   workspace   at least tbik_attention_workspace_bytes(batch, max_seqlen_q, max_seqlen_k, heads_q, heads_kv) bytes,
  *          256-byte aligned; that is 0 (and the pointer may be NULL) when max_seqlen_k <= 4096, else 68 KiB per
  *          128 rows of (query, head) of batch x max_seqlen_q tokens and -- below 512 such blocks -- per split of
- *          max_seqlen_k: about twice the bytes of Q for a long prefill.  Contents on entry do not matter; calls that share a
- *          workspace must not overlap in time
+ *          max_seqlen_k, but never more than 4608 x 68 KiB = 306 MiB (for the usual head counts): a call with more
+ *          blocks than that is launched in pieces that take turns at the area.  Contents on entry do not matter; calls
+ *          that share a workspace must not overlap in time
  *   head_dim 128 (other values: TBIK_ERR_UNSUPPORTED); heads_q a multiple of heads_kv; strides in elements, multiples
  *   of 8, at least heads * head_dim, below 2^24; pointers 16-byte aligned.  O must not overlap Q, K or V.
  * Errors: NULL, SHAPE, UNSUPPORTED, ALIGN, WORKSPACE, HIP.

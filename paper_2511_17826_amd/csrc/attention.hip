@@ -70,6 +70,8 @@ struct AttnParams {
     int ny, nz;                                       // head groups, sequences
     int nb;                                           // bound on the query blocks of the call: block ids 0 .. nb - 1 (see attention_work_item)
     int chunk, nchunks;                               // block ids are dealt to the XCDs in chunks of this many
+    int chunk_lo, chunk_hi;                           // this launch covers chunks chunk_lo .. chunk_hi - 1 (a long call is
+                                                      // launched in several pieces that take turns at one capped scratch area)
     int n_splits;                                     // 1: an item walks all key tiles (folding its splits as it goes);
                                                       // > 1: an item is one split of those, its state goes to `states`
     int max_tiles;                                    // key tiles of a sequence of max_seqlen_k keys: no workgroup walks further
@@ -112,8 +114,8 @@ __device__ __forceinline__ bool attention_work_item(const AttnParams &p, int R, 
     split = t % p.n_splits;
     t /= p.n_splits;
     by = t % p.ny;
-    const int ch = p.nchunks - 1 - t / p.ny;
-    if (ch < 0) return false;                         // the launch is padded to a multiple of 8 runs
+    const int ch = p.chunk_hi - 1 - t / p.ny;
+    if (ch < p.chunk_lo) return false;                // the launch is padded to a multiple of 8 runs
     const int g = ch * p.chunk + (p.chunk - 1 - bx);
     if (g >= p.nb) return false;
     seq = sequence_of_block(p, R, g, lane);
@@ -221,7 +223,7 @@ void attention_kernel(const AttnParams p) {
     if (!attention_work_item(p, R, lane, qb, by, seq, split, base_item)) return;     // uniform
     const bool one_split_each = p.n_splits > 1;                   // uniform: this workgroup computes one split's state
     f32x4 *const my_state = reinterpret_cast<f32x4 *>(const_cast<char *>(uniform_pointer(           // the workgroup's, in scalar registers
-        reinterpret_cast<const char *>(p.states + ((size_t)base_item * p.n_splits + split) * ATT_STATE_FLOATS))));
+        reinterpret_cast<const char *>(p.states + ((size_t)(base_item - p.chunk_lo * p.chunk * p.ny) * p.n_splits + split) * ATT_STATE_FLOATS))));
 
     // Sequence bounds, clamped so that no value of the offset arrays can lead outside the tensors.
     const int q0 = clampi(p.cu_q[seq], 0, p.total_q), q1 = clampi(p.cu_q[seq + 1], q0, p.total_q);
@@ -883,8 +885,15 @@ struct AttnPlan {
     int64_t nchunks;
     int splits_max;          // splits a sequence of max_seqlen_k keys has
     int n_splits;            // 1: every workgroup walks all its tiles; else one workgroup per split, then a merge kernel
-    size_t state_bytes;      // workspace: fold scratch (one state per item) or the states of all splits
+    size_t state_bytes;      // workspace: fold scratch (one state per item of a launch) or the states of all splits
+    int64_t chunks_per_launch;   // walking form: chunks (of block ids) per launch, so that a launch's items fit the capped scratch
 };
+
+// The scratch area never exceeds this many states (68 KiB each: 306 MiB; 16384 queries of 32 heads over 8 are 4104
+// items and still go in one launch).  A call with more items that fold as they walk is launched in equal pieces of at
+// most this many, one after the other on the stream, all using the same area; the form with one workgroup per split
+// is only chosen when all its states fit.
+constexpr int64_t ATT_MAX_STATES = 4608;
 
 // total_q: tokens in Q (or a bound on them); workspace_bytes: what the caller brought (SIZE_MAX: as much as is wanted).
 static AttnPlan plan_attention(int batch, int64_t total_q, int max_seqlen_k, int heads_q, int heads_kv, int variant, size_t workspace_bytes) {
@@ -905,13 +914,21 @@ static AttnPlan plan_attention(int batch, int64_t total_q, int max_seqlen_k, int
     // workgroup per split, all at once, then the fold in a second kernel.  Same bits as one workgroup walking the
     // splits, so the choice is free; below two workgroups per compute unit the parallel form wins -- if the caller's
     // workspace holds its states (sized from a bound on total_q it may not; walking needs less and always fits).
-    pl.n_splits = (pl.splits_max > 1 && pl.items < 512 && (size_t)pl.items * pl.splits_max * state <= workspace_bytes) ? pl.splits_max : 1;
-    pl.state_bytes = pl.splits_max > 1 ? (size_t)pl.items * pl.n_splits * state : 0;
+    pl.n_splits = (pl.splits_max > 1 && pl.items < 512 && pl.items * pl.splits_max <= ATT_MAX_STATES &&
+                   (size_t)pl.items * pl.splits_max * state <= workspace_bytes) ? pl.splits_max : 1;
     // Enough runs to keep every XCD busy (64 or more where the call has that many blocks), chunks of at most 128 blocks.
     const int64_t spread = (pl.items * pl.n_splits + 63) / 64;
     pl.chunk = (int)std::max<int64_t>(1, std::min<int64_t>(spread, std::min<int64_t>(128, pl.nb)));   // no chunk longer than the call: its idle
                                                                   // workgroups would pair the busy ones up on half the compute units
     pl.nchunks = (pl.nb + pl.chunk - 1) / pl.chunk;
+    pl.chunks_per_launch = pl.nchunks;
+    if (pl.splits_max > 1 && pl.n_splits == 1) {
+        const int64_t most = std::max<int64_t>(1, std::min<int64_t>(pl.nchunks, ATT_MAX_STATES / ((int64_t)pl.chunk * pl.ny)));
+        const int64_t pieces = (pl.nchunks + most - 1) / most;
+        pl.chunks_per_launch = (pl.nchunks + pieces - 1) / pieces;
+    }
+    const int64_t launch_items = std::min<int64_t>(pl.items, pl.chunks_per_launch * pl.chunk * pl.ny);
+    pl.state_bytes = pl.splits_max > 1 ? (size_t)(pl.n_splits > 1 ? pl.items * pl.n_splits : launch_items) * state : 0;
     return pl;
 }
 
@@ -923,19 +940,26 @@ size_t attention_workspace(int batch, int max_seqlen_q, int max_seqlen_k, int he
 }
 
 template <bool F16>
-static hipError_t launch_of(const AttnArgs &a, const AttnParams &p, const AttnPlan &pl, hipStream_t s) {
+static hipError_t launch_of(const AttnArgs &a, AttnParams p, const AttnPlan &pl, hipStream_t s) {
     static std::atomic<unsigned> done[4] = {{0}, {0}, {0}, {0}};     // one set per operand format
-    const int64_t runs = pl.nchunks * pl.ny * pl.n_splits;       // (chunk of block ids, head group, split) triples, dealt to the 8 XCDs in turn
-    const dim3 grid((unsigned)((runs + 7) / 8 * 8 * pl.chunk));
-    hipError_t e;
-    if (pl.pingpong) {
-        constexpr int RING = 4;
-        if (a.causal) return launch_with_lds(attention_pingpong_kernel<true, RING, F16>, done[0], grid, dim3(512), 2 * RING * ATT_TILE_BYTES, p, s);
-        return launch_with_lds(attention_pingpong_kernel<false, RING, F16>, done[1], grid, dim3(512), 2 * RING * ATT_TILE_BYTES, p, s);
+    hipError_t e = hipSuccess;
+    // Late chunks first, as inside a launch (under a causal mask they are the long ones).
+    for (int64_t hi = pl.nchunks; hi > 0 && e == hipSuccess; hi -= pl.chunks_per_launch) {
+        p.chunk_hi = (int)hi;
+        p.chunk_lo = (int)std::max<int64_t>(0, hi - pl.chunks_per_launch);
+        const int64_t runs = (int64_t)(p.chunk_hi - p.chunk_lo) * pl.ny * pl.n_splits;   // (chunk of block ids, head group, split) triples, dealt to the 8 XCDs in turn
+        const dim3 grid((unsigned)((runs + 7) / 8 * 8 * pl.chunk));
+        if (pl.pingpong) {
+            constexpr int RING = 4;
+            if (a.causal) e = launch_with_lds(attention_pingpong_kernel<true, RING, F16>, done[0], grid, dim3(512), 2 * RING * ATT_TILE_BYTES, p, s);
+            else e = launch_with_lds(attention_pingpong_kernel<false, RING, F16>, done[1], grid, dim3(512), 2 * RING * ATT_TILE_BYTES, p, s);
+        } else if (a.causal) {
+            e = launch_with_lds(attention_kernel<true, F16>, done[2], grid, dim3(256), 4 * ATT_TILE_BYTES, p, s);
+        } else {
+            e = launch_with_lds(attention_kernel<false, F16>, done[3], grid, dim3(256), 4 * ATT_TILE_BYTES, p, s);
+        }
     }
-    if (a.causal) e = launch_with_lds(attention_kernel<true, F16>, done[2], grid, dim3(256), 4 * ATT_TILE_BYTES, p, s);
-    else e = launch_with_lds(attention_kernel<false, F16>, done[3], grid, dim3(256), 4 * ATT_TILE_BYTES, p, s);
-    if (e != hipSuccess || pl.n_splits == 1) return e;
+    if (e != hipSuccess || pl.pingpong || pl.n_splits == 1) return e;
     hipLaunchKernelGGL(attention_merge_kernel<F16>, dim3((unsigned)pl.items, ATT_D / 32), dim3(256), 0, s, p);
     return hipGetLastError();
 }

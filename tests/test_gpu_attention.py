@@ -371,3 +371,32 @@ def test_understated_max_seqlen_k_leaves_keys_out_and_stays_in_bounds():
     # the binding's optional check turns the silent truncation into an error
     with pytest.raises(ValueError):
         tb.tbik_attention(Q, K, V, i32(c["cu_q"]), i32(c["cu_k"]), 1, c["scale"], False, max_seqlen_k=4096, verify_lengths=True)
+
+
+def test_workspace_is_bounded_and_a_long_call_in_pieces_gives_the_same_bits():
+    """The scratch for folding splits is capped (4608 states of 68 KiB): a call with more work items than that is launched
+    in pieces that take turns at the same area.  24 sequences of 4100..8192 tokens over 4 query heads on 2 key/value heads
+    (64 queries per head and workgroup) are about 5250 items of two splits each; every sequence must come out as when it
+    is run alone, which is one launch."""
+    cap = 4608 * 68 * 1024
+    for args in [(8, 16384, 16384, 32, 8), (64, 8192, 131072, 64, 8), (1024, 1, 131072, 32, 8), (3, 100000, 100000, 8, 8)]:
+        assert tb.attention_workspace_bytes(*args) <= cap, args
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(77)
+    lens = [8192, 4100, 7000, 8000, 4500, 6000, 8192, 5000, 7777, 4200, 8192, 6400, 7300, 8100, 4800, 6900, 8192, 5600, 7100, 8192,
+            8192, 8192, 8192, 8192]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T, Hq, Hkv, D = int(cu[-1]), 4, 2, 128
+    assert (T // 64 + len(lens)) * 2 > 4608
+    Q = torch.randn((T, Hq, D), generator=g, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+    K = torch.randn((T, Hkv, D), generator=g, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+    V = torch.randn((T, Hkv, D), generator=g, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+    need = tb.attention_workspace_bytes(len(lens), max(lens), max(lens), Hq, Hkv)
+    assert 0 < need <= cap
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+    O = tb.tbik_attention(Q, K, V, i32(cu), i32(cu), max(lens), D ** -0.5, True, max_seqlen_k=max(lens), workspace=ws)
+    for b in (0, 1, 9, 23):
+        a, e = int(cu[b]), int(cu[b + 1])
+        one = tb.tbik_attention(Q[a:e].contiguous(), K[a:e].contiguous(), V[a:e].contiguous(), i32([0, e - a]), i32([0, e - a]),
+                                e - a, D ** -0.5, True, max_seqlen_k=e - a)
+        assert torch.equal(one.view(torch.int16), O[a:e].view(torch.int16)), b
