@@ -403,6 +403,11 @@ def metric_shapes(tb, syn, torch, np, to_dev, X, W):
         ys = [torch.empty((Mc, Nc), dtype=torch.bfloat16, device=dev) for _ in range(n)]
         hbm_line("tree_combine_P%d_4096x4096" % P, [(lambda i=i: tb.tbik_tree_combine(ps[i], out=ys[i])) for i in range(n)],
                  (4.0 * P + 2) * Mc * Nc, 10)
+        if P == 8:
+            # Alg. 2 round by round on the same buffers (2 log2 P launches; the bytes every round moves, counted:
+            # the reduce rounds read 2 and write 1 buffer per pair, the broadcast rounds read 1 and write 1)
+            moved = 4.0 * Mc * Nc * sum(3 * (P >> (l + 1)) + 2 * (P >> (l + 1)) for l in range(3))
+            hbm_line("tree_allreduce_rounds_P8_4096x4096", [(lambda i=i: tb.tbik_tree_allreduce(ps[i])) for i in range(n)], moved, 5)
         del ps, ys
     return res
 

@@ -112,6 +112,20 @@ int tbik_tree_combine(const float *partials, int P, void *Y, int64_t ldy, tbik_d
                       int M, int N, void *hip_stream);
 
 /*
+ * The tree all-reduce of App. D.2 (Alg. 2) taken literally on one GPU: the P buffers stand for the ranks' tensors, a
+ * send/receive pair is a read of the partner's buffer.  Reduce phase: in round l = 0 .. log2(P) - 1 every rank r with
+ * r mod 2^(l+1) == 0 adds the buffer of rank r + 2^l to its own (own + received) and that partner drops out; broadcast
+ * phase: the same pairs in reverse order, the receiver copying.  Afterwards every buffer holds T(buffers), the value
+ * tbik_tree_combine gives before its rounding -- in 2 log2(P) rounds (one launch each) instead of one pass, which is
+ * what the wire protocol would do and what it costs to do it that way in memory.
+ *
+ *   bufs   device, fp32, dense [P, n], 16-byte aligned, updated in place; rows of n elements must keep that alignment
+ *          for the vector path (n % 4 == 0), any n works
+ * Errors: NULL, SHAPE, SHARDS, ALIGN, HIP.
+ */
+int tbik_tree_allreduce(float *bufs, int P, int64_t n, void *hip_stream);
+
+/*
  * The gated activation between the two GEMMs of the MLP block (implementation appendix, "other kernels":
  * SiLU is one of the position-wise kernels that every configuration shares):
  *   act[m][i] = round16( SiLU(gate[m][i]) * up[m][i] ),   SiLU(g) = g / (1 + e^-g)

@@ -34,6 +34,7 @@ SIGNATURES = {
     "tbik_row_reduce": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int64,
                                   C.c_void_p, C.c_size_t, C.c_void_p]),
     "tbik_row_reduce_static": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_void_p]),
+    "tbik_tree_allreduce": (C.c_int, [C.c_void_p, C.c_int, C.c_int64, C.c_void_p]),
     "tbik_silu_mul": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int,
                                 C.c_void_p]),
     "tbik_gemm_swiglu": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int,
@@ -325,6 +326,15 @@ def tbik_gemm_reference_fp8(X: torch.Tensor, Wt: torch.Tensor, leaf: int, k_firs
                                        M, N, K, leaf, k_first, P, _stream())
     _check(st, "tbik_gemm_reference_fp8")
     return (Y, parts) if P == 1 else parts
+
+
+def tbik_tree_allreduce(bufs: torch.Tensor) -> torch.Tensor:
+    """Alg. 2 round by round, in place, on rank buffers [P, ...] (fp32, contiguous): every buffer ends up holding T."""
+    assert bufs.is_cuda and bufs.is_contiguous() and bufs.dtype == torch.float32 and bufs.dim() >= 1
+    P = bufs.shape[0]
+    n = bufs.numel() // max(P, 1)
+    _check(lib().tbik_tree_allreduce(bufs.data_ptr(), P, n, _stream()), "tbik_tree_allreduce")
+    return bufs
 
 
 def tbik_silu_mul(gate: torch.Tensor, up: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:

@@ -94,6 +94,50 @@ static hipError_t launch_p(const float *partials, void *Y, int64_t ldy, int y_dt
     }
 }
 
+// Alg. 2 taken literally, round by round, on P buffers that stand for the ranks (App. D.2): in round l of the reduce
+// phase every rank r with r mod 2^(l+1) == 0 "receives" the buffer of rank r + 2^l and adds it to its own (own + received,
+// as the listing has it); the broadcast phase runs the same pairs backwards, the receiver copying.  One launch per
+// round handles all pairs of that round.
+template <bool ADD>
+__global__ __launch_bounds__(256) void allreduce_round_kernel(float *__restrict__ bufs, int64_t n, int stride_ranks, int pairs) {
+    // 16-byte accesses only when every rank's buffer starts on a 16-byte boundary (n a multiple of 4)
+    const int64_t quads = (n & 3) ? 0 : (n >> 2), total = quads * pairs, step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < total; q += step) {
+        const int64_t pair = q / quads, i = (q - pair * quads) << 2;
+        float *low = bufs + (pair * 2 * stride_ranks) * n + i;              // rank r
+        float *high = low + (int64_t)stride_ranks * n;                      // rank r + 2^l
+        if (ADD) {
+            const f32x4 a = *reinterpret_cast<const f32x4 *>(low), b = *reinterpret_cast<const f32x4 *>(high);
+            *reinterpret_cast<f32x4 *>(low) = f32x4{a[0] + b[0], a[1] + b[1], a[2] + b[2], a[3] + b[3]};
+        } else {
+            *reinterpret_cast<f32x4 *>(high) = *reinterpret_cast<const f32x4 *>(low);
+        }
+    }
+    // element by element otherwise
+    const int64_t tail = n - 4 * quads;
+    for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < tail * pairs; q += step) {
+        const int64_t pair = q / tail, i = (n - tail) + (q - pair * tail);
+        float *low = bufs + (pair * 2 * stride_ranks) * n + i;
+        float *high = low + (int64_t)stride_ranks * n;
+        if (ADD) *low = *low + *high;
+        else *high = *low;
+    }
+}
+
+hipError_t launch_tree_allreduce(float *bufs, int P, int64_t n, hipStream_t s) {
+    if (n <= 0 || P <= 1) return hipSuccess;
+    auto grid_of = [&](int pairs) {
+        int64_t blocks = (((n & 3) ? n : n / 4) * pairs + 255) / 256;
+        if (blocks > 256 * 64) blocks = 256 * 64;
+        return dim3((unsigned)(blocks < 1 ? 1 : blocks));
+    };
+    for (int st = 1; st < P; st *= 2)                                       // reduce phase, level by level
+        hipLaunchKernelGGL(allreduce_round_kernel<true>, grid_of(P / (2 * st)), dim3(256), 0, s, bufs, n, st, P / (2 * st));
+    for (int st = P / 2; st >= 1; st /= 2)                                  // broadcast phase
+        hipLaunchKernelGGL(allreduce_round_kernel<false>, grid_of(P / (2 * st)), dim3(256), 0, s, bufs, n, st, P / (2 * st));
+    return hipGetLastError();
+}
+
 hipError_t launch_tree_combine(const float *partials, int P, void *Y, int64_t ldy, int y_dtype, int M, int N,
                                hipStream_t s) {
     if (M <= 0 || N <= 0) return hipSuccess;

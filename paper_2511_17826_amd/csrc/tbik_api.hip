@@ -456,6 +456,16 @@ int tbik_gemm_swiglu(const void *X, int64_t ldx, const void *W_gu, int64_t ldw, 
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }
 
+int tbik_tree_allreduce(float *bufs, int P, int64_t n, void *hip_stream) {
+    if (n < 0) return TBIK_ERR_SHAPE;
+    if (P < 1 || !is_pow2(P) || P > TBIK_MAX_SHARDS) return TBIK_ERR_SHARDS;
+    if (n == 0) return TBIK_OK;
+    if (!bufs) return TBIK_ERR_NULL;
+    if (!aligned(bufs, 16)) return TBIK_ERR_ALIGN;
+    hipError_t e = launch_tree_allreduce(bufs, P, n, (hipStream_t)hip_stream);
+    return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
 static int rmsnorm(int dtype, const void *x, const void *weight, void *y, int M, int H, float eps, void *hip_stream) {
     if (M < 0 || H <= 0 || H % 8 != 0 || H > 65536) return TBIK_ERR_SHAPE;
     if (M == 0) return TBIK_OK;

@@ -59,6 +59,9 @@ bool gemm_fp8_tiled_supports(const GemmArgs &a);
 hipError_t launch_tree_combine(const float *partials, int P, void *Y, int64_t ldy, int y_dtype, int M, int N,
                                hipStream_t s);
 
+// Alg. 2 round by round on P rank buffers [P, n], in place: afterwards every buffer holds T(buffers).
+hipError_t launch_tree_allreduce(float *bufs, int P, int64_t n, hipStream_t s);
+
 // dtype: TBIK_BF16 or TBIK_F16, the format of every 16-bit tensor of the call.
 hipError_t launch_rmsnorm(const uint16_t *x, const uint16_t *w, uint16_t *y, int M, int H, float eps, int dtype, hipStream_t s);
 hipError_t launch_combine_residual_rmsnorm(const float *partials, int P, const uint16_t *res, const uint16_t *w,

@@ -263,3 +263,20 @@ def test_fused_tail_hand_value():
     hid, out = tb.tbik_combine_residual_rmsnorm(torch.from_numpy(parts).to("cuda:0"), gu.dev_bf16(res), gu.dev_bf16(w), 0.0)
     assert np.all(gu.host_bf16_bits(hid) == 0x3F82)
     assert np.all(gu.host_bf16_bits(out) == 0x3F80)
+
+
+@pytest.mark.parametrize("P", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("n", [4096 * 33, 1001, 3])
+def test_tree_allreduce_round_by_round_is_alg2(P, n):
+    """App. D.2 taken literally: after the reduce and broadcast rounds every rank's buffer holds the oracle's all-reduced
+    tensor bit for bit -- which is what tbik_tree_combine computes in one pass."""
+    rng = np.random.default_rng(P * 1000 + n)
+    bufs = (rng.standard_normal((P, n)) * np.exp2(rng.integers(-12, 13, size=(P, n)))).astype(np.float32)
+    want = orc.allreduce(bufs)
+    d = gu.dev_f32(bufs)
+    combined = tb.tbik_tree_combine(d.view(P, 1, n).clone(), out_dtype=torch.float32) if P > 1 else d.clone().view(1, n)
+    got = gu.host_f32(tb.tbik_tree_allreduce(d))
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    for r in range(P):
+        assert np.array_equal(got[r].view(np.uint32), want[0].view(np.uint32)), r
+    assert np.array_equal(gu.host_f32(combined).reshape(-1).view(np.uint32), want[0].view(np.uint32))
