@@ -36,6 +36,8 @@
  *   format only changes the exact widening and the one output rounding.
  *   tbik_oracle_gemm_f32*    the same GEMM on fp32 operands (third row of that table): a
  *                            leaf accumulates by one fused multiply-add per k.
+ *   tbik_oracle_gemm_mxfp4   the same GEMM on OCP MXFP4 operands: 4-bit E2M1 elements with one E8M0 (power-of-two)
+ *                            scale per block of 32 consecutive k; products stay exact in fp32.
  *   tbik_oracle_gemm_fp8*    the same GEMM on 8-bit floating-point operands (the paper's outlook: quantised
  *                            types): OCP E4M3 or E5M2 patterns widened exactly; a product of two of them has
  *                            at most 8 significant bits, so it is exact in fp32 and the 16-bit contract
@@ -632,6 +634,73 @@ int tbik_oracle_gemm_fp8_elements(const uint8_t *X, long ldx, const uint8_t *W, 
             out[i] = combine_superleaves(s, ns, evaluator, P, NULL);
         }
         free(s);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ 4-bit floating point with block scales (OCP MXFP4) */
+
+/*
+ * E2M1: sign | 2 exponent bits (bias 1) | 1 fraction bit.  Exponent 0 is the subnormal 0 or 0.5; the others are
+ * (1 + f/2) * 2^(e-1): 1, 1.5, 2, 3, 4, 6.  No infinities, no NaN.  Only the low four bits of `nibble` count.
+ */
+float tbik_oracle_fp4_to_f32(uint8_t nibble) {
+    const int sign = (nibble >> 3) & 1, e = (nibble >> 1) & 3, f = nibble & 1;
+    const float v = (e == 0) ? 0.5f * (float)f : ldexpf(1.0f + 0.5f * (float)f, e - 1);
+    return sign ? -v : v;
+}
+
+/* E8M0, the shared scale of a block: 2^(s - 127); s = 255 is NaN. */
+float tbik_oracle_e8m0_to_f32(uint8_t s) {
+    return s == 255 ? NAN : ldexpf(1.0f, (int)s - 127);
+}
+
+/*
+ * Y = X W on MXFP4 operands (the paper's outlook: quantised types; the order contract as for every other format):
+ * element k of a row is a 4-bit E2M1 number times the E8M0 scale of its block of 32 consecutive k,
+ *   x[m,k] = fp4(X[m, k/2] nibble k%2, low nibble first) * 2^(Xs[m, k/32] - 127)
+ * and likewise for the weight, which is stored TRANSPOSED (one row per output channel: the packing runs along k),
+ *   w[k,n] = fp4(Wt[n, k/2] nibble k%2) * 2^(Ws[n, k/32] - 127).
+ * A product has at most 4 significant bits and a power-of-two scale: exact in fp32 while it stays in range.
+ *   s_j = ((p_a + p_{a+1}) + ...) over superleaf j in ascending k from +0;  y = T(s_0 .. s_{n_s-1}).
+ * X [M, ldx] bytes (ldx >= K/2), Xs [M, lds_x] (>= K/32), Wt [N, ldw], Ws [N, lds_w].  K a multiple of 32.
+ */
+int tbik_oracle_gemm_mxfp4(const uint8_t *X, long ldx, const uint8_t *Xs, long ldxs,
+                           const uint8_t *Wt, long ldw, const uint8_t *Ws, long ldws,
+                           float *Y32, uint16_t *Ybf, long ldy, int M, int N, int K, int leaf, int k_first,
+                           int evaluator, int P, float *partials) {
+    long ns = superleaf_count(K, leaf, k_first, P);
+    if (ns < 0 || K % 32 != 0) return -1;
+    const long sl = (long)leaf * k_first;
+#pragma omp parallel
+    {
+        float *s = (float *)malloc((size_t)ns * sizeof(float));
+        float *xrow = (float *)malloc((size_t)K * sizeof(float));
+        float part[64];
+#pragma omp for schedule(dynamic, 1)
+        for (long m = 0; m < M; ++m) {
+            for (long k = 0; k < K; ++k)
+                xrow[k] = tbik_oracle_fp4_to_f32((uint8_t)(X[m * ldx + k / 2] >> (4 * (k & 1)))) * tbik_oracle_e8m0_to_f32(Xs[m * ldxs + k / 32]);
+            for (long n = 0; n < N; ++n) {
+                for (long j = 0; j < ns; ++j) {
+                    float acc = 0.0f;
+                    for (long k = j * sl; k < (j + 1) * sl; ++k) {
+                        const float w = tbik_oracle_fp4_to_f32((uint8_t)(Wt[n * ldw + k / 2] >> (4 * (k & 1)))) *
+                                        tbik_oracle_e8m0_to_f32(Ws[n * ldws + k / 32]);
+                        float pk = xrow[k] * w;
+                        acc = acc + pk;
+                    }
+                    s[j] = acc;
+                }
+                float y = combine_superleaves(s, ns, evaluator, P, part);
+                if (Y32) Y32[m * ldy + n] = y;
+                if (Ybf) Ybf[m * ldy + n] = f32_to_bf16(y);
+                if (partials && evaluator == EVAL_SHARDED)
+                    for (int p = 0; p < P; ++p) partials[((size_t)p * M + m) * N + n] = part[p];
+            }
+        }
+        free(s);
+        free(xrow);
     }
     return 0;
 }

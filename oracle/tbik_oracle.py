@@ -94,6 +94,13 @@ def lib():
         L.tbik_oracle_gemm_fp8_elements.restype = C.c_int
         L.tbik_oracle_gemm_fp8_elements.argtypes = [u8p, C.c_long, u8p, C.c_long, i64p, i64p, C.c_long,
                                                     C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f32p]
+        L.tbik_oracle_fp4_to_f32.restype = C.c_float
+        L.tbik_oracle_fp4_to_f32.argtypes = [C.c_uint8]
+        L.tbik_oracle_e8m0_to_f32.restype = C.c_float
+        L.tbik_oracle_e8m0_to_f32.argtypes = [C.c_uint8]
+        L.tbik_oracle_gemm_mxfp4.restype = C.c_int
+        L.tbik_oracle_gemm_mxfp4.argtypes = [u8p, C.c_long, u8p, C.c_long, u8p, C.c_long, u8p, C.c_long, f32p, u16p, C.c_long,
+                                             C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f32p]
         L.tbik_oracle_tree_combine.restype = C.c_int
         L.tbik_oracle_tree_combine.argtypes = [f32p, C.c_int, C.c_long, f32p, u16p, C.c_int]
         L.tbik_oracle_treesum.restype = C.c_float
@@ -351,6 +358,52 @@ def gemm_fp8_elements(X, W, rows, cols, leaf: int, k_first: int = 1, evaluator: 
     if rc != 0:
         raise ValueError("oracle gemm: illegal tree parameters (K, leaf, k_first, P)")
     return out
+
+
+def fp4_to_f32(nibbles) -> np.ndarray:
+    """4-bit E2M1 patterns (the low four bits of each entry) -> fp32 values."""
+    L = lib()
+    table = np.array([L.tbik_oracle_fp4_to_f32(b) for b in range(16)], dtype=np.float32)
+    return table[np.asarray(nibbles, dtype=np.uint8) & 15]
+
+
+def e8m0_to_f32(s) -> np.ndarray:
+    L = lib()
+    table = np.array([L.tbik_oracle_e8m0_to_f32(b) for b in range(256)], dtype=np.float32)
+    return table[np.asarray(s, dtype=np.uint8)]
+
+
+def mxfp4_dequant(packed, scales) -> np.ndarray:
+    """[R, K/2] packed E2M1 pairs (low nibble first) and [R, K/32] E8M0 scales -> fp32 [R, K] (exact)."""
+    packed = np.asarray(packed, dtype=np.uint8)
+    R, K2 = packed.shape
+    nib = np.empty((R, 2 * K2), dtype=np.uint8)
+    nib[:, 0::2] = packed & 15
+    nib[:, 1::2] = packed >> 4
+    return fp4_to_f32(nib) * np.repeat(e8m0_to_f32(scales), 32, axis=1)
+
+
+def gemm_mxfp4(X, Xs, Wt, Ws, leaf: int, k_first: int = 1, evaluator: int = EVAL_RECURSIVE, P: int = 1,
+               want_partials: bool = False):
+    """Y = X W in the tree order on MXFP4 operands: X [M, K/2] packed with scales Xs [M, K/32]; the weight transposed,
+    Wt [N, K/2] with Ws [N, K/32].  Returns (Y fp32 [M,N], Y bf16 patterns[, partials [P,M,N]])."""
+    X, xp = _u8(X)
+    Xs, xsp = _u8(Xs)
+    Wt, wp = _u8(Wt)
+    Ws, wsp = _u8(Ws)
+    M, K2 = X.shape
+    N = Wt.shape[0]
+    K = 2 * K2
+    assert Wt.shape[1] == K2 and Xs.shape == (M, K // 32) and Ws.shape == (N, K // 32)
+    Y32 = np.empty((M, N), dtype=np.float32)
+    Ybf = np.empty((M, N), dtype=np.uint16)
+    parts = np.zeros((P, M, N), dtype=np.float32) if want_partials else None
+    rc = lib().tbik_oracle_gemm_mxfp4(xp, K2, xsp, K // 32, wp, K2, wsp, K // 32, Y32.ctypes.data_as(C.POINTER(C.c_float)),
+                                      Ybf.ctypes.data_as(C.POINTER(C.c_uint16)), N, M, N, K, leaf, k_first, evaluator, P,
+                                      parts.ctypes.data_as(C.POINTER(C.c_float)) if want_partials else None)
+    if rc != 0:
+        raise ValueError("oracle gemm: illegal tree parameters (K, leaf, k_first, P)")
+    return (Y32, Ybf, parts) if want_partials else (Y32, Ybf)
 
 
 def tree_combine(partials: np.ndarray, fmt: str = "bf16"):

@@ -155,6 +155,43 @@ def gemm_random_fp8(seed: int, M: int, K: int, N: int, fmt: str = "e4m3"):
     return f32_to_fp8_bits(X, fmt), f32_to_fp8_bits(W, fmt)
 
 
+E2M1_VALUES = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], dtype=np.float32)   # the magnitudes an E2M1 element can hold
+
+
+def mxfp4_quantize(a: np.ndarray, scale_shift: int = 0):
+    """fp32 [R, K] (K a multiple of 32) -> (packed E2M1 pairs uint8 [R, K/2], low nibble = even k; E8M0 scales uint8
+    [R, K/32]).  Per block of 32 the scale is the power of two that brings the block's largest magnitude into (3, 6]
+    (an all-zero block gets 2^0), shifted by `scale_shift` binades; elements are rounded to the nearest E2M1 magnitude
+    (ties to the lower index).  An input recipe: nothing of the method's arithmetic."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    R, K = a.shape
+    assert K % 32 == 0
+    blocks = a.reshape(R, K // 32, 32)
+    amax = np.abs(blocks).max(axis=2)
+    e = np.where(amax > 0, np.ceil(np.log2(np.where(amax > 0, amax, 1.0) / 6.0)), 0.0).astype(np.int32) + scale_shift
+    scales = np.clip(e + 127, 1, 254).astype(np.uint8)
+    scaled = blocks / np.exp2(scales.astype(np.float32) - 127)[:, :, None]
+    idx = np.abs(np.abs(scaled)[..., None] - E2M1_VALUES).argmin(axis=-1).astype(np.uint8)
+    nib = (idx | (np.signbit(scaled).astype(np.uint8) << 3)).reshape(R, K)
+    packed = (nib[:, 0::2] | (nib[:, 1::2] << 4)).astype(np.uint8)
+    return packed, scales
+
+
+def gemm_random_mxfp4(seed: int, M: int, K: int, N: int, scale_spread: int = 0):
+    """MXFP4 operands from X ~ N(0,1), W ~ N(0,0.02) (the weight transposed, [N, K]): returns (X packed, X scales,
+    Wt packed, W scales).  With `scale_spread` every block's scale is moved by a random number of binades in
+    [-scale_spread, scale_spread] (the elements stay as quantised), which spreads the magnitudes of the products."""
+    rng = _rng(seed)
+    X = rng.standard_normal(size=(M, K), dtype=np.float32)
+    Wt = rng.standard_normal(size=(N, K), dtype=np.float32) * np.float32(0.02)
+    Xp, Xs = mxfp4_quantize(X)
+    Wp, Ws = mxfp4_quantize(Wt)
+    if scale_spread:
+        Xs = (Xs.astype(np.int32) + rng.integers(-scale_spread, scale_spread + 1, size=Xs.shape)).astype(np.uint8)
+        Ws = (Ws.astype(np.int32) + rng.integers(-scale_spread, scale_spread + 1, size=Ws.shape)).astype(np.uint8)
+    return Xp, Xs, Wp, Ws
+
+
 def gemm_random_f32(seed: int, M: int, K: int, N: int, x_std: float = 1.0, w_std: float = 0.02, exp_spread: int = 0):
     """fp32 operands X [M,K] ~ N(0, x_std), W [K,N] ~ N(0, w_std) with full 24-bit significands; with ``exp_spread`` every
     element is scaled by a random power of two in [-exp_spread, exp_spread] (cancellation and absorption cases)."""
