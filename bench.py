@@ -369,6 +369,21 @@ def metric_shapes(tb, syn, torch, np, to_dev, X, W):
                      "baseline_ms": round(tbase, 4) if tbase else None}
         del X8, Wt8, y8, ws8
 
+    # MXFP4 operands (random element and scale bytes: the timing does not depend on the values), same two shapes.
+    for name, K4, leaf4, g4 in (("mxfp4_oproj_M4096", 4096, 512, 1), ("mxfp4_downproj_M4096", 12288, 256, 3)):
+        g4r = torch.Generator(device=dev)
+        g4r.manual_seed(K4 + 1)
+        X4 = torch.randint(0, 256, (4096, K4 // 2), generator=g4r, device=dev, dtype=torch.uint8)
+        W4 = torch.randint(0, 256, (4096, K4 // 2), generator=g4r, device=dev, dtype=torch.uint8)
+        Xs4 = torch.randint(120, 134, (4096, K4 // 32), generator=g4r, device=dev, dtype=torch.uint8)
+        Ws4 = torch.randint(120, 134, (4096, K4 // 32), generator=g4r, device=dev, dtype=torch.uint8)
+        y4 = torch.empty((4096, 4096), dtype=torch.bfloat16, device=dev)
+        ws4 = torch.empty(max(256, tb.gemm_mxfp4_workspace_bytes(4096, 4096, K4, leaf4, g4)), dtype=torch.uint8, device=dev)
+        t = best_ms(lambda: tb.tbik_gemm_mxfp4(X4, Xs4, W4, Ws4, leaf4, g4, out=y4, workspace=ws4), 10, torch)
+        tf = 2.0 * 4096 * K4 * 4096 / (t * 1e-3) / 1e12
+        res[name] = {"ms": round(t, 4), "tflops": round(tf, 1), "frac_fp4_peak": round(tf / 10100.0, 4), "leaf": leaf4}
+        del X4, W4, Xs4, Ws4, y4, ws4
+
     def hbm_line(name, calls, byts, iters):
         cold = best_ms(rotating(calls), iters * len(calls), torch, warm=len(calls))
         warm = best_ms(calls[0], iters, torch)

@@ -59,7 +59,8 @@ typedef enum {
 typedef enum {
     TBIK_F32 = 0, TBIK_BF16 = 1, TBIK_F16 = 2,
     TBIK_FP8_E4M3 = 3,        /* OCP 8-bit float, 4 exponent / 3 fraction bits, bias 7, no infinities, max 448 */
-    TBIK_FP8_E5M2 = 4         /* OCP 8-bit float, 5 exponent / 2 fraction bits, bias 15, IEEE-style inf / NaN  */
+    TBIK_FP8_E5M2 = 4,        /* OCP 8-bit float, 5 exponent / 2 fraction bits, bias 15, IEEE-style inf / NaN  */
+    TBIK_MXFP4 = 5            /* OCP MXFP4: 4-bit E2M1 elements, one E8M0 scale per block of 32 consecutive k     */
 } tbik_dtype;
 typedef enum { TBIK_SUM = 0, TBIK_MAX = 1, TBIK_LOGSOFTMAX = 2 } tbik_rowop;
 
@@ -371,6 +372,39 @@ int tbik_gemm_shard_partials_fp8(const void *X, int64_t ldx, const void *Wt, int
 int tbik_gemm_reference_fp8(const void *X, int64_t ldx, const void *Wt, int64_t ldwt, float *partials,
                             void *Y, int64_t ldy, tbik_dtype y_dtype, tbik_dtype x_dtype,
                             int M, int N, int K, int leaf, int k_first, int P, void *hip_stream);
+
+/*
+ * The same three calls for OCP MXFP4 operands (microscaling: the low-bit format this GPU generation multiplies at four
+ * times the bf16 rate).  An element is a 4-bit E2M1 number (0, 0.5, 1, 1.5, 2, 3, 4, 6 and their negatives) times
+ * 2^(s - 127), s the E8M0 scale byte of its block of 32 consecutive k (s = 255, NaN, is out of contract).  Two elements
+ * share a byte, the one with the even k in the low four bits.  A product of two elements has at most four significant
+ * bits and a power-of-two scale, so it is exact in fp32 (as long as it stays in range) and the order contract of
+ * tbik_gemm holds word for word: per output element each superleaf's products are accumulated in fp32 in ascending k
+ * from +0, the superleaf sums are combined by T, the result is rounded once.  (The 64 products of one matrix instruction
+ * are added in that instruction's own fixed order, as for the other formats.)
+ *
+ * The packing runs along k, so the weight is taken TRANSPOSED: one row per output channel.
+ *
+ *   X    device, [M, ldx] bytes, ldx >= K / 2        Xs   device, [M, ldxs] scale bytes, ldxs >= K / 32
+ *   Wt   device, [N, ldwt] bytes, ldwt >= K / 2      Ws   device, [N, ldws] scale bytes, ldws >= K / 32
+ *   Y    device, y_dtype (TBIK_F32 or TBIK_BF16), [M, ldy], ldy >= N        partials  device, fp32, dense [P, M, N]
+ *   leaf * k_first a multiple of 64 (256 for the tiled kernel; else the reference kernel runs); K a multiple of 64;
+ *   X, Wt 16-byte aligned with ldx, ldwt multiples of 16; Xs, Ws 8-byte aligned with ldxs, ldws multiples of 8 (the
+ *   tiled kernel; the reference kernel takes any); the workspace rule (tbik_gemm_mxfp4_workspace_bytes), the determinism
+ *   contract and the errors are those of tbik_gemm, tbik_gemm_shard_partials and tbik_gemm_reference.
+ */
+size_t tbik_gemm_mxfp4_workspace_bytes(int M, int N, int K, int leaf, int k_first);
+int tbik_gemm_mxfp4(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                    const void *Ws, int64_t ldws, void *Y, int64_t ldy, tbik_dtype y_dtype,
+                    int M, int N, int K, int leaf, int k_first,
+                    void *workspace, size_t workspace_bytes, void *hip_stream);
+int tbik_gemm_shard_partials_mxfp4(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                                   const void *Ws, int64_t ldws, float *partials,
+                                   int M, int N, int K, int leaf, int k_first, int P,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+int tbik_gemm_reference_mxfp4(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                              const void *Ws, int64_t ldws, float *partials, void *Y, int64_t ldy, tbik_dtype y_dtype,
+                              int M, int N, int K, int leaf, int k_first, int P, void *hip_stream);
 
 /*
  * tbik_rmsnorm and tbik_combine_residual_rmsnorm for tensors of IEEE binary16 (App. B and Alg. 2 do not depend on

@@ -376,6 +376,96 @@ int tbik_gemm_reference_fp8(const void *X, int64_t ldx, const void *Wt, int64_t 
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }
 
+// ---- MXFP4 operands ----
+static int mxfp4_checks(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                        const void *Ws, int64_t ldws, int M, int N, int K, int leaf, int k_first, int P, int *sl, int *ns) {
+    int rc = check_tree(M, N, K, leaf, k_first, P, sl, ns);
+    if (rc != TBIK_OK) return rc;
+    if (*sl % 64 != 0) return TBIK_ERR_SHAPE;
+    if (M == 0 || N == 0) return TBIK_OK;
+    if (!X || !Wt || !Xs || !Ws) return TBIK_ERR_NULL;
+    if (ldx < K / 2 || ldwt < K / 2 || ldxs < K / 32 || ldws < K / 32) return TBIK_ERR_SHAPE;
+    if (!aligned(X, 16) || !aligned(Wt, 16) || ldx % 16 != 0 || ldwt % 16 != 0) return TBIK_ERR_ALIGN;
+    return TBIK_OK;
+}
+
+size_t tbik_gemm_mxfp4_workspace_bytes(int M, int N, int K, int leaf, int k_first) {
+    return tbik_gemm_fp8_workspace_bytes(M, N, K, leaf, k_first);      // one tile shape, the same K split
+}
+
+int tbik_gemm_mxfp4(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                    const void *Ws, int64_t ldws, void *Y, int64_t ldy, tbik_dtype y_dtype,
+                    int M, int N, int K, int leaf, int k_first,
+                    void *workspace, size_t workspace_bytes, void *hip_stream) {
+    int sl, ns;
+    int rc = mxfp4_checks(X, ldx, Xs, ldxs, Wt, ldwt, Ws, ldws, M, N, K, leaf, k_first, 1, &sl, &ns);
+    if (rc != TBIK_OK) return rc;
+    if (y_dtype != TBIK_F32 && y_dtype != TBIK_BF16) return TBIK_ERR_DTYPE;
+    if (M == 0 || N == 0) return TBIK_OK;
+    if (!Y) return TBIK_ERR_NULL;
+    if (ldy < N) return TBIK_ERR_SHAPE;
+    if (!aligned(Y, y_dtype == TBIK_F32 ? 4 : 2)) return TBIK_ERR_ALIGN;
+    const size_t need = tbik_gemm_mxfp4_workspace_bytes(M, N, K, leaf, k_first);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return TBIK_ERR_WORKSPACE;
+    if (workspace && !aligned(workspace, 256)) return TBIK_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)hip_stream;
+    GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)Wt, ldwt, nullptr, Y, ldy, (int)y_dtype, M, N, K, sl, ns, 1, TBIK_MXFP4, 0};
+    const Mxfp4Scales sc{(const uint8_t *)Xs, ldxs, (const uint8_t *)Ws, ldws};
+    const int split = fp8_split(M, N, ns);
+    GemmArgs probe = a;
+    probe.P = split;
+    const bool tiled = g_forced_variant.load() != VARIANT_REFERENCE && gemm_mxfp4_tiled_supports(probe, sc);
+    hipError_t e;
+    if (!tiled) {
+        e = launch_gemm_mxfp4_reference(a, sc, s);
+    } else if (split == 1) {
+        e = launch_gemm_mxfp4_tiled(a, sc, s);
+    } else {
+        a.partials = reinterpret_cast<float *>(workspace);
+        a.Y = nullptr;
+        a.P = split;
+        e = launch_gemm_mxfp4_tiled(a, sc, s);
+        if (e == hipSuccess) e = launch_tree_combine(a.partials, split, Y, ldy, (int)y_dtype, M, N, s);
+    }
+    return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
+int tbik_gemm_shard_partials_mxfp4(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                                   const void *Ws, int64_t ldws, float *partials,
+                                   int M, int N, int K, int leaf, int k_first, int P,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream) {
+    (void)workspace; (void)workspace_bytes;
+    int sl, ns;
+    int rc = mxfp4_checks(X, ldx, Xs, ldxs, Wt, ldwt, Ws, ldws, M, N, K, leaf, k_first, P, &sl, &ns);
+    if (rc != TBIK_OK) return rc;
+    if (M == 0 || N == 0) return TBIK_OK;
+    if (!partials) return TBIK_ERR_NULL;
+    if (!aligned(partials, 16)) return TBIK_ERR_ALIGN;
+    GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)Wt, ldwt, partials, nullptr, 0, TBIK_F32, M, N, K, sl, ns, P, TBIK_MXFP4, 0};
+    const Mxfp4Scales sc{(const uint8_t *)Xs, ldxs, (const uint8_t *)Ws, ldws};
+    const bool tiled = g_forced_variant.load() != VARIANT_REFERENCE && gemm_mxfp4_tiled_supports(a, sc);
+    hipError_t e = tiled ? launch_gemm_mxfp4_tiled(a, sc, (hipStream_t)hip_stream) : launch_gemm_mxfp4_reference(a, sc, (hipStream_t)hip_stream);
+    return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
+int tbik_gemm_reference_mxfp4(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                              const void *Ws, int64_t ldws, float *partials, void *Y, int64_t ldy, tbik_dtype y_dtype,
+                              int M, int N, int K, int leaf, int k_first, int P, void *hip_stream) {
+    int sl, ns;
+    int rc = mxfp4_checks(X, ldx, Xs, ldxs, Wt, ldwt, Ws, ldws, M, N, K, leaf, k_first, P, &sl, &ns);
+    if (rc != TBIK_OK) return rc;
+    if (y_dtype != TBIK_F32 && y_dtype != TBIK_BF16) return TBIK_ERR_DTYPE;
+    if (M == 0 || N == 0) return TBIK_OK;
+    if (!partials && !Y) return TBIK_ERR_NULL;
+    if (Y && P != 1) return TBIK_ERR_SHARDS;
+    if (Y && ldy < N) return TBIK_ERR_SHAPE;
+    if (Y && !aligned(Y, y_dtype == TBIK_F32 ? 4 : 2)) return TBIK_ERR_ALIGN;
+    GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)Wt, ldwt, partials, Y, ldy, (int)y_dtype, M, N, K, sl, ns, P, TBIK_MXFP4, 0};
+    const Mxfp4Scales sc{(const uint8_t *)Xs, ldxs, (const uint8_t *)Ws, ldws};
+    hipError_t e = launch_gemm_mxfp4_reference(a, sc, (hipStream_t)hip_stream);
+    return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
 // How tbik_gemm_swiglu runs a shape (pure): the K split of the [M, 2 I] GEMM, and whether the unsplit case can end in
 // the 128 x 128 tile's activation epilogue or has to pass gate and up through a 16-bit staging buffer.
 enum { SWIGLU_FUSED = 0, SWIGLU_SPLIT = 1, SWIGLU_STAGED = 2 };

@@ -100,6 +100,18 @@ __device__ __forceinline__ void load_16B_per_lane_to_lds(const void *uniform_bas
                      ::"v"(lane_offset), "s"(uniform_base), "n"(OFFSET), "{m0}"(m0_value) : "memory");
 }
 
+// The 4-byte form (global_load_lds_dword): lane i's 4 bytes land at LDS address m0 + OFFSET + 4*i.
+template <int OFFSET, bool AFTER_M0_WRITE>
+__device__ __forceinline__ void load_4B_per_lane_to_lds(const void *uniform_base, unsigned lane_offset, unsigned m0_value) {
+    static_assert(OFFSET >= -4096 && OFFSET < 4096, "13-bit signed instruction offset");
+    if (AFTER_M0_WRITE)
+        asm volatile("s_nop 0\n\tglobal_load_lds_dword %0, %1 offset:%2"
+                     ::"v"(lane_offset), "s"(uniform_base), "n"(OFFSET), "{m0}"(m0_value) : "memory");
+    else
+        asm volatile("global_load_lds_dword %0, %1 offset:%2"
+                     ::"v"(lane_offset), "s"(uniform_base), "n"(OFFSET), "{m0}"(m0_value) : "memory");
+}
+
 // Tells the compiler that a pointer is the same in every lane (it then lives in scalar registers).
 __device__ __forceinline__ const char *uniform_pointer(const char *p) {
     const uint64_t v = reinterpret_cast<uint64_t>(p);

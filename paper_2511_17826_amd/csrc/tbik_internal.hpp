@@ -55,6 +55,18 @@ hipError_t launch_gemm_fp8_reference(const GemmArgs &a, hipStream_t s);
 hipError_t launch_gemm_fp8_tiled(const GemmArgs &a, hipStream_t s);
 bool gemm_fp8_tiled_supports(const GemmArgs &a);
 
+// The same for MXFP4 operands (x_dtype TBIK_MXFP4): X points to [M, ldx] BYTES of packed element pairs (ldx >= K / 2),
+// W to the transposed weight [N, ldw] bytes; the block scales travel beside.  Y is fp32 or bf16.
+struct Mxfp4Scales {
+    const uint8_t *Xs;   // [M, ldxs], ldxs >= K / 32
+    int64_t ldxs;
+    const uint8_t *Ws;   // [N, ldws]
+    int64_t ldws;
+};
+hipError_t launch_gemm_mxfp4_reference(const GemmArgs &a, const Mxfp4Scales &sc, hipStream_t s);
+hipError_t launch_gemm_mxfp4_tiled(const GemmArgs &a, const Mxfp4Scales &sc, hipStream_t s);
+bool gemm_mxfp4_tiled_supports(const GemmArgs &a, const Mxfp4Scales &sc);
+
 // Y = T(partials[0..P)) elementwise + one rounding.
 hipError_t launch_tree_combine(const float *partials, int P, void *Y, int64_t ldy, int y_dtype, int M, int N,
                                hipStream_t s);
