@@ -367,7 +367,28 @@ def metric_shapes(tb, syn, torch, np, to_dev, X, W):
         tf = 2.0 * 4096 * K8 * 4096 / (t * 1e-3) / 1e12
         res[name] = {"ms": round(t, 4), "tflops": round(tf, 1), "frac_fp8_peak": round(tf / PEAK_FP8_TFLOPS, 4),
                      "baseline_ms": round(tbase, 4) if tbase else None}
-        del X8, Wt8, y8, ws8
+        # small batches: the 8-bit weight is the traffic; copies of it (more than the cache in all) walked inside one HIP graph
+        copies = max(2, -(-int(1.5 * CACHE_BYTES) // (4096 * K8)))
+        Wts = [Wt8] + [Wt8.clone() for _ in range(copies - 1)]
+        side = torch.cuda.Stream()
+        for Ms in (1, 64):
+            ys = torch.empty((Ms, 4096), dtype=torch.bfloat16, device=dev)
+            wss = torch.empty(max(256, tb.gemm_fp8_workspace_bytes(Ms, 4096, K8, leaf8, g8)), dtype=torch.uint8, device=dev)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                tb.tbik_gemm_fp8(X8[:Ms], Wts[0], leaf8, g8, "e4m3", out=ys, workspace=wss)
+                torch.cuda.synchronize()
+                with torch.cuda.graph(graph, stream=side):
+                    for Wc in Wts:
+                        tb.tbik_gemm_fp8(X8[:Ms], Wc, leaf8, g8, "e4m3", out=ys, workspace=wss)
+            graph.replay()
+            torch.cuda.synchronize()
+            tc = min(time_region(graph.replay, 5, torch) for _ in range(3)) / len(Wts)
+            gbs = 1.0 * K8 * 4096 / (tc * 1e-3) / 1e9
+            res[name.replace("M4096", "M%d_weights_from_hbm" % Ms)] = {"ms_cold_in_graph": round(tc, 4), "GBps_weights": round(gbs, 1),
+                                                                     "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
+            del ys, wss, graph
+        del X8, Wt8, y8, ws8, Wts
 
     # MXFP4 operands (random element and scale bytes: the timing does not depend on the values), same two shapes.
     for name, K4, leaf4, g4 in (("mxfp4_oproj_M4096", 4096, 512, 1), ("mxfp4_downproj_M4096", 12288, 256, 3)):

@@ -99,13 +99,12 @@ __global__ __launch_bounds__(64) void gemm_fp8_reference_kernel(
 // regions of 8 KiB, one per loading wavefront: [32 rows of the X tile | 32 rows of the Wt tile].  Rows are 128 bytes;
 // the 16-byte chunk c of row r sits at position c ^ ((r >> 1) & 7), so the 16 rows that a ds_read_b128 pass touches
 // cover all banks.  A lane's operand for one MFMA is 32 consecutive bytes of its row: chunks 4*ks + 2*lg and the next.
+// Three tile shapes, as for 16-bit operands: 128 x 128 (wave tile 64 x 64), 64 x 128 and 32 x 128 (four wavefronts side by
+// side) for small batches, where the weight is the traffic and a deeper ring keeps more of it in flight.
 constexpr int BK8 = 128;               // k (= bytes) per LDS stage row
 constexpr int ROW8 = 128;              // bytes per LDS row
 constexpr int KSTEPS8 = BK8 / 64;      // MFMA K-steps per stage
-constexpr int RING8 = 5;
-constexpr int LOADS8 = 4;              // 1 KiB loads per wavefront, stage and operand
-constexpr int REGION8 = 2 * LOADS8 * 1024;
-constexpr int STAGE8 = 4 * REGION8;
+constexpr int B_LOADS8 = 4;            // 1 KiB loads of Wt rows per wavefront and stage (128 rows / 8 rows / 4 wavefronts)
 
 template <int N>
 __device__ __forceinline__ void wait_loads_and_barrier() {
@@ -129,10 +128,14 @@ struct Fp8Params {
     int stream_stores;
 };
 
-template <int LEVELS, int FMT>
+template <int LEVELS, int WM, int WN, int MT, int NT, int RING8, int FMT>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_fp8_tiled_kernel(const Fp8Params p) {
-    constexpr int MT = 2, NT = 2, WN = 2, BM = 128, BN = 128;
+    constexpr int BM = 32 * MT * WM, BN = 32 * NT * WN;
+    static_assert(BN == 128 && WM * WN == 4, "tile shape");
+    constexpr int A_LOADS8 = BM / 32;                           // 1 KiB loads of X rows per wavefront and stage
+    constexpr int REGION8 = (A_LOADS8 + B_LOADS8) * 1024;       // [8 * A_LOADS8 rows of X | 32 rows of Wt] per loading wavefront
+    constexpr int STAGE8 = 4 * REGION8;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const int tid = threadIdx.x;
@@ -147,13 +150,13 @@ void gemm_fp8_tiled_kernel(const Fp8Params p) {
     // (the start of the Wt part of its region): instruction offsets -4 .. -1 KiB for X and 0 .. 3 KiB for Wt; the lane
     // offsets are biased so that the global side of the instruction offset cancels.  Rows past M or N re-read the last
     // valid row: an output depends on its own row of X and of Wt only, and theirs are never stored.
-    constexpr int LOADS_PER_STAGE = 2 * LOADS8;
+    constexpr int LOADS_PER_STAGE = A_LOADS8 + B_LOADS8;
     constexpr int WCOLS = 32 * NT;
     constexpr int STORES_F32 = MT * (32 * WCOLS / 4 / 64);
     constexpr int STORES_BF16 = MT * (32 * WCOLS / 8 / 64);
-    static_assert(LOADS_PER_STAGE * (RING8 - 3) + STORES_F32 < 64 && STORES_F32 != STORES_BF16, "vmcnt range");
+    static_assert(LOADS_PER_STAGE * (RING8 - 1) + STORES_F32 < 64 && STORES_F32 != STORES_BF16, "vmcnt range");
     constexpr int LANE_BIAS = 4096;
-    unsigned aoff[LOADS8], boff[LOADS8];
+    unsigned aoff[A_LOADS8], boff[B_LOADS8];
     const char *a_ptr = nullptr, *b_ptr = nullptr;
     int issue_item = blockIdx.x;
     int issue_stage = 0;
@@ -165,17 +168,22 @@ void gemm_fp8_tiled_kernel(const Fp8Params p) {
         a_ptr = uniform_pointer(reinterpret_cast<const char *>(p.X + (int64_t)m0 * p.ldx + kbase));
         b_ptr = uniform_pointer(reinterpret_cast<const char *>(p.Wt + (int64_t)n0 * p.ldw + kbase) - LANE_BIAS);
 #pragma unroll
-        for (int j = 0; j < LOADS8; ++j) {
-            const int r = (wave * LOADS8 + j) * 8 + (lane >> 3);
+        for (int j = 0; j < A_LOADS8; ++j) {
+            const int r = (wave * A_LOADS8 + j) * 8 + (lane >> 3);
             const int c = (lane & 7) ^ ((r >> 1) & 7);
-            aoff[j] = (unsigned)(min(r, p.M - 1 - m0) * (int)p.ldx + c * 16) + (unsigned)((LOADS8 - j) * 1024);
+            aoff[j] = (unsigned)(min(r, p.M - 1 - m0) * (int)p.ldx + c * 16) + (unsigned)((A_LOADS8 - j) * 1024);
+        }
+#pragma unroll
+        for (int j = 0; j < B_LOADS8; ++j) {
+            const int r = (wave * B_LOADS8 + j) * 8 + (lane >> 3);
+            const int c = (lane & 7) ^ ((r >> 1) & 7);
             boff[j] = (unsigned)(min(r, p.N - 1 - n0) * (int)p.ldw + c * 16) + (unsigned)(LANE_BIAS - j * 1024);
         }
     };
 
     const unsigned smem_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    const unsigned m0_in_stage = smem_lds + wave_u * REGION8 + LOADS8 * 1024;
+    const unsigned m0_in_stage = smem_lds + wave_u * REGION8 + A_LOADS8 * 1024;
     auto issue_part = [&](int slot, auto part_c) __attribute__((always_inline)) {
         constexpr int PART = decltype(part_c)::value;
         if (PART == 0 && __builtin_expect(issue_stage == stages_per_item, 0)) {
@@ -190,9 +198,9 @@ void gemm_fp8_tiled_kernel(const Fp8Params p) {
             }
         }
         const unsigned m0v = m0_in_stage + slot * STAGE8;
-        load_16B_per_lane_to_lds<(PART - LOADS8) * 1024, PART == 0>(a_ptr, aoff[PART], m0v);
+        if constexpr (PART < A_LOADS8) load_16B_per_lane_to_lds<(PART - A_LOADS8) * 1024, PART == 0>(a_ptr, aoff[PART], m0v);
         load_16B_per_lane_to_lds<PART * 1024, false>(b_ptr, boff[PART], m0v);
-        if (PART == LOADS8 - 1) {
+        if (PART == B_LOADS8 - 1) {
             ++issue_stage;
             a_ptr += BK8;
             b_ptr += BK8;
@@ -206,12 +214,16 @@ void gemm_fp8_tiled_kernel(const Fp8Params p) {
     };
 
     // ---- LDS fragment addresses (bytes inside a stage) ----
-    // Row R of the X tile lies in region R / 32 at row R % 32; row n of the Wt tile likewise, 4 KiB further.
+    // Row R of the X tile lies in region R / (8 A_LOADS8) at row R % (8 A_LOADS8); row n of the Wt tile in region n / 32
+    // at row n % 32, behind the region's X rows.
     int a_off[MT], b_off[NT];
 #pragma unroll
-    for (int a = 0; a < MT; ++a) a_off[a] = (wm * MT + a) * REGION8 + li * ROW8;
+    for (int a = 0; a < MT; ++a) {
+        const int R = (wm * MT + a) * 32 + li;
+        a_off[a] = (R / (8 * A_LOADS8)) * REGION8 + (R % (8 * A_LOADS8)) * ROW8;
+    }
 #pragma unroll
-    for (int b = 0; b < NT; ++b) b_off[b] = (wn * NT + b) * REGION8 + LOADS8 * 1024 + li * ROW8;
+    for (int b = 0; b < NT; ++b) b_off[b] = (wn * NT + b) * REGION8 + A_LOADS8 * 1024 + li * ROW8;
     const int sw = (li >> 1) & 7;
     // chunk positions of the lane's 32 bytes in K-step ks: (4 ks + 2 lg) ^ sw and (4 ks + 2 lg + 1) ^ sw
     int c_off[KSTEPS8][2];
@@ -288,13 +300,13 @@ void gemm_fp8_tiled_kernel(const Fp8Params p) {
 #pragma unroll
                 for (int r = m * READS_PER_KSTEP / NM; r < (m + 1) * READS_PER_KSTEP / NM; ++r)
                     read_frag_op(r, t_set, t_slot, t_set);
-                if (m == 1) {
-                    if (ks == 0) issue_part(free_slot, Int<0>{});
-                    if (ks == 1) issue_part(free_slot, Int<2>{});
-                }
-                if (m == 3) {
-                    if (ks == 0) issue_part(free_slot, Int<1>{});
-                    if (ks == 1) issue_part(free_slot, Int<3>{});
+                {   // the four parts of the next stage's loads, spread evenly over the stage's KSTEPS8 * NM groups
+                    constexpr int G = KSTEPS8 * NM;
+                    const int gi = ks * NM + m;
+                    if (gi == (0 * G) / 4) issue_part(free_slot, Int<0>{});
+                    if (gi == (1 * G) / 4) issue_part(free_slot, Int<1>{});
+                    if (gi == (2 * G) / 4) issue_part(free_slot, Int<2>{});
+                    if (gi == (3 * G) / 4) issue_part(free_slot, Int<3>{});
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -434,9 +446,10 @@ int compute_units() {
     return cus;
 }
 
-template <int FMT>
+template <int WM, int WN, int MT, int NT, int RING8, int FMT>
 hipError_t launch_tiled_fmt(const GemmArgs &a, hipStream_t s) {
-    constexpr int BM = 128, BN = 128;
+    constexpr int BM = 32 * MT * WM, BN = 32 * NT * WN;
+    constexpr int STAGE8 = 4 * (BM / 32 + B_LOADS8) * 1024;
     Fp8Params p;
     p.X = reinterpret_cast<const uint8_t *>(a.X); p.Wt = reinterpret_cast<const uint8_t *>(a.W);
     p.partials = a.partials; p.Y = (a.P == 1) ? a.Y : nullptr;
@@ -463,7 +476,7 @@ hipError_t launch_tiled_fmt(const GemmArgs &a, hipStream_t s) {
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 32) dev = 32;
 #define TBIK_LAUNCH8(L)                                                                                  \
     case L: {                                                                                            \
-        auto k = gemm_fp8_tiled_kernel<L, FMT>;                                                          \
+        auto k = gemm_fp8_tiled_kernel<L, WM, WN, MT, NT, RING8, FMT>;                                   \
         static std::atomic<unsigned> lds_allowed{0};                                                     \
         if (dev >= 32 || !((lds_allowed.load(std::memory_order_relaxed) >> dev) & 1u)) {                 \
             hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
@@ -487,6 +500,14 @@ hipError_t launch_tiled_fmt(const GemmArgs &a, hipStream_t s) {
 
 }  // namespace
 
+// rows: 128, 64 or 32 rows per workgroup tile (the caller's choice; the bits do not depend on it)
+template <int FMT>
+static hipError_t launch_rows(const GemmArgs &a, int rows, hipStream_t s) {
+    if (rows == 32) return launch_tiled_fmt<1, 4, 1, 1, 8, FMT>(a, s);      // 8 x 20 KiB slots: deep prefetch for weight streaming
+    if (rows == 64) return launch_tiled_fmt<1, 4, 2, 1, 6, FMT>(a, s);      // 6 x 24 KiB
+    return launch_tiled_fmt<2, 2, 2, 2, 5, FMT>(a, s);                      // 5 x 32 KiB
+}
+
 bool gemm_fp8_tiled_supports(const GemmArgs &a) {
     if (a.superleaf % BK8 != 0) return false;
     if (levels_for(a.ns / a.P) > 4) return false;
@@ -494,10 +515,10 @@ bool gemm_fp8_tiled_supports(const GemmArgs &a) {
     return true;
 }
 
-hipError_t launch_gemm_fp8_tiled(const GemmArgs &a, hipStream_t s) {
+hipError_t launch_gemm_fp8_tiled(const GemmArgs &a, int rows, hipStream_t s) {
     if (a.M <= 0 || a.N <= 0) return hipSuccess;
-    if (!gemm_fp8_tiled_supports(a)) return hipErrorInvalidValue;
-    return a.x_dtype == TBIK_FP8_E5M2 ? launch_tiled_fmt<1>(a, s) : launch_tiled_fmt<0>(a, s);
+    if (!gemm_fp8_tiled_supports(a) || (rows != 32 && rows != 64 && rows != 128)) return hipErrorInvalidValue;
+    return a.x_dtype == TBIK_FP8_E5M2 ? launch_rows<1>(a, rows, s) : launch_rows<0>(a, rows, s);
 }
 
 hipError_t launch_gemm_fp8_reference(const GemmArgs &a, hipStream_t s) {

@@ -278,7 +278,17 @@ int tbik_tree_combine(const float *partials, int P, void *Y, int64_t ldy, tbik_d
 // ---- 8-bit floating-point operands ----
 static bool is_fp8(int d) { return d == TBIK_FP8_E4M3 || d == TBIK_FP8_E5M2; }
 
-// K split of the 8-bit GEMM (pure): one tile shape (128 x 128), so only the two basic reasons of internal_split().
+// Rows of the 8-bit kernel's workgroup tile: the rule of the 16-bit kernels, or what tbik_set_gemm_variant forces.
+static int fp8_tile_rows(int M, int N) {
+    switch (g_forced_variant.load()) {
+        case VARIANT_T128: return 128;
+        case VARIANT_T64: return 64;
+        case VARIANT_T32: return 32;
+        default: return tile_rows(M, N);
+    }
+}
+
+// K split of a GEMM that has the 128 x 128 tile only (pure): the two basic reasons of internal_split().
 static int fp8_split(int M, int N, int ns) {
     const int64_t tiles = (((int64_t)M + 127) / 128) * (((int64_t)N + 127) / 128);
     int split = 1;
@@ -304,7 +314,7 @@ static int fp8_checks(int x_dtype, const void *X, int64_t ldx, const void *Wt, i
 size_t tbik_gemm_fp8_workspace_bytes(int M, int N, int K, int leaf, int k_first) {
     int sl, ns;
     if (check_tree(M, N, K, leaf, k_first, 1, &sl, &ns) != TBIK_OK) return 0;
-    const int split = fp8_split(M, N, ns);
+    const int split = internal_split(M, N, K, ns);         // the tile shapes and the rule of the 16-bit kernels
     return split > 1 ? (size_t)split * (size_t)M * (size_t)N * sizeof(float) : 0;
 }
 
@@ -324,7 +334,8 @@ int tbik_gemm_fp8(const void *X, int64_t ldx, const void *Wt, int64_t ldwt, void
     if (workspace && !aligned(workspace, 256)) return TBIK_ERR_ALIGN;
     hipStream_t s = (hipStream_t)hip_stream;
     GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)Wt, ldwt, nullptr, Y, ldy, (int)y_dtype, M, N, K, sl, ns, 1, (int)x_dtype, 0};
-    const int split = fp8_split(M, N, ns);
+    const int split = internal_split(M, N, K, ns);
+    const int rows = fp8_tile_rows(M, N);
     GemmArgs probe = a;
     probe.P = split;
     const bool tiled = g_forced_variant.load() != VARIANT_REFERENCE && gemm_fp8_tiled_supports(probe);
@@ -332,12 +343,12 @@ int tbik_gemm_fp8(const void *X, int64_t ldx, const void *Wt, int64_t ldwt, void
     if (!tiled) {
         e = launch_gemm_fp8_reference(a, s);
     } else if (split == 1) {
-        e = launch_gemm_fp8_tiled(a, s);
+        e = launch_gemm_fp8_tiled(a, rows, s);
     } else {
         a.partials = reinterpret_cast<float *>(workspace);
         a.Y = nullptr;
         a.P = split;
-        e = launch_gemm_fp8_tiled(a, s);
+        e = launch_gemm_fp8_tiled(a, rows, s);
         if (e == hipSuccess) e = launch_tree_combine(a.partials, split, Y, ldy, (int)y_dtype, M, N, s);
     }
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
@@ -355,7 +366,8 @@ int tbik_gemm_shard_partials_fp8(const void *X, int64_t ldx, const void *Wt, int
     if (!aligned(partials, 16)) return TBIK_ERR_ALIGN;
     GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)Wt, ldwt, partials, nullptr, 0, TBIK_F32, M, N, K, sl, ns, P, (int)x_dtype, 0};
     const bool tiled = g_forced_variant.load() != VARIANT_REFERENCE && gemm_fp8_tiled_supports(a);
-    hipError_t e = tiled ? launch_gemm_fp8_tiled(a, (hipStream_t)hip_stream) : launch_gemm_fp8_reference(a, (hipStream_t)hip_stream);
+    hipError_t e = tiled ? launch_gemm_fp8_tiled(a, fp8_tile_rows(M, N), (hipStream_t)hip_stream)
+                         : launch_gemm_fp8_reference(a, (hipStream_t)hip_stream);
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }
 
@@ -390,7 +402,10 @@ static int mxfp4_checks(const void *X, int64_t ldx, const void *Xs, int64_t ldxs
 }
 
 size_t tbik_gemm_mxfp4_workspace_bytes(int M, int N, int K, int leaf, int k_first) {
-    return tbik_gemm_fp8_workspace_bytes(M, N, K, leaf, k_first);      // one tile shape, the same K split
+    int sl, ns;
+    if (check_tree(M, N, K, leaf, k_first, 1, &sl, &ns) != TBIK_OK) return 0;
+    const int split = fp8_split(M, N, ns);                              // one tile shape (128 x 128)
+    return split > 1 ? (size_t)split * (size_t)M * (size_t)N * sizeof(float) : 0;
 }
 
 int tbik_gemm_mxfp4(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,

@@ -50,9 +50,9 @@ hipError_t launch_gemm_f32_tiled(const GemmArgs &a, int variant, hipStream_t s);
 bool gemm_f32_tiled_supports(const GemmArgs &a);
 
 // The same for 8-bit floating-point operands (x_dtype TBIK_FP8_E4M3 or TBIK_FP8_E5M2): X points to [M, ldx] bytes, W
-// to the TRANSPOSED weight [N, ldw] bytes; Y is fp32 or bf16.  One tile shape (128 x 128).
+// to the TRANSPOSED weight [N, ldw] bytes; Y is fp32 or bf16.  rows: 128, 64 or 32 rows per workgroup tile.
 hipError_t launch_gemm_fp8_reference(const GemmArgs &a, hipStream_t s);
-hipError_t launch_gemm_fp8_tiled(const GemmArgs &a, hipStream_t s);
+hipError_t launch_gemm_fp8_tiled(const GemmArgs &a, int rows, hipStream_t s);
 bool gemm_fp8_tiled_supports(const GemmArgs &a);
 
 // The same for MXFP4 operands (x_dtype TBIK_MXFP4): X points to [M, ldx] BYTES of packed element pairs (ldx >= K / 2),

@@ -39,7 +39,8 @@ def operands(Xb, Wb):
 def run_all_routes(Xd, Wt, leaf, g, Ps, fmt):
     """{(kernel, P): fp32 Y}: tbik_gemm_fp8 (P == 0) and shard partials + tree combine, on the tiled and the reference kernel."""
     out = {}
-    for name, v in (("tiled", tb.VARIANT_AUTO), ("reference", tb.VARIANT_REFERENCE)):
+    for name, v in (("tiled", tb.VARIANT_AUTO), ("reference", tb.VARIANT_REFERENCE), ("tile128", tb.VARIANT_T128),
+                    ("tile64", tb.VARIANT_T64), ("tile32", tb.VARIANT_T32)):
         tb.tbik_set_gemm_variant(v)
         out[(name, 0)] = tb.tbik_gemm_fp8(Xd, Wt, leaf, g, fmt, out_dtype=torch.float32)
         for P in Ps:
