@@ -118,3 +118,72 @@ def test_attention_random_batches_two_kernels_and_single_sequences():
         assert np.array_equal(gu.host_bf16_bits(alone), outs[0][q0:q1]), (case, b)
         if c["Q"].shape[0] * Hq <= 4000:
             check_against_oracle(outs[0], c, causal)
+
+
+def test_low_precision_gemms_random_shapes_all_routes():
+    """8-bit and MXFP4 operands: randomly drawn shapes, tile shapes (8-bit) and shard counts give the reference kernel's
+    bits; small-integer / equal-scale operands give the oracle's; operands inside wider buffers (strided rows)."""
+    rng = np.random.Generator(np.random.PCG64(4321))
+    u8 = lambda b: torch.from_numpy(np.ascontiguousarray(b, dtype=np.uint8)).to("cuda:0")
+
+    def inside_wider(t, pad):
+        buf = torch.zeros((t.shape[0], t.shape[1] + pad), dtype=torch.uint8, device="cuda:0")
+        buf[:, :t.shape[1]] = t
+        return buf[:, :t.shape[1]]
+
+    for case in range(16):
+        leaf = int(rng.choice([64, 128, 256, 512]))
+        g = int(rng.choice([1, 1, 2, 3]))
+        ns = int(rng.choice([1, 2, 4, 8, 16, 32]))
+        K = leaf * g * ns
+        if K > 16384:
+            continue
+        M = int(rng.choice([1, 2, 31, 33, 64, 100, 129, 300]))
+        N = int(rng.choice([8, 24, 128, 136, 392]))
+        pad = int(rng.choice([0, 16, 48]))
+        Ps = [p for p in (1, 2, 8, 32) if p <= ns]
+        if case % 2 == 0:
+            fmt = "e4m3" if case % 4 == 0 else "e5m2"
+            Xb, Wb = syn.gemm_small_integers(3000 + case, M, K, N, mag=8, fmt=fmt)
+            want, _ = orc.gemm_fp8(Xb, Wb, leaf, g, fmt=fmt)
+            Xd, Wt = inside_wider(u8(Xb), pad), inside_wider(u8(Wb.T), pad)
+            for v in (tb.VARIANT_REFERENCE, tb.VARIANT_T128, tb.VARIANT_T64, tb.VARIANT_T32, tb.VARIANT_AUTO):
+                tb.tbik_set_gemm_variant(v)
+                y = tb.tbik_gemm_fp8(Xd, Wt, leaf, g, fmt, out_dtype=torch.float32)
+                assert np.array_equal(gu.u32(gu.host_f32(y)), want.view(np.uint32)), (case, M, K, N, leaf, g, v, fmt)
+                for P in Ps:
+                    y = tb.tbik_tree_combine(tb.tbik_gemm_shard_partials_fp8(Xd, Wt, leaf, g, P, fmt), out_dtype=torch.float32)
+                    assert np.array_equal(gu.u32(gu.host_f32(y)), want.view(np.uint32)), (case, v, P, fmt)
+        else:
+            Xp, Xs, Wp, Ws = syn.gemm_random_mxfp4(3000 + case, M, K, N)
+            Xs[:] = 124
+            Ws[:] = 133
+            want, _ = orc.gemm_mxfp4(Xp, Xs, Wp, Ws, leaf, g)
+            ops = [inside_wider(u8(Xp), pad), inside_wider(u8(Xs), 8 if pad else 0), inside_wider(u8(Wp), pad), u8(Ws)]
+            for v in (tb.VARIANT_REFERENCE, tb.VARIANT_AUTO):
+                tb.tbik_set_gemm_variant(v)
+                y = tb.tbik_gemm_mxfp4(*ops, leaf, g, out_dtype=torch.float32)
+                assert np.array_equal(gu.u32(gu.host_f32(y)), want.view(np.uint32)), (case, M, K, N, leaf, g, v)
+                for P in Ps:
+                    y = tb.tbik_tree_combine(tb.tbik_gemm_shard_partials_mxfp4(*ops, leaf, g, P), out_dtype=torch.float32)
+                    assert np.array_equal(gu.u32(gu.host_f32(y)), want.view(np.uint32)), (case, v, P)
+    tb.tbik_set_gemm_variant(tb.VARIANT_AUTO)
+
+
+def test_gemm_swiglu_random_shapes_equal_two_gemms_then_the_activation():
+    rng = np.random.Generator(np.random.PCG64(99))
+    for case in range(10):
+        leaf = int(rng.choice([64, 128, 256]))
+        ns = int(rng.choice([1, 2, 8, 16]))
+        K = leaf * ns
+        M = int(rng.choice([1, 17, 64, 129, 500, 1100]))
+        I = int(rng.choice([64, 192, 1024, 1536, 2048]))
+        fmt = "fp16" if case % 3 == 2 else "bf16"
+        Xb, Wb = syn.gemm_random(500 + case, M, K, 2 * I, fmt=fmt)
+        dev = gu.dev_f16 if fmt == "fp16" else gu.dev_bf16
+        gemm = tb.tbik_gemm_f16 if fmt == "fp16" else tb.tbik_gemm
+        X, W = dev(Xb), dev(Wb)
+        act = tb.tbik_gemm_swiglu(X, W, leaf, 1)
+        gate = gemm(X, W[:, :I], leaf, 1, out_dtype=X.dtype)
+        up = gemm(X, W[:, I:], leaf, 1, out_dtype=X.dtype)
+        assert torch.equal(act.view(torch.int16), tb.tbik_silu_mul(gate, up).view(torch.int16)), (case, M, I, K, leaf, fmt)
