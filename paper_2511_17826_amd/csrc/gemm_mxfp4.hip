@@ -97,12 +97,12 @@ __global__ __launch_bounds__(64) void gemm_mxfp4_reference_kernel(
 // the X scales (row r at 8 r) and the Wt scales.  A lane's operand for one MFMA is chunk 2 ks + lg of its row and its
 // scale is byte 2 ks + lg of the row's eight.
 constexpr int BKB = 128;               // bytes of k per LDS stage row (256 k)
+// Three tile shapes as for the other formats: 128 x 128, and 64 x 128 / 32 x 128 (four wavefronts side by side) for small
+// batches, where the 4-bit weight is the traffic.  The X scale area always has four 256-byte parts, one per loading
+// wavefront: wavefront w brings the scales of rows (32 w) mod BM onward, so with fewer than 128 rows some parts repeat
+// others, and a reader takes row R from part R / 32.
 constexpr int KSTEPS4 = 4;             // MFMA K-steps (64 k) per stage
-constexpr int RING4 = 4;
-constexpr int LOADS4 = 4;              // 1 KiB data loads per wavefront, stage and operand
-constexpr int REGION4 = 2 * LOADS4 * 1024;
-constexpr int SCALES_AT = 4 * REGION4; // offset of the X scales in a slot; the Wt scales follow 1 KiB later
-constexpr int STAGE4 = SCALES_AT + 2048;
+constexpr int B_LOADS4 = 4;            // 1 KiB loads of Wt rows per wavefront and stage
 
 template <int N>
 __device__ __forceinline__ void wait_loads_and_barrier() {
@@ -127,10 +127,15 @@ struct Mx4Params {
 
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-template <int LEVELS>
+template <int LEVELS, int WM, int WN, int MT, int NT, int RING4>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_mxfp4_tiled_kernel(const Mx4Params p) {
-    constexpr int MT = 2, NT = 2, WN = 2, BM = 128, BN = 128;
+    constexpr int BM = 32 * MT * WM, BN = 32 * NT * WN;
+    static_assert(BN == 128 && WM * WN == 4, "tile shape");
+    constexpr int A_LOADS4 = BM / 32;                           // 1 KiB loads of X rows per wavefront and stage
+    constexpr int REGION4 = (A_LOADS4 + B_LOADS4) * 1024;
+    constexpr int SCALES_AT = 4 * REGION4;                      // offset of the X scales in a slot; the Wt scales follow 1 KiB later
+    constexpr int STAGE4 = SCALES_AT + 2048;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const int tid = threadIdx.x;
@@ -143,13 +148,13 @@ void gemm_mxfp4_tiled_kernel(const Mx4Params p) {
     // Per wavefront and stage: four 1 KiB loads of X rows, four of Wt rows (as in the 8-bit kernel: one m0, instruction
     // offsets -4 .. 3 KiB), then two 256-byte loads of scales (4 bytes per lane: lanes 2 r', 2 r' + 1 bring the eight
     // scale bytes of row 32 w + r'), with an m0 of their own.
-    constexpr int LOADS_PER_STAGE = 2 * LOADS4 + 2;
+    constexpr int LOADS_PER_STAGE = A_LOADS4 + B_LOADS4 + 2;
     constexpr int WCOLS = 32 * NT;
     constexpr int STORES_F32 = MT * (32 * WCOLS / 4 / 64);
     constexpr int STORES_BF16 = MT * (32 * WCOLS / 8 / 64);
     static_assert(LOADS_PER_STAGE * (RING4 - 1) + STORES_F32 < 64 && STORES_F32 != STORES_BF16, "vmcnt range");
     constexpr int LANE_BIAS = 4096;
-    unsigned aoff[LOADS4], boff[LOADS4], xsoff, wsoff;
+    unsigned aoff[A_LOADS4], boff[B_LOADS4], xsoff, wsoff;
     const char *a_ptr = nullptr, *b_ptr = nullptr, *xs_ptr = nullptr, *ws_ptr = nullptr;
     int issue_item = blockIdx.x;
     int issue_stage = 0;
@@ -163,20 +168,25 @@ void gemm_mxfp4_tiled_kernel(const Mx4Params p) {
         xs_ptr = uniform_pointer(reinterpret_cast<const char *>(p.Xs + (int64_t)m0 * p.ldxs + kbase / 32));
         ws_ptr = uniform_pointer(reinterpret_cast<const char *>(p.Ws + (int64_t)n0 * p.ldws + kbase / 32) - 1024);
 #pragma unroll
-        for (int j = 0; j < LOADS4; ++j) {
-            const int r = (wave * LOADS4 + j) * 8 + (lane >> 3);
+        for (int j = 0; j < A_LOADS4; ++j) {
+            const int r = (wave * A_LOADS4 + j) * 8 + (lane >> 3);
             const int c = (lane & 7) ^ ((r >> 1) & 7);
-            aoff[j] = (unsigned)(min(r, p.M - 1 - m0) * (int)p.ldx + c * 16) + (unsigned)((LOADS4 - j) * 1024);
+            aoff[j] = (unsigned)(min(r, p.M - 1 - m0) * (int)p.ldx + c * 16) + (unsigned)((A_LOADS4 - j) * 1024);
+        }
+#pragma unroll
+        for (int j = 0; j < B_LOADS4; ++j) {
+            const int r = (wave * B_LOADS4 + j) * 8 + (lane >> 3);
+            const int c = (lane & 7) ^ ((r >> 1) & 7);
             boff[j] = (unsigned)(min(r, p.N - 1 - n0) * (int)p.ldw + c * 16) + (unsigned)(LANE_BIAS - j * 1024);
         }
         const int rs = wave * 32 + (lane >> 1);
-        xsoff = (unsigned)(min(rs, p.M - 1 - m0) * (int)p.ldxs + 4 * (lane & 1));
+        xsoff = (unsigned)(min(rs % BM, p.M - 1 - m0) * (int)p.ldxs + 4 * (lane & 1));
         wsoff = (unsigned)(min(rs, p.N - 1 - n0) * (int)p.ldws + 4 * (lane & 1));    // + 1024 - 1024: the Wt scales' instruction offset
     };
 
     const unsigned smem_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    const unsigned m0_in_stage = smem_lds + wave_u * REGION4 + LOADS4 * 1024;
+    const unsigned m0_in_stage = smem_lds + wave_u * REGION4 + A_LOADS4 * 1024;
     const unsigned m0_scales = smem_lds + SCALES_AT + wave_u * 256;
     auto issue_part = [&](int slot, auto part_c) __attribute__((always_inline)) {
         constexpr int PART = decltype(part_c)::value;
@@ -194,9 +204,9 @@ void gemm_mxfp4_tiled_kernel(const Mx4Params p) {
             }
         }
         const unsigned m0v = m0_in_stage + slot * STAGE4;
-        load_16B_per_lane_to_lds<(PART - LOADS4) * 1024, PART == 0>(a_ptr, aoff[PART], m0v);
+        if constexpr (PART < A_LOADS4) load_16B_per_lane_to_lds<(PART - A_LOADS4) * 1024, PART == 0>(a_ptr, aoff[PART], m0v);
         load_16B_per_lane_to_lds<PART * 1024, false>(b_ptr, boff[PART], m0v);
-        if (PART == LOADS4 - 1) {
+        if (PART == B_LOADS4 - 1) {
             const unsigned m0s = m0_scales + slot * STAGE4;
             load_4B_per_lane_to_lds<0, true>(xs_ptr, xsoff, m0s);
             load_4B_per_lane_to_lds<1024, false>(ws_ptr, wsoff, m0s);
@@ -218,12 +228,13 @@ void gemm_mxfp4_tiled_kernel(const Mx4Params p) {
     int a_off[MT], b_off[NT], as_off[MT], bs_off[NT];
 #pragma unroll
     for (int a = 0; a < MT; ++a) {
-        a_off[a] = (wm * MT + a) * REGION4 + li * BKB;
-        as_off[a] = SCALES_AT + ((wm * MT + a) * 32 + li) * 8;
+        const int R = (wm * MT + a) * 32 + li;
+        a_off[a] = (R / (8 * A_LOADS4)) * REGION4 + (R % (8 * A_LOADS4)) * BKB;
+        as_off[a] = SCALES_AT + R * 8;
     }
 #pragma unroll
     for (int b = 0; b < NT; ++b) {
-        b_off[b] = (wn * NT + b) * REGION4 + LOADS4 * 1024 + li * BKB;
+        b_off[b] = (wn * NT + b) * REGION4 + A_LOADS4 * 1024 + li * BKB;
         bs_off[b] = SCALES_AT + 1024 + ((wn * NT + b) * 32 + li) * 8;
     }
     const int sw = (li >> 1) & 7;
@@ -236,7 +247,6 @@ void gemm_mxfp4_tiled_kernel(const Mx4Params p) {
     // the lane's four rows, fetched once per stage (for the next stage after the last K-step's bytes are taken out).
     i32x4 fr[2][MT + NT];
     u32x2 scl[MT + NT];
-    static_assert(MT + NT == MT * NT, "one fragment read per MFMA");
     auto read_frag_op = [&](int f, int set, int slot, int ks) {
         const unsigned char *sb = smem + slot * STAGE4;
         fr[set][f] = *reinterpret_cast<const i32x4 *>(sb + (f < MT ? a_off[f] : b_off[f - MT]) + c_off[ks]);
@@ -295,8 +305,10 @@ void gemm_mxfp4_tiled_kernel(const Mx4Params p) {
                 } else {
                     a.t[i][j] = mfma_32x32x64_mxfp4(fr[ks & 1][i], fr[ks & 1][MT + j], a.t[i][j], sc[i], sc[MT + j]);
                 }
-                read_frag_op(m, (ks + 1) & 1, t_slot, t_ks);   // one of the next K-step's four fragments per MFMA
-                if (m == 1) {                                  // one part of the next stage's loads per K-step
+#pragma unroll
+                for (int f = m * (MT + NT) / NM; f < (m + 1) * (MT + NT) / NM; ++f)
+                    read_frag_op(f, (ks + 1) & 1, t_slot, t_ks);   // this MFMA's share of the next K-step's fragments
+                if (m == NM - 1) {                             // one part of the next stage's loads per K-step
                     if (ks == 0) issue_part(free_slot, Int<0>{});
                     if (ks == 1) issue_part(free_slot, Int<1>{});
                     if (ks == 2) issue_part(free_slot, Int<2>{});
@@ -464,10 +476,10 @@ bool gemm_mxfp4_tiled_supports(const GemmArgs &a, const Mxfp4Scales &sc) {
     return true;
 }
 
-hipError_t launch_gemm_mxfp4_tiled(const GemmArgs &a, const Mxfp4Scales &sc, hipStream_t s) {
-    if (a.M <= 0 || a.N <= 0) return hipSuccess;
-    if (!gemm_mxfp4_tiled_supports(a, sc)) return hipErrorInvalidValue;
-    constexpr int BM = 128, BN = 128;
+template <int WM, int WN, int MT, int NT, int RING4>
+static hipError_t launch_mx4_shape(const GemmArgs &a, const Mxfp4Scales &sc, hipStream_t s) {
+    constexpr int BM = 32 * MT * WM, BN = 32 * NT * WN;
+    constexpr int STAGE4 = 4 * (BM / 32 + B_LOADS4) * 1024 + 2048;
     Mx4Params p;
     p.X = reinterpret_cast<const uint8_t *>(a.X); p.Wt = reinterpret_cast<const uint8_t *>(a.W);
     p.Xs = sc.Xs; p.Ws = sc.Ws;
@@ -495,7 +507,7 @@ hipError_t launch_gemm_mxfp4_tiled(const GemmArgs &a, const Mxfp4Scales &sc, hip
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 32) dev = 32;
 #define TBIK_LAUNCH4(L)                                                                                  \
     case L: {                                                                                            \
-        auto k = gemm_mxfp4_tiled_kernel<L>;                                                             \
+        auto k = gemm_mxfp4_tiled_kernel<L, WM, WN, MT, NT, RING4>;                                      \
         static std::atomic<unsigned> lds_allowed{0};                                                     \
         if (dev >= 32 || !((lds_allowed.load(std::memory_order_relaxed) >> dev) & 1u)) {                 \
             hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
@@ -515,6 +527,15 @@ hipError_t launch_gemm_mxfp4_tiled(const GemmArgs &a, const Mxfp4Scales &sc, hip
     }
 #undef TBIK_LAUNCH4
     return hipGetLastError();
+}
+
+hipError_t launch_gemm_mxfp4_tiled(const GemmArgs &a, const Mxfp4Scales &sc, int rows, hipStream_t s) {
+    if (a.M <= 0 || a.N <= 0) return hipSuccess;
+    if (!gemm_mxfp4_tiled_supports(a, sc)) return hipErrorInvalidValue;
+    if (rows == 32) return launch_mx4_shape<1, 4, 1, 1, 7>(a, sc, s);      // 7 x 22 KiB slots
+    if (rows == 64) return launch_mx4_shape<1, 4, 2, 1, 6>(a, sc, s);      // 6 x 26 KiB
+    if (rows == 128) return launch_mx4_shape<2, 2, 2, 2, 4>(a, sc, s);     // 4 x 34 KiB
+    return hipErrorInvalidValue;
 }
 
 }  // namespace tbik

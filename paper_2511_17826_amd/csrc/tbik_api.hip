@@ -288,16 +288,6 @@ static int fp8_tile_rows(int M, int N) {
     }
 }
 
-// K split of a GEMM that has the 128 x 128 tile only (pure): the two basic reasons of internal_split().
-static int fp8_split(int M, int N, int ns) {
-    const int64_t tiles = (((int64_t)M + 127) / 128) * (((int64_t)N + 127) / 128);
-    int split = 1;
-    while (ns / split > 16 && split < TBIK_MAX_SHARDS) split *= 2;
-    if (tiles >= 128) return split;
-    while (split < ns && split < 16 && tiles * split < 256) split *= 2;
-    return split;
-}
-
 static int fp8_checks(int x_dtype, const void *X, int64_t ldx, const void *Wt, int64_t ldwt, int M, int N, int K,
                       int leaf, int k_first, int P, int *sl, int *ns) {
     int rc = check_tree(M, N, K, leaf, k_first, P, sl, ns);
@@ -402,10 +392,7 @@ static int mxfp4_checks(const void *X, int64_t ldx, const void *Xs, int64_t ldxs
 }
 
 size_t tbik_gemm_mxfp4_workspace_bytes(int M, int N, int K, int leaf, int k_first) {
-    int sl, ns;
-    if (check_tree(M, N, K, leaf, k_first, 1, &sl, &ns) != TBIK_OK) return 0;
-    const int split = fp8_split(M, N, ns);                              // one tile shape (128 x 128)
-    return split > 1 ? (size_t)split * (size_t)M * (size_t)N * sizeof(float) : 0;
+    return tbik_gemm_fp8_workspace_bytes(M, N, K, leaf, k_first);      // the same tile shapes, the same K split
 }
 
 int tbik_gemm_mxfp4(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
@@ -426,7 +413,8 @@ int tbik_gemm_mxfp4(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, co
     hipStream_t s = (hipStream_t)hip_stream;
     GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)Wt, ldwt, nullptr, Y, ldy, (int)y_dtype, M, N, K, sl, ns, 1, TBIK_MXFP4, 0};
     const Mxfp4Scales sc{(const uint8_t *)Xs, ldxs, (const uint8_t *)Ws, ldws};
-    const int split = fp8_split(M, N, ns);
+    const int split = internal_split(M, N, K, ns);
+    const int rows = fp8_tile_rows(M, N);
     GemmArgs probe = a;
     probe.P = split;
     const bool tiled = g_forced_variant.load() != VARIANT_REFERENCE && gemm_mxfp4_tiled_supports(probe, sc);
@@ -434,12 +422,12 @@ int tbik_gemm_mxfp4(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, co
     if (!tiled) {
         e = launch_gemm_mxfp4_reference(a, sc, s);
     } else if (split == 1) {
-        e = launch_gemm_mxfp4_tiled(a, sc, s);
+        e = launch_gemm_mxfp4_tiled(a, sc, rows, s);
     } else {
         a.partials = reinterpret_cast<float *>(workspace);
         a.Y = nullptr;
         a.P = split;
-        e = launch_gemm_mxfp4_tiled(a, sc, s);
+        e = launch_gemm_mxfp4_tiled(a, sc, rows, s);
         if (e == hipSuccess) e = launch_tree_combine(a.partials, split, Y, ldy, (int)y_dtype, M, N, s);
     }
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
@@ -459,7 +447,8 @@ int tbik_gemm_shard_partials_mxfp4(const void *X, int64_t ldx, const void *Xs, i
     GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)Wt, ldwt, partials, nullptr, 0, TBIK_F32, M, N, K, sl, ns, P, TBIK_MXFP4, 0};
     const Mxfp4Scales sc{(const uint8_t *)Xs, ldxs, (const uint8_t *)Ws, ldws};
     const bool tiled = g_forced_variant.load() != VARIANT_REFERENCE && gemm_mxfp4_tiled_supports(a, sc);
-    hipError_t e = tiled ? launch_gemm_mxfp4_tiled(a, sc, (hipStream_t)hip_stream) : launch_gemm_mxfp4_reference(a, sc, (hipStream_t)hip_stream);
+    hipError_t e = tiled ? launch_gemm_mxfp4_tiled(a, sc, fp8_tile_rows(M, N), (hipStream_t)hip_stream)
+                         : launch_gemm_mxfp4_reference(a, sc, (hipStream_t)hip_stream);
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }
 

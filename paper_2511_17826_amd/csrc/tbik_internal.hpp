@@ -64,7 +64,7 @@ struct Mxfp4Scales {
     int64_t ldws;
 };
 hipError_t launch_gemm_mxfp4_reference(const GemmArgs &a, const Mxfp4Scales &sc, hipStream_t s);
-hipError_t launch_gemm_mxfp4_tiled(const GemmArgs &a, const Mxfp4Scales &sc, hipStream_t s);
+hipError_t launch_gemm_mxfp4_tiled(const GemmArgs &a, const Mxfp4Scales &sc, int rows, hipStream_t s);   // rows: 128, 64 or 32
 bool gemm_mxfp4_tiled_supports(const GemmArgs &a, const Mxfp4Scales &sc);
 
 // Y = T(partials[0..P)) elementwise + one rounding.

@@ -32,7 +32,8 @@ def dev(*arrays):
 def run_all_routes(ops, leaf, g, Ps):
     """{(kernel, P): fp32 Y}: tbik_gemm_mxfp4 (P == 0) and shard partials + tree combine, tiled and reference kernels."""
     out = {}
-    for name, v in (("tiled", tb.VARIANT_AUTO), ("reference", tb.VARIANT_REFERENCE)):
+    for name, v in (("tiled", tb.VARIANT_AUTO), ("reference", tb.VARIANT_REFERENCE), ("tile128", tb.VARIANT_T128),
+                    ("tile64", tb.VARIANT_T64), ("tile32", tb.VARIANT_T32)):
         tb.tbik_set_gemm_variant(v)
         out[(name, 0)] = tb.tbik_gemm_mxfp4(*ops, leaf, g, out_dtype=torch.float32)
         for P in Ps:

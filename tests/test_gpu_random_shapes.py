@@ -160,7 +160,7 @@ def test_low_precision_gemms_random_shapes_all_routes():
             Ws[:] = 133
             want, _ = orc.gemm_mxfp4(Xp, Xs, Wp, Ws, leaf, g)
             ops = [inside_wider(u8(Xp), pad), inside_wider(u8(Xs), 8 if pad else 0), inside_wider(u8(Wp), pad), u8(Ws)]
-            for v in (tb.VARIANT_REFERENCE, tb.VARIANT_AUTO):
+            for v in (tb.VARIANT_REFERENCE, tb.VARIANT_T128, tb.VARIANT_T64, tb.VARIANT_T32, tb.VARIANT_AUTO):
                 tb.tbik_set_gemm_variant(v)
                 y = tb.tbik_gemm_mxfp4(*ops, leaf, g, out_dtype=torch.float32)
                 assert np.array_equal(gu.u32(gu.host_f32(y)), want.view(np.uint32)), (case, M, K, N, leaf, g, v)
