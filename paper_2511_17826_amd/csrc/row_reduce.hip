@@ -11,6 +11,7 @@
 // workgroup keeps its block in registers and the blocks of a row exchange their maxima and sums through memory
 // (bounded waits; a row whose wait runs out is redone by a second, normally idle, kernel), so a row is read once.
 #include <atomic>
+#include <cstdlib>
 
 #include "tbik_device.hpp"
 #include "tbik_internal.hpp"
@@ -30,6 +31,16 @@ template <int XT> struct Elem {
     __device__ static __forceinline__ void load(const void *row, int64_t leaf, float (&f)[8]) {
         unpack8<XT == TBIK_F16>(reinterpret_cast<const uint4 *>(row)[leaf], f);
     }
+    __device__ static __forceinline__ void unpack(const uint4 &raw, float (&f)[8]) {
+        if constexpr (XT == TBIK_F16) {                 // element by element (the conversions are exact either way)
+            const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                f[e] = (float)__builtin_bit_cast(_Float16, (unsigned short)((e & 1) ? w[e >> 1] >> 16 : w[e >> 1] & 0xffffu));
+        } else {
+            unpack8<false>(raw, f);
+        }
+    }
 };
 template <> struct Elem<TBIK_F32> {
     static constexpr int EPL = 4;
@@ -37,6 +48,9 @@ template <> struct Elem<TBIK_F32> {
     __device__ static __forceinline__ void load(const void *row, int64_t leaf, float (&f)[8]) {
         const float4 v = reinterpret_cast<const float4 *>(row)[leaf];
         f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    }
+    __device__ static __forceinline__ void unpack(const uint4 &raw, float (&f)[8]) {
+        f[0] = __uint_as_float(raw.x); f[1] = __uint_as_float(raw.y); f[2] = __uint_as_float(raw.z); f[3] = __uint_as_float(raw.w);
     }
 };
 
@@ -246,44 +260,52 @@ constexpr unsigned RR_NOT_YET = 0xffffffffu;     // a NaN pattern: neither a max
 // workgroup gets the result.  Returns false if the wait ran out (or another workgroup of the row has given up).
 constexpr int RR_SLOTS_PER_LANE = 4;             // RR_MAX_COOP_BLOCKS / 64
 
+// The wavefront's part: lane = 0..63 of the calling wavefront.  Returns the combined value, or the "not yet" pattern
+// if the wait ran out.
+template <bool SUM>
+__device__ __forceinline__ unsigned wave_gather_row(const float *slots, int n, int n2, const unsigned *gave_up, int limit, int sleep_units,
+                                                    int lane) {
+    unsigned u[RR_SLOTS_PER_LANE];
+    bool complete = false;
+    for (int it = 0; it <= limit; ++it) {
+        bool mine = true;
+#pragma unroll
+        for (int j = 0; j < RR_SLOTS_PER_LANE; ++j) {
+            const int i = j * 64 + lane;
+            u[j] = 0u;
+            if (i < n) {
+                u[j] = __hip_atomic_load(reinterpret_cast<const unsigned *>(slots + i), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                mine = mine && (u[j] != RR_NOT_YET);
+            }
+        }
+        if (__all(mine)) { complete = true; break; }
+        if ((it & 15) == 15 && __hip_atomic_load(gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
+        for (int z = 0; z < (sleep_units & 255); ++z) __builtin_amdgcn_s_sleep(8);
+    }
+    float r;
+    if (SUM) {
+        TreeStash<2> st;                          // up to 4 groups of 64 slots
+        r = 0.0f;
+        const int nseg = n2 < 64 ? 1 : n2 >> 6;
+#pragma unroll
+        for (int j = 0; j < RR_SLOTS_PER_LANE; ++j)
+            if (j < nseg) r = st.push(wave_tree_sum((j * 64 + lane < n) ? __uint_as_float(u[j]) : 0.0f), (unsigned)j);
+    } else {
+        float m = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < RR_SLOTS_PER_LANE; ++j)
+            if (j * 64 + lane < n) m = fmaxf(m, __uint_as_float(u[j]));
+        r = wave_max(m);
+    }
+    return complete ? __float_as_uint(r) : RR_NOT_YET;
+}
+
 template <bool SUM>
 __device__ __forceinline__ bool gather_row(const float *slots, int n, int n2, const unsigned *gave_up, int limit, int sleep_units,
                                            unsigned *lds_word, float *value) {
     if (threadIdx.x < 64) {
-        const int lane = threadIdx.x;
-        unsigned u[RR_SLOTS_PER_LANE];
-        bool complete = false;
-        for (int it = 0; it <= limit; ++it) {
-            bool mine = true;
-#pragma unroll
-            for (int j = 0; j < RR_SLOTS_PER_LANE; ++j) {
-                const int i = j * 64 + lane;
-                u[j] = 0u;
-                if (i < n) {
-                    u[j] = __hip_atomic_load(reinterpret_cast<const unsigned *>(slots + i), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    mine = mine && (u[j] != RR_NOT_YET);
-                }
-            }
-            if (__all(mine)) { complete = true; break; }
-            if ((it & 15) == 15 && __hip_atomic_load(gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
-            for (int z = 0; z < (sleep_units & 255); ++z) __builtin_amdgcn_s_sleep(8);
-        }
-        float r;
-        if (SUM) {
-            TreeStash<2> st;                          // up to 4 groups of 64 slots
-            r = 0.0f;
-            const int nseg = n2 < 64 ? 1 : n2 >> 6;
-#pragma unroll
-            for (int j = 0; j < RR_SLOTS_PER_LANE; ++j)
-                if (j < nseg) r = st.push(wave_tree_sum((j * 64 + lane < n) ? __uint_as_float(u[j]) : 0.0f), (unsigned)j);
-        } else {
-            float m = -INFINITY;
-#pragma unroll
-            for (int j = 0; j < RR_SLOTS_PER_LANE; ++j)
-                if (j * 64 + lane < n) m = fmaxf(m, __uint_as_float(u[j]));
-            r = wave_max(m);
-        }
-        if (lane == 0) *lds_word = complete ? __float_as_uint(r) : RR_NOT_YET;
+        const unsigned r = wave_gather_row<SUM>(slots, n, n2, gave_up, limit, sleep_units, (int)threadIdx.x);
+        if (threadIdx.x == 0) *lds_word = r;
     }
     __syncthreads();
     const unsigned v = *lds_word;
@@ -385,6 +407,236 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_coop_kernel(const void 
         }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// The same exchange for launches of more (row, block) items than the device holds workgroups: a fixed number of
+// resident workgroups walks the items (item t = row * nb + block; workgroup g takes t = g, g + G, g + 2G, ...) as a
+// software pipeline over THREE blocks, two in registers and one parked in LDS.  With one block per workgroup the device alternates between
+// everybody loading, everybody waiting and everybody storing, and a workgroup that takes its items one after the
+// other waits, at every hand-off, for the slowest of its row.  Here a workgroup's step s is
+//     the sum of item s's row and the maximum of item s + 1's row arrive (one wait for both);
+//     write item s, start the loads of item s + 3 into the freed registers;
+//     sum of exponentials of item s + 1, published;
+//     the loads of item s + 3 have landed meanwhile: its maximum, published;
+// so a sum is asked for most of a step after it was published and a maximum more than a step after, and a
+// workgroup that lags its row by less than that delays nobody.  The first wavefront polls at the start of a step,
+// when it has nothing else in flight that its polls would queue behind (a wavefront's memory results come back in
+// issue order); the other waits are plain barriers, which do not wait for outstanding loads.
+// Every workgroup publishes a block's maximum without waiting for anything of that block or of a later one, so
+// with all G workgroups resident no wait is circular; the waits are bounded all the same, and a row whose wait
+// runs out is marked and redone as above.  Leaves, block tree, tree over blocks and the elementwise arithmetic are
+// those of logsoftmax_coop_kernel.
+__device__ __forceinline__ void lds_then_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+struct PipeLds {
+    float part[RR_SEGS * 4];   // the wavefronts' partial sums of a block
+    float max4[4];             // the wavefronts' maxima of a block
+    unsigned row_sum;          // T over the block sums of item s's row, or "not yet" if the wait ran out
+    unsigned row_max;          // the maximum of item s + 1's row, or "not yet"
+};
+
+// All eight loads of a block are issued by every thread in every step -- a leaf past the end of the row re-reads the
+// row's last leaf, and a step past the workgroup's last item (real = false) re-reads the first leaf of the tensor;
+// such values are never used -- so that the loads sit in straight-line code: the compiler's bookkeeping of
+// outstanding loads is then exact and nothing that works on one block waits for another block's loads or stores.
+template <int XT>
+__device__ __forceinline__ void pipe_load_block(const void *__restrict__ x, int64_t V, unsigned nleaves, int nb, int item, bool real,
+                                                uint4 (&raw)[RR_SEGS]) {
+    const int row = real ? item / nb : 0;
+    const unsigned b = real ? (unsigned)(item - row * nb) : 0u;
+    const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * Elem<XT>::BYTES;     // wave-uniform
+#pragma unroll
+    for (int seg = 0; seg < RR_SEGS; ++seg) {
+        const unsigned leaf = b * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;      // a row here has < 2^20 leaves
+        const unsigned at = real ? (leaf < nleaves ? leaf : nleaves - 1u) * 16u : 0u;
+        raw[seg] = *reinterpret_cast<const uint4 *>(rowp + at);
+    }
+}
+
+constexpr int RR_PIPE_SLOTS_PER_LANE = 1;         // rows of up to 64 blocks: one slot per lane and hand-off
+constexpr int RR_MAX_PIPE_BLOCKS = 64 * RR_PIPE_SLOTS_PER_LANE;
+
+// The first wavefront's wait at the start of a step: the block sums of one row (want_sum) and the block maxima of
+// another (want_max), looked at together until both sets are complete.  Results go to LDS; a set that is not
+// complete when the looks run out is reported as "not yet" and its row marked.
+__device__ __forceinline__ void pipe_gather(bool want_sum, const float *sum_slots, unsigned *sum_gave_up, bool want_max,
+                                            const float *max_slots, unsigned *max_gave_up, int n, int n2, int limit, int sleep_units,
+                                            int lane, PipeLds *lds) {
+    unsigned us[RR_PIPE_SLOTS_PER_LANE], um[RR_PIPE_SLOTS_PER_LANE];
+    bool sum_done = !want_sum, max_done = !want_max;
+    for (int it = 0; it <= limit; ++it) {
+        bool s_ok = true, m_ok = true;
+#pragma unroll
+        for (int j = 0; j < RR_PIPE_SLOTS_PER_LANE; ++j) {
+            const int i = j * 64 + lane;
+            us[j] = 0u;
+            um[j] = 0u;
+            if (i < n) {
+                if (!sum_done) {
+                    us[j] = __hip_atomic_load(reinterpret_cast<const unsigned *>(sum_slots + i), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    s_ok = s_ok && (us[j] != RR_NOT_YET);
+                }
+                if (!max_done) {
+                    um[j] = __hip_atomic_load(reinterpret_cast<const unsigned *>(max_slots + i), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    m_ok = m_ok && (um[j] != RR_NOT_YET);
+                }
+            }
+        }
+        if (!sum_done && __all(s_ok)) {
+            sum_done = true;
+            TreeStash<2> st;                          // up to 4 groups of 64 slots
+            float r = 0.0f;
+            const int nseg = n2 < 64 ? 1 : n2 >> 6;
+#pragma unroll
+            for (int j = 0; j < RR_PIPE_SLOTS_PER_LANE; ++j)
+                if (j < nseg) r = st.push(wave_tree_sum((j * 64 + lane < n) ? __uint_as_float(us[j]) : 0.0f), (unsigned)j);
+            if (lane == 0) lds->row_sum = __float_as_uint(r);
+        }
+        if (!max_done && __all(m_ok)) {
+            max_done = true;
+            float m = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < RR_PIPE_SLOTS_PER_LANE; ++j)
+                if (j * 64 + lane < n) m = fmaxf(m, __uint_as_float(um[j]));
+            m = wave_max(m);
+            if (lane == 0) lds->row_max = __float_as_uint(m);
+        }
+        if (sum_done && max_done) return;
+        if ((it & 15) == 15) {
+            if (!sum_done && __hip_atomic_load(sum_gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
+            if (!max_done && __hip_atomic_load(max_gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
+        }
+        for (int z = 0; z < (sleep_units & 255); ++z) __builtin_amdgcn_s_sleep(8);
+    }
+    if (lane == 0) {
+        if (!sum_done) {
+            lds->row_sum = RR_NOT_YET;
+            __hip_atomic_store(sum_gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (!max_done) {
+            lds->row_max = RR_NOT_YET;
+            __hip_atomic_store(max_gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// One step.  The workgroup's own items are numbered 0..n-1 (item j is global item g + j G) and step s works on items
+// s .. s + 3: P holds item s and then item s + 1, Q holds item s + 2 and then item s + 3, parked is this thread's part
+// of the block in LDS (leaf seg at parked[seg * RR_THREADS]; nobody else touches it), which holds item s + 1 and
+// then item s + 2.
+// rowmax: in, the maximum of item s's row as bits ("not yet" if that wait ran out); out, the same for item s + 1.
+template <int XT>
+__device__ __forceinline__ void pipe_step(const void *__restrict__ x, int64_t V, unsigned nleaves, int nb, int nb2, int g, int G,
+                                          int s, int n, uint4 (&P)[RR_SEGS], uint4 (&Q)[RR_SEGS], uint4 *parked, unsigned &rowmax,
+                                          float *wsmax, float *wssum, unsigned *sync_words, int wait_limit, int sleep_units,
+                                          PipeLds *lds, float *__restrict__ out) {
+    constexpr int EPL = Elem<XT>::EPL;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool has0 = s >= 0 && s < n, has1 = s + 1 >= 0 && s + 1 < n, has2 = s + 2 >= 0 && s + 2 < n, has3 = s + 3 < n;
+    const int item0 = g + s * G, item1 = g + (s + 1) * G, item3 = g + (s + 3) * G;     // the host keeps items below 2^31
+    const bool want_sum = has0 && rowmax != RR_NOT_YET;
+    if (wave == 0 && (want_sum || has1)) {
+        const int64_t row0 = want_sum ? item0 / nb : 0, row1 = has1 ? item1 / nb : 0;
+        pipe_gather(want_sum, wssum + row0 * nb, sync_words + row0 * RR_SYNC_WORDS + RR_W_GAVE_UP, has1, wsmax + row1 * nb,
+                    sync_words + row1 * RR_SYNC_WORDS + RR_W_GAVE_UP, nb, nb2, wait_limit, sleep_units, lane, lds);
+    }
+    lds_then_barrier();                                                   // 0: row_sum (item s) and row_max (item s + 1) are in LDS
+    const unsigned us = lds->row_sum, um = lds->row_max;
+    if (want_sum && us != RR_NOT_YET) {                                   // uniform
+        const int row = item0 / nb;
+        const unsigned leaf0 = (unsigned)(item0 - row * nb) * RR_BLOCK_LEAVES + threadIdx.x;
+        const float rm = __uint_as_float(rowmax), lg = logf(__uint_as_float(us));
+        char *orow = reinterpret_cast<char *>(out + (int64_t)row * V);    // wave-uniform
+#pragma unroll
+        for (int seg = 0; seg < RR_SEGS; ++seg) {
+            const unsigned leaf = leaf0 + seg * RR_THREADS;
+            float f[8], o[8];
+            Elem<XT>::unpack(P[seg], f);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) o[e] = (f[e] - rm) - lg;
+            if (leaf < nleaves) {
+                float4 *dst = reinterpret_cast<float4 *>(orow + leaf * (unsigned)(EPL * 4));
+                dst[0] = make_float4(o[0], o[1], o[2], o[3]);
+                if (EPL == 8) dst[1] = make_float4(o[4], o[5], o[6], o[7]);
+            }
+        }
+    }
+    if (has1) {
+#pragma unroll
+        for (int seg = 0; seg < RR_SEGS; ++seg) P[seg] = parked[seg * RR_THREADS];
+    }
+    if (has2) {
+#pragma unroll
+        for (int seg = 0; seg < RR_SEGS; ++seg) parked[seg * RR_THREADS] = Q[seg];
+    }
+    pipe_load_block<XT>(x, V, nleaves, nb, item3, has3, Q);
+    if (has1) {
+        rowmax = um;
+        const int row = item1 / nb;
+        const unsigned leaf0 = (unsigned)(item1 - row * nb) * RR_BLOCK_LEAVES + threadIdx.x;
+        const float rm = __uint_as_float(um);                             // "not yet": the sums are not used
+#pragma unroll
+        for (int seg = 0; seg < RR_SEGS; ++seg) {
+            float f[8];
+            Elem<XT>::unpack(P[seg], f);
+            float acc = 0.0f;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc = acc + expf(f[e] - rm);
+            const float w = wave_tree_sum(leaf0 + seg * RR_THREADS < nleaves ? acc : 0.0f);   // levels 0..5
+            if (lane == 0) lds->part[seg * 4 + wave] = w;
+        }
+    }
+    lds_then_barrier();                                                   // 1: the partial sums of item s + 1 are in LDS
+    if (wave == 0 && has1 && um != RR_NOT_YET) {
+        float t[RR_SEGS];
+#pragma unroll
+        for (int seg = 0; seg < RR_SEGS; ++seg)                           // levels 6..7: the four wavefronts
+            t[seg] = (lds->part[seg * 4 + 0] + lds->part[seg * 4 + 1]) + (lds->part[seg * 4 + 2] + lds->part[seg * 4 + 3]);
+        const float bs = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));   // levels 8..10
+        if (lane == 0)
+            __hip_atomic_exchange(reinterpret_cast<unsigned *>(wssum + item1), __float_as_uint(bs), __ATOMIC_RELAXED,
+                                  __HIP_MEMORY_SCOPE_AGENT);
+    }
+    {                                                                     // (of no consequence if there is no item s + 3)
+        const int row = item3 / nb;
+        const unsigned leaf0 = (unsigned)(item3 - row * nb) * RR_BLOCK_LEAVES + threadIdx.x;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int seg = 0; seg < RR_SEGS; ++seg) {
+            float f[8];
+            Elem<XT>::unpack(Q[seg], f);
+            float m = f[0];
+#pragma unroll
+            for (int e = 1; e < EPL; ++e) m = fmaxf(m, f[e]);
+            mx = fmaxf(mx, leaf0 + seg * RR_THREADS < nleaves ? m : -INFINITY);
+        }
+        mx = wave_max(mx);
+        if (lane == 0) lds->max4[wave] = mx;
+    }
+    lds_then_barrier();                                                   // 2: the four maxima of item s + 3 are in LDS
+    if (wave == 0 && has3) {
+        const float bm = fmaxf(fmaxf(lds->max4[0], lds->max4[1]), fmaxf(lds->max4[2], lds->max4[3]));
+        if (lane == 0)
+            __hip_atomic_exchange(reinterpret_cast<unsigned *>(wsmax + item3), __float_as_uint(bm), __ATOMIC_RELAXED,
+                                  __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+template <int XT>
+__global__ __launch_bounds__(RR_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) void logsoftmax_pipe_kernel(
+    const void *__restrict__ x, int64_t V, int nb, int nb2, int64_t items, float *wsmax, float *wssum, unsigned *sync_words,
+    int wait_limit, int sleep_units, float *__restrict__ out) {
+    __shared__ PipeLds lds;
+    __shared__ uint4 parked[RR_SEGS * RR_THREADS];                        // one block, each thread its own eight leaves
+    const int G = (int)gridDim.x, g = (int)blockIdx.x;
+    const int n = g < items ? (int)((items - g + G - 1) / G) : 0;        // this workgroup's items
+    const unsigned nleaves = (unsigned)(V / Elem<XT>::EPL);
+    uint4 P[RR_SEGS], Q[RR_SEGS];
+    unsigned rowmax = RR_NOT_YET;
+    for (int s = -3; s < n; ++s)
+        pipe_step<XT>(x, V, nleaves, nb, nb2, g, G, s, n, P, Q, parked + threadIdx.x, rowmax, wsmax, wssum, sync_words, wait_limit,
+                      sleep_units, &lds, out);
+}
+
 // Recomputes the rows that logsoftmax_coop_kernel marked (normally none): one workgroup walks all blocks of its row
 // three times.  Same leaves, block trees and tree over blocks, hence the same bits.
 template <int XT>
@@ -470,6 +722,29 @@ __global__ __launch_bounds__(256) void reset_sync_words_kernel(unsigned *slots_m
 static std::atomic<int> g_wait_limit{1 << 14};   // polls per wait: tens of milliseconds at most
 int set_row_wait_limit(int limit) { return g_wait_limit.exchange(limit < 0 ? 0 : limit); }
 
+// How many workgroups of logsoftmax_pipe_kernel the current device holds at a time (asked once per device and
+// element type; 0 if the runtime cannot say, and then the kernel is not used).
+template <int XT>
+static int pipe_resident_workgroups() {
+    constexpr int MAXDEV = 64;
+    static std::atomic<int> cached[MAXDEV];             // 0: not asked yet, -1: unknown
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAXDEV) return 0;
+    int v = cached[dev].load();
+    if (v == 0) {
+        int per_cu = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, logsoftmax_pipe_kernel<XT>, RR_THREADS, 0) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || per_cu <= 0 || cus <= 0) {
+            (void)hipGetLastError();
+            v = -1;
+        } else {
+            v = per_cu * cus;
+        }
+        cached[dev].store(v);
+    }
+    return v > 0 ? v : 0;
+}
+
 static int blocks_of(int64_t V, int x_dtype) {
     const int epl = (x_dtype == TBIK_F32) ? 4 : 8;
     const int64_t nleaves = V / epl;
@@ -512,22 +787,30 @@ static hipError_t run(const void *x, void *out, int op, int M, int64_t V, void *
             const int64_t nslots = (int64_t)mc * nb, nreset = nslots > nwords ? nslots : nwords;
             hipLaunchKernelGGL(reset_sync_words_kernel, dim3((unsigned)((nreset + 255) / 256)), dim3(256), 0, s,
                                reinterpret_cast<unsigned *>(w0), reinterpret_cast<unsigned *>(w1), nslots, words, nwords);
-            // two blocks per workgroup for fp32 rows once the launch has more workgroups than the device holds at a time
-            // (more of the row on the chip per resident workgroup); the choice cannot change a bit
-            // Waiting costs the others bandwidth: a wavefront that polls takes issue slots and memory requests from the
-            // workgroups that stream.  When the launch fills the device, a workgroup sleeps about 2 us (2 x s_sleep 32)
-            // before its first look -- no hand-off completes sooner -- and about 0.5 us between looks (measured at
-            // 512 x 151936: 200 us without the first sleep, 171 us with it, 191 us with twice as long; M = 1 loses 3 us
-            // with it, so small launches look at once).
-            const int sleep_units = (((int64_t)mc * nb >= 256 ? 2 : 0) << 8) | 2;
-            const bool two = false;   // measured: 195 -> 282 us at 512 x 151936 (170 registers, three workgroups per compute unit)
-            const int nwg = two ? (nb + 1) / 2 : nb, nwg2 = two ? (nb2 + 1) / 2 : nb2;
-            if (two)
-                hipLaunchKernelGGL((logsoftmax_coop_kernel<XT, (XT == TBIK_F32 ? 2 : 1)>), dim3((unsigned)((int64_t)mc * nwg)), block, 0, s,
-                                   xp, V, nwg, nwg2, w0, w1, words, g_wait_limit.load(), sleep_units, o + m0 * V);
-            else
-                hipLaunchKernelGGL((logsoftmax_coop_kernel<XT, 1>), dim3((unsigned)((int64_t)mc * nwg)), block, 0, s,
-                                   xp, V, nwg, nwg2, w0, w1, words, g_wait_limit.load(), sleep_units, o + m0 * V);
+            // From two rounds of resident workgroups on, the pipelined kernel: measured at V = 151936, fp32,
+            // 512 rows 160 -> 137 us, 128 rows 40.4 -> 38.5 us, 64 rows (1.2 rounds) 23.6 -> 26.8 us.  Its grid is the
+            // smallest that keeps the number of rounds, so that all workgroups have the same number of items or one less.
+            const int resident = pipe_resident_workgroups<XT>();
+            const int64_t items = (int64_t)mc * nb;
+            if (resident > 0 && nb <= RR_MAX_PIPE_BLOCKS && items >= 2 * (int64_t)resident) {
+                const int64_t rounds = (items + resident - 1) / resident;
+                int pipe_grid = (int)((items + rounds - 1) / rounds);
+#ifdef TBIK_TUNING
+                if (const char *e = getenv("TBIK_RR_PIPE_GRID")) pipe_grid = atoi(e) < resident ? atoi(e) : resident;
+#endif
+                hipLaunchKernelGGL((logsoftmax_pipe_kernel<XT>), dim3((unsigned)pipe_grid), block, 0, s, xp, V, nb, nb2, items, w0, w1,
+                                   words, g_wait_limit.load(), /* units of s_sleep 8 between looks */ 4, o + m0 * V);
+            } else {
+                // Waiting costs the others bandwidth: a wavefront that polls takes issue slots and memory requests from
+                // the workgroups that stream.  When the launch fills the device, a workgroup sleeps about 2 us
+                // (2 x s_sleep 32) before its first look -- no hand-off completes sooner -- and about 0.5 us between
+                // looks (measured at 512 x 151936: 200 us without the first sleep, 171 us with it, 191 us with twice as
+                // long; M = 1 loses 3 us with it, so small launches look at once).  Two blocks per workgroup measured
+                // slower (195 -> 282 us: 170 registers, three workgroups per compute unit).
+                const int sleep_units = ((items >= 256 ? 2 : 0) << 8) | 2;
+                hipLaunchKernelGGL((logsoftmax_coop_kernel<XT, 1>), dim3((unsigned)items), block, 0, s, xp, V, nb, nb2, w0, w1, words,
+                                   g_wait_limit.load(), sleep_units, o + m0 * V);
+            }
             hipLaunchKernelGGL((logsoftmax_redo_kernel<XT>), dim3(mc), block, 0, s, xp, V, nb, nb2,
                                (const unsigned *)words, o + m0 * V);
         } else {

@@ -151,24 +151,39 @@ struct TreeStash {
     }
 };
 
-// One level of the tree across lanes: lane i and lane i^mask hold sibling subtrees; both get the sum.
-__device__ __forceinline__ float lane_pair_add(float v, int mask) { return v + __shfl_xor(v, mask, 64); }
+// The value of another lane of the same row of 16 lanes, chosen by a data-parallel-primitive control word: no trip
+// through the LDS crossbar, the move folds into the instruction that uses it.
+// 0xB1: quad_perm [1,0,3,2] (lane ^ 1); 0x4E: quad_perm [2,3,0,1] (lane ^ 2); 0x141: mirror within 8 lanes; 0x140:
+// mirror within 16 lanes.
+template <int CTRL>
+__device__ __forceinline__ float from_lane_in_row(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float value_of_lane(float v, int lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
 
-// T over the 64 lanes of a wavefront (lane index = leaf index): levels 0..5.  Every lane gets the result.
+// T over the 64 lanes of a wavefront (lane index = leaf index): levels 0..5.  Every lane gets the result.  All 64
+// lanes must be active.  Levels 0..3 pair a lane with one whose value is the sibling subtree's sum: lane ^ 1,
+// lane ^ 2, then the mirror image within 8 and within 16 lanes -- after level l all lanes of an aligned group of
+// 2^(l+1) hold the same bits (the additions are the same up to the order of the two operands), so any lane of the
+// sibling group will do.  Levels 4 and 5 take the four row sums through scalar registers.
 __device__ __forceinline__ float wave_tree_sum(float v) {
-    v = lane_pair_add(v, 1);
-    v = lane_pair_add(v, 2);
-    v = lane_pair_add(v, 4);
-    v = lane_pair_add(v, 8);
-    v = lane_pair_add(v, 16);
-    v = lane_pair_add(v, 32);
-    return v;
+    v = v + from_lane_in_row<0xB1>(v);
+    v = v + from_lane_in_row<0x4E>(v);
+    v = v + from_lane_in_row<0x141>(v);
+    v = v + from_lane_in_row<0x140>(v);
+    const float r0 = value_of_lane(v, 0), r1 = value_of_lane(v, 16), r2 = value_of_lane(v, 32), r3 = value_of_lane(v, 48);
+    return (r0 + r1) + (r2 + r3);
 }
 
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int m = 1; m < 64; m <<= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
-    return v;
+    v = fmaxf(v, from_lane_in_row<0xB1>(v));
+    v = fmaxf(v, from_lane_in_row<0x4E>(v));
+    v = fmaxf(v, from_lane_in_row<0x141>(v));
+    v = fmaxf(v, from_lane_in_row<0x140>(v));
+    const float r0 = value_of_lane(v, 0), r1 = value_of_lane(v, 16), r2 = value_of_lane(v, 32), r3 = value_of_lane(v, 48);
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
 }
 
 }  // namespace tbik

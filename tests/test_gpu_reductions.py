@@ -167,6 +167,41 @@ def test_logsoftmax_bounded_wait_runs_out_same_bits():
     assert np.max(np.abs(o - want) / np.maximum(1.0, np.abs(want))) <= 1e-5
 
 
+@pytest.mark.parametrize("fmt,M,V", [("f32", 130, 151936), ("bf16", 450, 80008), ("fp16", 700, 40000)])
+def test_logsoftmax_pipelined_launch_equals_row_by_row_and_survives_a_zero_wait(fmt, M, V):
+    """Launches of two or more rounds of resident workgroups take the pipelined kernel (a workgroup walks several
+    blocks, three of them in flight).  Its rows must have the bits of the same rows computed a few at a time (the
+    one-block-per-workgroup kernel), must agree with the oracle, and with the wait bound forced to 0 from the host
+    (every hand-off gets one look, most rows are marked and redone) the call must still end normally with the same
+    bits."""
+    rng = np.random.Generator(np.random.PCG64(M + V))
+    if fmt == "f32":
+        x = syn.logits_f32(M, V, seed=M)
+        xd = gu.dev_f32(x)
+        x32, leaf = x, orc.LEAF_F32
+    else:
+        xb = syn.to_storage(rng.standard_normal((M, V)).astype(np.float32) * 3.0, fmt)
+        xd = gu.dev_bf16(xb) if fmt == "bf16" else gu.dev_f16(xb)
+        x32, leaf = syn.from_storage(xb, fmt), orc.LEAF_BF16
+    full = tb.tbik_row_reduce(xd, tb.TBIK_LOGSOFTMAX)
+    torch.cuda.synchronize()
+    for a in range(0, M, 37):
+        b = min(M, a + 37)
+        y = tb.tbik_row_reduce(xd[a:b].contiguous(), tb.TBIK_LOGSOFTMAX)
+        assert torch.equal(y.view(torch.int32), full[a:b].view(torch.int32)), (a, b)
+    rows = [0, M // 2, M - 1]
+    want = orc.row_logsoftmax(x32[rows], leaf)
+    got = gu.host_f32(full[rows])
+    assert np.max(np.abs(got - want) / np.maximum(1.0, np.abs(want))) <= 1e-5
+    prev = tb.tbik_set_row_wait_limit(0)
+    try:
+        forced = tb.tbik_row_reduce(xd, tb.TBIK_LOGSOFTMAX)
+        torch.cuda.synchronize()
+    finally:
+        tb.tbik_set_row_wait_limit(prev)
+    assert torch.equal(forced.view(torch.int32), full.view(torch.int32))
+
+
 def test_logsoftmax_long_rows_repeatable_under_load():
     """The workgroups of a long row hand their maxima and sums to each other through memory, across chiplets: with
     all compute units busy (512 rows), repeated runs and runs on slices of the batch must keep giving the same bits."""
