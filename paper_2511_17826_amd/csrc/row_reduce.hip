@@ -788,13 +788,13 @@ static hipError_t run(const void *x, void *out, int op, int M, int64_t V, void *
             hipLaunchKernelGGL(reset_sync_words_kernel, dim3((unsigned)((nreset + 255) / 256)), dim3(256), 0, s,
                                reinterpret_cast<unsigned *>(w0), reinterpret_cast<unsigned *>(w1), nslots, words, nwords);
             // From two rounds of resident workgroups on, the pipelined kernel: measured at V = 151936, fp32,
-            // 512 rows 160 -> 137 us, 128 rows 40.4 -> 38.5 us, 64 rows (1.2 rounds) 23.6 -> 26.8 us.  Its grid is the
-            // smallest that keeps the number of rounds, so that all workgroups have the same number of items or one less.
+            // 512 rows 160 -> 135 us, 128 rows 40.4 -> 38.5 us, 64 rows (1.2 rounds) 23.6 -> 26.8 us.  Its grid is all the
+            // device holds (a smaller grid that gives every workgroup the same number of items measured slower:
+            // 973 workgroups 138 us, 1024 135 us).
             const int resident = pipe_resident_workgroups<XT>();
             const int64_t items = (int64_t)mc * nb;
             if (resident > 0 && nb <= RR_MAX_PIPE_BLOCKS && items >= 2 * (int64_t)resident) {
-                const int64_t rounds = (items + resident - 1) / resident;
-                int pipe_grid = (int)((items + rounds - 1) / rounds);
+                int pipe_grid = resident;
 #ifdef TBIK_TUNING
                 if (const char *e = getenv("TBIK_RR_PIPE_GRID")) pipe_grid = atoi(e) < resident ? atoi(e) : resident;
 #endif
