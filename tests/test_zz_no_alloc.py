@@ -55,6 +55,21 @@ def test_static_scratch_matches_workspace_entry_point_twice_in_a_row(V):
         assert np.array_equal(gu.u32(s), gu.u32(orc.row_sum(x, orc.LEAF_F32)))
 
 
+def test_static_scratch_with_the_pipelined_launch_then_a_small_one():
+    # 120 rows of 19 blocks are more than two rounds of resident workgroups: the pipelined log-softmax kernel, whose
+    # slots and flags live in the scratch as well; then a small call on the same scratch
+    V = 151936
+    for M, seed in ((120, 8), (5, 9)):
+        xd = gu.dev_f32(logits(M, V, seed))
+        want = tb.tbik_row_reduce(xd, tb.TBIK_LOGSOFTMAX)
+        got = torch.full_like(want, float("nan"))
+        before = torch.cuda.memory_allocated()
+        call_static(xd, tb.TBIK_LOGSOFTMAX, got)
+        torch.cuda.synchronize()
+        assert torch.cuda.memory_allocated() == before
+        assert torch.equal(got.view(torch.int32), want.view(torch.int32)), M
+
+
 def test_static_scratch_limit_and_setup_call():
     L = tb.lib()
     x = torch.zeros((1, 8), dtype=torch.float32, device="cuda:0")
