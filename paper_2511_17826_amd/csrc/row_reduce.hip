@@ -11,7 +11,6 @@
 // workgroup keeps its block in registers and the blocks of a row exchange their maxima and sums through memory
 // (bounded waits; a row whose wait runs out is redone by a second, normally idle, kernel), so a row is read once.
 #include <atomic>
-#include <cstdlib>
 
 #include "tbik_device.hpp"
 #include "tbik_internal.hpp"
@@ -794,10 +793,7 @@ static hipError_t run(const void *x, void *out, int op, int M, int64_t V, void *
             const int resident = pipe_resident_workgroups<XT>();
             const int64_t items = (int64_t)mc * nb;
             if (resident > 0 && nb <= RR_MAX_PIPE_BLOCKS && items >= 2 * (int64_t)resident) {
-                int pipe_grid = resident;
-#ifdef TBIK_TUNING
-                if (const char *e = getenv("TBIK_RR_PIPE_GRID")) pipe_grid = atoi(e) < resident ? atoi(e) : resident;
-#endif
+                const int pipe_grid = resident;
                 hipLaunchKernelGGL((logsoftmax_pipe_kernel<XT>), dim3((unsigned)pipe_grid), block, 0, s, xp, V, nb, nb2, items, w0, w1,
                                    words, g_wait_limit.load(), /* units of s_sleep 8 between looks */ 4, o + m0 * V);
             } else {
