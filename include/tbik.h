@@ -428,8 +428,8 @@ const char *tbik_variant_name(int variant);      /* NULL past the last variant *
 int tbik_set_attention_variant(int variant);
 
 /* Log-softmax of rows longer than one block lets the workgroups of a row wait for each other a bounded number of
- * polls; a row whose wait runs out is recomputed by a second kernel of the same call, with the same bits.  This
- * sets the bound (testing only: 0 makes the waits run out, so that the second kernel is exercised).  Returns the
+ * polls; a workgroup whose wait runs out finishes its block by itself (it walks the whole row), with the same bits.
+ * This sets the bound (testing only: 0 makes the waits run out, so that this path is exercised).  Returns the
  * previous bound; negative values are taken as 0. */
 int tbik_set_row_wait_limit(int polls);
 

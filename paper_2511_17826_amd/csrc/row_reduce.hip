@@ -67,6 +67,17 @@ __device__ __forceinline__ float wave_tree_of_array(const float *p, int n, int n
     return tot;
 }
 
+// The same for n2 <= 256 (up to four groups of 64 values), without a loop: the stash stays in registers.
+__device__ __forceinline__ float wave_tree_of_256(const float *p, int n, int n2, int lane) {
+    TreeStash<2> st;
+    float tot = 0.0f;
+    const int nseg = n2 < 64 ? 1 : n2 >> 6;
+#pragma unroll
+    for (int seg = 0; seg < 4; ++seg)
+        if (seg < nseg) tot = st.push(wave_tree_sum((seg * 64 + lane < n) ? p[seg * 64 + lane] : 0.0f), (unsigned)seg);
+    return tot;
+}
+
 __device__ __forceinline__ float wave_max_of_array(const float *p, int n, int lane) {
     float m = -INFINITY;
     for (int i = lane; i < n; i += 64) m = fmaxf(m, p[i]);
@@ -234,14 +245,82 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_one_block_kernel(const 
     }
 }
 
+// What a workgroup does for block b of a row whose hand-off ran out (normally never): it computes the row's maximum
+// and the row's sum by itself, walking all blocks of the row twice, and writes its own block.  Same leaves, block
+// trees and tree over blocks as the exchange, hence the same bits.  Called by all threads of the workgroup (256, the
+// data wavefronts), convergently; per_block holds RR_MAX_COOP_BLOCKS floats and lds RR_SEGS * 4.
+template <int XT>
+__device__ __forceinline__ void logsoftmax_block_alone(const void *__restrict__ x, int64_t V, int nb, int nb2, int row, int b,
+                                                    float *lds, float *per_block, float *__restrict__ out) {
+    constexpr int EPL = Elem<XT>::EPL;
+    const int lane = threadIdx.x & 63;
+    const int64_t nleaves = V / EPL;
+    const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * Elem<XT>::BYTES;
+    float *orow = out + (int64_t)row * V;
+    __syncthreads();                                                      // per_block and lds may still be in use
+    for (int k = 0; k < nb; ++k) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int seg = 0; seg < RR_SEGS; ++seg) {
+            const int64_t leaf = (int64_t)k * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
+            if (leaf < nleaves) {
+                float f[8];
+                Elem<XT>::load(rowp, leaf, f);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) mx = fmaxf(mx, f[e]);
+            }
+        }
+        const float bm = block_max(mx, lds);
+        if (threadIdx.x == 0) per_block[k] = bm;
+    }
+    __syncthreads();
+    const float rowmax = wave_max_of_array(per_block, nb, lane);
+    __syncthreads();
+    for (int k = 0; k < nb; ++k) {
+        float L[RR_SEGS];
+#pragma unroll
+        for (int seg = 0; seg < RR_SEGS; ++seg) {
+            const int64_t leaf = (int64_t)k * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
+            float acc = 0.0f;
+            if (leaf < nleaves) {
+                float f[8];
+                Elem<XT>::load(rowp, leaf, f);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc = acc + expf(f[e] - rowmax);
+            }
+            L[seg] = acc;
+        }
+        const float bs = block_tree_sum(L, lds);
+        if (threadIdx.x == 0) per_block[k] = bs;
+    }
+    __syncthreads();
+    const float S = wave_tree_of_256(per_block, nb, nb2, lane);      // nb <= RR_MAX_COOP_BLOCKS = 256
+    const float lg = logf(S);
+#pragma unroll
+    for (int seg = 0; seg < RR_SEGS; ++seg) {
+        const int64_t leaf = (int64_t)b * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
+        if (leaf < nleaves) {
+            float f[8], o[8];
+            Elem<XT>::load(rowp, leaf, f);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) o[e] = (f[e] - rowmax) - lg;
+            float4 *dst = reinterpret_cast<float4 *>(orow + leaf * EPL);
+            dst[0] = make_float4(o[0], o[1], o[2], o[3]);
+            if (EPL == 8) dst[1] = make_float4(o[4], o[5], o[6], o[7]);
+        }
+    }
+    __syncthreads();
+}
+
 // ---------------------------------------------------------------------------------------------------------
 // Log-softmax of rows of 2..RR_MAX_COOP_BLOCKS blocks, one launch, one workgroup per (row, block), block index
 // fastest.  Each workgroup loads its block once and keeps it in registers; the blocks of a row publish their
-// maxima, wait for each other, publish their sums of exp(x - rowmax), wait again, and write.  The waits are on
-// per-row arrival counters.  Workgroups are started in index order and a row's workgroups are consecutive, so
-// the ones a workgroup waits for are running or about to be started as long as a row has fewer blocks than
-// the device has workgroup slots.  Nothing here relies on that for correctness: every wait is bounded, a
-// workgroup whose wait runs out marks its row and leaves, and logsoftmax_redo_kernel recomputes marked rows.
+// maxima, wait for each other, publish their sums of exp(x - rowmax), wait again, and write.  Workgroups are
+// started in index order and a row's workgroups are consecutive, so the ones a workgroup waits for are running or
+// about to be started as long as a row has fewer blocks than the device has workgroup slots.  Nothing here relies
+// on that for correctness: every wait is bounded, and a workgroup whose wait runs out finishes its block alone
+// (logsoftmax_block_alone) after raising the row's flag, which lets the row's other workgroups stop waiting for
+// what it will not publish any more; they do the same.
 // Arithmetic (leaves, block tree, tree over blocks, expf, logf) is that of the three-kernel path: same bits.
 constexpr int RR_MAX_COOP_BLOCKS = 256;
 // Per row 64 words (a 256-byte line of its own), of which one is used: the give-up flag.
@@ -325,7 +404,9 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_coop_kernel(const void 
     // between looks.
     __shared__ float lds[RR_SEGS * 4];
     __shared__ unsigned lds_word;
+    __shared__ float per_block[RR_MAX_COOP_BLOCKS];                       // only for a block that has to be finished alone
     constexpr int EPL = Elem<XT>::EPL;
+    static_assert(BPW == 1, "a workgroup that finishes alone writes one block");
     const int row = (int)(blockIdx.x / (unsigned)nwg), w = (int)(blockIdx.x % (unsigned)nwg);
     const int64_t nleaves = V / EPL;
     const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * Elem<XT>::BYTES;
@@ -356,10 +437,8 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_coop_kernel(const void 
                               __HIP_MEMORY_SCOPE_AGENT);
     for (int z = 0; z < (sleep_units >> 8); ++z) __builtin_amdgcn_s_sleep(32);
     float rowmax;
-    if (!gather_row<false>(wsmax + (int64_t)row * nwg, nwg, nwg2, gave_up, wait_limit, sleep_units, &lds_word, &rowmax)) {
-        if (threadIdx.x == 0) __hip_atomic_store(gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        return;
-    }
+    bool arrived = gather_row<false>(wsmax + (int64_t)row * nwg, nwg, nwg2, gave_up, wait_limit, sleep_units, &lds_word, &rowmax);
+    if (arrived) {
 
     float bsum[BPW];
 #pragma unroll
@@ -384,10 +463,8 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_coop_kernel(const void 
                               __HIP_MEMORY_SCOPE_AGENT);
     for (int z = 0; z < (sleep_units >> 8); ++z) __builtin_amdgcn_s_sleep(32);
     float S;
-    if (!gather_row<true>(wssum + (int64_t)row * nwg, nwg, nwg2, gave_up, wait_limit, sleep_units, &lds_word, &S)) {
-        if (threadIdx.x == 0) __hip_atomic_store(gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        return;
-    }
+    arrived = gather_row<true>(wssum + (int64_t)row * nwg, nwg, nwg2, gave_up, wait_limit, sleep_units, &lds_word, &S);
+    if (arrived) {
     const float lg = logf(S);
 #pragma unroll
     for (int k = 0; k < BPW; ++k)
@@ -404,6 +481,12 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_coop_kernel(const void 
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+    }   // the sums arrived
+    }   // the maxima arrived
+    if (!arrived) {                                                       // uniform; the block's registers are free by now
+        if (threadIdx.x == 0) __hip_atomic_store(gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        logsoftmax_block_alone<XT>(x, V, nwg, nwg2, row, w, lds, per_block, out);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -422,7 +505,7 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_coop_kernel(const void 
 // issue order); the other waits are plain barriers, which do not wait for outstanding loads.
 // Every workgroup publishes a block's maximum without waiting for anything of that block or of a later one, so
 // with all G workgroups resident no wait is circular; the waits are bounded all the same, and a row whose wait
-// runs out is marked and redone as above.  Leaves, block tree, tree over blocks and the elementwise arithmetic are
+// runs out is finished alone as above.  Leaves, block tree, tree over blocks and the elementwise arithmetic are
 // those of logsoftmax_coop_kernel.
 __device__ __forceinline__ void lds_then_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
@@ -456,7 +539,7 @@ constexpr int RR_MAX_PIPE_BLOCKS = 64 * RR_PIPE_SLOTS_PER_LANE;
 
 // The first wavefront's wait at the start of a step: the block sums of one row (want_sum) and the block maxima of
 // another (want_max), looked at together until both sets are complete.  Results go to LDS; a set that is not
-// complete when the looks run out is reported as "not yet" and its row marked.
+// complete when the looks run out is reported as "not yet" and its row's flag raised.
 __device__ __forceinline__ void pipe_gather(bool want_sum, const float *sum_slots, unsigned *sum_gave_up, bool want_max,
                                             const float *max_slots, unsigned *max_gave_up, int n, int n2, int limit, int sleep_units,
                                             int lane, PipeLds *lds) {
@@ -527,7 +610,7 @@ template <int XT>
 __device__ __forceinline__ void pipe_step(const void *__restrict__ x, int64_t V, unsigned nleaves, int nb, int nb2, int g, int G,
                                           int s, int n, uint4 (&P)[RR_SEGS], uint4 (&Q)[RR_SEGS], uint4 *parked, unsigned &rowmax,
                                           float *wsmax, float *wssum, unsigned *sync_words, int wait_limit, int sleep_units,
-                                          PipeLds *lds, float *__restrict__ out) {
+                                          PipeLds *lds, float *per_block, float *__restrict__ out) {
     constexpr int EPL = Elem<XT>::EPL;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool has0 = s >= 0 && s < n, has1 = s + 1 >= 0 && s + 1 < n, has2 = s + 2 >= 0 && s + 2 < n, has3 = s + 3 < n;
@@ -540,6 +623,10 @@ __device__ __forceinline__ void pipe_step(const void *__restrict__ x, int64_t V,
     }
     lds_then_barrier();                                                   // 0: row_sum (item s) and row_max (item s + 1) are in LDS
     const unsigned us = lds->row_sum, um = lds->row_max;
+    if (has0 && !(want_sum && us != RR_NOT_YET)) {                        // uniform: a wait for this item's row ran out
+        const int row = item0 / nb;
+        logsoftmax_block_alone<XT>(x, V, nb, nb2, row, item0 - row * nb, lds->part, per_block, out);
+    }
     if (want_sum && us != RR_NOT_YET) {                                   // uniform
         const int row = item0 / nb;
         const unsigned leaf0 = (unsigned)(item0 - row * nb) * RR_BLOCK_LEAVES + threadIdx.x;
@@ -626,6 +713,7 @@ __global__ __launch_bounds__(RR_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4
     int wait_limit, int sleep_units, float *__restrict__ out) {
     __shared__ PipeLds lds;
     __shared__ uint4 parked[RR_SEGS * RR_THREADS];                        // one block, each thread its own eight leaves
+    __shared__ float per_block[RR_MAX_PIPE_BLOCKS];                       // only for a block that has to be finished alone
     const int G = (int)gridDim.x, g = (int)blockIdx.x;
     const int n = g < items ? (int)((items - g + G - 1) / G) : 0;        // this workgroup's items
     const unsigned nleaves = (unsigned)(V / Elem<XT>::EPL);
@@ -633,78 +721,7 @@ __global__ __launch_bounds__(RR_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4
     unsigned rowmax = RR_NOT_YET;
     for (int s = -3; s < n; ++s)
         pipe_step<XT>(x, V, nleaves, nb, nb2, g, G, s, n, P, Q, parked + threadIdx.x, rowmax, wsmax, wssum, sync_words, wait_limit,
-                      sleep_units, &lds, out);
-}
-
-// Recomputes the rows that logsoftmax_coop_kernel marked (normally none): one workgroup walks all blocks of its row
-// three times.  Same leaves, block trees and tree over blocks, hence the same bits.
-template <int XT>
-__global__ __launch_bounds__(RR_THREADS) void logsoftmax_redo_kernel(const void *__restrict__ x, int64_t V, int nb, int nb2,
-                                                                    const unsigned *__restrict__ sync_words,
-                                                                    float *__restrict__ out) {
-    __shared__ float lds[RR_SEGS * 4];
-    __shared__ float per_block[RR_MAX_COOP_BLOCKS];
-    const int row = blockIdx.x;
-    if (sync_words[(int64_t)row * RR_SYNC_WORDS + RR_W_GAVE_UP] == 0u) return;   // uniform over the workgroup
-    constexpr int EPL = Elem<XT>::EPL;
-    const int lane = threadIdx.x & 63;
-    const int64_t nleaves = V / EPL;
-    const char *rowp = reinterpret_cast<const char *>(x) + (int64_t)row * V * Elem<XT>::BYTES;
-    float *orow = out + (int64_t)row * V;
-
-    for (int b = 0; b < nb; ++b) {
-        float mx = -INFINITY;
-#pragma unroll
-        for (int seg = 0; seg < RR_SEGS; ++seg) {
-            const int64_t leaf = (int64_t)b * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
-            if (leaf < nleaves) {
-                float f[8];
-                Elem<XT>::load(rowp, leaf, f);
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) mx = fmaxf(mx, f[e]);
-            }
-        }
-        const float bm = block_max(mx, lds);
-        if (threadIdx.x == 0) per_block[b] = bm;
-    }
-    __syncthreads();
-    const float rowmax = wave_max_of_array(per_block, nb, lane);
-    __syncthreads();
-    for (int b = 0; b < nb; ++b) {
-        float L[RR_SEGS];
-#pragma unroll
-        for (int seg = 0; seg < RR_SEGS; ++seg) {
-            const int64_t leaf = (int64_t)b * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
-            float acc = 0.0f;
-            if (leaf < nleaves) {
-                float f[8];
-                Elem<XT>::load(rowp, leaf, f);
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) acc = acc + expf(f[e] - rowmax);
-            }
-            L[seg] = acc;
-        }
-        const float bs = block_tree_sum(L, lds);
-        if (threadIdx.x == 0) per_block[b] = bs;
-    }
-    __syncthreads();
-    const float S = wave_tree_of_array(per_block, nb, nb2, lane);
-    const float lg = logf(S);
-    for (int b = 0; b < nb; ++b) {
-#pragma unroll
-        for (int seg = 0; seg < RR_SEGS; ++seg) {
-            const int64_t leaf = (int64_t)b * RR_BLOCK_LEAVES + seg * RR_THREADS + threadIdx.x;
-            if (leaf < nleaves) {
-                float f[8], o[8];
-                Elem<XT>::load(rowp, leaf, f);
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) o[e] = (f[e] - rowmax) - lg;
-                float4 *dst = reinterpret_cast<float4 *>(orow + leaf * EPL);
-                dst[0] = make_float4(o[0], o[1], o[2], o[3]);
-                if (EPL == 8) dst[1] = make_float4(o[4], o[5], o[6], o[7]);
-            }
-        }
-    }
+                      sleep_units, &lds, per_block, out);
 }
 
 // Before every call: the slots of both hand-offs to "not yet", the rows' flags to zero.
@@ -807,8 +824,6 @@ static hipError_t run(const void *x, void *out, int op, int M, int64_t V, void *
                 hipLaunchKernelGGL((logsoftmax_coop_kernel<XT, 1>), dim3((unsigned)items), block, 0, s, xp, V, nb, nb2, w0, w1, words,
                                    g_wait_limit.load(), sleep_units, o + m0 * V);
             }
-            hipLaunchKernelGGL((logsoftmax_redo_kernel<XT>), dim3(mc), block, 0, s, xp, V, nb, nb2,
-                               (const unsigned *)words, o + m0 * V);
         } else {
             hipLaunchKernelGGL((row_block_kernel<XT, MODE_MAX>), grid, block, 0, s, xp, V, nb, (const float *)nullptr, w0);
             hipLaunchKernelGGL((row_block_kernel<XT, MODE_EXPSUM>), grid, block, 0, s, xp, V, nb, (const float *)w0, w1);

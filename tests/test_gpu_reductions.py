@@ -137,7 +137,7 @@ def test_logsoftmax_one_block_and_two_block_rows(V):
 
 def test_logsoftmax_bounded_wait_runs_out_same_bits():
     """Long rows: the workgroups of a row wait for each other a bounded number of polls.  With the bound forced to 0
-    from the host the waits run out, the rows are marked and the second kernel of the call recomputes them: the bits
+    from the host the waits run out and the workgroups finish their blocks alone, walking the row themselves: the bits
     must be those of the normal run (two implementations of the same arithmetic), and every kernel exits normally."""
     V = 151936
     x = syn.logits_f32(24, V, seed=5)
@@ -172,8 +172,8 @@ def test_logsoftmax_pipelined_launch_equals_row_by_row_and_survives_a_zero_wait(
     """Launches of two or more rounds of resident workgroups take the pipelined kernel (a workgroup walks several
     blocks, three of them in flight).  Its rows must have the bits of the same rows computed a few at a time (the
     one-block-per-workgroup kernel), must agree with the oracle, and with the wait bound forced to 0 from the host
-    (every hand-off gets one look, most rows are marked and redone) the call must still end normally with the same
-    bits."""
+    (every hand-off gets one look, most workgroups finish their blocks alone) the call must still end normally with
+    the same bits."""
     rng = np.random.Generator(np.random.PCG64(M + V))
     if fmt == "f32":
         x = syn.logits_f32(M, V, seed=M)
