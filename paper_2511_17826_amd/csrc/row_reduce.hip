@@ -9,7 +9,7 @@
 // row's bits cannot depend on the batch.  Log-softmax keeps the plain two-pass definition:
 // exact max first, then TreeSum(exp(x - max)).  Rows of several blocks are handled by one launch in which every
 // workgroup keeps its block in registers and the blocks of a row exchange their maxima and sums through memory
-// (bounded waits; a row whose wait runs out is redone by a second, normally idle, kernel), so a row is read once.
+// (bounded waits; a workgroup whose wait runs out finishes its block alone, from memory), so a row is read once.
 #include <atomic>
 
 #include "tbik_device.hpp"
