@@ -202,6 +202,32 @@ def test_logsoftmax_pipelined_launch_equals_row_by_row_and_survives_a_zero_wait(
     assert torch.equal(forced.view(torch.int32), full.view(torch.int32))
 
 
+def test_logsoftmax_two_streams_at_once_same_bits():
+    """Two pipelined launches on two streams compete for the compute units, so neither may have all its workgroups
+    resident: hand-offs can then run out and workgroups finish blocks alone.  Whatever the interleaving, both calls
+    must end and give the bits of the calls run one after the other."""
+    V = 151936
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    xs = [torch.randn((192, V), generator=g, device="cuda") * 3.0 for _ in range(2)]
+    need = int(tb.lib().tbik_row_reduce_workspace_bytes(192, V, tb.TBIK_LOGSOFTMAX))
+    want = [tb.tbik_row_reduce(x, tb.TBIK_LOGSOFTMAX) for x in xs]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in range(2)]
+    wss = [torch.empty(need, dtype=torch.uint8, device="cuda:0") for _ in range(2)]
+    outs = [torch.empty_like(w) for w in want]
+    for rep in range(3):
+        for i in range(2):
+            outs[i].fill_(float("nan"))
+        torch.cuda.synchronize()
+        for i in range(2):
+            with torch.cuda.stream(streams[i]):
+                tb.tbik_row_reduce(xs[i], tb.TBIK_LOGSOFTMAX, out=outs[i], workspace=wss[i])
+        torch.cuda.synchronize()
+        for i in range(2):
+            assert torch.equal(outs[i].view(torch.int32), want[i].view(torch.int32)), (rep, i)
+
+
 def test_logsoftmax_long_rows_repeatable_under_load():
     """The workgroups of a long row hand their maxima and sums to each other through memory, across chiplets: with
     all compute units busy (512 rows), repeated runs and runs on slices of the batch must keep giving the same bits."""
