@@ -112,6 +112,12 @@ __device__ __forceinline__ float block_max(float m, float *lds) {
     return r;
 }
 
+// 16 bytes written around the caches (an output that is written once and not read back soon).
+__device__ __forceinline__ void stream_store_16B(float4 *dst, float a, float b, float c, float d) {
+    typedef float nt_f32x4 __attribute__((ext_vector_type(4)));
+    __builtin_nontemporal_store(nt_f32x4{a, b, c, d}, reinterpret_cast<nt_f32x4 *>(dst));
+}
+
 // Pass over one (row, block): MODE_SUM -> block tree sum; MODE_MAX -> block max;
 // MODE_EXPSUM -> block tree sum of exp(x - rowmax), rowmax taken from the block maxima in wsmax.
 template <int XT, int MODE>
@@ -239,8 +245,8 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_one_block_kernel(const 
 #pragma unroll
             for (int e = 0; e < EPL; ++e) o[e] = (f[seg][e] - rowmax) - lg;
             float4 *dst = reinterpret_cast<float4 *>(orow + leaf * EPL);
-            dst[0] = make_float4(o[0], o[1], o[2], o[3]);
-            if (EPL == 8) dst[1] = make_float4(o[4], o[5], o[6], o[7]);
+            dst[0] = make_float4(o[0], o[1], o[2], o[3]);             // short rows: ordinary stores (a reader of the whole
+            if (EPL == 8) dst[1] = make_float4(o[4], o[5], o[6], o[7]);   // output may follow; streaming gained 4 % here)
         }
     }
 }
@@ -476,8 +482,9 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_coop_kernel(const void 
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) o[e] = (f[k][seg][e] - rowmax) - lg;
                 float4 *dst = reinterpret_cast<float4 *>(orow + leaf * EPL);
-                dst[0] = make_float4(o[0], o[1], o[2], o[3]);
-                if (EPL == 8) dst[1] = make_float4(o[4], o[5], o[6], o[7]);
+                // streaming stores, as in the pipelined kernel (64 x 151936 cold: 26.3 -> 21.2 us)
+                stream_store_16B(dst, o[0], o[1], o[2], o[3]);
+                if (EPL == 8) stream_store_16B(dst + 1, o[4], o[5], o[6], o[7]);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -641,8 +648,10 @@ __device__ __forceinline__ void pipe_step(const void *__restrict__ x, int64_t V,
             for (int e = 0; e < EPL; ++e) o[e] = (f[e] - rm) - lg;
             if (leaf < nleaves) {
                 float4 *dst = reinterpret_cast<float4 *>(orow + leaf * (unsigned)(EPL * 4));
-                dst[0] = make_float4(o[0], o[1], o[2], o[3]);
-                if (EPL == 8) dst[1] = make_float4(o[4], o[5], o[6], o[7]);
+                // Streaming stores: the output of a launch this size is written once and is larger than what the caches
+                // would keep for a reader (512 x 151936: 136 -> 121 us; the same hint on the loads gains nothing more).
+                stream_store_16B(dst, o[0], o[1], o[2], o[3]);
+                if (EPL == 8) stream_store_16B(dst + 1, o[4], o[5], o[6], o[7]);
             }
         }
     }
