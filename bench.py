@@ -445,6 +445,13 @@ def metric_shapes(tb, syn, torch, np, to_dev, X, W):
             tg = min(time_region(graph.replay, 5, torch) for _ in range(3)) / len(calls)
             res["logsoftmax_%dx151936_8V_basis" % M]["ms_cold_in_graph"] = round(tg, 4)
             res["logsoftmax_%dx151936_8V_basis" % M]["GBps_cold_in_graph"] = round(8.0 * M * V / (tg * 1e-3) / 1e9, 1)
+    # row sum and row maximum of the same rows: read-only, 4V bytes per row
+    red_out = torch.empty(512, dtype=torch.float32, device=dev)
+    for opname, op in (("rowsum", tb.TBIK_SUM), ("rowmax", tb.TBIK_MAX)):
+        t = best_ms(lambda: tb.tbik_row_reduce(lg, op, out=red_out, workspace=ws_rr), 10, torch)
+        res["%s_512x151936" % opname] = {"ms": round(t, 4), "GBps": round(4.0 * 512 * V / (t * 1e-3) / 1e9, 1),
+                                         "frac_hbm": round(4.0 * 512 * V / (t * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                                         "note": "311 MiB read once per call: more than the memory-side cache holds"}
     del lg, out
     Mc = Nc = 4096
     for P in (2, 4, 8):
