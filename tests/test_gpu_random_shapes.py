@@ -187,3 +187,43 @@ def test_gemm_swiglu_random_shapes_equal_two_gemms_then_the_activation():
         gate = gemm(X, W[:, :I], leaf, 1, out_dtype=X.dtype)
         up = gemm(X, W[:, I:], leaf, 1, out_dtype=X.dtype)
         assert torch.equal(act.view(torch.int16), tb.tbik_silu_mul(gate, up).view(torch.int16)), (case, M, I, K, leaf, fmt)
+
+
+def test_row_reductions_random_shapes_every_path_and_batch_slices():
+    """Random (M, V, format): rows of one block, of several blocks with few rows (one block per workgroup), of several
+    blocks with enough rows for the pipelined launch (two rounds of resident workgroups or more), and of more than 256
+    blocks (three launches).  Sum and max bit-exact against the oracle; log-softmax within its tolerance; and a row's
+    bits never depend on which rows it is launched with -- slices of the batch take other paths than the whole."""
+    rng = np.random.Generator(np.random.PCG64(77))
+    cases = []
+    for _ in range(4):
+        cases.append((int(rng.integers(1, 40)), 4 * int(rng.integers(1, 2048))))                  # one block (fp32: V <= 8192)
+        cases.append((int(rng.integers(1, 30)), 4 * int(rng.integers(2049, 60000))))              # a few rows of several blocks
+    cases.append((int(rng.integers(300, 500)), 4 * int(rng.integers(12000, 20000))))              # pipelined: >= 2048 (row, block) items
+    cases.append((int(rng.integers(600, 900)), 8 * int(rng.integers(6000, 9000))))
+    cases.append((3, 4 * (2048 * 257 + int(rng.integers(0, 2048)))))                              # more than 256 blocks per row
+    for idx, (M, V) in enumerate(cases):
+        fmt = ("f32", "bf16", "fp16")[idx % 3]
+        if fmt != "f32":
+            V = (V + 7) // 8 * 8
+        x32 = (rng.standard_normal((M, V)) * 3.0).astype(np.float32)
+        if fmt == "f32":
+            xd, leaf = gu.dev_f32(x32), orc.LEAF_F32
+        else:
+            bits = syn.to_storage(x32, fmt)
+            x32, leaf = syn.from_storage(bits, fmt), orc.LEAF_BF16
+            xd = gu.dev_bf16(bits) if fmt == "bf16" else gu.dev_f16(bits)
+        s = gu.host_f32(tb.tbik_row_reduce(xd, tb.TBIK_SUM))
+        assert np.array_equal(gu.u32(s), gu.u32(orc.row_sum(x32, leaf))), (M, V, fmt)
+        mx = gu.host_f32(tb.tbik_row_reduce(xd, tb.TBIK_MAX))
+        assert np.array_equal(gu.u32(mx), gu.u32(orc.row_max(x32))), (M, V, fmt)
+        full = tb.tbik_row_reduce(xd, tb.TBIK_LOGSOFTMAX)
+        rows = sorted(set([0, M // 2, M - 1]))
+        want = orc.row_logsoftmax(x32[rows], leaf)
+        got = gu.host_f32(full[rows])
+        assert np.max(np.abs(got - want) / np.maximum(1.0, np.abs(want))) <= 1e-5, (M, V, fmt)
+        for _ in range(3):
+            a = int(rng.integers(0, M))
+            b = int(rng.integers(a + 1, M + 1))
+            y = tb.tbik_row_reduce(xd[a:b].contiguous(), tb.TBIK_LOGSOFTMAX)
+            assert torch.equal(y.view(torch.int32), full[a:b].view(torch.int32)), (M, V, fmt, a, b)
