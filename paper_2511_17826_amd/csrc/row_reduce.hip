@@ -193,8 +193,8 @@ __global__ __launch_bounds__(RR_THREADS) void logsoftmax_write_kernel(const void
 #pragma unroll
             for (int e = 0; e < EPL; ++e) o[e] = (f[e] - rowmax) - lg;
             float4 *dst = reinterpret_cast<float4 *>(orow + leaf * EPL);
-            dst[0] = make_float4(o[0], o[1], o[2], o[3]);
-            if (EPL == 8) dst[1] = make_float4(o[4], o[5], o[6], o[7]);
+            stream_store_16B(dst, o[0], o[1], o[2], o[3]);              // rows this long: written once, around the caches
+            if (EPL == 8) stream_store_16B(dst + 1, o[4], o[5], o[6], o[7]);
         }
     }
 }
