@@ -124,6 +124,7 @@ __global__ __launch_bounds__(64 * RMS_ROWS_PER_BLOCK) void combine_residual_rmsn
     if (row >= M) return;                              // whole wavefront leaves together
     const int nchunks = H >> 3;
     const int64_t plane = (int64_t)M * H;
+    const bool stream = plane * P * 4 > ((int64_t)192 << 20);   // uniform: planes that no cache holds are read around the caches
     const float *pr = partials + (int64_t)row * H;
     const uint4 *rr = reinterpret_cast<const uint4 *>(res + (int64_t)row * H);
     const uint4 *wr = reinterpret_cast<const uint4 *>(w);
@@ -139,8 +140,16 @@ __global__ __launch_bounds__(64 * RMS_ROWS_PER_BLOCK) void combine_residual_rmsn
             float4 lo[P], hi[P];
 #pragma unroll
             for (int p = 0; p < P; ++p) {
-                lo[p] = *reinterpret_cast<const float4 *>(pr + (int64_t)p * plane + c * 8);
-                hi[p] = *reinterpret_cast<const float4 *>(pr + (int64_t)p * plane + c * 8 + 4);
+                if (stream) {
+                    typedef float nt_f32x4 __attribute__((ext_vector_type(4)));
+                    const nt_f32x4 a = __builtin_nontemporal_load(reinterpret_cast<const nt_f32x4 *>(pr + (int64_t)p * plane + c * 8));
+                    const nt_f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const nt_f32x4 *>(pr + (int64_t)p * plane + c * 8 + 4));
+                    lo[p] = make_float4(a[0], a[1], a[2], a[3]);
+                    hi[p] = make_float4(b[0], b[1], b[2], b[3]);
+                } else {
+                    lo[p] = *reinterpret_cast<const float4 *>(pr + (int64_t)p * plane + c * 8);
+                    hi[p] = *reinterpret_cast<const float4 *>(pr + (int64_t)p * plane + c * 8 + 4);
+                }
             }
             float y[8];
 #pragma unroll
@@ -184,23 +193,6 @@ __global__ __launch_bounds__(64 * RMS_ROWS_PER_BLOCK) void combine_residual_rmsn
     }
 }
 
-// hidden = bf16(y + residual), 8 elements per thread (the middle step of the unfused route below).
-template <bool F16>
-__global__ __launch_bounds__(256) void residual_add_kernel(const uint16_t *__restrict__ y, const uint16_t *res,
-                                                           uint16_t *hidden, int64_t nchunks) {
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < nchunks; c += stride) {
-        float a[8], b[8];
-        unpack8<F16>(reinterpret_cast<const uint4 *>(y)[c], a);
-        unpack8<F16>(reinterpret_cast<const uint4 *>(res)[c], b);
-        float h[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) h[e] = a[e] + b[e];
-        reinterpret_cast<uint4 *>(hidden)[c] =
-            make_uint4(pack_16x2<F16>(h[0], h[1]), pack_16x2<F16>(h[2], h[3]), pack_16x2<F16>(h[4], h[5]), pack_16x2<F16>(h[6], h[7]));
-    }
-}
-
 template <bool F16>
 static hipError_t rmsnorm_of(const uint16_t *x, const uint16_t *w, uint16_t *y, int M, int H, float eps, hipStream_t s) {
     if (M <= 0) return hipSuccess;
@@ -231,19 +223,6 @@ static hipError_t tail_of(const float *partials, int P, const uint16_t *res, con
     int n2 = 1;
     while (n2 < nchunks) n2 *= 2;
     const int nseg2 = n2 < 64 ? 1 : n2 / 64;
-    // With many partial tensors and a large batch the row-per-wavefront walk over P planes falls behind the plain
-    // combine kernel; then the three steps run one after the other (the normed buffer holds Y in between).  Same bits.
-    if (P > 4 && (int64_t)M * H * P > (int64_t)32 << 20) {
-        hipError_t e = launch_tree_combine(partials, P, normed, H, F16 ? TBIK_F16 : TBIK_BF16, M, H, s);
-        if (e != hipSuccess) return e;
-        const int64_t chunks = (int64_t)M * H / 8;
-        const int64_t blocks = (chunks + 255) / 256;
-        hipLaunchKernelGGL(residual_add_kernel<F16>, dim3((unsigned)(blocks < 65536 ? blocks : 65536)), dim3(256), 0, s, normed, res,
-                           hidden, chunks);
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        return rmsnorm_of<F16>(hidden, w, normed, M, H, eps, s);
-    }
     dim3 grid((M + RMS_ROWS_PER_BLOCK - 1) / RMS_ROWS_PER_BLOCK), block(64 * RMS_ROWS_PER_BLOCK);
     switch (P) {
         case 1: hipLaunchKernelGGL((combine_residual_rmsnorm_kernel<1, F16>), grid, block, 0, s, partials, res, w, hidden, normed, M, H, eps, nseg2); break;

@@ -281,7 +281,7 @@ def test_logsoftmax_512_rows_sampled():
 # ----------------------------------------------------------------------------- fused tail: combine + residual + RMSNorm
 
 @pytest.mark.parametrize("P,M,H", [(1, 5, 4096), (2, 33, 5120), (4, 64, 4096), (8, 7, 24), (16, 3, 1000), (8, 130, 8192),
-                                   (8, 1100, 4096)])          # the last one is large enough for the three-kernel route
+                                   (8, 1100, 4096), (8, 2100, 4096)])   # the last one: more than 192 MiB of partials, read with streaming loads
 def test_fused_tail_equals_the_three_steps_and_the_oracle(P, M, H):
     """tbik_combine_residual_rmsnorm against (a) tbik_tree_combine -> bf16 add -> tbik_rmsnorm on the GPU and (b) the
     oracle's step-by-step definition: bit for bit, also when the hidden state is updated in place."""
