@@ -36,6 +36,8 @@
  *   format only changes the exact widening and the one output rounding.
  *   tbik_oracle_gemm_f32*    the same GEMM on fp32 operands (third row of that table): a
  *                            leaf accumulates by one fused multiply-add per k.
+ *   tbik_oracle_gemm_mxfp8   the same GEMM on OCP MXFP8 operands: 8-bit E4M3 / E5M2 elements with one E8M0 scale
+ *                            per block of 32 consecutive k
  *   tbik_oracle_gemm_mxfp4   the same GEMM on OCP MXFP4 operands: 4-bit E2M1 elements with one E8M0 (power-of-two)
  *                            scale per block of 32 consecutive k; products stay exact in fp32.
  *   tbik_oracle_gemm_fp8*    the same GEMM on 8-bit floating-point operands (the paper's outlook: quantised
@@ -687,6 +689,57 @@ int tbik_oracle_gemm_mxfp4(const uint8_t *X, long ldx, const uint8_t *Xs, long l
                     for (long k = j * sl; k < (j + 1) * sl; ++k) {
                         const float w = tbik_oracle_fp4_to_f32((uint8_t)(Wt[n * ldw + k / 2] >> (4 * (k & 1)))) *
                                         tbik_oracle_e8m0_to_f32(Ws[n * ldws + k / 32]);
+                        float pk = xrow[k] * w;
+                        acc = acc + pk;
+                    }
+                    s[j] = acc;
+                }
+                float y = combine_superleaves(s, ns, evaluator, P, part);
+                if (Y32) Y32[m * ldy + n] = y;
+                if (Ybf) Ybf[m * ldy + n] = f32_to_bf16(y);
+                if (partials && evaluator == EVAL_SHARDED)
+                    for (int p = 0; p < P; ++p) partials[((size_t)p * M + m) * N + n] = part[p];
+            }
+        }
+        free(s);
+        free(xrow);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ 8-bit floating point with block scales (OCP MXFP8) */
+
+/*
+ * Y = X W on MXFP8 operands (quantised types of the paper's outlook; the order contract as for every other format):
+ * element k of a row is an 8-bit float (E4M3 or E5M2, fmt8 as above) times the E8M0 scale of its block of 32
+ * consecutive k,
+ *   x[m,k] = fp8(X[m,k]) * 2^(Xs[m, k/32] - 127),     w[k,n] = fp8(Wt[n,k]) * 2^(Ws[n, k/32] - 127)
+ * with the weight stored TRANSPOSED (one row per output channel), as the scales run along k.  A product has at most
+ * 8 significant bits and a power-of-two scale: exact in fp32 while it stays in range.
+ *   s_j = ((p_a + p_{a+1}) + ...) over superleaf j in ascending k from +0;  y = T(s_0 .. s_{n_s-1}).
+ * X [M, ldx] bytes (ldx >= K), Xs [M, ldxs] (>= K/32), Wt [N, ldw], Ws [N, ldws].  K a multiple of 32.
+ */
+int tbik_oracle_gemm_mxfp8(const uint8_t *X, long ldx, const uint8_t *Xs, long ldxs,
+                           const uint8_t *Wt, long ldw, const uint8_t *Ws, long ldws,
+                           float *Y32, uint16_t *Ybf, long ldy, int M, int N, int K, int leaf, int k_first,
+                           int evaluator, int P, int fmt8, float *partials) {
+    long ns = superleaf_count(K, leaf, k_first, P);
+    if (ns < 0 || K % 32 != 0) return -1;
+    const long sl = (long)leaf * k_first;
+#pragma omp parallel
+    {
+        float *s = (float *)malloc((size_t)ns * sizeof(float));
+        float *xrow = (float *)malloc((size_t)K * sizeof(float));
+        float part[64];
+#pragma omp for schedule(dynamic, 1)
+        for (long m = 0; m < M; ++m) {
+            for (long k = 0; k < K; ++k)
+                xrow[k] = tbik_oracle_fp8_to_f32(X[m * ldx + k], fmt8) * tbik_oracle_e8m0_to_f32(Xs[m * ldxs + k / 32]);
+            for (long n = 0; n < N; ++n) {
+                for (long j = 0; j < ns; ++j) {
+                    float acc = 0.0f;
+                    for (long k = j * sl; k < (j + 1) * sl; ++k) {
+                        const float w = tbik_oracle_fp8_to_f32(Wt[n * ldw + k], fmt8) * tbik_oracle_e8m0_to_f32(Ws[n * ldws + k / 32]);
                         float pk = xrow[k] * w;
                         acc = acc + pk;
                     }

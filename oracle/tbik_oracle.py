@@ -101,6 +101,9 @@ def lib():
         L.tbik_oracle_gemm_mxfp4.restype = C.c_int
         L.tbik_oracle_gemm_mxfp4.argtypes = [u8p, C.c_long, u8p, C.c_long, u8p, C.c_long, u8p, C.c_long, f32p, u16p, C.c_long,
                                              C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f32p]
+        L.tbik_oracle_gemm_mxfp8.restype = C.c_int
+        L.tbik_oracle_gemm_mxfp8.argtypes = [u8p, C.c_long, u8p, C.c_long, u8p, C.c_long, u8p, C.c_long, f32p, u16p, C.c_long,
+                                             C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f32p]
         L.tbik_oracle_tree_combine.restype = C.c_int
         L.tbik_oracle_tree_combine.argtypes = [f32p, C.c_int, C.c_long, f32p, u16p, C.c_int]
         L.tbik_oracle_treesum.restype = C.c_float
@@ -401,6 +404,33 @@ def gemm_mxfp4(X, Xs, Wt, Ws, leaf: int, k_first: int = 1, evaluator: int = EVAL
     rc = lib().tbik_oracle_gemm_mxfp4(xp, K2, xsp, K // 32, wp, K2, wsp, K // 32, Y32.ctypes.data_as(C.POINTER(C.c_float)),
                                       Ybf.ctypes.data_as(C.POINTER(C.c_uint16)), N, M, N, K, leaf, k_first, evaluator, P,
                                       parts.ctypes.data_as(C.POINTER(C.c_float)) if want_partials else None)
+    if rc != 0:
+        raise ValueError("oracle gemm: illegal tree parameters (K, leaf, k_first, P)")
+    return (Y32, Ybf, parts) if want_partials else (Y32, Ybf)
+
+
+def mxfp8_dequant(bits, scales, fmt: str = "e4m3") -> np.ndarray:
+    """[R, K] 8-bit float patterns and [R, K/32] E8M0 scales -> fp32 [R, K] (exact while in range)."""
+    return fp8_to_f32(np.asarray(bits, dtype=np.uint8), fmt) * np.repeat(e8m0_to_f32(scales), 32, axis=1)
+
+
+def gemm_mxfp8(X, Xs, Wt, Ws, leaf: int, k_first: int = 1, evaluator: int = EVAL_RECURSIVE, P: int = 1,
+               want_partials: bool = False, fmt: str = "e4m3"):
+    """Y = X W in the tree order on MXFP8 operands: X [M, K] 8-bit patterns with scales Xs [M, K/32]; the weight
+    transposed, Wt [N, K] with Ws [N, K/32].  Returns (Y fp32 [M,N], Y bf16 patterns[, partials [P,M,N]])."""
+    X, xp = _u8(X)
+    Xs, xsp = _u8(Xs)
+    Wt, wp = _u8(Wt)
+    Ws, wsp = _u8(Ws)
+    M, K = X.shape
+    N = Wt.shape[0]
+    assert Wt.shape[1] == K and Xs.shape == (M, K // 32) and Ws.shape == (N, K // 32)
+    Y32 = np.empty((M, N), dtype=np.float32)
+    Ybf = np.empty((M, N), dtype=np.uint16)
+    parts = np.zeros((P, M, N), dtype=np.float32) if want_partials else None
+    rc = lib().tbik_oracle_gemm_mxfp8(xp, K, xsp, K // 32, wp, K, wsp, K // 32, Y32.ctypes.data_as(C.POINTER(C.c_float)),
+                                      Ybf.ctypes.data_as(C.POINTER(C.c_uint16)), N, M, N, K, leaf, k_first, evaluator, P,
+                                      FORMATS8[fmt], parts.ctypes.data_as(C.POINTER(C.c_float)) if want_partials else None)
     if rc != 0:
         raise ValueError("oracle gemm: illegal tree parameters (K, leaf, k_first, P)")
     return (Y32, Ybf, parts) if want_partials else (Y32, Ybf)

@@ -192,6 +192,38 @@ def gemm_random_mxfp4(seed: int, M: int, K: int, N: int, scale_spread: int = 0):
     return Xp, Xs, Wp, Ws
 
 
+def mxfp8_quantize(a: np.ndarray, fmt: str = "e4m3"):
+    """fp32 [R, K] (K a multiple of 32) -> (8-bit patterns uint8 [R, K], E8M0 scales uint8 [R, K/32]).  Per block of 32
+    the scale is the power of two that brings the block's largest magnitude into (2^(emax-1), 2^emax] with emax the
+    largest exponent of the element format (8 for E4M3, 15 for E5M2; an all-zero block gets 2^0); elements are rounded
+    to nearest even by the library's conversion.  An input recipe: nothing of the method's arithmetic."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    R, K = a.shape
+    assert K % 32 == 0
+    emax = 8 if fmt == "e4m3" else 15
+    blocks = a.reshape(R, K // 32, 32)
+    amax = np.abs(blocks).max(axis=2)
+    e = np.where(amax > 0, np.ceil(np.log2(np.where(amax > 0, amax, 1.0))), float(emax)).astype(np.int32) - emax
+    scales = np.clip(e + 127, 1, 254).astype(np.uint8)
+    scaled = blocks / np.exp2(scales.astype(np.float32) - 127)[:, :, None]
+    return f32_to_fp8_bits(scaled.reshape(R, K), fmt), scales
+
+
+def gemm_random_mxfp8(seed: int, M: int, K: int, N: int, fmt: str = "e4m3", scale_spread: int = 0):
+    """MXFP8 operands from X ~ N(0,1), W ~ N(0,0.02) (the weight transposed, [N, K]): returns (X patterns, X scales,
+    Wt patterns, W scales).  With `scale_spread` every block's scale is moved by a random number of binades in
+    [-scale_spread, scale_spread] (the elements stay as quantised), which spreads the magnitudes of the products."""
+    rng = _rng(seed)
+    X = rng.standard_normal(size=(M, K), dtype=np.float32)
+    Wt = rng.standard_normal(size=(N, K), dtype=np.float32) * np.float32(0.02)
+    Xq, Xs = mxfp8_quantize(X, fmt)
+    Wq, Ws = mxfp8_quantize(Wt, fmt)
+    if scale_spread:
+        Xs = (Xs.astype(np.int32) + rng.integers(-scale_spread, scale_spread + 1, size=Xs.shape)).astype(np.uint8)
+        Ws = (Ws.astype(np.int32) + rng.integers(-scale_spread, scale_spread + 1, size=Ws.shape)).astype(np.uint8)
+    return Xq, Xs, Wq, Ws
+
+
 def gemm_random_f32(seed: int, M: int, K: int, N: int, x_std: float = 1.0, w_std: float = 0.02, exp_spread: int = 0):
     """fp32 operands X [M,K] ~ N(0, x_std), W [K,N] ~ N(0, w_std) with full 24-bit significands; with ``exp_spread`` every
     element is scaled by a random power of two in [-exp_spread, exp_spread] (cancellation and absorption cases)."""
