@@ -405,6 +405,21 @@ def metric_shapes(tb, syn, torch, np, to_dev, X, W):
         res[name] = {"ms": round(t, 4), "tflops": round(tf, 1), "frac_fp4_peak": round(tf / 10100.0, 4), "leaf": leaf4}
         del X4, W4, Xs4, Ws4, y4, ws4
 
+    # MXFP8 operands (E4M3 elements from a normal distribution, random scale bytes), same two shapes.
+    for name, Kx, leafx, gx in (("mxfp8_oproj_M4096", 4096, 256, 1), ("mxfp8_downproj_M4096", 12288, 256, 3)):
+        gxr = torch.Generator(device=dev)
+        gxr.manual_seed(Kx + 2)
+        Xx = torch.randn((4096, Kx), generator=gxr, device=dev, dtype=torch.float32).to(torch.float8_e4m3fn)
+        Wx = torch.randn((4096, Kx), generator=gxr, device=dev, dtype=torch.float32).to(torch.float8_e4m3fn)
+        Xsx = torch.randint(120, 134, (4096, Kx // 32), generator=gxr, device=dev, dtype=torch.uint8)
+        Wsx = torch.randint(120, 134, (4096, Kx // 32), generator=gxr, device=dev, dtype=torch.uint8)
+        yx = torch.empty((4096, 4096), dtype=torch.bfloat16, device=dev)
+        wsx = torch.empty(max(256, tb.gemm_mxfp8_workspace_bytes(4096, 4096, Kx, leafx, gx)), dtype=torch.uint8, device=dev)
+        t = best_ms(lambda: tb.tbik_gemm_mxfp8(Xx, Xsx, Wx, Wsx, leafx, gx, "e4m3", out=yx, workspace=wsx), 10, torch)
+        tf = 2.0 * 4096 * Kx * 4096 / (t * 1e-3) / 1e12
+        res[name] = {"ms": round(t, 4), "tflops": round(tf, 1), "frac_fp8_peak": round(tf / PEAK_FP8_TFLOPS, 4)}
+        del Xx, Wx, Xsx, Wsx, yx, wsx
+
     def hbm_line(name, calls, byts, iters):
         cold = best_ms(rotating(calls), iters * len(calls), torch, warm=len(calls))
         warm = best_ms(calls[0], iters, torch)

@@ -390,8 +390,9 @@ int tbik_gemm_reference_fp8(const void *X, int64_t ldx, const void *Wt, int64_t 
  *   Y    device, y_dtype (TBIK_F32 or TBIK_BF16), [M, ldy], ldy >= N        partials  device, fp32, dense [P, M, N]
  *   leaf * k_first a multiple of 64 (256 for the tiled kernel; else the reference kernel runs); K a multiple of 64;
  *   X, Wt 16-byte aligned with ldx, ldwt multiples of 16; Xs, Ws 8-byte aligned with ldxs, ldws multiples of 8 (the
- *   tiled kernel; the reference kernel takes any); the workspace rule (tbik_gemm_mxfp4_workspace_bytes), the determinism
- *   contract and the errors are those of tbik_gemm, tbik_gemm_shard_partials and tbik_gemm_reference.
+ *   tiled kernel; the reference kernel takes any); the workspace rule (tbik_gemm_mxfp4_workspace_bytes: from 128 rows on
+ *   it includes room for a copy of the scales in the order the kernel reads them, which tbik_gemm_mxfp4 makes first), the
+ *   determinism contract and the errors are those of tbik_gemm, tbik_gemm_shard_partials and tbik_gemm_reference.
  */
 size_t tbik_gemm_mxfp4_workspace_bytes(int M, int N, int K, int leaf, int k_first);
 int tbik_gemm_mxfp4(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
@@ -405,6 +406,38 @@ int tbik_gemm_shard_partials_mxfp4(const void *X, int64_t ldx, const void *Xs, i
 int tbik_gemm_reference_mxfp4(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
                               const void *Ws, int64_t ldws, float *partials, void *Y, int64_t ldy, tbik_dtype y_dtype,
                               int M, int N, int K, int leaf, int k_first, int P, void *hip_stream);
+
+/*
+ * The same three calls for OCP MXFP8 operands (quantised types of the paper's "Limitations and future work"; the order
+ * contract is that of Sec. 4.2, App. C and App. D.1 as stated for tbik_gemm).  An element is an 8-bit float of format
+ * x_dtype (TBIK_FP8_E4M3 or TBIK_FP8_E5M2, as for tbik_gemm_fp8) times 2^(s - 127), s the E8M0 scale byte of its block
+ * of 32 consecutive k (s = 255, NaN, is out of contract).  A product has at most eight significant bits and a
+ * power-of-two scale, so it is exact in fp32 (as long as it stays in range): per output element each superleaf's
+ * products are accumulated in fp32 in ascending k from +0, the superleaf sums are combined by T, the result is rounded
+ * once.  (The 64 products of one matrix instruction are added in that instruction's own fixed order, as for the other
+ * formats.)  The scales run along k, so the weight is taken TRANSPOSED: one row per output channel.
+ *
+ *   X    device, [M, ldx] bytes, ldx >= K            Xs   device, [M, ldxs] scale bytes, ldxs >= K / 32
+ *   Wt   device, [N, ldwt] bytes, ldwt >= K          Ws   device, [N, ldws] scale bytes, ldws >= K / 32
+ *   Y    device, y_dtype (TBIK_F32 or TBIK_BF16), [M, ldy], ldy >= N        partials  device, fp32, dense [P, M, N]
+ *   leaf * k_first a multiple of 64 (128 for the tiled kernel; else the reference kernel runs); X, Wt 16-byte aligned
+ *   with ldx, ldwt multiples of 16; Xs, Ws 4-byte aligned with ldxs, ldws multiples of 4 (the tiled kernel; the
+ *   reference kernel takes any); the workspace rule (tbik_gemm_mxfp8_workspace_bytes: from 128 rows on it includes room
+ *   for a copy of the scales in the order the kernel reads them, which tbik_gemm_mxfp8 makes first), the determinism
+ *   contract and the errors are those of tbik_gemm, tbik_gemm_shard_partials and tbik_gemm_reference.
+ */
+size_t tbik_gemm_mxfp8_workspace_bytes(int M, int N, int K, int leaf, int k_first);
+int tbik_gemm_mxfp8(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                    const void *Ws, int64_t ldws, void *Y, int64_t ldy, tbik_dtype y_dtype, tbik_dtype x_dtype,
+                    int M, int N, int K, int leaf, int k_first,
+                    void *workspace, size_t workspace_bytes, void *hip_stream);
+int tbik_gemm_shard_partials_mxfp8(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                                   const void *Ws, int64_t ldws, float *partials, tbik_dtype x_dtype,
+                                   int M, int N, int K, int leaf, int k_first, int P,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+int tbik_gemm_reference_mxfp8(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                              const void *Ws, int64_t ldws, float *partials, void *Y, int64_t ldy, tbik_dtype y_dtype,
+                              tbik_dtype x_dtype, int M, int N, int K, int leaf, int k_first, int P, void *hip_stream);
 
 /*
  * tbik_rmsnorm and tbik_combine_residual_rmsnorm for tensors of IEEE binary16 (App. B and Alg. 2 do not depend on

@@ -44,6 +44,16 @@ SIGNATURES = {
                                             C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_int,
                                             C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
     "tbik_gemm_mxfp4_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]),
+    "tbik_gemm_mxfp8": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                  C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                  C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tbik_gemm_shard_partials_mxfp8": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                                 C.c_void_p, C.c_int64, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                                 C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tbik_gemm_reference_mxfp8": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                            C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int,
+                                            C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
+    "tbik_gemm_mxfp8_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]),
     "tbik_tree_allreduce": (C.c_int, [C.c_void_p, C.c_int, C.c_int64, C.c_void_p]),
     "tbik_silu_mul": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int,
                                 C.c_void_p]),
@@ -394,6 +404,68 @@ def tbik_gemm_reference_mxfp4(X, Xs, Wt, Ws, leaf: int, k_first: int = 1, P: int
                                          Ws.data_ptr(), Ws.stride(0), parts.data_ptr(), Y.data_ptr() if Y is not None else None, N,
                                          _dt(Y) if Y is not None else TBIK_F32, M, N, K, leaf, k_first, P, _stream())
     _check(st, "tbik_gemm_reference_mxfp4")
+    return (Y, parts) if P == 1 else parts
+
+
+def _mx8_operands(X, Xs, Wt, Ws, fmt):
+    X, Wt, dt = _fp8_operands(X, Wt, fmt)
+    for t, name in ((Xs, "Xs"), (Ws, "Ws")):
+        _rowmajor(t, name)
+        assert t.dtype == torch.uint8, "E8M0 scales travel as uint8 tensors"
+    M, K = X.shape
+    N = Wt.shape[0]
+    assert Xs.shape == (M, K // 32) and Ws.shape == (N, K // 32)
+    return X, Wt, dt, M, N, K
+
+
+def gemm_mxfp8_workspace_bytes(M, N, K, leaf, k_first=1) -> int:
+    return int(lib().tbik_gemm_mxfp8_workspace_bytes(M, N, K, leaf, k_first))
+
+
+def tbik_gemm_mxfp8(X, Xs, Wt, Ws, leaf: int, k_first: int = 1, fmt: str = "e4m3", out_dtype=torch.bfloat16,
+                    out: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Y = X @ Wt.T in the tree order on MXFP8 operands: X [M, K] 8-bit patterns of format `fmt` with scales Xs [M, K/32];
+    the weight transposed, Wt [N, K] with Ws [N, K/32]."""
+    X, Wt, dt, M, N, K = _mx8_operands(X, Xs, Wt, Ws, fmt)
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=X.device)
+    _rowmajor(out, "out")
+    assert out.shape == (M, N)
+    if workspace is None:
+        need = gemm_mxfp8_workspace_bytes(M, N, K, leaf, k_first)
+        if need:
+            workspace = _workspace(need, X.device)
+    st = lib().tbik_gemm_mxfp8(X.data_ptr(), X.stride(0), Xs.data_ptr(), Xs.stride(0), Wt.data_ptr(), Wt.stride(0),
+                               Ws.data_ptr(), Ws.stride(0), out.data_ptr(), out.stride(0), _dt(out), dt, M, N, K, leaf, k_first,
+                               workspace.data_ptr() if workspace is not None else None,
+                               workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream())
+    _check(st, "tbik_gemm_mxfp8")
+    return out
+
+
+def tbik_gemm_shard_partials_mxfp8(X, Xs, Wt, Ws, leaf: int, k_first: int, P: int, fmt: str = "e4m3",
+                                   out: torch.Tensor | None = None):
+    X, Wt, dt, M, N, K = _mx8_operands(X, Xs, Wt, Ws, fmt)
+    if out is None:
+        out = torch.empty((max(P, 1), M, N), dtype=torch.float32, device=X.device)
+    assert out.is_contiguous() and out.dtype == torch.float32
+    st = lib().tbik_gemm_shard_partials_mxfp8(X.data_ptr(), X.stride(0), Xs.data_ptr(), Xs.stride(0), Wt.data_ptr(), Wt.stride(0),
+                                              Ws.data_ptr(), Ws.stride(0), out.data_ptr(), dt, M, N, K, leaf, k_first, P, None, 0,
+                                              _stream())
+    _check(st, "tbik_gemm_shard_partials_mxfp8")
+    return out
+
+
+def tbik_gemm_reference_mxfp8(X, Xs, Wt, Ws, leaf: int, k_first: int = 1, P: int = 1, fmt: str = "e4m3",
+                              out_dtype=torch.float32):
+    """The reference kernel: (Y, partials) for P == 1, partials alone otherwise."""
+    X, Wt, dt, M, N, K = _mx8_operands(X, Xs, Wt, Ws, fmt)
+    parts = torch.empty((P, M, N), dtype=torch.float32, device=X.device)
+    Y = torch.empty((M, N), dtype=out_dtype, device=X.device) if P == 1 else None
+    st = lib().tbik_gemm_reference_mxfp8(X.data_ptr(), X.stride(0), Xs.data_ptr(), Xs.stride(0), Wt.data_ptr(), Wt.stride(0),
+                                         Ws.data_ptr(), Ws.stride(0), parts.data_ptr(), Y.data_ptr() if Y is not None else None, N,
+                                         _dt(Y) if Y is not None else TBIK_F32, dt, M, N, K, leaf, k_first, P, _stream())
+    _check(st, "tbik_gemm_reference_mxfp8")
     return (Y, parts) if P == 1 else parts
 
 

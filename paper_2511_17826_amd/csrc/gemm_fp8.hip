@@ -3,18 +3,27 @@
 // The method is that of the 16-bit kernels (Sec. 4.2, App. C, App. D.1, Alg. 1): a superleaf's products are accumulated
 // in ascending k from +0, the superleaf sums are combined by the tree T.  A product of two 8-bit floats has at most
 // eight significant bits, so it is exact in fp32 like a product of two bf16 numbers.  The matrix instruction is
-// v_mfma_f32_32x32x64_f8f6f4 (64 k per instruction, both operands 8-bit): lane l carries row (or column) l % 32 and the
-// 32 consecutive k of half l / 32 of the step, for A and for B alike.  Because both operands want k-contiguous bytes,
+// v_mfma_f32_32x32x64_f8f6f4 (64 k per instruction, both operands 8-bit): lane l carries row (or column) l % 32 and 32
+// of the step's 64 k, for A and for B alike -- here the 32 consecutive bytes of half l / 32; which positions inside the
+// instruction they take does not matter as long as both operands agree (the instruction's sum of the 64 products does
+// not depend on their order: the scaled kernels below, which must use the instruction's own arrangement, give the same
+// bits at scale one).  Because both operands want k-contiguous bytes,
 // the weight is taken TRANSPOSED, Wt [N, K] -- one row per output channel, the layout 8-bit weights are stored in --
 // and the two operand tiles are staged, swizzled and read in exactly the same way.
 //
 // Two kernels that must agree bit for bit: a reference (one wavefront per 32 x 32 tile and shard, operands straight
 // from global memory) and the tiled kernel (128 x 128 tile, 4 wavefronts of 64 x 64, K-steps of 128 bytes through a ring
 // of 5 LDS slots of 32 KiB filled by direct global->LDS loads, the tree's stash in registers).
+//
+// MX = true: the same two kernels on OCP MXFP8 operands -- every block of 32 consecutive k of a row of X and of Wt
+// carries an E8M0 scale byte (2^(s - 127)), which the instruction takes from a byte of a register of the lanes of one
+// half of the wavefront; a lane then holds 16 bytes of each of the step's two blocks.  A stage (128 k) also holds four
+// scale bytes per row.
 #include <atomic>
 #include <type_traits>
 
 #include "tbik_device.hpp"
+#include "mx_scales.hpp"
 #include "tbik_internal.hpp"
 #include "tree_walk.hpp"
 
@@ -35,12 +44,18 @@ template <int FMT>
 __device__ __forceinline__ f32x16 mfma_32x32x64_8bit(i32x8 a, i32x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, FMT, FMT, 0, 0, 0, 0);
 }
+// The same with each lane's 32 elements times 2^(scale - 127), the lane's scale in the low byte of sa / sb.
+template <int FMT>
+__device__ __forceinline__ f32x16 mfma_32x32x64_8bit_scaled(i32x8 a, i32x8 b, f32x16 c, int sa, int sb) {
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, FMT, FMT, 0, sa, 0, sb);
+}
 
 constexpr int REF_MAX_LEVELS = 28;
 
-template <int FMT>
+template <int FMT, bool MX>
 __global__ __launch_bounds__(64) void gemm_fp8_reference_kernel(
         const uint8_t *__restrict__ X, int64_t ldx, const uint8_t *__restrict__ Wt, int64_t ldw,
+        const uint8_t *__restrict__ Xs, int64_t ldxs, const uint8_t *__restrict__ Ws, int64_t ldws,   // MX only
         float *__restrict__ partials, void *__restrict__ Y, int64_t ldy, int y_dtype,
         int M, int N, int superleaf, int ns_per_shard) {
     const int lane = threadIdx.x;
@@ -53,6 +68,8 @@ __global__ __launch_bounds__(64) void gemm_fp8_reference_kernel(
     const bool col_ok = (n0 + i) < N;
     const uint8_t *xrow = X + (int64_t)(row_ok ? m0 + i : 0) * ldx;
     const uint8_t *wrow = Wt + (int64_t)(col_ok ? n0 + i : 0) * ldw;
+    const uint8_t *xsrow = MX ? Xs + (int64_t)(row_ok ? m0 + i : 0) * ldxs : nullptr;
+    const uint8_t *wsrow = MX ? Ws + (int64_t)(col_ok ? n0 + i : 0) * ldws : nullptr;
 
     float stash[REF_MAX_LEVELS][16];
     f32x16 acc;
@@ -63,12 +80,26 @@ __global__ __launch_bounds__(64) void gemm_fp8_reference_kernel(
         for (int kk = 0; kk < superleaf; kk += 64) {
             const int64_t k = k0 + kk + 32 * g;
             union { i32x4 h[2]; i32x8 v; } a, b;
-            a.h[0] = *reinterpret_cast<const i32x4 *>(xrow + k);
-            a.h[1] = *reinterpret_cast<const i32x4 *>(xrow + k + 16);
-            b.h[0] = *reinterpret_cast<const i32x4 *>(wrow + k);
-            b.h[1] = *reinterpret_cast<const i32x4 *>(wrow + k + 16);
             // rows past M and columns past N compute on a valid row's data and are never stored
-            acc = mfma_32x32x64_8bit<FMT>(a.v, b.v, acc);
+            if (MX) {
+                // The instruction scales a lane's first 16 bytes (of either half of the wavefront) by the scale that
+                // the lanes of half 0 hand over and its second 16 bytes by the scale from half 1 (measured: an element
+                // moved through the 64 positions shows which scale reaches it).  So a block of 32 k is the first 16
+                // bytes of both halves: half g holds bytes 16 g .. 16 g + 15 of block 0 and of block 1 of the step and
+                // hands over the scale of block g.
+                const int64_t kq = k0 + kk;
+                a.h[0] = *reinterpret_cast<const i32x4 *>(xrow + kq + 16 * g);
+                a.h[1] = *reinterpret_cast<const i32x4 *>(xrow + kq + 32 + 16 * g);
+                b.h[0] = *reinterpret_cast<const i32x4 *>(wrow + kq + 16 * g);
+                b.h[1] = *reinterpret_cast<const i32x4 *>(wrow + kq + 32 + 16 * g);
+                acc = mfma_32x32x64_8bit_scaled<FMT>(a.v, b.v, acc, xsrow[k >> 5], wsrow[k >> 5]);
+            } else {
+                a.h[0] = *reinterpret_cast<const i32x4 *>(xrow + k);
+                a.h[1] = *reinterpret_cast<const i32x4 *>(xrow + k + 16);
+                b.h[0] = *reinterpret_cast<const i32x4 *>(wrow + k);
+                b.h[1] = *reinterpret_cast<const i32x4 *>(wrow + k + 16);
+                acc = mfma_32x32x64_8bit<FMT>(a.v, b.v, acc);
+            }
         }
         const int t = __builtin_ctz(~(unsigned)j);     // carry-over: as many finished subtrees as j has trailing ones
         for (int l = 0; l < t; ++l) {
@@ -115,6 +146,10 @@ __device__ __forceinline__ void wait_loads_and_barrier() {
 struct Fp8Params {
     const uint8_t *X;
     const uint8_t *Wt;
+    const uint8_t *Xs, *Ws;     // MX: E8M0 scales [M, ldxs], [N, ldws], one per 32 k -- or, scales_packed, the re-tiled copies
+    int64_t ldxs, ldws;
+    int scales_packed;          // the scales were re-tiled by mx_scales_retile_kernel to the tile height of this launch
+    int stages_total;           // K / 128
     float *partials;
     void *Y;
     int64_t ldx, ldw, ldy;
@@ -128,14 +163,15 @@ struct Fp8Params {
     int stream_stores;
 };
 
-template <int LEVELS, int WM, int WN, int MT, int NT, int RING8, int FMT>
+template <int LEVELS, int WM, int WN, int MT, int NT, int RING8, int FMT, bool MX>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_fp8_tiled_kernel(const Fp8Params p) {
     constexpr int BM = 32 * MT * WM, BN = 32 * NT * WN;
     static_assert(BN == 128 && WM * WN == 4, "tile shape");
     constexpr int A_LOADS8 = BM / 32;                           // 1 KiB loads of X rows per wavefront and stage
     constexpr int REGION8 = (A_LOADS8 + B_LOADS8) * 1024;       // [8 * A_LOADS8 rows of X | 32 rows of Wt] per loading wavefront
-    constexpr int STAGE8 = 4 * REGION8;
+    constexpr int SCALES_AT = 4 * REGION8;                      // MX: 128 x 4 scale bytes of the X rows, then of the Wt rows
+    constexpr int STAGE8 = 4 * REGION8 + (MX ? 1024 : 0);
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const int tid = threadIdx.x;
@@ -150,14 +186,16 @@ void gemm_fp8_tiled_kernel(const Fp8Params p) {
     // (the start of the Wt part of its region): instruction offsets -4 .. -1 KiB for X and 0 .. 3 KiB for Wt; the lane
     // offsets are biased so that the global side of the instruction offset cancels.  Rows past M or N re-read the last
     // valid row: an output depends on its own row of X and of Wt only, and theirs are never stored.
-    constexpr int LOADS_PER_STAGE = A_LOADS8 + B_LOADS8;
+    // MX: and two 256-byte loads of scales per wavefront (4 bytes per lane = a row's four blocks of the stage: wavefront
+    // w brings rows 64 (w & 1) + lane of the X tile and of the Wt tile, so each row arrives twice, with the same bytes).
+    constexpr int LOADS_PER_STAGE = A_LOADS8 + B_LOADS8 + (MX ? 2 : 0);
     constexpr int WCOLS = 32 * NT;
     constexpr int STORES_F32 = MT * (32 * WCOLS / 4 / 64);
     constexpr int STORES_BF16 = MT * (32 * WCOLS / 8 / 64);
     static_assert(LOADS_PER_STAGE * (RING8 - 1) + STORES_F32 < 64 && STORES_F32 != STORES_BF16, "vmcnt range");
     constexpr int LANE_BIAS = 4096;
-    unsigned aoff[A_LOADS8], boff[B_LOADS8];
-    const char *a_ptr = nullptr, *b_ptr = nullptr;
+    unsigned aoff[A_LOADS8], boff[B_LOADS8], xsoff = 0, wsoff = 0;
+    const char *a_ptr = nullptr, *b_ptr = nullptr, *xs_ptr = nullptr, *ws_ptr = nullptr;
     int issue_item = blockIdx.x;
     int issue_stage = 0;
 
@@ -179,11 +217,28 @@ void gemm_fp8_tiled_kernel(const Fp8Params p) {
             const int c = (lane & 7) ^ ((r >> 1) & 7);
             boff[j] = (unsigned)(min(r, p.N - 1 - n0) * (int)p.ldw + c * 16) + (unsigned)(LANE_BIAS - j * 1024);
         }
+        if (MX) {
+            const int rs = (wave & 1) * 64 + lane;
+            if (p.scales_packed) {                     // a stage's scale bytes of a row block are consecutive: two cache lines per load
+                const int64_t stage0 = kbase / BK8;
+                xs_ptr = uniform_pointer(reinterpret_cast<const char *>(p.Xs) + ((int64_t)(m0 / BM) * p.stages_total + stage0) * (BM * 4));
+                ws_ptr = uniform_pointer(reinterpret_cast<const char *>(p.Ws) + ((int64_t)(n0 / BN) * p.stages_total + stage0) * (BN * 4) - 512);
+                xsoff = (unsigned)(4 * (rs % BM));
+                wsoff = (unsigned)(4 * rs);
+            } else {                                   // straight from the caller's [rows, K / 32] arrays: a cache line per lane
+                xs_ptr = uniform_pointer(reinterpret_cast<const char *>(p.Xs + (int64_t)m0 * p.ldxs + kbase / 32));
+                ws_ptr = uniform_pointer(reinterpret_cast<const char *>(p.Ws + (int64_t)n0 * p.ldws + kbase / 32) - 512);
+                xsoff = (unsigned)(min(rs % BM, p.M - 1 - m0) * (int)p.ldxs);
+                wsoff = (unsigned)(min(rs, p.N - 1 - n0) * (int)p.ldws);  // + 512 - 512: the Wt scales' instruction offset
+            }
+        }
     };
 
     const unsigned smem_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const unsigned m0_in_stage = smem_lds + wave_u * REGION8 + A_LOADS8 * 1024;
+    const unsigned m0_scales = smem_lds + SCALES_AT + (wave_u & 1) * 256;
+    const int xs_step = (MX && p.scales_packed) ? BM * 4 : BK8 / 32, ws_step = (MX && p.scales_packed) ? BN * 4 : BK8 / 32;   // bytes per stage
     auto issue_part = [&](int slot, auto part_c) __attribute__((always_inline)) {
         constexpr int PART = decltype(part_c)::value;
         if (PART == 0 && __builtin_expect(issue_stage == stages_per_item, 0)) {
@@ -195,12 +250,21 @@ void gemm_fp8_tiled_kernel(const Fp8Params p) {
                 issue_stage = stages_per_item - 1;
                 a_ptr -= BK8;
                 b_ptr -= BK8;
+                xs_ptr -= xs_step;
+                ws_ptr -= ws_step;
             }
         }
         const unsigned m0v = m0_in_stage + slot * STAGE8;
         if constexpr (PART < A_LOADS8) load_16B_per_lane_to_lds<(PART - A_LOADS8) * 1024, PART == 0>(a_ptr, aoff[PART], m0v);
         load_16B_per_lane_to_lds<PART * 1024, false>(b_ptr, boff[PART], m0v);
         if (PART == B_LOADS8 - 1) {
+            if (MX) {
+                const unsigned m0s = m0_scales + slot * STAGE8;
+                load_4B_per_lane_to_lds<0, true>(xs_ptr, xsoff, m0s);
+                load_4B_per_lane_to_lds<512, false>(ws_ptr, wsoff, m0s);
+                xs_ptr += xs_step;
+                ws_ptr += ws_step;
+            }
             ++issue_stage;
             a_ptr += BK8;
             b_ptr += BK8;
@@ -224,13 +288,21 @@ void gemm_fp8_tiled_kernel(const Fp8Params p) {
     }
 #pragma unroll
     for (int b = 0; b < NT; ++b) b_off[b] = (wn * NT + b) * REGION8 + A_LOADS8 * 1024 + li * ROW8;
+    // MX: where the four scale bytes of the lane's rows sit in a slot; block 2 ks + lg is the lane's in K-step ks
+    int s_off[MT + NT];
+#pragma unroll
+    for (int a = 0; a < MT; ++a) s_off[a] = SCALES_AT + ((wm * MT + a) * 32 + li) * 4;
+#pragma unroll
+    for (int b = 0; b < NT; ++b) s_off[MT + b] = SCALES_AT + 512 + ((wn * NT + b) * 32 + li) * 4;
     const int sw = (li >> 1) & 7;
-    // chunk positions of the lane's 32 bytes in K-step ks: (4 ks + 2 lg) ^ sw and (4 ks + 2 lg + 1) ^ sw
+    // chunk positions of the lane's 32 bytes in K-step ks: (4 ks + 2 lg) ^ sw and (4 ks + 2 lg + 1) ^ sw; with block
+    // scales chunks 4 ks + lg and 4 ks + 2 + lg (the instruction's blocks are the first, and the second, 16 bytes of both
+    // halves of the wavefront: see the reference kernel)
     int c_off[KSTEPS8][2];
 #pragma unroll
     for (int ks = 0; ks < KSTEPS8; ++ks) {
-        c_off[ks][0] = ((4 * ks + 2 * lg) ^ sw) << 4;
-        c_off[ks][1] = ((4 * ks + 2 * lg + 1) ^ sw) << 4;
+        c_off[ks][0] = ((4 * ks + (MX ? lg : 2 * lg)) ^ sw) << 4;
+        c_off[ks][1] = ((4 * ks + (MX ? 2 + lg : 2 * lg + 1)) ^ sw) << 4;
     }
 
     // Fragment registers: one set per K-step of a stage; the reads run one K-step (four MFMAs of 16 passes) ahead.
@@ -252,6 +324,14 @@ void gemm_fp8_tiled_kernel(const Fp8Params p) {
         u.h[1] = fr[set][f][1];
         return u.v;
     };
+    // MX: the four scale bytes of each of the lane's rows, fetched once per stage (for the next stage after the last
+    // K-step's bytes are taken out).
+    unsigned scl[MT + NT];
+    auto read_scales = [&](int slot) {
+        const unsigned char *sb = smem + slot * STAGE8;
+#pragma unroll
+        for (int f = 0; f < MT + NT; ++f) scl[f] = *reinterpret_cast<const unsigned *>(sb + s_off[f]);
+    };
 
     Acc<MT, NT> acc, acc2;
     TileStash<LEVELS - 1, MT, NT> stash;
@@ -264,6 +344,7 @@ void gemm_fp8_tiled_kernel(const Fp8Params p) {
     for (int i = 0; i < RING8 - 1; ++i) issue_next_stage(i);
     wait_loads_and_barrier<LOADS_PER_STAGE * (RING8 - 2)>();
     read_frags(0, 0, 0);
+    if (MX) read_scales(0);
 
     int cur = 0;
     int stores_in_flight = 0;          // output stores share the counter of the loads (see the 16-bit kernel)
@@ -287,15 +368,20 @@ void gemm_fp8_tiled_kernel(const Fp8Params p) {
             const bool ahead_in_stage = ks + 1 < KSTEPS8;
             const int t_set = ahead_in_stage ? ks + 1 : 0;
             const int t_slot = ahead_in_stage ? cur : nxt;
+            int sc[MT + NT];
+            if (MX) {
+#pragma unroll
+                for (int f = 0; f < MT + NT; ++f) sc[f] = (int)__builtin_amdgcn_ubfe(scl[f], 16u * ks + 8u * lg, 8u);
+                if (ks == KSTEPS8 - 1) read_scales(nxt);       // the next stage's, complete in LDS since this stage's barrier
+            }
 #pragma unroll
             for (int m = 0; m < NM; ++m) {
                 const int i = m / NT, j = m % NT;
-                if (FIRST && ks == 0) {
-                    const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-                    a.t[i][j] = mfma_32x32x64_8bit<FMT>(frag(0, i), frag(0, MT + j), zero);
-                } else {
-                    a.t[i][j] = mfma_32x32x64_8bit<FMT>(frag(ks, i), frag(ks, MT + j), a.t[i][j]);
-                }
+                const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                const int set = (FIRST && ks == 0) ? 0 : ks;
+                const f32x16 c_in = (FIRST && ks == 0) ? zero : a.t[i][j];
+                if (MX) a.t[i][j] = mfma_32x32x64_8bit_scaled<FMT>(frag(set, i), frag(set, MT + j), c_in, sc[i], sc[MT + j]);
+                else a.t[i][j] = mfma_32x32x64_8bit<FMT>(frag(set, i), frag(set, MT + j), c_in);
                 // this MFMA's share of the LDS reads of the next K-step and of the loads of the stage being fetched
 #pragma unroll
                 for (int r = m * READS_PER_KSTEP / NM; r < (m + 1) * READS_PER_KSTEP / NM; ++r)
@@ -446,12 +532,17 @@ int compute_units() {
     return cus;
 }
 
-template <int WM, int WN, int MT, int NT, int RING8, int FMT>
-hipError_t launch_tiled_fmt(const GemmArgs &a, hipStream_t s) {
+template <int WM, int WN, int MT, int NT, int RING8, int FMT, bool MX>
+hipError_t launch_tiled_fmt(const GemmArgs &a, const Mxfp4Scales *sc, hipStream_t s) {
     constexpr int BM = 32 * MT * WM, BN = 32 * NT * WN;
-    constexpr int STAGE8 = 4 * (BM / 32 + B_LOADS8) * 1024;
+    constexpr int STAGE8 = 4 * (BM / 32 + B_LOADS8) * 1024 + (MX ? 1024 : 0);
+    static_assert(RING8 * STAGE8 <= 160 * 1024, "LDS of a compute unit");
     Fp8Params p;
     p.X = reinterpret_cast<const uint8_t *>(a.X); p.Wt = reinterpret_cast<const uint8_t *>(a.W);
+    p.Xs = MX ? sc->Xs : nullptr; p.Ws = MX ? sc->Ws : nullptr;
+    p.ldxs = MX ? sc->ldxs : 0; p.ldws = MX ? sc->ldws : 0;
+    p.scales_packed = MX ? sc->packed : 0;
+    p.stages_total = a.K / BK8;
     p.partials = a.partials; p.Y = (a.P == 1) ? a.Y : nullptr;
     p.ldx = a.ldx; p.ldw = a.ldw; p.ldy = a.ldy;
     p.M = a.M; p.N = a.N;
@@ -476,7 +567,7 @@ hipError_t launch_tiled_fmt(const GemmArgs &a, hipStream_t s) {
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 32) dev = 32;
 #define TBIK_LAUNCH8(L)                                                                                  \
     case L: {                                                                                            \
-        auto k = gemm_fp8_tiled_kernel<L, WM, WN, MT, NT, RING8, FMT>;                                   \
+        auto k = gemm_fp8_tiled_kernel<L, WM, WN, MT, NT, RING8, FMT, MX>;                               \
         static std::atomic<unsigned> lds_allowed{0};                                                     \
         if (dev >= 32 || !((lds_allowed.load(std::memory_order_relaxed) >> dev) & 1u)) {                 \
             hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
@@ -503,9 +594,16 @@ hipError_t launch_tiled_fmt(const GemmArgs &a, hipStream_t s) {
 // rows: 128, 64 or 32 rows per workgroup tile (the caller's choice; the bits do not depend on it)
 template <int FMT>
 static hipError_t launch_rows(const GemmArgs &a, int rows, hipStream_t s) {
-    if (rows == 32) return launch_tiled_fmt<1, 4, 1, 1, 8, FMT>(a, s);      // 8 x 20 KiB slots: deep prefetch for weight streaming
-    if (rows == 64) return launch_tiled_fmt<1, 4, 2, 1, 6, FMT>(a, s);      // 6 x 24 KiB
-    return launch_tiled_fmt<2, 2, 2, 2, 5, FMT>(a, s);                      // 5 x 32 KiB
+    if (rows == 32) return launch_tiled_fmt<1, 4, 1, 1, 8, FMT, false>(a, nullptr, s);   // 8 x 20 KiB slots: deep prefetch for weight streaming
+    if (rows == 64) return launch_tiled_fmt<1, 4, 2, 1, 6, FMT, false>(a, nullptr, s);   // 6 x 24 KiB
+    return launch_tiled_fmt<2, 2, 2, 2, 5, FMT, false>(a, nullptr, s);                   // 5 x 32 KiB
+}
+// With block scales a slot is 1 KiB larger: one slot fewer where the ring filled LDS.
+template <int FMT>
+static hipError_t launch_rows_mx(const GemmArgs &a, const Mxfp4Scales &sc, int rows, hipStream_t s) {
+    if (rows == 32) return launch_tiled_fmt<1, 4, 1, 1, 7, FMT, true>(a, &sc, s);        // 7 x 21 KiB
+    if (rows == 64) return launch_tiled_fmt<1, 4, 2, 1, 6, FMT, true>(a, &sc, s);        // 6 x 25 KiB
+    return launch_tiled_fmt<2, 2, 2, 2, 4, FMT, true>(a, &sc, s);                        // 4 x 33 KiB
 }
 
 bool gemm_fp8_tiled_supports(const GemmArgs &a) {
@@ -527,10 +625,48 @@ hipError_t launch_gemm_fp8_reference(const GemmArgs &a, hipStream_t s) {
     dim3 grid((a.N + 31) / 32, (a.M + 31) / 32, a.P);
     if (grid.y > 65535u || grid.z > 65535u) return hipErrorInvalidValue;
     void *Y = (a.P == 1) ? a.Y : nullptr;
-    auto kernel = (a.x_dtype == TBIK_FP8_E5M2) ? gemm_fp8_reference_kernel<1> : gemm_fp8_reference_kernel<0>;
+    auto kernel = (a.x_dtype == TBIK_FP8_E5M2) ? gemm_fp8_reference_kernel<1, false> : gemm_fp8_reference_kernel<0, false>;
     hipLaunchKernelGGL(kernel, grid, dim3(64), 0, s, reinterpret_cast<const uint8_t *>(a.X), a.ldx,
-                       reinterpret_cast<const uint8_t *>(a.W), a.ldw, a.partials, Y, a.ldy, a.y_dtype, a.M, a.N,
-                       a.superleaf, a.ns / a.P);
+                       reinterpret_cast<const uint8_t *>(a.W), a.ldw, nullptr, 0, nullptr, 0, a.partials, Y, a.ldy, a.y_dtype,
+                       a.M, a.N, a.superleaf, a.ns / a.P);
+    return hipGetLastError();
+}
+
+// MXFP8: x_dtype names the element format (TBIK_FP8_E4M3 or TBIK_FP8_E5M2); sc carries the E8M0 scales.
+bool gemm_mxfp8_tiled_supports(const GemmArgs &a, const Mxfp4Scales &sc) {
+    if (!gemm_fp8_tiled_supports(a)) return false;
+    auto a4 = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 3) == 0; };
+    if (!a4(sc.Xs) || !a4(sc.Ws) || sc.ldxs % 4 != 0 || sc.ldws % 4 != 0) return false;   // a row's four scale bytes per stage: one aligned dword
+    if (sc.ldxs >= (1 << 24) || sc.ldws >= (1 << 24)) return false;                       // per-lane byte offsets of a tile's scales stay below 2^31
+    return true;
+}
+
+size_t mxfp8_retiled_scales_bytes(int M, int N, int K) { return mx_retiled_scales_bytes<1>(M, N, K / BK8); }
+
+// packed_ws: nullptr, or mxfp8_retiled_scales_bytes(M, N, K) bytes (4-byte aligned) into which the scales are re-tiled
+// first (one short launch), after which every scale load of the GEMM touches two cache lines instead of 64.
+hipError_t launch_gemm_mxfp8_tiled(const GemmArgs &a, const Mxfp4Scales &sc, int rows, void *packed_ws, hipStream_t s) {
+    if (a.M <= 0 || a.N <= 0) return hipSuccess;
+    if (!gemm_mxfp8_tiled_supports(a, sc) || (rows != 32 && rows != 64 && rows != 128)) return hipErrorInvalidValue;
+    Mxfp4Scales use = sc;
+    if (packed_ws) {
+        hipError_t e = launch_mx_scales_retile<1>(sc.Xs, sc.ldxs, a.M, rows, sc.Ws, sc.ldws, a.N, a.K / BK8, packed_ws, &use.Xs, &use.Ws, s);
+        if (e != hipSuccess) return e;
+        use.packed = 1;
+    }
+    return a.x_dtype == TBIK_FP8_E5M2 ? launch_rows_mx<1>(a, use, rows, s) : launch_rows_mx<0>(a, use, rows, s);
+}
+
+hipError_t launch_gemm_mxfp8_reference(const GemmArgs &a, const Mxfp4Scales &sc, hipStream_t s) {
+    if (a.M <= 0 || a.N <= 0) return hipSuccess;
+    if (a.superleaf % 64 != 0) return hipErrorInvalidValue;
+    dim3 grid((a.N + 31) / 32, (a.M + 31) / 32, a.P);
+    if (grid.y > 65535u || grid.z > 65535u) return hipErrorInvalidValue;
+    void *Y = (a.P == 1) ? a.Y : nullptr;
+    auto kernel = (a.x_dtype == TBIK_FP8_E5M2) ? gemm_fp8_reference_kernel<1, true> : gemm_fp8_reference_kernel<0, true>;
+    hipLaunchKernelGGL(kernel, grid, dim3(64), 0, s, reinterpret_cast<const uint8_t *>(a.X), a.ldx,
+                       reinterpret_cast<const uint8_t *>(a.W), a.ldw, sc.Xs, sc.ldxs, sc.Ws, sc.ldws, a.partials, Y, a.ldy,
+                       a.y_dtype, a.M, a.N, a.superleaf, a.ns / a.P);
     return hipGetLastError();
 }
 

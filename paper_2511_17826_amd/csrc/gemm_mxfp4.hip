@@ -14,6 +14,7 @@
 #include <atomic>
 #include <type_traits>
 
+#include "mx_scales.hpp"
 #include "tbik_device.hpp"
 #include "tbik_internal.hpp"
 #include "tree_walk.hpp"
@@ -123,6 +124,8 @@ struct Mx4Params {
     int tiles_n, tiles, work;
     int vector_stores;
     int stream_stores;
+    int scales_packed;          // Xs, Ws are the re-tiled copies (mx_scales_retile_kernel<2>, blocks of this launch's tile height)
+    int stages_total;           // K / 256
 };
 
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
@@ -165,8 +168,14 @@ void gemm_mxfp4_tiled_kernel(const Mx4Params p) {
         const int64_t kbase = (int64_t)shard * p.k_per_shard;
         a_ptr = uniform_pointer(reinterpret_cast<const char *>(p.X + (int64_t)m0 * p.ldx + kbase / 2));
         b_ptr = uniform_pointer(reinterpret_cast<const char *>(p.Wt + (int64_t)n0 * p.ldw + kbase / 2) - LANE_BIAS);
-        xs_ptr = uniform_pointer(reinterpret_cast<const char *>(p.Xs + (int64_t)m0 * p.ldxs + kbase / 32));
-        ws_ptr = uniform_pointer(reinterpret_cast<const char *>(p.Ws + (int64_t)n0 * p.ldws + kbase / 32) - 1024);
+        if (p.scales_packed) {                         // a stage's scale bytes of a row block are consecutive: two cache lines per load
+            const int64_t stage0 = kbase / 256;
+            xs_ptr = uniform_pointer(reinterpret_cast<const char *>(p.Xs) + ((int64_t)(m0 / BM) * p.stages_total + stage0) * (BM * 8));
+            ws_ptr = uniform_pointer(reinterpret_cast<const char *>(p.Ws) + ((int64_t)(n0 / BN) * p.stages_total + stage0) * (BN * 8) - 1024);
+        } else {                                       // straight from the caller's [rows, K / 32] arrays: a cache line per row
+            xs_ptr = uniform_pointer(reinterpret_cast<const char *>(p.Xs + (int64_t)m0 * p.ldxs + kbase / 32));
+            ws_ptr = uniform_pointer(reinterpret_cast<const char *>(p.Ws + (int64_t)n0 * p.ldws + kbase / 32) - 1024);
+        }
 #pragma unroll
         for (int j = 0; j < A_LOADS4; ++j) {
             const int r = (wave * A_LOADS4 + j) * 8 + (lane >> 3);
@@ -180,14 +189,20 @@ void gemm_mxfp4_tiled_kernel(const Mx4Params p) {
             boff[j] = (unsigned)(min(r, p.N - 1 - n0) * (int)p.ldw + c * 16) + (unsigned)(LANE_BIAS - j * 1024);
         }
         const int rs = wave * 32 + (lane >> 1);
-        xsoff = (unsigned)(min(rs % BM, p.M - 1 - m0) * (int)p.ldxs + 4 * (lane & 1));
-        wsoff = (unsigned)(min(rs, p.N - 1 - n0) * (int)p.ldws + 4 * (lane & 1));    // + 1024 - 1024: the Wt scales' instruction offset
+        if (p.scales_packed) {
+            xsoff = (unsigned)((rs % BM) * 8 + 4 * (lane & 1));
+            wsoff = (unsigned)(rs * 8 + 4 * (lane & 1));
+        } else {
+            xsoff = (unsigned)(min(rs % BM, p.M - 1 - m0) * (int)p.ldxs + 4 * (lane & 1));
+            wsoff = (unsigned)(min(rs, p.N - 1 - n0) * (int)p.ldws + 4 * (lane & 1));    // + 1024 - 1024: the Wt scales' instruction offset
+        }
     };
 
     const unsigned smem_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const unsigned m0_in_stage = smem_lds + wave_u * REGION4 + A_LOADS4 * 1024;
     const unsigned m0_scales = smem_lds + SCALES_AT + wave_u * 256;
+    const int xs_step = p.scales_packed ? BM * 8 : 8, ws_step = p.scales_packed ? BN * 8 : 8;   // scale bytes per stage
     auto issue_part = [&](int slot, auto part_c) __attribute__((always_inline)) {
         constexpr int PART = decltype(part_c)::value;
         if (PART == 0 && __builtin_expect(issue_stage == stages_per_item, 0)) {
@@ -199,8 +214,8 @@ void gemm_mxfp4_tiled_kernel(const Mx4Params p) {
                 issue_stage = stages_per_item - 1;
                 a_ptr -= BKB;
                 b_ptr -= BKB;
-                xs_ptr -= 8;
-                ws_ptr -= 8;
+                xs_ptr -= xs_step;
+                ws_ptr -= ws_step;
             }
         }
         const unsigned m0v = m0_in_stage + slot * STAGE4;
@@ -213,8 +228,8 @@ void gemm_mxfp4_tiled_kernel(const Mx4Params p) {
             ++issue_stage;
             a_ptr += BKB;
             b_ptr += BKB;
-            xs_ptr += 8;
-            ws_ptr += 8;
+            xs_ptr += xs_step;
+            ws_ptr += ws_step;
         }
     };
     auto issue_next_stage = [&](int slot) {
@@ -483,6 +498,8 @@ static hipError_t launch_mx4_shape(const GemmArgs &a, const Mxfp4Scales &sc, hip
     Mx4Params p;
     p.X = reinterpret_cast<const uint8_t *>(a.X); p.Wt = reinterpret_cast<const uint8_t *>(a.W);
     p.Xs = sc.Xs; p.Ws = sc.Ws;
+    p.scales_packed = sc.packed;
+    p.stages_total = a.K / 256;
     p.partials = a.partials; p.Y = (a.P == 1) ? a.Y : nullptr;
     p.ldx = a.ldx; p.ldw = a.ldw; p.ldxs = sc.ldxs; p.ldws = sc.ldws; p.ldy = a.ldy;
     p.M = a.M; p.N = a.N;
@@ -529,13 +546,22 @@ static hipError_t launch_mx4_shape(const GemmArgs &a, const Mxfp4Scales &sc, hip
     return hipGetLastError();
 }
 
-hipError_t launch_gemm_mxfp4_tiled(const GemmArgs &a, const Mxfp4Scales &sc, int rows, hipStream_t s) {
+size_t mxfp4_retiled_scales_bytes(int M, int N, int K) { return mx_retiled_scales_bytes<2>(M, N, K / 256); }
+
+// packed_ws: nullptr, or mxfp4_retiled_scales_bytes(M, N, K) bytes (4-byte aligned) into which the scales are re-tiled
+// first (one short launch), after which every scale load of the GEMM touches two cache lines instead of 32.
+hipError_t launch_gemm_mxfp4_tiled(const GemmArgs &a, const Mxfp4Scales &sc, int rows, void *packed_ws, hipStream_t s) {
     if (a.M <= 0 || a.N <= 0) return hipSuccess;
-    if (!gemm_mxfp4_tiled_supports(a, sc)) return hipErrorInvalidValue;
-    if (rows == 32) return launch_mx4_shape<1, 4, 1, 1, 7>(a, sc, s);      // 7 x 22 KiB slots
-    if (rows == 64) return launch_mx4_shape<1, 4, 2, 1, 6>(a, sc, s);      // 6 x 26 KiB
-    if (rows == 128) return launch_mx4_shape<2, 2, 2, 2, 4>(a, sc, s);     // 4 x 34 KiB
-    return hipErrorInvalidValue;
+    if (!gemm_mxfp4_tiled_supports(a, sc) || (rows != 32 && rows != 64 && rows != 128)) return hipErrorInvalidValue;
+    Mxfp4Scales use = sc;
+    if (packed_ws) {
+        hipError_t e = launch_mx_scales_retile<2>(sc.Xs, sc.ldxs, a.M, rows, sc.Ws, sc.ldws, a.N, a.K / 256, packed_ws, &use.Xs, &use.Ws, s);
+        if (e != hipSuccess) return e;
+        use.packed = 1;
+    }
+    if (rows == 32) return launch_mx4_shape<1, 4, 1, 1, 7>(a, use, s);     // 7 x 22 KiB slots
+    if (rows == 64) return launch_mx4_shape<1, 4, 2, 1, 6>(a, use, s);     // 6 x 26 KiB
+    return launch_mx4_shape<2, 2, 2, 2, 4>(a, use, s);                     // 4 x 34 KiB
 }
 
 }  // namespace tbik

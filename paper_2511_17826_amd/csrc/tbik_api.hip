@@ -391,8 +391,16 @@ static int mxfp4_checks(const void *X, int64_t ldx, const void *Xs, int64_t ldxs
     return TBIK_OK;
 }
 
+// From 128 rows on the microscaling GEMMs re-tile their scales first (a launch of its own, which a small batch would
+// feel): the workspace is the fp32 planes of the K split, rounded up to 256 bytes, then the re-tiled scales.
+static bool mx_retiles(int M) { return M >= 128; }
+static size_t mx_planes_bytes(int M, int N, int K, int leaf, int k_first) {
+    return (tbik_gemm_fp8_workspace_bytes(M, N, K, leaf, k_first) + 255) & ~(size_t)255;      // the same tile shapes, the same K split
+}
 size_t tbik_gemm_mxfp4_workspace_bytes(int M, int N, int K, int leaf, int k_first) {
-    return tbik_gemm_fp8_workspace_bytes(M, N, K, leaf, k_first);      // the same tile shapes, the same K split
+    int sl, ns;
+    if (check_tree(M, N, K, leaf, k_first, 1, &sl, &ns) != TBIK_OK) return 0;
+    return mx_planes_bytes(M, N, K, leaf, k_first) + (mx_retiles(M) && K % 256 == 0 ? mxfp4_retiled_scales_bytes(M, N, K) : 0);
 }
 
 int tbik_gemm_mxfp4(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
@@ -419,15 +427,16 @@ int tbik_gemm_mxfp4(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, co
     probe.P = split;
     const bool tiled = g_forced_variant.load() != VARIANT_REFERENCE && gemm_mxfp4_tiled_supports(probe, sc);
     hipError_t e;
+    void *retiled = (tiled && mx_retiles(M)) ? static_cast<char *>(workspace) + mx_planes_bytes(M, N, K, leaf, k_first) : nullptr;
     if (!tiled) {
         e = launch_gemm_mxfp4_reference(a, sc, s);
     } else if (split == 1) {
-        e = launch_gemm_mxfp4_tiled(a, sc, rows, s);
+        e = launch_gemm_mxfp4_tiled(a, sc, rows, retiled, s);
     } else {
         a.partials = reinterpret_cast<float *>(workspace);
         a.Y = nullptr;
         a.P = split;
-        e = launch_gemm_mxfp4_tiled(a, sc, rows, s);
+        e = launch_gemm_mxfp4_tiled(a, sc, rows, retiled, s);
         if (e == hipSuccess) e = launch_tree_combine(a.partials, split, Y, ldy, (int)y_dtype, M, N, s);
     }
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
@@ -447,7 +456,7 @@ int tbik_gemm_shard_partials_mxfp4(const void *X, int64_t ldx, const void *Xs, i
     GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)Wt, ldwt, partials, nullptr, 0, TBIK_F32, M, N, K, sl, ns, P, TBIK_MXFP4, 0};
     const Mxfp4Scales sc{(const uint8_t *)Xs, ldxs, (const uint8_t *)Ws, ldws};
     const bool tiled = g_forced_variant.load() != VARIANT_REFERENCE && gemm_mxfp4_tiled_supports(a, sc);
-    hipError_t e = tiled ? launch_gemm_mxfp4_tiled(a, sc, fp8_tile_rows(M, N), (hipStream_t)hip_stream)
+    hipError_t e = tiled ? launch_gemm_mxfp4_tiled(a, sc, fp8_tile_rows(M, N), nullptr, (hipStream_t)hip_stream)
                          : launch_gemm_mxfp4_reference(a, sc, (hipStream_t)hip_stream);
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }
@@ -467,6 +476,99 @@ int tbik_gemm_reference_mxfp4(const void *X, int64_t ldx, const void *Xs, int64_
     GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)Wt, ldwt, partials, Y, ldy, (int)y_dtype, M, N, K, sl, ns, P, TBIK_MXFP4, 0};
     const Mxfp4Scales sc{(const uint8_t *)Xs, ldxs, (const uint8_t *)Ws, ldws};
     hipError_t e = launch_gemm_mxfp4_reference(a, sc, (hipStream_t)hip_stream);
+    return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
+// ---- MXFP8 operands ----
+static int mxfp8_checks(int x_dtype, const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                        const void *Ws, int64_t ldws, int M, int N, int K, int leaf, int k_first, int P, int *sl, int *ns) {
+    int rc = fp8_checks(x_dtype, X, ldx, Wt, ldwt, M, N, K, leaf, k_first, P, sl, ns);
+    if (rc != TBIK_OK) return rc;
+    if (M == 0 || N == 0) return TBIK_OK;
+    if (!Xs || !Ws) return TBIK_ERR_NULL;
+    if (ldxs < K / 32 || ldws < K / 32) return TBIK_ERR_SHAPE;
+    return TBIK_OK;
+}
+
+size_t tbik_gemm_mxfp8_workspace_bytes(int M, int N, int K, int leaf, int k_first) {
+    int sl, ns;
+    if (check_tree(M, N, K, leaf, k_first, 1, &sl, &ns) != TBIK_OK) return 0;
+    return mx_planes_bytes(M, N, K, leaf, k_first) + (mx_retiles(M) && K % 128 == 0 ? mxfp8_retiled_scales_bytes(M, N, K) : 0);
+}
+
+int tbik_gemm_mxfp8(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                    const void *Ws, int64_t ldws, void *Y, int64_t ldy, tbik_dtype y_dtype, tbik_dtype x_dtype,
+                    int M, int N, int K, int leaf, int k_first,
+                    void *workspace, size_t workspace_bytes, void *hip_stream) {
+    int sl, ns;
+    int rc = mxfp8_checks((int)x_dtype, X, ldx, Xs, ldxs, Wt, ldwt, Ws, ldws, M, N, K, leaf, k_first, 1, &sl, &ns);
+    if (rc != TBIK_OK) return rc;
+    if (y_dtype != TBIK_F32 && y_dtype != TBIK_BF16) return TBIK_ERR_DTYPE;
+    if (M == 0 || N == 0) return TBIK_OK;
+    if (!Y) return TBIK_ERR_NULL;
+    if (ldy < N) return TBIK_ERR_SHAPE;
+    if (!aligned(Y, y_dtype == TBIK_F32 ? 4 : 2)) return TBIK_ERR_ALIGN;
+    const size_t need = tbik_gemm_mxfp8_workspace_bytes(M, N, K, leaf, k_first);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return TBIK_ERR_WORKSPACE;
+    if (workspace && !aligned(workspace, 256)) return TBIK_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)hip_stream;
+    GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)Wt, ldwt, nullptr, Y, ldy, (int)y_dtype, M, N, K, sl, ns, 1, (int)x_dtype, 0};
+    const Mxfp4Scales sc{(const uint8_t *)Xs, ldxs, (const uint8_t *)Ws, ldws};
+    const int split = internal_split(M, N, K, ns);
+    const int rows = fp8_tile_rows(M, N);
+    GemmArgs probe = a;
+    probe.P = split;
+    const bool tiled = g_forced_variant.load() != VARIANT_REFERENCE && gemm_mxfp8_tiled_supports(probe, sc);
+    hipError_t e;
+    void *retiled = (tiled && mx_retiles(M)) ? static_cast<char *>(workspace) + mx_planes_bytes(M, N, K, leaf, k_first) : nullptr;
+    if (!tiled) {
+        e = launch_gemm_mxfp8_reference(a, sc, s);
+    } else if (split == 1) {
+        e = launch_gemm_mxfp8_tiled(a, sc, rows, retiled, s);
+    } else {
+        a.partials = reinterpret_cast<float *>(workspace);
+        a.Y = nullptr;
+        a.P = split;
+        e = launch_gemm_mxfp8_tiled(a, sc, rows, retiled, s);
+        if (e == hipSuccess) e = launch_tree_combine(a.partials, split, Y, ldy, (int)y_dtype, M, N, s);
+    }
+    return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
+int tbik_gemm_shard_partials_mxfp8(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                                   const void *Ws, int64_t ldws, float *partials, tbik_dtype x_dtype,
+                                   int M, int N, int K, int leaf, int k_first, int P,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream) {
+    (void)workspace; (void)workspace_bytes;
+    int sl, ns;
+    int rc = mxfp8_checks((int)x_dtype, X, ldx, Xs, ldxs, Wt, ldwt, Ws, ldws, M, N, K, leaf, k_first, P, &sl, &ns);
+    if (rc != TBIK_OK) return rc;
+    if (M == 0 || N == 0) return TBIK_OK;
+    if (!partials) return TBIK_ERR_NULL;
+    if (!aligned(partials, 16)) return TBIK_ERR_ALIGN;
+    GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)Wt, ldwt, partials, nullptr, 0, TBIK_F32, M, N, K, sl, ns, P, (int)x_dtype, 0};
+    const Mxfp4Scales sc{(const uint8_t *)Xs, ldxs, (const uint8_t *)Ws, ldws};
+    const bool tiled = g_forced_variant.load() != VARIANT_REFERENCE && gemm_mxfp8_tiled_supports(a, sc);
+    hipError_t e = tiled ? launch_gemm_mxfp8_tiled(a, sc, fp8_tile_rows(M, N), nullptr, (hipStream_t)hip_stream)
+                         : launch_gemm_mxfp8_reference(a, sc, (hipStream_t)hip_stream);
+    return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
+int tbik_gemm_reference_mxfp8(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                              const void *Ws, int64_t ldws, float *partials, void *Y, int64_t ldy, tbik_dtype y_dtype,
+                              tbik_dtype x_dtype, int M, int N, int K, int leaf, int k_first, int P, void *hip_stream) {
+    int sl, ns;
+    int rc = mxfp8_checks((int)x_dtype, X, ldx, Xs, ldxs, Wt, ldwt, Ws, ldws, M, N, K, leaf, k_first, P, &sl, &ns);
+    if (rc != TBIK_OK) return rc;
+    if (y_dtype != TBIK_F32 && y_dtype != TBIK_BF16) return TBIK_ERR_DTYPE;
+    if (M == 0 || N == 0) return TBIK_OK;
+    if (!partials && !Y) return TBIK_ERR_NULL;
+    if (Y && P != 1) return TBIK_ERR_SHARDS;
+    if (Y && ldy < N) return TBIK_ERR_SHAPE;
+    if (Y && !aligned(Y, y_dtype == TBIK_F32 ? 4 : 2)) return TBIK_ERR_ALIGN;
+    GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)Wt, ldwt, partials, Y, ldy, (int)y_dtype, M, N, K, sl, ns, P, (int)x_dtype, 0};
+    const Mxfp4Scales sc{(const uint8_t *)Xs, ldxs, (const uint8_t *)Ws, ldws};
+    hipError_t e = launch_gemm_mxfp8_reference(a, sc, (hipStream_t)hip_stream);
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }
 

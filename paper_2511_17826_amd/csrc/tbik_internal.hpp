@@ -62,10 +62,21 @@ struct Mxfp4Scales {
     int64_t ldxs;
     const uint8_t *Ws;   // [N, ldws]
     int64_t ldws;
+    int packed = 0;      // set by the tiled launchers only: Xs, Ws point at their re-tiled copies
 };
 hipError_t launch_gemm_mxfp4_reference(const GemmArgs &a, const Mxfp4Scales &sc, hipStream_t s);
-hipError_t launch_gemm_mxfp4_tiled(const GemmArgs &a, const Mxfp4Scales &sc, int rows, hipStream_t s);   // rows: 128, 64 or 32
+// rows: 128, 64 or 32.  packed_ws: nullptr or mxfp4_retiled_scales_bytes(M, N, K) bytes of device memory for re-tiled scales.
+hipError_t launch_gemm_mxfp4_tiled(const GemmArgs &a, const Mxfp4Scales &sc, int rows, void *packed_ws, hipStream_t s);
+size_t mxfp4_retiled_scales_bytes(int M, int N, int K);
 bool gemm_mxfp4_tiled_supports(const GemmArgs &a, const Mxfp4Scales &sc);
+
+// The same for MXFP8 operands: the 8-bit kernels with one E8M0 scale per block of 32 k beside each operand (a.x_dtype
+// names the element format, TBIK_FP8_E4M3 or TBIK_FP8_E5M2; X [M, ldx] bytes, W the transposed weight [N, ldw] bytes).
+hipError_t launch_gemm_mxfp8_reference(const GemmArgs &a, const Mxfp4Scales &sc, hipStream_t s);
+// rows: 128, 64 or 32.  packed_ws: nullptr or mxfp8_retiled_scales_bytes(M, N, K) bytes of device memory for re-tiled scales.
+hipError_t launch_gemm_mxfp8_tiled(const GemmArgs &a, const Mxfp4Scales &sc, int rows, void *packed_ws, hipStream_t s);
+size_t mxfp8_retiled_scales_bytes(int M, int N, int K);
+bool gemm_mxfp8_tiled_supports(const GemmArgs &a, const Mxfp4Scales &sc);
 
 // Y = T(partials[0..P)) elementwise + one rounding.
 hipError_t launch_tree_combine(const float *partials, int P, void *Y, int64_t ldy, int y_dtype, int M, int N,
