@@ -179,6 +179,7 @@ void gemm_fp8_tiled_kernel(const Fp8Params p) {
     const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, lg = lane >> 5;
     const int stages_per_item = p.ns_per_shard * p.stages_per_superleaf;
+    const bool wave_is_x = __builtin_amdgcn_readfirstlane(wave) < 2;      // MX: whose scales this wavefront fetches
 
     // ---- global -> LDS (global_load_lds_dwordx4: lane i's 16 bytes land at LDS base + 16 i) ----
     // Load j of wavefront w brings rows 32 w + 8 j + (lane >> 3) of a tile; the lane fetches the chunk that belongs at
@@ -186,16 +187,17 @@ void gemm_fp8_tiled_kernel(const Fp8Params p) {
     // (the start of the Wt part of its region): instruction offsets -4 .. -1 KiB for X and 0 .. 3 KiB for Wt; the lane
     // offsets are biased so that the global side of the instruction offset cancels.  Rows past M or N re-read the last
     // valid row: an output depends on its own row of X and of Wt only, and theirs are never stored.
-    // MX: and two 256-byte loads of scales per wavefront (4 bytes per lane = a row's four blocks of the stage: wavefront
-    // w brings rows 64 (w & 1) + lane of the X tile and of the Wt tile, so each row arrives twice, with the same bytes).
-    constexpr int LOADS_PER_STAGE = A_LOADS8 + B_LOADS8 + (MX ? 2 : 0);
+    // MX: and one 256-byte load of scales per wavefront (4 bytes per lane = a row's four blocks of the stage): wavefronts
+    // 0 and 1 bring rows 0 .. 63 and 64 .. 127 of the X tile (with fewer rows in the tile, rows again), 2 and 3 those of
+    // the Wt tile.
+    constexpr int LOADS_PER_STAGE = A_LOADS8 + B_LOADS8 + (MX ? 1 : 0);
     constexpr int WCOLS = 32 * NT;
     constexpr int STORES_F32 = MT * (32 * WCOLS / 4 / 64);
     constexpr int STORES_BF16 = MT * (32 * WCOLS / 8 / 64);
     static_assert(LOADS_PER_STAGE * (RING8 - 1) + STORES_F32 < 64 && STORES_F32 != STORES_BF16, "vmcnt range");
     constexpr int LANE_BIAS = 4096;
-    unsigned aoff[A_LOADS8], boff[B_LOADS8], xsoff = 0, wsoff = 0;
-    const char *a_ptr = nullptr, *b_ptr = nullptr, *xs_ptr = nullptr, *ws_ptr = nullptr;
+    unsigned aoff[A_LOADS8], boff[B_LOADS8], soff = 0;
+    const char *a_ptr = nullptr, *b_ptr = nullptr, *s_ptr = nullptr;      // s_ptr, soff: this wavefront's scale rows (X's or Wt's)
     int issue_item = blockIdx.x;
     int issue_stage = 0;
 
@@ -219,17 +221,18 @@ void gemm_fp8_tiled_kernel(const Fp8Params p) {
         }
         if (MX) {
             const int rs = (wave & 1) * 64 + lane;
+            const bool of_x = wave_is_x;               // uniform
             if (p.scales_packed) {                     // a stage's scale bytes of a row block are consecutive: two cache lines per load
                 const int64_t stage0 = kbase / BK8;
-                xs_ptr = uniform_pointer(reinterpret_cast<const char *>(p.Xs) + ((int64_t)(m0 / BM) * p.stages_total + stage0) * (BM * 4));
-                ws_ptr = uniform_pointer(reinterpret_cast<const char *>(p.Ws) + ((int64_t)(n0 / BN) * p.stages_total + stage0) * (BN * 4) - 512);
-                xsoff = (unsigned)(4 * (rs % BM));
-                wsoff = (unsigned)(4 * rs);
+                const char *xs = reinterpret_cast<const char *>(p.Xs) + ((int64_t)(m0 / BM) * p.stages_total + stage0) * (BM * 4);
+                const char *ws = reinterpret_cast<const char *>(p.Ws) + ((int64_t)(n0 / BN) * p.stages_total + stage0) * (BN * 4);
+                s_ptr = uniform_pointer(of_x ? xs : ws);
+                soff = (unsigned)(4 * (of_x ? rs % BM : rs));
             } else {                                   // straight from the caller's [rows, K / 32] arrays: a cache line per lane
-                xs_ptr = uniform_pointer(reinterpret_cast<const char *>(p.Xs + (int64_t)m0 * p.ldxs + kbase / 32));
-                ws_ptr = uniform_pointer(reinterpret_cast<const char *>(p.Ws + (int64_t)n0 * p.ldws + kbase / 32) - 512);
-                xsoff = (unsigned)(min(rs % BM, p.M - 1 - m0) * (int)p.ldxs);
-                wsoff = (unsigned)(min(rs, p.N - 1 - n0) * (int)p.ldws);  // + 512 - 512: the Wt scales' instruction offset
+                const char *xs = reinterpret_cast<const char *>(p.Xs + (int64_t)m0 * p.ldxs + kbase / 32);
+                const char *ws = reinterpret_cast<const char *>(p.Ws + (int64_t)n0 * p.ldws + kbase / 32);
+                s_ptr = uniform_pointer(of_x ? xs : ws);
+                soff = of_x ? (unsigned)(min(rs % BM, p.M - 1 - m0) * (int)p.ldxs) : (unsigned)(min(rs, p.N - 1 - n0) * (int)p.ldws);
             }
         }
     };
@@ -237,8 +240,8 @@ void gemm_fp8_tiled_kernel(const Fp8Params p) {
     const unsigned smem_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const unsigned m0_in_stage = smem_lds + wave_u * REGION8 + A_LOADS8 * 1024;
-    const unsigned m0_scales = smem_lds + SCALES_AT + (wave_u & 1) * 256;
-    const int xs_step = (MX && p.scales_packed) ? BM * 4 : BK8 / 32, ws_step = (MX && p.scales_packed) ? BN * 4 : BK8 / 32;   // bytes per stage
+    const unsigned m0_scales = smem_lds + SCALES_AT + wave_u * 256;         // X rows 0 .. 127, then Wt rows 0 .. 127, four bytes each
+    const int s_step = !(MX && p.scales_packed) ? BK8 / 32 : (wave_u < 2 ? BM * 4 : BN * 4);      // scale bytes per stage
     auto issue_part = [&](int slot, auto part_c) __attribute__((always_inline)) {
         constexpr int PART = decltype(part_c)::value;
         if (PART == 0 && __builtin_expect(issue_stage == stages_per_item, 0)) {
@@ -250,8 +253,7 @@ void gemm_fp8_tiled_kernel(const Fp8Params p) {
                 issue_stage = stages_per_item - 1;
                 a_ptr -= BK8;
                 b_ptr -= BK8;
-                xs_ptr -= xs_step;
-                ws_ptr -= ws_step;
+                s_ptr -= s_step;
             }
         }
         const unsigned m0v = m0_in_stage + slot * STAGE8;
@@ -259,11 +261,8 @@ void gemm_fp8_tiled_kernel(const Fp8Params p) {
         load_16B_per_lane_to_lds<PART * 1024, false>(b_ptr, boff[PART], m0v);
         if (PART == B_LOADS8 - 1) {
             if (MX) {
-                const unsigned m0s = m0_scales + slot * STAGE8;
-                load_4B_per_lane_to_lds<0, true>(xs_ptr, xsoff, m0s);
-                load_4B_per_lane_to_lds<512, false>(ws_ptr, wsoff, m0s);
-                xs_ptr += xs_step;
-                ws_ptr += ws_step;
+                load_4B_per_lane_to_lds<0, true>(s_ptr, soff, m0_scales + slot * STAGE8);
+                s_ptr += s_step;
             }
             ++issue_stage;
             a_ptr += BK8;
