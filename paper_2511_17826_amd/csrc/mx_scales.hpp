@@ -10,22 +10,25 @@ namespace tbik {
 //   out[((block * stages + stage) * block_rows + r) * DWORDS + d]
 // (rows past the end repeat the last one), so that a stage's scales of a row block are consecutive bytes and a
 // wavefront's load of them touches two cache lines instead of one per row.  One thread per dword, X's first, then Wt's
-// (blocks of 128 rows, behind the x_total dwords of X); consecutive threads read consecutive dwords of a row.
+// (blocks of 128 rows, behind the x_total dwords of X); consecutive threads write consecutive dwords (the reads, one
+// cache line per row, are served by the caches: a line holds the scales of 32 / DWORDS stages).
 template <int DWORDS>
 __global__ __launch_bounds__(256) void mx_scales_retile_kernel(const uint8_t *__restrict__ Xs, int64_t ldxs, int x_rows, int x_block_rows,
                                                                const uint8_t *__restrict__ Ws, int64_t ldws, int w_rows,
                                                                int stages, uint32_t *__restrict__ out, int64_t x_total, int64_t total) {
-    const int per_row = stages * DWORDS;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
         const bool x = i < x_total;
-        const int64_t j = x ? i : i - x_total;
+        const int64_t j = x ? i : i - x_total;                    // = ((block * stages + stage) * block_rows + r) * DWORDS + d
         const int rows = x ? x_rows : w_rows, block_rows = x ? x_block_rows : 128;
-        const int64_t row = j / per_row;
-        const int in_row = (int)(j - row * per_row), stage = in_row / DWORDS, d = in_row - stage * DWORDS;
-        const int64_t block = row / block_rows, r = row - block * block_rows;
-        const int64_t src_row = row < rows ? row : rows - 1;
+        const int64_t q = j / DWORDS;
+        const int d = (int)(j - q * DWORDS);
+        const int64_t bs = q / block_rows;
+        const int r = (int)(q - bs * block_rows);
+        const int64_t block = bs / stages;
+        const int stage = (int)(bs - block * stages);
+        const int64_t row = block * block_rows + r, src_row = row < rows ? row : rows - 1;
         const uint8_t *src = x ? Xs + src_row * ldxs : Ws + src_row * ldws;
-        out[(x ? 0 : x_total) + ((block * stages + stage) * block_rows + r) * DWORDS + d] = *reinterpret_cast<const uint32_t *>(src + 4 * in_row);
+        out[i] = *reinterpret_cast<const uint32_t *>(src + 4 * (stage * DWORDS + d));
     }
 }
 
