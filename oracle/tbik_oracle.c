@@ -38,6 +38,7 @@
  *                            leaf accumulates by one fused multiply-add per k.
  *   tbik_oracle_gemm_mxfp8   the same GEMM on OCP MXFP8 operands: 8-bit E4M3 / E5M2 elements with one E8M0 scale
  *                            per block of 32 consecutive k
+ *   tbik_oracle_gemm_mxfp6   the same GEMM on OCP MXFP6 operands: 6-bit E2M3 / E3M2 elements (24 bytes per block of 32)
  *   tbik_oracle_gemm_mxfp4   the same GEMM on OCP MXFP4 operands: 4-bit E2M1 elements with one E8M0 (power-of-two)
  *                            scale per block of 32 consecutive k; products stay exact in fp32.
  *   tbik_oracle_gemm_fp8*    the same GEMM on 8-bit floating-point operands (the paper's outlook: quantised
@@ -740,6 +741,77 @@ int tbik_oracle_gemm_mxfp8(const uint8_t *X, long ldx, const uint8_t *Xs, long l
                     float acc = 0.0f;
                     for (long k = j * sl; k < (j + 1) * sl; ++k) {
                         const float w = tbik_oracle_fp8_to_f32(Wt[n * ldw + k], fmt8) * tbik_oracle_e8m0_to_f32(Ws[n * ldws + k / 32]);
+                        float pk = xrow[k] * w;
+                        acc = acc + pk;
+                    }
+                    s[j] = acc;
+                }
+                float y = combine_superleaves(s, ns, evaluator, P, part);
+                if (Y32) Y32[m * ldy + n] = y;
+                if (Ybf) Ybf[m * ldy + n] = f32_to_bf16(y);
+                if (partials && evaluator == EVAL_SHARDED)
+                    for (int p = 0; p < P; ++p) partials[((size_t)p * M + m) * N + n] = part[p];
+            }
+        }
+        free(s);
+        free(xrow);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ 6-bit floating point with block scales (OCP MXFP6) */
+
+enum { FMT6_E2M3 = 0, FMT6_E3M2 = 1 };
+
+/*
+ * A 6-bit pattern (the low six bits of `b`) -> fp32, exact.  Sign | exponent | fraction, IEEE-style bias, subnormals, no
+ * infinities and no NaN:
+ *   E2M3: 2 exponent bits (bias 1), 3 fraction bits: 0, 0.125 .. 0.875 (subnormal), then (1 + f/8) 2^(e-1) up to 7.5.
+ *   E3M2: 3 exponent bits (bias 3), 2 fraction bits: 0, 0.0625 .. 0.1875 (subnormal), then (1 + f/4) 2^(e-3) up to 28.
+ */
+float tbik_oracle_fp6_to_f32(uint8_t b, int fmt6) {
+    const int ebits = fmt6 == FMT6_E3M2 ? 3 : 2, fbits = 5 - ebits, bias = fmt6 == FMT6_E3M2 ? 3 : 1;
+    const int sign = (b >> 5) & 1, e = (b >> fbits) & ((1 << ebits) - 1), f = b & ((1 << fbits) - 1);
+    const float v = (e == 0) ? ldexpf((float)f, 1 - bias - fbits) : ldexpf((float)(f + (1 << fbits)), e - bias - fbits);
+    return sign ? -v : v;
+}
+
+/* Element k of a packed row: the elements form one little-endian bit stream, element k in bits 6k .. 6k+5. */
+static uint8_t fp6_element(const uint8_t *row, long k) {
+    const long bit = 6 * k;
+    const unsigned two = (unsigned)row[bit >> 3] | ((unsigned)row[(bit >> 3) + ((bit & 7) > 2 ? 1 : 0)] << 8);
+    return (uint8_t)((two >> (bit & 7)) & 63u);
+}
+
+/*
+ * Y = X W on MXFP6 operands (quantised types of the paper's outlook; the order contract as for every other format):
+ *   x[m,k] = fp6(element k of row m of X) * 2^(Xs[m, k/32] - 127),   w[k,n] = fp6(element k of row n of Wt) * 2^(Ws[n, k/32] - 127)
+ * with 32 elements (one block, one scale) in 24 bytes and the weight stored TRANSPOSED.  A product has at most eight
+ * significant bits and a power-of-two scale: exact in fp32 while it stays in range.
+ *   s_j = ((p_a + p_{a+1}) + ...) over superleaf j in ascending k from +0;  y = T(s_0 .. s_{n_s-1}).
+ * X [M, ldx] bytes (ldx >= 3K/4), Xs [M, ldxs] (>= K/32), Wt [N, ldw], Ws [N, ldws].  K a multiple of 32.
+ */
+int tbik_oracle_gemm_mxfp6(const uint8_t *X, long ldx, const uint8_t *Xs, long ldxs,
+                           const uint8_t *Wt, long ldw, const uint8_t *Ws, long ldws,
+                           float *Y32, uint16_t *Ybf, long ldy, int M, int N, int K, int leaf, int k_first,
+                           int evaluator, int P, int fmt6, float *partials) {
+    long ns = superleaf_count(K, leaf, k_first, P);
+    if (ns < 0 || K % 32 != 0) return -1;
+    const long sl = (long)leaf * k_first;
+#pragma omp parallel
+    {
+        float *s = (float *)malloc((size_t)ns * sizeof(float));
+        float *xrow = (float *)malloc((size_t)K * sizeof(float));
+        float part[64];
+#pragma omp for schedule(dynamic, 1)
+        for (long m = 0; m < M; ++m) {
+            for (long k = 0; k < K; ++k)
+                xrow[k] = tbik_oracle_fp6_to_f32(fp6_element(X + m * ldx, k), fmt6) * tbik_oracle_e8m0_to_f32(Xs[m * ldxs + k / 32]);
+            for (long n = 0; n < N; ++n) {
+                for (long j = 0; j < ns; ++j) {
+                    float acc = 0.0f;
+                    for (long k = j * sl; k < (j + 1) * sl; ++k) {
+                        const float w = tbik_oracle_fp6_to_f32(fp6_element(Wt + n * ldw, k), fmt6) * tbik_oracle_e8m0_to_f32(Ws[n * ldws + k / 32]);
                         float pk = xrow[k] * w;
                         acc = acc + pk;
                     }

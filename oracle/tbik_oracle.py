@@ -104,6 +104,11 @@ def lib():
         L.tbik_oracle_gemm_mxfp8.restype = C.c_int
         L.tbik_oracle_gemm_mxfp8.argtypes = [u8p, C.c_long, u8p, C.c_long, u8p, C.c_long, u8p, C.c_long, f32p, u16p, C.c_long,
                                              C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f32p]
+        L.tbik_oracle_fp6_to_f32.restype = C.c_float
+        L.tbik_oracle_fp6_to_f32.argtypes = [C.c_uint8, C.c_int]
+        L.tbik_oracle_gemm_mxfp6.restype = C.c_int
+        L.tbik_oracle_gemm_mxfp6.argtypes = [u8p, C.c_long, u8p, C.c_long, u8p, C.c_long, u8p, C.c_long, f32p, u16p, C.c_long,
+                                             C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f32p]
         L.tbik_oracle_tree_combine.restype = C.c_int
         L.tbik_oracle_tree_combine.argtypes = [f32p, C.c_int, C.c_long, f32p, u16p, C.c_int]
         L.tbik_oracle_treesum.restype = C.c_float
@@ -431,6 +436,53 @@ def gemm_mxfp8(X, Xs, Wt, Ws, leaf: int, k_first: int = 1, evaluator: int = EVAL
     rc = lib().tbik_oracle_gemm_mxfp8(xp, K, xsp, K // 32, wp, K, wsp, K // 32, Y32.ctypes.data_as(C.POINTER(C.c_float)),
                                       Ybf.ctypes.data_as(C.POINTER(C.c_uint16)), N, M, N, K, leaf, k_first, evaluator, P,
                                       FORMATS8[fmt], parts.ctypes.data_as(C.POINTER(C.c_float)) if want_partials else None)
+    if rc != 0:
+        raise ValueError("oracle gemm: illegal tree parameters (K, leaf, k_first, P)")
+    return (Y32, Ybf, parts) if want_partials else (Y32, Ybf)
+
+
+FORMATS6 = {"e2m3": 0, "e3m2": 1}
+
+
+def fp6_to_f32(patterns, fmt: str = "e2m3") -> np.ndarray:
+    """6-bit patterns (the low six bits of each entry) of format `fmt` -> fp32 values."""
+    L = lib()
+    table = np.array([L.tbik_oracle_fp6_to_f32(b, FORMATS6[fmt]) for b in range(64)], dtype=np.float32)
+    return table[np.asarray(patterns, dtype=np.uint8) & 63]
+
+
+def fp6_unpack(packed) -> np.ndarray:
+    """[R, 3K/4] bytes -> [R, K] 6-bit patterns: the elements of a row are one little-endian bit stream."""
+    packed = np.asarray(packed, dtype=np.uint8)
+    bits = np.unpackbits(packed, axis=1, bitorder="little")
+    R = packed.shape[0]
+    six = bits.reshape(R, -1, 6)
+    return (six * (1 << np.arange(6, dtype=np.uint8))).sum(axis=2).astype(np.uint8)
+
+
+def mxfp6_dequant(packed, scales, fmt: str = "e2m3") -> np.ndarray:
+    """[R, 3K/4] packed 6-bit elements and [R, K/32] E8M0 scales -> fp32 [R, K] (exact while in range)."""
+    return fp6_to_f32(fp6_unpack(packed), fmt) * np.repeat(e8m0_to_f32(scales), 32, axis=1)
+
+
+def gemm_mxfp6(X, Xs, Wt, Ws, leaf: int, k_first: int = 1, evaluator: int = EVAL_RECURSIVE, P: int = 1,
+               want_partials: bool = False, fmt: str = "e2m3"):
+    """Y = X W in the tree order on MXFP6 operands: X [M, 3K/4] packed elements with scales Xs [M, K/32]; the weight
+    transposed, Wt [N, 3K/4] with Ws [N, K/32].  Returns (Y fp32 [M,N], Y bf16 patterns[, partials [P,M,N]])."""
+    X, xp = _u8(X)
+    Xs, xsp = _u8(Xs)
+    Wt, wp = _u8(Wt)
+    Ws, wsp = _u8(Ws)
+    M, KB = X.shape
+    N = Wt.shape[0]
+    K = KB * 4 // 3
+    assert KB * 4 == 3 * K and Wt.shape[1] == KB and Xs.shape == (M, K // 32) and Ws.shape == (N, K // 32)
+    Y32 = np.empty((M, N), dtype=np.float32)
+    Ybf = np.empty((M, N), dtype=np.uint16)
+    parts = np.zeros((P, M, N), dtype=np.float32) if want_partials else None
+    rc = lib().tbik_oracle_gemm_mxfp6(xp, KB, xsp, K // 32, wp, KB, wsp, K // 32, Y32.ctypes.data_as(C.POINTER(C.c_float)),
+                                      Ybf.ctypes.data_as(C.POINTER(C.c_uint16)), N, M, N, K, leaf, k_first, evaluator, P,
+                                      FORMATS6[fmt], parts.ctypes.data_as(C.POINTER(C.c_float)) if want_partials else None)
     if rc != 0:
         raise ValueError("oracle gemm: illegal tree parameters (K, leaf, k_first, P)")
     return (Y32, Ybf, parts) if want_partials else (Y32, Ybf)

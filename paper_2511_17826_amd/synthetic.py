@@ -224,6 +224,58 @@ def gemm_random_mxfp8(seed: int, M: int, K: int, N: int, fmt: str = "e4m3", scal
     return Xq, Xs, Wq, Ws
 
 
+def fp6_magnitudes(fmt: str = "e2m3") -> np.ndarray:
+    """The 32 magnitudes a 6-bit element can hold, by pattern (sign bit clear), from the format's definition."""
+    ebits, fbits, bias = (2, 3, 1) if fmt == "e2m3" else (3, 2, 3)
+    out = []
+    for p in range(32):
+        e, f = p >> fbits, p & ((1 << fbits) - 1)
+        out.append(f * 2.0 ** (1 - bias - fbits) if e == 0 else (f + (1 << fbits)) * 2.0 ** (e - bias - fbits))
+    return np.array(out, dtype=np.float32)
+
+
+def fp6_pack(patterns: np.ndarray) -> np.ndarray:
+    """[R, K] 6-bit patterns -> [R, 3K/4] bytes: one little-endian bit stream per row, element k in bits 6k .. 6k+5."""
+    patterns = np.asarray(patterns, dtype=np.uint8)
+    bits = ((patterns[..., None] >> np.arange(6, dtype=np.uint8)) & 1).astype(np.uint8)
+    return np.packbits(bits.reshape(patterns.shape[0], -1), axis=1, bitorder="little")
+
+
+def mxfp6_quantize(a: np.ndarray, fmt: str = "e2m3"):
+    """fp32 [R, K] (K a multiple of 32) -> (packed 6-bit elements uint8 [R, 3K/4], E8M0 scales uint8 [R, K/32]).  Per block
+    of 32 the scale is the power of two that brings the block's largest magnitude into the element format's top binade
+    (an all-zero block gets 2^0); elements go to the nearest representable magnitude (ties to the lower pattern).  An input
+    recipe: nothing of the method's arithmetic."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    R, K = a.shape
+    assert K % 32 == 0
+    mags = fp6_magnitudes(fmt)
+    top = 2.0 if fmt == "e2m3" else 4.0                      # log2 of the top binade's lower end: values up to 7.5 / 28
+    blocks = a.reshape(R, K // 32, 32)
+    amax = np.abs(blocks).max(axis=2)
+    e = np.where(amax > 0, np.floor(np.log2(np.where(amax > 0, amax, 1.0))) - top, 0.0).astype(np.int32)
+    scales = np.clip(e + 127, 1, 254).astype(np.uint8)
+    scaled = blocks / np.exp2(scales.astype(np.float32) - 127)[:, :, None]
+    idx = np.abs(np.abs(scaled)[..., None] - mags).argmin(axis=-1).astype(np.uint8)
+    pat = (idx | (np.signbit(scaled).astype(np.uint8) << 5)).reshape(R, K)
+    return fp6_pack(pat), scales
+
+
+def gemm_random_mxfp6(seed: int, M: int, K: int, N: int, fmt: str = "e2m3", scale_spread: int = 0):
+    """MXFP6 operands from X ~ N(0,1), W ~ N(0,0.02) (the weight transposed, [N, K]): returns (X packed, X scales,
+    Wt packed, W scales).  With `scale_spread` every block's scale is moved by a random number of binades in
+    [-scale_spread, scale_spread] (the elements stay as quantised)."""
+    rng = _rng(seed)
+    X = rng.standard_normal(size=(M, K), dtype=np.float32)
+    Wt = rng.standard_normal(size=(N, K), dtype=np.float32) * np.float32(0.02)
+    Xp, Xs = mxfp6_quantize(X, fmt)
+    Wp, Ws = mxfp6_quantize(Wt, fmt)
+    if scale_spread:
+        Xs = (Xs.astype(np.int32) + rng.integers(-scale_spread, scale_spread + 1, size=Xs.shape)).astype(np.uint8)
+        Ws = (Ws.astype(np.int32) + rng.integers(-scale_spread, scale_spread + 1, size=Ws.shape)).astype(np.uint8)
+    return Xp, Xs, Wp, Ws
+
+
 def gemm_random_f32(seed: int, M: int, K: int, N: int, x_std: float = 1.0, w_std: float = 0.02, exp_spread: int = 0):
     """fp32 operands X [M,K] ~ N(0, x_std), W [K,N] ~ N(0, w_std) with full 24-bit significands; with ``exp_spread`` every
     element is scaled by a random power of two in [-exp_spread, exp_spread] (cancellation and absorption cases)."""
