@@ -420,6 +420,21 @@ def metric_shapes(tb, syn, torch, np, to_dev, X, W):
         res[name] = {"ms": round(t, 4), "tflops": round(tf, 1), "frac_fp8_peak": round(tf / PEAK_FP8_TFLOPS, 4)}
         del Xx, Wx, Xsx, Wsx, yx, wsx
 
+    # MXFP6 operands (random element and scale bytes: the timing does not depend on the values), same two shapes.
+    for name, K6, leaf6, g6 in (("mxfp6_oproj_M4096", 4096, 256, 1), ("mxfp6_downproj_M4096", 12288, 256, 3)):
+        g6r = torch.Generator(device=dev)
+        g6r.manual_seed(K6 + 3)
+        X6 = torch.randint(0, 256, (4096, K6 * 3 // 4), generator=g6r, device=dev, dtype=torch.uint8)
+        W6 = torch.randint(0, 256, (4096, K6 * 3 // 4), generator=g6r, device=dev, dtype=torch.uint8)
+        Xs6 = torch.randint(120, 134, (4096, K6 // 32), generator=g6r, device=dev, dtype=torch.uint8)
+        Ws6 = torch.randint(120, 134, (4096, K6 // 32), generator=g6r, device=dev, dtype=torch.uint8)
+        y6 = torch.empty((4096, 4096), dtype=torch.bfloat16, device=dev)
+        ws6 = torch.empty(max(256, tb.gemm_mxfp6_workspace_bytes(4096, 4096, K6, leaf6, g6)), dtype=torch.uint8, device=dev)
+        t = best_ms(lambda: tb.tbik_gemm_mxfp6(X6, Xs6, W6, Ws6, leaf6, g6, "e2m3", out=y6, workspace=ws6), 10, torch)
+        tf = 2.0 * 4096 * K6 * 4096 / (t * 1e-3) / 1e12
+        res[name] = {"ms": round(t, 4), "tflops": round(tf, 1), "frac_fp6_peak": round(tf / 10100.0, 4)}
+        del X6, W6, Xs6, Ws6, y6, ws6
+
     def hbm_line(name, calls, byts, iters):
         cold = best_ms(rotating(calls), iters * len(calls), torch, warm=len(calls))
         warm = best_ms(calls[0], iters, torch)

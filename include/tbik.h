@@ -60,7 +60,9 @@ typedef enum {
     TBIK_F32 = 0, TBIK_BF16 = 1, TBIK_F16 = 2,
     TBIK_FP8_E4M3 = 3,        /* OCP 8-bit float, 4 exponent / 3 fraction bits, bias 7, no infinities, max 448 */
     TBIK_FP8_E5M2 = 4,        /* OCP 8-bit float, 5 exponent / 2 fraction bits, bias 15, IEEE-style inf / NaN  */
-    TBIK_MXFP4 = 5            /* OCP MXFP4: 4-bit E2M1 elements, one E8M0 scale per block of 32 consecutive k     */
+    TBIK_MXFP4 = 5,           /* OCP MXFP4: 4-bit E2M1 elements, one E8M0 scale per block of 32 consecutive k     */
+    TBIK_FP6_E2M3 = 6,        /* OCP 6-bit float, 2 exponent / 3 fraction bits, bias 1, no infinities or NaN, max 7.5 */
+    TBIK_FP6_E3M2 = 7         /* OCP 6-bit float, 3 exponent / 2 fraction bits, bias 3, no infinities or NaN, max 28  */
 } tbik_dtype;
 typedef enum { TBIK_SUM = 0, TBIK_MAX = 1, TBIK_LOGSOFTMAX = 2 } tbik_rowop;
 
@@ -436,6 +438,39 @@ int tbik_gemm_shard_partials_mxfp8(const void *X, int64_t ldx, const void *Xs, i
                                    int M, int N, int K, int leaf, int k_first, int P,
                                    void *workspace, size_t workspace_bytes, void *hip_stream);
 int tbik_gemm_reference_mxfp8(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                              const void *Ws, int64_t ldws, float *partials, void *Y, int64_t ldy, tbik_dtype y_dtype,
+                              tbik_dtype x_dtype, int M, int N, int K, int leaf, int k_first, int P, void *hip_stream);
+
+/*
+ * The same three calls for OCP MXFP6 operands (quantised types of the paper's "Limitations and future work"; the order
+ * contract is that of Sec. 4.2, App. C and App. D.1 as stated for tbik_gemm).  An element is a 6-bit float of format
+ * x_dtype (TBIK_FP6_E2M3 or TBIK_FP6_E3M2) times 2^(s - 127), s the E8M0 scale byte of its block of 32 consecutive k
+ * (s = 255, NaN, is out of contract).  The elements of a row form one little-endian bit stream, element k in bits
+ * 6 k .. 6 k + 5: a block is 24 bytes.  A product has at most eight significant bits and a power-of-two scale, so it is
+ * exact in fp32 (as long as it stays in range): per output element each superleaf's products are accumulated in fp32 in
+ * ascending k from +0, the superleaf sums are combined by T, the result is rounded once.  (The 64 products of one
+ * matrix instruction are added in that instruction's own fixed order, as for the other formats.)  The weight is taken
+ * TRANSPOSED: one row per output channel.
+ *
+ *   X    device, [M, ldx] bytes, ldx >= 3 K / 4      Xs   device, [M, ldxs] scale bytes, ldxs >= K / 32
+ *   Wt   device, [N, ldwt] bytes, ldwt >= 3 K / 4    Ws   device, [N, ldws] scale bytes, ldws >= K / 32
+ *   Y    device, y_dtype (TBIK_F32 or TBIK_BF16), [M, ldy], ldy >= N        partials  device, fp32, dense [P, M, N]
+ *   leaf * k_first a multiple of 64 (128 for the tiled kernel; else the reference kernel runs); X, Wt 16-byte aligned
+ *   with ldx, ldwt multiples of 16; Xs, Ws 4-byte aligned with ldxs, ldws multiples of 4 (the tiled kernel; the
+ *   reference kernel takes scales at any address); the workspace rule (tbik_gemm_mxfp6_workspace_bytes: from 128 rows on
+ *   it includes room for a copy of the scales in the order the kernel reads them, which tbik_gemm_mxfp6 makes first),
+ *   the determinism contract and the errors are those of tbik_gemm, tbik_gemm_shard_partials and tbik_gemm_reference.
+ */
+size_t tbik_gemm_mxfp6_workspace_bytes(int M, int N, int K, int leaf, int k_first);
+int tbik_gemm_mxfp6(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                    const void *Ws, int64_t ldws, void *Y, int64_t ldy, tbik_dtype y_dtype, tbik_dtype x_dtype,
+                    int M, int N, int K, int leaf, int k_first,
+                    void *workspace, size_t workspace_bytes, void *hip_stream);
+int tbik_gemm_shard_partials_mxfp6(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                                   const void *Ws, int64_t ldws, float *partials, tbik_dtype x_dtype,
+                                   int M, int N, int K, int leaf, int k_first, int P,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+int tbik_gemm_reference_mxfp6(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
                               const void *Ws, int64_t ldws, float *partials, void *Y, int64_t ldy, tbik_dtype y_dtype,
                               tbik_dtype x_dtype, int M, int N, int K, int leaf, int k_first, int P, void *hip_stream);
 

@@ -54,6 +54,16 @@ SIGNATURES = {
                                             C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int,
                                             C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
     "tbik_gemm_mxfp8_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]),
+    "tbik_gemm_mxfp6": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                  C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                  C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tbik_gemm_shard_partials_mxfp6": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                                 C.c_void_p, C.c_int64, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                                 C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tbik_gemm_reference_mxfp6": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                            C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int,
+                                            C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
+    "tbik_gemm_mxfp6_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]),
     "tbik_tree_allreduce": (C.c_int, [C.c_void_p, C.c_int, C.c_int64, C.c_void_p]),
     "tbik_silu_mul": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int,
                                 C.c_void_p]),
@@ -466,6 +476,72 @@ def tbik_gemm_reference_mxfp8(X, Xs, Wt, Ws, leaf: int, k_first: int = 1, P: int
                                          Ws.data_ptr(), Ws.stride(0), parts.data_ptr(), Y.data_ptr() if Y is not None else None, N,
                                          _dt(Y) if Y is not None else TBIK_F32, dt, M, N, K, leaf, k_first, P, _stream())
     _check(st, "tbik_gemm_reference_mxfp8")
+    return (Y, parts) if P == 1 else parts
+
+
+TBIK_FP6_E2M3, TBIK_FP6_E3M2 = 6, 7
+_FP6 = {"e2m3": TBIK_FP6_E2M3, "e3m2": TBIK_FP6_E3M2}
+
+
+def _mx6_operands(X, Xs, Wt, Ws, fmt):
+    for t, name in ((X, "X"), (Xs, "Xs"), (Wt, "Wt"), (Ws, "Ws")):
+        _rowmajor(t, name)
+        assert t.dtype == torch.uint8, "MXFP6 operands travel as uint8 tensors: packed 6-bit elements and scale bytes"
+    M, KB = X.shape
+    N = Wt.shape[0]
+    K = KB * 4 // 3
+    assert KB * 4 == K * 3 and Wt.shape[1] == KB and Xs.shape == (M, K // 32) and Ws.shape == (N, K // 32)
+    return _FP6[fmt], M, N, K
+
+
+def gemm_mxfp6_workspace_bytes(M, N, K, leaf, k_first=1) -> int:
+    return int(lib().tbik_gemm_mxfp6_workspace_bytes(M, N, K, leaf, k_first))
+
+
+def tbik_gemm_mxfp6(X, Xs, Wt, Ws, leaf: int, k_first: int = 1, fmt: str = "e2m3", out_dtype=torch.bfloat16,
+                    out: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Y = X @ Wt.T in the tree order on MXFP6 operands: X [M, 3K/4] packed 6-bit elements of format `fmt` with scales
+    Xs [M, K/32]; the weight transposed, Wt [N, 3K/4] with Ws [N, K/32]."""
+    dt, M, N, K = _mx6_operands(X, Xs, Wt, Ws, fmt)
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=X.device)
+    _rowmajor(out, "out")
+    assert out.shape == (M, N)
+    if workspace is None:
+        need = gemm_mxfp6_workspace_bytes(M, N, K, leaf, k_first)
+        if need:
+            workspace = _workspace(need, X.device)
+    st = lib().tbik_gemm_mxfp6(X.data_ptr(), X.stride(0), Xs.data_ptr(), Xs.stride(0), Wt.data_ptr(), Wt.stride(0),
+                               Ws.data_ptr(), Ws.stride(0), out.data_ptr(), out.stride(0), _dt(out), dt, M, N, K, leaf, k_first,
+                               workspace.data_ptr() if workspace is not None else None,
+                               workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream())
+    _check(st, "tbik_gemm_mxfp6")
+    return out
+
+
+def tbik_gemm_shard_partials_mxfp6(X, Xs, Wt, Ws, leaf: int, k_first: int, P: int, fmt: str = "e2m3",
+                                   out: torch.Tensor | None = None):
+    dt, M, N, K = _mx6_operands(X, Xs, Wt, Ws, fmt)
+    if out is None:
+        out = torch.empty((max(P, 1), M, N), dtype=torch.float32, device=X.device)
+    assert out.is_contiguous() and out.dtype == torch.float32
+    st = lib().tbik_gemm_shard_partials_mxfp6(X.data_ptr(), X.stride(0), Xs.data_ptr(), Xs.stride(0), Wt.data_ptr(), Wt.stride(0),
+                                              Ws.data_ptr(), Ws.stride(0), out.data_ptr(), dt, M, N, K, leaf, k_first, P, None, 0,
+                                              _stream())
+    _check(st, "tbik_gemm_shard_partials_mxfp6")
+    return out
+
+
+def tbik_gemm_reference_mxfp6(X, Xs, Wt, Ws, leaf: int, k_first: int = 1, P: int = 1, fmt: str = "e2m3",
+                              out_dtype=torch.float32):
+    """The reference kernel: (Y, partials) for P == 1, partials alone otherwise."""
+    dt, M, N, K = _mx6_operands(X, Xs, Wt, Ws, fmt)
+    parts = torch.empty((P, M, N), dtype=torch.float32, device=X.device)
+    Y = torch.empty((M, N), dtype=out_dtype, device=X.device) if P == 1 else None
+    st = lib().tbik_gemm_reference_mxfp6(X.data_ptr(), X.stride(0), Xs.data_ptr(), Xs.stride(0), Wt.data_ptr(), Wt.stride(0),
+                                         Ws.data_ptr(), Ws.stride(0), parts.data_ptr(), Y.data_ptr() if Y is not None else None, N,
+                                         _dt(Y) if Y is not None else TBIK_F32, dt, M, N, K, leaf, k_first, P, _stream())
+    _check(st, "tbik_gemm_reference_mxfp6")
     return (Y, parts) if P == 1 else parts
 
 

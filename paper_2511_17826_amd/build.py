@@ -17,7 +17,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtbik.so")
 
-SOURCES = ["tbik_api.hip", "gemm_reference.hip", "gemm_tiled.hip", "gemm_f32.hip", "gemm_fp8.hip", "gemm_mxfp4.hip", "combine.hip", "activation.hip", "rmsnorm.hip", "row_reduce.hip",
+SOURCES = ["tbik_api.hip", "gemm_reference.hip", "gemm_tiled.hip", "gemm_f32.hip", "gemm_fp8.hip", "gemm_mxfp4.hip", "gemm_mxfp6.hip", "combine.hip", "activation.hip", "rmsnorm.hip", "row_reduce.hip",
            "attention.hip"]
 
 # -ffp-contract=off: a tree addition or an RMSNorm multiply must never be fused into an FMA.
@@ -82,6 +82,7 @@ def build(save_temps: bool = True, jobs: int = 8, defines=(), lib_path: str = LI
         check_generated_code(os.path.join(BUILD, "gemm_f32-hip-amdgcn-amd-amdhsa-gfx950.s"), "gemm_f32_tiled_kernel")
         check_generated_code(os.path.join(BUILD, "gemm_fp8-hip-amdgcn-amd-amdhsa-gfx950.s"), "gemm_fp8_tiled_kernel")
         check_generated_code(os.path.join(BUILD, "gemm_mxfp4-hip-amdgcn-amd-amdhsa-gfx950.s"), "gemm_mxfp4_tiled_kernel")
+        check_generated_code(os.path.join(BUILD, "gemm_mxfp6-hip-amdgcn-amd-amdhsa-gfx950.s"), "gemm_mxfp6_tiled_kernel")
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib_path, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:

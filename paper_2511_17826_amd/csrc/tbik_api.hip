@@ -572,6 +572,113 @@ int tbik_gemm_reference_mxfp8(const void *X, int64_t ldx, const void *Xs, int64_
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }
 
+// ---- MXFP6 operands: one tile shape (128 x 128), so the K cut is that of a 128-row tile whatever M ----
+static int mxfp6_split(int M, int N, int ns) {
+    const int64_t tiles = (((int64_t)M + 127) / 128) * (((int64_t)N + 127) / 128);
+    int split = 1;
+    while (ns / split > 16 && split < TBIK_MAX_SHARDS) split *= 2;     // the tiled kernel walks at most 16 superleaves per shard
+    if (tiles >= 128) return split;
+    while (split < ns && split < 16 && tiles * split < 256) split *= 2;
+    return split;
+}
+
+static int mxfp6_checks(int x_dtype, const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                        const void *Ws, int64_t ldws, int M, int N, int K, int leaf, int k_first, int P, int *sl, int *ns) {
+    int rc = check_tree(M, N, K, leaf, k_first, P, sl, ns);
+    if (rc != TBIK_OK) return rc;
+    if (x_dtype != TBIK_FP6_E2M3 && x_dtype != TBIK_FP6_E3M2) return TBIK_ERR_DTYPE;
+    if (*sl % 64 != 0) return TBIK_ERR_SHAPE;
+    if (M == 0 || N == 0) return TBIK_OK;
+    if (!X || !Wt || !Xs || !Ws) return TBIK_ERR_NULL;
+    if (ldx < (int64_t)K / 4 * 3 || ldwt < (int64_t)K / 4 * 3 || ldxs < K / 32 || ldws < K / 32) return TBIK_ERR_SHAPE;
+    if (!aligned(X, 16) || !aligned(Wt, 16) || ldx % 16 != 0 || ldwt % 16 != 0) return TBIK_ERR_ALIGN;
+    return TBIK_OK;
+}
+
+size_t tbik_gemm_mxfp6_workspace_bytes(int M, int N, int K, int leaf, int k_first) {
+    int sl, ns;
+    if (check_tree(M, N, K, leaf, k_first, 1, &sl, &ns) != TBIK_OK) return 0;
+    const int split = mxfp6_split(M, N, ns);
+    const size_t planes = split > 1 ? (((size_t)split * (size_t)M * (size_t)N * sizeof(float) + 255) & ~(size_t)255) : 0;
+    return planes + (mx_retiles(M) && K % 128 == 0 ? mxfp6_retiled_scales_bytes(M, N, K) : 0);
+}
+
+int tbik_gemm_mxfp6(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                    const void *Ws, int64_t ldws, void *Y, int64_t ldy, tbik_dtype y_dtype, tbik_dtype x_dtype,
+                    int M, int N, int K, int leaf, int k_first,
+                    void *workspace, size_t workspace_bytes, void *hip_stream) {
+    int sl, ns;
+    int rc = mxfp6_checks((int)x_dtype, X, ldx, Xs, ldxs, Wt, ldwt, Ws, ldws, M, N, K, leaf, k_first, 1, &sl, &ns);
+    if (rc != TBIK_OK) return rc;
+    if (y_dtype != TBIK_F32 && y_dtype != TBIK_BF16) return TBIK_ERR_DTYPE;
+    if (M == 0 || N == 0) return TBIK_OK;
+    if (!Y) return TBIK_ERR_NULL;
+    if (ldy < N) return TBIK_ERR_SHAPE;
+    if (!aligned(Y, y_dtype == TBIK_F32 ? 4 : 2)) return TBIK_ERR_ALIGN;
+    const size_t need = tbik_gemm_mxfp6_workspace_bytes(M, N, K, leaf, k_first);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return TBIK_ERR_WORKSPACE;
+    if (workspace && !aligned(workspace, 256)) return TBIK_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)hip_stream;
+    GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)Wt, ldwt, nullptr, Y, ldy, (int)y_dtype, M, N, K, sl, ns, 1, (int)x_dtype, 0};
+    const Mxfp4Scales sc{(const uint8_t *)Xs, ldxs, (const uint8_t *)Ws, ldws};
+    const int split = mxfp6_split(M, N, ns);
+    GemmArgs probe = a;
+    probe.P = split;
+    const bool tiled = g_forced_variant.load() != VARIANT_REFERENCE && gemm_mxfp6_tiled_supports(probe, sc);
+    const size_t planes = split > 1 ? (((size_t)split * (size_t)M * (size_t)N * sizeof(float) + 255) & ~(size_t)255) : 0;
+    void *retiled = (tiled && mx_retiles(M)) ? static_cast<char *>(workspace) + planes : nullptr;
+    hipError_t e;
+    if (!tiled) {
+        e = launch_gemm_mxfp6_reference(a, sc, s);
+    } else if (split == 1) {
+        e = launch_gemm_mxfp6_tiled(a, sc, retiled, s);
+    } else {
+        a.partials = reinterpret_cast<float *>(workspace);
+        a.Y = nullptr;
+        a.P = split;
+        e = launch_gemm_mxfp6_tiled(a, sc, retiled, s);
+        if (e == hipSuccess) e = launch_tree_combine(a.partials, split, Y, ldy, (int)y_dtype, M, N, s);
+    }
+    return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
+int tbik_gemm_shard_partials_mxfp6(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                                   const void *Ws, int64_t ldws, float *partials, tbik_dtype x_dtype,
+                                   int M, int N, int K, int leaf, int k_first, int P,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream) {
+    (void)workspace; (void)workspace_bytes;
+    int sl, ns;
+    int rc = mxfp6_checks((int)x_dtype, X, ldx, Xs, ldxs, Wt, ldwt, Ws, ldws, M, N, K, leaf, k_first, P, &sl, &ns);
+    if (rc != TBIK_OK) return rc;
+    if (M == 0 || N == 0) return TBIK_OK;
+    if (!partials) return TBIK_ERR_NULL;
+    if (!aligned(partials, 16)) return TBIK_ERR_ALIGN;
+    GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)Wt, ldwt, partials, nullptr, 0, TBIK_F32, M, N, K, sl, ns, P, (int)x_dtype, 0};
+    const Mxfp4Scales sc{(const uint8_t *)Xs, ldxs, (const uint8_t *)Ws, ldws};
+    const bool tiled = g_forced_variant.load() != VARIANT_REFERENCE && gemm_mxfp6_tiled_supports(a, sc);
+    hipError_t e = tiled ? launch_gemm_mxfp6_tiled(a, sc, nullptr, (hipStream_t)hip_stream)
+                         : launch_gemm_mxfp6_reference(a, sc, (hipStream_t)hip_stream);
+    return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
+int tbik_gemm_reference_mxfp6(const void *X, int64_t ldx, const void *Xs, int64_t ldxs, const void *Wt, int64_t ldwt,
+                              const void *Ws, int64_t ldws, float *partials, void *Y, int64_t ldy, tbik_dtype y_dtype,
+                              tbik_dtype x_dtype, int M, int N, int K, int leaf, int k_first, int P, void *hip_stream) {
+    int sl, ns;
+    int rc = mxfp6_checks((int)x_dtype, X, ldx, Xs, ldxs, Wt, ldwt, Ws, ldws, M, N, K, leaf, k_first, P, &sl, &ns);
+    if (rc != TBIK_OK) return rc;
+    if (y_dtype != TBIK_F32 && y_dtype != TBIK_BF16) return TBIK_ERR_DTYPE;
+    if (M == 0 || N == 0) return TBIK_OK;
+    if (!partials && !Y) return TBIK_ERR_NULL;
+    if (Y && P != 1) return TBIK_ERR_SHARDS;
+    if (Y && ldy < N) return TBIK_ERR_SHAPE;
+    if (Y && !aligned(Y, y_dtype == TBIK_F32 ? 4 : 2)) return TBIK_ERR_ALIGN;
+    GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)Wt, ldwt, partials, Y, ldy, (int)y_dtype, M, N, K, sl, ns, P, (int)x_dtype, 0};
+    const Mxfp4Scales sc{(const uint8_t *)Xs, ldxs, (const uint8_t *)Ws, ldws};
+    hipError_t e = launch_gemm_mxfp6_reference(a, sc, (hipStream_t)hip_stream);
+    return e == hipSuccess ? TBIK_OK : hip_fail(e);
+}
+
 // How tbik_gemm_swiglu runs a shape (pure): the K split of the [M, 2 I] GEMM, and whether the unsplit case can end in
 // the 128 x 128 tile's activation epilogue or has to pass gate and up through a 16-bit staging buffer.
 enum { SWIGLU_FUSED = 0, SWIGLU_SPLIT = 1, SWIGLU_STAGED = 2 };

@@ -78,6 +78,13 @@ hipError_t launch_gemm_mxfp8_tiled(const GemmArgs &a, const Mxfp4Scales &sc, int
 size_t mxfp8_retiled_scales_bytes(int M, int N, int K);
 bool gemm_mxfp8_tiled_supports(const GemmArgs &a, const Mxfp4Scales &sc);
 
+// The same for MXFP6 operands (a.x_dtype TBIK_FP6_E2M3 or TBIK_FP6_E3M2): X [M, ldx] bytes of packed 6-bit elements
+// (ldx >= 3 K / 4), W the transposed weight [N, ldw] bytes; one tile shape, 128 x 128.
+hipError_t launch_gemm_mxfp6_reference(const GemmArgs &a, const Mxfp4Scales &sc, hipStream_t s);
+hipError_t launch_gemm_mxfp6_tiled(const GemmArgs &a, const Mxfp4Scales &sc, void *packed_ws, hipStream_t s);
+bool gemm_mxfp6_tiled_supports(const GemmArgs &a, const Mxfp4Scales &sc);
+size_t mxfp6_retiled_scales_bytes(int M, int N, int K);
+
 // Y = T(partials[0..P)) elementwise + one rounding.
 hipError_t launch_tree_combine(const float *partials, int P, void *Y, int64_t ldy, int y_dtype, int M, int N,
                                hipStream_t s);
