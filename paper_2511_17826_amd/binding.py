@@ -399,8 +399,11 @@ def tbik_gemm_shard_partials_mxfp4(X, Xs, Wt, Ws, leaf: int, k_first: int, P: in
     if out is None:
         out = torch.empty((max(P, 1), M, N), dtype=torch.float32, device=X.device)
     assert out.is_contiguous() and out.dtype == torch.float32
+    need = gemm_mxfp4_workspace_bytes(M, N, K, leaf, k_first)
+    ws = _workspace(need, X.device) if need else None
     st = lib().tbik_gemm_shard_partials_mxfp4(X.data_ptr(), X.stride(0), Xs.data_ptr(), Xs.stride(0), Wt.data_ptr(), Wt.stride(0),
-                                              Ws.data_ptr(), Ws.stride(0), out.data_ptr(), M, N, K, leaf, k_first, P, None, 0, _stream())
+                                              Ws.data_ptr(), Ws.stride(0), out.data_ptr(), M, N, K, leaf, k_first, P,
+                                              ws.data_ptr() if ws is not None else None, need, _stream())
     _check(st, "tbik_gemm_shard_partials_mxfp4")
     return out
 
@@ -459,9 +462,11 @@ def tbik_gemm_shard_partials_mxfp8(X, Xs, Wt, Ws, leaf: int, k_first: int, P: in
     if out is None:
         out = torch.empty((max(P, 1), M, N), dtype=torch.float32, device=X.device)
     assert out.is_contiguous() and out.dtype == torch.float32
+    need = gemm_mxfp8_workspace_bytes(M, N, K, leaf, k_first)
+    ws = _workspace(need, X.device) if need else None
     st = lib().tbik_gemm_shard_partials_mxfp8(X.data_ptr(), X.stride(0), Xs.data_ptr(), Xs.stride(0), Wt.data_ptr(), Wt.stride(0),
-                                              Ws.data_ptr(), Ws.stride(0), out.data_ptr(), dt, M, N, K, leaf, k_first, P, None, 0,
-                                              _stream())
+                                              Ws.data_ptr(), Ws.stride(0), out.data_ptr(), dt, M, N, K, leaf, k_first, P,
+                                              ws.data_ptr() if ws is not None else None, need, _stream())
     _check(st, "tbik_gemm_shard_partials_mxfp8")
     return out
 
@@ -525,9 +530,11 @@ def tbik_gemm_shard_partials_mxfp6(X, Xs, Wt, Ws, leaf: int, k_first: int, P: in
     if out is None:
         out = torch.empty((max(P, 1), M, N), dtype=torch.float32, device=X.device)
     assert out.is_contiguous() and out.dtype == torch.float32
+    need = gemm_mxfp6_workspace_bytes(M, N, K, leaf, k_first)
+    ws = _workspace(need, X.device) if need else None
     st = lib().tbik_gemm_shard_partials_mxfp6(X.data_ptr(), X.stride(0), Xs.data_ptr(), Xs.stride(0), Wt.data_ptr(), Wt.stride(0),
-                                              Ws.data_ptr(), Ws.stride(0), out.data_ptr(), dt, M, N, K, leaf, k_first, P, None, 0,
-                                              _stream())
+                                              Ws.data_ptr(), Ws.stride(0), out.data_ptr(), dt, M, N, K, leaf, k_first, P,
+                                              ws.data_ptr() if ws is not None else None, need, _stream())
     _check(st, "tbik_gemm_shard_partials_mxfp6")
     return out
 

@@ -446,7 +446,6 @@ int tbik_gemm_shard_partials_mxfp4(const void *X, int64_t ldx, const void *Xs, i
                                    const void *Ws, int64_t ldws, float *partials,
                                    int M, int N, int K, int leaf, int k_first, int P,
                                    void *workspace, size_t workspace_bytes, void *hip_stream) {
-    (void)workspace; (void)workspace_bytes;
     int sl, ns;
     int rc = mxfp4_checks(X, ldx, Xs, ldxs, Wt, ldwt, Ws, ldws, M, N, K, leaf, k_first, P, &sl, &ns);
     if (rc != TBIK_OK) return rc;
@@ -456,7 +455,11 @@ int tbik_gemm_shard_partials_mxfp4(const void *X, int64_t ldx, const void *Xs, i
     GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)Wt, ldwt, partials, nullptr, 0, TBIK_F32, M, N, K, sl, ns, P, TBIK_MXFP4, 0};
     const Mxfp4Scales sc{(const uint8_t *)Xs, ldxs, (const uint8_t *)Ws, ldws};
     const bool tiled = g_forced_variant.load() != VARIANT_REFERENCE && gemm_mxfp4_tiled_supports(a, sc);
-    hipError_t e = tiled ? launch_gemm_mxfp4_tiled(a, sc, fp8_tile_rows(M, N), nullptr, (hipStream_t)hip_stream)
+    // a workspace as tbik_gemm_mxfp4 takes it has room for the re-tiled scales behind the planes of the K cut
+    void *retiled = (tiled && mx_retiles(M) && workspace && aligned(workspace, 256) &&
+                     workspace_bytes >= tbik_gemm_mxfp4_workspace_bytes(M, N, K, leaf, k_first))
+                        ? static_cast<char *>(workspace) + mx_planes_bytes(M, N, K, leaf, k_first) : nullptr;
+    hipError_t e = tiled ? launch_gemm_mxfp4_tiled(a, sc, fp8_tile_rows(M, N), retiled, (hipStream_t)hip_stream)
                          : launch_gemm_mxfp4_reference(a, sc, (hipStream_t)hip_stream);
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }
@@ -539,7 +542,6 @@ int tbik_gemm_shard_partials_mxfp8(const void *X, int64_t ldx, const void *Xs, i
                                    const void *Ws, int64_t ldws, float *partials, tbik_dtype x_dtype,
                                    int M, int N, int K, int leaf, int k_first, int P,
                                    void *workspace, size_t workspace_bytes, void *hip_stream) {
-    (void)workspace; (void)workspace_bytes;
     int sl, ns;
     int rc = mxfp8_checks((int)x_dtype, X, ldx, Xs, ldxs, Wt, ldwt, Ws, ldws, M, N, K, leaf, k_first, P, &sl, &ns);
     if (rc != TBIK_OK) return rc;
@@ -549,7 +551,11 @@ int tbik_gemm_shard_partials_mxfp8(const void *X, int64_t ldx, const void *Xs, i
     GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)Wt, ldwt, partials, nullptr, 0, TBIK_F32, M, N, K, sl, ns, P, (int)x_dtype, 0};
     const Mxfp4Scales sc{(const uint8_t *)Xs, ldxs, (const uint8_t *)Ws, ldws};
     const bool tiled = g_forced_variant.load() != VARIANT_REFERENCE && gemm_mxfp8_tiled_supports(a, sc);
-    hipError_t e = tiled ? launch_gemm_mxfp8_tiled(a, sc, fp8_tile_rows(M, N), nullptr, (hipStream_t)hip_stream)
+    // a workspace as tbik_gemm_mxfp8 takes it has room for the re-tiled scales behind the planes of the K cut
+    void *retiled = (tiled && mx_retiles(M) && workspace && aligned(workspace, 256) &&
+                     workspace_bytes >= tbik_gemm_mxfp8_workspace_bytes(M, N, K, leaf, k_first))
+                        ? static_cast<char *>(workspace) + mx_planes_bytes(M, N, K, leaf, k_first) : nullptr;
+    hipError_t e = tiled ? launch_gemm_mxfp8_tiled(a, sc, fp8_tile_rows(M, N), retiled, (hipStream_t)hip_stream)
                          : launch_gemm_mxfp8_reference(a, sc, (hipStream_t)hip_stream);
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }
@@ -646,7 +652,6 @@ int tbik_gemm_shard_partials_mxfp6(const void *X, int64_t ldx, const void *Xs, i
                                    const void *Ws, int64_t ldws, float *partials, tbik_dtype x_dtype,
                                    int M, int N, int K, int leaf, int k_first, int P,
                                    void *workspace, size_t workspace_bytes, void *hip_stream) {
-    (void)workspace; (void)workspace_bytes;
     int sl, ns;
     int rc = mxfp6_checks((int)x_dtype, X, ldx, Xs, ldxs, Wt, ldwt, Ws, ldws, M, N, K, leaf, k_first, P, &sl, &ns);
     if (rc != TBIK_OK) return rc;
@@ -656,7 +661,13 @@ int tbik_gemm_shard_partials_mxfp6(const void *X, int64_t ldx, const void *Xs, i
     GemmArgs a{(const uint16_t *)X, ldx, (const uint16_t *)Wt, ldwt, partials, nullptr, 0, TBIK_F32, M, N, K, sl, ns, P, (int)x_dtype, 0};
     const Mxfp4Scales sc{(const uint8_t *)Xs, ldxs, (const uint8_t *)Ws, ldws};
     const bool tiled = g_forced_variant.load() != VARIANT_REFERENCE && gemm_mxfp6_tiled_supports(a, sc);
-    hipError_t e = tiled ? launch_gemm_mxfp6_tiled(a, sc, nullptr, (hipStream_t)hip_stream)
+    // a workspace as tbik_gemm_mxfp6 takes it has room for the re-tiled scales behind the planes of the K cut
+    const int own_split = mxfp6_split(M, N, ns);
+    const size_t planes = own_split > 1 ? (((size_t)own_split * (size_t)M * (size_t)N * sizeof(float) + 255) & ~(size_t)255) : 0;
+    void *retiled = (tiled && mx_retiles(M) && workspace && aligned(workspace, 256) &&
+                     workspace_bytes >= tbik_gemm_mxfp6_workspace_bytes(M, N, K, leaf, k_first))
+                        ? static_cast<char *>(workspace) + planes : nullptr;
+    hipError_t e = tiled ? launch_gemm_mxfp6_tiled(a, sc, retiled, (hipStream_t)hip_stream)
                          : launch_gemm_mxfp6_reference(a, sc, (hipStream_t)hip_stream);
     return e == hipSuccess ? TBIK_OK : hip_fail(e);
 }
