@@ -27,6 +27,20 @@ def pytest_collection_modifyitems(config, items):
             item.add_marker(skip)
 
 
+@pytest.fixture(autouse=True)
+def _library_switches_at_their_defaults(request):
+    """The library's three process-wide test and tuning switches (forced GEMM variant, forced attention kernel, bound of
+    the log-softmax waits) are put back after every GPU test, whatever the test did with them, so that no test changes
+    what a later one runs or measures."""
+    yield
+    if "gpu" not in request.keywords:
+        return
+    from paper_2511_17826_amd import binding as tb
+    tb.tbik_set_gemm_variant(tb.VARIANT_AUTO)
+    tb.tbik_set_attention_variant(0)
+    tb.tbik_set_row_wait_limit(1 << 14)
+
+
 def read_tree_pins():
     """Parse tests/golden/tree_pins.txt -> list of (name, [float32 leaves], T_bits, seq_bits)."""
     import numpy as np
