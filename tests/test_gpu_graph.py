@@ -104,3 +104,48 @@ def test_fp32_gemm_fp16_tail_and_attention_in_a_hip_graph():
         torch.cuda.synchronize()
         for got, ref in zip(outs, want):
             assert torch.equal(got.view(torch.uint8), ref.view(torch.uint8)), rep
+
+
+def test_8_bit_and_microscaling_gemms_in_a_hip_graph():
+    """The 8-bit GEMM and the three microscaling ones (which re-tile their scales in a launch of their own from 128 rows
+    on, into the caller's workspace) under capture and replay: a shape with the K cut and one without."""
+    dev = "cuda:0"
+    u8 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint8)).to(dev)
+    cases = []
+    for M, K, N, leaf in ((200, 2048, 264, 256), (40, 1024, 136, 128)):
+        X8, Xs8, W8, Ws8 = [u8(a) for a in syn.gemm_random_mxfp8(M, M, K, N, scale_spread=1)]
+        X6, Xs6, W6, Ws6 = [u8(a) for a in syn.gemm_random_mxfp6(M + 1, M, K, N, fmt="e3m2", scale_spread=1)]
+        X4, Xs4, W4, Ws4 = [u8(a) for a in syn.gemm_random_mxfp4(M + 2, M, K, max(N, 256) if leaf == 256 else N, scale_spread=1)]
+        outs = [torch.empty((M, W.shape[0]), dtype=torch.float32, device=dev) for W in (W8, W8, W6, W4)]
+        ws = [torch.empty(max(256, n), dtype=torch.uint8, device=dev) for n in (
+            tb.gemm_fp8_workspace_bytes(M, N, K, leaf, 1), tb.gemm_mxfp8_workspace_bytes(M, N, K, leaf, 1),
+            tb.gemm_mxfp6_workspace_bytes(M, N, K, leaf, 1), tb.gemm_mxfp4_workspace_bytes(M, W4.shape[0], K, max(leaf, 256), 1))]
+        cases.append((leaf, (X8, Xs8, W8, Ws8), (X6, Xs6, W6, Ws6), (X4, Xs4, W4, Ws4), outs, ws))
+
+    def one_pass():
+        for leaf, m8, m6, m4, outs, ws in cases:
+            tb.tbik_gemm_fp8(m8[0], m8[2], leaf, 1, "e4m3", out=outs[0], workspace=ws[0])
+            tb.tbik_gemm_mxfp8(*m8, leaf, 1, "e4m3", out=outs[1], workspace=ws[1])
+            tb.tbik_gemm_mxfp6(*m6, leaf, 1, "e3m2", out=outs[2], workspace=ws[2])
+            tb.tbik_gemm_mxfp4(*m4, max(leaf, 256), 1, out=outs[3], workspace=ws[3])
+
+    one_pass()
+    torch.cuda.synchronize()
+    tensors = [t for c in cases for t in c[4]]
+    want = [t.clone() for t in tensors]
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            one_pass()
+    for rep in range(3):
+        for t in tensors:
+            t.zero_()
+        for c in cases:
+            for w in c[5]:
+                w.fill_(0xA5)                              # the workspaces' old contents do not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip(tensors, want):
+            assert torch.equal(got.view(torch.uint8), ref.view(torch.uint8)), rep
