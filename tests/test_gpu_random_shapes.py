@@ -170,6 +170,61 @@ def test_low_precision_gemms_random_shapes_all_routes():
     tb.tbik_set_gemm_variant(tb.VARIANT_AUTO)
 
 
+def test_mxfp8_and_mxfp6_gemms_random_shapes_all_routes():
+    """MXFP8 and MXFP6 operands with a random scale per row and block: randomly drawn shapes, tile heights and shard
+    counts give the reference kernel's bits (operands and scales inside wider buffers: strided rows); integer elements
+    under equal scales give the oracle's."""
+    rng = np.random.Generator(np.random.PCG64(8642))
+    u8 = lambda b: torch.from_numpy(np.ascontiguousarray(b, dtype=np.uint8)).to("cuda:0")
+
+    def inside_wider(t, pad):
+        buf = torch.zeros((t.shape[0], t.shape[1] + pad), dtype=torch.uint8, device="cuda:0")
+        buf[:, :t.shape[1]] = t
+        return buf[:, :t.shape[1]]
+
+    for case in range(16):
+        leaf = int(rng.choice([64, 128, 256, 512]))
+        g = int(rng.choice([1, 1, 2, 3]))
+        ns = int(rng.choice([1, 2, 4, 8, 16, 32]))
+        K = leaf * g * ns
+        if K > 16384:
+            continue
+        M = int(rng.choice([1, 2, 31, 33, 64, 100, 129, 300, 520]))
+        N = int(rng.choice([8, 24, 128, 136, 392]))
+        pad = int(rng.choice([0, 16, 48]))
+        Ps = [p for p in (1, 2, 8, 32) if p <= ns]
+        six = case % 2 == 1
+        fmt = (("e2m3", "e3m2") if six else ("e4m3", "e5m2"))[(case // 2) % 2]
+        gen, gemm, shard, oracle = ((syn.gemm_random_mxfp6, tb.tbik_gemm_mxfp6, tb.tbik_gemm_shard_partials_mxfp6, orc.gemm_mxfp6) if six else
+                                    (syn.gemm_random_mxfp8, tb.tbik_gemm_mxfp8, tb.tbik_gemm_shard_partials_mxfp8, orc.gemm_mxfp8))
+        Xq, Xs, Wq, Ws = gen(7000 + case, M, K, N, fmt=fmt, scale_spread=int(rng.choice([0, 2, 6])))
+        ops = [inside_wider(u8(Xq), pad), inside_wider(u8(Xs), 4 if pad else 0), inside_wider(u8(Wq), pad), inside_wider(u8(Ws), 8 if pad else 0)]
+        tb.tbik_set_gemm_variant(tb.VARIANT_REFERENCE)
+        ref = gemm(*ops, leaf, g, fmt, out_dtype=torch.float32).clone()
+        for v in (tb.VARIANT_T128, tb.VARIANT_T64, tb.VARIANT_T32, tb.VARIANT_AUTO):
+            tb.tbik_set_gemm_variant(v)
+            y = gemm(*ops, leaf, g, fmt, out_dtype=torch.float32)
+            assert torch.equal(y.view(torch.int32), ref.view(torch.int32)), (case, M, K, N, leaf, g, v, fmt)
+            for P in Ps:
+                y = tb.tbik_tree_combine(shard(*ops, leaf, g, P, fmt), out_dtype=torch.float32)
+                assert torch.equal(y.view(torch.int32), ref.view(torch.int32)), (case, v, P, fmt)
+        # the same shape with integer elements and equal scales: the oracle's bits
+        tb.tbik_set_gemm_variant(tb.VARIANT_AUTO)
+        mags = syn.fp6_magnitudes(fmt) if six else None
+        def ints(shape):
+            v = rng.integers(-4, 5, size=shape)
+            if not six:
+                return syn.f32_to_fp8_bits(v.astype(np.float32), fmt)
+            idx = np.abs(np.abs(v)[..., None].astype(np.float32) - mags).argmin(axis=-1).astype(np.uint8)
+            return syn.fp6_pack(idx | ((v < 0).astype(np.uint8) << 5))
+        Xi, Wi = ints((M, K)), ints((N, K))
+        Xs1, Ws1 = np.full((M, K // 32), 126, dtype=np.uint8), np.full((N, K // 32), 130, dtype=np.uint8)
+        want, _ = oracle(Xi, Xs1, Wi, Ws1, leaf, g, fmt=fmt)
+        y = gemm(u8(Xi), u8(Xs1), u8(Wi), u8(Ws1), leaf, g, fmt, out_dtype=torch.float32)
+        assert np.array_equal(gu.u32(gu.host_f32(y)), want.view(np.uint32)), (case, M, K, N, leaf, g, fmt)
+    tb.tbik_set_gemm_variant(tb.VARIANT_AUTO)
+
+
 def test_gemm_swiglu_random_shapes_equal_two_gemms_then_the_activation():
     rng = np.random.Generator(np.random.PCG64(99))
     for case in range(10):
