@@ -129,7 +129,9 @@ __global__ __launch_bounds__(64) void gemm_fp8_reference_kernel(
 // Tiled kernel.  A stage is 128 k: a [128 rows x 128 bytes] tile of X and one of Wt.  A stage slot is cut into four
 // regions of 8 KiB, one per loading wavefront: [32 rows of the X tile | 32 rows of the Wt tile].  Rows are 128 bytes;
 // the 16-byte chunk c of row r sits at position c ^ ((r >> 1) & 7), so the 16 rows that a ds_read_b128 pass touches
-// cover all banks.  A lane's operand for one MFMA is 32 consecutive bytes of its row: chunks 4*ks + 2*lg and the next.
+// cover all banks.  A lane's operand for one MFMA is 32 consecutive bytes of its row: chunks 4*ks + 2*lg and the next
+// (with block scales: chunks 4*ks + lg and 4*ks + 2 + lg, and a slot carries 1 KiB of scales behind the four regions:
+// four bytes per row of the X tile, then of the Wt tile).
 // Three tile shapes, as for 16-bit operands: 128 x 128 (wave tile 64 x 64), 64 x 128 and 32 x 128 (four wavefronts side by
 // side) for small batches, where the weight is the traffic and a deeper ring keeps more of it in flight.
 constexpr int BK8 = 128;               // k (= bytes) per LDS stage row
