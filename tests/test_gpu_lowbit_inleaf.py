@@ -67,3 +67,24 @@ def test_microscaling_random_operands_bit_equal_but_for_rare_last_places(spread)
     y = gu.host_f32(tb.tbik_gemm_mxfp4(*dev(Xp, Xs, Wp, Ws), leaf, 1, out_dtype=torch.float32))
     A = np.abs(orc.mxfp4_dequant(Xp, Xs).astype(np.float64)) @ np.abs(orc.mxfp4_dequant(Wp, Ws).astype(np.float64).T)
     _close("mxfp4 spread %d" % spread, y, want, A)
+
+
+def test_benchmark_shape_at_full_size_on_sampled_outputs():
+    """4096^3 with leaf 256 (the benchmark's o_proj), plain 8-bit, MXFP8 and MXFP4 operands: a 48 x 40 sample of rows and
+    columns of the full-size launch, bit for bit against the instruction-level oracle (which computes the sample as the
+    product of the sampled rows of X with the sampled rows of the transposed weight)."""
+    M = K = N = 4096
+    rng = np.random.default_rng(17)
+    rows, cols = np.sort(rng.choice(M, 48, replace=False)), np.sort(rng.choice(N, 40, replace=False))
+    Xb, Wb = syn.gemm_random_fp8(41, M, K, N)
+    y = gu.host_f32(tb.tbik_gemm_fp8(*dev(Xb, Wb.T), 256, 1, "e4m3", out_dtype=torch.float32))
+    want, _ = orc.gemm_fp8_hw(Xb[rows], Wb[:, cols], 256, 1)
+    assert np.array_equal(gu.u32(y[np.ix_(rows, cols)]), want.view(np.uint32))
+    Xq, Xs, Wq, Ws = syn.gemm_random_mxfp8(42, M, K, N, scale_spread=2)
+    y = gu.host_f32(tb.tbik_gemm_mxfp8(*dev(Xq, Xs, Wq, Ws), 256, 1, "e4m3", out_dtype=torch.float32))
+    want, _ = orc.gemm_mxfp8_hw(Xq[rows], Xs[rows], Wq[cols], Ws[cols], 256, 1)
+    assert np.array_equal(gu.u32(y[np.ix_(rows, cols)]), want.view(np.uint32))
+    Xp, Xs, Wp, Ws = syn.gemm_random_mxfp4(43, M, K, N, scale_spread=2)
+    y = gu.host_f32(tb.tbik_gemm_mxfp4(*dev(Xp, Xs, Wp, Ws), 256, 1, out_dtype=torch.float32))
+    want, _ = orc.gemm_mxfp4_hw(Xp[rows], Xs[rows], Wp[cols], Ws[cols], 256, 1)
+    assert np.array_equal(gu.u32(y[np.ix_(rows, cols)]), want.view(np.uint32))
