@@ -114,7 +114,7 @@ def lib():
         L.tbik_oracle_mfma8_step.argtypes = [C.c_float, f64p, i32pp, C.c_int]
         L.tbik_oracle_gemm_lowbit_hw.restype = C.c_int
         L.tbik_oracle_gemm_lowbit_hw.argtypes = [f64p, i32pp, f64p, i32pp, f32p, u16p, C.c_long, C.c_int, C.c_int, C.c_int, C.c_int,
-                                                 C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f32p]
+                                                 C.c_int, C.c_int, C.c_int, C.c_int, f32p]
         L.tbik_oracle_tree_combine.restype = C.c_int
         L.tbik_oracle_tree_combine.argtypes = [f32p, C.c_int, C.c_long, f32p, u16p, C.c_int]
         L.tbik_oracle_treesum.restype = C.c_float
@@ -515,7 +515,7 @@ def mfma8_step(c, products, exponents) -> np.float32:
                                                    e.ctypes.data_as(C.POINTER(C.c_int32)), p.size))
 
 
-def _gemm_lowbit_hw(Xv, Xe, Wv, We, leaf, k_first, evaluator, P, block, swapped, want_partials):
+def _gemm_lowbit_hw(Xv, Xe, Wv, We, leaf, k_first, evaluator, P, block, want_partials):
     Xv = np.ascontiguousarray(Xv, dtype=np.float64); Wv = np.ascontiguousarray(Wv, dtype=np.float64)
     Xe = np.ascontiguousarray(Xe, dtype=np.int32); We = np.ascontiguousarray(We, dtype=np.int32)
     M, K = Xv.shape
@@ -527,7 +527,7 @@ def _gemm_lowbit_hw(Xv, Xe, Wv, We, leaf, k_first, evaluator, P, block, swapped,
     dp, ip = C.POINTER(C.c_double), C.POINTER(C.c_int32)
     rc = lib().tbik_oracle_gemm_lowbit_hw(Xv.ctypes.data_as(dp), Xe.ctypes.data_as(ip), Wv.ctypes.data_as(dp), We.ctypes.data_as(ip),
                                           Y32.ctypes.data_as(C.POINTER(C.c_float)), Ybf.ctypes.data_as(C.POINTER(C.c_uint16)), N,
-                                          M, N, K, leaf, k_first, evaluator, P, block, int(swapped),
+                                          M, N, K, leaf, k_first, evaluator, P, block,
                                           parts.ctypes.data_as(C.POINTER(C.c_float)) if want_partials else None)
     if rc != 0:
         raise ValueError("oracle gemm: illegal tree parameters (K, leaf, k_first, P), or a superleaf that is no multiple of 64")
@@ -540,11 +540,10 @@ def _scale_exponents(scales):
 
 def gemm_fp8_hw(X, W, leaf: int, k_first: int = 1, evaluator: int = EVAL_RECURSIVE, P: int = 1, want_partials: bool = False,
                 fmt: str = "e4m3"):
-    """gemm_fp8 (X [M,K], W [K,N] patterns) with the instruction's arithmetic inside a superleaf, the step's sixteens in
-    the order in which the unscaled 8-bit kernels present them."""
+    """gemm_fp8 (X [M,K], W [K,N] patterns) with the instruction's arithmetic inside a superleaf."""
     X = np.asarray(X, dtype=np.uint8); Wt = np.ascontiguousarray(np.asarray(W, dtype=np.uint8).T)
     return _gemm_lowbit_hw(fp8_to_f32(X, fmt), element_exponents(X, fmt), fp8_to_f32(Wt, fmt), element_exponents(Wt, fmt),
-                           leaf, k_first, evaluator, P, 16, True, want_partials)
+                           leaf, k_first, evaluator, P, 16, want_partials)
 
 
 def gemm_mxfp8_hw(X, Xs, Wt, Ws, leaf: int, k_first: int = 1, evaluator: int = EVAL_RECURSIVE, P: int = 1,
@@ -553,7 +552,7 @@ def gemm_mxfp8_hw(X, Xs, Wt, Ws, leaf: int, k_first: int = 1, evaluator: int = E
     X = np.asarray(X, dtype=np.uint8); Wt = np.asarray(Wt, dtype=np.uint8)
     return _gemm_lowbit_hw(mxfp8_dequant(X, Xs, fmt), element_exponents(X, fmt) + _scale_exponents(Xs),
                            mxfp8_dequant(Wt, Ws, fmt), element_exponents(Wt, fmt) + _scale_exponents(Ws),
-                           leaf, k_first, evaluator, P, 16, False, want_partials)
+                           leaf, k_first, evaluator, P, 16, want_partials)
 
 
 def gemm_mxfp6_hw(X, Xs, Wt, Ws, leaf: int, k_first: int = 1, evaluator: int = EVAL_RECURSIVE, P: int = 1,
@@ -562,7 +561,7 @@ def gemm_mxfp6_hw(X, Xs, Wt, Ws, leaf: int, k_first: int = 1, evaluator: int = E
     px, pw = fp6_unpack(X), fp6_unpack(Wt)
     return _gemm_lowbit_hw(mxfp6_dequant(X, Xs, fmt), element_exponents(px & 31, fmt) + _scale_exponents(Xs),
                            mxfp6_dequant(Wt, Ws, fmt), element_exponents(pw & 31, fmt) + _scale_exponents(Ws),
-                           leaf, k_first, evaluator, P, 32, False, want_partials)
+                           leaf, k_first, evaluator, P, 32, want_partials)
 
 
 def gemm_mxfp4_hw(X, Xs, Wt, Ws, leaf: int, k_first: int = 1, evaluator: int = EVAL_RECURSIVE, P: int = 1,
@@ -577,7 +576,7 @@ def gemm_mxfp4_hw(X, Xs, Wt, Ws, leaf: int, k_first: int = 1, evaluator: int = E
     nx, nw = nibbles(X), nibbles(Wt)
     return _gemm_lowbit_hw(mxfp4_dequant(X, Xs), element_exponents(nx & 7, "e2m1") + _scale_exponents(Xs),
                            mxfp4_dequant(Wt, Ws), element_exponents(nw & 7, "e2m1") + _scale_exponents(Ws),
-                           leaf, k_first, evaluator, P, 32, False, want_partials)
+                           leaf, k_first, evaluator, P, 32, want_partials)
 
 
 def tree_combine(partials: np.ndarray, fmt: str = "bf16"):

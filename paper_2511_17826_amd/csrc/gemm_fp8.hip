@@ -4,12 +4,10 @@
 // in ascending k from +0, the superleaf sums are combined by the tree T.  A product of two 8-bit floats has at most
 // eight significant bits, so it is exact in fp32 like a product of two bf16 numbers.  The matrix instruction is
 // v_mfma_f32_32x32x64_f8f6f4 (64 k per instruction, both operands 8-bit): lane l carries row (or column) l % 32 and 32
-// of the step's 64 k, for A and for B alike -- here the 32 consecutive bytes of half l / 32.  Both operands agree on
-// that arrangement, so every product is the right one; the instruction itself takes a lane's first 16 bytes (of either
-// half of the wavefront) as positions 0..31 and its second 16 bytes as 32..63, and adds the 64 products as a chain of
-// four rounded steps of 16, so within a step of 64 k these kernels' order of accumulation is k 0..15, 32..47, 16..31,
-// 48..63 (reference and tiled kernel alike; the scaled kernels below use the ascending arrangement, which the block
-// scales require).  Because both operands want k-contiguous bytes,
+// of the step's 64 k, for A and for B alike.  The instruction takes a lane's first 16 bytes (of either half of the
+// wavefront) as positions 0..31 and its second 16 bytes as 32..63, and adds the 64 products as a chain of four rounded
+// steps of 16 positions; the kernels give half l / 32 bytes 16 h .. 16 h + 15 of the step's first and of its second
+// 32 k, so that the instruction meets k in ascending order.  Because both operands want k-contiguous bytes,
 // the weight is taken TRANSPOSED, Wt [N, K] -- one row per output channel, the layout 8-bit weights are stored in --
 // and the two operand tiles are staged, swizzled and read in exactly the same way.
 //
@@ -82,26 +80,20 @@ __global__ __launch_bounds__(64) void gemm_fp8_reference_kernel(
         for (int kk = 0; kk < superleaf; kk += 64) {
             const int64_t k = k0 + kk + 32 * g;
             union { i32x4 h[2]; i32x8 v; } a, b;
-            // rows past M and columns past N compute on a valid row's data and are never stored
-            if (MX) {
-                // The instruction scales a lane's first 16 bytes (of either half of the wavefront) by the scale that
-                // the lanes of half 0 hand over and its second 16 bytes by the scale from half 1 (measured: an element
-                // moved through the 64 positions shows which scale reaches it).  So a block of 32 k is the first 16
-                // bytes of both halves: half g holds bytes 16 g .. 16 g + 15 of block 0 and of block 1 of the step and
-                // hands over the scale of block g.
-                const int64_t kq = k0 + kk;
-                a.h[0] = *reinterpret_cast<const i32x4 *>(xrow + kq + 16 * g);
-                a.h[1] = *reinterpret_cast<const i32x4 *>(xrow + kq + 32 + 16 * g);
-                b.h[0] = *reinterpret_cast<const i32x4 *>(wrow + kq + 16 * g);
-                b.h[1] = *reinterpret_cast<const i32x4 *>(wrow + kq + 32 + 16 * g);
-                acc = mfma_32x32x64_8bit_scaled<FMT>(a.v, b.v, acc, xsrow[k >> 5], wsrow[k >> 5]);
-            } else {
-                a.h[0] = *reinterpret_cast<const i32x4 *>(xrow + k);
-                a.h[1] = *reinterpret_cast<const i32x4 *>(xrow + k + 16);
-                b.h[0] = *reinterpret_cast<const i32x4 *>(wrow + k);
-                b.h[1] = *reinterpret_cast<const i32x4 *>(wrow + k + 16);
-                acc = mfma_32x32x64_8bit<FMT>(a.v, b.v, acc);
-            }
+            // rows past M and columns past N compute on a valid row's data and are never stored.
+            // The instruction takes a lane's first 16 bytes (of either half of the wavefront) as positions 0..31 of the
+            // step and its second 16 bytes as positions 32..63, scales them by what the lanes of half 0 resp. half 1 hand
+            // over (measured: an element moved through the 64 positions shows which scale reaches it) and adds the
+            // products as a chain of four rounded steps of 16 positions.  So half g holds bytes 16 g .. 16 g + 15 of the
+            // step's first 32 k and of its second 32 k: the instruction then meets k in ascending order, and with block
+            // scales half g hands over the scale of block g.
+            const int64_t kq = k0 + kk;
+            a.h[0] = *reinterpret_cast<const i32x4 *>(xrow + kq + 16 * g);
+            a.h[1] = *reinterpret_cast<const i32x4 *>(xrow + kq + 32 + 16 * g);
+            b.h[0] = *reinterpret_cast<const i32x4 *>(wrow + kq + 16 * g);
+            b.h[1] = *reinterpret_cast<const i32x4 *>(wrow + kq + 32 + 16 * g);
+            if (MX) acc = mfma_32x32x64_8bit_scaled<FMT>(a.v, b.v, acc, xsrow[k >> 5], wsrow[k >> 5]);
+            else acc = mfma_32x32x64_8bit<FMT>(a.v, b.v, acc);
         }
         const int t = __builtin_ctz(~(unsigned)j);     // carry-over: as many finished subtrees as j has trailing ones
         for (int l = 0; l < t; ++l) {
@@ -131,9 +123,8 @@ __global__ __launch_bounds__(64) void gemm_fp8_reference_kernel(
 // Tiled kernel.  A stage is 128 k: a [128 rows x 128 bytes] tile of X and one of Wt.  A stage slot is cut into four
 // regions of 8 KiB, one per loading wavefront: [32 rows of the X tile | 32 rows of the Wt tile].  Rows are 128 bytes;
 // the 16-byte chunk c of row r sits at position c ^ ((r >> 1) & 7), so the 16 rows that a ds_read_b128 pass touches
-// cover all banks.  A lane's operand for one MFMA is 32 consecutive bytes of its row: chunks 4*ks + 2*lg and the next
-// (with block scales: chunks 4*ks + lg and 4*ks + 2 + lg, and a slot carries 1 KiB of scales behind the four regions:
-// four bytes per row of the X tile, then of the Wt tile).
+// cover all banks.  A lane's operand for one MFMA is chunks 4*ks + lg and 4*ks + 2 + lg of its row (with block scales a
+// slot carries 1 KiB of scales behind the four regions: four bytes per row of the X tile, then of the Wt tile).
 // Three tile shapes, as for 16-bit operands: 128 x 128 (wave tile 64 x 64), 64 x 128 and 32 x 128 (four wavefronts side by
 // side) for small batches, where the weight is the traffic and a deeper ring keeps more of it in flight.
 constexpr int BK8 = 128;               // k (= bytes) per LDS stage row
@@ -298,14 +289,14 @@ void gemm_fp8_tiled_kernel(const Fp8Params p) {
 #pragma unroll
     for (int b = 0; b < NT; ++b) s_off[MT + b] = SCALES_AT + 512 + ((wn * NT + b) * 32 + li) * 4;
     const int sw = (li >> 1) & 7;
-    // chunk positions of the lane's 32 bytes in K-step ks: (4 ks + 2 lg) ^ sw and (4 ks + 2 lg + 1) ^ sw; with block
-    // scales chunks 4 ks + lg and 4 ks + 2 + lg (the instruction's blocks are the first, and the second, 16 bytes of both
-    // halves of the wavefront: see the reference kernel)
+    // chunk positions of the lane's two 16-byte pieces in K-step ks: chunks 4 ks + lg and 4 ks + 2 + lg (the
+    // instruction's first and second 32 positions are the first, and the second, 16 bytes of both halves of the
+    // wavefront: see the reference kernel)
     int c_off[KSTEPS8][2];
 #pragma unroll
     for (int ks = 0; ks < KSTEPS8; ++ks) {
-        c_off[ks][0] = ((4 * ks + (MX ? lg : 2 * lg)) ^ sw) << 4;
-        c_off[ks][1] = ((4 * ks + (MX ? 2 + lg : 2 * lg + 1)) ^ sw) << 4;
+        c_off[ks][0] = ((4 * ks + lg) ^ sw) << 4;
+        c_off[ks][1] = ((4 * ks + 2 + lg) ^ sw) << 4;
     }
 
     // Fragment registers: one set per K-step of a stage; the reads run one K-step (four MFMAs of 16 passes) ahead.

@@ -135,14 +135,11 @@ def test_full_size_tiled_equals_reference():
 
 
 def test_scale_one_equals_the_unscaled_8_bit_gemm():
-    """Every scale 2^0 and integer elements: the same bits as tbik_gemm_fp8 on the same patterns.  (The two kernels
-    present the four sixteens of a step of 64 k to the instruction in different orders, which shows as soon as one of the
-    instruction's four internal steps rounds; with small integers none does.)"""
-    rng = np.random.default_rng(5)
-    Xq = syn.f32_to_fp8_bits(rng.integers(-8, 9, size=(200, 2048)).astype(np.float32), "e4m3")
-    Wq = syn.f32_to_fp8_bits(rng.integers(-8, 9, size=(264, 2048)).astype(np.float32), "e4m3")
-    Xs = np.full((200, 64), 127, dtype=np.uint8)
-    Ws = np.full((264, 64), 127, dtype=np.uint8)
+    """Every scale 2^0: the same bits as tbik_gemm_fp8 on the same (random) patterns -- the two kernels present a step of
+    64 k to the instruction in the same, ascending arrangement."""
+    Xq, Xs, Wq, Ws = syn.gemm_random_mxfp8(5, 200, 2048, 264)
+    Xs[:] = 127
+    Ws[:] = 127
     X, XS, W, WS = dev(Xq, Xs, Wq, Ws)
     a = tb.tbik_gemm_mxfp8(X, XS, W, WS, 256, 1, out_dtype=torch.float32)
     b = tb.tbik_gemm_fp8(X, W, 256, 1, out_dtype=torch.float32)
