@@ -54,6 +54,11 @@ def test_group_sums_are_aligned_to_the_step_s_unit_and_the_accumulator_sets_the_
     assert bits(step(2.0 ** 30, items)) == bits(2.0 ** 30)
     assert bits(step(2.0 ** 24, items)) == bits(2.0 ** 24 + 2.0)                 # 2^24 + 2.2422 -> spacing 2: 2^24 + 2
     assert bits(step(2.0 ** 10, items)) == bits(2.0 ** 10 + 2.25 - 2.0 ** -13)   # unit 2^-21: nothing lost, fits 24 bits
+    # the groups are added on the products' own grid before their sum is aligned to the step's unit: c = 2^23 + 1 (unit
+    # 2^-8, spacing 1), group sums 0.25 + 2^-9 and 0.25 - 2^-9: together exactly one half -- a tie, to the even neighbour
+    # above; aligned one by one they would lose 2^-8 and stay below the tie
+    halves = [(0, 0.5, -1, 0.5, -1), (1, 2.0 ** -4, -4, 2.0 ** -5, -5), (8, 0.5, -1, 0.5, -1), (9, -2.0 ** -4, -4, 2.0 ** -5, -5)]
+    assert bits(step(8388609.0, halves)) == bits(8388610.0)
     # a step of 32 products (6- and 4-bit operands): four groups, one result
     many = [(g * 8, 1.0, 0, 1.0, 0) for g in range(4)]
     assert bits(step(0.0, many, n=32)) == bits(4.0)
